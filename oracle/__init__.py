@@ -1,0 +1,163 @@
+"""ctypes front end of the CPU oracle (oracle/pcr_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+CPU-baseline leg.  The GPU package never imports this module.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pcr_oracle.c")
+_LIB = os.path.join(_HERE, "liborc.so")
+_lib = None
+
+OK, E_ARG, E_FORMAT, E_TRUNCATED, E_UNSUPPORTED, E_RANGE = 0, -1, -2, -3, -4, -5
+
+
+class OracleError(Exception):
+    def __init__(self, code):
+        super().__init__("oracle error %d" % code)
+        self.code = code
+
+
+class Info(ctypes.Structure):
+    _fields_ = [("W", ctypes.c_int), ("H", ctypes.c_int), ("nc", ctypes.c_int),
+                ("hs", ctypes.c_int * 3), ("vs", ctypes.c_int * 3), ("bw", ctypes.c_int * 3), ("bh", ctypes.c_int * 3),
+                ("nscans", ctypes.c_int), ("progressive", ctypes.c_int)]
+
+    @property
+    def coef_count(self):
+        return sum(self.bw[c] * self.bh[c] * 64 for c in range(self.nc))
+
+
+def build(force=False):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        u8p = ctypes.POINTER(ctypes.c_uint8)
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.orc_record_header.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32),
+                                        ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_int)]
+        L.orc_record_index.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint32),
+                                       ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint64)]
+        L.orc_reassemble.argtypes = [u8p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_int, u8p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+        L.orc_image_info.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(Info)]
+        L.orc_decode.argtypes = [u8p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int16), u8p]
+        L.orc_decode_record_image.argtypes = [u8p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.POINTER(ctypes.c_int16), u8p]
+        L.orc_record_image_info.argtypes = [u8p, ctypes.c_size_t, ctypes.c_uint32, ctypes.POINTER(Info)]
+        L.orc_idct_direct.argtypes = [dp, dp]
+        L.orc_idct_direct.restype = None
+        L.orc_idct_separable.argtypes = [dp, dp]
+        L.orc_idct_separable.restype = None
+        _lib = L
+    return _lib
+
+
+def _u8(b):
+    a = np.frombuffer(b, np.uint8) if not isinstance(b, np.ndarray) else b
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+def _check(rc):
+    if rc != 0:
+        raise OracleError(rc)
+
+
+def record_header(rec):
+    a, p = _u8(rec)
+    n, G, hb, k = ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_uint64(), ctypes.c_int()
+    _check(lib().orc_record_header(p, a.size, ctypes.byref(n), ctypes.byref(G), ctypes.byref(hb), ctypes.byref(k)))
+    return dict(n=n.value, G=G.value, header_bytes=hb.value, k_avail=k.value)
+
+
+def record_index(rec):
+    """off [G, n] u64, len [G, n] u32, label [n] i32, n_scans [n] u32, group_end [G] u64."""
+    h = record_header(rec)
+    a, p = _u8(rec)
+    n, G = h["n"], h["G"]
+    off = np.zeros((G, n), np.uint64); ln = np.zeros((G, n), np.uint32)
+    label = np.zeros(n, np.int32); ns = np.zeros(n, np.uint32); ge = np.zeros(G, np.uint64)
+    _check(lib().orc_record_index(p, a.size, off.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
+                                  ln.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
+                                  label.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                  ns.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
+                                  ge.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))))
+    return off, ln, label, ns, ge
+
+
+def reassemble(rec, i, k):
+    """Bytes given to the image decoder for image i at scan group k."""
+    a, p = _u8(rec)
+    L = ctypes.c_size_t()
+    _check(lib().orc_reassemble(p, a.size, i, k, None, 0, ctypes.byref(L)))
+    out = np.empty(L.value, np.uint8)
+    _check(lib().orc_reassemble(p, a.size, i, k, out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), out.size, ctypes.byref(L)))
+    return out.tobytes()
+
+
+def image_info(jpg):
+    a, p = _u8(jpg)
+    info = Info()
+    _check(lib().orc_image_info(p, a.size, ctypes.byref(info)))
+    return info
+
+
+def decode(jpg, upsample="replicate", idct="separable", want_coef=True, want_pix=True):
+    """Decode a JPEG byte string (all scans in it).  Returns (coef int16 flat | None,
+    pixels uint8 [H, W, C] | None, info)."""
+    a, p = _u8(jpg)
+    info = image_info(jpg)
+    coef = np.empty(info.coef_count, np.int16) if want_coef else None
+    pix = np.empty((info.H, info.W, info.nc), np.uint8) if want_pix else None
+    _check(lib().orc_decode(p, a.size, 1 if upsample == "triangle" else 0, 1 if idct == "direct" else 0,
+                            coef.ctypes.data_as(ctypes.POINTER(ctypes.c_int16)) if want_coef else None,
+                            pix.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)) if want_pix else None))
+    return coef, pix, info
+
+
+def record_image_info(rec, i):
+    a, p = _u8(rec)
+    info = Info()
+    _check(lib().orc_record_image_info(p, a.size, i, ctypes.byref(info)))
+    return info
+
+
+def decode_record_image(rec, i, k, want_coef=True, want_pix=True, info=None):
+    a, p = _u8(rec)
+    info = info or record_image_info(rec, i)
+    coef = np.empty(info.coef_count, np.int16) if want_coef else None
+    pix = np.empty((info.H, info.W, info.nc), np.uint8) if want_pix else None
+    _check(lib().orc_decode_record_image(p, a.size, i, k, 0, 0,
+                                         coef.ctypes.data_as(ctypes.POINTER(ctypes.c_int16)) if want_coef else None,
+                                         pix.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)) if want_pix else None))
+    return coef, pix, info
+
+
+def decode_record(rec, k, images=None, threads=1, want_coef=True, want_pix=True):
+    """Decode images of a record at scan group k.  Returns list of (coef, pix, info)."""
+    h = record_header(rec)
+    idx = range(h["n"]) if images is None else images
+    if threads <= 1:
+        return [decode_record_image(rec, i, k, want_coef, want_pix) for i in idx]
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(threads) as ex:
+        return list(ex.map(lambda i: decode_record_image(rec, i, k, want_coef, want_pix), idx))
+
+
+def idct(F, direct=False):
+    F = np.ascontiguousarray(F, np.float64).reshape(64)
+    f = np.empty(64, np.float64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    (lib().orc_idct_direct if direct else lib().orc_idct_separable)(F.ctypes.data_as(dp), f.ctypes.data_as(dp))
+    return f.reshape(8, 8)
