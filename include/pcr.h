@@ -1,0 +1,133 @@
+/*
+ * pcr.h -- C ABI of the MI355X (gfx950) decoder for Progressive Compressed Records (PCRs).
+ *
+ * A PCR stores, after a small metadata block, "scan group" 1, 2, ..., G: group g holds the
+ * g-th scan of the progressive JPEG file of every image in the record, so that reading the
+ * record from its start to the end of group k yields the whole batch at fidelity k (paper
+ * Section 3, record figure).  This library opens such a byte prefix, rebuilds the index that
+ * un-groups the scans, and decodes all images at a chosen scan group into uint8 pixels on the
+ * GPU: each image's scans 1..k followed by an end-of-image marker are what a JPEG decoder is
+ * given (Section 3, "Decoding").
+ *
+ * Conventions
+ *   - every function returns PCR_OK (0) or a negative PCR_E_* code; nothing throws or aborts;
+ *     out-parameters are written only on success;
+ *   - "host" / "device" say where a pointer must live; device pointers belong to the HIP
+ *     device the record was opened on;
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream);
+ *   - one handle must not be used from two threads at once; different handles are independent.
+ *
+ * Record byte layout ("PCR1", little endian):
+ *   "PCR1" | u32 version=1 | u32 n | u32 G | u64 header_bytes | u64 group_end[G] |
+ *   i32 label[n] | u32 n_scans[n] | u32 len[G][n] | zero padding to header_bytes |
+ *   group 1 | ... | group G,   group g = region(0,g) | region(1,g) | ... | region(n-1,g)
+ * region(i,g) is the slice of image i's progressive JPEG file from the end of its scan g-1
+ * (or the file start) to the end of its scan g (or the file end for its last scan).
+ *
+ * Not supported (PCR_E_UNSUPPORTED): arithmetic coding, 12-bit samples, lossless and
+ * hierarchical modes, DNL, component counts other than 1 or 3, sampling factors other than 1
+ * or 2, sequential (non-progressive) files, records of 4 GiB or more.
+ */
+#ifndef PCR_H
+#define PCR_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pcr_record pcr_record;      /* opaque; owned by the library */
+
+enum {
+    PCR_OK = 0,
+    PCR_E_ARG = -1,          /* NULL or otherwise unusable argument */
+    PCR_E_FORMAT = -2,       /* bytes are not a well-formed record / JPEG stream */
+    PCR_E_TRUNCATED = -3,    /* the bytes given do not reach the requested scan group */
+    PCR_E_UNSUPPORTED = -4,  /* well-formed but outside what this library decodes */
+    PCR_E_RANGE = -5,        /* index or capacity out of range */
+    PCR_E_NOMEM = -6,
+    PCR_E_DEVICE = -7        /* a HIP call failed, or no gfx950 code object could be loaded */
+};
+
+/*
+ * Open a record (Section 3, "Decoding": locate the scan-group offsets in the metadata).
+ *   bytes, nbytes  host pointer to the record or to any prefix of it; groups that are not
+ *                  wholly inside the prefix are unavailable, never partially used.
+ *   device_id      HIP device that will hold the record and run the decode.
+ * The library copies what it needs (the bytes go to device memory); the caller may free
+ * `bytes` when the call returns.  Frame headers of all images are validated here, so that
+ * malformed or unsupported content is reported synchronously.
+ */
+int pcr_open(const void* bytes, size_t nbytes, int device_id, pcr_record** out);
+
+/* Release a handle and all device memory it owns.  NULL is allowed. */
+void pcr_close(pcr_record* rec);
+
+int pcr_num_images(const pcr_record* rec, int* n);
+int pcr_num_scan_groups(const pcr_record* rec, int* G);            /* groups the record defines */
+int pcr_available_scan_groups(const pcr_record* rec, int* k_max);  /* groups inside the bytes given */
+
+/* Bytes that must be read from the start of the record for fidelity k (1..G): the absolute
+ * offset one past scan group k (Section 3: "from the start of the PCR to the end of the
+ * corresponding scan group"). */
+int pcr_group_end_offset(const pcr_record* rec, int k, uint64_t* off);
+
+/* Width, height, channels (1 or 3) and the 32-bit label of image i.  Any out pointer may be NULL. */
+int pcr_image_info(const pcr_record* rec, int i, int* width, int* height, int* channels, int32_t* label);
+
+/* Output layout: image i occupies bytes [offsets[i], offsets[i+1]) of the output buffer as
+ * H_i x W_i x C_i uint8, row-major, channel-interleaved (NHWC; a dense [N,H,W,C] tensor when all
+ * images have one size).  offsets: host, n+1 entries. */
+int pcr_output_layout(const pcr_record* rec, uint64_t* offsets);
+
+/* ---- parity hooks: intermediate results, computed on the device, returned to the host ---- */
+
+/* The un-grouping index (Section 3, "Encoding": "an index must be created for ungrouping the
+ * scans"): off[g*n+i] = absolute offset of region(i,g+1), len[g*n+i] its length, for the
+ * available groups g < k_max (entries of unavailable groups are left untouched).
+ * Computed by the index kernel.  off, len: host, G*n entries. */
+int pcr_index(pcr_record* rec, uint64_t* off, uint32_t* len);
+
+/* The byte string of image i at fidelity k: regions 1..min(k, scans of i), followed by FF D9 if
+ * and only if scans were left out (Section 3, "Decoding").  dst: host, cap bytes; *len receives
+ * the length (also when dst is NULL, to query).  Gathered by a device kernel. */
+int pcr_reassemble(pcr_record* rec, int i, int k, uint8_t* dst, size_t cap, size_t* len);
+
+/* Coefficient layout: image i occupies int16 elements [offsets[i], offsets[i+1]); inside, the
+ * component planes follow each other, each [bh_c][bw_c][64] in natural (row-major) order, where
+ * bw_c x bh_c is the MCU-padded block grid.  offsets: host, n+1 entries. */
+int pcr_coef_layout(const pcr_record* rec, uint64_t* offsets);
+
+/* Quantised coefficients after scans 1..k (partially refined coefficients are multiples of
+ * 2^Al; coefficients not yet received are 0).  d_coef: device, offsets[n] int16 elements.
+ * Asynchronous on hip_stream. */
+int pcr_decode_coefficients(pcr_record* rec, int k, int16_t* d_coef, void* hip_stream);
+
+/*
+ * The hot call: decode every image of the record at scan group k (1..k_max) to pixels.
+ *   out_u8_nhwc   device pointer, layout as pcr_output_layout; out_capacity in bytes
+ *   d_status      optional device array of n int32: 0, or a PCR_E_* code for an image whose
+ *                 entropy-coded data is corrupt (its pixels are zero-filled)
+ * Runs the whole path on the device: index, marker parsing, unstuffing, progressive Huffman
+ * decode of scans 1..k, refinement, de-quantisation, inverse DCT, chroma replication and
+ * YCbCr->RGB.  Coefficients not yet received count as zero; no smoothing is applied.
+ * Asynchronous and stream-ordered; argument errors are returned before anything is enqueued.
+ */
+int pcr_decode_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
+                     void* hip_stream, int32_t* d_status);
+
+/* Milliseconds the kernels of the last pcr_decode_batch / pcr_decode_coefficients call on this
+ * handle took, one value per stage, measured with HIP events on the call's stream.  Blocks until
+ * that call has finished.  stage_ms: host, PCR_NUM_STAGES floats. */
+enum { PCR_STAGE_INDEX_PARSE = 0, PCR_STAGE_UNSTUFF = 1, PCR_STAGE_ENTROPY = 2, PCR_STAGE_REFINE_APPLY = 3,
+       PCR_STAGE_PIXEL = 4, PCR_NUM_STAGES = 5 };
+int pcr_enable_stage_timing(pcr_record* rec, int on);   /* off by default */
+int pcr_last_stage_ms(pcr_record* rec, float* stage_ms);
+
+const char* pcr_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,166 @@
+"""Thin ctypes binding of libpcr.so (include/pcr.h).  Argument marshalling only: every step of
+the decode path runs in the library's HIP kernels.  PyTorch is used for device memory and the
+current stream.  There is no CPU fallback: without the built library, or without a GPU for the
+calls that need one, these functions raise."""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpcr.so")
+
+OK, E_ARG, E_FORMAT, E_TRUNCATED, E_UNSUPPORTED, E_RANGE, E_NOMEM, E_DEVICE = 0, -1, -2, -3, -4, -5, -6, -7
+NUM_STAGES = 5
+STAGE_NAMES = ("index_parse", "unstuff", "entropy", "refine_apply", "pixel")
+
+# every symbol include/pcr.h declares: name -> (restype, argtypes)
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_vp = ctypes.c_void_p
+SYMBOLS = {
+    "pcr_open": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(_vp)]),
+    "pcr_close": (None, [_vp]),
+    "pcr_num_images": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
+    "pcr_num_scan_groups": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
+    "pcr_available_scan_groups": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
+    "pcr_group_end_offset": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_image_info": (ctypes.c_int, [_vp, ctypes.c_int] + [ctypes.POINTER(ctypes.c_int)] * 3 + [ctypes.POINTER(ctypes.c_int32)]),
+    "pcr_output_layout": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_index": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint32)]),
+    "pcr_reassemble": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, _u8p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]),
+    "pcr_coef_layout": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_decode_coefficients": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp]),
+    "pcr_decode_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
+    "pcr_enable_stage_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "pcr_last_stage_ms": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_float)]),
+    "pcr_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+}
+
+_lib = None
+
+
+class PcrError(RuntimeError):
+    def __init__(self, code, what=""):
+        msg = lib().pcr_strerror(code).decode() if _lib is not None else str(code)
+        super().__init__("%s failed: %s (%d)" % (what or "pcr call", msg, code))
+        self.code = code
+
+
+def lib():
+    """Load libpcr.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libpcr.so is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(or paper_1911_00472_amd/build.py) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            f = getattr(L, name)
+            f.restype = res
+            f.argtypes = args
+        _lib = L
+    return _lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise PcrError(rc, what)
+
+
+class Record:
+    """One opened PCR record (pcr_open ... pcr_close)."""
+
+    def __init__(self, data, device=0):
+        self._h = _vp()
+        self._buf = np.frombuffer(data, np.uint8) if not isinstance(data, np.ndarray) else data
+        _check(lib().pcr_open(self._buf.ctypes.data_as(_vp), self._buf.size, device, ctypes.byref(self._h)), "pcr_open")
+        self.device = device
+        self._buf = None
+        v = ctypes.c_int()
+        _check(lib().pcr_num_images(self._h, ctypes.byref(v)), "pcr_num_images"); self.n = v.value
+        _check(lib().pcr_num_scan_groups(self._h, ctypes.byref(v)), "pcr_num_scan_groups"); self.G = v.value
+        _check(lib().pcr_available_scan_groups(self._h, ctypes.byref(v)), "pcr_available_scan_groups"); self.k_avail = v.value
+
+    def close(self):
+        if self._h:
+            lib().pcr_close(self._h)
+            self._h = _vp()
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def group_end_offset(self, k):
+        v = ctypes.c_uint64()
+        _check(lib().pcr_group_end_offset(self._h, k, ctypes.byref(v)), "pcr_group_end_offset")
+        return v.value
+
+    def image_info(self, i):
+        w, h, c, lab = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int32()
+        _check(lib().pcr_image_info(self._h, i, ctypes.byref(w), ctypes.byref(h), ctypes.byref(c), ctypes.byref(lab)), "pcr_image_info")
+        return w.value, h.value, c.value, lab.value
+
+    def output_layout(self):
+        o = np.zeros(self.n + 1, np.uint64)
+        _check(lib().pcr_output_layout(self._h, o.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))), "pcr_output_layout")
+        return o
+
+    def coef_layout(self):
+        o = np.zeros(self.n + 1, np.uint64)
+        _check(lib().pcr_coef_layout(self._h, o.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))), "pcr_coef_layout")
+        return o
+
+    def index(self):
+        off = np.zeros((self.G, self.n), np.uint64)
+        ln = np.zeros((self.G, self.n), np.uint32)
+        _check(lib().pcr_index(self._h, off.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
+                               ln.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32))), "pcr_index")
+        return off, ln
+
+    def reassemble(self, i, k):
+        L = ctypes.c_size_t()
+        _check(lib().pcr_reassemble(self._h, i, k, None, 0, ctypes.byref(L)), "pcr_reassemble")
+        out = np.empty(L.value, np.uint8)
+        _check(lib().pcr_reassemble(self._h, i, k, out.ctypes.data_as(_u8p), out.size, ctypes.byref(L)), "pcr_reassemble")
+        return out.tobytes()
+
+    def decode_coefficients(self, k, out=None, stream=None):
+        """int16 CUDA tensor of coef_layout()[n] elements (asynchronous on the stream)."""
+        import torch
+        total = int(self.coef_layout()[-1])
+        if out is None:
+            out = torch.empty(total, dtype=torch.int16, device="cuda:%d" % self.device)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_decode_coefficients(self._h, k, out.data_ptr(), s), "pcr_decode_coefficients")
+        return out
+
+    def decode_batch(self, k, out=None, status=None, stream=None):
+        """uint8 CUDA tensor of output_layout()[n] bytes, ragged NHWC (asynchronous on the stream)."""
+        import torch
+        total = int(self.output_layout()[-1])
+        if out is None:
+            out = torch.empty(total, dtype=torch.uint8, device="cuda:%d" % self.device)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_decode_batch(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
+               "pcr_decode_batch")
+        return out
+
+    def enable_stage_timing(self, on=True):
+        _check(lib().pcr_enable_stage_timing(self._h, 1 if on else 0), "pcr_enable_stage_timing")
+
+    def last_stage_ms(self):
+        ms = (ctypes.c_float * NUM_STAGES)()
+        _check(lib().pcr_last_stage_ms(self._h, ms), "pcr_last_stage_ms")
+        return dict(zip(STAGE_NAMES, (float(x) for x in ms)))
+
+
+def pcr_open(data, device=0):
+    return Record(data, device)

@@ -1,0 +1,423 @@
+// C ABI of the PCR decode library (see include/pcr.h) and the host logic behind it: header
+// validation, layout of the device buffers, the work lists that map lanes to restart
+// intervals, and the kernel launches.  Everything data-dependent runs in the kernels of
+// pcr_kernels.h; the host parse done in pcr_open only sizes buffers and rejects bad input early.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <map>
+#include <new>
+#include <vector>
+
+#include "../../include/pcr.h"
+#include "pcr_kernels.h"
+
+using namespace pcr;
+
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return PCR_E_DEVICE; } } while (0)
+
+namespace {
+
+struct LevelList { Unit* d_units = nullptr; uint32_t n = 0; };
+
+struct Plan {                               // launch geometry for one scan group k
+    std::vector<LevelList> levels;
+    ApplyUnit* d_apply = nullptr; uint32_t n_apply = 0, apply_grid_x = 0;
+};
+
+template <class T> int dev_alloc(T** p, size_t count) {
+    *p = nullptr;
+    if (count == 0) count = 1;
+    return hipMalloc((void**)p, count * sizeof(T)) == hipSuccess ? PCR_OK : PCR_E_NOMEM;
+}
+template <class T> int dev_upload(T** p, const std::vector<T>& v) {
+    int rc = dev_alloc(p, v.size());
+    if (rc) return rc;
+    if (!v.empty() && hipMemcpy(*p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return PCR_E_DEVICE;
+    return PCR_OK;
+}
+
+}  // namespace
+
+struct pcr_record {
+    int device = 0;
+    size_t nbytes = 0;
+    RecordHeader hdr{};
+    std::vector<uint8_t> header;            // host copy of the metadata block
+    std::vector<ImgDesc> img;               // host parse (sizes, validation)
+    std::vector<ScanDesc> scan;
+    std::vector<uint8_t> level;             // [n][G] dependency level of each scan (1-based)
+    std::vector<uint64_t> out_off, coef_off, mask_off;
+    std::vector<uint32_t> slot_base, slot_cnt;
+    uint64_t n_masks = 0; uint32_t n_slots = 0; uint32_t max_level = 0;
+    DevRecord d{};
+    uint8_t* d_rec = nullptr;
+    PixelTile* d_tiles = nullptr; uint32_t n_tiles = 0;
+    uint8_t* d_gather = nullptr; size_t gather_cap = 0;
+    std::map<int, Plan> plans;
+    bool timing = false;
+    hipEvent_t ev[PCR_NUM_STAGES + 1] = {};
+    bool ev_valid = false, ev_recorded = false;
+};
+
+namespace {
+
+// level[g] = 1 + max level of an earlier scan that shares a component and overlaps in band
+void compute_levels(pcr_record* r) {
+    const uint32_t n = r->hdr.n, G = r->hdr.G;
+    r->level.assign((size_t)n * G, 0);
+    r->max_level = 0;
+    for (uint32_t i = 0; i < n; i++) {
+        const ScanDesc* s = &r->scan[(size_t)i * G];
+        for (uint32_t g = 0; g < r->img[i].nscans; g++) {
+            uint32_t lv = 1;
+            for (uint32_t q = 0; q < g; q++) {
+                bool share = false;
+                for (int a = 0; a < s[g].ns; a++) for (int b = 0; b < s[q].ns; b++) if (s[g].comp[a] == s[q].comp[b]) share = true;
+                if (share && s[q].Ss <= s[g].Se && s[g].Ss <= s[q].Se) lv = std::max<uint32_t>(lv, r->level[(size_t)i * G + q] + 1u);
+            }
+            r->level[(size_t)i * G + g] = (uint8_t)lv;
+            r->max_level = std::max(r->max_level, lv);
+        }
+    }
+}
+
+int build_plan(pcr_record* r, int k, Plan** out) {
+    auto it = r->plans.find(k);
+    if (it != r->plans.end()) { *out = &it->second; return PCR_OK; }
+    const uint32_t n = r->hdr.n, G = r->hdr.G;
+    Plan plan;
+    std::vector<std::vector<Unit>> lists(r->max_level);
+    std::vector<ApplyUnit> apply; uint32_t max_cov = 0;
+    for (uint32_t i = 0; i < n; i++) {
+        const uint32_t upto = std::min<uint32_t>(r->img[i].nscans, (uint32_t)k);
+        bool refine[kMaxComp] = {false, false, false};
+        for (uint32_t g = 0; g < upto; g++) {
+            const size_t ig = (size_t)i * G + g;
+            const ScanDesc& sd = r->scan[ig];
+            for (uint32_t j = 0; j < r->slot_cnt[ig]; j++) lists[r->level[ig] - 1].push_back(Unit{i, g, j, r->slot_base[ig]});
+            if (sd.Ss > 0 && sd.Ah > 0) refine[sd.comp[0]] = true;
+        }
+        for (int c = 0; c < r->img[i].nc; c++) if (refine[c]) {
+            apply.push_back(ApplyUnit{i, (uint32_t)c});
+            max_cov = std::max<uint32_t>(max_cov, (uint32_t)r->img[i].cw[c] * r->img[i].ch[c]);
+        }
+    }
+    for (auto& l : lists) {
+        LevelList ll; ll.n = (uint32_t)l.size();
+        if (ll.n) { int rc = dev_upload(&ll.d_units, l); if (rc) return rc; }
+        plan.levels.push_back(ll);
+    }
+    plan.n_apply = (uint32_t)apply.size();
+    plan.apply_grid_x = (max_cov * 64 + 255) / 256;
+    if (plan.n_apply) { int rc = dev_upload(&plan.d_apply, apply); if (rc) return rc; }
+    auto ins = r->plans.emplace(k, plan);
+    *out = &ins.first->second;
+    return PCR_OK;
+}
+
+void free_plans(pcr_record* r) {
+    for (auto& kv : r->plans) {
+        for (auto& l : kv.second.levels) if (l.d_units) (void)hipFree(l.d_units);
+        if (kv.second.d_apply) (void)hipFree(kv.second.d_apply);
+    }
+    r->plans.clear();
+}
+
+int check_scan_group(const pcr_record* r, int k) {
+    if (k < 1 || k > (int)r->hdr.G) return PCR_E_RANGE;
+    if (k > (int)r->hdr.k_avail) return PCR_E_TRUNCATED;
+    return PCR_OK;
+}
+
+void stamp(pcr_record* r, int idx, hipStream_t s) { if (r->timing && r->ev_valid) (void)hipEventRecord(r->ev[idx], s); }
+
+// Steps 1-5 of the path (index .. entropy decode + refinement) for scans 1..k.
+int run_entropy_stages(pcr_record* r, int k, hipStream_t s) {
+    Plan* plan = nullptr;
+    int rc = build_plan(r, k, &plan);
+    if (rc) return rc;
+    const uint32_t n = r->hdr.n;
+    stamp(r, 0, s);
+    hipLaunchKernelGGL(k_index, dim3(k), dim3(256), 0, s, r->d, (uint32_t)k);
+    hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, (uint32_t)k);
+    stamp(r, 1, s);
+    hipLaunchKernelGGL(k_unstuff, dim3(n, k), dim3(256), 0, s, r->d, (uint32_t)k);
+    const size_t coef_bytes = r->coef_off[n] * sizeof(int16_t);
+    hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
+    stamp(r, 2, s);
+    const size_t smem = sizeof(HuffTab) * kEntropyLanes * kTabsPerLane + 64;
+    for (auto& l : plan->levels) {
+        if (!l.n) continue;
+        hipLaunchKernelGGL(k_entropy, dim3((l.n + kEntropyLanes - 1) / kEntropyLanes), dim3(kEntropyLanes), smem, s, r->d, l.d_units, l.n);
+    }
+    stamp(r, 3, s);
+    if (plan->n_apply) hipLaunchKernelGGL(k_apply, dim3(plan->apply_grid_x, plan->n_apply), dim3(256), 0, s, r->d, plan->d_apply, (uint32_t)k);
+    stamp(r, 4, s);
+    if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
+    return PCR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out) {
+    if (!bytes_ || !out) return PCR_E_ARG;
+    const uint8_t* bytes = (const uint8_t*)bytes_;
+    RecordHeader h;
+    int rc = parse_record_header(bytes, nbytes, &h);
+    if (rc) return rc;
+    if (nbytes >= (1ull << 32)) return PCR_E_UNSUPPORTED;
+    if (h.k_avail == 0) return PCR_E_TRUNCATED;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device_id < 0 || device_id >= ndev) { (void)hipGetLastError(); return PCR_E_DEVICE; }
+    HIP_TRY(hipSetDevice(device_id));
+
+    pcr_record* r = new (std::nothrow) pcr_record();
+    if (!r) return PCR_E_NOMEM;
+    r->device = device_id; r->nbytes = nbytes; r->hdr = h;
+    const uint32_t n = h.n, G = h.G;
+    // ---- host index over the available groups (sizes buffers, validates tiling) ----
+    std::vector<uint32_t> off((size_t)G * n, 0), len((size_t)G * n, 0), nsc(n);
+    r->header.assign(bytes, bytes + h.header_bytes);
+    uint64_t start = h.header_bytes;
+    for (uint32_t g = 0; g < h.k_avail; g++) {
+        uint64_t pos = start;
+        for (uint32_t i = 0; i < n; i++) {
+            uint32_t L = ld_le32(bytes + hdr_len_pos(n, G, g, i));
+            off[(size_t)g * n + i] = (uint32_t)pos; len[(size_t)g * n + i] = L; pos += L;
+        }
+        if (pos != ld_le64(bytes + hdr_group_end_pos(g))) { delete r; return PCR_E_FORMAT; }
+        start = pos;
+    }
+    for (uint32_t i = 0; i < n; i++) {
+        nsc[i] = ld_le32(bytes + hdr_nscans_pos(n, G, i));
+        if (nsc[i] == 0 || nsc[i] > G) { delete r; return PCR_E_FORMAT; }
+        for (uint32_t g = 0; g < h.k_avail; g++)
+            if ((g < nsc[i]) != (len[(size_t)g * n + i] != 0)) { delete r; return PCR_E_FORMAT; }
+    }
+    // ---- host marker parse of every image: layout, work sizes, early rejection ----
+    r->img.resize(n); r->scan.assign((size_t)n * G, ScanDesc{});
+    for (uint32_t i = 0; i < n; i++) {
+        parse_image(bytes, off.data(), len.data(), n, i, nsc[i], h.k_avail, &r->img[i], &r->scan[(size_t)i * G]);
+        if (r->img[i].status != kOk) { rc = r->img[i].status; delete r; return rc; }
+    }
+    compute_levels(r);
+    r->out_off.assign(n + 1, 0); r->coef_off.assign(n + 1, 0);
+    r->mask_off.assign((size_t)n * G, 0); r->slot_base.assign((size_t)n * G, 0); r->slot_cnt.assign((size_t)n * G, 0);
+    std::vector<PixelTile> tiles;
+    uint64_t nm = 0; uint64_t ns = 0;
+    for (uint32_t i = 0; i < n; i++) {
+        const ImgDesc& d = r->img[i];
+        r->out_off[i + 1] = r->out_off[i] + (uint64_t)d.W * d.H * d.nc;
+        uint64_t cc = 0;
+        for (int c = 0; c < d.nc; c++) cc += (uint64_t)d.bw[c] * d.bh[c] * 64;
+        r->coef_off[i + 1] = r->coef_off[i] + cc;
+        for (uint32_t g = 0; g < d.nscans; g++) {
+            const size_t ig = (size_t)i * G + g;
+            const ScanDesc& sd = r->scan[ig];
+            if (sd.Ss > 0) {
+                r->mask_off[ig] = nm;
+                nm += (uint64_t)d.bw[sd.comp[0]] * d.bh[sd.comp[0]] * (sd.Ah ? 3 : 1);
+            }
+            uint32_t cnt = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;
+            r->slot_base[ig] = (uint32_t)ns; r->slot_cnt[ig] = cnt;
+            ns += cnt + 1;
+        }
+        for (uint32_t my = 0; my < d.mcuy; my++)
+            for (uint32_t mx = 0; mx < d.mcux; mx += kStripMcus) tiles.push_back(PixelTile{i, (uint16_t)my, (uint16_t)mx});
+    }
+    if (ns >= (1ull << 32)) { delete r; return PCR_E_UNSUPPORTED; }
+    r->n_masks = nm; r->n_slots = (uint32_t)ns; r->n_tiles = (uint32_t)tiles.size();
+
+    // ---- device buffers ----
+    DevRecord& d = r->d;
+    rc = PCR_OK;
+    const size_t padded = nbytes + 64;
+    if (!rc) rc = dev_alloc(&r->d_rec, padded);
+    if (!rc) rc = dev_alloc(&d.clean, padded);
+    if (!rc) rc = dev_alloc(&d.off, (size_t)G * n);
+    if (!rc) rc = dev_alloc(&d.img, n);
+    if (!rc) rc = dev_alloc(&d.scan, (size_t)n * G);
+    if (!rc) rc = dev_alloc(&d.coef, r->coef_off[n]);
+    if (!rc) rc = dev_alloc(&d.masks, nm);
+    if (!rc) rc = dev_alloc(&d.ivl_start, ns);
+    if (!rc) rc = dev_alloc(&d.status, n);
+    uint64_t *d_coef_off = nullptr, *d_out_off = nullptr, *d_mask_off = nullptr; uint32_t *d_sb = nullptr, *d_sc = nullptr;
+    if (!rc) rc = dev_upload(&d_coef_off, r->coef_off);
+    if (!rc) rc = dev_upload(&d_out_off, r->out_off);
+    if (!rc) rc = dev_upload(&d_mask_off, r->mask_off);
+    if (!rc) rc = dev_upload(&d_sb, r->slot_base);
+    if (!rc) rc = dev_upload(&d_sc, r->slot_cnt);
+    if (!rc) rc = dev_upload(&r->d_tiles, tiles);
+    d.coef_off = d_coef_off; d.out_off = d_out_off; d.mask_off = d_mask_off; d.slot_base = d_sb; d.slot_cnt = d_sc;
+    if (!rc && hipMemcpy(r->d_rec, bytes, nbytes, hipMemcpyHostToDevice) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemset(r->d_rec + nbytes, 0, padded - nbytes) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemset(d.clean, 0xFF, padded) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemset(d.off, 0, (size_t)G * n * sizeof(uint32_t)) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemset(d.scan, 0, (size_t)n * G * sizeof(ScanDesc)) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemset(d.masks, 0, (nm ? nm : 1) * sizeof(uint64_t)) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemset(d.ivl_start, 0, (ns ? ns : 1) * sizeof(uint32_t)) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc) {
+        d.rec = r->d_rec; d.n = n; d.G = G;
+        d.len = (const uint32_t*)(r->d_rec + hdr_len_pos(n, G, 0, 0));
+        d.nscans = (const uint32_t*)(r->d_rec + hdr_nscans_pos(n, G, 0));
+        const size_t smem = sizeof(HuffTab) * kEntropyLanes * kTabsPerLane + 64;
+        if (hipFuncSetAttribute((const void*)k_entropy, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) rc = PCR_E_DEVICE;
+    }
+    if (!rc) {
+        bool ok = true;
+        for (auto& e : r->ev) ok = ok && hipEventCreate(&e) == hipSuccess;
+        r->ev_valid = ok;
+    }
+    if (rc) { (void)hipGetLastError(); pcr_close(r); return rc; }
+    *out = r;
+    return PCR_OK;
+}
+
+void pcr_close(pcr_record* r) {
+    if (!r) return;
+    (void)hipSetDevice(r->device);
+    (void)hipDeviceSynchronize();
+    free_plans(r);
+    DevRecord& d = r->d;
+    void* ptrs[] = { r->d_rec, d.clean, d.off, d.img, d.scan, d.coef, d.masks, d.ivl_start, d.status, (void*)d.coef_off, (void*)d.out_off,
+                     (void*)d.mask_off, (void*)d.slot_base, (void*)d.slot_cnt, r->d_tiles, r->d_gather };
+    for (void* p : ptrs) if (p) (void)hipFree(p);
+    if (r->ev_valid) for (auto& e : r->ev) (void)hipEventDestroy(e);
+    delete r;
+}
+
+int pcr_num_images(const pcr_record* r, int* n) { if (!r || !n) return PCR_E_ARG; *n = (int)r->hdr.n; return PCR_OK; }
+int pcr_num_scan_groups(const pcr_record* r, int* G) { if (!r || !G) return PCR_E_ARG; *G = (int)r->hdr.G; return PCR_OK; }
+int pcr_available_scan_groups(const pcr_record* r, int* k) { if (!r || !k) return PCR_E_ARG; *k = (int)r->hdr.k_avail; return PCR_OK; }
+
+int pcr_group_end_offset(const pcr_record* r, int k, uint64_t* off) {
+    if (!r || !off) return PCR_E_ARG;
+    if (k < 1 || k > (int)r->hdr.G) return PCR_E_RANGE;
+    *off = ld_le64(r->header.data() + hdr_group_end_pos((uint32_t)k - 1));
+    return PCR_OK;
+}
+
+int pcr_image_info(const pcr_record* r, int i, int* w, int* h, int* c, int32_t* label) {
+    if (!r) return PCR_E_ARG;
+    if (i < 0 || i >= (int)r->hdr.n) return PCR_E_RANGE;
+    if (w) *w = r->img[i].W;
+    if (h) *h = r->img[i].H;
+    if (c) *c = r->img[i].nc;
+    if (label) *label = (int32_t)ld_le32(r->header.data() + hdr_label_pos(r->hdr.G, (uint32_t)i));
+    return PCR_OK;
+}
+
+int pcr_output_layout(const pcr_record* r, uint64_t* offsets) {
+    if (!r || !offsets) return PCR_E_ARG;
+    std::memcpy(offsets, r->out_off.data(), r->out_off.size() * sizeof(uint64_t));
+    return PCR_OK;
+}
+
+int pcr_coef_layout(const pcr_record* r, uint64_t* offsets) {
+    if (!r || !offsets) return PCR_E_ARG;
+    std::memcpy(offsets, r->coef_off.data(), r->coef_off.size() * sizeof(uint64_t));
+    return PCR_OK;
+}
+
+int pcr_index(pcr_record* r, uint64_t* off, uint32_t* len) {
+    if (!r || !off || !len) return PCR_E_ARG;
+    HIP_TRY(hipSetDevice(r->device));
+    const uint32_t n = r->hdr.n, G = r->hdr.G, k = r->hdr.k_avail;
+    hipLaunchKernelGGL(k_index, dim3(k), dim3(256), 0, 0, r->d, k);
+    std::vector<uint32_t> o((size_t)G * n);
+    HIP_TRY(hipMemcpy(o.data(), r->d.off, o.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    std::vector<uint32_t> l((size_t)G * n);
+    HIP_TRY(hipMemcpy(l.data(), r->d.len, l.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    for (size_t e = 0; e < (size_t)k * n; e++) { off[e] = o[e]; len[e] = l[e]; }
+    return PCR_OK;
+}
+
+int pcr_reassemble(pcr_record* r, int i, int k, uint8_t* dst, size_t cap, size_t* len) {
+    if (!r || !len) return PCR_E_ARG;
+    if (i < 0 || i >= (int)r->hdr.n) return PCR_E_RANGE;
+    int rc = check_scan_group(r, k);
+    if (rc) return rc;
+    const uint32_t n = r->hdr.n, G = r->hdr.G;
+    const uint32_t ns = ld_le32(r->header.data() + hdr_nscans_pos(n, G, (uint32_t)i));
+    const uint32_t have = std::min<uint32_t>(ns, (uint32_t)k);
+    size_t total = 0;
+    for (uint32_t g = 0; g < have; g++) total += ld_le32(r->header.data() + hdr_len_pos(n, G, g, (uint32_t)i));
+    const int add_eoi = have < ns;
+    total += add_eoi ? 2 : 0;
+    if (!dst) { *len = total; return PCR_OK; }
+    if (cap < total) return PCR_E_RANGE;
+    HIP_TRY(hipSetDevice(r->device));
+    if (r->gather_cap < total) {
+        if (r->d_gather) (void)hipFree(r->d_gather);
+        r->d_gather = nullptr; r->gather_cap = 0;
+        if (hipMalloc((void**)&r->d_gather, total) != hipSuccess) return PCR_E_NOMEM;
+        r->gather_cap = total;
+    }
+    hipLaunchKernelGGL(k_index, dim3(k), dim3(256), 0, 0, r->d, (uint32_t)k);
+    hipLaunchKernelGGL(k_gather, dim3(64), dim3(256), 0, 0, r->d, (uint32_t)i, have, add_eoi, r->d_gather);
+    HIP_TRY(hipMemcpy(dst, r->d_gather, total, hipMemcpyDeviceToHost));
+    *len = total;
+    return PCR_OK;
+}
+
+int pcr_enable_stage_timing(pcr_record* r, int on) { if (!r) return PCR_E_ARG; r->timing = on != 0; return PCR_OK; }
+
+int pcr_last_stage_ms(pcr_record* r, float* ms) {
+    if (!r || !ms) return PCR_E_ARG;
+    if (!r->timing || !r->ev_valid || !r->ev_recorded) return PCR_E_ARG;
+    HIP_TRY(hipSetDevice(r->device));
+    HIP_TRY(hipEventSynchronize(r->ev[PCR_NUM_STAGES]));
+    for (int s = 0; s < PCR_NUM_STAGES; s++) HIP_TRY(hipEventElapsedTime(&ms[s], r->ev[s], r->ev[s + 1]));
+    return PCR_OK;
+}
+
+int pcr_decode_coefficients(pcr_record* r, int k, int16_t* d_coef, void* stream) {
+    if (!r || !d_coef) return PCR_E_ARG;
+    int rc = check_scan_group(r, k);
+    if (rc) return rc;
+    HIP_TRY(hipSetDevice(r->device));
+    hipStream_t s = (hipStream_t)stream;
+    rc = run_entropy_stages(r, k, s);
+    if (rc) return rc;
+    stamp(r, 5, s);
+    r->ev_recorded = r->timing && r->ev_valid;
+    HIP_TRY(hipMemcpyAsync(d_coef, r->d.coef, r->coef_off[r->hdr.n] * sizeof(int16_t), hipMemcpyDeviceToDevice, s));
+    return PCR_OK;
+}
+
+int pcr_decode_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status) {
+    if (!r || !out) return PCR_E_ARG;
+    int rc = check_scan_group(r, k);
+    if (rc) return rc;
+    if (cap < r->out_off[r->hdr.n]) return PCR_E_RANGE;
+    HIP_TRY(hipSetDevice(r->device));
+    hipStream_t s = (hipStream_t)stream;
+    rc = run_entropy_stages(r, k, s);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_pixel, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out);
+    stamp(r, 5, s);
+    r->ev_recorded = r->timing && r->ev_valid;
+    if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
+    if (d_status) HIP_TRY(hipMemcpyAsync(d_status, r->d.status, r->hdr.n * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+    return PCR_OK;
+}
+
+const char* pcr_strerror(int code) {
+    switch (code) {
+        case PCR_OK: return "ok";
+        case PCR_E_ARG: return "invalid argument";
+        case PCR_E_FORMAT: return "malformed record or JPEG stream";
+        case PCR_E_TRUNCATED: return "record bytes do not reach the requested scan group";
+        case PCR_E_UNSUPPORTED: return "unsupported JPEG feature or record size";
+        case PCR_E_RANGE: return "index or capacity out of range";
+        case PCR_E_NOMEM: return "out of memory";
+        case PCR_E_DEVICE: return "HIP device error";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

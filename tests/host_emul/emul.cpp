@@ -1,0 +1,133 @@
+// CPU build of the library's host/device decode functions (pcr_format.h, pcr_entropy.h,
+// pcr_pixel.h) driven by plain loops.  Test-only: lets the exact lane code be checked against
+// the oracle, with bounds-checked buffers and a debugger, before it runs on a GPU.  The
+// kernels' own indexing (k_unstuff, k_pixel tiling) is NOT covered here.
+#include <cstdint>
+#include <cstring>
+#include <vector>
+#include "../../paper_1911_00472_amd/csrc/pcr_format.h"
+#include "../../paper_1911_00472_amd/csrc/pcr_entropy.h"
+#include "../../paper_1911_00472_amd/csrc/pcr_pixel.h"
+
+using namespace pcr;
+
+// serial stand-in for the unstuff kernel: same rules (drop stuffed zeros, fill bytes and
+// restart markers, stop at any other marker, note interval starts)
+static void unstuff(const uint8_t* src, uint32_t L, std::vector<uint8_t>& out, std::vector<uint32_t>& starts) {
+    out.clear(); starts.assign(1, 0);
+    for (uint32_t q = 0; q < L; q++) {
+        uint8_t cur = src[q];
+        if (cur != 0xFF) { out.push_back(cur); continue; }
+        if (q + 1 >= L) break;
+        uint8_t nx = src[q + 1];
+        if (nx == 0x00) { out.push_back(0xFF); q++; }
+        else if (nx >= 0xD0 && nx <= 0xD7) { starts.push_back((uint32_t)out.size()); q++; }
+        else if (nx == 0xFF) continue;
+        else break;
+    }
+}
+
+extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int64_t want_img, int16_t* coef_out, uint8_t* pix_out,
+                                  int* W, int* H, int* C) {
+    RecordHeader h;
+    int rc = parse_record_header(rec, nbytes, &h);
+    if (rc) return rc;
+    if (k < 1 || k > (int)h.k_avail) return kERange;
+    uint32_t n = h.n, G = h.G;
+    std::vector<uint32_t> off((size_t)G * n), len((size_t)G * n);
+    uint64_t start = h.header_bytes;
+    for (uint32_t g = 0; g < h.k_avail; g++) {
+        uint64_t pos = start;
+        for (uint32_t i = 0; i < n; i++) { uint32_t L = ld_le32(rec + hdr_len_pos(n, G, g, i)); off[(size_t)g * n + i] = (uint32_t)pos; len[(size_t)g * n + i] = L; pos += L; }
+        start = pos;
+    }
+    uint32_t i = (uint32_t)want_img;
+    ImgDesc img; std::vector<ScanDesc> sc(G);
+    memset(&img, 0, sizeof img);
+    parse_image(rec, off.data(), len.data(), n, i, ld_le32(rec + hdr_nscans_pos(n, G, i)), (uint32_t)k, &img, sc.data());
+    if (img.status) return img.status;
+    *W = img.W; *H = img.H; *C = img.nc;
+    size_t poff[4] = {0, 0, 0, 0};
+    for (int c = 0; c < img.nc; c++) poff[c + 1] = poff[c] + (size_t)img.bw[c] * img.bh[c] * 64;
+    std::vector<int16_t> coef(poff[img.nc], 0);
+    std::vector<std::vector<uint64_t>> masks(G);
+    uint8_t zz[64]; for (int q = 0; q < 64; q++) zz[q] = (uint8_t)zigzag_natural(q);
+    for (uint32_t g = 0; g < img.nscans; g++) {
+        const ScanDesc& sd = sc[g];
+        std::vector<uint8_t> clean; std::vector<uint32_t> starts;
+        unstuff(rec + sd.data_off, sd.data_len, clean, starts);
+        uint32_t nint = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;
+        if (starts.size() != nint) return kEFormat;
+        starts.push_back((uint32_t)clean.size());
+        clean.resize(clean.size() + 16, 0xFF);
+        int c0 = sd.comp[0];
+        size_t plane = (size_t)img.bw[c0] * img.bh[c0];
+        if (sd.Ss > 0) masks[g].assign(plane * (sd.Ah ? 3 : 1), 0);
+        for (uint32_t j = 0; j < nint; j++) {
+            BitReader br; br.init(clean.data() + starts[j], starts[j + 1] - starts[j]);
+            UnitGeom ug; ug.mcu_w = sd.mcu_w; ug.mcu0 = sd.ri ? j * sd.ri : 0;
+            ug.mcu1 = sd.ri ? (ug.mcu0 + sd.ri < sd.mcus ? ug.mcu0 + sd.ri : sd.mcus) : sd.mcus;
+            int16_t* cpl[kMaxComp];
+            for (int q = 0; q < sd.ns; q++) cpl[q] = coef.data() + poff[sd.comp[q]];
+            std::vector<HuffTab> tabs(3);
+            if (sd.Ss == 0) {
+                if (sd.Ah == 0) {
+                    const HuffTab* tp[kMaxComp];
+                    for (int q = 0; q < sd.ns; q++) { hufftab_build(&tabs[q], rec + sd.dc_off[q]); tp[q] = &tabs[q]; }
+                    rc = decode_dc_first(&br, &img, &sd, &ug, tp, cpl);
+                } else rc = decode_dc_refine(&br, &img, &sd, &ug, cpl);
+            } else {
+                hufftab_build(&tabs[0], rec + sd.ac_off);
+                if (sd.Ah == 0) rc = decode_ac_first(&br, &img, &sd, &ug, &tabs[0], zz, cpl[0], masks[g].data());
+                else {
+                    const uint64_t* hist[kMaxHist];
+                    for (int q = 0; q < sd.nhist; q++) hist[q] = masks[sd.hist[q]].data();
+                    rc = decode_ac_refine(&br, &img, &sd, &ug, &tabs[0], hist, sd.nhist, masks[g].data(), masks[g].data() + plane, masks[g].data() + 2 * plane);
+                }
+            }
+            if (rc) return rc;
+        }
+    }
+    // refinement apply
+    for (int c = 0; c < img.nc; c++) {
+        size_t plane = (size_t)img.bw[c] * img.bh[c];
+        for (uint32_t by = 0; by < img.ch[c]; by++) for (uint32_t bx = 0; bx < img.cw[c]; bx++) for (int kk = 0; kk < 64; kk++) {
+            size_t blk = (size_t)by * img.bw[c] + bx;
+            int16_t* cp = coef.data() + poff[c] + blk * 64 + zz[kk];
+            int16_t v = *cp; uint64_t hh = 0;
+            for (uint32_t g = 0; g < img.nscans; g++) {
+                const ScanDesc& sd = sc[g];
+                if (sd.Ss == 0 || sd.comp[0] != c) continue;
+                const uint64_t* mk = masks[g].data();
+                if (sd.Ah != 0 && kk >= sd.Ss && kk <= sd.Se) v = refine_apply(v, kk, hh & band_mask(sd.Ss, sd.Se), mk[blk], mk[plane + blk], mk[2 * plane + blk], sd.Al);
+                hh |= mk[blk];
+            }
+            *cp = v;
+        }
+    }
+    if (coef_out) memcpy(coef_out, coef.data(), coef.size() * sizeof(int16_t));
+    if (pix_out) {
+        std::vector<std::vector<float>> pl(img.nc);
+        for (int c = 0; c < img.nc; c++) {
+            uint32_t pw = img.bw[c] * 8;
+            pl[c].assign((size_t)pw * img.bh[c] * 8, 0.f);
+            float qn[64];
+            const uint8_t* q = rec + img.qoff[img.tq[c]];
+            for (int kk = 0; kk < 64; kk++) qn[zz[kk]] = img.qprec[img.tq[c]] ? (float)ld_be16(q + 2 * kk) : (float)q[kk];
+            for (uint32_t by = 0; by < img.bh[c]; by++) for (uint32_t bx = 0; bx < img.bw[c]; bx++) {
+                const int16_t* blk = coef.data() + poff[c] + ((size_t)by * img.bw[c] + bx) * 64;
+                float t[64];
+                for (int v = 0; v < 8; v++) { float in[8], res[8]; for (int u = 0; u < 8; u++) in[u] = (float)blk[v * 8 + u] * qn[v * 8 + u]; idct8(in, res); for (int x = 0; x < 8; x++) t[v * 8 + x] = res[x]; }
+                for (int x = 0; x < 8; x++) { float in[8], res[8]; for (int v = 0; v < 8; v++) in[v] = t[v * 8 + x]; idct8(in, res);
+                    for (int y = 0; y < 8; y++) pl[c][(size_t)(by * 8 + y) * pw + bx * 8 + x] = clamp255(res[y] + 128.f); }
+            }
+        }
+        for (uint32_t y = 0; y < img.H; y++) for (uint32_t x = 0; x < img.W; x++) {
+            float s[3];
+            for (int c = 0; c < img.nc; c++) s[c] = pl[c][(size_t)(y * img.vs[c] / img.vmax) * (img.bw[c] * 8) + x * img.hs[c] / img.hmax];
+            uint8_t* o = pix_out + ((size_t)y * img.W + x) * img.nc;
+            if (img.nc == 1) o[0] = round_u8(s[0]); else ycc_to_rgb(s[0], s[1], s[2], o);
+        }
+    }
+    return kOk;
+}

@@ -1,0 +1,71 @@
+"""The library's host/device decode functions (marker parser, Huffman tables, bit reader, the
+four scan decoders, refinement apply, IDCT and colour) compiled for the CPU and driven by plain
+loops, compared with the oracle.  This checks the lane code before it ever runs on a GPU; the
+kernels' own indexing is covered by the GPU tests."""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+import pcrgen
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "host_emul", "emul.cpp")
+LIB = os.path.join(HERE, "host_emul", "libemul.so")
+u8p = ctypes.POINTER(ctypes.c_uint8)
+
+
+@pytest.fixture(scope="module")
+def emul():
+    subprocess.check_call(["g++", "-O1", "-std=c++17", "-fPIC", "-shared", "-o", LIB, SRC])
+    L = ctypes.CDLL(LIB)
+    L.emul_decode_record.argtypes = [u8p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int64, ctypes.POINTER(ctypes.c_int16), u8p] + \
+        [ctypes.POINTER(ctypes.c_int)] * 3
+
+    def run(rec, i, k, info):
+        a = np.frombuffer(rec, np.uint8)
+        coef = np.zeros(info.coef_count, np.int16)
+        pix = np.zeros((info.H, info.W, info.nc), np.uint8)
+        W, H, C = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        rc = L.emul_decode_record(a.ctypes.data_as(u8p), a.size, k, i, coef.ctypes.data_as(ctypes.POINTER(ctypes.c_int16)),
+                                  pix.ctypes.data_as(u8p), W, H, C)
+        assert rc == 0, rc
+        assert (W.value, H.value, C.value) == (info.W, info.H, info.nc)
+        return coef, pix
+    return run
+
+
+def _compare(emul, rec, images, ks):
+    for i in images:
+        info = oracle.record_image_info(rec, i)
+        for k in ks:
+            c0, p0, _ = oracle.decode_record_image(rec, i, k)
+            c1, p1 = emul(rec, i, k, info)
+            assert np.array_equal(c0, c1), (i, k)
+            assert np.abs(p0.astype(int) - p1).max() <= 1, (i, k)
+
+
+def test_lane_code_matches_oracle_small_colour(emul, rgb_small):
+    rec, files = rgb_small
+    _compare(emul, rec, range(len(files)), range(1, 11))
+
+
+def test_lane_code_matches_oracle_gray(emul, gray64):
+    rec, files = gray64
+    _compare(emul, rec, range(0, 64, 7), range(1, 7))
+
+
+def test_lane_code_matches_oracle_444_and_deep_script(emul):
+    from test_oracle_entropy import DEEP
+    files = []
+    for i, (w, h) in enumerate([(50, 35), (90, 41), (33, 70)]):
+        img = pcrgen.synth(300 + i, 2, w, h, 3, 10.0)
+        files.append(pcrgen.encode_pixels(img, 1, 1, 95, None, restart=i % 2))
+        files.append(pcrgen.encode_pixels(img, 2, 1, 80, DEEP, restart=0))
+    rec = pcrgen.write_record(files)
+    G = oracle.record_header(rec)["G"]
+    assert G == len(DEEP)
+    _compare(emul, rec, range(len(files)), range(1, G + 1))

@@ -1,0 +1,184 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Bit-exact for the index, the reassembled bytes and the coefficient planes; at most
+1 LSB apart on uint8 pixels (fp32 on the GPU against fp64 in the oracle, one final rounding on
+both sides)."""
+import numpy as np
+import pytest
+
+import oracle
+import pcrgen
+import paper_1911_00472_amd as pkg
+
+pytestmark = pytest.mark.gpu
+
+PIXEL_TOL = 1      # LSB of uint8
+
+
+def _torch():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def _check_record(rec, ks, images=None, threads=16, check_bytes=True):
+    torch = _torch()
+    with pkg.pcr_open(rec, 0) as r:
+        h = oracle.record_header(rec)
+        assert (r.n, r.G, r.k_avail) == (h["n"], h["G"], h["k_avail"])
+        off0, len0, label0, ns0, ge0 = oracle.record_index(rec)
+        off1, len1 = r.index()
+        assert np.array_equal(off0, off1) and np.array_equal(len0, len1)
+        for k in range(1, r.G + 1):
+            assert r.group_end_offset(k) == ge0[k - 1]
+        lay, clay = r.output_layout(), r.coef_layout()
+        idx = list(range(r.n)) if images is None else list(images)
+        infos = {i: oracle.record_image_info(rec, i) for i in idx}
+        for i in idx:
+            w, hh, c, lab = r.image_info(i)
+            assert (w, hh, c, lab) == (infos[i].W, infos[i].H, infos[i].nc, label0[i])
+            assert lay[i + 1] - lay[i] == w * hh * c and clay[i + 1] - clay[i] == infos[i].coef_count
+        for k in ks:
+            status = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
+            coef = r.decode_coefficients(k).cpu().numpy()
+            out = r.decode_batch(k, status=status).cpu().numpy()
+            assert (status.cpu().numpy() == 0).all()
+            ref = oracle.decode_record(rec, k, images=idx, threads=threads)
+            for i, (c0, p0, info) in zip(idx, ref):
+                assert np.array_equal(coef[int(clay[i]):int(clay[i + 1])], c0), ("coefficients", i, k)
+                got = out[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
+                assert np.abs(got - p0).max() <= PIXEL_TOL, ("pixels", i, k)
+            if check_bytes:
+                for i in idx[:4]:
+                    assert r.reassemble(i, k) == oracle.reassemble(rec, i, k)
+
+
+def test_gray64_all_images(gray64):
+    rec, _ = gray64
+    _check_record(rec, (1, 3, 6))
+
+
+def test_odd_sizes_420_every_scan_group(rgb_small):
+    rec, _ = rgb_small
+    _check_record(rec, range(1, 11))
+
+
+def test_444_422_and_deep_script():
+    from test_oracle_entropy import DEEP
+    files = []
+    for i, (w, h) in enumerate([(50, 35), (90, 41), (33, 70), (1, 1), (300, 8)]):
+        img = pcrgen.synth(300 + i, 2, w, h, 3, 10.0)
+        files.append(pcrgen.encode_pixels(img, 1, 1, 95, None, restart=i % 2))
+        files.append(pcrgen.encode_pixels(img, 2, 1, 80, DEEP, restart=0))
+        files.append(pcrgen.encode_pixels(img, 1, 2, 85, DEEP, restart=3))
+    rec = pcrgen.write_record(files)
+    _check_record(rec, range(1, len(DEEP) + 1))
+
+
+def test_heterogeneous_record_gray_and_colour():
+    g = [pcrgen.make_jpeg(i, 0, 40 + i, 24 + 2 * i, 1, 8.0, 1, 1, 90) for i in range(5)]
+    c = [pcrgen.make_jpeg(50 + i, 1, 33 + i, 47, 3, 6.0, 2, 2, 90, restart=i % 2) for i in range(5)]
+    rec = pcrgen.write_record([g[0], c[0], g[1], c[1], c[2], g[2], g[3], c[3], c[4], g[4]])
+    _check_record(rec, range(1, 11))
+
+
+def test_rgb256_record_spans_many_workgroups():
+    """A slice of the 1024 x 256x256 workload: 96 images, every scan group."""
+    records, _ = pcrgen.make_workload("rgb256", limit=96)
+    _check_record(records[0], range(1, 11), check_bytes=False)
+
+
+def test_restart_intervals_high_resolution():
+    """Two 1024x1024 images with one restart interval per MCU row of each scan."""
+    records, _ = pcrgen.make_workload("hires1024", limit=2)
+    _check_record(records[0], (1, 5, 10), check_bytes=False)
+
+
+def test_headline_workload_sampled():
+    """The benchmark's workload (variable 300..500 px, 4:2:0, about 105 kB per image) in the
+    launch configuration the benchmark times: one record of 256 images, oracle on a sample."""
+    records, _ = pcrgen.make_workload("imagenet_like", limit=256)
+    rng = np.random.default_rng(5)
+    sample = sorted(rng.choice(256, size=24, replace=False).tolist())
+    _check_record(records[0], (1, 2, 5, 10), images=sample, check_bytes=False)
+
+
+def test_ham_like_444():
+    records, _ = pcrgen.make_workload("ham_like", limit=12)
+    _check_record(records[0], (1, 4, 7, 10), check_bytes=False)
+
+
+def test_truncated_record_prefix(rgb_small):
+    """Reading only up to the end of group k (paper Section 3) serves fidelities 1..k with the
+    same results as the whole record, and refuses k+1."""
+    rec, _ = rgb_small
+    _, _, _, _, ge = oracle.record_index(rec)
+    torch = _torch()
+    with pkg.pcr_open(rec, 0) as full:
+        want = {k: full.decode_batch(k).cpu().numpy() for k in (1, 3)}
+    part = rec[:int(ge[2])]
+    with pkg.pcr_open(part, 0) as r:
+        assert r.k_avail == 3 and r.G == 10
+        for k in (1, 3):
+            assert np.array_equal(r.decode_batch(k).cpu().numpy(), want[k])
+        with pytest.raises(pkg.PcrError) as e:
+            r.decode_batch(4)
+        assert e.value.code == pkg.E_TRUNCATED
+        with pytest.raises(pkg.PcrError) as e:
+            r.decode_batch(11)
+        assert e.value.code == pkg.E_RANGE
+        small = torch.empty(10, dtype=torch.uint8, device="cuda")
+        with pytest.raises(pkg.PcrError) as e:
+            r.decode_batch(1, out=small)
+        assert e.value.code == pkg.E_RANGE
+
+
+def test_corrupt_entropy_data_flags_the_image_only(rgb_small):
+    """Damage inside one image's scan-2 data: that image is flagged and zero-filled or decoded
+    without any out-of-bounds access; every other image is untouched."""
+    rec, files = rgb_small
+    torch = _torch()
+    off, ln, _, _, _ = oracle.record_index(rec)
+    a = bytearray(rec)
+    victim = 5
+    p = int(off[1, victim]) + int(ln[1, victim]) - 40
+    for j in range(30):
+        a[p + j] = 0x55 if a[p + j] != 0x55 else 0xAA
+    bad = bytes(a)
+    with pkg.pcr_open(rec, 0) as r:
+        good = r.decode_batch(2).cpu().numpy()
+        lay = r.output_layout()
+    with pkg.pcr_open(bad, 0) as r:
+        status = torch.zeros(r.n, dtype=torch.int32, device="cuda")
+        out = r.decode_batch(2, status=status).cpu().numpy()
+        st = status.cpu().numpy()
+    for i in range(len(files)):
+        sl = slice(int(lay[i]), int(lay[i + 1]))
+        if i != victim:
+            assert st[i] == 0 and np.array_equal(out[sl], good[sl])
+    try:
+        oracle.decode_record_image(bad, victim, 2)
+        oracle_ok = True
+    except oracle.OracleError:
+        oracle_ok = False
+    if not oracle_ok:
+        assert st[victim] != 0 and not out[int(lay[victim]):int(lay[victim + 1])].any()
+
+
+def test_unsupported_and_malformed_images_are_refused_at_open():
+    good = pcrgen.make_jpeg(1, 1, 40, 24, 3, 6.0, 2, 2, 90)
+    arith = good.replace(b"\xff\xc2", b"\xff\xca", 1)
+    seq = pcrgen.encode_pixels(pcrgen.synth(1, 1, 40, 24, 3, 6.0), 2, 2, 90, "sequential")
+    for bad, code in ((arith, pkg.E_UNSUPPORTED), (seq, pkg.E_UNSUPPORTED)):
+        rec = pcrgen.write_record([good, bad])
+        with pytest.raises(pkg.PcrError) as e:
+            pkg.pcr_open(rec, 0)
+        assert e.value.code == code
+
+
+def test_repeatable_bit_for_bit(rgb_small):
+    rec, _ = rgb_small
+    with pkg.pcr_open(rec, 0) as r:
+        a = r.decode_batch(10).cpu().numpy()
+        b = r.decode_batch(4).cpu().numpy()
+        c = r.decode_batch(10).cpu().numpy()
+    assert np.array_equal(a, c) and not np.array_equal(a, b)

@@ -1,0 +1,70 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol include/pcr.h
+declares, and its host logic (header validation, argument checks) answers without a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import pcrgen
+import paper_1911_00472_amd as pkg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "pcr.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pcr_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = _declared()
+    assert "pcr_open" in names and "pcr_decode_batch" in names and len(names) >= 14
+    L = ctypes.CDLL(pkg.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+        assert n in pkg.SYMBOLS, n
+    assert sorted(pkg.SYMBOLS) == names
+
+
+def test_strerror_and_null_arguments():
+    L = pkg.lib()
+    assert L.pcr_strerror(0) == b"ok"
+    for code in range(-7, 0):
+        assert L.pcr_strerror(code) not in (b"ok", b"unknown error")
+    assert L.pcr_strerror(-99) == b"unknown error"
+    assert L.pcr_open(None, 0, 0, None) == pkg.E_ARG
+    assert L.pcr_num_images(None, None) == pkg.E_ARG
+    assert L.pcr_decode_batch(None, 1, None, 0, None, None) == pkg.E_ARG
+    L.pcr_close(None)
+
+
+def test_header_validation_precedes_any_device_call(rgb_small):
+    rec, _ = rgb_small
+    L = pkg.lib()
+    h = ctypes.c_void_p()
+
+    def try_open(b):
+        a = np.frombuffer(b, np.uint8)
+        return L.pcr_open(a.ctypes.data_as(ctypes.c_void_p), a.size, 0, ctypes.byref(h))
+
+    assert try_open(b"XCR1" + rec[4:]) == pkg.E_FORMAT
+    assert try_open(rec[:20]) == pkg.E_TRUNCATED
+    assert try_open(rec[:200]) == pkg.E_TRUNCATED                  # header itself cut short
+    bad_version = rec[:4] + (2).to_bytes(4, "little") + rec[8:]
+    assert try_open(bad_version) == pkg.E_UNSUPPORTED
+    zero_images = rec[:8] + (0).to_bytes(4, "little") + rec[12:]
+    assert try_open(zero_images) == pkg.E_FORMAT
+    hb = int.from_bytes(rec[16:24], "little")
+    assert try_open(rec[:hb]) == pkg.E_TRUNCATED                   # metadata only: no scan group available
+    assert not h.value
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    import paper_1911_00472_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", "/nonexistent/libpcr.so")
+    with pytest.raises(RuntimeError):
+        b.lib()
