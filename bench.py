@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the PCR decode path on one MI355X.
+
+A step is one pass of the whole path (index, marker parse, unstuff, progressive Huffman decode
+of scans 1..k, refinement, de-quantise, IDCT, chroma replication, YCbCr->RGB, store) over the
+whole workload: 4096 variable-size progressive JPEGs in 4 records of 1024, record bytes already
+resident in device memory.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--images N] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+SCAN_GROUPS = (1, 2, 5, 10)    # the scan groups the paper tabulates (Tables 1 and 2)
+HEADLINE_K = 10
+
+
+def scan_tables(files):
+    """Per file: cumulative compressed bytes per scan; per image: geometry for byte accounting."""
+    import pcrgen
+    return np.array([pcrgen.split_scans(f) for f in files], dtype=np.int64)
+
+
+def algorithmic_bytes(ends, shapes, k):
+    """Bytes the method itself must move for scan group k (per image, summed):
+    compressed prefix read once, each coefficient position covered by scans <= k written once and
+    read once (2 bytes each), pixels written once.  10-scan 4:2:0 script: DC for all components
+    at k=1, luma positions 1..5 at k=2, Cr 1..63 at k=3, Cb 1..63 at k=4, all luma from k=5."""
+    comp = ends[:, k - 1].sum()
+    out = 0
+    touched = 0          # int16 elements
+    for (W, H) in shapes:
+        mx, my = -(-W // 16), -(-H // 16)
+        yb, cb = 4 * mx * my, mx * my
+        ycov = (1 if k >= 1 else 0) + (5 if k >= 2 else 0) + (58 if k >= 5 else 0)
+        crcov = 1 + (63 if k >= 3 else 0)
+        cbcov = 1 + (63 if k >= 4 else 0)
+        touched += yb * ycov + cb * (crcov + cbcov)
+        out += W * H * 3
+    return dict(compressed=int(comp), touched=int(2 * touched), out=int(out),
+                path=int(comp + 2 * 2 * touched + out), entropy=int(comp + 2 * touched))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--images", type=int, default=4096, help="images of the workload to use (default: all 4096)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scan-group", type=int, default=HEADLINE_K)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the decode path shards by record with no exchange between GPUs, "
+              "and this build runs on a single MI355X; --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import pcrgen
+    import paper_1911_00472_amd as pkg
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    pkg.lib()
+
+    t0 = time.time()
+    records, files = pcrgen.make_workload("imagenet_like", limit=args.images)
+    Ws, Hs = pcrgen.workload_shapes("imagenet_like", limit=args.images)
+    shapes = list(zip((int(w) for w in Ws), (int(h) for h in Hs)))
+    ends = scan_tables(files)
+    n_img = len(files)
+    gen_s = time.time() - t0
+    print("[bench] generated %d images (mean %.1f kB) in %d records, %.1f s" % (n_img, ends[:, -1].mean() / 1000, len(records), gen_s),
+          file=sys.stderr, flush=True)
+
+    handles = [pkg.pcr_open(r, 0) for r in records]
+    outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in handles]
+    for h in handles:
+        h.enable_stage_timing(True)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(k):
+        for h, o in zip(handles, outs):
+            h.decode_batch(k, out=o, stream=stream)
+
+    # ---- parity spot check against the oracle before anything is timed ----
+    import oracle
+    step(HEADLINE_K)
+    torch.cuda.synchronize()
+    lay = handles[0].output_layout()
+    host = outs[0].cpu().numpy()
+    for i in (0, 1, min(7, handles[0].n - 1)):
+        _, p0, info = oracle.decode_record_image(records[0], i, HEADLINE_K, want_coef=False)
+        got = host[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
+        assert np.abs(got - p0).max() <= 1, "parity check failed for image %d" % i
+
+    def timed(k, steps, warmup):
+        for _ in range(warmup):
+            step(k)
+        torch.cuda.synchronize()
+        stage = np.zeros(pkg.NUM_STAGES)
+        t = time.perf_counter()
+        for _ in range(steps):
+            step(k)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        # stage times of the last step (HIP events recorded by the library on the decode stream)
+        for h in handles:
+            ms = h.last_stage_ms()
+            stage += np.array([ms[s] for s in pkg.STAGE_NAMES])
+        return dt / steps, stage
+
+    per_k = {}
+    for k in SCAN_GROUPS:
+        if k == args.scan_group:
+            continue
+        sec, stage = timed(k, max(2, args.steps // 2), 1)
+        per_k[k] = (sec, stage)
+    sec, stage = timed(args.scan_group, args.steps, args.warmup)
+    per_k[args.scan_group] = (sec, stage)
+
+    report = {}
+    for k in sorted(per_k):
+        sec, stage = per_k[k]
+        ab = algorithmic_bytes(ends, shapes, k)
+        report[str(k)] = {
+            "images_per_s": n_img / sec,
+            "ms_per_step": sec * 1e3,
+            "output_GBps": ab["out"] / sec / 1e9,
+            "algorithmic_GBps": ab["path"] / sec / 1e9,
+            "hbm_roofline_frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS,
+            "must_move_floor_GBps": (ab["compressed"] + ab["out"]) / sec / 1e9,
+            "stage_ms": dict(zip(pkg.STAGE_NAMES, (float(x) for x in stage))),
+        }
+    sec, stage = per_k[args.scan_group]
+    ab = algorithmic_bytes(ends, shapes, args.scan_group)
+    ent_ms = float(stage[pkg.STAGE_NAMES.index("entropy")])
+    roofline = {
+        "kernel": "k_entropy (all dependency levels of one step)",
+        "bound": "hbm", "achieved": ab["entropy"] / (ent_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": ab["entropy"] / (ent_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+        "algorithmic_bytes_per_step": ab["entropy"], "ms_per_step": ent_ms,
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        threads = min(16, os.cpu_count() or 1)
+        sample = min(192, handles[0].n)
+        t = time.perf_counter()
+        oracle.decode_record(records[0], args.scan_group, images=range(sample), threads=threads, want_coef=False)
+        dt = time.perf_counter() - t
+        cpu = {"value": sample / dt, "unit": "images/s", "cores": threads, "kind": "oracle",
+               "sample": "first %d images of record 0 at scan group %d, %d threads, %.1f s" % (sample, args.scan_group, threads, dt)}
+
+    line = {
+        "metric": "decoded_images_per_sec_at_scan_group_%d" % args.scan_group,
+        "value": n_img / sec, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int16 coefficients, fp32 IDCT/colour, u8 pixels", "data": "synthetic",
+        "config": {"workload": "imagenet_like: %d RGB images, width/height uniform in [300,500], 4:2:0, quality 90, "
+                               "10-scan progressive, mean %.0f kB, %d records of <=1024" % (n_img, ends[:, -1].mean() / 1000, len(records)),
+                   "scan_group": args.scan_group, "images": n_img, "records": len(records)},
+        "output_GBps": ab["out"] / sec / 1e9,
+        "path_roofline": {"bound": "hbm", "achieved": ab["path"] / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "per_scan_group": report,
+    }
+    for h in handles:
+        h.close()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
