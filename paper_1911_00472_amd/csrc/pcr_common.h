@@ -61,6 +61,20 @@ PCR_HD uint32_t ld_le32(const uint8_t* p) { return (uint32_t)p[0] | ((uint32_t)p
 PCR_HD uint64_t ld_le64(const uint8_t* p) { return (uint64_t)ld_le32(p) | ((uint64_t)ld_le32(p + 4) << 32); }
 PCR_HD uint32_t ld_be16(const uint8_t* p) { return ((uint32_t)p[0] << 8) | p[1]; }
 
+// Tell the compiler a value is the same in every lane of the wavefront (it then lives in a
+// scalar register).  Only used where that is true by construction.
+PCR_HD uint32_t uni(uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
+#else
+    return v;
+#endif
+}
+PCR_HD int uni(int v) { return (int)uni((uint32_t)v); }
+PCR_HD uint64_t uni(uint64_t v) { return ((uint64_t)uni((uint32_t)(v >> 32)) << 32) | uni((uint32_t)v); }
+// (pointers: apply uni() to the offset and add it to a kernel-argument base pointer; a pointer
+// rebuilt from integers loses its address space and loads through it count as divergent)
+
 PCR_HD uint32_t bitrev32(uint32_t v) {
 #if defined(__has_builtin)
 #if __has_builtin(__builtin_bitreverse32)

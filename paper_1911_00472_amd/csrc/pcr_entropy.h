@@ -5,263 +5,447 @@
 // Compression"; Section 3: scan k of an image is usable once scans 1..k have been read).
 //
 // Input is the *unstuffed* entropy-coded data of the unit (FF 00 -> FF, restart markers
-// removed); a unit never reads a bit past its end: doing so is a data error, not a guess.
+// removed); consuming a bit past the unit's end is a data error, never a guess.
+//
+// Shape of the decoders: every lane of a wavefront decodes a different stream, so the loops
+// are FLAT -- one Huffman symbol per iteration, with the end-of-block bookkeeping predicated
+// inside the same iteration -- which keeps lanes that are in different blocks converged.
+// All per-scan parameters live in registers (LaneScan); tables live in LDS, one per lane.
 //
 // AC refinement is decoded against a 64-bit "already non-zero" mask per block (zig-zag bit
-// order) instead of against the coefficients themselves: the serial decoder only finds
-// where new coefficients go, which signs they get, and the string of correction bits; the
-// arithmetic on the coefficients happens later in a data-parallel pass (refine_apply).
+// order) instead of against the coefficients: the serial decoder only finds where new
+// coefficients go, their signs, and the string of correction bits (exactly one per already
+// non-zero coefficient of the band, in zig-zag order); the arithmetic on the coefficients is
+// data-parallel (refine_apply).  DC refinement needs no serial decoder at all: it is one
+// bit per block at a position known in advance (dc_refine_bit).
 #pragma once
 #include "pcr_common.h"
 
 namespace pcr {
 
 // ---------------------------------------------------------------------------------------
-// Huffman table: 8-bit look-ahead table plus canonical limits for the longer codes.
+// Huffman tables.  Codes of <= 8 bits resolve through `lut`, indexed by the next 8 bits.  In a
+// canonical code the longer code words are the numerically largest ones, so all of them lie in
+// [limit8, 65536) when left-aligned in 16 bits; `lut2`, indexed by the distance from limit8
+// scaled to 128 entries, resolves every long code that owns at least one whole entry, and the
+// canonical limits resolve the rest.  An entry is (length << 8) | symbol; 0 means "not here".
 // ---------------------------------------------------------------------------------------
-struct HuffTab {
-    uint16_t lut[256];          // (length << 8) | symbol for codes of <= 8 bits, 0 otherwise
-    uint32_t limit[17];         // limit[L]: first 16-bit-left-aligned code value NOT of length <= L
-    int32_t base[17];           // symbol index = base[L] + (code16 >> (16 - L))
+struct AcTab {
+    uint16_t lut[256];
+    uint16_t lut2[128];
+    uint32_t limit[9];          // limit[L-8]: first 16-bit-left-aligned code value NOT of length <= L (L = 8..16)
+    uint16_t valptr[8];         // valptr[L-9]: index in huffval of the first code of length L
+    uint32_t sh2;               // lut2 index = (code16 - limit[0]) >> sh2
     uint8_t huffval[256];
+    uint32_t pad;               // odd number of dwords: per-lane copies spread over the LDS banks
 };
+static_assert(sizeof(AcTab) == 1084, "AcTab layout");
+
+struct DcTab {                  // DC symbols are categories 0..15
+    uint8_t lut[256];           // (length << 4) | symbol for codes of <= 8 bits, 0xFF otherwise
+    uint32_t limit[9];
+    uint16_t valptr[8];
+    uint8_t huffval[16];
+};
+static_assert(sizeof(DcTab) == 324, "DcTab layout");
 
 // Build from a DHT payload: 16 counts followed by the symbols in code order.  Codes of each
 // length are consecutive integers in symbol order; moving to the next length doubles the code.
-PCR_HD void hufftab_build(HuffTab* t, const uint8_t* bits_vals) {
-    for (int i = 0; i < 256; i++) t->lut[i] = 0;
+PCR_HD void dctab_build(DcTab* t, const uint8_t* bits_vals) {
+    for (int i = 0; i < 256; i++) t->lut[i] = 0xFF;
     uint32_t code = 0; int k = 0;
     for (int L = 1; L <= 16; L++) {
         int cnt = bits_vals[L - 1];
-        t->base[L] = k - (int)code;
+        if (L >= 9) t->valptr[L - 9] = (uint16_t)k;
+        for (int j = 0; j < cnt; j++) {
+            if (k < 16) {
+                uint8_t sym = bits_vals[16 + k];
+                t->huffval[k] = sym;
+                if (L <= 8) {
+                    uint32_t first = code << (8 - L), span = 1u << (8 - L);
+                    for (uint32_t e = 0; e < span && first + e < 256; e++) t->lut[first + e] = (uint8_t)((L << 4) | (sym & 15));
+                }
+            }
+            code++; k++;
+        }
+        if (L >= 8) { uint64_t lim = (uint64_t)code << (16 - L); t->limit[L - 8] = lim > 65536 ? 65536u : (uint32_t)lim; }
+        code <<= 1;
+    }
+}
+
+PCR_HD void actab_build(AcTab* t, const uint8_t* bits_vals) {
+    for (int i = 0; i < 256; i++) t->lut[i] = 0;
+    for (int i = 0; i < 128; i++) t->lut2[i] = 0;
+    // pass 1: short codes, limits
+    uint32_t code = 0; int k = 0;
+    for (int L = 1; L <= 16; L++) {
+        int cnt = bits_vals[L - 1];
+        if (L >= 9) t->valptr[L - 9] = (uint16_t)k;
         for (int j = 0; j < cnt; j++) {
             if (k < 256) {
                 uint8_t sym = bits_vals[16 + k];
                 t->huffval[k] = sym;
                 if (L <= 8) {
-                    uint32_t first = code << (8 - L);
-                    uint32_t span = 1u << (8 - L);
+                    uint32_t first = code << (8 - L), span = 1u << (8 - L);
                     for (uint32_t e = 0; e < span && first + e < 256; e++) t->lut[first + e] = (uint16_t)((L << 8) | sym);
                 }
             }
             code++; k++;
         }
-        uint64_t lim = (uint64_t)code << (16 - L);
-        t->limit[L] = lim > 65536 ? 65536u : (uint32_t)lim;
+        if (L >= 8) { uint64_t lim = (uint64_t)code << (16 - L); t->limit[L - 8] = lim > 65536 ? 65536u : (uint32_t)lim; }
+        code <<= 1;
+    }
+    // pass 2: long codes into lut2
+    const uint32_t lim8 = t->limit[0];
+    const uint32_t D = 65536u - lim8;
+    uint32_t sh2 = 0;
+    while (D && ((D - 1) >> sh2) >= 128) sh2++;
+    t->sh2 = sh2;
+    code = 0; k = 0;
+    for (int L = 1; L <= 16; L++) {
+        int cnt = bits_vals[L - 1];
+        for (int j = 0; j < cnt; j++) {
+            if (L >= 9 && k < 256 && (uint32_t)(16 - L) >= sh2) {
+                uint64_t c = (uint64_t)code << (16 - L);
+                if (c >= lim8 && c < 65536) {
+                    uint32_t first = ((uint32_t)c - lim8) >> sh2, span = 1u << (16 - L - sh2);
+                    for (uint32_t e = 0; e < span && first + e < 128; e++) t->lut2[first + e] = (uint16_t)((L << 8) | bits_vals[16 + k]);
+                }
+            }
+            code++; k++;
+        }
         code <<= 1;
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// Bit reader over unstuffed bytes [p, p + nbytes).  The accumulator holds `cnt` valid bits
-// left-aligned in 64 bits.  Bytes past the end read as 0xFF (the padding an encoder
-// writes); `overrun()` tells whether more bits were consumed than the unit holds.
+// Bit reader over the unstuffed data of one unit.  The data is stored as big-endian 32-bit
+// words (the unstuff step swaps the bytes of every aligned 4-byte group), so a word is usable
+// as loaded.  `acc` holds `cnt` valid bits left-aligned in 64 bits; words come from a 4-word
+// queue q*, itself refilled from a second group nx whose 16-byte load was issued a whole group
+// earlier: the loop never waits on the load it has just issued.  `left` counts the unit's unread
+// bits and goes negative when a decoder consumes more than the unit holds.  The buffer must
+// stay readable for 48 bytes past any position a decoder can reach before it checks `left`.
+// Everything here is wave-uniform when the unit is: it then lives in scalar registers.
 // ---------------------------------------------------------------------------------------
-struct BitReader {
-    const uint8_t* p;
-    uint32_t nbytes, pos;       // pos: next byte to load
-    uint64_t acc;
-    int32_t cnt;
-    int64_t consumed;           // bits consumed so far
+struct __attribute__((packed, aligned(4))) Word4 { uint32_t a, b, c, d; };
 
-    PCR_HD void init(const uint8_t* data, uint32_t n) { p = data; nbytes = n; pos = 0; acc = 0; cnt = 0; consumed = 0; refill(); }
-    PCR_HD void refill() {
-        while (cnt <= 32) {
-            uint32_t w = 0;
-            for (int j = 0; j < 4; j++) { uint32_t b = (pos + j < nbytes) ? p[pos + j] : 0xFFu; w = (w << 8) | b; }
-            pos += 4;
-            acc |= (uint64_t)w << (32 - cnt);
-            cnt += 32;
-        }
+struct BitReader {
+    const Word4* p;             // next group to load
+    uint64_t acc;
+    uint32_t q0, q1, q2, q3;    // queued words
+    Word4 nx;                   // prefetched group
+    int32_t cnt, nq, left;
+
+    // words: 4-byte aligned base of the segment; byte_off: where the unit starts inside it
+    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes) {
+        const uint32_t mis = byte_off & 3;
+        p = (const Word4*)(words + (byte_off >> 2));
+        Word4 g = p[0]; nx = p[1]; p += 2;
+        acc = ((uint64_t)g.a << 32) | g.b; cnt = 64;
+        q0 = g.c; q1 = g.d; q2 = 0; q3 = 0; nq = 2;
+        left = (int32_t)(nbytes * 8 + mis * 8);
+        advance((int)(mis * 8));
     }
-    PCR_HD uint32_t peek(int n) const { return (uint32_t)(acc >> (64 - n)); }        // 1 <= n <= 32
-    PCR_HD void skip(int n) { acc <<= n; cnt -= n; consumed += n; }
-    PCR_HD uint32_t get(int n) {                                                      // 0 <= n <= 32, cnt >= n
-        if (n == 0) return 0;
-        uint32_t v = peek(n); skip(n); return v;
+    PCR_HD uint32_t window() const { return (uint32_t)(acc >> 32); }     // the next 32 unread bits
+    PCR_HD void pop_word() {                                 // cnt <= 32: append one word
+        acc |= (uint64_t)q0 << (32 - cnt); cnt += 32;
+        q0 = q1; q1 = q2; q2 = q3;
+        if (--nq == 0) { q0 = nx.a; q1 = nx.b; q2 = nx.c; q3 = nx.d; nq = 4; nx = *p++; }
     }
-    PCR_HD bool overrun() const { return consumed > (int64_t)nbytes * 8; }
+    PCR_HD void advance(int n) {                             // 0 <= n <= 32; afterwards cnt >= 33
+        acc <<= n; cnt -= n; left -= n;
+        if (cnt <= 32) pop_word();
+    }
+    PCR_HD void advance_long(int n) {                        // any n >= 0
+        left -= n;
+        while (n > 32) { acc <<= 32; cnt -= 32; if (cnt <= 32) pop_word(); n -= 32; }
+        acc <<= n; cnt -= n;
+        if (cnt <= 32) pop_word();
+    }
+    PCR_HD bool overrun() const { return left < 0; }
 };
 
-// Decode one Huffman symbol; needs >= 16 valid bits.  Returns -1 for a code that is not in the table.
-PCR_HD int huff_decode(BitReader* br, const HuffTab* t) {
-    uint32_t e = t->lut[br->peek(8)];
-    if (e) { br->skip((int)(e >> 8)); return (int)(e & 255); }
-    uint32_t c16 = br->peek(16);
+// bits [len, len+n) of a 32-bit window (n may be 0)
+PCR_HD uint32_t field(uint32_t win, int len, int n) { return n ? (win << len) >> (32 - n) : 0; }
+
+// Resolve a code of more than 8 bits.  Returns (length << 8) | symbol, or 0 if it is no code.
+PCR_HD uint32_t ac_long_code(const AcTab* t, uint32_t win) {
+    const uint32_t c16 = win >> 16;
+    const uint32_t lim8 = t->limit[0];
+    if (c16 < lim8) return 0;
+    const uint32_t i2 = (c16 - lim8) >> t->sh2;
+    uint32_t e = i2 < 128 ? t->lut2[i2] : 0;
+    if (e) return e;
     for (int L = 9; L <= 16; L++) {
-        if (c16 < t->limit[L]) {
-            int idx = t->base[L] + (int)(c16 >> (16 - L));
-            br->skip(L);
-            return (idx >= 0 && idx < 256) ? t->huffval[idx] : -1;
+        if (c16 < t->limit[L - 8]) {
+            uint32_t idx = t->valptr[L - 9] + ((c16 - t->limit[L - 9]) >> (16 - L));
+            return idx < 256 ? ((uint32_t)L << 8) | t->huffval[idx] : 0;
         }
     }
-    return -1;
+    return 0;
+}
+PCR_HD uint32_t ac_code(const AcTab* t, uint32_t win) {
+    uint32_t e = t->lut[win >> 24];
+    return e ? e : ac_long_code(t, win);
+}
+// DC: returns (length << 4) | category, or 0 if it is no code (a valid entry is never 0: length >= 1)
+PCR_HD uint32_t dc_code(const DcTab* t, uint32_t win) {
+    uint32_t e = t->lut[win >> 24];
+    if (e != 0xFF) return e;
+    const uint32_t c16 = win >> 16;
+    if (c16 < t->limit[0]) return 0;
+    for (int L = 9; L <= 16; L++) {
+        if (c16 < t->limit[L - 8]) {
+            uint32_t idx = t->valptr[L - 9] + ((c16 - t->limit[L - 9]) >> (16 - L));
+            return idx < 16 ? ((uint32_t)L << 4) | t->huffval[idx] : 0;
+        }
+    }
+    return 0;
 }
 
 PCR_HD int extend(uint32_t v, int s) { return (s && v < (1u << (s - 1))) ? (int)v - (1 << s) + 1 : (int)v; }
 
-// Where a unit's blocks live.  Non-interleaved scans visit only the blocks that cover the
-// component's own samples (cw x ch), interleaved scans the MCU-padded grid.
-struct UnitGeom {
+// Per-lane parameters of the unit being decoded (all in registers).
+struct LaneScan {
     uint32_t mcu0, mcu1;        // MCU range [mcu0, mcu1) of the scan handled by this unit
-    uint32_t mcu_w;             // MCUs per row of this scan
+    uint32_t mcu_w;             // MCUs per row of the scan
+    int Ss, Se, Al;
+    // interleaved DC scans: per scan component j
+    int ns;
+    uint32_t hs[kMaxComp], vs[kMaxComp], bw[kMaxComp];
 };
 
 // ---------------------------------------------------------------------------------------
-// DC first scan (possibly interleaved).  coef[c]: plane of component c, [bh][bw][64].
-// Returns kOk or kEFormat.
+// DC first scan.  Non-interleaved scans visit the blocks covering the component's own
+// samples, interleaved scans the MCU-padded grid, component by component inside each MCU.
+// coef0/1/2: planes of the scan's components ([bh][bw][64], DC at element 0 of each block).
 // ---------------------------------------------------------------------------------------
-PCR_HD int decode_dc_first(BitReader* br, const ImgDesc* img, const ScanDesc* sd, const UnitGeom* ug,
-                           const HuffTab* const* tabs, int16_t* const* coef) {
+PCR_HD int decode_dc_first(BitReader* br, const LaneScan& ls, const DcTab* tab0, const DcTab* tab1, const DcTab* tab2,
+                           int16_t* coef0, int16_t* coef1, int16_t* coef2) {
     int pred[kMaxComp] = {0, 0, 0};
-    for (uint32_t m = ug->mcu0; m < ug->mcu1; m++) {
-        uint32_t my = m / ug->mcu_w, mx = m % ug->mcu_w;
-        for (int j = 0; j < sd->ns; j++) {
-            int c = sd->comp[j];
-            int nx = sd->ns > 1 ? img->hs[c] : 1, ny = sd->ns > 1 ? img->vs[c] : 1;
-            for (int by = 0; by < ny; by++) for (int bx = 0; bx < nx; bx++) {
-                uint32_t row = sd->ns > 1 ? my * img->vs[c] + by : my, col = sd->ns > 1 ? mx * img->hs[c] + bx : mx;
-                br->refill();
-                int t = huff_decode(br, tabs[j]);
-                if (t < 0 || t > 15) return kEFormat;
-                int diff = extend(br->get(t), t);
-                pred[j] += diff;
-                coef[j][((size_t)row * img->bw[c] + col) * 64] = (int16_t)(pred[j] * (1 << sd->Al));
+    const DcTab* tabs[kMaxComp] = {tab0, tab1, tab2};
+    int16_t* coefs[kMaxComp] = {coef0, coef1, coef2};
+    uint32_t my = ls.mcu0 / ls.mcu_w, mx = ls.mcu0 % ls.mcu_w;
+    for (uint32_t m = ls.mcu0; m < ls.mcu1; m++) {
+#pragma unroll
+        for (int j = 0; j < kMaxComp; j++) {                 // unrolled: every index below is a constant
+            if (j < ls.ns) {
+                const uint32_t hs = ls.ns > 1 ? ls.hs[j] : 1, vs = ls.ns > 1 ? ls.vs[j] : 1, bw = ls.bw[j];
+                for (uint32_t by = 0; by < vs; by++) for (uint32_t bx = 0; bx < hs; bx++) {
+                    const uint32_t win = br->window();
+                    const uint32_t e = dc_code(tabs[j], win);
+                    if (!e) return kEFormat;
+                    const int len = (int)(e >> 4), t = (int)(e & 15);
+                    pred[j] += extend(field(win, len, t), t);
+                    br->advance(len + t);
+                    coefs[j][((size_t)(my * vs + by) * bw + mx * hs + bx) * 64] = (int16_t)(pred[j] * (1 << ls.Al));
+                }
             }
         }
         if (br->overrun()) return kEFormat;
+        if (++mx == ls.mcu_w) { mx = 0; my++; }
     }
     return kOk;
 }
 
-// DC refinement: one bit per block, OR-ed in at bit Al.
-PCR_HD int decode_dc_refine(BitReader* br, const ImgDesc* img, const ScanDesc* sd, const UnitGeom* ug, int16_t* const* coef) {
-    for (uint32_t m = ug->mcu0; m < ug->mcu1; m++) {
-        uint32_t my = m / ug->mcu_w, mx = m % ug->mcu_w;
-        for (int j = 0; j < sd->ns; j++) {
-            int c = sd->comp[j];
-            int nx = sd->ns > 1 ? img->hs[c] : 1, ny = sd->ns > 1 ? img->vs[c] : 1;
-            for (int by = 0; by < ny; by++) for (int bx = 0; bx < nx; bx++) {
-                uint32_t row = sd->ns > 1 ? my * img->vs[c] + by : my, col = sd->ns > 1 ? mx * img->hs[c] + bx : mx;
-                br->refill();
-                if (br->get(1)) coef[j][((size_t)row * img->bw[c] + col) * 64] |= (int16_t)(1 << sd->Al);
-            }
+// ---------------------------------------------------------------------------------------
+// AC first scan of one component, band Ss..Se, flat loop.  Writes coefficient values in
+// ZIG-ZAG order inside each 64-element block (element k of a block is zig-zag position k) and,
+// per block, the mask of positions it made non-zero.  Blocks skipped by an end-of-band run are
+// not touched: coefficients and nzout must be zero-filled beforehand.
+// ---------------------------------------------------------------------------------------
+PCR_HD int decode_ac_first(BitReader* br, const LaneScan& ls, const AcTab* tab, int16_t* coef, uint64_t* nzout) {
+    const int Ss = ls.Ss, Se = ls.Se, Al = ls.Al;
+    const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
+    uint32_t m = ls.mcu0;
+    uint32_t row = m / mcu_w, col = m % mcu_w;
+    size_t blk = (size_t)row * bw + col;
+    uint64_t mask = 0;
+    int k = Ss;
+    while (m < ls.mcu1) {
+        const uint32_t win = br->window();
+        const uint32_t e = ac_code(tab, win);
+        if (!e) return kEFormat;
+        const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
+        const bool eob = (s == 0) & (r != 15);
+        const int nx = s ? s : (eob ? r : 0);                // extra bits after the code
+        const uint32_t extra = field(win, len, nx);
+        br->advance(len + nx);
+        uint32_t eobrun = 0;
+        if (s) {
+            k += r;
+            if (k > Se) return kEFormat;
+            coef[blk * 64 + k] = (int16_t)(extend(extra, s) * (1 << Al));
+            mask |= 1ull << k;
+            k++;
+        } else if (eob) { eobrun = (1u << r) - 1 + extra; k = 64; }
+        else k += 16;
+        if (k > Se) {                                        // block finished
+            nzout[blk] = mask;
+            if (br->overrun()) return kEFormat;
+            uint32_t adv = 1 + eobrun;                       // this block + the blocks the run covers
+            if (adv > ls.mcu1 - m) adv = ls.mcu1 - m;
+            m += adv; col += adv;
+            if (col >= mcu_w) { row += col / mcu_w; col %= mcu_w; }
+            blk = (size_t)row * bw + col;
+            mask = 0; k = Ss;
         }
-        if (br->overrun()) return kEFormat;
     }
     return kOk;
 }
 
 // ---------------------------------------------------------------------------------------
-// AC first scan of one component, band Ss..Se.  Writes coefficient values (natural order,
-// through zz[]) and, per block, the mask of zig-zag positions it made non-zero.
-// ---------------------------------------------------------------------------------------
-PCR_HD int decode_ac_first(BitReader* br, const ImgDesc* img, const ScanDesc* sd, const UnitGeom* ug, const HuffTab* tab,
-                           const uint8_t* zz, int16_t* coef, uint64_t* nzout) {
-    int c = sd->comp[0];
-    uint32_t eobrun = 0;
-    const int Ss = sd->Ss, Se = sd->Se, Al = sd->Al;
-    for (uint32_t m = ug->mcu0; m < ug->mcu1; m++) {
-        size_t blk = (size_t)(m / ug->mcu_w) * img->bw[c] + (m % ug->mcu_w);
-        if (eobrun > 0) { eobrun--; continue; }            // nzout stays 0 (planes are zero-filled)
-        uint64_t mask = 0;
-        int k = Ss;
-        while (k <= Se) {
-            br->refill();
-            int rs = huff_decode(br, tab);
-            if (rs < 0) return kEFormat;
-            int r = rs >> 4, s = rs & 15;
-            if (s) {
-                k += r;
-                if (k > Se) return kEFormat;
-                int v = extend(br->get(s), s);
-                coef[blk * 64 + zz[k]] = (int16_t)(v * (1 << Al));
-                mask |= 1ull << k;
-                k++;
-            } else if (r == 15) k += 16;
-            else { eobrun = (1u << r) - 1 + br->get(r); break; }
-        }
-        nzout[blk] = mask;
-        if (br->overrun()) return kEFormat;
-    }
-    return kOk;
-}
-
-// ---------------------------------------------------------------------------------------
-// AC refinement scan.  hist planes: masks written by the earlier AC scans of the component.
-// Per block this writes
+// AC refinement scan, flat loop.  hist0..: masks written by the earlier AC scans of the
+// component (nhist of them).  Per block this writes
 //   nzout  positions that become non-zero in this scan,
 //   sign   for those positions, 1 = positive,
-//   cbits  the correction bits in reading order (first bit read = bit 0); there is exactly one
-//          per already-non-zero coefficient of the band, in zig-zag order.
+//   cbits  the correction bits in reading order (first bit read = bit 0).
 // ---------------------------------------------------------------------------------------
 PCR_HD uint64_t band_mask(int Ss, int Se) { return ((Se >= 63) ? ~0ull : ((1ull << (Se + 1)) - 1)) & ~((1ull << Ss) - 1); }
 
 PCR_HD uint64_t take_correction_bits(BitReader* br, int n) {    // n <= 63; first bit read -> bit 0
     uint64_t out = 0; int done = 0;
     while (n > 0) {
-        int t = n > 32 ? 32 : n;
-        br->refill();
-        uint32_t v = br->get(t);                                // first-read bit is the MSB of the t bits
-        uint32_t rv = bitrev32(v) >> (32 - t);
-        out |= (uint64_t)rv << done;
+        const int t = n > 31 ? 31 : n;
+        const uint32_t v = br->window() >> (32 - t);            // first-read bit is the MSB of the t bits
+        br->advance(t);
+        out |= (uint64_t)(bitrev32(v) >> (32 - t)) << done;
         done += t; n -= t;
     }
     return out;
 }
 
-PCR_HD int decode_ac_refine(BitReader* br, const ImgDesc* img, const ScanDesc* sd, const UnitGeom* ug, const HuffTab* tab,
-                            const uint64_t* const* hist, int nhist, uint64_t* nzout, uint64_t* sign, uint64_t* cbits) {
-    int c = sd->comp[0];
+struct HistPlanes { const uint64_t* p[kMaxHist]; int n; };
+
+PCR_HD uint64_t hist_at(const HistPlanes& hp, size_t blk) {
+    uint64_t h = 0;
+    if (hp.n > 0) h |= hp.p[0][blk];
+    if (hp.n > 1) h |= hp.p[1][blk];
+    if (hp.n > 2) h |= hp.p[2][blk];
+    if (hp.n > 3) h |= hp.p[3][blk];
+    if (hp.n > 4) h |= hp.p[4][blk];
+    if (hp.n > 5) h |= hp.p[5][blk];
+    return h;
+}
+
+// Phase 1 (serial, one lane per unit): walk the scan only as far as needed to know where
+// every block starts.  For each symbol that means: the code (length, run, size), the position
+// the run ends on -- found on the zero-history mask -- and the NUMBER of correction bits in
+// between -- a population count on the non-zero-history mask; the sign and correction bits are
+// stepped over, not read.  Per block it writes
+//   nzout  positions that become non-zero in this scan (later scans need them as history),
+//   start  bit offset of the block inside the unit (low 32 bits) and the end-of-band run still
+//          pending when the block starts (high 32 bits).
+// Masks are kept as 32-bit halves: the lanes' ALUs are 32 bits wide.
+PCR_HD int skim_ac_refine(BitReader* br, const LaneScan& ls, const AcTab* tab, const HistPlanes& hp,
+                          uint64_t* nzout, uint64_t* start) {
+    const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
+    const uint64_t band = band_mask(ls.Ss, ls.Se);
+    const uint32_t blo = (uint32_t)band, bhi = (uint32_t)(band >> 32);
+    uint32_t m = ls.mcu0;
+    if (m >= ls.mcu1) return kOk;
+    uint32_t row = m / mcu_w, col = m % mcu_w;
+    size_t blk = (size_t)row * bw + col;
+    const int32_t left0 = br->left;
+    uint64_t h = hist_at(hp, blk);
+    uint32_t hlo = (uint32_t)h & blo, hhi = (uint32_t)(h >> 32) & bhi;
+    uint32_t zlo = ~hlo & blo, zhi = ~hhi & bhi;
+    uint32_t nlo = 0, nhi = 0;
     uint32_t eobrun = 0;
-    const int Ss = sd->Ss, Se = sd->Se;
-    const uint64_t band = band_mask(Ss, Se);
-    for (uint32_t m = ug->mcu0; m < ug->mcu1; m++) {
-        size_t blk = (size_t)(m / ug->mcu_w) * img->bw[c] + (m % ug->mcu_w);
-        uint64_t h = 0;
-        for (int q = 0; q < nhist; q++) h |= hist[q][blk];
-        h &= band;
-        uint64_t newm = 0, sgn = 0, cb = 0; int ncb = 0;
-        int k = Ss;
+    start[blk] = 0;
+    while (true) {
+        int tot; bool done;
         if (eobrun == 0) {
-            while (k <= Se) {
-                br->refill();
-                int rs = huff_decode(br, tab);
-                if (rs < 0) return kEFormat;
-                int r = rs >> 4, s = rs & 15;
-                uint32_t sbit = 0;
-                if (s == 1) sbit = br->get(1);
-                else if (s != 0) return kEFormat;
-                else if (r < 15) { eobrun = (1u << r) + br->get(r); break; }
-                // pass r still-zero positions, then stop on the next still-zero one
-                uint64_t from_k = band & ~((1ull << k) - 1);
-                uint64_t z = ~h & from_k;
-                for (int q = 0; q < r && z; q++) z &= z - 1;
-                int pos = z ? __builtin_ctzll(z) : Se + 1;
-                if (pos > Se && s == 1) return kEFormat;       // no place left for the new coefficient
-                uint64_t upto = (pos >= 64) ? ~0ull : ((1ull << pos) - 1);
-                uint64_t cm = h & from_k & upto;
-                int n = __builtin_popcountll(cm);
-                if (n) { cb |= take_correction_bits(br, n) << ncb; ncb += n; }
-                if (s == 1) { newm |= 1ull << pos; sgn |= (uint64_t)sbit << pos; }
-                k = pos + 1;
+            const uint32_t win = br->window();
+            const uint32_t e = ac_code(tab, win);
+            if (!e) return kEFormat;
+            const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
+            if (s > 1) return kEFormat;
+            if ((s == 0) & (r != 15)) {                      // end of band (run): the rest of the block is corrections
+                eobrun = (1u << r) + field(win, len, r) - 1;
+                tot = len + r + __builtin_popcount(hlo) + __builtin_popcount(hhi);
+                done = true;
+            } else {
+                for (int q = 0; q < r; q++) { if (zlo) zlo &= zlo - 1; else zhi &= zhi - 1; }   // pass r still-zero positions
+                uint32_t mlo, mhi;                            // positions below the one the run stops on
+                if (zlo) { const int pos = __builtin_ctz(zlo); mlo = (1u << pos) - 1; mhi = 0; zlo &= zlo - 1; if (s) nlo |= 1u << pos; }
+                else if (zhi) { const int pos = __builtin_ctz(zhi); mlo = ~0u; mhi = (1u << pos) - 1; zhi &= zhi - 1; if (s) nhi |= 1u << pos; }
+                else { if (s) return kEFormat; mlo = ~0u; mhi = ~0u; }   // ran off the band: only legal for a zero run
+                tot = len + s + __builtin_popcount(hlo & mlo) + __builtin_popcount(hhi & mhi);
+                hlo &= ~mlo; hhi &= ~mhi;
+                done = (zlo | zhi | hlo | hhi) == 0;
             }
-        }
-        if (eobrun > 0) {
-            uint64_t cm = (k <= Se) ? (h & band & ~((1ull << k) - 1)) : 0;
-            int n = __builtin_popcountll(cm);
-            if (n) { cb |= take_correction_bits(br, n) << ncb; ncb += n; }
+        } else {
+            tot = __builtin_popcount(hlo) + __builtin_popcount(hhi);
             eobrun--;
+            done = true;
         }
-        nzout[blk] = newm; sign[blk] = sgn; cbits[blk] = cb;
-        if (br->overrun()) return kEFormat;
+        br->advance_long(tot);
+        if (done) {
+            nzout[blk] = ((uint64_t)nhi << 32) | nlo;
+            if (br->overrun()) return kEFormat;
+            if (++m >= ls.mcu1) break;
+            if (++col == mcu_w) { col = 0; row++; }
+            blk = (size_t)row * bw + col;
+            start[blk] = ((uint64_t)eobrun << 32) | (uint32_t)(left0 - br->left);
+            h = hist_at(hp, blk);
+            hlo = (uint32_t)h & blo; hhi = (uint32_t)(h >> 32) & bhi;
+            zlo = ~hlo & blo; zhi = ~hhi & bhi;
+            nlo = 0; nhi = 0;
+        }
     }
     return kOk;
 }
 
+// Phase 2 (data-parallel, one lane per block): decode one block completely from its start.
+//   words, byte_off  the unit's unstuffed data;  st  the block's entry of `start`;  h  history mask
+// Returns the sign mask (1 = positive) of the positions that become non-zero and the correction
+// bits in reading order (first bit read = bit 0): exactly one per history-non-zero position of
+// the band, in zig-zag order.
+PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, const AcTab* tab, uint64_t h, int Ss, int Se,
+                         uint64_t* sign_out, uint64_t* cbits_out) {
+    const uint64_t band = band_mask(Ss, Se);
+    h &= band;
+    const uint32_t bitpos = (uint32_t)st;
+    uint32_t eobrun = (uint32_t)(st >> 32);
+    BitReader br;
+    br.init(words, byte_off + (bitpos >> 3), 1u << 20);
+    br.advance((int)(bitpos & 7));
+    uint64_t sgn = 0, cb = 0; int ncb = 0;
+    int k = Ss;
+    if (eobrun == 0) {
+        while (k <= Se) {
+            const uint32_t win = br.window();
+            const uint32_t e = ac_code(tab, win);
+            if (!e) break;                                   // phase 1 has already flagged the image
+            const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
+            const bool eob = (s == 0) & (r != 15);
+            const int nx = s ? 1 : (eob ? r : 0);
+            const uint32_t sbit = field(win, len, nx);
+            br.advance(len + nx);
+            if (eob) { eobrun = 1; break; }
+            const uint64_t from_k = band & ~((1ull << k) - 1);
+            uint64_t z = ~h & from_k;
+            for (int q = 0; q < r && z; q++) z &= z - 1;
+            const int pos = z ? __builtin_ctzll(z) : Se + 1;
+            const uint64_t upto = (pos >= 64) ? ~0ull : ((1ull << pos) - 1);
+            const int n = __builtin_popcountll(h & from_k & upto);
+            if (n) { cb |= take_correction_bits(&br, n) << ncb; ncb += n; }
+            if (s && pos <= Se) sgn |= (uint64_t)(sbit & 1) << pos;
+            k = pos + 1;
+        }
+    }
+    if (eobrun > 0 && k <= Se) {
+        const int n = __builtin_popcountll(h & ~((1ull << k) - 1));
+        if (n) cb |= take_correction_bits(&br, n) << ncb;
+    }
+    *sign_out = sgn; *cbits_out = cb;
+}
+
 // ---------------------------------------------------------------------------------------
 // Data-parallel part of AC refinement for one coefficient at zig-zag position k of a block.
-//   h       mask of positions non-zero before the scan (already restricted to the band)
+//   h       mask of positions non-zero before the scan (restricted to the band)
 // ---------------------------------------------------------------------------------------
 PCR_HD int16_t refine_apply(int16_t v, int k, uint64_t h, uint64_t newm, uint64_t sgn, uint64_t cb, int Al) {
     uint64_t bit = 1ull << k;
@@ -273,6 +457,15 @@ PCR_HD int16_t refine_apply(int16_t v, int k, uint64_t h, uint64_t newm, uint64_
         v = (int16_t)((sgn & bit) ? p : -p);
     }
     return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// DC refinement: bit number `index` (0 = first bit) of an unstuffed segment.
+// ---------------------------------------------------------------------------------------
+// words: aligned base of the segment (big-endian words); byte_off: start of the interval in it.
+PCR_HD int dc_refine_bit(const uint32_t* words, uint32_t byte_off, uint32_t index) {
+    const uint32_t bit = byte_off * 8 + index;
+    return (words[bit >> 5] >> (31 - (bit & 31))) & 1;
 }
 
 }  // namespace pcr

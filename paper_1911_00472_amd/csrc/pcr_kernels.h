@@ -2,8 +2,9 @@
 //   k_index      scan-group index (prefix sums of region lengths)
 //   k_parse      JPEG marker parsing, one lane per image
 //   k_unstuff    byte un-stuffing + restart-interval location, one workgroup per (image, scan)
-//   k_entropy    progressive Huffman decode, one lane per restart interval of a scan
-//   k_apply      data-parallel part of AC refinement
+//   k_dc_first, k_ac_first, k_ac_refine   progressive Huffman decode, one lane per restart
+//                interval of a scan
+//   k_apply      data-parallel refinement (DC bits, AC corrections and new coefficients)
 //   k_pixel      de-quantise + IDCT + chroma replication + YCbCr->RGB + store
 //   k_gather     materialise an image's scan prefix (parity hook)
 #pragma once
@@ -34,7 +35,12 @@ struct DevRecord {
     int16_t* coef;
     uint64_t* masks;
     int32_t* status;           // [n]
+    AcTab* tabs;               // Huffman tables of the AC refinement scans (written by phase 1, read by phase 2)
+    const uint32_t* tab_idx;   // [n][G] index into tabs
 };
+
+// segment of a scan in the clean buffer: 4-byte aligned base (big-endian words)
+PCR_HD uint32_t clean_base(uint32_t data_off) { return (data_off + 3u) & ~3u; }
 
 // --------------------------------------------------------------------------------------
 // k_index: off[g][i] = start of group g + sum of len[g][j], j < i.  One workgroup per group.
@@ -92,7 +98,7 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kmax) {
     if (img.status != kOk || g >= img.nscans) return;
     const ScanDesc& sd = R.scan[(size_t)i * R.G + g];
     const uint8_t* src = R.rec + sd.data_off;
-    uint8_t* dst = R.clean + sd.data_off;
+    uint8_t* dst = R.clean + clean_base(sd.data_off);     // stored as big-endian 32-bit words: byte o goes to o ^ 3
     const uint32_t L = sd.data_len;
     const uint32_t sb = R.slot_base[(size_t)i * R.G + g], sc = R.slot_cnt[(size_t)i * R.G + g];
     uint32_t out_total = 0, rst_total = 0;
@@ -142,7 +148,7 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kmax) {
         uint32_t excl = part[threadIdx.x] - mine;
         uint32_t o = out_total + (excl & 0xFFFF), r = rst_total + (excl >> 16);
         for (int j = 0; j < kUnstuffPer; j++) {
-            if (keep & (1u << j)) dst[o++] = b[j + 1];
+            if (keep & (1u << j)) { dst[o ^ 3u] = b[j + 1]; o++; }
             if (rst & (1u << j)) { r++; if (r < sc) R.ivl_start[sb + r] = o; }
         }
         uint32_t tot = part[255];
@@ -153,107 +159,246 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kmax) {
     if (threadIdx.x == 0) {
         // intervals whose restart marker never showed up get an empty range; the end goes last
         for (uint32_t r = rst_total + 1; r <= sc; r++) R.ivl_start[sb + r] = out_total;
+        R.ivl_start[sb + sc] = out_total;
         if (rst_total + 1 != sc) R.status[i] = kEFormat;
+        if (sd.Ss == 0 && sd.Ah != 0) {
+            // DC refinement is read in place later (one bit per block): check every interval is long enough
+            uint32_t bpm = 0;
+            for (int q = 0; q < sd.ns; q++) bpm += sd.ns > 1 ? (uint32_t)img.hs[sd.comp[q]] * img.vs[sd.comp[q]] : 1;
+            for (uint32_t r = 0; r < sc; r++) {
+                uint32_t m0 = sd.ri ? r * sd.ri : 0, m1 = sd.ri ? (m0 + sd.ri < sd.mcus ? m0 + sd.ri : sd.mcus) : sd.mcus;
+                uint32_t have = (R.ivl_start[sb + r + 1] - R.ivl_start[sb + r]) * 8;
+                if ((m1 - m0) * bpm > have) R.status[i] = kEFormat;
+            }
+        }
     }
 }
 
 // --------------------------------------------------------------------------------------
-// k_entropy: one lane per unit.  Each lane builds the Huffman tables of its scan in LDS.
+// Entropy kernels: ONE WAVEFRONT PER UNIT (a restart interval of one scan of one image).
+// Everything the decoder touches is a function of blockIdx.x alone, i.e. wave-uniform, so the
+// compiler keeps the decoder state in scalar registers and runs it on the scalar ALU with
+// native 64-bit shifts, population counts and find-first-set; the Huffman table sits in LDS.
+// A serial bit-stream decoder has no use for 64 lanes, but a lone wavefront issues only about
+// one instruction per ten cycles whatever its width, and packing 64 different streams into one
+// wavefront makes every loop iteration pay for the union of all lanes' branches; one stream
+// per wavefront costs only the branch actually taken and lets thousands of streams interleave
+// on the SIMDs.  The host orders units by decreasing byte length (longest first).
 // --------------------------------------------------------------------------------------
-constexpr int kEntropyLanes = 32;
-constexpr int kTabsPerLane = 3;
+constexpr int kEntropyLanes = 64;
 
-__global__ void __launch_bounds__(kEntropyLanes) k_entropy(DevRecord R, const Unit* units, uint32_t nunits) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    HuffTab* tabs = reinterpret_cast<HuffTab*>(smem) + (size_t)threadIdx.x * kTabsPerLane;
-    uint8_t* zz = smem + sizeof(HuffTab) * kEntropyLanes * kTabsPerLane;
-    for (int k = threadIdx.x; k < 64; k += blockDim.x) zz[k] = (uint8_t)zigzag_natural(k);
-    __syncthreads();
-    uint32_t u = blockIdx.x * blockDim.x + threadIdx.x;
-    if (u >= nunits) return;
-    const Unit un = units[u];
-    const ImgDesc& img = R.img[un.img];
-    if (R.status[un.img] != kOk || un.scan >= img.nscans) return;
-    const ScanDesc& sd = R.scan[(size_t)un.img * R.G + un.scan];
-    if (!sd.valid) return;
+struct UnitSetup {
+    BitReader br;
+    LaneScan ls;
+    int16_t* plane[kMaxComp];     // planes of the scan's components
+    bool ok;
+};
+
+PCR_D void unit_setup(const DevRecord& R, const Unit& un, UnitSetup* L) {
+    L->ok = false;
+    const ImgDesc* img = &R.img[un.img];
+    if (R.status[un.img] != kOk || un.scan >= img->nscans) return;
     const size_t ig = (size_t)un.img * R.G + un.scan;
+    const ScanDesc* sd = &R.scan[ig];
+    if (!sd->valid) return;
     const uint32_t sb = R.slot_base[ig];
     const uint32_t b0 = R.ivl_start[sb + un.interval], b1 = R.ivl_start[sb + un.interval + 1];
-    BitReader br;
-    br.init(R.clean + sd.data_off + b0, b1 > b0 ? b1 - b0 : 0);
-    UnitGeom ug;
-    ug.mcu_w = sd.mcu_w;
-    ug.mcu0 = sd.ri ? un.interval * sd.ri : 0;
-    ug.mcu1 = sd.ri ? (ug.mcu0 + sd.ri < sd.mcus ? ug.mcu0 + sd.ri : sd.mcus) : sd.mcus;
-    if (ug.mcu0 >= sd.mcus) return;
-    int16_t* base = R.coef + R.coef_off[un.img];
-    int16_t* cpl[kMaxComp];
-    {
-        size_t o = 0; int16_t* pl[kMaxComp];
-        for (int c = 0; c < img.nc; c++) { pl[c] = base + o; o += (size_t)img.bw[c] * img.bh[c] * 64; }
-        for (int j = 0; j < sd.ns; j++) cpl[j] = pl[sd.comp[j]];
+    const uint32_t ri = sd->ri, mcus = sd->mcus;
+    LaneScan& ls = L->ls;
+    ls.mcu_w = uni(sd->mcu_w);
+    ls.mcu0 = uni(ri ? un.interval * ri : 0);
+    ls.mcu1 = uni(ri ? (ls.mcu0 + ri < mcus ? ls.mcu0 + ri : mcus) : mcus);
+    if (ls.mcu0 >= mcus) return;
+    ls.Ss = uni((int)sd->Ss); ls.Se = uni((int)sd->Se); ls.Al = uni((int)sd->Al); ls.ns = uni((int)sd->ns);
+    int16_t* base = R.coef + uni((uint64_t)R.coef_off[un.img]);
+    size_t poff[kMaxComp + 1]; poff[0] = 0;
+#pragma unroll
+    for (int c = 0; c < kMaxComp; c++) poff[c + 1] = poff[c] + (c < img->nc ? (size_t)uni((uint32_t)img->bw[c]) * uni((uint32_t)img->bh[c]) * 64 : 0);
+#pragma unroll
+    for (int j = 0; j < kMaxComp; j++) {
+        const int c = uni(j < ls.ns ? (int)sd->comp[j] : 0);
+        ls.hs[j] = uni((uint32_t)img->hs[c]); ls.vs[j] = uni((uint32_t)img->vs[c]); ls.bw[j] = uni((uint32_t)img->bw[c]);
+        L->plane[j] = base + (c == 0 ? poff[0] : (c == 1 ? poff[1] : poff[2]));
     }
-    int rc;
-    if (sd.Ss == 0) {
-        if (sd.Ah == 0) {
-            const HuffTab* tp[kMaxComp];
-            for (int j = 0; j < sd.ns; j++) {
-                int same = -1;
-                for (int q = 0; q < j; q++) if (sd.dc_off[q] == sd.dc_off[j]) same = q;
-                if (same >= 0) tp[j] = tp[same];
-                else { hufftab_build(&tabs[j], R.rec + sd.dc_off[j]); tp[j] = &tabs[j]; }
-            }
-            rc = decode_dc_first(&br, &img, &sd, &ug, tp, cpl);
-        } else rc = decode_dc_refine(&br, &img, &sd, &ug, cpl);
-    } else {
-        hufftab_build(&tabs[0], R.rec + sd.ac_off);
-        int c = sd.comp[0];
-        size_t plane = (size_t)img.bw[c] * img.bh[c];
-        uint64_t* mk = R.masks + R.mask_off[ig];
-        if (sd.Ah == 0) rc = decode_ac_first(&br, &img, &sd, &ug, &tabs[0], zz, cpl[0], mk);
-        else {
-            const uint64_t* hist[kMaxHist];
-            for (int q = 0; q < sd.nhist; q++) hist[q] = R.masks + R.mask_off[(size_t)un.img * R.G + sd.hist[q]];
-            rc = decode_ac_refine(&br, &img, &sd, &ug, &tabs[0], hist, sd.nhist, mk, mk + plane, mk + 2 * plane);
-        }
-    }
+    L->br.init(reinterpret_cast<const uint32_t*>(R.clean + uni(clean_base(sd->data_off))), uni(b0), uni(b1 > b0 ? b1 - b0 : 0));
+    L->ok = true;
+}
+
+__global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits) {
+    __shared__ DcTab tabs[kMaxComp];
+    const Unit un = units[blockIdx.x];
+    UnitSetup L;
+    unit_setup(R, un, &L);
+    if (!L.ok) return;
+    const ScanDesc* sd = &R.scan[(size_t)un.img * R.G + un.scan];
+    const uint32_t o0 = sd->dc_off[0], o1 = L.ls.ns > 1 ? sd->dc_off[1] : o0, o2 = L.ls.ns > 2 ? sd->dc_off[2] : o0;
+    DcTab* t0 = &tabs[0];
+    DcTab* t1 = t0; DcTab* t2 = t0;
+    if (o1 != o0) t1 = &tabs[1];
+    if (o2 == o1) t2 = t1; else if (o2 != o0) t2 = &tabs[2];
+    if (threadIdx.x == 0) dctab_build(t0, R.rec + o0);
+    if (threadIdx.x == 1 && t1 != t0) dctab_build(t1, R.rec + o1);
+    if (threadIdx.x == 2 && t2 != t0 && t2 != t1) dctab_build(t2, R.rec + o2);
+    __syncthreads();
+    int rc = decode_dc_first(&L.br, L.ls, t0, t1, t2, L.plane[0], L.plane[1], L.plane[2]);
     if (rc != kOk) R.status[un.img] = rc;
 }
 
+__global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits) {
+    __shared__ AcTab tab;
+    const Unit un = units[blockIdx.x];
+    UnitSetup L;
+    unit_setup(R, un, &L);
+    if (!L.ok) return;
+    const size_t ig = (size_t)un.img * R.G + un.scan;
+    if (threadIdx.x == 0) actab_build(&tab, R.rec + R.scan[ig].ac_off);
+    __syncthreads();
+    int rc = decode_ac_first(&L.br, L.ls, &tab, L.plane[0], R.masks + uni((uint64_t)R.mask_off[ig]));
+    if (rc != kOk) R.status[un.img] = rc;
+}
+
+__global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const Unit* __restrict__ units, uint32_t nunits) {
+    __shared__ AcTab tab;
+    const Unit un = units[blockIdx.x];
+    UnitSetup L;
+    unit_setup(R, un, &L);
+    if (!L.ok) return;
+    const size_t ig = (size_t)un.img * R.G + un.scan;
+    const ScanDesc* sd = &R.scan[ig];
+    if (threadIdx.x == 0) actab_build(&tab, R.rec + sd->ac_off);
+    __syncthreads();
+    if (un.interval == 0) {                                 // phase 2 needs the same table: keep a copy
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&tab);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&R.tabs[R.tab_idx[ig]]);
+        for (uint32_t e = threadIdx.x; e < sizeof(AcTab) / 4; e += kEntropyLanes) dst[e] = src[e];
+    }
+    HistPlanes hp;
+    hp.n = sd->nhist;
+#pragma unroll
+    for (int q = 0; q < kMaxHist; q++) hp.p[q] = R.masks + uni((uint64_t)R.mask_off[(size_t)un.img * R.G + (q < hp.n ? sd->hist[q] : 0)]);
+    hp.n = uni(hp.n);
+    const ImgDesc* img = &R.img[un.img];
+    const int c = sd->comp[0];
+    const size_t plane = (size_t)uni((uint32_t)img->bw[c]) * uni((uint32_t)img->bh[c]);
+    uint64_t* mk = R.masks + uni((uint64_t)R.mask_off[ig]);
+    int rc = skim_ac_refine(&L.br, L.ls, &tab, hp, mk, mk + 3 * plane);
+    if (rc != kOk) R.status[un.img] = rc;
+}
+
+// Phase 2 of AC refinement: one lane per block of the scan.  grid: (ceil(max blocks / 256), scans)
+struct RefineScan { uint32_t img; uint32_t scan; };
+
+__global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const RefineScan* rs) {
+    __shared__ AcTab tab;
+    const RefineScan a = rs[blockIdx.y];
+    if (R.status[a.img] != kOk) return;
+    const ImgDesc* img = &R.img[a.img];
+    const size_t ig = (size_t)a.img * R.G + a.scan;
+    const ScanDesc* sd = &R.scan[ig];
+    const int c = sd->comp[0];
+    const uint32_t cw = img->cw[c], ncov = cw * img->ch[c];
+    if (blockIdx.x * 256 >= ncov) return;
+    {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.tabs[R.tab_idx[ig]]);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&tab);
+        for (uint32_t e = threadIdx.x; e < sizeof(AcTab) / 4; e += 256) dst[e] = src[e];
+    }
+    __syncthreads();
+    const uint32_t b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= ncov) return;
+    const uint32_t bw = img->bw[c];
+    const size_t blk = (size_t)(b / cw) * bw + (b % cw);
+    const size_t plane = (size_t)bw * img->bh[c];
+    uint64_t h = 0;
+    for (int q = 0; q < sd->nhist; q++) h |= R.masks[R.mask_off[(size_t)a.img * R.G + sd->hist[q]] + blk];
+    uint64_t* mk = R.masks + R.mask_off[ig];
+    const uint32_t ivl = sd->ri ? b / sd->ri : 0;
+    const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + clean_base(sd->data_off));
+    uint64_t sgn, cb;
+    refine_block(words, R.ivl_start[R.slot_base[ig] + ivl], mk[3 * plane + blk], &tab, h, sd->Ss, sd->Se, &sgn, &cb);
+    mk[plane + blk] = sgn; mk[2 * plane + blk] = cb;
+}
+
 // --------------------------------------------------------------------------------------
-// k_apply: for every coefficient of every block a non-interleaved scan visits, replay the AC
-// scans of its component in file order: first scans only extend the non-zero mask, refinement
-// scans add their correction bit or place their new +-2^Al value.
-// grid: (ceil(max covered coefficients / 256), apply units)
+// Refinement, data-parallel.  One lane per coefficient of every block of a component
+// (natural order within the block, so loads and stores are contiguous).
+//   k = 0: DC refinement scans -- the block's bit sits at a position fixed by the scan's block
+//          order (and restart intervals), so it is simply fetched and OR-ed in;
+//   k > 0: replay the AC scans of the component in file order: first scans only extend the
+//          non-zero mask, refinement scans add a correction bit or place a new +-2^Al.
 // --------------------------------------------------------------------------------------
+PCR_D int16_t refine_coefficient(const DevRecord& R, uint32_t i, const ImgDesc* img, int c, uint32_t row, uint32_t col, int k,
+                                 int16_t v, uint32_t upto) {
+    const uint32_t bw = img->bw[c];
+    const size_t blk = (size_t)row * bw + col;
+    const size_t plane = (size_t)bw * img->bh[c];
+    const bool covered = row < img->ch[c] && col < img->cw[c];
+    uint64_t h = 0;
+    for (uint32_t g = 0; g < upto; g++) {
+        const size_t ig = (size_t)i * R.G + g;
+        const ScanDesc* sd = &R.scan[ig];
+        if (sd->Ss == 0) {
+            if (k != 0 || sd->Ah == 0) continue;
+            // position of this block in the scan's bit string
+            int j = -1; uint32_t before = 0, bpm = 0;
+            for (int q = 0; q < sd->ns; q++) {
+                const int cq = sd->comp[q];
+                const uint32_t nb = sd->ns > 1 ? (uint32_t)img->hs[cq] * img->vs[cq] : 1;
+                if (cq == c) { j = q; before = bpm; }
+                bpm += nb;
+            }
+            if (j < 0) continue;
+            uint32_t m, within;
+            if (sd->ns > 1) {
+                const uint32_t hs = img->hs[c], vs = img->vs[c];
+                m = (row / vs) * sd->mcu_w + col / hs;
+                within = before + (row % vs) * hs + col % hs;
+            } else {
+                if (!covered) continue;
+                m = row * sd->mcu_w + col; within = 0;
+            }
+            const uint32_t ivl = sd->ri ? m / sd->ri : 0;
+            const uint32_t bit = (m - ivl * sd->ri) * bpm + within;
+            const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + clean_base(sd->data_off));
+            if (dc_refine_bit(words, R.ivl_start[R.slot_base[ig] + ivl], bit)) v |= (int16_t)(1 << sd->Al);
+        } else if (k != 0 && covered && sd->comp[0] == c) {
+            const uint64_t* mk = R.masks + R.mask_off[ig];
+            const uint64_t nz = mk[blk];
+            if (sd->Ah != 0 && k >= sd->Ss && k <= sd->Se)
+                v = refine_apply(v, k, h & band_mask(sd->Ss, sd->Se), nz, mk[plane + blk], mk[2 * plane + blk], sd->Al);
+            h |= nz;
+        }
+    }
+    return v;
+}
+
 struct ApplyUnit { uint32_t img; uint32_t comp; };
 
 __global__ void __launch_bounds__(256) k_apply(DevRecord R, const ApplyUnit* au, uint32_t kmax) {
     const ApplyUnit a = au[blockIdx.y];
-    const ImgDesc& img = R.img[a.img];
+    const ImgDesc* img = &R.img[a.img];
     if (R.status[a.img] != kOk) return;
     const int c = a.comp;
-    const uint32_t cw = img.cw[c], ncov = cw * img.ch[c];
-    uint32_t idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= ncov * 64) return;
-    const uint32_t cb = idx >> 6; const int k = idx & 63;
-    const size_t blk = (size_t)(cb / cw) * img.bw[c] + (cb % cw);
-    const size_t plane = (size_t)img.bw[c] * img.bh[c];
+    const uint32_t bw = img->bw[c], nblk = bw * img->bh[c];
+    const uint32_t idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nblk * 64) return;
+    const uint32_t b = idx >> 6;
     int16_t* pl = R.coef + R.coef_off[a.img];
-    for (int q = 0; q < c; q++) pl += (size_t)img.bw[q] * img.bh[q] * 64;
-    int16_t* cp = pl + blk * 64 + zigzag_natural(k);
-    int16_t v = *cp; const int16_t v0 = v;
-    uint64_t h = 0;
-    const uint32_t upto = img.nscans < kmax ? img.nscans : kmax;
-    for (uint32_t g = 0; g < upto; g++) {
-        const ScanDesc& sd = R.scan[(size_t)a.img * R.G + g];
-        if (sd.Ss == 0 || sd.comp[0] != c) continue;
-        const uint64_t* mk = R.masks + R.mask_off[(size_t)a.img * R.G + g];
-        if (sd.Ah != 0 && k >= sd.Ss && k <= sd.Se)
-            v = refine_apply(v, k, h & band_mask(sd.Ss, sd.Se), mk[blk], mk[plane + blk], mk[2 * plane + blk], sd.Al);
-        h |= mk[blk];
-    }
-    if (v != v0) *cp = v;
+    for (int q = 0; q < c; q++) pl += (size_t)img->bw[q] * img->bh[q] * 64;
+    const uint32_t upto = img->nscans < kmax ? img->nscans : kmax;
+    const int16_t v0 = pl[idx];
+    const int16_t v = refine_coefficient(R, a.img, img, c, b / bw, b % bw, (int)(idx & 63), v0, upto);   // element k = zig-zag position k
+    if (v != v0) pl[idx] = v;
+}
+
+// Parity hook: internal planes (zig-zag order inside each block) -> natural order.
+__global__ void __launch_bounds__(256) k_export_natural(const int16_t* in, int16_t* out, size_t n) {
+    __shared__ uint8_t zz[64];
+    if (threadIdx.x < 64) zz[threadIdx.x] = (uint8_t)zigzag_natural(threadIdx.x);
+    __syncthreads();
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n; i += stride) out[(i & ~(size_t)63) + zz[i & 63]] = in[i];
 }
 
 // --------------------------------------------------------------------------------------
@@ -269,6 +414,8 @@ struct PixelTile { uint32_t img; uint16_t mcu_row; uint16_t mcu_col0; };
 __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* tiles, uint8_t* out) {
     __shared__ float tile[kStripMcus * kMaxBlocksPerMcu * 64];
     __shared__ float qn[kMaxComp][64];
+    __shared__ uint8_t izz[64];                            // natural index -> zig-zag position (= element inside a block)
+    if (threadIdx.x < 64) izz[zigzag_natural(threadIdx.x)] = (uint8_t)threadIdx.x;
     const PixelTile t = tiles[blockIdx.x];
     const ImgDesc& img = R.img[t.img];
     const int nc = img.nc;
@@ -306,9 +453,9 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* til
         uint32_t brow = t.mcu_row * img.vs[c] + lb / bwc, bcol = t.mcu_col0 * img.hs[c] + lb % bwc;
         const int16_t* pl = coef;
         for (int q = 0; q < c; q++) pl += (size_t)img.bw[q] * img.bh[q] * 64;
-        const int16_t* src = pl + ((size_t)brow * img.bw[c] + bcol) * 64 + v * 8;
+        const int16_t* src = pl + ((size_t)brow * img.bw[c] + bcol) * 64;
         float in[8], res[8];
-        for (int u = 0; u < 8; u++) in[u] = (float)src[u] * qn[c][v * 8 + u];
+        for (int u = 0; u < 8; u++) in[u] = (float)src[izz[v * 8 + u]] * qn[c][v * 8 + u];
         idct8(in, res);
         for (int x = 0; x < 8; x++) tile[b * 64 + v * 8 + x] = res[x];
     }

@@ -19,7 +19,11 @@ using namespace pcr;
 
 namespace {
 
-struct LevelList { Unit* d_units = nullptr; uint32_t n = 0; };
+enum Kind { kDcFirst = 0, kAcFirst = 1, kAcRefine = 2, kNumKinds = 3 };
+struct LevelList {
+    Unit* d_units = nullptr; uint32_t n = 0; int kind = 0;
+    RefineScan* d_refine = nullptr; uint32_t n_refine = 0, refine_grid_x = 0;   // phase 2 of an AC refinement launch
+};
 
 struct Plan {                               // launch geometry for one scan group k
     std::vector<LevelList> levels;
@@ -88,29 +92,49 @@ int build_plan(pcr_record* r, int k, Plan** out) {
     if (it != r->plans.end()) { *out = &it->second; return PCR_OK; }
     const uint32_t n = r->hdr.n, G = r->hdr.G;
     Plan plan;
-    std::vector<std::vector<Unit>> lists(r->max_level);
-    std::vector<ApplyUnit> apply; uint32_t max_cov = 0;
+    struct Item { Unit u; uint32_t bytes; };
+    std::vector<std::vector<Item>> lists((size_t)r->max_level * kNumKinds);
+    std::vector<std::vector<RefineScan>> rlists(r->max_level); std::vector<uint32_t> rmax(r->max_level, 0);
+    std::vector<ApplyUnit> apply; uint32_t max_blk = 0;
     for (uint32_t i = 0; i < n; i++) {
         const uint32_t upto = std::min<uint32_t>(r->img[i].nscans, (uint32_t)k);
         bool refine[kMaxComp] = {false, false, false};
         for (uint32_t g = 0; g < upto; g++) {
             const size_t ig = (size_t)i * G + g;
             const ScanDesc& sd = r->scan[ig];
-            for (uint32_t j = 0; j < r->slot_cnt[ig]; j++) lists[r->level[ig] - 1].push_back(Unit{i, g, j, r->slot_base[ig]});
-            if (sd.Ss > 0 && sd.Ah > 0) refine[sd.comp[0]] = true;
+            if (sd.Ah > 0) for (int j = 0; j < sd.ns; j++) refine[sd.comp[j]] = true;
+            if (sd.Ss == 0 && sd.Ah > 0) continue;             // DC refinement has no serial decode
+            const int kind = sd.Ss == 0 ? kDcFirst : (sd.Ah == 0 ? kAcFirst : kAcRefine);
+            if (kind == kAcRefine) {
+                rlists[r->level[ig] - 1].push_back(RefineScan{i, g});
+                rmax[r->level[ig] - 1] = std::max<uint32_t>(rmax[r->level[ig] - 1], (uint32_t)r->img[i].cw[sd.comp[0]] * r->img[i].ch[sd.comp[0]]);
+            }
+            const uint32_t cnt = r->slot_cnt[ig];
+            for (uint32_t j = 0; j < cnt; j++)
+                lists[(size_t)(r->level[ig] - 1) * kNumKinds + kind].push_back(Item{Unit{i, g, j, r->slot_base[ig]}, sd.data_len / cnt});
         }
         for (int c = 0; c < r->img[i].nc; c++) if (refine[c]) {
             apply.push_back(ApplyUnit{i, (uint32_t)c});
-            max_cov = std::max<uint32_t>(max_cov, (uint32_t)r->img[i].cw[c] * r->img[i].ch[c]);
+            max_blk = std::max<uint32_t>(max_blk, (uint32_t)r->img[i].bw[c] * r->img[i].bh[c]);
         }
     }
-    for (auto& l : lists) {
-        LevelList ll; ll.n = (uint32_t)l.size();
-        if (ll.n) { int rc = dev_upload(&ll.d_units, l); if (rc) return rc; }
+    for (size_t li = 0; li < lists.size(); li++) {
+        auto& l = lists[li];
+        if (l.empty()) continue;
+        std::stable_sort(l.begin(), l.end(), [](const Item& a, const Item& b) { return a.bytes > b.bytes; });   // longest first
+        std::vector<Unit> units(l.size());
+        for (size_t e = 0; e < l.size(); e++) units[e] = l[e].u;
+        LevelList ll; ll.n = (uint32_t)units.size(); ll.kind = (int)(li % kNumKinds);
+        int rc = dev_upload(&ll.d_units, units); if (rc) return rc;
+        if (ll.kind == kAcRefine) {
+            const auto& rl = rlists[li / kNumKinds];
+            ll.n_refine = (uint32_t)rl.size(); ll.refine_grid_x = (rmax[li / kNumKinds] + 255) / 256;
+            rc = dev_upload(&ll.d_refine, rl); if (rc) return rc;
+        }
         plan.levels.push_back(ll);
     }
     plan.n_apply = (uint32_t)apply.size();
-    plan.apply_grid_x = (max_cov * 64 + 255) / 256;
+    plan.apply_grid_x = (max_blk * 64 + 255) / 256;
     if (plan.n_apply) { int rc = dev_upload(&plan.d_apply, apply); if (rc) return rc; }
     auto ins = r->plans.emplace(k, plan);
     *out = &ins.first->second;
@@ -119,7 +143,7 @@ int build_plan(pcr_record* r, int k, Plan** out) {
 
 void free_plans(pcr_record* r) {
     for (auto& kv : r->plans) {
-        for (auto& l : kv.second.levels) if (l.d_units) (void)hipFree(l.d_units);
+        for (auto& l : kv.second.levels) { if (l.d_units) (void)hipFree(l.d_units); if (l.d_refine) (void)hipFree(l.d_refine); }
         if (kv.second.d_apply) (void)hipFree(kv.second.d_apply);
     }
     r->plans.clear();
@@ -146,11 +170,16 @@ int run_entropy_stages(pcr_record* r, int k, hipStream_t s) {
     hipLaunchKernelGGL(k_unstuff, dim3(n, k), dim3(256), 0, s, r->d, (uint32_t)k);
     const size_t coef_bytes = r->coef_off[n] * sizeof(int16_t);
     hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
+    if (r->n_masks) hipLaunchKernelGGL(k_fill_zero, dim3(1024), dim3(256), 0, s, (uint4*)r->d.masks, (r->n_masks * 8 + 15) / 16);
     stamp(r, 2, s);
-    const size_t smem = sizeof(HuffTab) * kEntropyLanes * kTabsPerLane + 64;
     for (auto& l : plan->levels) {
-        if (!l.n) continue;
-        hipLaunchKernelGGL(k_entropy, dim3((l.n + kEntropyLanes - 1) / kEntropyLanes), dim3(kEntropyLanes), smem, s, r->d, l.d_units, l.n);
+        const dim3 grid(l.n), block(kEntropyLanes);
+        if (l.kind == kDcFirst) hipLaunchKernelGGL(k_dc_first, grid, block, 0, s, r->d, l.d_units, l.n);
+        else if (l.kind == kAcFirst) hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n);
+        else {
+            hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n);
+            hipLaunchKernelGGL(k_refine_blocks, dim3(l.refine_grid_x, l.n_refine), dim3(256), 0, s, r->d, l.d_refine);
+        }
     }
     stamp(r, 3, s);
     if (plan->n_apply) hipLaunchKernelGGL(k_apply, dim3(plan->apply_grid_x, plan->n_apply), dim3(256), 0, s, r->d, plan->d_apply, (uint32_t)k);
@@ -209,6 +238,7 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
     r->mask_off.assign((size_t)n * G, 0); r->slot_base.assign((size_t)n * G, 0); r->slot_cnt.assign((size_t)n * G, 0);
     std::vector<PixelTile> tiles;
     uint64_t nm = 0; uint64_t ns = 0;
+    std::vector<uint32_t> tab_idx((size_t)n * G, 0); uint32_t ntabs = 0;
     for (uint32_t i = 0; i < n; i++) {
         const ImgDesc& d = r->img[i];
         r->out_off[i + 1] = r->out_off[i] + (uint64_t)d.W * d.H * d.nc;
@@ -220,7 +250,8 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
             const ScanDesc& sd = r->scan[ig];
             if (sd.Ss > 0) {
                 r->mask_off[ig] = nm;
-                nm += (uint64_t)d.bw[sd.comp[0]] * d.bh[sd.comp[0]] * (sd.Ah ? 3 : 1);
+                nm += (uint64_t)d.bw[sd.comp[0]] * d.bh[sd.comp[0]] * (sd.Ah ? 4 : 1);   // refinement: nzout, sign, cbits, start
+                if (sd.Ah) tab_idx[ig] = ntabs++;
             }
             uint32_t cnt = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;
             r->slot_base[ig] = (uint32_t)ns; r->slot_cnt[ig] = cnt;
@@ -235,14 +266,14 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
     // ---- device buffers ----
     DevRecord& d = r->d;
     rc = PCR_OK;
-    const size_t padded = nbytes + 64;
+    const size_t padded = nbytes + 1024;      // slack: bit readers look ahead, gathers round up
     if (!rc) rc = dev_alloc(&r->d_rec, padded);
     if (!rc) rc = dev_alloc(&d.clean, padded);
     if (!rc) rc = dev_alloc(&d.off, (size_t)G * n);
     if (!rc) rc = dev_alloc(&d.img, n);
     if (!rc) rc = dev_alloc(&d.scan, (size_t)n * G);
     if (!rc) rc = dev_alloc(&d.coef, r->coef_off[n]);
-    if (!rc) rc = dev_alloc(&d.masks, nm);
+    if (!rc) rc = dev_alloc(&d.masks, nm + 2);
     if (!rc) rc = dev_alloc(&d.ivl_start, ns);
     if (!rc) rc = dev_alloc(&d.status, n);
     uint64_t *d_coef_off = nullptr, *d_out_off = nullptr, *d_mask_off = nullptr; uint32_t *d_sb = nullptr, *d_sc = nullptr;
@@ -252,6 +283,10 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
     if (!rc) rc = dev_upload(&d_sb, r->slot_base);
     if (!rc) rc = dev_upload(&d_sc, r->slot_cnt);
     if (!rc) rc = dev_upload(&r->d_tiles, tiles);
+    uint32_t* d_tab_idx = nullptr;
+    if (!rc) rc = dev_upload(&d_tab_idx, tab_idx);
+    if (!rc) rc = dev_alloc(&d.tabs, (size_t)ntabs);
+    d.tab_idx = d_tab_idx;
     d.coef_off = d_coef_off; d.out_off = d_out_off; d.mask_off = d_mask_off; d.slot_base = d_sb; d.slot_cnt = d_sc;
     if (!rc && hipMemcpy(r->d_rec, bytes, nbytes, hipMemcpyHostToDevice) != hipSuccess) rc = PCR_E_DEVICE;
     if (!rc && hipMemset(r->d_rec + nbytes, 0, padded - nbytes) != hipSuccess) rc = PCR_E_DEVICE;
@@ -264,8 +299,6 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
         d.rec = r->d_rec; d.n = n; d.G = G;
         d.len = (const uint32_t*)(r->d_rec + hdr_len_pos(n, G, 0, 0));
         d.nscans = (const uint32_t*)(r->d_rec + hdr_nscans_pos(n, G, 0));
-        const size_t smem = sizeof(HuffTab) * kEntropyLanes * kTabsPerLane + 64;
-        if (hipFuncSetAttribute((const void*)k_entropy, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) rc = PCR_E_DEVICE;
     }
     if (!rc) {
         bool ok = true;
@@ -284,7 +317,7 @@ void pcr_close(pcr_record* r) {
     free_plans(r);
     DevRecord& d = r->d;
     void* ptrs[] = { r->d_rec, d.clean, d.off, d.img, d.scan, d.coef, d.masks, d.ivl_start, d.status, (void*)d.coef_off, (void*)d.out_off,
-                     (void*)d.mask_off, (void*)d.slot_base, (void*)d.slot_cnt, r->d_tiles, r->d_gather };
+                     (void*)d.mask_off, (void*)d.slot_base, (void*)d.slot_cnt, r->d_tiles, r->d_gather, d.tabs, (void*)d.tab_idx };
     for (void* p : ptrs) if (p) (void)hipFree(p);
     if (r->ev_valid) for (auto& e : r->ev) (void)hipEventDestroy(e);
     delete r;
@@ -385,7 +418,8 @@ int pcr_decode_coefficients(pcr_record* r, int k, int16_t* d_coef, void* stream)
     if (rc) return rc;
     stamp(r, 5, s);
     r->ev_recorded = r->timing && r->ev_valid;
-    HIP_TRY(hipMemcpyAsync(d_coef, r->d.coef, r->coef_off[r->hdr.n] * sizeof(int16_t), hipMemcpyDeviceToDevice, s));
+    hipLaunchKernelGGL(k_export_natural, dim3(2048), dim3(256), 0, s, r->d.coef, d_coef, (size_t)r->coef_off[r->hdr.n]);
+    if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
     return PCR_OK;
 }
 

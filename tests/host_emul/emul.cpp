@@ -52,58 +52,92 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
     std::vector<int16_t> coef(poff[img.nc], 0);
     std::vector<std::vector<uint64_t>> masks(G);
     uint8_t zz[64]; for (int q = 0; q < 64; q++) zz[q] = (uint8_t)zigzag_natural(q);
+    std::vector<std::vector<uint8_t>> cleans(G); std::vector<std::vector<uint32_t>> ivls(G);
     for (uint32_t g = 0; g < img.nscans; g++) {
         const ScanDesc& sd = sc[g];
-        std::vector<uint8_t> clean; std::vector<uint32_t> starts;
+        std::vector<uint8_t>& clean = cleans[g]; std::vector<uint32_t>& starts = ivls[g];
+        clean.reserve(sd.data_len + 64);
         unstuff(rec + sd.data_off, sd.data_len, clean, starts);
         uint32_t nint = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;
         if (starts.size() != nint) return kEFormat;
         starts.push_back((uint32_t)clean.size());
-        clean.resize(clean.size() + 16, 0xFF);
+        clean.resize((clean.size() + 3) / 4 * 4 + 64, 0xFF);      // look-ahead slack
+        for (size_t e = 0; e + 3 < clean.size(); e += 4) { std::swap(clean[e], clean[e + 3]); std::swap(clean[e + 1], clean[e + 2]); }   // big-endian words
         int c0 = sd.comp[0];
         size_t plane = (size_t)img.bw[c0] * img.bh[c0];
-        if (sd.Ss > 0) masks[g].assign(plane * (sd.Ah ? 3 : 1), 0);
+        if (sd.Ss > 0) masks[g].assign(plane * (sd.Ah ? 4 : 1), 0);
+        if (sd.Ss == 0 && sd.Ah > 0) continue;                     // DC refinement: applied below, in place
         for (uint32_t j = 0; j < nint; j++) {
-            BitReader br; br.init(clean.data() + starts[j], starts[j + 1] - starts[j]);
-            UnitGeom ug; ug.mcu_w = sd.mcu_w; ug.mcu0 = sd.ri ? j * sd.ri : 0;
-            ug.mcu1 = sd.ri ? (ug.mcu0 + sd.ri < sd.mcus ? ug.mcu0 + sd.ri : sd.mcus) : sd.mcus;
-            int16_t* cpl[kMaxComp];
-            for (int q = 0; q < sd.ns; q++) cpl[q] = coef.data() + poff[sd.comp[q]];
-            std::vector<HuffTab> tabs(3);
+            BitReader br; br.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j]);
+            LaneScan ls;
+            ls.mcu_w = sd.mcu_w; ls.mcu0 = sd.ri ? j * sd.ri : 0;
+            ls.mcu1 = sd.ri ? (ls.mcu0 + sd.ri < sd.mcus ? ls.mcu0 + sd.ri : sd.mcus) : sd.mcus;
+            ls.Ss = sd.Ss; ls.Se = sd.Se; ls.Al = sd.Al; ls.ns = sd.ns;
+            int16_t* cpl[kMaxComp] = {nullptr, nullptr, nullptr};
+            for (int q = 0; q < kMaxComp; q++) {
+                int c = q < sd.ns ? sd.comp[q] : 0;
+                ls.hs[q] = img.hs[c]; ls.vs[q] = img.vs[c]; ls.bw[q] = img.bw[c];
+                cpl[q] = coef.data() + poff[c];
+            }
             if (sd.Ss == 0) {
-                if (sd.Ah == 0) {
-                    const HuffTab* tp[kMaxComp];
-                    for (int q = 0; q < sd.ns; q++) { hufftab_build(&tabs[q], rec + sd.dc_off[q]); tp[q] = &tabs[q]; }
-                    rc = decode_dc_first(&br, &img, &sd, &ug, tp, cpl);
-                } else rc = decode_dc_refine(&br, &img, &sd, &ug, cpl);
+                std::vector<DcTab> dt(3);
+                for (int q = 0; q < sd.ns; q++) dctab_build(&dt[q], rec + sd.dc_off[q]);
+                rc = decode_dc_first(&br, ls, &dt[0], &dt[1], &dt[2], cpl[0], cpl[1], cpl[2]);
             } else {
-                hufftab_build(&tabs[0], rec + sd.ac_off);
-                if (sd.Ah == 0) rc = decode_ac_first(&br, &img, &sd, &ug, &tabs[0], zz, cpl[0], masks[g].data());
+                AcTab at; actab_build(&at, rec + sd.ac_off);
+                if (sd.Ah == 0) rc = decode_ac_first(&br, ls, &at, cpl[0], masks[g].data());
                 else {
-                    const uint64_t* hist[kMaxHist];
-                    for (int q = 0; q < sd.nhist; q++) hist[q] = masks[sd.hist[q]].data();
-                    rc = decode_ac_refine(&br, &img, &sd, &ug, &tabs[0], hist, sd.nhist, masks[g].data(), masks[g].data() + plane, masks[g].data() + 2 * plane);
+                    HistPlanes hp; hp.n = sd.nhist;
+                    for (int q = 0; q < kMaxHist; q++) hp.p[q] = masks[q < sd.nhist ? sd.hist[q] : 0].data();
+                    rc = skim_ac_refine(&br, ls, &at, hp, masks[g].data(), masks[g].data() + 3 * plane);
+                    if (rc) return rc;
+                    // phase 2: every block of this interval on its own
+                    for (uint32_t mm = ls.mcu0; mm < ls.mcu1; mm++) {
+                        size_t blk = (size_t)(mm / sd.mcu_w) * img.bw[c0] + (mm % sd.mcu_w);
+                        uint64_t hh = 0;
+                        for (int q = 0; q < sd.nhist; q++) hh |= masks[sd.hist[q]][blk];
+                        refine_block(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], masks[g][3 * plane + blk], &at, hh, sd.Ss, sd.Se,
+                                     &masks[g][plane + blk], &masks[g][2 * plane + blk]);
+                    }
                 }
             }
             if (rc) return rc;
         }
     }
-    // refinement apply
+    // refinement, one coefficient at a time (mirrors refine_coefficient of the kernels)
     for (int c = 0; c < img.nc; c++) {
         size_t plane = (size_t)img.bw[c] * img.bh[c];
-        for (uint32_t by = 0; by < img.ch[c]; by++) for (uint32_t bx = 0; bx < img.cw[c]; bx++) for (int kk = 0; kk < 64; kk++) {
-            size_t blk = (size_t)by * img.bw[c] + bx;
-            int16_t* cp = coef.data() + poff[c] + blk * 64 + zz[kk];
+        for (uint32_t row = 0; row < img.bh[c]; row++) for (uint32_t col = 0; col < img.bw[c]; col++) for (int kk = 0; kk < 64; kk++) {
+            size_t blk = (size_t)row * img.bw[c] + col;
+            bool covered = row < img.ch[c] && col < img.cw[c];
+            int16_t* cp = coef.data() + poff[c] + blk * 64 + kk;     // internal order: element k = zig-zag position k
             int16_t v = *cp; uint64_t hh = 0;
             for (uint32_t g = 0; g < img.nscans; g++) {
                 const ScanDesc& sd = sc[g];
-                if (sd.Ss == 0 || sd.comp[0] != c) continue;
-                const uint64_t* mk = masks[g].data();
-                if (sd.Ah != 0 && kk >= sd.Ss && kk <= sd.Se) v = refine_apply(v, kk, hh & band_mask(sd.Ss, sd.Se), mk[blk], mk[plane + blk], mk[2 * plane + blk], sd.Al);
-                hh |= mk[blk];
+                if (sd.Ss == 0) {
+                    if (kk != 0 || sd.Ah == 0) continue;
+                    int j = -1; uint32_t before = 0, bpm = 0;
+                    for (int q = 0; q < sd.ns; q++) { int cq = sd.comp[q]; uint32_t nb = sd.ns > 1 ? (uint32_t)img.hs[cq] * img.vs[cq] : 1; if (cq == c) { j = q; before = bpm; } bpm += nb; }
+                    if (j < 0) continue;
+                    uint32_t m, within;
+                    if (sd.ns > 1) { m = (row / img.vs[c]) * sd.mcu_w + col / img.hs[c]; within = before + (row % img.vs[c]) * img.hs[c] + col % img.hs[c]; }
+                    else { if (!covered) continue; m = row * sd.mcu_w + col; within = 0; }
+                    uint32_t ivl = sd.ri ? m / sd.ri : 0, bit = (m - ivl * sd.ri) * bpm + within;
+                    if (bit >= (ivls[g][ivl + 1] - ivls[g][ivl]) * 8) return kEFormat;
+                    if (dc_refine_bit(reinterpret_cast<const uint32_t*>(cleans[g].data()), ivls[g][ivl], bit)) v |= (int16_t)(1 << sd.Al);
+                } else if (kk != 0 && covered && sd.comp[0] == c) {
+                    const uint64_t* mk = masks[g].data();
+                    if (sd.Ah != 0 && kk >= sd.Ss && kk <= sd.Se) v = refine_apply(v, kk, hh & band_mask(sd.Ss, sd.Se), mk[blk], mk[plane + blk], mk[2 * plane + blk], sd.Al);
+                    hh |= mk[blk];
+                }
             }
             *cp = v;
         }
+    }
+    {   // internal (zig-zag inside each block) -> natural order
+        std::vector<int16_t> nat(coef.size());
+        for (size_t e = 0; e < coef.size(); e++) nat[(e & ~(size_t)63) + zz[e & 63]] = coef[e];
+        coef.swap(nat);
     }
     if (coef_out) memcpy(coef_out, coef.data(), coef.size() * sizeof(int16_t));
     if (pix_out) {

@@ -69,3 +69,9 @@ def test_lane_code_matches_oracle_444_and_deep_script(emul):
     G = oracle.record_header(rec)["G"]
     assert G == len(DEEP)
     _compare(emul, rec, range(len(files)), range(1, G + 1))
+
+
+def test_lane_code_matches_oracle_headline_images(emul):
+    """Large, noisy images: Huffman codes longer than the 8-bit look-ahead table, long streams."""
+    records, _ = pcrgen.make_workload("imagenet_like", limit=6)
+    _compare(emul, records[0], range(6), (1, 2, 5, 6, 10))
