@@ -87,11 +87,12 @@ def main():
     outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in handles]
     for h in handles:
         h.enable_stage_timing(True)
-    stream = torch.cuda.current_stream().cuda_stream
+    # one stream per record: records are independent, so their kernels may overlap (default priority)
+    streams = [torch.cuda.Stream() for _ in handles]
 
     def step(k):
-        for h, o in zip(handles, outs):
-            h.decode_batch(k, out=o, stream=stream)
+        for h, o, st in zip(handles, outs, streams):
+            h.decode_batch(k, out=o, stream=st.cuda_stream)
 
     # ---- parity spot check against the oracle before anything is timed ----
     import oracle

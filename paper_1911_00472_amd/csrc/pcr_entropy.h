@@ -121,49 +121,51 @@ PCR_HD void actab_build(AcTab* t, const uint8_t* bits_vals) {
 // ---------------------------------------------------------------------------------------
 // Bit reader over the unstuffed data of one unit.  The data is stored as big-endian 32-bit
 // words (the unstuff step swaps the bytes of every aligned 4-byte group), so a word is usable
-// as loaded.  `acc` holds `cnt` valid bits left-aligned in 64 bits; words come from a 4-word
-// queue q*, itself refilled from a second group nx whose 16-byte load was issued a whole group
-// earlier: the loop never waits on the load it has just issued.  `left` counts the unit's unread
-// bits and goes negative when a decoder consumes more than the unit holds.  The buffer must
-// stay readable for 48 bytes past any position a decoder can reach before it checks `left`.
-// Everything here is wave-uniform when the unit is: it then lives in scalar registers.
+// as loaded.  `acc` holds `cnt` valid bits left-aligned in 64 bits; `nxt` is the following
+// word, loaded one refill ahead so that the loop never waits on the load it has just issued.
+// The state is deliberately tiny (pointer, accumulator, one word, one count): when the unit is
+// wave-uniform all of it sits in scalar registers.  The buffer must stay readable for 16 bytes
+// past any position a decoder can reach before it checks overrun().
 // ---------------------------------------------------------------------------------------
-struct __attribute__((packed, aligned(4))) Word4 { uint32_t a, b, c, d; };
-
 struct BitReader {
-    const Word4* p;             // next group to load
+    const uint32_t* p;          // word after nxt
+    const uint32_t* end_word;   // first word wholly past the unit
     uint64_t acc;
-    uint32_t q0, q1, q2, q3;    // queued words
-    Word4 nx;                   // prefetched group
-    int32_t cnt, nq, left;
+    uint32_t nxt;
+    int32_t cnt;
+    int32_t tail_bits;          // bits of the unit that lie in the words before end_word
 
     // words: 4-byte aligned base of the segment; byte_off: where the unit starts inside it
     PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes) {
         const uint32_t mis = byte_off & 3;
-        p = (const Word4*)(words + (byte_off >> 2));
-        Word4 g = p[0]; nx = p[1]; p += 2;
-        acc = ((uint64_t)g.a << 32) | g.b; cnt = 64;
-        q0 = g.c; q1 = g.d; q2 = 0; q3 = 0; nq = 2;
-        left = (int32_t)(nbytes * 8 + mis * 8);
+        p = words + (byte_off >> 2);
+        const uint32_t total_bits = nbytes * 8 + mis * 8;    // from the first word's first bit
+        end_word = p + ((total_bits + 31) >> 5);
+        tail_bits = (int32_t)(((total_bits + 31) & ~31u) - total_bits);   // padding bits inside the last word
+        acc = ((uint64_t)p[0] << 32) | p[1]; cnt = 64;
+        nxt = p[2]; p += 3;
         advance((int)(mis * 8));
     }
     PCR_HD uint32_t window() const { return (uint32_t)(acc >> 32); }     // the next 32 unread bits
-    PCR_HD void pop_word() {                                 // cnt <= 32: append one word
-        acc |= (uint64_t)q0 << (32 - cnt); cnt += 32;
-        q0 = q1; q1 = q2; q2 = q3;
-        if (--nq == 0) { q0 = nx.a; q1 = nx.b; q2 = nx.c; q3 = nx.d; nq = 4; nx = *p++; }
+    PCR_HD void pop_word() {                                 // cnt <= 32: append one word, fetch the one after
+        acc |= (uint64_t)nxt << (32 - cnt); cnt += 32;
+        nxt = *p++;
     }
     PCR_HD void advance(int n) {                             // 0 <= n <= 32; afterwards cnt >= 33
-        acc <<= n; cnt -= n; left -= n;
+        acc <<= n; cnt -= n;
         if (cnt <= 32) pop_word();
     }
     PCR_HD void advance_long(int n) {                        // any n >= 0
-        left -= n;
         while (n > 32) { acc <<= 32; cnt -= 32; if (cnt <= 32) pop_word(); n -= 32; }
         acc <<= n; cnt -= n;
         if (cnt <= 32) pop_word();
     }
-    PCR_HD bool overrun() const { return left < 0; }
+    // bits consumed so far, counted from the unit's first bit
+    PCR_HD int64_t unread_bits() const {                     // may be negative: bits taken beyond the unit
+        // words handed out so far: everything before p, minus nxt (32 bits) and the cnt bits still in acc
+        return (int64_t)(end_word - p) * 32 + 32 + cnt - tail_bits;
+    }
+    PCR_HD bool overrun() const { return unread_bits() < 0; }
 };
 
 // bits [len, len+n) of a 32-bit window (n may be 0)
@@ -250,7 +252,7 @@ PCR_HD int decode_dc_first(BitReader* br, const LaneScan& ls, const DcTab* tab0,
 }
 
 // ---------------------------------------------------------------------------------------
-// AC first scan of one component, band Ss..Se, flat loop.  Writes coefficient values in
+// AC first scan of one component, band Ss..Se.  Writes coefficient values in
 // ZIG-ZAG order inside each 64-element block (element k of a block is zig-zag position k) and,
 // per block, the mask of positions it made non-zero.  Blocks skipped by an end-of-band run are
 // not touched: coefficients and nzout must be zero-filled beforehand.
@@ -260,43 +262,46 @@ PCR_HD int decode_ac_first(BitReader* br, const LaneScan& ls, const AcTab* tab, 
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     uint32_t m = ls.mcu0;
     uint32_t row = m / mcu_w, col = m % mcu_w;
-    size_t blk = (size_t)row * bw + col;
-    uint64_t mask = 0;
-    int k = Ss;
     while (m < ls.mcu1) {
-        const uint32_t win = br->window();
-        const uint32_t e = ac_code(tab, win);
-        if (!e) return kEFormat;
-        const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
-        const bool eob = (s == 0) & (r != 15);
-        const int nx = s ? s : (eob ? r : 0);                // extra bits after the code
-        const uint32_t extra = field(win, len, nx);
-        br->advance(len + nx);
-        uint32_t eobrun = 0;
-        if (s) {
-            k += r;
-            if (k > Se) return kEFormat;
-            coef[blk * 64 + k] = (int16_t)(extend(extra, s) * (1 << Al));
-            mask |= 1ull << k;
-            k++;
-        } else if (eob) { eobrun = (1u << r) - 1 + extra; k = 64; }
-        else k += 16;
-        if (k > Se) {                                        // block finished
-            nzout[blk] = mask;
-            if (br->overrun()) return kEFormat;
-            uint32_t adv = 1 + eobrun;                       // this block + the blocks the run covers
-            if (adv > ls.mcu1 - m) adv = ls.mcu1 - m;
-            m += adv; col += adv;
-            if (col >= mcu_w) { row += col / mcu_w; col %= mcu_w; }
-            blk = (size_t)row * bw + col;
-            mask = 0; k = Ss;
+        const size_t blk = (size_t)row * bw + col;
+        int16_t* cb = coef + blk * 64;
+        uint64_t mask = 0;
+        uint32_t skip = 1;                                   // blocks to move on by: this one + an end-of-band run
+        int k = Ss;
+        while (k <= Se) {
+            const uint32_t win = br->window();
+            const uint32_t e = ac_code(tab, win);
+            const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
+            if (__builtin_expect(s != 0, 1)) {               // a coefficient: run r, then s value bits
+                const uint32_t bits = (win << len) >> (32 - s);
+                br->advance(len + s);
+                k += r;
+                if (k > Se) return kEFormat;
+                const int v = (int)bits + ((bits >> (s - 1)) ? 0 : 1 - (1 << s));
+                cb[k] = (int16_t)(v * (1 << Al));
+                mask |= 1ull << k;
+                k++;
+            } else if (r == 15) {                            // sixteen zeros
+                br->advance(len);
+                k += 16;
+            } else {                                         // end of band, run of 2^r + extra blocks
+                if (!e) return kEFormat;
+                skip = (1u << r) + field(win, len, r);
+                br->advance(len + r);
+                break;
+            }
         }
+        nzout[blk] = mask;
+        if (br->overrun()) return kEFormat;
+        if (skip > ls.mcu1 - m) skip = ls.mcu1 - m;
+        m += skip; col += skip;
+        if (col >= mcu_w) { row += col / mcu_w; col %= mcu_w; }
     }
     return kOk;
 }
 
 // ---------------------------------------------------------------------------------------
-// AC refinement scan, flat loop.  hist0..: masks written by the earlier AC scans of the
+// AC refinement scan.  hist0..: masks written by the earlier AC scans of the
 // component (nhist of them).  Per block this writes
 //   nzout  positions that become non-zero in this scan,
 //   sign   for those positions, 1 = positive,
@@ -342,58 +347,47 @@ PCR_HD int skim_ac_refine(BitReader* br, const LaneScan& ls, const AcTab* tab, c
                           uint64_t* nzout, uint64_t* start) {
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     const uint64_t band = band_mask(ls.Ss, ls.Se);
-    const uint32_t blo = (uint32_t)band, bhi = (uint32_t)(band >> 32);
     uint32_t m = ls.mcu0;
     if (m >= ls.mcu1) return kOk;
     uint32_t row = m / mcu_w, col = m % mcu_w;
-    size_t blk = (size_t)row * bw + col;
-    const int32_t left0 = br->left;
-    uint64_t h = hist_at(hp, blk);
-    uint32_t hlo = (uint32_t)h & blo, hhi = (uint32_t)(h >> 32) & bhi;
-    uint32_t zlo = ~hlo & blo, zhi = ~hhi & bhi;
-    uint32_t nlo = 0, nhi = 0;
-    uint32_t eobrun = 0;
-    start[blk] = 0;
-    while (true) {
-        int tot; bool done;
+    const int64_t left0 = br->unread_bits();
+    uint32_t eobrun = 0;                                     // blocks still covered by an end-of-band run
+    for (; m < ls.mcu1; m++) {
+        const size_t blk = (size_t)row * bw + col;
+        if (++col == mcu_w) { col = 0; row++; }
+        start[blk] = ((uint64_t)eobrun << 32) | (uint32_t)(left0 - br->unread_bits());
+        uint64_t h = hist_at(hp, blk) & band;                // already non-zero, not yet passed
+        uint64_t z = ~h & band;                              // still zero, not yet passed
+        uint64_t newm = 0;
         if (eobrun == 0) {
-            const uint32_t win = br->window();
-            const uint32_t e = ac_code(tab, win);
-            if (!e) return kEFormat;
-            const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
-            if (s > 1) return kEFormat;
-            if ((s == 0) & (r != 15)) {                      // end of band (run): the rest of the block is corrections
-                eobrun = (1u << r) + field(win, len, r) - 1;
-                tot = len + r + __builtin_popcount(hlo) + __builtin_popcount(hhi);
-                done = true;
-            } else {
-                for (int q = 0; q < r; q++) { if (zlo) zlo &= zlo - 1; else zhi &= zhi - 1; }   // pass r still-zero positions
-                uint32_t mlo, mhi;                            // positions below the one the run stops on
-                if (zlo) { const int pos = __builtin_ctz(zlo); mlo = (1u << pos) - 1; mhi = 0; zlo &= zlo - 1; if (s) nlo |= 1u << pos; }
-                else if (zhi) { const int pos = __builtin_ctz(zhi); mlo = ~0u; mhi = (1u << pos) - 1; zhi &= zhi - 1; if (s) nhi |= 1u << pos; }
-                else { if (s) return kEFormat; mlo = ~0u; mhi = ~0u; }   // ran off the band: only legal for a zero run
-                tot = len + s + __builtin_popcount(hlo & mlo) + __builtin_popcount(hhi & mhi);
-                hlo &= ~mlo; hhi &= ~mhi;
-                done = (zlo | zhi | hlo | hhi) == 0;
+            while (z | h) {
+                const uint32_t win = br->window();
+                const uint32_t e = ac_code(tab, win);
+                const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
+                if (__builtin_expect(s == 1, 1)) {           // a new +-1: pass r zeros, take the next one
+                    for (int q = 0; q < r; q++) z &= z - 1;
+                    if (!z) return kEFormat;                 // no place left for it
+                    const uint64_t bit = z & (0 - z);
+                    const uint64_t below = bit - 1;
+                    br->advance_long(len + 1 + __builtin_popcountll(h & below));   // code, sign, corrections passed
+                    h &= ~below; z &= ~bit; newm |= bit;
+                } else if (s == 0 && r == 15) {              // sixteen zeros (or to the end of the band)
+                    for (int q = 0; q < 15; q++) z &= z - 1;
+                    const uint64_t bit = z & (0 - z);
+                    const uint64_t below = bit ? bit - 1 : ~0ull;
+                    br->advance_long(len + __builtin_popcountll(h & below));
+                    h &= ~below; z &= ~bit;
+                } else {                                     // end of band (run): the rest is corrections
+                    if (!e || s > 1) return kEFormat;
+                    eobrun = (1u << r) + field(win, len, r);
+                    br->advance(len + r);
+                    break;
+                }
             }
-        } else {
-            tot = __builtin_popcount(hlo) + __builtin_popcount(hhi);
-            eobrun--;
-            done = true;
         }
-        br->advance_long(tot);
-        if (done) {
-            nzout[blk] = ((uint64_t)nhi << 32) | nlo;
-            if (br->overrun()) return kEFormat;
-            if (++m >= ls.mcu1) break;
-            if (++col == mcu_w) { col = 0; row++; }
-            blk = (size_t)row * bw + col;
-            start[blk] = ((uint64_t)eobrun << 32) | (uint32_t)(left0 - br->left);
-            h = hist_at(hp, blk);
-            hlo = (uint32_t)h & blo; hhi = (uint32_t)(h >> 32) & bhi;
-            zlo = ~hlo & blo; zhi = ~hhi & bhi;
-            nlo = 0; nhi = 0;
-        }
+        if (eobrun > 0) { br->advance_long(__builtin_popcountll(h)); eobrun--; }
+        nzout[blk] = newm;
+        if (br->overrun()) return kEFormat;
     }
     return kOk;
 }

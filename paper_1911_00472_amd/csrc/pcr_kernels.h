@@ -327,68 +327,96 @@ __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const Refine
 //   k > 0: replay the AC scans of the component in file order: first scans only extend the
 //          non-zero mask, refinement scans add a correction bit or place a new +-2^Al.
 // --------------------------------------------------------------------------------------
-PCR_D int16_t refine_coefficient(const DevRecord& R, uint32_t i, const ImgDesc* img, int c, uint32_t row, uint32_t col, int k,
-                                 int16_t v, uint32_t upto) {
-    const uint32_t bw = img->bw[c];
-    const size_t blk = (size_t)row * bw + col;
-    const size_t plane = (size_t)bw * img->bh[c];
-    const bool covered = row < img->ch[c] && col < img->cw[c];
-    uint64_t h = 0;
-    for (uint32_t g = 0; g < upto; g++) {
-        const size_t ig = (size_t)i * R.G + g;
+struct ApplyUnit { uint32_t img; uint32_t comp; };
+
+// k_apply_prep gathers, once per (image, component), the scans that matter for refinement (AC
+// scans of the component in file order, DC refinement scans) into a compact list; k_apply then
+// runs one lane per coefficient, a workgroup covering kApplyChunk consecutive coefficients.
+struct ApplyScan { uint64_t mask_off; uint32_t slot; uint32_t data_base; uint32_t mcu_w; uint16_t ri; uint8_t Ss, Se, Ah, Al, ns, before, bpm, pad[3]; };
+constexpr int kApplyMaxScans = 16;
+struct ApplyList { uint32_t n; uint32_t pad; ApplyScan sc[kApplyMaxScans]; };
+constexpr uint32_t kApplyChunk = 4096;
+
+__global__ void __launch_bounds__(64) k_apply_prep(DevRecord R, const ApplyUnit* __restrict__ au, uint32_t nau, uint32_t kmax, ApplyList* lists) {
+    const uint32_t u = blockIdx.x * 64 + threadIdx.x;
+    if (u >= nau) return;
+    const ApplyUnit a = au[u];
+    const ImgDesc* img = &R.img[a.img];
+    const int c = a.comp;
+    ApplyList* L = &lists[u];
+    uint32_t n = 0;
+    const uint32_t upto = img->nscans < kmax ? img->nscans : kmax;
+    for (uint32_t g = 0; g < upto && n < kApplyMaxScans; g++) {
+        const size_t ig = (size_t)a.img * R.G + g;
         const ScanDesc* sd = &R.scan[ig];
+        ApplyScan e;
+        e.Ss = sd->Ss; e.Se = sd->Se; e.Ah = sd->Ah; e.Al = sd->Al; e.ns = sd->ns; e.ri = sd->ri; e.mcu_w = sd->mcu_w;
+        e.mask_off = R.mask_off[ig]; e.slot = R.slot_base[ig]; e.data_base = clean_base(sd->data_off);
+        e.before = 0; e.bpm = 0; e.pad[0] = e.pad[1] = e.pad[2] = 0;
         if (sd->Ss == 0) {
-            if (k != 0 || sd->Ah == 0) continue;
-            // position of this block in the scan's bit string
+            if (sd->Ah == 0) continue;
             int j = -1; uint32_t before = 0, bpm = 0;
             for (int q = 0; q < sd->ns; q++) {
                 const int cq = sd->comp[q];
-                const uint32_t nb = sd->ns > 1 ? (uint32_t)img->hs[cq] * img->vs[cq] : 1;
                 if (cq == c) { j = q; before = bpm; }
-                bpm += nb;
+                bpm += sd->ns > 1 ? (uint32_t)img->hs[cq] * img->vs[cq] : 1;
             }
             if (j < 0) continue;
-            uint32_t m, within;
-            if (sd->ns > 1) {
-                const uint32_t hs = img->hs[c], vs = img->vs[c];
-                m = (row / vs) * sd->mcu_w + col / hs;
-                within = before + (row % vs) * hs + col % hs;
-            } else {
-                if (!covered) continue;
-                m = row * sd->mcu_w + col; within = 0;
-            }
-            const uint32_t ivl = sd->ri ? m / sd->ri : 0;
-            const uint32_t bit = (m - ivl * sd->ri) * bpm + within;
-            const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + clean_base(sd->data_off));
-            if (dc_refine_bit(words, R.ivl_start[R.slot_base[ig] + ivl], bit)) v |= (int16_t)(1 << sd->Al);
-        } else if (k != 0 && covered && sd->comp[0] == c) {
-            const uint64_t* mk = R.masks + R.mask_off[ig];
-            const uint64_t nz = mk[blk];
-            if (sd->Ah != 0 && k >= sd->Ss && k <= sd->Se)
-                v = refine_apply(v, k, h & band_mask(sd->Ss, sd->Se), nz, mk[plane + blk], mk[2 * plane + blk], sd->Al);
-            h |= nz;
-        }
+            e.before = (uint8_t)before; e.bpm = (uint8_t)bpm;
+        } else if (sd->comp[0] != c) continue;
+        L->sc[n++] = e;
     }
-    return v;
+    L->n = n;
 }
 
-struct ApplyUnit { uint32_t img; uint32_t comp; };
-
-__global__ void __launch_bounds__(256) k_apply(DevRecord R, const ApplyUnit* au, uint32_t kmax) {
+__global__ void __launch_bounds__(256) k_apply(DevRecord R, const ApplyUnit* __restrict__ au, const ApplyList* __restrict__ lists) {
+    __shared__ ApplyList L;
     const ApplyUnit a = au[blockIdx.y];
     const ImgDesc* img = &R.img[a.img];
     if (R.status[a.img] != kOk) return;
     const int c = a.comp;
     const uint32_t bw = img->bw[c], nblk = bw * img->bh[c];
-    const uint32_t idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= nblk * 64) return;
-    const uint32_t b = idx >> 6;
+    const uint32_t first = blockIdx.x * kApplyChunk;
+    if (first >= nblk * 64) return;
+    {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&lists[blockIdx.y]);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&L);
+        for (uint32_t e = threadIdx.x; e < sizeof(ApplyList) / 4; e += 256) dst[e] = src[e];
+    }
+    __syncthreads();
+    const uint32_t n = L.n;
+    const uint32_t cw = img->cw[c], ch = img->ch[c], hs = img->hs[c], vs = img->vs[c];
+    const size_t plane = nblk;
     int16_t* pl = R.coef + R.coef_off[a.img];
     for (int q = 0; q < c; q++) pl += (size_t)img->bw[q] * img->bh[q] * 64;
-    const uint32_t upto = img->nscans < kmax ? img->nscans : kmax;
-    const int16_t v0 = pl[idx];
-    const int16_t v = refine_coefficient(R, a.img, img, c, b / bw, b % bw, (int)(idx & 63), v0, upto);   // element k = zig-zag position k
-    if (v != v0) pl[idx] = v;
+    for (uint32_t idx = first + threadIdx.x; idx < first + kApplyChunk && idx < nblk * 64; idx += 256) {
+        const uint32_t b = idx >> 6; const int k = (int)(idx & 63);  // element k of a block = zig-zag position k
+        const uint32_t row = b / bw, col = b % bw;
+        const bool covered = row < ch && col < cw;
+        const int16_t v0 = pl[idx];
+        int16_t v = v0;
+        uint64_t h = 0;
+        for (uint32_t e = 0; e < n; e++) {
+            const ApplyScan& S = L.sc[e];
+            if (S.Ss == 0) {
+                if (k != 0) continue;
+                uint32_t m, within;
+                if (S.ns > 1) { m = (row / vs) * S.mcu_w + col / hs; within = S.before + (row % vs) * hs + col % hs; }
+                else { if (!covered) continue; m = row * S.mcu_w + col; within = 0; }
+                const uint32_t ivl = S.ri ? m / S.ri : 0;
+                const uint32_t bit = (m - ivl * S.ri) * S.bpm + within;
+                const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + S.data_base);
+                if (dc_refine_bit(words, R.ivl_start[S.slot + ivl], bit)) v |= (int16_t)(1 << S.Al);
+            } else if (k != 0 && covered) {
+                const uint64_t* mk = R.masks + S.mask_off;
+                const uint64_t nz = mk[b];
+                if (S.Ah != 0 && k >= S.Ss && k <= S.Se)
+                    v = refine_apply(v, k, h & band_mask(S.Ss, S.Se), nz, mk[plane + b], mk[2 * plane + b], S.Al);
+                h |= nz;
+            }
+        }
+        if (v != v0) pl[idx] = v;
+    }
 }
 
 // Parity hook: internal planes (zig-zag order inside each block) -> natural order.

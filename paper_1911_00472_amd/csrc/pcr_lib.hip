@@ -27,7 +27,7 @@ struct LevelList {
 
 struct Plan {                               // launch geometry for one scan group k
     std::vector<LevelList> levels;
-    ApplyUnit* d_apply = nullptr; uint32_t n_apply = 0, apply_grid_x = 0;
+    ApplyUnit* d_apply = nullptr; ApplyList* d_apply_lists = nullptr; uint32_t n_apply = 0, apply_grid_x = 0;
 };
 
 template <class T> int dev_alloc(T** p, size_t count) {
@@ -134,8 +134,11 @@ int build_plan(pcr_record* r, int k, Plan** out) {
         plan.levels.push_back(ll);
     }
     plan.n_apply = (uint32_t)apply.size();
-    plan.apply_grid_x = (max_blk * 64 + 255) / 256;
-    if (plan.n_apply) { int rc = dev_upload(&plan.d_apply, apply); if (rc) return rc; }
+    plan.apply_grid_x = (max_blk * 64 + kApplyChunk - 1) / kApplyChunk;
+    if (plan.n_apply) {
+        int rc = dev_upload(&plan.d_apply, apply); if (rc) return rc;
+        rc = dev_alloc(&plan.d_apply_lists, apply.size()); if (rc) return rc;
+    }
     auto ins = r->plans.emplace(k, plan);
     *out = &ins.first->second;
     return PCR_OK;
@@ -145,6 +148,7 @@ void free_plans(pcr_record* r) {
     for (auto& kv : r->plans) {
         for (auto& l : kv.second.levels) { if (l.d_units) (void)hipFree(l.d_units); if (l.d_refine) (void)hipFree(l.d_refine); }
         if (kv.second.d_apply) (void)hipFree(kv.second.d_apply);
+        if (kv.second.d_apply_lists) (void)hipFree(kv.second.d_apply_lists);
     }
     r->plans.clear();
 }
@@ -182,7 +186,10 @@ int run_entropy_stages(pcr_record* r, int k, hipStream_t s) {
         }
     }
     stamp(r, 3, s);
-    if (plan->n_apply) hipLaunchKernelGGL(k_apply, dim3(plan->apply_grid_x, plan->n_apply), dim3(256), 0, s, r->d, plan->d_apply, (uint32_t)k);
+    if (plan->n_apply) {
+        hipLaunchKernelGGL(k_apply_prep, dim3((plan->n_apply + 63) / 64), dim3(64), 0, s, r->d, plan->d_apply, plan->n_apply, (uint32_t)k, plan->d_apply_lists);
+        hipLaunchKernelGGL(k_apply, dim3(plan->apply_grid_x, plan->n_apply), dim3(256), 0, s, r->d, plan->d_apply, plan->d_apply_lists);
+    }
     stamp(r, 4, s);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
     return PCR_OK;
