@@ -7,10 +7,11 @@
 // Input is the *unstuffed* entropy-coded data of the unit (FF 00 -> FF, restart markers
 // removed); consuming a bit past the unit's end is a data error, never a guess.
 //
-// Shape of the decoders: every lane of a wavefront decodes a different stream, so the loops
-// are FLAT -- one Huffman symbol per iteration, with the end-of-block bookkeeping predicated
-// inside the same iteration -- which keeps lanes that are in different blocks converged.
-// All per-scan parameters live in registers (LaneScan); tables live in LDS, one per lane.
+// Shape of the decoders: ONE WAVEFRONT DECODES ONE UNIT.  Every value below is then the same in
+// all 64 lanes, so the compiler keeps it in scalar registers and the loops run on the scalar
+// ALU (native 64-bit shifts, population count, find-first-set), paying only for the branch
+// actually taken.  All per-scan parameters are passed in registers (LaneScan); the Huffman
+// table lives in LDS.
 //
 // AC refinement is decoded against a 64-bit "already non-zero" mask per block (zig-zag bit
 // order) instead of against the coefficients: the serial decoder only finds where new
