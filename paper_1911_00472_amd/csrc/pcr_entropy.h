@@ -209,6 +209,90 @@ PCR_HD uint32_t dc_code(const DcTab* t, uint32_t win) {
 
 PCR_HD int extend(uint32_t v, int s) { return (s && v < (1u << (s - 1))) ? (int)v - (1 << s) + 1 : (int)v; }
 
+// ---------------------------------------------------------------------------------------
+// Window reader for the AC scans: the 64 lanes of the wavefront look up, in parallel, the
+// Huffman code that WOULD start at each of the next 64 bit offsets of the stream (which code
+// starts where does not depend on the decoder's state), and pack what follows from it --
+// symbol, total length with its appended bits, the appended value -- into one word per lane.
+// The serial part of the decoder then only follows the chain of offsets, fetching the word of
+// the offset it stands on with one cross-lane read (readlane), instead of doing a table look-up,
+// field extraction, sign extension and bit-buffer refill per symbol on the scalar ALU.
+// Codes longer than 8 bits are left unresolved (word 0) and decoded on the spot if the chain
+// really lands on them.  The window is 96 bits of stream (w0,w1,w2): offsets 0..63 each with
+// 32 bits of look-ahead; two more words are always already loaded.
+//
+// packed word: value (16 bits, signed) << 16 | total bits (6) << 8 | run (4) << 4 | size (4)
+// ---------------------------------------------------------------------------------------
+PCR_HD uint32_t bits_at(uint32_t w0, uint32_t w1, uint32_t w2, int j) {      // 32 bits from offset j (0..63)
+    const uint32_t hi = j < 32 ? w0 : w1, lo = j < 32 ? w1 : w2;
+    return (uint32_t)((((((uint64_t)hi) << 32) | lo) << (j & 31)) >> 32);
+}
+
+// e: table entry (length << 8 | symbol), non-zero.  first: AC first scan (size s = s value bits,
+// sign-extended here); otherwise refinement (size 1 = one sign bit).  An end-of-band symbol
+// (size 0, run r < 15) is followed by r bits of run length in both.
+PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
+    const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
+    const int nx = s ? (first ? s : 1) : (r != 15 ? r : 0);
+    const uint32_t extra = field(win, len, nx);
+    const int value = (first && s) ? extend(extra, s) : (int)extra;
+    return ((uint32_t)(value & 0xFFFF) << 16) | ((uint32_t)(len + nx) << 8) | ((uint32_t)r << 4) | (uint32_t)s;
+}
+
+struct WindowReader {
+    const uint32_t* p;          // words after n1
+    const AcTab* tab;
+    uint32_t w0, w1, w2, n0, n1;
+    uint32_t o;                 // offset of the next unread bit inside the window (may run past 63 until normalised)
+    uint32_t wbase;             // bits of the stream before the window
+    uint32_t mis_bits, total_bits;
+    uint32_t lane;              // this lane's offset (device); unused on the host
+    uint32_t vinfo;             // this lane's packed word (device)
+    bool first;
+
+    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const AcTab* t, bool first_scan, uint32_t lane_id) {
+        tab = t; first = first_scan; lane = lane_id;
+        mis_bits = (byte_off & 3) * 8;
+        p = words + (byte_off >> 2);
+        w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
+        o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits;
+        fill();
+    }
+    PCR_HD void fill() {
+#if defined(__HIP_DEVICE_COMPILE__)
+        const uint32_t win = bits_at(w0, w1, w2, (int)lane);
+        const uint32_t e = tab->lut[win >> 24];
+        vinfo = e ? pack_symbol(e, win, first) : 0;
+#endif
+    }
+    PCR_HD uint32_t lookup(uint32_t off) const {
+#if defined(__HIP_DEVICE_COMPILE__)
+        return (uint32_t)__builtin_amdgcn_readlane((int)vinfo, (int)off);
+#else
+        const uint32_t win = bits_at(w0, w1, w2, (int)off);
+        const uint32_t e = tab->lut[win >> 24];
+        return e ? pack_symbol(e, win, first) : 0;
+#endif
+    }
+    // packed word of the symbol at the current position; 0 if the bits there are no code
+    PCR_HD uint32_t symbol() {
+        if (o >= 64) {
+            do { w0 = w2; w1 = n0; w2 = n1; n0 = p[0]; n1 = p[1]; p += 2; o -= 64; wbase += 64; } while (o >= 64);
+            fill();
+        }
+        uint32_t info = lookup(o);
+        if (__builtin_expect(info == 0, 0)) {                // a code longer than 8 bits, or garbage
+            const uint32_t win = bits_at(w0, w1, w2, (int)o);
+            const uint32_t e = ac_long_code(tab, win);
+            info = e ? pack_symbol(e, win, first) : 0;
+        }
+        return info;
+    }
+    PCR_HD void consume(uint32_t n) { o += n; }
+    PCR_HD uint32_t position() const { return wbase + o - mis_bits; }       // bits consumed since the unit's first bit
+    PCR_HD bool overrun() const { return wbase + o > total_bits; }
+};
+
 // Per-lane parameters of the unit being decoded (all in registers).
 struct LaneScan {
     uint32_t mcu0, mcu1;        // MCU range [mcu0, mcu1) of the scan handled by this unit
@@ -258,11 +342,15 @@ PCR_HD int decode_dc_first(BitReader* br, const LaneScan& ls, const DcTab* tab0,
 // per block, the mask of positions it made non-zero.  Blocks skipped by an end-of-band run are
 // not touched: coefficients and nzout must be zero-filled beforehand.
 // ---------------------------------------------------------------------------------------
-PCR_HD int decode_ac_first(BitReader* br, const LaneScan& ls, const AcTab* tab, int16_t* coef, uint64_t* nzout) {
+// (Control flow is kept structured -- loop conditions and flags instead of returns and breaks
+// inside the loops -- because the compiler turns early exits from nested loops into a state
+// variable that is tested after every symbol.)
+PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, int16_t* coef, uint64_t* nzout) {
     const int Ss = ls.Ss, Se = ls.Se, Al = ls.Al;
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     uint32_t m = ls.mcu0;
     uint32_t row = m / mcu_w, col = m % mcu_w;
+    uint32_t bad = 0;
     while (m < ls.mcu1) {
         const size_t blk = (size_t)row * bw + col;
         int16_t* cb = coef + blk * 64;
@@ -270,35 +358,31 @@ PCR_HD int decode_ac_first(BitReader* br, const LaneScan& ls, const AcTab* tab, 
         uint32_t skip = 1;                                   // blocks to move on by: this one + an end-of-band run
         int k = Ss;
         while (k <= Se) {
-            const uint32_t win = br->window();
-            const uint32_t e = ac_code(tab, win);
-            const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
-            if (__builtin_expect(s != 0, 1)) {               // a coefficient: run r, then s value bits
-                const uint32_t bits = (win << len) >> (32 - s);
-                br->advance(len + s);
+            const uint32_t info = wr->symbol();
+            const int s = (int)(info & 15), r = (int)((info >> 4) & 15);
+            wr->consume((info >> 8) & 63);
+            if (__builtin_expect(s != 0, 1)) {               // a coefficient: run r, then the value
                 k += r;
-                if (k > Se) return kEFormat;
-                const int v = (int)bits + ((bits >> (s - 1)) ? 0 : 1 - (1 << s));
-                cb[k] = (int16_t)(v * (1 << Al));
-                mask |= 1ull << k;
+                const int kk = k <= Se ? k : Se;             // a run past the band is an error; stay in bounds
+                bad |= (uint32_t)(k > Se);
+                cb[kk] = (int16_t)(((int32_t)info >> 16) * (1 << Al));
+                mask |= 1ull << kk;
                 k++;
-            } else if (r == 15) {                            // sixteen zeros
-                br->advance(len);
-                k += 16;
-            } else {                                         // end of band, run of 2^r + extra blocks
-                if (!e) return kEFormat;
-                skip = (1u << r) + field(win, len, r);
-                br->advance(len + r);
-                break;
+            } else if (r == 15) k += 16;                     // sixteen zeros
+            else {                                           // end of band, run of 2^r + extra blocks (or no code at all)
+                bad |= (uint32_t)(info == 0);
+                skip = (1u << r) + (info >> 16);
+                k = 64;
             }
         }
         nzout[blk] = mask;
-        if (br->overrun()) return kEFormat;
+        bad |= (uint32_t)wr->overrun();
         if (skip > ls.mcu1 - m) skip = ls.mcu1 - m;
+        if (bad) skip = ls.mcu1 - m;                         // stop at the first damaged block
         m += skip; col += skip;
         if (col >= mcu_w) { row += col / mcu_w; col %= mcu_w; }
     }
-    return kOk;
+    return bad ? kEFormat : kOk;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -344,53 +428,51 @@ PCR_HD uint64_t hist_at(const HistPlanes& hp, size_t blk) {
 //   start  bit offset of the block inside the unit (low 32 bits) and the end-of-band run still
 //          pending when the block starts (high 32 bits).
 // Masks are kept as 32-bit halves: the lanes' ALUs are 32 bits wide.
-PCR_HD int skim_ac_refine(BitReader* br, const LaneScan& ls, const AcTab* tab, const HistPlanes& hp,
-                          uint64_t* nzout, uint64_t* start) {
+PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes& hp, uint64_t* nzout, uint64_t* start) {
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     const uint64_t band = band_mask(ls.Ss, ls.Se);
     uint32_t m = ls.mcu0;
-    if (m >= ls.mcu1) return kOk;
     uint32_t row = m / mcu_w, col = m % mcu_w;
-    const int64_t left0 = br->unread_bits();
     uint32_t eobrun = 0;                                     // blocks still covered by an end-of-band run
-    for (; m < ls.mcu1; m++) {
+    uint32_t bad = 0;
+    while (m < ls.mcu1) {
         const size_t blk = (size_t)row * bw + col;
         if (++col == mcu_w) { col = 0; row++; }
-        start[blk] = ((uint64_t)eobrun << 32) | (uint32_t)(left0 - br->unread_bits());
+        start[blk] = ((uint64_t)eobrun << 32) | wr->position();
         uint64_t h = hist_at(hp, blk) & band;                // already non-zero, not yet passed
         uint64_t z = ~h & band;                              // still zero, not yet passed
         uint64_t newm = 0;
-        if (eobrun == 0) {
-            while (z | h) {
-                const uint32_t win = br->window();
-                const uint32_t e = ac_code(tab, win);
-                const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
-                if (__builtin_expect(s == 1, 1)) {           // a new +-1: pass r zeros, take the next one
-                    for (int q = 0; q < r; q++) z &= z - 1;
-                    if (!z) return kEFormat;                 // no place left for it
-                    const uint64_t bit = z & (0 - z);
-                    const uint64_t below = bit - 1;
-                    br->advance_long(len + 1 + __builtin_popcountll(h & below));   // code, sign, corrections passed
-                    h &= ~below; z &= ~bit; newm |= bit;
-                } else if (s == 0 && r == 15) {              // sixteen zeros (or to the end of the band)
-                    for (int q = 0; q < 15; q++) z &= z - 1;
-                    const uint64_t bit = z & (0 - z);
-                    const uint64_t below = bit ? bit - 1 : ~0ull;
-                    br->advance_long(len + __builtin_popcountll(h & below));
-                    h &= ~below; z &= ~bit;
-                } else {                                     // end of band (run): the rest is corrections
-                    if (!e || s > 1) return kEFormat;
-                    eobrun = (1u << r) + field(win, len, r);
-                    br->advance(len + r);
-                    break;
-                }
+        uint32_t open = eobrun == 0;                         // symbols are read only outside an end-of-band run
+        while (open && (z | h)) {
+            const uint32_t info = wr->symbol();
+            const int s = (int)(info & 15), r = (int)((info >> 4) & 15);
+            uint32_t tot = (info >> 8) & 63;
+            if (__builtin_expect(s == 1, 1)) {               // a new +-1: pass r zeros, take the next one
+                for (int q = 0; q < r; q++) z &= z - 1;
+                bad |= (uint32_t)(z == 0);                   // no place left for it
+                const uint64_t bit = z & (0 - z);
+                const uint64_t below = bit - 1;              // (z == 0: everything; the unit is abandoned anyway)
+                tot += (uint32_t)__builtin_popcountll(h & below);                   // code, sign, corrections passed
+                h &= ~below; z &= ~bit; newm |= bit;
+            } else if ((s == 0) & (r == 15)) {               // sixteen zeros (or to the end of the band)
+                for (int q = 0; q < 15; q++) z &= z - 1;
+                const uint64_t bit = z & (0 - z);
+                const uint64_t below = bit - 1;              // z == 0: all ones
+                tot += (uint32_t)__builtin_popcountll(h & below);
+                h &= ~below; z &= ~bit;
+            } else {                                         // end of band (run): the rest is corrections
+                bad |= (uint32_t)((info == 0) | (s > 1));
+                eobrun = (1u << r) + (info >> 16);
+                open = 0;
             }
+            wr->consume(tot);
         }
-        if (eobrun > 0) { br->advance_long(__builtin_popcountll(h)); eobrun--; }
+        if (eobrun > 0) { wr->consume((uint32_t)__builtin_popcountll(h)); eobrun--; }
         nzout[blk] = newm;
-        if (br->overrun()) return kEFormat;
+        bad |= (uint32_t)wr->overrun();
+        m = bad ? ls.mcu1 : m + 1;                           // stop at the first damaged block
     }
-    return kOk;
+    return bad ? kEFormat : kOk;
 }
 
 // Phase 2 (data-parallel, one lane per block): decode one block completely from its start.

@@ -188,7 +188,9 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kmax) {
 constexpr int kEntropyLanes = 64;
 
 struct UnitSetup {
-    BitReader br;
+    BitReader br;                 // DC scans
+    const uint32_t* words;        // AC scans: segment base, unit start and length for the window reader
+    uint32_t byte_off, nbytes;
     LaneScan ls;
     int16_t* plane[kMaxComp];     // planes of the scan's components
     bool ok;
@@ -220,7 +222,9 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, UnitSetup* L) {
         ls.hs[j] = uni((uint32_t)img->hs[c]); ls.vs[j] = uni((uint32_t)img->vs[c]); ls.bw[j] = uni((uint32_t)img->bw[c]);
         L->plane[j] = base + (c == 0 ? poff[0] : (c == 1 ? poff[1] : poff[2]));
     }
-    L->br.init(reinterpret_cast<const uint32_t*>(R.clean + uni(clean_base(sd->data_off))), uni(b0), uni(b1 > b0 ? b1 - b0 : 0));
+    L->words = reinterpret_cast<const uint32_t*>(R.clean + uni(clean_base(sd->data_off)));
+    L->byte_off = uni(b0); L->nbytes = uni(b1 > b0 ? b1 - b0 : 0);
+    if (ls.Ss == 0) L->br.init(L->words, L->byte_off, L->nbytes);
     L->ok = true;
 }
 
@@ -253,7 +257,9 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     const size_t ig = (size_t)un.img * R.G + un.scan;
     if (threadIdx.x == 0) actab_build(&tab, R.rec + R.scan[ig].ac_off);
     __syncthreads();
-    int rc = decode_ac_first(&L.br, L.ls, &tab, L.plane[0], R.masks + uni((uint64_t)R.mask_off[ig]));
+    WindowReader wr;
+    wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x);
+    int rc = decode_ac_first(&wr, L.ls, L.plane[0], R.masks + uni((uint64_t)R.mask_off[ig]));
     if (rc != kOk) R.status[un.img] = rc;
 }
 
@@ -281,7 +287,9 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     const int c = sd->comp[0];
     const size_t plane = (size_t)uni((uint32_t)img->bw[c]) * uni((uint32_t)img->bh[c]);
     uint64_t* mk = R.masks + uni((uint64_t)R.mask_off[ig]);
-    int rc = skim_ac_refine(&L.br, L.ls, &tab, hp, mk, mk + 3 * plane);
+    WindowReader wr;
+    wr.init(L.words, L.byte_off, L.nbytes, &tab, false, threadIdx.x);
+    int rc = skim_ac_refine(&wr, L.ls, hp, mk, mk + 3 * plane);
     if (rc != kOk) R.status[un.img] = rc;
 }
 

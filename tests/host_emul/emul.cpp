@@ -85,11 +85,12 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 rc = decode_dc_first(&br, ls, &dt[0], &dt[1], &dt[2], cpl[0], cpl[1], cpl[2]);
             } else {
                 AcTab at; actab_build(&at, rec + sd.ac_off);
-                if (sd.Ah == 0) rc = decode_ac_first(&br, ls, &at, cpl[0], masks[g].data());
+                WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &at, sd.Ah == 0, 0);
+                if (sd.Ah == 0) rc = decode_ac_first(&wr, ls, cpl[0], masks[g].data());
                 else {
                     HistPlanes hp; hp.n = sd.nhist;
                     for (int q = 0; q < kMaxHist; q++) hp.p[q] = masks[q < sd.nhist ? sd.hist[q] : 0].data();
-                    rc = skim_ac_refine(&br, ls, &at, hp, masks[g].data(), masks[g].data() + 3 * plane);
+                    rc = skim_ac_refine(&wr, ls, hp, masks[g].data(), masks[g].data() + 3 * plane);
                     if (rc) return rc;
                     // phase 2: every block of this interval on its own
                     for (uint32_t mm = ls.mcu0; mm < ls.mcu1; mm++) {
