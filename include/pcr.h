@@ -61,6 +61,18 @@ enum {
  */
 int pcr_open(const void* bytes, size_t nbytes, int device_id, pcr_record** out);
 
+/*
+ * Open a record whose bytes are already in device memory (for loaders that stream record prefixes
+ * to the GPU themselves; paper Section 3, "Loader": whole-record buffers that are re-used).
+ *   d_bytes, nbytes  device pointer (16-byte aligned) to the record or a prefix of it.  The bytes are
+ *                    BORROWED: they must stay valid and unchanged until pcr_close.
+ *   hip_stream       stream the open-time kernels and copies run on; the call synchronises it.
+ * The index and the JPEG marker segments are parsed on the device; only the metadata block and the
+ * small per-image descriptor tables are copied back to size the buffers.  The device is the one
+ * that owns d_bytes.
+ */
+int pcr_open_device(const void* d_bytes, size_t nbytes, void* hip_stream, pcr_record** out);
+
 /* Release a handle and all device memory it owns.  NULL is allowed. */
 void pcr_close(pcr_record* rec);
 

@@ -19,6 +19,7 @@ _u8p = ctypes.POINTER(ctypes.c_uint8)
 _vp = ctypes.c_void_p
 SYMBOLS = {
     "pcr_open": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(_vp)]),
+    "pcr_open_device": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.POINTER(_vp)]),
     "pcr_close": (None, [_vp]),
     "pcr_num_images": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
     "pcr_num_scan_groups": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
@@ -70,12 +71,20 @@ def _check(rc, what):
 class Record:
     """One opened PCR record (pcr_open ... pcr_close)."""
 
-    def __init__(self, data, device=0):
+    def __init__(self, data, device=0, stream=None):
         self._h = _vp()
-        self._buf = np.frombuffer(data, np.uint8) if not isinstance(data, np.ndarray) else data
-        _check(lib().pcr_open(self._buf.ctypes.data_as(_vp), self._buf.size, device, ctypes.byref(self._h)), "pcr_open")
+        self._keep = None
+        if hasattr(data, "data_ptr"):                       # a CUDA uint8 tensor: bytes already on the device (borrowed)
+            import torch
+            assert data.is_cuda and data.dtype == torch.uint8 and data.is_contiguous()
+            device = data.device.index
+            s = torch.cuda.current_stream(device).cuda_stream if stream is None else stream
+            _check(lib().pcr_open_device(data.data_ptr(), data.numel(), s, ctypes.byref(self._h)), "pcr_open_device")
+            self._keep = data
+        else:
+            buf = np.frombuffer(data, np.uint8) if not isinstance(data, np.ndarray) else data
+            _check(lib().pcr_open(buf.ctypes.data_as(_vp), buf.size, device, ctypes.byref(self._h)), "pcr_open")
         self.device = device
-        self._buf = None
         v = ctypes.c_int()
         _check(lib().pcr_num_images(self._h, ctypes.byref(v)), "pcr_num_images"); self.n = v.value
         _check(lib().pcr_num_scan_groups(self._h, ctypes.byref(v)), "pcr_num_scan_groups"); self.G = v.value
@@ -85,6 +94,7 @@ class Record:
         if self._h:
             lib().pcr_close(self._h)
             self._h = _vp()
+            self._keep = None
 
     def __enter__(self):
         return self
@@ -163,4 +173,10 @@ class Record:
 
 
 def pcr_open(data, device=0):
+    """Open a record from host bytes (copied to the device)."""
     return Record(data, device)
+
+
+def pcr_open_device(tensor, stream=None):
+    """Open a record whose bytes are a CUDA uint8 tensor (borrowed until close)."""
+    return Record(tensor, stream=stream)

@@ -61,6 +61,7 @@ struct pcr_record {
     uint8_t* d_gather = nullptr; size_t gather_cap = 0;
     std::map<int, Plan> plans;
     bool timing = false;
+    bool borrowed = false;                  // record bytes belong to the caller (pcr_open_device)
     hipEvent_t ev[PCR_NUM_STAGES + 1] = {};
     bool ev_valid = false, ev_recorded = false;
 };
@@ -199,47 +200,36 @@ int run_entropy_stages(pcr_record* r, int k, hipStream_t s) {
 
 extern "C" {
 
-int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out) {
-    if (!bytes_ || !out) return PCR_E_ARG;
-    const uint8_t* bytes = (const uint8_t*)bytes_;
-    RecordHeader h;
-    int rc = parse_record_header(bytes, nbytes, &h);
-    if (rc) return rc;
-    if (nbytes >= (1ull << 32)) return PCR_E_UNSUPPORTED;
-    if (h.k_avail == 0) return PCR_E_TRUNCATED;
-    int ndev = 0;
-    if (hipGetDeviceCount(&ndev) != hipSuccess || device_id < 0 || device_id >= ndev) { (void)hipGetLastError(); return PCR_E_DEVICE; }
-    HIP_TRY(hipSetDevice(device_id));
-
-    pcr_record* r = new (std::nothrow) pcr_record();
-    if (!r) return PCR_E_NOMEM;
-    r->device = device_id; r->nbytes = nbytes; r->hdr = h;
+// Host-side validation of the metadata block: region lengths must tile every available group and
+// agree with the per-image scan counts.  hdr: host copy of the first header_bytes bytes.
+static int validate_index(const uint8_t* hdr, const RecordHeader& h, std::vector<uint32_t>* off, std::vector<uint32_t>* len, std::vector<uint32_t>* nsc) {
     const uint32_t n = h.n, G = h.G;
-    // ---- host index over the available groups (sizes buffers, validates tiling) ----
-    std::vector<uint32_t> off((size_t)G * n, 0), len((size_t)G * n, 0), nsc(n);
-    r->header.assign(bytes, bytes + h.header_bytes);
+    off->assign((size_t)G * n, 0); len->assign((size_t)G * n, 0); nsc->assign(n, 0);
     uint64_t start = h.header_bytes;
     for (uint32_t g = 0; g < h.k_avail; g++) {
         uint64_t pos = start;
         for (uint32_t i = 0; i < n; i++) {
-            uint32_t L = ld_le32(bytes + hdr_len_pos(n, G, g, i));
-            off[(size_t)g * n + i] = (uint32_t)pos; len[(size_t)g * n + i] = L; pos += L;
+            uint32_t L = ld_le32(hdr + hdr_len_pos(n, G, g, i));
+            (*off)[(size_t)g * n + i] = (uint32_t)pos; (*len)[(size_t)g * n + i] = L; pos += L;
         }
-        if (pos != ld_le64(bytes + hdr_group_end_pos(g))) { delete r; return PCR_E_FORMAT; }
+        if (pos != ld_le64(hdr + hdr_group_end_pos(g))) return PCR_E_FORMAT;
         start = pos;
     }
     for (uint32_t i = 0; i < n; i++) {
-        nsc[i] = ld_le32(bytes + hdr_nscans_pos(n, G, i));
-        if (nsc[i] == 0 || nsc[i] > G) { delete r; return PCR_E_FORMAT; }
+        (*nsc)[i] = ld_le32(hdr + hdr_nscans_pos(n, G, i));
+        if ((*nsc)[i] == 0 || (*nsc)[i] > G) return PCR_E_FORMAT;
         for (uint32_t g = 0; g < h.k_avail; g++)
-            if ((g < nsc[i]) != (len[(size_t)g * n + i] != 0)) { delete r; return PCR_E_FORMAT; }
+            if ((g < (*nsc)[i]) != ((*len)[(size_t)g * n + i] != 0)) return PCR_E_FORMAT;
     }
-    // ---- host marker parse of every image: layout, work sizes, early rejection ----
-    r->img.resize(n); r->scan.assign((size_t)n * G, ScanDesc{});
-    for (uint32_t i = 0; i < n; i++) {
-        parse_image(bytes, off.data(), len.data(), n, i, nsc[i], h.k_avail, &r->img[i], &r->scan[(size_t)i * G]);
-        if (r->img[i].status != kOk) { rc = r->img[i].status; delete r; return rc; }
-    }
+    return PCR_OK;
+}
+
+// Everything after the image/scan descriptors are known (r->img, r->scan filled, r->d.rec set):
+// dependency levels, buffer layout, remaining device allocations.
+static int finish_open(pcr_record* r) {
+    const uint32_t n = r->hdr.n, G = r->hdr.G;
+    const size_t nbytes = r->nbytes;
+    for (uint32_t i = 0; i < n; i++) if (r->img[i].status != kOk) return r->img[i].status;
     compute_levels(r);
     r->out_off.assign(n + 1, 0); r->coef_off.assign(n + 1, 0);
     r->mask_off.assign((size_t)n * G, 0); r->slot_base.assign((size_t)n * G, 0); r->slot_cnt.assign((size_t)n * G, 0);
@@ -267,22 +257,16 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
         for (uint32_t my = 0; my < d.mcuy; my++)
             for (uint32_t mx = 0; mx < d.mcux; mx += kStripMcus) tiles.push_back(PixelTile{i, (uint16_t)my, (uint16_t)mx});
     }
-    if (ns >= (1ull << 32)) { delete r; return PCR_E_UNSUPPORTED; }
+    if (ns >= (1ull << 32)) return PCR_E_UNSUPPORTED;
     r->n_masks = nm; r->n_slots = (uint32_t)ns; r->n_tiles = (uint32_t)tiles.size();
 
-    // ---- device buffers ----
     DevRecord& d = r->d;
-    rc = PCR_OK;
-    const size_t padded = nbytes + 1024;      // slack: bit readers look ahead, gathers round up
-    if (!rc) rc = dev_alloc(&r->d_rec, padded);
+    int rc = PCR_OK;
+    const size_t padded = nbytes + 1024;      // slack: bit readers look ahead
     if (!rc) rc = dev_alloc(&d.clean, padded);
-    if (!rc) rc = dev_alloc(&d.off, (size_t)G * n);
-    if (!rc) rc = dev_alloc(&d.img, n);
-    if (!rc) rc = dev_alloc(&d.scan, (size_t)n * G);
     if (!rc) rc = dev_alloc(&d.coef, r->coef_off[n]);
     if (!rc) rc = dev_alloc(&d.masks, nm + 2);
     if (!rc) rc = dev_alloc(&d.ivl_start, ns);
-    if (!rc) rc = dev_alloc(&d.status, n);
     uint64_t *d_coef_off = nullptr, *d_out_off = nullptr, *d_mask_off = nullptr; uint32_t *d_sb = nullptr, *d_sc = nullptr;
     if (!rc) rc = dev_upload(&d_coef_off, r->coef_off);
     if (!rc) rc = dev_upload(&d_out_off, r->out_off);
@@ -295,23 +279,114 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
     if (!rc) rc = dev_alloc(&d.tabs, (size_t)ntabs);
     d.tab_idx = d_tab_idx;
     d.coef_off = d_coef_off; d.out_off = d_out_off; d.mask_off = d_mask_off; d.slot_base = d_sb; d.slot_cnt = d_sc;
-    if (!rc && hipMemcpy(r->d_rec, bytes, nbytes, hipMemcpyHostToDevice) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc && hipMemset(r->d_rec + nbytes, 0, padded - nbytes) != hipSuccess) rc = PCR_E_DEVICE;
     if (!rc && hipMemset(d.clean, 0xFF, padded) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc && hipMemset(d.off, 0, (size_t)G * n * sizeof(uint32_t)) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc && hipMemset(d.scan, 0, (size_t)n * G * sizeof(ScanDesc)) != hipSuccess) rc = PCR_E_DEVICE;
     if (!rc && hipMemset(d.masks, 0, (nm ? nm : 1) * sizeof(uint64_t)) != hipSuccess) rc = PCR_E_DEVICE;
     if (!rc && hipMemset(d.ivl_start, 0, (ns ? ns : 1) * sizeof(uint32_t)) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc) {
-        d.rec = r->d_rec; d.n = n; d.G = G;
-        d.len = (const uint32_t*)(r->d_rec + hdr_len_pos(n, G, 0, 0));
-        d.nscans = (const uint32_t*)(r->d_rec + hdr_nscans_pos(n, G, 0));
-    }
     if (!rc) {
         bool ok = true;
         for (auto& e : r->ev) ok = ok && hipEventCreate(&e) == hipSuccess;
         r->ev_valid = ok;
     }
+    return rc;
+}
+
+// Buffers the index and parse kernels write; needed before the descriptors exist.
+static int alloc_descriptor_buffers(pcr_record* r) {
+    const uint32_t n = r->hdr.n, G = r->hdr.G;
+    DevRecord& d = r->d;
+    int rc = dev_alloc(&d.off, (size_t)G * n);
+    if (!rc) rc = dev_alloc(&d.img, n);
+    if (!rc) rc = dev_alloc(&d.scan, (size_t)n * G);
+    if (!rc) rc = dev_alloc(&d.status, n);
+    if (!rc && hipMemset(d.off, 0, (size_t)G * n * sizeof(uint32_t)) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemset(d.scan, 0, (size_t)n * G * sizeof(ScanDesc)) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemset(d.img, 0, (size_t)n * sizeof(ImgDesc)) != hipSuccess) rc = PCR_E_DEVICE;
+    d.n = n; d.G = G;
+    d.len = (const uint32_t*)(d.rec + hdr_len_pos(n, G, 0, 0));
+    d.nscans = (const uint32_t*)(d.rec + hdr_nscans_pos(n, G, 0));
+    return rc;
+}
+
+int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out) {
+    if (!bytes_ || !out) return PCR_E_ARG;
+    const uint8_t* bytes = (const uint8_t*)bytes_;
+    RecordHeader h;
+    int rc = parse_record_header(bytes, nbytes, &h);
+    if (rc) return rc;
+    if (nbytes >= (1ull << 32)) return PCR_E_UNSUPPORTED;
+    if (h.k_avail == 0) return PCR_E_TRUNCATED;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device_id < 0 || device_id >= ndev) { (void)hipGetLastError(); return PCR_E_DEVICE; }
+    HIP_TRY(hipSetDevice(device_id));
+
+    pcr_record* r = new (std::nothrow) pcr_record();
+    if (!r) return PCR_E_NOMEM;
+    r->device = device_id; r->nbytes = nbytes; r->hdr = h;
+    const uint32_t n = h.n, G = h.G;
+    r->header.assign(bytes, bytes + h.header_bytes);
+    std::vector<uint32_t> off, len, nsc;
+    rc = validate_index(r->header.data(), h, &off, &len, &nsc);
+    // host marker parse of every image: layout, work sizes, early rejection
+    if (!rc) {
+        r->img.resize(n); r->scan.assign((size_t)n * G, ScanDesc{});
+        for (uint32_t i = 0; i < n && !rc; i++) {
+            parse_image(bytes, off.data(), len.data(), n, i, nsc[i], h.k_avail, &r->img[i], &r->scan[(size_t)i * G]);
+            rc = r->img[i].status;
+        }
+    }
+    if (!rc) rc = dev_alloc(&r->d_rec, nbytes + 64);
+    if (!rc && hipMemcpy(r->d_rec, bytes, nbytes, hipMemcpyHostToDevice) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemset(r->d_rec + nbytes, 0, 64) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc) { r->d.rec = r->d_rec; rc = alloc_descriptor_buffers(r); }
+    if (!rc) rc = finish_open(r);
+    if (rc) { (void)hipGetLastError(); pcr_close(r); return rc; }
+    *out = r;
+    return PCR_OK;
+}
+
+int pcr_open_device(const void* d_bytes, size_t nbytes, void* stream, pcr_record** out) {
+    if (!d_bytes || !out) return PCR_E_ARG;
+    if (((uintptr_t)d_bytes & 15) != 0) return PCR_E_ARG;              // header tables are read as aligned words
+    if (nbytes < 24) return PCR_E_TRUNCATED;
+    if (nbytes >= (1ull << 32)) return PCR_E_UNSUPPORTED;
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, d_bytes) != hipSuccess) { (void)hipGetLastError(); return PCR_E_ARG; }
+    if (attr.type != hipMemoryTypeDevice) return PCR_E_ARG;
+    HIP_TRY(hipSetDevice(attr.device));
+    hipStream_t s = (hipStream_t)stream;
+    // fixed part of the header, then the whole metadata block
+    uint8_t fixed[24];
+    HIP_TRY(hipMemcpyAsync(fixed, d_bytes, 24, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (fixed[0] != 'P' || fixed[1] != 'C' || fixed[2] != 'R' || fixed[3] != '1') return PCR_E_FORMAT;
+    const uint64_t header_bytes = ld_le64(fixed + 16);
+    if (header_bytes < 24 || header_bytes > (1ull << 31)) return PCR_E_FORMAT;
+    if (header_bytes > nbytes) return PCR_E_TRUNCATED;
+    pcr_record* r = new (std::nothrow) pcr_record();
+    if (!r) return PCR_E_NOMEM;
+    r->header.resize(header_bytes);
+    if (hipMemcpyAsync(r->header.data(), d_bytes, header_bytes, hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) {
+        (void)hipGetLastError(); delete r; return PCR_E_DEVICE;
+    }
+    RecordHeader h;
+    int rc = parse_record_header(r->header.data(), nbytes, &h);
+    if (!rc && h.k_avail == 0) rc = PCR_E_TRUNCATED;
+    if (rc) { delete r; return rc; }
+    r->device = attr.device; r->nbytes = nbytes; r->hdr = h; r->borrowed = true;
+    const uint32_t n = h.n, G = h.G;
+    std::vector<uint32_t> off, len, nsc;
+    rc = validate_index(r->header.data(), h, &off, &len, &nsc);
+    // index and marker parse ON THE DEVICE; only the small descriptor tables come back
+    if (!rc) { r->d.rec = (const uint8_t*)d_bytes; rc = alloc_descriptor_buffers(r); }
+    if (!rc) {
+        hipLaunchKernelGGL(k_index, dim3(h.k_avail), dim3(256), 0, s, r->d, h.k_avail);
+        hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, h.k_avail);
+        r->img.resize(n); r->scan.resize((size_t)n * G);
+        if (hipMemcpyAsync(r->img.data(), r->d.img, n * sizeof(ImgDesc), hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipMemcpyAsync(r->scan.data(), r->d.scan, (size_t)n * G * sizeof(ScanDesc), hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess) rc = PCR_E_DEVICE;
+    }
+    if (!rc) rc = finish_open(r);
     if (rc) { (void)hipGetLastError(); pcr_close(r); return rc; }
     *out = r;
     return PCR_OK;
@@ -323,7 +398,7 @@ void pcr_close(pcr_record* r) {
     (void)hipDeviceSynchronize();
     free_plans(r);
     DevRecord& d = r->d;
-    void* ptrs[] = { r->d_rec, d.clean, d.off, d.img, d.scan, d.coef, d.masks, d.ivl_start, d.status, (void*)d.coef_off, (void*)d.out_off,
+    void* ptrs[] = { r->borrowed ? nullptr : r->d_rec, d.clean, d.off, d.img, d.scan, d.coef, d.masks, d.ivl_start, d.status, (void*)d.coef_off, (void*)d.out_off,
                      (void*)d.mask_off, (void*)d.slot_base, (void*)d.slot_cnt, r->d_tiles, r->d_gather, d.tabs, (void*)d.tab_idx };
     for (void* p : ptrs) if (p) (void)hipFree(p);
     if (r->ev_valid) for (auto& e : r->ev) (void)hipEventDestroy(e);

@@ -182,3 +182,72 @@ def test_repeatable_bit_for_bit(rgb_small):
         b = r.decode_batch(4).cpu().numpy()
         c = r.decode_batch(10).cpu().numpy()
     assert np.array_equal(a, c) and not np.array_equal(a, b)
+
+
+def test_open_device_parses_on_the_gpu(rgb_small):
+    """Record bytes already resident in device memory: index and markers are parsed on the
+    device at open; results are identical to the host-opened record, for the full record and for
+    a prefix that ends at a group boundary."""
+    rec, _ = rgb_small
+    torch = _torch()
+    _, _, _, _, ge = oracle.record_index(rec)
+    with pkg.pcr_open(rec, 0) as a:
+        want = {k: (a.decode_coefficients(k).cpu().numpy(), a.decode_batch(k).cpu().numpy()) for k in (1, 5, 10)}
+        lay = a.output_layout()
+    dev = torch.frombuffer(bytearray(rec), dtype=torch.uint8).cuda()
+    with pkg.pcr_open_device(dev) as r:
+        assert (r.n, r.G, r.k_avail) == (a.n, a.G, 10)
+        assert np.array_equal(r.output_layout(), lay)
+        for k in (1, 5, 10):
+            assert np.array_equal(r.decode_coefficients(k).cpu().numpy(), want[k][0])
+            assert np.array_equal(r.decode_batch(k).cpu().numpy(), want[k][1])
+        off0, len0, _, _, _ = oracle.record_index(rec)
+        off1, len1 = r.index()
+        assert np.array_equal(off0, off1) and np.array_equal(len0, len1)
+    part = torch.frombuffer(bytearray(rec[:int(ge[4])]), dtype=torch.uint8).cuda()
+    with pkg.pcr_open_device(part) as r:
+        assert r.k_avail == 5
+        assert np.array_equal(r.decode_batch(5).cpu().numpy(), want[5][1])
+        with pytest.raises(pkg.PcrError) as e:
+            r.decode_batch(6)
+        assert e.value.code == pkg.E_TRUNCATED
+    # a pointer that is not 16-byte aligned, and malformed bytes, are refused
+    shifted = torch.empty(len(rec) + 1, dtype=torch.uint8, device="cuda")
+    shifted[1:] = dev
+    with pytest.raises(pkg.PcrError) as e:
+        pkg.pcr_open_device(shifted[1:])
+    assert e.value.code == pkg.E_ARG
+    bad = dev.clone()
+    bad[0] = 0x58
+    with pytest.raises(pkg.PcrError) as e:
+        pkg.pcr_open_device(bad)
+    assert e.value.code == pkg.E_FORMAT
+
+
+def test_streamed_444_records_opened_on_device():
+    """Two high-quality 4:4:4 records uploaded as they would be by a streaming loader, opened from
+    device memory, decoded at every scan group; oracle on a sample."""
+    records, _ = pcrgen.make_workload("ham_like", limit=20)
+    torch = _torch()
+    rec = records[0]
+    dev = torch.frombuffer(bytearray(rec), dtype=torch.uint8).cuda()
+    with pkg.pcr_open_device(dev) as r:
+        lay, clay = r.output_layout(), r.coef_layout()
+        for k in range(1, 11):
+            coef = r.decode_coefficients(k).cpu().numpy()
+            out = r.decode_batch(k).cpu().numpy()
+            for i in (0, 7, 19):
+                c0, p0, info = oracle.decode_record_image(rec, i, k)
+                assert np.array_equal(coef[int(clay[i]):int(clay[i + 1])], c0), (i, k)
+                got = out[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
+                assert np.abs(got - p0).max() <= PIXEL_TOL, (i, k)
+
+
+def test_degenerate_shapes():
+    """One image per record; a 1x1 image; very wide and very tall strips; an image of one MCU row
+    with restart intervals of a single MCU."""
+    cases = [[(1, 1)], [(2000, 8)], [(8, 2000)], [(640, 16)]]
+    for ci, sizes in enumerate(cases):
+        files = [pcrgen.make_jpeg(900 + ci, 1, w, h, 3, 6.0, 2, 2, 90, restart=(2 if ci == 3 else 0)) for (w, h) in sizes]
+        rec = pcrgen.write_record(files)
+        _check_record(rec, (1, 2, 6, 10))
