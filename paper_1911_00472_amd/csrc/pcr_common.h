@@ -33,7 +33,11 @@ struct ImgDesc {
     uint8_t qprec[4];                      // 0: 8-bit entries, 1: 16-bit big endian
     int32_t status;                        // kOk or the first error found while parsing
     uint32_t nscans;                       // scans parsed
+    uint8_t zmax[kMaxComp];                // per component: zig-zag positions [0, zmax) may be non-zero after the scans parsed
+    uint8_t pad;
 };
+
+static_assert(sizeof(ImgDesc) % 4 == 0, "ImgDesc is copied as dwords");
 
 // One scan of one image.
 struct ScanDesc {

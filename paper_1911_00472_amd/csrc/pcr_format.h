@@ -178,6 +178,8 @@ PCR_HD void parse_image(const uint8_t* rec, const uint32_t* off, const uint32_t*
     st.ri = 0; st.have_frame = 0;
     for (int t = 0; t < 4; t++) { img->qoff[t] = 0; img->qprec[t] = 0; }
     img->status = kOk; img->nscans = 0; img->nc = 0; img->W = 0; img->H = 0;
+    for (int c = 0; c < kMaxComp; c++) img->zmax[c] = 0;
+    img->pad = 0;
     uint32_t upto = nscans_i < kmax ? nscans_i : kmax;
     for (uint32_t g = 0; g < upto; g++) {
         scans[g].valid = 0;
@@ -185,6 +187,10 @@ PCR_HD void parse_image(const uint8_t* rec, const uint32_t* off, const uint32_t*
         int rc = parse_region(rec, p, p + L, g == 0, &st, img, scans, g);
         if (rc != kOk) { img->status = rc; return; }
         img->nscans = g + 1;
+        for (int j = 0; j < scans[g].ns; j++) {
+            const int c = scans[g].comp[j];
+            if (scans[g].Se + 1 > img->zmax[c]) img->zmax[c] = (uint8_t)(scans[g].Se + 1);
+        }
     }
     if (img->nscans == 0) { img->status = kEFormat; return; }
     for (int c = 0; c < img->nc; c++) if (!img->qoff[img->tq[c]]) { img->status = kEFormat; return; }

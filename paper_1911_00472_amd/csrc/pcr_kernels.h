@@ -188,8 +188,7 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kmax) {
 constexpr int kEntropyLanes = 64;
 
 struct UnitSetup {
-    BitReader br;                 // DC scans
-    const uint32_t* words;        // AC scans: segment base, unit start and length for the window reader
+    const uint32_t* words;        // segment base, unit start and length for the window readers
     uint32_t byte_off, nbytes;
     LaneScan ls;
     int16_t* plane[kMaxComp];     // planes of the scan's components
@@ -224,7 +223,6 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, UnitSetup* L) {
     }
     L->words = reinterpret_cast<const uint32_t*>(R.clean + uni(clean_base(sd->data_off)));
     L->byte_off = uni(b0); L->nbytes = uni(b1 > b0 ? b1 - b0 : 0);
-    if (ls.Ss == 0) L->br.init(L->words, L->byte_off, L->nbytes);
     L->ok = true;
 }
 
@@ -236,15 +234,17 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     if (!L.ok) return;
     const ScanDesc* sd = &R.scan[(size_t)un.img * R.G + un.scan];
     const uint32_t o0 = sd->dc_off[0], o1 = L.ls.ns > 1 ? sd->dc_off[1] : o0, o2 = L.ls.ns > 2 ? sd->dc_off[2] : o0;
-    DcTab* t0 = &tabs[0];
-    DcTab* t1 = t0; DcTab* t2 = t0;
-    if (o1 != o0) t1 = &tabs[1];
-    if (o2 == o1) t2 = t1; else if (o2 != o0) t2 = &tabs[2];
-    if (threadIdx.x == 0) dctab_build(t0, R.rec + o0);
-    if (threadIdx.x == 1 && t1 != t0) dctab_build(t1, R.rec + o1);
-    if (threadIdx.x == 2 && t2 != t0 && t2 != t1) dctab_build(t2, R.rec + o2);
+    // distinct tables of the scan's components: slot 0 always, slot 1/2 when a component uses another one
+    int tj1 = 0, tj2 = 0, ntab = 1;
+    if (o1 != o0) { tj1 = 1; ntab = 2; }
+    if (o2 == o1) tj2 = tj1; else if (o2 != o0) { tj2 = ntab; ntab++; }
+    if (threadIdx.x == 0) dctab_build(&tabs[0], R.rec + o0);
+    if (threadIdx.x == 1 && tj1 == 1) dctab_build(&tabs[1], R.rec + o1);
+    if (threadIdx.x == 2 && tj2 != 0 && tj2 != tj1) dctab_build(&tabs[tj2], R.rec + o2);
     __syncthreads();
-    int rc = decode_dc_first(&L.br, L.ls, t0, t1, t2, L.plane[0], L.plane[1], L.plane[2]);
+    DcWindowReader wr;
+    wr.init(L.words, L.byte_off, L.nbytes, &tabs[0], &tabs[1], &tabs[2], uni(ntab), threadIdx.x);
+    int rc = decode_dc_first(&wr, L.ls, 0, uni(tj1), uni(tj2), L.plane[0], L.plane[1], L.plane[2]);
     if (rc != kOk) R.status[un.img] = rc;
 }
 
@@ -438,88 +438,180 @@ __global__ void __launch_bounds__(256) k_export_natural(const int16_t* in, int16
 }
 
 // --------------------------------------------------------------------------------------
-// k_pixel: one workgroup per strip of up to kStripMcus MCUs of one MCU row of one image.
-// Phase 1: de-quantise + row IDCT per (block, row); phase 2: column IDCT + level shift + clamp;
-// phase 3: chroma replication + colour + store.
+// k_pixel: one workgroup per strip of MCUs (128 pixels wide at most) of one MCU row of one image.
+//   phase 1  coefficients -> LDS: every lane loads 16 contiguous bytes (8 coefficients in
+//            zig-zag order), de-quantises and scatters them to their natural positions; chunks
+//            that no scan <= k can have touched are not read at all
+//   phase 2  row IDCT, one lane per (block, row)       } skipped for components that only have
+//   phase 3  column IDCT + level shift + clamp          } their DC: the block is flat
+//   phase 4  chroma replication + colour + store: one lane per ALIGNED 4-byte word of an output
+//            row, so that every store is a full dword whatever the image width; a word straddles
+//            at most two pixels, which the lane converts itself
 // --------------------------------------------------------------------------------------
-constexpr int kStripMcus = 8;
-constexpr int kMaxBlocksPerMcu = 6;        // 4:2:0: 4 + 1 + 1
+constexpr int kStripPx = 128;              // strip width in pixels
+constexpr int kMaxStripBlocks = 96;        // worst sampling: 16 MCUs x 6 blocks or 8 MCUs x 12 blocks (4:2:0: 48)
+constexpr int kStripMcus = 8;              // MCUs per strip when the MCU is 16 pixels wide (tiles are built for this)
 
 struct PixelTile { uint32_t img; uint16_t mcu_row; uint16_t mcu_col0; };
+typedef short short8 __attribute__((ext_vector_type(8)));
 
-__global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* tiles, uint8_t* out) {
-    __shared__ float tile[kStripMcus * kMaxBlocksPerMcu * 64];
+__global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out) {
+    // samples of the strip, one row-major plane per component (so that neighbouring pixels are
+    // neighbouring words of LDS in phase 4)
+    __shared__ float tile[kMaxStripBlocks * 64];
     __shared__ float qn[kMaxComp][64];
-    __shared__ uint8_t izz[64];                            // natural index -> zig-zag position (= element inside a block)
-    if (threadIdx.x < 64) izz[zigzag_natural(threadIdx.x)] = (uint8_t)threadIdx.x;
+    __shared__ uint8_t zz[64];
+    __shared__ ImgDesc img;                                // this image's descriptor, read many times below
+    __shared__ uint32_t pbase[kMaxComp];                   // first block of each component plane in the coefficient buffer
     const PixelTile t = tiles[blockIdx.x];
-    const ImgDesc& img = R.img[t.img];
-    const int nc = img.nc;
+    {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.img[t.img]);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&img);
+        if (threadIdx.x < sizeof(ImgDesc) / 4) dst[threadIdx.x] = src[threadIdx.x];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t acc = 0;
+        for (uint32_t c = 0; c < kMaxComp; c++) { pbase[c] = acc; if (c < img.nc) acc += (uint32_t)img.bw[c] * img.bh[c]; }
+    }
+    const uint32_t nc = img.nc;
     const uint32_t W = img.W, H = img.H;
     uint8_t* o = out + R.out_off[t.img];
-    const uint32_t mcu_px_w = 8 * img.hmax, mcu_px_h = 8 * img.vmax;
-    const uint32_t nm = (uint32_t)img.mcux - t.mcu_col0 < (uint32_t)kStripMcus ? (uint32_t)img.mcux - t.mcu_col0 : (uint32_t)kStripMcus;
-    const uint32_t x0 = t.mcu_col0 * mcu_px_w, y0 = t.mcu_row * mcu_px_h;
+    const uint32_t hmax = img.hmax, vmax = img.vmax;
+    const uint32_t mcu_px_w = 8 * hmax, mcu_px_h = 8 * vmax;
+    const uint32_t per = kStripPx / mcu_px_w;              // MCUs per strip: 8 (16-px MCUs) or 16 (8-px MCUs)
+    const uint32_t col0 = t.mcu_col0 * (per / kStripMcus);
+    if (col0 >= img.mcux) return;                          // tiles are laid out for 8 MCUs per strip; wider strips need fewer
+    const uint32_t nm = img.mcux - col0 < per ? img.mcux - col0 : per;
+    const uint32_t x0 = col0 * mcu_px_w, y0 = t.mcu_row * mcu_px_h;
     const uint32_t sw = nm * mcu_px_w;                     // strip width in pixels
-    if (R.status[t.img] != kOk) {                          // corrupt image: zero-filled
-        for (uint32_t p = threadIdx.x; p < sw * mcu_px_h; p += 256) {
-            uint32_t y = y0 + p / sw, x = x0 + p % sw;
-            if (x < W && y < H) for (int c = 0; c < nc; c++) o[((size_t)y * W + x) * nc + c] = 0;
-        }
-        return;
-    }
-    // quantisation tables in natural order
-    for (int e = threadIdx.x; e < nc * 64; e += 256) {
-        int c = e >> 6, k = e & 63;
+    const uint32_t xe = x0 + sw < W ? x0 + sw : W;         // visible part of the strip
+    const uint32_t rows = y0 + mcu_px_h < H ? mcu_px_h : H - y0;
+    const uint32_t row_bytes = (xe - x0) * nc;
+    const bool dead = R.status[t.img] != kOk;
+    if (threadIdx.x < 64) zz[threadIdx.x] = (uint8_t)zigzag_natural(threadIdx.x);
+    for (uint32_t e = threadIdx.x; e < nc * 64; e += 256) {
+        const uint32_t c = e >> 6, k = e & 63;
         const uint8_t* q = R.rec + img.qoff[img.tq[c]];
         qn[c][zigzag_natural(k)] = img.qprec[img.tq[c]] ? (float)ld_be16(q + 2 * k) : (float)q[k];
     }
-    __syncthreads();
-    // blocks of the strip, component by component: component c contributes nm*hs rows of vs
-    uint32_t cbase[kMaxComp + 1]; cbase[0] = 0;
-    for (int c = 0; c < nc; c++) cbase[c + 1] = cbase[c] + nm * img.hs[c] * img.vs[c];
+    // per component: blocks of the strip [cbase[c], cbase[c+1]), blocks per strip row, plane offset and row stride in `tile`
+    uint32_t cbase[kMaxComp + 1], bwc[kMaxComp], poff[kMaxComp], pstr[kMaxComp];
+    bool flat[kMaxComp];
+    cbase[0] = 0;
+#pragma unroll
+    for (uint32_t c = 0; c < kMaxComp; c++) {
+        const uint32_t hs = c < nc ? img.hs[c] : 0, vs = c < nc ? img.vs[c] : 0;
+        bwc[c] = nm * hs; pstr[c] = bwc[c] * 8; poff[c] = cbase[c] * 64;
+        cbase[c + 1] = cbase[c] + bwc[c] * vs;
+        flat[c] = c < nc && img.zmax[c] <= 1;
+    }
     const uint32_t nblk = cbase[nc];
-    const int16_t* coef = R.coef + R.coef_off[t.img];
-    // phase 1
-    for (uint32_t w = threadIdx.x; w < nblk * 8; w += 256) {
-        uint32_t b = w >> 3, v = w & 7;
-        int c = 0; while (b >= cbase[c + 1]) c++;
-        uint32_t lb = b - cbase[c];
-        uint32_t bwc = nm * img.hs[c];                     // blocks per row of this strip in component c
-        uint32_t brow = t.mcu_row * img.vs[c] + lb / bwc, bcol = t.mcu_col0 * img.hs[c] + lb % bwc;
-        const int16_t* pl = coef;
-        for (int q = 0; q < c; q++) pl += (size_t)img.bw[q] * img.bh[q] * 64;
-        const int16_t* src = pl + ((size_t)brow * img.bw[c] + bcol) * 64;
-        float in[8], res[8];
-        for (int u = 0; u < 8; u++) in[u] = (float)src[izz[v * 8 + u]] * qn[c][v * 8 + u];
-        idct8(in, res);
-        for (int x = 0; x < 8; x++) tile[b * 64 + v * 8 + x] = res[x];
-    }
     __syncthreads();
-    // phase 2
-    for (uint32_t w = threadIdx.x; w < nblk * 8; w += 256) {
-        uint32_t b = w >> 3, x = w & 7;
-        float in[8], res[8];
-        for (int v = 0; v < 8; v++) in[v] = tile[b * 64 + v * 8 + x];
-        idct8(in, res);
-        for (int y = 0; y < 8; y++) tile[b * 64 + y * 8 + x] = clamp255(res[y] + 128.f);
-    }
-    __syncthreads();
-    // phase 3
-    for (uint32_t p = threadIdx.x; p < sw * mcu_px_h; p += 256) {
-        uint32_t ly = p / sw, lx = p % sw;
-        uint32_t y = y0 + ly, x = x0 + lx;
-        if (x >= W || y >= H) continue;
-        float s[kMaxComp];
-        for (int c = 0; c < nc; c++) {
-            uint32_t sx = lx * img.hs[c] / img.hmax, sy = ly * img.vs[c] / img.vmax;   // sample in the strip's plane
-            uint32_t bwc = nm * img.hs[c];
-            uint32_t b = cbase[c] + (sy >> 3) * bwc + (sx >> 3);
-            s[c] = tile[b * 64 + (sy & 7) * 8 + (sx & 7)];
+    if (!dead) {
+        const int16_t* coef = R.coef + R.coef_off[t.img];
+        // phase 1: chunk = 8 consecutive coefficients (zig-zag order) of a block
+        for (uint32_t w = threadIdx.x; w < nblk * 8; w += 256) {
+            const uint32_t b = w >> 3, ch = w & 7;
+            const uint32_t c = b < cbase[1] ? 0 : (b < cbase[2] ? 1 : 2);
+            const uint32_t lb = b - cbase[c];
+            const uint32_t lrow = lb / bwc[c], lcol = lb % bwc[c];
+            const uint32_t brow = t.mcu_row * img.vs[c] + lrow, bcol = col0 * img.hs[c] + lcol;
+            const int16_t* pl = coef + (size_t)pbase[c] * 64;
+            short8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (ch * 8 < img.zmax[c]) v = *reinterpret_cast<const short8*>(pl + ((size_t)brow * img.bw[c] + bcol) * 64 + ch * 8);
+            float* blk = tile + poff[c] + (lrow * 8) * pstr[c] + lcol * 8;      // sample (0,0) of the block
+            if (flat[c]) { if (ch == 0) blk[0] = (float)v[0] * qn[c][0]; continue; }   // flat blocks only need their DC
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const uint32_t p = zz[ch * 8 + j];
+                blk[(p >> 3) * pstr[c] + (p & 7)] = (float)v[j] * qn[c][p];
+            }
         }
-        uint8_t* dst = o + ((size_t)y * W + x) * nc;
-        if (nc == 1) dst[0] = round_u8(s[0]);
-        else ycc_to_rgb(s[0], s[1], s[2], dst);
+        __syncthreads();
+        // phase 2: rows
+        for (uint32_t w = threadIdx.x; w < nblk * 8; w += 256) {
+            const uint32_t b = w >> 3, v = w & 7;
+            const uint32_t c = b < cbase[1] ? 0 : (b < cbase[2] ? 1 : 2);
+            if (flat[c]) continue;
+            const uint32_t lb = b - cbase[c];
+            float* rowp = tile + poff[c] + ((lb / bwc[c]) * 8 + v) * pstr[c] + (lb % bwc[c]) * 8;
+            float in[8], res[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) in[u] = rowp[u];
+            idct8(in, res);
+#pragma unroll
+            for (int x = 0; x < 8; x++) rowp[x] = res[x];
+        }
+        __syncthreads();
+        // phase 3: columns
+        for (uint32_t w = threadIdx.x; w < nblk * 8; w += 256) {
+            const uint32_t b = w >> 3, x = w & 7;
+            const uint32_t c = b < cbase[1] ? 0 : (b < cbase[2] ? 1 : 2);
+            const uint32_t lb = b - cbase[c];
+            float* colp = tile + poff[c] + ((lb / bwc[c]) * 8) * pstr[c] + (lb % bwc[c]) * 8 + x;
+            if (flat[c]) { if (x == 0) colp[0] = clamp255(colp[0] * 0.125f + 128.f); continue; }
+            float in[8], res[8];
+#pragma unroll
+            for (int v = 0; v < 8; v++) in[v] = colp[v * pstr[c]];
+            idct8(in, res);
+#pragma unroll
+            for (int y = 0; y < 8; y++) colp[y * pstr[c]] = clamp255(res[y] + 128.f);
+        }
+        __syncthreads();
+    }
+    // phase 4: one lane per aligned dword of an output row of the strip
+    if (row_bytes == 0) return;
+    const uint32_t shx0 = img.hs[0] == hmax ? 0 : 1, shy0 = img.vs[0] == vmax ? 0 : 1;     // sampling factors are 1 or 2
+    const uint32_t shx1 = nc > 1 && img.hs[1] != hmax, shy1 = nc > 1 && img.vs[1] != vmax;
+    const uint32_t shx2 = nc > 2 && img.hs[2] != hmax, shy2 = nc > 2 && img.vs[2] != vmax;
+    const uint32_t m0 = flat[0] ? ~7u : ~0u, m1 = flat[1] ? ~7u : ~0u, m2 = flat[2] ? ~7u : ~0u;   // flat: read the block's corner
+    const uint32_t max_words = (row_bytes + 3) / 4 + 1;
+    for (uint32_t w = threadIdx.x; w < rows * max_words; w += 256) {
+        const uint32_t ly = w / max_words, wi = w % max_words;
+        const uint32_t y = y0 + ly;
+        uint8_t* rowp = o + ((size_t)y * W + x0) * nc;     // first byte of this row inside the strip
+        const uint32_t mis = (uint32_t)((uintptr_t)rowp & 3);
+        uint8_t* wp = rowp - mis + (size_t)wi * 4;         // aligned word this lane writes
+        const int32_t r0 = (int32_t)(wi * 4) - (int32_t)mis;   // byte offset of the word in the row (may be -3..-1)
+        if (r0 >= (int32_t)row_bytes) continue;
+        uint32_t word = 0, valid = 0;                      // valid: bit j set if byte j lies inside the row
+        if (nc == 1) {
+            const float* yrow = tile + poff[0] + ((ly >> shy0) & m0) * pstr[0];
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int32_t r = r0 + j;
+                if (r < 0 || r >= (int32_t)row_bytes) continue;
+                const float s = dead ? 0.f : yrow[((uint32_t)r >> shx0) & m0];
+                word |= (uint32_t)round_u8(s) << (8 * j); valid |= 1u << j;
+            }
+        } else {
+            const int32_t rf = r0 < 0 ? 0 : r0;
+            const uint32_t p0 = (uint32_t)rf / 3;          // first pixel the word touches; it touches at most p0, p0+1
+            const float* yrow = tile + poff[0] + ((ly >> shy0) & m0) * pstr[0];
+            const float* brow = tile + poff[1] + ((ly >> shy1) & m1) * pstr[1];
+            const float* rrow = tile + poff[2] + ((ly >> shy2) & m2) * pstr[2];
+            uint32_t six_lo = 0, six_hi = 0;               // the six bytes R G B R G B of pixels p0, p0+1
+#pragma unroll
+            for (int q = 0; q < 2; q++) {
+                const uint32_t lx = p0 + q;
+                uint8_t px[3] = {0, 0, 0};
+                if (lx * 3 < row_bytes && !dead)
+                    ycc_to_rgb(yrow[(lx >> shx0) & m0], brow[(lx >> shx1) & m1], rrow[(lx >> shx2) & m2], px);
+                const uint32_t three = (uint32_t)px[0] | ((uint32_t)px[1] << 8) | ((uint32_t)px[2] << 16);
+                if (q == 0) six_lo = three; else { six_lo |= three << 24; six_hi = three >> 8; }
+            }
+            const uint64_t six = ((uint64_t)six_hi << 32) | six_lo;
+            const int32_t first = r0 - (int32_t)(p0 * 3);  // byte of `six` that lands on byte 0 of the word: -3..2
+            word = first >= 0 ? (uint32_t)(six >> (8 * first)) : (uint32_t)(six << (8 * -first));
+#pragma unroll
+            for (int j = 0; j < 4; j++) { const int32_t r = r0 + j; if (r >= 0 && r < (int32_t)row_bytes) valid |= 1u << j; }
+        }
+        if (valid == 15u) *reinterpret_cast<uint32_t*>(wp) = word;
+        else {
+#pragma unroll
+            for (int j = 0; j < 4; j++) if (valid & (1u << j)) wp[j] = (uint8_t)(word >> (8 * j));
+        }
     }
 }
 

@@ -68,7 +68,6 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
         if (sd.Ss > 0) masks[g].assign(plane * (sd.Ah ? 4 : 1), 0);
         if (sd.Ss == 0 && sd.Ah > 0) continue;                     // DC refinement: applied below, in place
         for (uint32_t j = 0; j < nint; j++) {
-            BitReader br; br.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j]);
             LaneScan ls;
             ls.mcu_w = sd.mcu_w; ls.mcu0 = sd.ri ? j * sd.ri : 0;
             ls.mcu1 = sd.ri ? (ls.mcu0 + sd.ri < sd.mcus ? ls.mcu0 + sd.ri : sd.mcus) : sd.mcus;
@@ -82,7 +81,8 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
             if (sd.Ss == 0) {
                 std::vector<DcTab> dt(3);
                 for (int q = 0; q < sd.ns; q++) dctab_build(&dt[q], rec + sd.dc_off[q]);
-                rc = decode_dc_first(&br, ls, &dt[0], &dt[1], &dt[2], cpl[0], cpl[1], cpl[2]);
+                DcWindowReader dw; dw.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &dt[0], &dt[1], &dt[2], sd.ns, 0);
+                rc = decode_dc_first(&dw, ls, 0, 1, 2, cpl[0], cpl[1], cpl[2]);
             } else {
                 AcTab at; actab_build(&at, rec + sd.ac_off);
                 WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &at, sd.Ah == 0, 0);
