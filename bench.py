@@ -16,6 +16,13 @@ import time
 
 import numpy as np
 
+# The records of a step are decoded on one HIP stream each.  HIP multiplexes its streams over
+# GPU_MAX_HW_QUEUES hardware queues (default 4); with four, pairs of the record streams were measured to
+# share a queue and run one after the other.  Eight queues give every record stream its own.  Must be set
+# before the HIP runtime starts.
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -51,6 +58,51 @@ def algorithmic_bytes(ends, shapes, k):
                 path=int(comp + 2 * 2 * touched + out), entropy=int(comp + 2 * touched))
 
 
+# rocprofv3 counters of the dominant kernel, k_ac_refine, per launch (mean of its two launches per
+# record: scans 6, 8, 9, then scan 10) for record 0 of the default workload at scan group 10; summaries
+# under profiles/.  FETCH_SIZE reads 0.5 KiB per KiB a plain copy kernel fetches and WRITE_SIZE 1.0, so the
+# fetch figure is scaled by 2.  They describe the kernel as it stood when they were taken and are set to
+# None whenever k_ac_refine changes, until the counters are read again.
+AC_REFINE_PMC = {
+    "salu_insts_per_launch": 0.5 * (2406.93e6 + 1889.56e6),
+    "valu_insts_per_launch": 0.5 * (315.79e6 + 268.40e6),
+    "fetch_bytes_per_launch": 0.5 * (43295.25 + 44649.69) * 1024 * 2.0,
+    "write_bytes_per_launch": 0.5 * (65234.16 + 42189.25) * 1024 * 1.0,
+}
+SALU_PEAK_GINSTS = 256 * 2.4      # one scalar instruction per cycle per compute unit, 256 CUs, 2.4 GHz
+
+
+def dominant_kernel_roofline(args, ends0, alone_ms, over_ms, alone, n_img):
+    """Roofline object for k_ac_refine, the kernel with the largest share of the step at scan group 10
+    (at scan groups without AC refinement scans: k_ac_first, else k_dc_first)."""
+    k = args.scan_group
+    name = "ac_refine" if alone["ac_refine"][1] else ("ac_first" if alone["ac_first"][1] else "dc_first")
+    ms = alone_ms[name]
+    # what the method itself makes this kernel move: the entropy-coded bytes of its scans, read once
+    # (refinement scans of the 10-scan script: 6, 8, 9, 10; AC first: 2..5; DC first: 1)
+    scans = {"ac_refine": [6, 8, 9, 10], "ac_first": [2, 3, 4, 5], "dc_first": [1]}[name]
+    sizes = np.diff(np.concatenate([np.zeros((ends0.shape[0], 1), dtype=np.int64), ends0], axis=1), axis=1)
+    launches_per_call = max(1, alone[name][1] // 3)
+    alg = float(sum(sizes[:, j - 1].sum() for j in scans if j <= k)) / launches_per_call
+    default = args.images == 4096 and k == HEADLINE_K and name == "ac_refine"
+    pmc = AC_REFINE_PMC if default else None
+    out = {
+        "kernel": "k_%s (one record of %d images decoded alone, mean of its %d launches per decode)" % (name, ends0.shape[0], launches_per_call),
+        "bound": "alu",
+        "achieved": (pmc["salu_insts_per_launch"] / (ms * 1e-3) / 1e9) if pmc else None,
+        "peak": SALU_PEAK_GINSTS, "unit": "G scalar instructions/s",
+        "frac": (pmc["salu_insts_per_launch"] / (ms * 1e-3) / 1e9 / SALU_PEAK_GINSTS) if pmc else None,
+        "traffic": (pmc["fetch_bytes_per_launch"] + pmc["write_bytes_per_launch"]) if pmc else None,
+        "ms_per_launch": ms, "ms_per_launch_overlapped": over_ms[name],
+        "hbm_view": {"algorithmic_bytes_per_launch": alg, "achieved_GBps": alg / (ms * 1e-3) / 1e9,
+                     "frac_of_8TBps": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "note": "a serial Huffman decoder is bound by scalar-ALU issue (one wavefront per stream), not by HBM; the "
+                "instruction and byte counts per launch are rocprofv3 counter readings (profiles/), the duration is "
+                "measured here with HIP events",
+    }
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +111,8 @@ def main():
     ap.add_argument("--images", type=int, default=4096, help="images of the workload to use (default: all 4096)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scan-group", type=int, default=HEADLINE_K)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain elementwise copy of 256 MiB (untimed), the yardstick for rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the decode path shards by record with no exchange between GPUs, "
@@ -85,14 +139,23 @@ def main():
 
     handles = [pkg.pcr_open(r, 0) for r in records]
     outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in handles]
-    for h in handles:
-        h.enable_stage_timing(True)
     # one stream per record: records are independent, so their kernels may overlap (default priority)
     streams = [torch.cuda.Stream() for _ in handles]
 
     def step(k):
         for h, o, st in zip(handles, outs, streams):
             h.decode_batch(k, out=o, stream=st.cuda_stream)
+
+    if args.calibrate_copy:
+        # a kernel that reads 256 MiB and writes 256 MiB, nothing else: what the HBM counters read for it
+        # gives the factor by which the same counters of the decode kernels are scaled
+        a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        torch.add(a, 1, out=b)
+        torch.cuda.synchronize()
+        print("[bench] calibration copy: elementwise kernel, %d bytes read, %d bytes written" % (a.numel(), b.numel()), file=sys.stderr, flush=True)
+        del a, b
 
     # ---- parity spot check against the oracle before anything is timed ----
     import oracle
@@ -109,34 +172,44 @@ def main():
         for _ in range(warmup):
             step(k)
         torch.cuda.synchronize()
+        for h in handles:
+            h.enable_stage_timing(True)          # starts a new event history on every handle
         t = time.perf_counter()
         for _ in range(steps):
             step(k)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t
-        # per-stage kernel times: record 0 decoded ALONE on its stream (the four records of a step
-        # overlap, so their per-stage HIP events would measure each other), HIP events recorded by
-        # the library on that stream around each stage
-        stage = np.zeros(pkg.NUM_STAGES)
-        reps = 3
-        for _ in range(reps):
+        # HIP events the library recorded on each record's own stream around every kernel of the timed
+        # steps.  The records of a step overlap, so an interval here also holds the time a kernel spent
+        # sharing the GPU with the other records' kernels.
+        over = {n: [0.0, 0] for n in pkg.STAGE_NAMES}
+        for h in handles:
+            calls, hist = h.stage_ms_history()
+            for n, (ms, launches) in hist.items():
+                over[n][0] += ms
+                over[n][1] += launches
+        # the same with record 0 decoded ALONE on its stream: every kernel has the GPU to itself, which is
+        # also what rocprofv3 reports (it serialises dispatches)
+        handles[0].enable_stage_timing(True)
+        for _ in range(3):
             handles[0].decode_batch(k, out=outs[0], stream=streams[0].cuda_stream)
-            ms = handles[0].last_stage_ms()
-            stage += np.array([ms[s] for s in pkg.STAGE_NAMES]) / reps
-        return dt / steps, stage
+        torch.cuda.synchronize()
+        calls, alone = handles[0].stage_ms_history()
+        return dt / steps, over, alone, calls
 
     per_k = {}
     for k in SCAN_GROUPS:
         if k == args.scan_group:
             continue
-        sec, stage = timed(k, max(2, args.steps // 2), 1)
-        per_k[k] = (sec, stage)
-    sec, stage = timed(args.scan_group, args.steps, args.warmup)
-    per_k[args.scan_group] = (sec, stage)
+        per_k[k] = timed(k, max(2, args.steps // 2), 1)
+    per_k[args.scan_group] = timed(args.scan_group, args.steps, args.warmup)
+
+    def per_launch(d):
+        return {n: (ms / launches if launches else 0.0) for n, (ms, launches) in d.items()}
 
     report = {}
     for k in sorted(per_k):
-        sec, stage = per_k[k]
+        sec, over, alone, calls = per_k[k]
         ab = algorithmic_bytes(ends, shapes, k)
         report[str(k)] = {
             "images_per_s": n_img / sec,
@@ -145,31 +218,28 @@ def main():
             "algorithmic_GBps": ab["path"] / sec / 1e9,
             "hbm_roofline_frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS,
             "must_move_floor_GBps": (ab["compressed"] + ab["out"]) / sec / 1e9,
-            "stage_ms_one_record_alone": dict(zip(pkg.STAGE_NAMES, (float(x) for x in stage))),
+            "stage_ms_one_record_alone": {n: ms / calls for n, (ms, launches) in alone.items()},
+            "kernel_ms_per_launch_alone": per_launch(alone),
+            "kernel_ms_per_launch_overlapped": per_launch(over),
         }
-    sec, stage = per_k[args.scan_group]
+    sec, over, alone, calls = per_k[args.scan_group]
     ab = algorithmic_bytes(ends, shapes, args.scan_group)
     n0 = handles[0].n
-    ab0 = algorithmic_bytes(ends[:n0], shapes[:n0], args.scan_group)      # record 0 alone
-    ent_ms = float(stage[pkg.STAGE_NAMES.index("entropy")])
-    roofline = {
-        "kernel": "entropy stage of one %d-image record decoded alone: k_dc_first + k_ac_first + k_ac_refine + "
-                  "k_refine_blocks, all dependency levels" % n0,
-        "bound": "hbm", "achieved": ab0["entropy"] / (ent_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": ab0["entropy"] / (ent_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
-        "algorithmic_bytes_per_launch": ab0["entropy"], "ms_per_launch": ent_ms,
-        "note": "the stage is bound by scalar-ALU issue and single-wavefront latency, not by HBM; see DESIGN.md section 7",
-    }
+    roofline = dominant_kernel_roofline(args, ends[:n0], per_launch(alone), per_launch(over), alone, n_img)
 
     cpu = None
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
-        sample = min(192, handles[0].n)
+        # bounded sample: every record of the workload once, a few seconds of wall time on 16 threads
         t = time.perf_counter()
-        oracle.decode_record(records[0], args.scan_group, images=range(sample), threads=threads, want_coef=False)
+        sample = 0
+        for rec_bytes, h in zip(records, handles):
+            oracle.decode_record(rec_bytes, args.scan_group, images=range(h.n), threads=threads, want_coef=False)
+            sample += h.n
         dt = time.perf_counter() - t
         cpu = {"value": sample / dt, "unit": "images/s", "cores": threads, "kind": "oracle",
-               "sample": "first %d images of record 0 at scan group %d, %d threads, %.1f s" % (sample, args.scan_group, threads, dt)}
+               "sample": "all %d images of the workload once at scan group %d, %d threads, %.1f s wall (%.0f CPU-seconds)"
+                         % (sample, args.scan_group, threads, dt, dt * threads)}
 
     line = {
         "metric": "decoded_images_per_sec_at_scan_group_%d" % args.scan_group,

@@ -11,8 +11,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpcr.so")
 
 OK, E_ARG, E_FORMAT, E_TRUNCATED, E_UNSUPPORTED, E_RANGE, E_NOMEM, E_DEVICE = 0, -1, -2, -3, -4, -5, -6, -7
-NUM_STAGES = 5
-STAGE_NAMES = ("index_parse", "unstuff", "entropy", "refine_apply", "pixel")
+NUM_STAGES = 8
+STAGE_NAMES = ("index_parse", "unstuff", "dc_first", "ac_first", "ac_refine", "refine_blocks", "refine_apply", "pixel")
 
 # every symbol include/pcr.h declares: name -> (restype, argtypes)
 _u8p = ctypes.POINTER(ctypes.c_uint8)
@@ -34,6 +34,7 @@ SYMBOLS = {
     "pcr_decode_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_enable_stage_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
     "pcr_last_stage_ms": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_float)]),
+    "pcr_stage_ms_history": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]),
     "pcr_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
 
@@ -170,6 +171,14 @@ class Record:
         ms = (ctypes.c_float * NUM_STAGES)()
         _check(lib().pcr_last_stage_ms(self._h, ms), "pcr_last_stage_ms")
         return dict(zip(STAGE_NAMES, (float(x) for x in ms)))
+
+    def stage_ms_history(self):
+        """(calls, {stage: (summed ms, timed launches)}) over the calls since timing was switched on."""
+        ms = (ctypes.c_double * NUM_STAGES)()
+        launches = (ctypes.c_uint32 * NUM_STAGES)()
+        calls = ctypes.c_uint32(0)
+        _check(lib().pcr_stage_ms_history(self._h, ms, launches, ctypes.byref(calls)), "pcr_stage_ms_history")
+        return int(calls.value), {n: (float(ms[i]), int(launches[i])) for i, n in enumerate(STAGE_NAMES)}
 
 
 def pcr_open(data, device=0):

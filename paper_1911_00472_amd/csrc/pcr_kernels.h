@@ -441,12 +441,17 @@ __global__ void __launch_bounds__(256) k_export_natural(const int16_t* in, int16
 // k_pixel: one workgroup per strip of MCUs (128 pixels wide at most) of one MCU row of one image.
 //   phase 1  coefficients -> LDS: every lane loads 16 contiguous bytes (8 coefficients in
 //            zig-zag order), de-quantises and scatters them to their natural positions; chunks
-//            that no scan <= k can have touched are not read at all
-//   phase 2  row IDCT, one lane per (block, row)       } skipped for components that only have
-//   phase 3  column IDCT + level shift + clamp          } their DC: the block is flat
-//   phase 4  chroma replication + colour + store: one lane per ALIGNED 4-byte word of an output
-//            row, so that every store is a full dword whatever the image width; a word straddles
-//            at most two pixels, which the lane converts itself
+//            that no scan <= k can have touched are not read at all; a component that only
+//            has its DC gets one lane per block, which writes the flat block's value
+//   phase 2  row IDCT, one lane per (block, row)
+//   phase 3  column IDCT + level shift + clamp, one lane per (block, column)
+//   phase 4  chroma replication + colour + store: one lane per ALIGNED group of 12 bytes of an
+//            output row (three full dwords whatever the image width); for RGB such a group
+//            covers four pixels and, when the row starts off a pixel boundary, parts of a fifth
+// The measured limit of this kernel is vector-ALU issue, so the index arithmetic is kept off
+// the lanes: components are handled one after the other (their geometry is wave-uniform),
+// divisions by strip widths use a reciprocal computed once, and the zig-zag scatter offsets
+// and quantiser steps come from two small LDS tables.
 // --------------------------------------------------------------------------------------
 constexpr int kStripPx = 128;              // strip width in pixels
 constexpr int kMaxStripBlocks = 96;        // worst sampling: 16 MCUs x 6 blocks or 8 MCUs x 12 blocks (4:2:0: 48)
@@ -455,14 +460,17 @@ constexpr int kStripMcus = 8;              // MCUs per strip when the MCU is 16 
 struct PixelTile { uint32_t img; uint16_t mcu_row; uint16_t mcu_col0; };
 typedef short short8 __attribute__((ext_vector_type(8)));
 
+// w / d as (w * recip16(d)) >> 16, exact while w * d < 65536
+PCR_HD uint32_t recip16(uint32_t d) { return d ? 65536u / d + 1u : 0u; }
+
 __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out) {
     // samples of the strip, one row-major plane per component (so that neighbouring pixels are
-    // neighbouring words of LDS in phase 4)
-    __shared__ float tile[kMaxStripBlocks * 64];
-    __shared__ float qn[kMaxComp][64];
-    __shared__ uint8_t zz[64];
+    // neighbouring words of LDS in phase 4); rows are one word longer than the data, which
+    // spreads the rows of a block over the banks for phase 2
+    __shared__ float tile[kMaxStripBlocks * 64 + 64];
+    __shared__ __attribute__((aligned(16))) float qz[kMaxComp][64];       // quantiser steps, zig-zag order
+    __shared__ __attribute__((aligned(16))) uint16_t zoff[kMaxComp][64];  // zig-zag index -> offset of that position from the block's corner in `tile`
     __shared__ ImgDesc img;                                // this image's descriptor, read many times below
-    __shared__ uint32_t pbase[kMaxComp];                   // first block of each component plane in the coefficient buffer
     const PixelTile t = tiles[blockIdx.x];
     {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.img[t.img]);
@@ -470,10 +478,6 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
         if (threadIdx.x < sizeof(ImgDesc) / 4) dst[threadIdx.x] = src[threadIdx.x];
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t acc = 0;
-        for (uint32_t c = 0; c < kMaxComp; c++) { pbase[c] = acc; if (c < img.nc) acc += (uint32_t)img.bw[c] * img.bh[c]; }
-    }
     const uint32_t nc = img.nc;
     const uint32_t W = img.W, H = img.H;
     uint8_t* o = out + R.out_off[t.img];
@@ -489,128 +493,161 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
     const uint32_t rows = y0 + mcu_px_h < H ? mcu_px_h : H - y0;
     const uint32_t row_bytes = (xe - x0) * nc;
     const bool dead = R.status[t.img] != kOk;
-    if (threadIdx.x < 64) zz[threadIdx.x] = (uint8_t)zigzag_natural(threadIdx.x);
+    // per component (all wave-uniform): blocks per strip row, blocks in the strip, row stride and plane
+    // offset in `tile`, reciprocal of the blocks per row, first block of the strip in the coefficient buffer
+    uint32_t bwc[kMaxComp], nbc[kMaxComp], pstr[kMaxComp], poff[kMaxComp], rcp[kMaxComp], first_blk[kMaxComp], bwi[kMaxComp], zmx[kMaxComp];
+    bool flat[kMaxComp];
+    {
+        uint32_t plane0 = 0, lds = 0;
+#pragma unroll
+        for (uint32_t c = 0; c < kMaxComp; c++) {
+            const uint32_t hs = c < nc ? img.hs[c] : 0, vs = c < nc ? img.vs[c] : 0;
+            bwi[c] = c < nc ? img.bw[c] : 0;
+            bwc[c] = nm * hs; nbc[c] = bwc[c] * vs; pstr[c] = bwc[c] * 8 + 1; poff[c] = lds; lds += vs * 8 * pstr[c];
+            rcp[c] = recip16(bwc[c]);
+            first_blk[c] = plane0 + (t.mcu_row * vs) * bwi[c] + col0 * hs;
+            plane0 += c < nc ? bwi[c] * (uint32_t)img.bh[c] : 0;
+            zmx[c] = c < nc ? img.zmax[c] : 0;
+            flat[c] = c < nc && zmx[c] <= 1;
+        }
+    }
     for (uint32_t e = threadIdx.x; e < nc * 64; e += 256) {
         const uint32_t c = e >> 6, k = e & 63;
         const uint8_t* q = R.rec + img.qoff[img.tq[c]];
-        qn[c][zigzag_natural(k)] = img.qprec[img.tq[c]] ? (float)ld_be16(q + 2 * k) : (float)q[k];
+        const uint32_t p = (uint32_t)zigzag_natural((int)k);
+        qz[c][k] = img.qprec[img.tq[c]] ? (float)ld_be16(q + 2 * k) : (float)q[k];
+        zoff[c][k] = (uint16_t)((p >> 3) * (c == 0 ? pstr[0] : (c == 1 ? pstr[1] : pstr[2])) + (p & 7));
     }
-    // per component: blocks of the strip [cbase[c], cbase[c+1]), blocks per strip row, plane offset and row stride in `tile`
-    uint32_t cbase[kMaxComp + 1], bwc[kMaxComp], poff[kMaxComp], pstr[kMaxComp];
-    bool flat[kMaxComp];
-    cbase[0] = 0;
-#pragma unroll
-    for (uint32_t c = 0; c < kMaxComp; c++) {
-        const uint32_t hs = c < nc ? img.hs[c] : 0, vs = c < nc ? img.vs[c] : 0;
-        bwc[c] = nm * hs; pstr[c] = bwc[c] * 8; poff[c] = cbase[c] * 64;
-        cbase[c + 1] = cbase[c] + bwc[c] * vs;
-        flat[c] = c < nc && img.zmax[c] <= 1;
-    }
-    const uint32_t nblk = cbase[nc];
     __syncthreads();
     if (!dead) {
         const int16_t* coef = R.coef + R.coef_off[t.img];
-        // phase 1: chunk = 8 consecutive coefficients (zig-zag order) of a block
-        for (uint32_t w = threadIdx.x; w < nblk * 8; w += 256) {
-            const uint32_t b = w >> 3, ch = w & 7;
-            const uint32_t c = b < cbase[1] ? 0 : (b < cbase[2] ? 1 : 2);
-            const uint32_t lb = b - cbase[c];
-            const uint32_t lrow = lb / bwc[c], lcol = lb % bwc[c];
-            const uint32_t brow = t.mcu_row * img.vs[c] + lrow, bcol = col0 * img.hs[c] + lcol;
-            const int16_t* pl = coef + (size_t)pbase[c] * 64;
-            short8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (ch * 8 < img.zmax[c]) v = *reinterpret_cast<const short8*>(pl + ((size_t)brow * img.bw[c] + bcol) * 64 + ch * 8);
-            float* blk = tile + poff[c] + (lrow * 8) * pstr[c] + lcol * 8;      // sample (0,0) of the block
-            if (flat[c]) { if (ch == 0) blk[0] = (float)v[0] * qn[c][0]; continue; }   // flat blocks only need their DC
+        // phase 1: chunk = 8 consecutive coefficients (zig-zag order) of a block.  Component c starts
+        // at wave c, so that the small chroma planes of a 4:2:0 strip do not all land on wave 0.
 #pragma unroll
-            for (int j = 0; j < 8; j++) {
-                const uint32_t p = zz[ch * 8 + j];
-                blk[(p >> 3) * pstr[c] + (p & 7)] = (float)v[j] * qn[c][p];
+        for (uint32_t c = 0; c < kMaxComp; c++) {
+            if (c >= nc) continue;
+            const uint32_t tt = (threadIdx.x - 64 * c) & 255;
+            const int16_t* pl = coef + (size_t)first_blk[c] * 64;
+            float* plane = tile + poff[c];
+            if (flat[c]) {                                 // only the DC: the block is flat
+                const float q0 = qz[c][0];
+                for (uint32_t lb = tt; lb < nbc[c]; lb += 256) {
+                    const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
+                    const float dc = (float)pl[((size_t)lrow * bwi[c] + lcol) * 64] * q0;
+                    plane[lrow * 8 * pstr[c] + lcol * 8] = clamp255(dc * 0.125f + 128.f);
+                }
+                continue;
+            }
+            for (uint32_t w = tt; w < nbc[c] * 8; w += 256) {
+                const uint32_t lb = w >> 3, ch = w & 7;
+                const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
+                short8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (ch * 8 < zmx[c]) v = *reinterpret_cast<const short8*>(pl + ((size_t)lrow * bwi[c] + lcol) * 64 + ch * 8);
+                float* blk = plane + lrow * 8 * pstr[c] + lcol * 8;               // sample (0,0) of the block
+                const float4 qa = *reinterpret_cast<const float4*>(&qz[c][ch * 8]), qb = *reinterpret_cast<const float4*>(&qz[c][ch * 8 + 4]);
+                const uint4 zo = *reinterpret_cast<const uint4*>(&zoff[c][ch * 8]);
+                blk[zo.x & 0xFFFF] = (float)v[0] * qa.x; blk[zo.x >> 16] = (float)v[1] * qa.y;
+                blk[zo.y & 0xFFFF] = (float)v[2] * qa.z; blk[zo.y >> 16] = (float)v[3] * qa.w;
+                blk[zo.z & 0xFFFF] = (float)v[4] * qb.x; blk[zo.z >> 16] = (float)v[5] * qb.y;
+                blk[zo.w & 0xFFFF] = (float)v[6] * qb.z; blk[zo.w >> 16] = (float)v[7] * qb.w;
             }
         }
         __syncthreads();
         // phase 2: rows
-        for (uint32_t w = threadIdx.x; w < nblk * 8; w += 256) {
-            const uint32_t b = w >> 3, v = w & 7;
-            const uint32_t c = b < cbase[1] ? 0 : (b < cbase[2] ? 1 : 2);
-            if (flat[c]) continue;
-            const uint32_t lb = b - cbase[c];
-            float* rowp = tile + poff[c] + ((lb / bwc[c]) * 8 + v) * pstr[c] + (lb % bwc[c]) * 8;
-            float in[8], res[8];
 #pragma unroll
-            for (int u = 0; u < 8; u++) in[u] = rowp[u];
-            idct8(in, res);
+        for (uint32_t c = 0; c < kMaxComp; c++) {
+            if (c >= nc || flat[c]) continue;
+            const uint32_t tt = (threadIdx.x - 64 * c) & 255;
+            for (uint32_t w = tt; w < nbc[c] * 8; w += 256) {
+                const uint32_t lb = w >> 3, v = w & 7;
+                const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
+                float* rowp = tile + poff[c] + (lrow * 8 + v) * pstr[c] + lcol * 8;
+                float in[8], res[8];
 #pragma unroll
-            for (int x = 0; x < 8; x++) rowp[x] = res[x];
+                for (int u = 0; u < 8; u++) in[u] = rowp[u];
+                idct8(in, res);
+#pragma unroll
+                for (int x = 0; x < 8; x++) rowp[x] = res[x];
+            }
         }
         __syncthreads();
         // phase 3: columns
-        for (uint32_t w = threadIdx.x; w < nblk * 8; w += 256) {
-            const uint32_t b = w >> 3, x = w & 7;
-            const uint32_t c = b < cbase[1] ? 0 : (b < cbase[2] ? 1 : 2);
-            const uint32_t lb = b - cbase[c];
-            float* colp = tile + poff[c] + ((lb / bwc[c]) * 8) * pstr[c] + (lb % bwc[c]) * 8 + x;
-            if (flat[c]) { if (x == 0) colp[0] = clamp255(colp[0] * 0.125f + 128.f); continue; }
-            float in[8], res[8];
 #pragma unroll
-            for (int v = 0; v < 8; v++) in[v] = colp[v * pstr[c]];
-            idct8(in, res);
+        for (uint32_t c = 0; c < kMaxComp; c++) {
+            if (c >= nc || flat[c]) continue;
+            const uint32_t tt = (threadIdx.x - 64 * c) & 255;
+            for (uint32_t w = tt; w < nbc[c] * 8; w += 256) {
+                const uint32_t lb = w >> 3, x = w & 7;
+                const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
+                float* colp = tile + poff[c] + (lrow * 8) * pstr[c] + lcol * 8 + x;
+                float in[8], res[8];
 #pragma unroll
-            for (int y = 0; y < 8; y++) colp[y * pstr[c]] = clamp255(res[y] + 128.f);
+                for (int v = 0; v < 8; v++) in[v] = colp[v * pstr[c]];
+                idct8(in, res);
+#pragma unroll
+                for (int y = 0; y < 8; y++) colp[y * pstr[c]] = clamp255(res[y] + 128.f);
+            }
         }
         __syncthreads();
     }
-    // phase 4: one lane per aligned dword of an output row of the strip
+    // phase 4: one lane per aligned group of 12 bytes of an output row of the strip
     if (row_bytes == 0) return;
     const uint32_t shx0 = img.hs[0] == hmax ? 0 : 1, shy0 = img.vs[0] == vmax ? 0 : 1;     // sampling factors are 1 or 2
     const uint32_t shx1 = nc > 1 && img.hs[1] != hmax, shy1 = nc > 1 && img.vs[1] != vmax;
     const uint32_t shx2 = nc > 2 && img.hs[2] != hmax, shy2 = nc > 2 && img.vs[2] != vmax;
     const uint32_t m0 = flat[0] ? ~7u : ~0u, m1 = flat[1] ? ~7u : ~0u, m2 = flat[2] ? ~7u : ~0u;   // flat: read the block's corner
-    const uint32_t max_words = (row_bytes + 3) / 4 + 1;
-    for (uint32_t w = threadIdx.x; w < rows * max_words; w += 256) {
-        const uint32_t ly = w / max_words, wi = w % max_words;
-        const uint32_t y = y0 + ly;
-        uint8_t* rowp = o + ((size_t)y * W + x0) * nc;     // first byte of this row inside the strip
+    const uint32_t groups = (row_bytes + 14) / 12;         // per row, allowing for a row that starts 3 bytes into its first group
+    const uint32_t rcpg = recip16(groups);
+    for (uint32_t it = threadIdx.x; it < rows * groups; it += 256) {
+        const uint32_t ly = (it * rcpg) >> 16, g = it - ly * groups;
+        uint8_t* rowp = o + ((size_t)(y0 + ly) * W + x0) * nc;     // first byte of this row inside the strip
         const uint32_t mis = (uint32_t)((uintptr_t)rowp & 3);
-        uint8_t* wp = rowp - mis + (size_t)wi * 4;         // aligned word this lane writes
-        const int32_t r0 = (int32_t)(wi * 4) - (int32_t)mis;   // byte offset of the word in the row (may be -3..-1)
+        const int32_t r0 = (int32_t)(g * 12) - (int32_t)mis;       // byte offset of the group in the row (may be -3..-1)
         if (r0 >= (int32_t)row_bytes) continue;
-        uint32_t word = 0, valid = 0;                      // valid: bit j set if byte j lies inside the row
+        uint8_t* wp = rowp + r0;                                    // 4-byte aligned
+        uint32_t wd[3];
         if (nc == 1) {
             const float* yrow = tile + poff[0] + ((ly >> shy0) & m0) * pstr[0];
+            wd[0] = wd[1] = wd[2] = 0;
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
+            for (int j = 0; j < 12; j++) {
                 const int32_t r = r0 + j;
-                if (r < 0 || r >= (int32_t)row_bytes) continue;
-                const float s = dead ? 0.f : yrow[((uint32_t)r >> shx0) & m0];
-                word |= (uint32_t)round_u8(s) << (8 * j); valid |= 1u << j;
+                const bool ok = r >= 0 && r < (int32_t)row_bytes && !dead;
+                const float s = ok ? yrow[((uint32_t)r >> shx0) & m0] : 0.f;
+                wd[j >> 2] |= (uint32_t)round_u8(s) << (8 * (j & 3));
             }
         } else {
-            const int32_t rf = r0 < 0 ? 0 : r0;
-            const uint32_t p0 = (uint32_t)rf / 3;          // first pixel the word touches; it touches at most p0, p0+1
+            const uint32_t p0 = (uint32_t)(r0 < 0 ? 0 : r0) / 3;   // first pixel the group touches; it touches at most p0 .. p0+4
             const float* yrow = tile + poff[0] + ((ly >> shy0) & m0) * pstr[0];
             const float* brow = tile + poff[1] + ((ly >> shy1) & m1) * pstr[1];
             const float* rrow = tile + poff[2] + ((ly >> shy2) & m2) * pstr[2];
-            uint32_t six_lo = 0, six_hi = 0;               // the six bytes R G B R G B of pixels p0, p0+1
+            uint32_t three[5];                                      // R | G << 8 | B << 16 of the five pixels
 #pragma unroll
-            for (int q = 0; q < 2; q++) {
+            for (int q = 0; q < 5; q++) {
                 const uint32_t lx = p0 + q;
                 uint8_t px[3] = {0, 0, 0};
                 if (lx * 3 < row_bytes && !dead)
                     ycc_to_rgb(yrow[(lx >> shx0) & m0], brow[(lx >> shx1) & m1], rrow[(lx >> shx2) & m2], px);
-                const uint32_t three = (uint32_t)px[0] | ((uint32_t)px[1] << 8) | ((uint32_t)px[2] << 16);
-                if (q == 0) six_lo = three; else { six_lo |= three << 24; six_hi = three >> 8; }
+                three[q] = (uint32_t)px[0] | ((uint32_t)px[1] << 8) | ((uint32_t)px[2] << 16);
             }
-            const uint64_t six = ((uint64_t)six_hi << 32) | six_lo;
-            const int32_t first = r0 - (int32_t)(p0 * 3);  // byte of `six` that lands on byte 0 of the word: -3..2
-            word = first >= 0 ? (uint32_t)(six >> (8 * first)) : (uint32_t)(six << (8 * -first));
-#pragma unroll
-            for (int j = 0; j < 4; j++) { const int32_t r = r0 + j; if (r >= 0 && r < (int32_t)row_bytes) valid |= 1u << j; }
+            // the fifteen bytes as four dwords, then shifted so that byte r0 of the row lands on byte 0
+            uint32_t d0 = three[0] | (three[1] << 24), d1 = (three[1] >> 8) | (three[2] << 16),
+                     d2 = (three[2] >> 16) | (three[3] << 8), d3 = three[4];
+            uint32_t sh = (uint32_t)r0 - p0 * 3;                    // 0..2
+            if (r0 < 0) { d3 = d2; d2 = d1; d1 = d0; d0 = 0; sh = (uint32_t)(4 + r0); }   // bytes before the row: shift the other way
+            wd[0] = __builtin_amdgcn_alignbyte(d1, d0, sh);
+            wd[1] = __builtin_amdgcn_alignbyte(d2, d1, sh);
+            wd[2] = __builtin_amdgcn_alignbyte(d3, d2, sh);
         }
-        if (valid == 15u) *reinterpret_cast<uint32_t*>(wp) = word;
-        else {
+        if (r0 >= 0 && r0 + 12 <= (int32_t)row_bytes) {
+            uint32_t* w32 = reinterpret_cast<uint32_t*>(wp);
+            w32[0] = wd[0]; w32[1] = wd[1]; w32[2] = wd[2];
+        } else {
 #pragma unroll
-            for (int j = 0; j < 4; j++) if (valid & (1u << j)) wp[j] = (uint8_t)(word >> (8 * j));
+            for (int j = 0; j < 12; j++) {
+                const int32_t r = r0 + j;
+                if (r >= 0 && r < (int32_t)row_bytes) wp[j] = (uint8_t)(wd[j >> 2] >> (8 * (j & 3)));
+            }
         }
     }
 }

@@ -44,6 +44,13 @@ template <class T> int dev_upload(T** p, const std::vector<T>& v) {
 
 }  // namespace
 
+constexpr size_t kTimingRing = 64;
+struct CallTiming {
+    std::vector<hipEvent_t> ev;                // ev[0] = start of the call, ev[i] = end of interval i
+    std::vector<uint8_t> stage;                // stage[i] = stage that interval (ev[i-1], ev[i]) belongs to
+    size_t used = 0;                           // events recorded by the call that last used this slot
+};
+
 struct pcr_record {
     int device = 0;
     size_t nbytes = 0;
@@ -62,8 +69,10 @@ struct pcr_record {
     std::map<int, Plan> plans;
     bool timing = false;
     bool borrowed = false;                  // record bytes belong to the caller (pcr_open_device)
-    hipEvent_t ev[PCR_NUM_STAGES + 1] = {};
-    bool ev_valid = false, ev_recorded = false;
+    // stage timing: one list of events per call, the last kTimingRing calls are kept
+    std::vector<CallTiming> ring;
+    uint64_t timed_calls = 0;                  // calls recorded since timing was switched on
+    CallTiming* cur = nullptr;                 // the call being enqueued
 };
 
 namespace {
@@ -160,7 +169,41 @@ int check_scan_group(const pcr_record* r, int k) {
     return PCR_OK;
 }
 
-void stamp(pcr_record* r, int idx, hipStream_t s) { if (r->timing && r->ev_valid) (void)hipEventRecord(r->ev[idx], s); }
+// Stage timing.  call_begin records the start event, mark(stage) closes an interval that belongs to
+// `stage` (one mark per kernel for the entropy kernels and the pixel kernel, so that a stage's time
+// divided by its marks is the average duration of that kernel), call_end files the call.
+void mark(pcr_record* r, int stage, hipStream_t s) {
+    CallTiming* c = r->cur;
+    if (!c) return;
+    if (c->used == c->ev.size()) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { r->cur = nullptr; c->used = 0; return; }
+        c->ev.push_back(e); c->stage.push_back(0);
+    }
+    c->stage[c->used] = (uint8_t)stage;
+    (void)hipEventRecord(c->ev[c->used++], s);
+}
+void call_begin(pcr_record* r, hipStream_t s) {
+    r->cur = nullptr;
+    if (!r->timing) return;
+    if (r->ring.empty()) r->ring.resize(kTimingRing);
+    r->cur = &r->ring[r->timed_calls % kTimingRing];
+    r->cur->used = 0;
+    mark(r, 0, s);
+}
+void call_end(pcr_record* r) { if (r->cur) { r->timed_calls++; r->cur = nullptr; } }
+
+// adds the per-stage milliseconds and marks of one recorded call; waits for that call to finish
+int add_call_times(const CallTiming& c, double* ms, uint32_t* marks) {
+    if (c.used < 2) return PCR_OK;
+    HIP_TRY(hipEventSynchronize(c.ev[c.used - 1]));
+    for (size_t i = 1; i < c.used; i++) {
+        float t = 0;
+        HIP_TRY(hipEventElapsedTime(&t, c.ev[i - 1], c.ev[i]));
+        ms[c.stage[i]] += t; marks[c.stage[i]]++;
+    }
+    return PCR_OK;
+}
 
 // Steps 1-5 of the path (index .. entropy decode + refinement) for scans 1..k.
 int run_entropy_stages(pcr_record* r, int k, hipStream_t s) {
@@ -168,31 +211,32 @@ int run_entropy_stages(pcr_record* r, int k, hipStream_t s) {
     int rc = build_plan(r, k, &plan);
     if (rc) return rc;
     const uint32_t n = r->hdr.n;
-    stamp(r, 0, s);
+    call_begin(r, s);
     hipLaunchKernelGGL(k_index, dim3(k), dim3(256), 0, s, r->d, (uint32_t)k);
     hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, (uint32_t)k);
-    stamp(r, 1, s);
+    mark(r, PCR_STAGE_INDEX_PARSE, s);
     hipLaunchKernelGGL(k_unstuff, dim3(n, k), dim3(256), 0, s, r->d, (uint32_t)k);
     const size_t coef_bytes = r->coef_off[n] * sizeof(int16_t);
     hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
     if (r->n_masks) hipLaunchKernelGGL(k_fill_zero, dim3(1024), dim3(256), 0, s, (uint4*)r->d.masks, (r->n_masks * 8 + 15) / 16);
-    stamp(r, 2, s);
+    mark(r, PCR_STAGE_UNSTUFF, s);
     for (auto& l : plan->levels) {
         const dim3 grid(l.n), block(kEntropyLanes);
-        if (l.kind == kDcFirst) hipLaunchKernelGGL(k_dc_first, grid, block, 0, s, r->d, l.d_units, l.n);
-        else if (l.kind == kAcFirst) hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n);
+        if (l.kind == kDcFirst) { hipLaunchKernelGGL(k_dc_first, grid, block, 0, s, r->d, l.d_units, l.n); mark(r, PCR_STAGE_DC_FIRST, s); }
+        else if (l.kind == kAcFirst) { hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n); mark(r, PCR_STAGE_AC_FIRST, s); }
         else {
             hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n);
+            mark(r, PCR_STAGE_AC_REFINE, s);
             hipLaunchKernelGGL(k_refine_blocks, dim3(l.refine_grid_x, l.n_refine), dim3(256), 0, s, r->d, l.d_refine);
+            mark(r, PCR_STAGE_REFINE_BLOCKS, s);
         }
     }
-    stamp(r, 3, s);
     if (plan->n_apply) {
         hipLaunchKernelGGL(k_apply_prep, dim3((plan->n_apply + 63) / 64), dim3(64), 0, s, r->d, plan->d_apply, plan->n_apply, (uint32_t)k, plan->d_apply_lists);
         hipLaunchKernelGGL(k_apply, dim3(plan->apply_grid_x, plan->n_apply), dim3(256), 0, s, r->d, plan->d_apply, plan->d_apply_lists);
     }
-    stamp(r, 4, s);
-    if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
+    if (plan->n_apply) mark(r, PCR_STAGE_REFINE_APPLY, s);
+    if (hipGetLastError() != hipSuccess) { r->cur = nullptr; return PCR_E_DEVICE; }
     return PCR_OK;
 }
 
@@ -282,11 +326,6 @@ static int finish_open(pcr_record* r) {
     if (!rc && hipMemset(d.clean, 0xFF, padded) != hipSuccess) rc = PCR_E_DEVICE;
     if (!rc && hipMemset(d.masks, 0, (nm ? nm : 1) * sizeof(uint64_t)) != hipSuccess) rc = PCR_E_DEVICE;
     if (!rc && hipMemset(d.ivl_start, 0, (ns ? ns : 1) * sizeof(uint32_t)) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc) {
-        bool ok = true;
-        for (auto& e : r->ev) ok = ok && hipEventCreate(&e) == hipSuccess;
-        r->ev_valid = ok;
-    }
     return rc;
 }
 
@@ -401,7 +440,7 @@ void pcr_close(pcr_record* r) {
     void* ptrs[] = { r->borrowed ? nullptr : r->d_rec, d.clean, d.off, d.img, d.scan, d.coef, d.masks, d.ivl_start, d.status, (void*)d.coef_off, (void*)d.out_off,
                      (void*)d.mask_off, (void*)d.slot_base, (void*)d.slot_cnt, r->d_tiles, r->d_gather, d.tabs, (void*)d.tab_idx };
     for (void* p : ptrs) if (p) (void)hipFree(p);
-    if (r->ev_valid) for (auto& e : r->ev) (void)hipEventDestroy(e);
+    for (auto& c : r->ring) for (auto& e : c.ev) (void)hipEventDestroy(e);
     delete r;
 }
 
@@ -479,14 +518,35 @@ int pcr_reassemble(pcr_record* r, int i, int k, uint8_t* dst, size_t cap, size_t
     return PCR_OK;
 }
 
-int pcr_enable_stage_timing(pcr_record* r, int on) { if (!r) return PCR_E_ARG; r->timing = on != 0; return PCR_OK; }
+int pcr_enable_stage_timing(pcr_record* r, int on) {
+    if (!r) return PCR_E_ARG;
+    r->timing = on != 0;
+    r->timed_calls = 0;                        // switching on (again) starts a new history
+    return PCR_OK;
+}
 
 int pcr_last_stage_ms(pcr_record* r, float* ms) {
     if (!r || !ms) return PCR_E_ARG;
-    if (!r->timing || !r->ev_valid || !r->ev_recorded) return PCR_E_ARG;
+    if (!r->timing || r->timed_calls == 0) return PCR_E_ARG;
     HIP_TRY(hipSetDevice(r->device));
-    HIP_TRY(hipEventSynchronize(r->ev[PCR_NUM_STAGES]));
-    for (int s = 0; s < PCR_NUM_STAGES; s++) HIP_TRY(hipEventElapsedTime(&ms[s], r->ev[s], r->ev[s + 1]));
+    double sum[PCR_NUM_STAGES] = {}; uint32_t marks[PCR_NUM_STAGES] = {};
+    int rc = add_call_times(r->ring[(r->timed_calls - 1) % kTimingRing], sum, marks);
+    if (rc) return rc;
+    for (int s = 0; s < PCR_NUM_STAGES; s++) ms[s] = (float)sum[s];
+    return PCR_OK;
+}
+
+int pcr_stage_ms_history(pcr_record* r, double* sum_ms, uint32_t* launches, uint32_t* calls) {
+    if (!r || !sum_ms || !launches || !calls) return PCR_E_ARG;
+    if (!r->timing) return PCR_E_ARG;
+    HIP_TRY(hipSetDevice(r->device));
+    for (int s = 0; s < PCR_NUM_STAGES; s++) { sum_ms[s] = 0; launches[s] = 0; }
+    const uint64_t have = r->timed_calls < kTimingRing ? r->timed_calls : kTimingRing;
+    for (uint64_t j = 0; j < have; j++) {
+        int rc = add_call_times(r->ring[(r->timed_calls - 1 - j) % kTimingRing], sum_ms, launches);
+        if (rc) return rc;
+    }
+    *calls = (uint32_t)have;
     return PCR_OK;
 }
 
@@ -498,8 +558,7 @@ int pcr_decode_coefficients(pcr_record* r, int k, int16_t* d_coef, void* stream)
     hipStream_t s = (hipStream_t)stream;
     rc = run_entropy_stages(r, k, s);
     if (rc) return rc;
-    stamp(r, 5, s);
-    r->ev_recorded = r->timing && r->ev_valid;
+    call_end(r);
     hipLaunchKernelGGL(k_export_natural, dim3(2048), dim3(256), 0, s, r->d.coef, d_coef, (size_t)r->coef_off[r->hdr.n]);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
     return PCR_OK;
@@ -515,8 +574,8 @@ int pcr_decode_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* strea
     rc = run_entropy_stages(r, k, s);
     if (rc) return rc;
     hipLaunchKernelGGL(k_pixel, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out);
-    stamp(r, 5, s);
-    r->ev_recorded = r->timing && r->ev_valid;
+    mark(r, PCR_STAGE_PIXEL, s);
+    call_end(r);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
     if (d_status) HIP_TRY(hipMemcpyAsync(d_status, r->d.status, r->hdr.n * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
     return PCR_OK;

@@ -251,3 +251,32 @@ def test_degenerate_shapes():
         files = [pcrgen.make_jpeg(900 + ci, 1, w, h, 3, 6.0, 2, 2, 90, restart=(2 if ci == 3 else 0)) for (w, h) in sizes]
         rec = pcrgen.write_record(files)
         _check_record(rec, (1, 2, 6, 10))
+
+
+@pytest.mark.gpu
+def test_stage_timing_history(rgb_small):
+    """Stage timing: per-call and accumulated event times, one interval per entropy kernel launch."""
+    import paper_1911_00472_amd as pkg
+    rec, files = rgb_small
+    h = pkg.pcr_open(rec, 0)
+    try:
+        with pytest.raises(pkg.PcrError):
+            h.last_stage_ms()                      # nothing recorded yet
+        h.enable_stage_timing(True)
+        k = h.G
+        for _ in range(3):
+            out = h.decode_batch(k)
+        last = h.last_stage_ms()
+        calls, hist = h.stage_ms_history()
+        assert calls == 3
+        assert set(hist) == set(pkg.STAGE_NAMES)
+        for name in ("index_parse", "unstuff", "dc_first", "pixel"):
+            assert hist[name][1] == 3 and hist[name][0] > 0 and last[name] > 0
+        # the 10-scan script has two levels of AC refinement scans: two launches of each refinement kernel per call
+        assert hist["ac_refine"][1] == 6 and hist["refine_blocks"][1] == 6 and hist["ac_first"][1] == 3
+        h.enable_stage_timing(True)                # restarts the history
+        h.decode_batch(1)
+        calls, hist = h.stage_ms_history()
+        assert calls == 1 and hist["ac_first"][1] == 0 and hist["dc_first"][1] == 1
+    finally:
+        h.close()
