@@ -231,12 +231,17 @@ PCR_HD uint32_t bits_at(uint32_t w0, uint32_t w1, uint32_t w2, int j) {      // 
 // e: table entry (length << 8 | symbol), non-zero.  first: AC first scan (size s = s value bits,
 // sign-extended here); otherwise refinement (size 1 = one sign bit).  An end-of-band symbol
 // (size 0, run r < 15) is followed by r bits of run length in both.
+constexpr uint32_t kSymCoef = 0x8000u, kSymEob = 0x4000u;
+constexpr uint32_t kSymInvalid = kSymEob;                    // "end of band" of length 0: what an AC first scan sees where no code matches
+
 PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
     const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
     const int nx = s ? (first ? s : 1) : (r != 15 ? r : 0);
     const uint32_t extra = field(win, len, nx);
     const int value = (first && s) ? extend(extra, s) : (int)extra;
-    return ((uint32_t)(value & 0xFFFF) << 16) | ((uint32_t)(len + nx) << 8) | ((uint32_t)r << 4) | (uint32_t)s;
+    // bit 15: the symbol carries a coefficient; bit 14: it is an end-of-band symbol
+    const uint32_t flags = (s ? kSymCoef : 0u) | ((s == 0 && r != 15) ? kSymEob : 0u);
+    return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | ((uint32_t)r << 4) | (uint32_t)s;
 }
 
 struct WindowReader {
@@ -274,17 +279,22 @@ struct WindowReader {
         return e ? pack_symbol(e, win, first) : 0;
 #endif
     }
+    PCR_HD bool exhausted() const { return o >= 64; }         // the next symbol starts beyond the window
+    PCR_HD void refill() {
+        do { w0 = w2; w1 = n0; w2 = n1; n0 = p[0]; n1 = p[1]; p += 2; o -= 64; wbase += 64; } while (o >= 64);
+        fill();
+    }
     // packed word of the symbol at the current position; 0 if the bits there are no code
     PCR_HD uint32_t symbol() {
-        if (o >= 64) {
-            do { w0 = w2; w1 = n0; w2 = n1; n0 = p[0]; n1 = p[1]; p += 2; o -= 64; wbase += 64; } while (o >= 64);
-            fill();
-        }
+        if (o >= 64) refill();
+        return peek();
+    }
+    PCR_HD uint32_t peek() {                                  // as symbol(), for a position known to lie inside the window
         uint32_t info = lookup(o);
         if (__builtin_expect(info == 0, 0)) {                // a code longer than 8 bits, or garbage
             const uint32_t win = bits_at(w0, w1, w2, (int)o);
             const uint32_t e = ac_long_code(tab, win);
-            info = e ? pack_symbol(e, win, first) : 0;
+            info = e ? pack_symbol(e, win, first) : (first ? kSymInvalid : 0u);
         }
         return info;
     }
@@ -402,51 +412,97 @@ PCR_HD int decode_dc_first(DcWindowReader* wr, const LaneScan& ls, int tj0, int 
 }
 
 // ---------------------------------------------------------------------------------------
-// AC first scan of one component, band Ss..Se.  Writes coefficient values in
-// ZIG-ZAG order inside each 64-element block (element k of a block is zig-zag position k) and,
-// per block, the mask of positions it made non-zero.  Blocks skipped by an end-of-band run are
-// not touched: coefficients and nzout must be zero-filled beforehand.
+// AC first scan of one component, band Ss..Se.  Writes coefficient values in ZIG-ZAG order
+// inside each 64-element block (element k of a block is zig-zag position k).  Blocks skipped by
+// an end-of-band run are not touched: coefficients must be zero-filled beforehand.
+//
+// The serial part handles one symbol per loop iteration and does no memory access: a decoded
+// coefficient goes, as (element index, value), into the next free lane of two vector registers
+// (CoefSink), and the lanes store them all at once each time the bit window slides.  A window
+// of 64 bits holds at most 32 coefficient symbols (each is at least 2 bits long), so the 64
+// lanes always suffice.  Control flow is structured -- flags and loop conditions instead of
+// returns and breaks -- because the compiler turns early exits from nested loops into a state
+// variable that is tested after every symbol.
 // ---------------------------------------------------------------------------------------
-// (Control flow is kept structured -- loop conditions and flags instead of returns and breaks
-// inside the loops -- because the compiler turns early exits from nested loops into a state
-// variable that is tested after every symbol.)
-PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, int16_t* coef, uint64_t* nzout) {
-    const int Ss = ls.Ss, Se = ls.Se, Al = ls.Al;
-    const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
-    uint32_t m = ls.mcu0;
-    uint32_t row = m / mcu_w, col = m % mcu_w;
-    uint32_t bad = 0;
-    while (m < ls.mcu1) {
-        const size_t blk = (size_t)row * bw + col;
-        int16_t* cb = coef + blk * 64;
-        uint64_t mask = 0;
-        uint32_t skip = 1;                                   // blocks to move on by: this one + an end-of-band run
-        int k = Ss;
-        while (k <= Se) {
-            const uint32_t info = wr->symbol();
-            const int s = (int)(info & 15), r = (int)((info >> 4) & 15);
-            wr->consume((info >> 8) & 63);
-            if (__builtin_expect(s != 0, 1)) {               // a coefficient: run r, then the value
-                k += r;
-                const int kk = k <= Se ? k : Se;             // a run past the band is an error; stay in bounds
-                bad |= (uint32_t)(k > Se);
-                cb[kk] = (int16_t)(((int32_t)info >> 16) * (1 << Al));
-                mask |= 1ull << kk;
-                k++;
-            } else if (r == 15) k += 16;                     // sixteen zeros
-            else {                                           // end of band, run of 2^r + extra blocks (or no code at all)
-                bad |= (uint32_t)(info == 0);
-                skip = (1u << r) + (info >> 16);
-                k = 64;
-            }
-        }
-        nzout[blk] = mask;
-        bad |= (uint32_t)wr->overrun();
-        if (skip > ls.mcu1 - m) skip = ls.mcu1 - m;
-        if (bad) skip = ls.mcu1 - m;                         // stop at the first damaged block
-        m += skip; col += skip;
-        if (col >= mcu_w) { row += col / mcu_w; col %= mcu_w; }
+struct CoefSink {
+    int16_t* plane;
+    uint32_t lane, cnt;
+    uint32_t vidx; int vval;                                  // device: one pending store per lane below cnt
+    PCR_HD void init(int16_t* p, uint32_t lane_id) { plane = p; lane = lane_id; cnt = 0; vidx = 0; vval = 0; }
+    PCR_HD void emit(uint32_t elem, int value, uint32_t count_it) {   // count_it = 0: the pair is dropped
+#if defined(__HIP_DEVICE_COMPILE__)
+        // lane `cnt` of the two registers takes the pair (the lane select travels in m0: a vector
+        // instruction of this chip reads at most one scalar register besides it)
+        asm volatile("s_mov_b32 m0, %4\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
+                     : "+v"(vidx), "+v"(vval) : "s"(elem), "s"(value), "s"(cnt) : "m0");
+        cnt += count_it;
+#else
+        if (count_it) plane[elem] = (int16_t)value;
+#endif
     }
+    PCR_HD void flush() {
+#if defined(__HIP_DEVICE_COMPILE__)
+        if (lane < cnt) plane[vidx] = (int16_t)vval;
+        cnt = 0;
+#endif
+    }
+};
+
+// Non-zero mask of the band Ss..Se of one block in internal (zig-zag) order: what an AC first
+// scan over that band has made non-zero.
+PCR_HD uint64_t nz_mask_of_block(const int16_t* blk, int Ss, int Se) {
+    uint64_t m = 0;
+    for (int k = Ss; k <= Se; k++) m |= (uint64_t)(blk[k] != 0) << k;
+    return m;
+}
+
+PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink) {
+    const uint32_t Ss = (uint32_t)ls.Ss, Se = (uint32_t)ls.Se; const int Al = ls.Al;
+    const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
+    uint32_t left = ls.mcu1 - ls.mcu0;                       // blocks of the unit not finished yet (the current one included)
+    uint32_t row = ls.mcu0 / mcu_w, col = ls.mcu0 % mcu_w;
+    uint32_t base = (row * bw + col) * 64;                   // element index of the current block
+    uint32_t k = Ss;
+    uint32_t bad = 0;
+    while (left != 0) {
+        if (wr->exhausted()) {
+            sink->flush();
+            bad |= wr->overrun() ? 1u : 0u;                  // never walk far beyond the unit's data
+            wr->refill();
+        }
+        uint32_t window_end = 64;                            // set to 0 to leave the inner loop when the unit is done
+        do {                                                 // symbols that start inside the current window
+            const uint32_t info = wr->peek();
+            const uint32_t tot = (info >> 8) & 63;
+            wr->consume(tot);
+            uint32_t adv;                                    // blocks to move on by
+            if (__builtin_expect((info & kSymEob) == 0, 1)) {
+                // A coefficient (run r, then the value) or sixteen zeros (r = 15): both move on by r + 1.  The
+                // pair is handed to the sink in both cases and simply not counted for a zero run: no branch,
+                // and one definition of the sink's registers per iteration.
+                const uint32_t isc = (info >> 15) & 1;       // 1 for a coefficient
+                const uint32_t k2 = k + ((info >> 4) & 15);
+                const uint32_t kk = k2 < Se ? k2 : Se;       // a run past the band is an error for a coefficient; stay in bounds
+                bad |= (k2 - kk) & (0u - isc);
+                sink->emit(base + kk, ((int32_t)info >> 16) * (1 << Al), isc);
+                k = k2 + 1;
+                adv = (Se - k) >> 31;                        // 1 if k > Se (k <= 80)
+            } else {                                         // end of band, run of 2^r + extra blocks; no code at all has length 0
+                bad |= (tot - 1) >> 31;
+                adv = (1u << ((info >> 4) & 15)) + (info >> 16);
+            }
+            if (adv != 0) {
+                adv = adv < left ? adv : left;
+                left = bad ? 0 : left - adv;                 // stop at the first damaged block
+                window_end = left ? 64 : 0;
+                col += adv; k = Ss;
+                while (col >= mcu_w) { col -= mcu_w; row++; }
+                base = (row * bw + col) * 64;
+            }
+        } while (wr->o < window_end);
+    }
+    sink->flush();
+    bad |= wr->overrun() ? 1u : 0u;
     return bad ? kEFormat : kOk;
 }
 

@@ -259,8 +259,57 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     __syncthreads();
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x);
-    int rc = decode_ac_first(&wr, L.ls, L.plane[0], R.masks + uni((uint64_t)R.mask_off[ig]));
+    CoefSink sink;
+    sink.init(L.plane[0], threadIdx.x);
+    int rc = decode_ac_first(&wr, L.ls, &sink);
     if (rc != kOk) R.status[un.img] = rc;
+}
+
+// --------------------------------------------------------------------------------------
+// k_nz_masks: after the AC first scans, before the first AC refinement scan.  For every
+// (image, component) that has refinement scans: one wavefront per block reads the block (one
+// coefficient per lane, zig-zag order) and writes, for each AC first scan of the component, the
+// mask of the positions of its band that are non-zero -- the history the refinement scans work
+// on.  grid: (chunks of kNzBlocks blocks, (image, component) pairs), 256 threads.
+// --------------------------------------------------------------------------------------
+struct ApplyUnit { uint32_t img; uint32_t comp; };
+constexpr int kApplyMaxScans = 16;
+constexpr uint32_t kNzBlocks = 256;
+constexpr int kNzMaxFirst = 8;               // AC first scans per component (they partition positions 1..63)
+
+struct NzList { uint32_t n; uint32_t pad; uint64_t off[kNzMaxFirst]; uint64_t band[kNzMaxFirst]; };   // AC first scans of one (image, component): mask plane, band
+
+__global__ void __launch_bounds__(256) k_nz_masks(DevRecord R, const ApplyUnit* __restrict__ au, const NzList* __restrict__ lists) {
+    const ApplyUnit a = au[blockIdx.y];
+    const ImgDesc* img = &R.img[a.img];
+    if (R.status[a.img] != kOk) return;
+    const uint32_t c = a.comp;
+    const uint32_t nblk = (uint32_t)img->bw[c] * img->bh[c];
+    const uint32_t first = blockIdx.x * kNzBlocks;
+    if (first >= nblk) return;
+    const NzList* L = &lists[blockIdx.y];
+    const uint32_t n = L->n;
+    const int16_t* pl = R.coef + R.coef_off[a.img];
+    for (uint32_t q = 0; q < c; q++) pl += (size_t)img->bw[q] * img->bh[q] * 64;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // a wavefront takes 64 consecutive blocks: lane i keeps the mask of block i, so that the masks leave
+    // as one contiguous 512-byte store per AC first scan
+    const uint32_t w0 = first + wave * 64;
+    if (w0 >= nblk) return;
+    const uint32_t cnt = nblk - w0 < 64 ? nblk - w0 : 64;
+    uint64_t mine = 0;
+    for (uint32_t i0 = 0; i0 < cnt; i0 += 8) {               // eight loads in flight
+        int16_t v[8];
+#pragma unroll
+        for (uint32_t j = 0; j < 8; j++) v[j] = i0 + j < cnt ? pl[(size_t)(w0 + i0 + j) * 64 + lane] : (int16_t)0;
+#pragma unroll
+        for (uint32_t j = 0; j < 8; j++) {
+            const uint64_t nz = __ballot(v[j] != 0);
+            if (lane == i0 + j) mine = nz;
+        }
+    }
+    if (lane < cnt)
+        for (uint32_t e = 0; e < n; e++) R.masks[L->off[e] + w0 + lane] = mine & L->band[e];
 }
 
 __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const Unit* __restrict__ units, uint32_t nunits) {
@@ -335,13 +384,10 @@ __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const Refine
 //   k > 0: replay the AC scans of the component in file order: first scans only extend the
 //          non-zero mask, refinement scans add a correction bit or place a new +-2^Al.
 // --------------------------------------------------------------------------------------
-struct ApplyUnit { uint32_t img; uint32_t comp; };
-
 // k_apply_prep gathers, once per (image, component), the scans that matter for refinement (AC
 // scans of the component in file order, DC refinement scans) into a compact list; k_apply then
 // runs one lane per coefficient, a workgroup covering kApplyChunk consecutive coefficients.
 struct ApplyScan { uint64_t mask_off; uint32_t slot; uint32_t data_base; uint32_t mcu_w; uint16_t ri; uint8_t Ss, Se, Ah, Al, ns, before, bpm, pad[3]; };
-constexpr int kApplyMaxScans = 16;
 struct ApplyList { uint32_t n; uint32_t pad; ApplyScan sc[kApplyMaxScans]; };
 constexpr uint32_t kApplyChunk = 4096;
 

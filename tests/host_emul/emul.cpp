@@ -86,8 +86,12 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
             } else {
                 AcTab at; actab_build(&at, rec + sd.ac_off);
                 WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &at, sd.Ah == 0, 0);
-                if (sd.Ah == 0) rc = decode_ac_first(&wr, ls, cpl[0], masks[g].data());
-                else {
+                if (sd.Ah == 0) {
+                    CoefSink sink; sink.init(cpl[0], 0);
+                    rc = decode_ac_first(&wr, ls, &sink);
+                    // what k_nz_masks does on the device: the scan's non-zero mask, read back from the coefficients
+                    for (size_t blk = 0; blk < plane; blk++) masks[g][blk] = nz_mask_of_block(cpl[0] + blk * 64, sd.Ss, sd.Se);
+                } else {
                     HistPlanes hp; hp.n = sd.nhist;
                     for (int q = 0; q < kMaxHist; q++) hp.p[q] = masks[q < sd.nhist ? sd.hist[q] : 0].data();
                     rc = skim_ac_refine(&wr, ls, hp, masks[g].data(), masks[g].data() + 3 * plane);
