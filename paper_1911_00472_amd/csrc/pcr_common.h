@@ -112,4 +112,15 @@ PCR_HD int zigzag_natural(int k) {
     return row * 8 + (d - row);
 }
 
+// Pointer to the unstuffed entropy data as the decoders read it.  The data was written by an earlier
+// kernel and is never written while a decoder runs, so on the device it is addressed as constant memory:
+// loads through such a pointer at a wave-uniform address are scalar loads, which arrive straight in
+// scalar registers and are only waited for at their first use.
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) uint32_t* StreamPtr;
+#else
+typedef const uint32_t* StreamPtr;
+#endif
+PCR_HD StreamPtr stream_ptr(const uint32_t* p) { return (StreamPtr)p; }
+
 }  // namespace pcr

@@ -245,7 +245,7 @@ PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
 }
 
 struct WindowReader {
-    const uint32_t* p;          // words after n1
+    StreamPtr p;                // words after n1
     const AcTab* tab;
     uint32_t w0, w1, w2, n0, n1;
     uint32_t o;                 // offset of the next unread bit inside the window (may run past 63 until normalised)
@@ -258,7 +258,7 @@ struct WindowReader {
     PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const AcTab* t, bool first_scan, uint32_t lane_id) {
         tab = t; first = first_scan; lane = lane_id;
         mis_bits = (byte_off & 3) * 8;
-        p = words + (byte_off >> 2);
+        p = stream_ptr(words + (byte_off >> 2));
         w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
         o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits;
         fill();
@@ -326,7 +326,7 @@ PCR_HD uint32_t pack_dc(uint32_t e, uint32_t win) {          // e = (length << 4
 }
 
 struct DcWindowReader {
-    const uint32_t* p;
+    StreamPtr p;
     const DcTab* tab[kMaxComp];
     uint32_t w0, w1, w2, n0, n1;
     uint32_t o, wbase, mis_bits, total_bits, lane;
@@ -337,7 +337,7 @@ struct DcWindowReader {
                      int ntables, uint32_t lane_id) {
         tab[0] = t0; tab[1] = t1; tab[2] = t2; ntab = ntables; lane = lane_id;
         mis_bits = (byte_off & 3) * 8;
-        p = words + (byte_off >> 2);
+        p = stream_ptr(words + (byte_off >> 2));
         w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
         o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits;
         vinfo[0] = vinfo[1] = vinfo[2] = 0;

@@ -186,6 +186,10 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kmax) {
 // on the SIMDs.  The host orders units by decreasing byte length (longest first).
 // --------------------------------------------------------------------------------------
 constexpr int kEntropyLanes = 64;
+// clean32 and hist64 are R.clean and R.masks again, as separate restrict-qualified kernel arguments: the
+// kernels only read the unstuffed data and the history planes of EARLIER scans, and knowing that nothing
+// written here aliases them lets the compiler fetch them with scalar loads (straight into scalar
+// registers, waited for at the first use) instead of vector loads followed by a read-first-lane.
 
 struct UnitSetup {
     const uint32_t* words;        // segment base, unit start and length for the window readers
@@ -195,7 +199,7 @@ struct UnitSetup {
     bool ok;
 };
 
-PCR_D void unit_setup(const DevRecord& R, const Unit& un, UnitSetup* L) {
+PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __restrict__ clean32, UnitSetup* L) {
     L->ok = false;
     const ImgDesc* img = &R.img[un.img];
     if (R.status[un.img] != kOk || un.scan >= img->nscans) return;
@@ -221,16 +225,17 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, UnitSetup* L) {
         ls.hs[j] = uni((uint32_t)img->hs[c]); ls.vs[j] = uni((uint32_t)img->vs[c]); ls.bw[j] = uni((uint32_t)img->bw[c]);
         L->plane[j] = base + (c == 0 ? poff[0] : (c == 1 ? poff[1] : poff[2]));
     }
-    L->words = reinterpret_cast<const uint32_t*>(R.clean + uni(clean_base(sd->data_off)));
+    L->words = clean32 + (uni(clean_base(sd->data_off)) >> 2);
     L->byte_off = uni(b0); L->nbytes = uni(b1 > b0 ? b1 - b0 : 0);
     L->ok = true;
 }
 
-__global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits) {
+__global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
+        const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {
     __shared__ DcTab tabs[kMaxComp];
     const Unit un = units[blockIdx.x];
     UnitSetup L;
-    unit_setup(R, un, &L);
+    unit_setup(R, un, clean32, &L);
     if (!L.ok) return;
     const ScanDesc* sd = &R.scan[(size_t)un.img * R.G + un.scan];
     const uint32_t o0 = sd->dc_off[0], o1 = L.ls.ns > 1 ? sd->dc_off[1] : o0, o2 = L.ls.ns > 2 ? sd->dc_off[2] : o0;
@@ -248,11 +253,12 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     if (rc != kOk) R.status[un.img] = rc;
 }
 
-__global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits) {
+__global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
+        const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {
     __shared__ AcTab tab;
     const Unit un = units[blockIdx.x];
     UnitSetup L;
-    unit_setup(R, un, &L);
+    unit_setup(R, un, clean32, &L);
     if (!L.ok) return;
     const size_t ig = (size_t)un.img * R.G + un.scan;
     if (threadIdx.x == 0) actab_build(&tab, R.rec + R.scan[ig].ac_off);
@@ -312,11 +318,12 @@ __global__ void __launch_bounds__(256) k_nz_masks(DevRecord R, const ApplyUnit* 
         for (uint32_t e = 0; e < n; e++) R.masks[L->off[e] + w0 + lane] = mine & L->band[e];
 }
 
-__global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const Unit* __restrict__ units, uint32_t nunits) {
+__global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
+        const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {
     __shared__ AcTab tab;
     const Unit un = units[blockIdx.x];
     UnitSetup L;
-    unit_setup(R, un, &L);
+    unit_setup(R, un, clean32, &L);
     if (!L.ok) return;
     const size_t ig = (size_t)un.img * R.G + un.scan;
     const ScanDesc* sd = &R.scan[ig];
@@ -330,7 +337,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     HistPlanes hp;
     hp.n = sd->nhist;
 #pragma unroll
-    for (int q = 0; q < kMaxHist; q++) hp.p[q] = R.masks + uni((uint64_t)R.mask_off[(size_t)un.img * R.G + (q < hp.n ? sd->hist[q] : 0)]);
+    for (int q = 0; q < kMaxHist; q++) hp.p[q] = hist64 + uni((uint64_t)R.mask_off[(size_t)un.img * R.G + (q < hp.n ? sd->hist[q] : 0)]);
     hp.n = uni(hp.n);
     const ImgDesc* img = &R.img[un.img];
     const int c = sd->comp[0];

@@ -234,17 +234,19 @@ int run_entropy_stages(pcr_record* r, int k, hipStream_t s) {
     if (r->n_masks) hipLaunchKernelGGL(k_fill_zero, dim3(1024), dim3(256), 0, s, (uint4*)r->d.masks, (r->n_masks * 8 + 15) / 16);
     mark(r, PCR_STAGE_UNSTUFF, s);
     bool masks_done = false;
+    const uint32_t* c32 = reinterpret_cast<const uint32_t*>(r->d.clean);
+    const uint64_t* h64 = r->d.masks;
     for (auto& l : plan->levels) {
         const dim3 grid(l.n), block(kEntropyLanes);
-        if (l.kind == kDcFirst) { hipLaunchKernelGGL(k_dc_first, grid, block, 0, s, r->d, l.d_units, l.n); mark(r, PCR_STAGE_DC_FIRST, s); }
-        else if (l.kind == kAcFirst) { hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n); mark(r, PCR_STAGE_AC_FIRST, s); }
+        if (l.kind == kDcFirst) { hipLaunchKernelGGL(k_dc_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_DC_FIRST, s); }
+        else if (l.kind == kAcFirst) { hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_AC_FIRST, s); }
         else {
             if (!masks_done) {                               // history of the refinement scans: what the AC first scans made non-zero
                 hipLaunchKernelGGL(k_nz_masks, dim3(plan->nz_grid_x, plan->n_apply), dim3(256), 0, s, r->d, plan->d_apply, plan->d_nz);
                 mark(r, PCR_STAGE_NZ_MASKS, s);
                 masks_done = true;
             }
-            hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n);
+            hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64);
             mark(r, PCR_STAGE_AC_REFINE, s);
             hipLaunchKernelGGL(k_refine_blocks, dim3(l.refine_grid_x, l.n_refine), dim3(256), 0, s, r->d, l.d_refine);
             mark(r, PCR_STAGE_REFINE_BLOCKS, s);
