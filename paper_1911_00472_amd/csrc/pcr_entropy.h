@@ -232,7 +232,7 @@ PCR_HD uint32_t bits_at(uint32_t w0, uint32_t w1, uint32_t w2, int j) {      // 
 // sign-extended here); otherwise refinement (size 1 = one sign bit).  An end-of-band symbol
 // (size 0, run r < 15) is followed by r bits of run length in both.
 constexpr uint32_t kSymCoef = 0x8000u, kSymEob = 0x4000u;
-constexpr uint32_t kSymInvalid = kSymEob;                    // "end of band" of length 0: what an AC first scan sees where no code matches
+constexpr uint32_t kSymInvalid = kSymEob;                    // "end of band" of length 0: what the AC decoders see where no code matches
 
 PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
     const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
@@ -294,13 +294,14 @@ struct WindowReader {
         if (__builtin_expect(info == 0, 0)) {                // a code longer than 8 bits, or garbage
             const uint32_t win = bits_at(w0, w1, w2, (int)o);
             const uint32_t e = ac_long_code(tab, win);
-            info = e ? pack_symbol(e, win, first) : (first ? kSymInvalid : 0u);
+            info = e ? pack_symbol(e, win, first) : kSymInvalid;
         }
         return info;
     }
     PCR_HD void consume(uint32_t n) { o += n; }
     PCR_HD uint32_t position() const { return wbase + o - mis_bits; }       // bits consumed since the unit's first bit
     PCR_HD bool overrun() const { return wbase + o > total_bits; }
+    PCR_HD uint32_t overrun_bit() const { return (total_bits - (wbase + o)) >> 31; }   // the same as 0 / 1, without a compare (streams are < 2^31 bits)
 };
 
 // Per-lane parameters of the unit being decoded (all in registers).
@@ -467,7 +468,7 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
     while (left != 0) {
         if (wr->exhausted()) {
             sink->flush();
-            bad |= wr->overrun() ? 1u : 0u;                  // never walk far beyond the unit's data
+            bad |= wr->overrun_bit();                        // never walk far beyond the unit's data
             wr->refill();
         }
         uint32_t window_end = 64;                            // set to 0 to leave the inner loop when the unit is done
@@ -502,7 +503,7 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
         } while (wr->o < window_end);
     }
     sink->flush();
-    bad |= wr->overrun() ? 1u : 0u;
+    bad |= wr->overrun_bit();
     return bad ? kEFormat : kOk;
 }
 
@@ -527,20 +528,19 @@ PCR_HD uint64_t take_correction_bits(BitReader* br, int n) {    // n <= 63; firs
     return out;
 }
 
+// History planes of a refinement scan: masks written for the earlier AC scans of the component whose
+// band overlaps.  Entries beyond n repeat entry 0, so that the first three can be OR-ed without a test.
 struct HistPlanes { const uint64_t* p[kMaxHist]; int n; };
 
-PCR_HD uint64_t hist_at(const HistPlanes& hp, size_t blk) {
-    uint64_t h = 0;
-    if (hp.n > 0) h |= hp.p[0][blk];
-    if (hp.n > 1) h |= hp.p[1][blk];
-    if (hp.n > 2) h |= hp.p[2][blk];
-    if (hp.n > 3) h |= hp.p[3][blk];
-    if (hp.n > 4) h |= hp.p[4][blk];
-    if (hp.n > 5) h |= hp.p[5][blk];
-    return h;
+struct HistWords { uint64_t a, b, c; };                       // three planes' words of one block, OR-ed only when used
+PCR_HD HistWords hist_fetch(const HistPlanes& hp, uint32_t blk) {
+    HistWords w; w.a = hp.p[0][blk]; w.b = hp.p[1][blk]; w.c = hp.p[2][blk];
+    if (__builtin_expect(hp.n > 3, 0)) w.a |= hp.p[3][blk] | hp.p[4][blk] | hp.p[5][blk];
+    return w;
 }
+PCR_HD uint64_t hist_at(const HistPlanes& hp, uint32_t blk) { const HistWords w = hist_fetch(hp, blk); return w.a | w.b | w.c; }
 
-// Phase 1 (serial, one lane per unit): walk the scan only as far as needed to know where
+// Phase 1 (serial, one wavefront per unit): walk the scan only as far as needed to know where
 // every block starts.  For each symbol that means: the code (length, run, size), the position
 // the run ends on -- found on the zero-history mask -- and the NUMBER of correction bits in
 // between -- a population count on the non-zero-history mask; the sign and correction bits are
@@ -548,50 +548,60 @@ PCR_HD uint64_t hist_at(const HistPlanes& hp, size_t blk) {
 //   nzout  positions that become non-zero in this scan (later scans need them as history),
 //   start  bit offset of the block inside the unit (low 32 bits) and the end-of-band run still
 //          pending when the block starts (high 32 bits).
-// Masks are kept as 32-bit halves: the lanes' ALUs are 32 bits wide.
+// The history of the next block is fetched while the current one is decoded.  Conditions are kept
+// as integer arithmetic and single compares: a boolean widened to an integer, or two conditions
+// and-ed together, cost the compiler a detour through the vector unit or through 64-bit lane masks.
 PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes& hp, uint64_t* nzout, uint64_t* start) {
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     const uint64_t band = band_mask(ls.Ss, ls.Se);
-    uint32_t m = ls.mcu0;
-    uint32_t row = m / mcu_w, col = m % mcu_w;
+    uint32_t left = ls.mcu1 - ls.mcu0;                       // blocks still to do
+    uint32_t row = ls.mcu0 / mcu_w, col = ls.mcu0 % mcu_w;
+    uint32_t blk = row * bw + col;
     uint32_t eobrun = 0;                                     // blocks still covered by an end-of-band run
     uint32_t bad = 0;
-    while (m < ls.mcu1) {
-        const size_t blk = (size_t)row * bw + col;
+    HistWords hnext = hist_fetch(hp, blk);
+    while (left != 0) {
+        uint64_t h = (hnext.a | hnext.b | hnext.c) & band;                           // already non-zero, not yet passed
+        uint64_t z = h ^ band;                               // still zero, not yet passed
+        const uint32_t here = blk;
+        // the block after this one, and its history (the last block fetches its own again)
         if (++col == mcu_w) { col = 0; row++; }
-        start[blk] = ((uint64_t)eobrun << 32) | wr->position();
-        uint64_t h = hist_at(hp, blk) & band;                // already non-zero, not yet passed
-        uint64_t z = ~h & band;                              // still zero, not yet passed
+        left--;
+        blk = left ? row * bw + col : here;
+        hnext = hist_fetch(hp, blk);
+        start[here] = ((uint64_t)eobrun << 32) | wr->position();
         uint64_t newm = 0;
-        uint32_t open = eobrun == 0;                         // symbols are read only outside an end-of-band run
-        while (open && (z | h)) {
-            const uint32_t info = wr->symbol();
-            const int s = (int)(info & 15), r = (int)((info >> 4) & 15);
-            uint32_t tot = (info >> 8) & 63;
-            if (__builtin_expect(s == 1, 1)) {               // a new +-1: pass r zeros, take the next one
-                for (int q = 0; q < r; q++) z &= z - 1;
-                bad |= (uint32_t)(z == 0);                   // no place left for it
-                const uint64_t bit = z & (0 - z);
-                const uint64_t below = bit - 1;              // (z == 0: everything; the unit is abandoned anyway)
-                tot += (uint32_t)__builtin_popcountll(h & below);                   // code, sign, corrections passed
-                h &= ~below; z &= ~bit; newm |= bit;
-            } else if ((s == 0) & (r == 15)) {               // sixteen zeros (or to the end of the band)
-                for (int q = 0; q < 15; q++) z &= z - 1;
-                const uint64_t bit = z & (0 - z);
-                const uint64_t below = bit - 1;              // z == 0: all ones
-                tot += (uint32_t)__builtin_popcountll(h & below);
-                h &= ~below; z &= ~bit;
-            } else {                                         // end of band (run): the rest is corrections
-                bad |= (uint32_t)((info == 0) | (s > 1));
-                eobrun = (1u << r) + (info >> 16);
-                open = 0;
+        if (eobrun == 0) {                                   // symbols are read only outside an end-of-band run
+            while ((z | h) != 0) {
+                const uint32_t info = wr->symbol();
+                const uint32_t s = info & 15, r = (info >> 4) & 15;
+                uint32_t tot = (info >> 8) & 63;
+                if (__builtin_expect((info & kSymEob) == 0, 1)) {
+                    // s = 1: a new +-1 after r zeros; s = 0 (r = 15): sixteen zeros.  Either way pass r zeros,
+                    // then one more position; only s = 1 marks it.
+                    for (uint32_t q = r; q != 0; q--) z &= z - 1;
+                    const uint64_t bit = z & (0 - z);        // z == 0: no place left (an error for s = 1) -> bit = 0, below = all ones
+                    const uint64_t below = bit - 1;
+                    bad |= (bit ? 0u : s) | (s >> 1);        // sizes above 1 do not exist in a refinement scan
+                    tot += (uint32_t)__builtin_popcountll(h & below);               // code, sign, corrections passed
+                    h &= ~below; z ^= bit;
+                    newm |= s ? bit : 0;
+                } else {                                     // end of band (run): the rest of the block is corrections
+                    bad |= tot ? 0u : 1u;                    // no code at all
+                    eobrun = (1u << r) + (info >> 16);
+                    tot += (uint32_t)__builtin_popcountll(h);
+                    h = 0; z = 0;
+                }
+                wr->consume(tot);
             }
-            wr->consume(tot);
+            eobrun -= eobrun ? 1u : 0u;                      // the run counted this block
+        } else {
+            wr->consume((uint32_t)__builtin_popcountll(h));
+            eobrun--;
         }
-        if (eobrun > 0) { wr->consume((uint32_t)__builtin_popcountll(h)); eobrun--; }
-        nzout[blk] = newm;
-        bad |= (uint32_t)wr->overrun();
-        m = bad ? ls.mcu1 : m + 1;                           // stop at the first damaged block
+        nzout[here] = newm;
+        bad |= wr->overrun_bit();
+        left = bad ? 0 : left;                               // stop at the first damaged block
     }
     return bad ? kEFormat : kOk;
 }

@@ -337,7 +337,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     HistPlanes hp;
     hp.n = sd->nhist;
 #pragma unroll
-    for (int q = 0; q < kMaxHist; q++) hp.p[q] = hist64 + uni((uint64_t)R.mask_off[(size_t)un.img * R.G + (q < hp.n ? sd->hist[q] : 0)]);
+    for (int q = 0; q < kMaxHist; q++) hp.p[q] = hist64 + uni((uint64_t)R.mask_off[(size_t)un.img * R.G + sd->hist[q < hp.n ? q : 0]]);
     hp.n = uni(hp.n);
     const ImgDesc* img = &R.img[un.img];
     const int c = sd->comp[0];
@@ -397,6 +397,19 @@ __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const Refine
 struct ApplyScan { uint64_t mask_off; uint32_t slot; uint32_t data_base; uint32_t mcu_w; uint16_t ri; uint8_t Ss, Se, Ah, Al, ns, before, bpm, pad[3]; };
 struct ApplyList { uint32_t n; uint32_t pad; ApplyScan sc[kApplyMaxScans]; };
 constexpr uint32_t kApplyChunk = 4096;
+
+// DC refinement of the block at (row, col) of a component with sampling hs x vs: the block's bit sits at
+// a position fixed by the scan's block order and restart intervals; returns the bit (0 / 1), 0 for a block
+// a non-interleaved scan does not visit.
+PCR_D uint32_t dc_refinement_bit(const DevRecord& R, const ApplyScan& S, uint32_t row, uint32_t col, uint32_t hs, uint32_t vs, bool covered) {
+    uint32_t m, within;
+    if (S.ns > 1) { m = (row / vs) * S.mcu_w + col / hs; within = S.before + (row % vs) * hs + col % hs; }
+    else { if (!covered) return 0; m = row * S.mcu_w + col; within = 0; }
+    const uint32_t ivl = S.ri ? m / S.ri : 0;
+    const uint32_t bit = (m - ivl * S.ri) * S.bpm + within;
+    const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + S.data_base);
+    return (uint32_t)dc_refine_bit(words, R.ivl_start[S.slot + ivl], bit);
+}
 
 __global__ void __launch_bounds__(64) k_apply_prep(DevRecord R, const ApplyUnit* __restrict__ au, uint32_t nau, uint32_t kmax, ApplyList* lists) {
     const uint32_t u = blockIdx.x * 64 + threadIdx.x;
@@ -461,13 +474,7 @@ __global__ void __launch_bounds__(256) k_apply(DevRecord R, const ApplyUnit* __r
             const ApplyScan& S = L.sc[e];
             if (S.Ss == 0) {
                 if (k != 0) continue;
-                uint32_t m, within;
-                if (S.ns > 1) { m = (row / vs) * S.mcu_w + col / hs; within = S.before + (row % vs) * hs + col % hs; }
-                else { if (!covered) continue; m = row * S.mcu_w + col; within = 0; }
-                const uint32_t ivl = S.ri ? m / S.ri : 0;
-                const uint32_t bit = (m - ivl * S.ri) * S.bpm + within;
-                const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + S.data_base);
-                if (dc_refine_bit(words, R.ivl_start[S.slot + ivl], bit)) v |= (int16_t)(1 << S.Al);
+                if (dc_refinement_bit(R, S, row, col, hs, vs, covered)) v |= (int16_t)(1 << S.Al);
             } else if (k != 0 && covered) {
                 const uint64_t* mk = R.masks + S.mask_off;
                 const uint64_t nz = mk[b];
@@ -516,7 +523,15 @@ typedef short short8 __attribute__((ext_vector_type(8)));
 // w / d as (w * recip16(d)) >> 16, exact while w * d < 65536
 PCR_HD uint32_t recip16(uint32_t d) { return d ? 65536u / d + 1u : 0u; }
 
-__global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out) {
+// Refinement is applied here, on the way in: the coefficient planes hold what the first scans wrote, and a
+// lane that loads eight coefficients replays the component's refinement scans on them from the mask planes
+// (exactly what k_apply does for the coefficient export, which is the only caller that still needs the
+// refined values in memory).  lists / list_idx: the per-(image, component) scan lists of k_apply_prep and
+// their index by image * 3 + component (-1: nothing to refine); both null if no scan <= k refines.
+// kRefine = false compiles the replay out (scan groups without refinement scans: fewer registers).
+template <bool kRefine>
+__global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out,
+                                               const ApplyList* __restrict__ lists, const int32_t* __restrict__ list_idx) {
     // samples of the strip, one row-major plane per component (so that neighbouring pixels are
     // neighbouring words of LDS in phase 4); rows are one word longer than the data, which
     // spreads the rows of a block over the banks for phase 2
@@ -524,6 +539,7 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
     __shared__ __attribute__((aligned(16))) float qz[kMaxComp][64];       // quantiser steps, zig-zag order
     __shared__ __attribute__((aligned(16))) uint16_t zoff[kMaxComp][64];  // zig-zag index -> offset of that position from the block's corner in `tile`
     __shared__ ImgDesc img;                                // this image's descriptor, read many times below
+    __shared__ ApplyList rl[kMaxComp];                     // refinement scan lists of the components (n = 0: none)
     const PixelTile t = tiles[blockIdx.x];
     {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.img[t.img]);
@@ -564,6 +580,14 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
             flat[c] = c < nc && zmx[c] <= 1;
         }
     }
+    for (uint32_t c = 0; kRefine && c < nc; c++) {
+        const int32_t li = list_idx ? list_idx[t.img * kMaxComp + c] : -1;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&rl[c]);
+        if (li >= 0) {
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(&lists[li]);
+            for (uint32_t e = threadIdx.x; e < sizeof(ApplyList) / 4; e += 256) dst[e] = src[e];
+        } else if (threadIdx.x == 0) dst[0] = 0;           // n = 0
+    }
     for (uint32_t e = threadIdx.x; e < nc * 64; e += 256) {
         const uint32_t c = e >> 6, k = e & 63;
         const uint8_t* q = R.rec + img.qoff[img.tq[c]];
@@ -582,12 +606,20 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
             const uint32_t tt = (threadIdx.x - 64 * c) & 255;
             const int16_t* pl = coef + (size_t)first_blk[c] * 64;
             float* plane = tile + poff[c];
+            const uint32_t nref = kRefine ? rl[c].n : 0;   // scans to replay (0: the planes are final)
+            const uint32_t hsc = img.hs[c], vsc = img.vs[c], cwc = img.cw[c], chc = img.ch[c];
+            const uint32_t nplane = bwi[c] * (uint32_t)img.bh[c];
             if (flat[c]) {                                 // only the DC: the block is flat
                 const float q0 = qz[c][0];
                 for (uint32_t lb = tt; lb < nbc[c]; lb += 256) {
                     const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
-                    const float dc = (float)pl[((size_t)lrow * bwi[c] + lcol) * 64] * q0;
-                    plane[lrow * 8 * pstr[c] + lcol * 8] = clamp255(dc * 0.125f + 128.f);
+                    int dcv = pl[((size_t)lrow * bwi[c] + lcol) * 64];
+                    if (kRefine && nref != 0) {
+                        const uint32_t brow = t.mcu_row * vsc + lrow, bcol = col0 * hsc + lcol;
+                        for (uint32_t e = 0; e < nref; e++)
+                            if (rl[c].sc[e].Ss == 0 && dc_refinement_bit(R, rl[c].sc[e], brow, bcol, hsc, vsc, brow < chc && bcol < cwc)) dcv |= 1 << rl[c].sc[e].Al;
+                    }
+                    plane[lrow * 8 * pstr[c] + lcol * 8] = clamp255((float)dcv * q0 * 0.125f + 128.f);
                 }
                 continue;
             }
@@ -595,7 +627,44 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
                 const uint32_t lb = w >> 3, ch = w & 7;
                 const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
                 short8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (ch * 8 < zmx[c]) v = *reinterpret_cast<const short8*>(pl + ((size_t)lrow * bwi[c] + lcol) * 64 + ch * 8);
+                if (ch * 8 < zmx[c]) {
+                    v = *reinterpret_cast<const short8*>(pl + ((size_t)lrow * bwi[c] + lcol) * 64 + ch * 8);
+                    if (kRefine && nref != 0) {
+                        const uint32_t brow = t.mcu_row * vsc + lrow, bcol = col0 * hsc + lcol;
+                        const bool covered = brow < chc && bcol < cwc;
+                        const uint32_t b = brow * bwi[c] + bcol;       // block index in the component's plane
+                        const uint32_t k0 = ch * 8;
+                        uint64_t h = 0;
+                        for (uint32_t e = 0; e < nref; e++) {
+                            const ApplyScan& S = rl[c].sc[e];
+                            if (S.Ss == 0) {
+                                if (k0 == 0 && dc_refinement_bit(R, S, brow, bcol, hsc, vsc, covered)) v[0] |= (short)(1 << S.Al);
+                            } else if (covered) {
+                                const uint64_t* mk = R.masks + S.mask_off;
+                                const uint64_t nz = mk[b];
+                                if (S.Ah != 0 && k0 <= S.Se && k0 + 7 >= S.Ss) {
+                                    // the eight positions k0..k0+7 as 8-bit fields; the correction bit of position
+                                    // k0 + j is number (non-zero history positions below it) of the scan's string
+                                    const uint64_t band = band_mask(S.Ss, S.Se), hb = h & band;
+                                    const uint32_t h8 = (uint32_t)(hb >> k0) & 0xFF, n8 = (uint32_t)((nz & band) >> k0) & 0xFF;
+                                    const uint32_t s8 = (uint32_t)(mk[nplane + b] >> k0) & 0xFF;
+                                    const uint32_t below = (uint32_t)__builtin_popcountll(hb & ((1ull << k0) - 1));
+                                    const uint32_t c8 = (uint32_t)(mk[2 * (size_t)nplane + b] >> below) & 0xFF;
+                                    const int p1 = 1 << S.Al;
+#pragma unroll
+                                    for (int j = 0; j < 8; j++) {
+                                        const uint32_t bj = 1u << j;
+                                        const int vj = v[j];
+                                        if (h8 & bj) {
+                                            if ((c8 >> __builtin_popcount(h8 & (bj - 1))) & 1) v[j] = (short)(vj > 0 ? vj + p1 : vj - p1);
+                                        } else if (n8 & bj) v[j] = (short)((s8 & bj) ? p1 : -p1);
+                                    }
+                                }
+                                h |= nz;
+                            }
+                        }
+                    }
+                }
                 float* blk = plane + lrow * 8 * pstr[c] + lcol * 8;               // sample (0,0) of the block
                 const float4 qa = *reinterpret_cast<const float4*>(&qz[c][ch * 8]), qb = *reinterpret_cast<const float4*>(&qz[c][ch * 8 + 4]);
                 const uint4 zo = *reinterpret_cast<const uint4*>(&zoff[c][ch * 8]);

@@ -27,7 +27,7 @@ struct LevelList {
 
 struct Plan {                               // launch geometry for one scan group k
     std::vector<LevelList> levels;
-    ApplyUnit* d_apply = nullptr; ApplyList* d_apply_lists = nullptr; NzList* d_nz = nullptr; uint32_t n_apply = 0, apply_grid_x = 0, nz_grid_x = 0;
+    ApplyUnit* d_apply = nullptr; ApplyList* d_apply_lists = nullptr; NzList* d_nz = nullptr; int32_t* d_list_idx = nullptr; uint32_t n_apply = 0, apply_grid_x = 0, nz_grid_x = 0;
 };
 
 template <class T> int dev_alloc(T** p, size_t count) {
@@ -159,6 +159,9 @@ int build_plan(pcr_record* r, int k, Plan** out) {
     if (plan.n_apply) {
         int rc = dev_upload(&plan.d_apply, apply); if (rc) return rc;
         rc = dev_upload(&plan.d_nz, nz); if (rc) return rc;
+        std::vector<int32_t> list_idx((size_t)n * kMaxComp, -1);
+        for (size_t e = 0; e < apply.size(); e++) list_idx[(size_t)apply[e].img * kMaxComp + apply[e].comp] = (int32_t)e;
+        rc = dev_upload(&plan.d_list_idx, list_idx); if (rc) return rc;
         rc = dev_alloc(&plan.d_apply_lists, apply.size()); if (rc) return rc;
     }
     auto ins = r->plans.emplace(k, plan);
@@ -172,6 +175,7 @@ void free_plans(pcr_record* r) {
         if (kv.second.d_apply) (void)hipFree(kv.second.d_apply);
         if (kv.second.d_apply_lists) (void)hipFree(kv.second.d_apply_lists);
         if (kv.second.d_nz) (void)hipFree(kv.second.d_nz);
+        if (kv.second.d_list_idx) (void)hipFree(kv.second.d_list_idx);
     }
     r->plans.clear();
 }
@@ -219,10 +223,13 @@ int add_call_times(const CallTiming& c, double* ms, uint32_t* marks) {
 }
 
 // Steps 1-5 of the path (index .. entropy decode + refinement) for scans 1..k.
-int run_entropy_stages(pcr_record* r, int k, hipStream_t s) {
+// refine_in_memory: also run k_apply, which leaves the refined coefficients in the planes (the coefficient
+// export needs that; the pixel kernel replays the refinement itself from the lists of k_apply_prep).
+int run_entropy_stages(pcr_record* r, int k, hipStream_t s, bool refine_in_memory, Plan** plan_out) {
     Plan* plan = nullptr;
     int rc = build_plan(r, k, &plan);
     if (rc) return rc;
+    *plan_out = plan;
     const uint32_t n = r->hdr.n;
     call_begin(r, s);
     hipLaunchKernelGGL(k_index, dim3(k), dim3(256), 0, s, r->d, (uint32_t)k);
@@ -254,7 +261,8 @@ int run_entropy_stages(pcr_record* r, int k, hipStream_t s) {
     }
     if (plan->n_apply) {
         hipLaunchKernelGGL(k_apply_prep, dim3((plan->n_apply + 63) / 64), dim3(64), 0, s, r->d, plan->d_apply, plan->n_apply, (uint32_t)k, plan->d_apply_lists);
-        hipLaunchKernelGGL(k_apply, dim3(plan->apply_grid_x, plan->n_apply), dim3(256), 0, s, r->d, plan->d_apply, plan->d_apply_lists);
+        if (refine_in_memory)
+            hipLaunchKernelGGL(k_apply, dim3(plan->apply_grid_x, plan->n_apply), dim3(256), 0, s, r->d, plan->d_apply, plan->d_apply_lists);
     }
     if (plan->n_apply) mark(r, PCR_STAGE_REFINE_APPLY, s);
     if (hipGetLastError() != hipSuccess) { r->cur = nullptr; return PCR_E_DEVICE; }
@@ -581,7 +589,8 @@ int pcr_decode_coefficients(pcr_record* r, int k, int16_t* d_coef, void* stream)
     if (rc) return rc;
     HIP_TRY(hipSetDevice(r->device));
     hipStream_t s = (hipStream_t)stream;
-    rc = run_entropy_stages(r, k, s);
+    Plan* plan = nullptr;
+    rc = run_entropy_stages(r, k, s, true, &plan);
     if (rc) return rc;
     call_end(r);
     hipLaunchKernelGGL(k_export_natural, dim3(2048), dim3(256), 0, s, r->d.coef, d_coef, (size_t)r->coef_off[r->hdr.n]);
@@ -596,9 +605,13 @@ int pcr_decode_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* strea
     if (cap < r->out_off[r->hdr.n]) return PCR_E_RANGE;
     HIP_TRY(hipSetDevice(r->device));
     hipStream_t s = (hipStream_t)stream;
-    rc = run_entropy_stages(r, k, s);
+    Plan* plan = nullptr;
+    rc = run_entropy_stages(r, k, s, false, &plan);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_pixel, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out);
+    if (plan->n_apply)
+        hipLaunchKernelGGL(k_pixel<true>, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx);
+    else
+        hipLaunchKernelGGL(k_pixel<false>, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr);
     mark(r, PCR_STAGE_PIXEL, s);
     call_end(r);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;

@@ -93,7 +93,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                     for (size_t blk = 0; blk < plane; blk++) masks[g][blk] = nz_mask_of_block(cpl[0] + blk * 64, sd.Ss, sd.Se);
                 } else {
                     HistPlanes hp; hp.n = sd.nhist;
-                    for (int q = 0; q < kMaxHist; q++) hp.p[q] = masks[q < sd.nhist ? sd.hist[q] : 0].data();
+                    for (int q = 0; q < kMaxHist; q++) hp.p[q] = masks[sd.hist[q < sd.nhist ? q : 0]].data();
                     rc = skim_ac_refine(&wr, ls, hp, masks[g].data(), masks[g].data() + 3 * plane);
                     if (rc) return rc;
                     // phase 2: every block of this interval on its own
