@@ -241,6 +241,7 @@ PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
     const int value = (first && s) ? extend(extra, s) : (int)extra;
     // bit 15: the symbol carries a coefficient; bit 14: it is an end-of-band symbol
     const uint32_t flags = (s ? kSymCoef : 0u) | ((s == 0 && r != 15) ? kSymEob : 0u);
+    if (!first && s > 1) return kSymInvalid;                 // sizes above 1 do not exist in a refinement scan
     return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | ((uint32_t)r << 4) | (uint32_t)s;
 }
 
@@ -540,11 +541,71 @@ PCR_HD HistWords hist_fetch(const HistPlanes& hp, uint32_t blk) {
 }
 PCR_HD uint64_t hist_at(const HistPlanes& hp, uint32_t blk) { const HistWords w = hist_fetch(hp, blk); return w.a | w.b | w.c; }
 
+// Zero table of one block: entry n describes the n-th position of the band that is still zero
+// when the scan reaches the block (n = 0, 1, ...; zig-zag order):
+//     position (bits 0..5) | non-zero-history positions below it (bits 8..14) | kZtLast | kZtSentinel
+// kZtLast marks the entry after which nothing is left in the block: the last zero if no non-zero
+// history position follows it, and every sentinel.  Entries from number-of-zeros on are sentinels:
+// "no such zero", with the count field = all non-zero-history positions of the band.
+// With the table the serial decoder does no bit arithmetic per symbol: a run of r zeros followed by
+// a new coefficient is "index += r, read the entry, index += 1", and the number of correction bits
+// to step over is the difference of two count fields.  The 64 lanes build the table in a handful
+// of vector instructions (a prefix count of the two masks and one permute); lane i also keeps the
+// index of ITS position so that the positions that were taken can be read back as a mask.
+constexpr uint32_t kZtLast = 1u << 16, kZtSentinel = 1u << 17;
+
+struct ZeroTable {
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint32_t ventry, vindex;                                  // lane n: entry n; lane i: table index of position i (64 if not a zero)
+#else
+    uint32_t entry[64], index[64];
+#endif
+    PCR_HD void build(uint64_t h, uint64_t z, uint32_t nzeros, uint32_t ncorr, uint32_t lane) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(z >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)z, 0));
+        const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(h >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)h, 0));
+        const bool iz = (z >> lane) & 1;
+        const uint32_t last = (rank + 1 == nzeros && below == ncorr) ? kZtLast : 0u;
+        const uint32_t data = iz ? (lane | (below << 8) | last) : (lane | (ncorr << 8) | kZtLast | kZtSentinel);
+        const uint32_t dest = iz ? rank : nzeros + (lane - rank);       // a permutation of the 64 lanes
+        ventry = (uint32_t)__builtin_amdgcn_ds_permute((int)(dest * 4), (int)data);
+        vindex = iz ? rank : 64u;
+#else
+        (void)lane;
+        uint32_t rank = 0, below = 0;
+        for (uint32_t i = 0; i < 64; i++) {
+            const bool iz = (z >> i) & 1;
+            const uint32_t last = (rank + 1 == nzeros && below == ncorr) ? kZtLast : 0u;
+            const uint32_t data = iz ? (i | (below << 8) | last) : (i | (ncorr << 8) | kZtLast | kZtSentinel);
+            entry[iz ? rank : nzeros + (i - rank)] = data;
+            index[i] = iz ? rank : 64u;
+            rank += iz; below += (h >> i) & 1;
+        }
+#endif
+    }
+    PCR_HD uint32_t at(uint32_t n) const {                    // n <= 63
+#if defined(__HIP_DEVICE_COMPILE__)
+        return (uint32_t)__builtin_amdgcn_readlane((int)ventry, (int)n);
+#else
+        return entry[n];
+#endif
+    }
+    // positions whose table index is set in `taken`
+    PCR_HD uint64_t positions(uint64_t taken) const {
+#if defined(__HIP_DEVICE_COMPILE__)
+        return __ballot(vindex < 64u && ((taken >> vindex) & 1));
+#else
+        uint64_t m = 0;
+        for (uint32_t i = 0; i < 64; i++) if (index[i] < 64u && ((taken >> index[i]) & 1)) m |= 1ull << i;
+        return m;
+#endif
+    }
+};
+
 // Phase 1 (serial, one wavefront per unit): walk the scan only as far as needed to know where
-// every block starts.  For each symbol that means: the code (length, run, size), the position
-// the run ends on -- found on the zero-history mask -- and the NUMBER of correction bits in
-// between -- a population count on the non-zero-history mask; the sign and correction bits are
-// stepped over, not read.  Per block it writes
+// every block starts.  For each symbol that means: the code (length, run, size), the zero the run
+// ends on and the NUMBER of correction bits stepped over on the way -- both read from the block's
+// zero table; the sign and correction bits themselves are not read.  Per block it writes
 //   nzout  positions that become non-zero in this scan (later scans need them as history),
 //   start  bit offset of the block inside the unit (low 32 bits) and the end-of-band run still
 //          pending when the block starts (high 32 bits).
@@ -560,9 +621,10 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
     uint32_t eobrun = 0;                                     // blocks still covered by an end-of-band run
     uint32_t bad = 0;
     HistWords hnext = hist_fetch(hp, blk);
+    ZeroTable zt;
     while (left != 0) {
-        uint64_t h = (hnext.a | hnext.b | hnext.c) & band;                           // already non-zero, not yet passed
-        uint64_t z = h ^ band;                               // still zero, not yet passed
+        const uint64_t h = (hnext.a | hnext.b | hnext.c) & band;   // already non-zero
+        const uint64_t z = h ^ band;                         // still zero
         const uint32_t here = blk;
         // the block after this one, and its history (the last block fetches its own again)
         if (++col == mcu_w) { col = 0; row++; }
@@ -570,33 +632,40 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
         blk = left ? row * bw + col : here;
         hnext = hist_fetch(hp, blk);
         start[here] = ((uint64_t)eobrun << 32) | wr->position();
+        const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
         uint64_t newm = 0;
         if (eobrun == 0) {                                   // symbols are read only outside an end-of-band run
-            while ((z | h) != 0) {
-                const uint32_t info = wr->symbol();
-                const uint32_t s = info & 15, r = (info >> 4) & 15;
-                uint32_t tot = (info >> 8) & 63;
-                if (__builtin_expect((info & kSymEob) == 0, 1)) {
-                    // s = 1: a new +-1 after r zeros; s = 0 (r = 15): sixteen zeros.  Either way pass r zeros,
-                    // then one more position; only s = 1 marks it.
-                    for (uint32_t q = r; q != 0; q--) z &= z - 1;
-                    const uint64_t bit = z & (0 - z);        // z == 0: no place left (an error for s = 1) -> bit = 0, below = all ones
-                    const uint64_t below = bit - 1;
-                    bad |= (bit ? 0u : s) | (s >> 1);        // sizes above 1 do not exist in a refinement scan
-                    tot += (uint32_t)__builtin_popcountll(h & below);               // code, sign, corrections passed
-                    h &= ~below; z ^= bit;
-                    newm |= s ? bit : 0;
-                } else {                                     // end of band (run): the rest of the block is corrections
-                    bad |= tot ? 0u : 1u;                    // no code at all
-                    eobrun = (1u << r) + (info >> 16);
-                    tot += (uint32_t)__builtin_popcountll(h);
-                    h = 0; z = 0;
+            if (band != 0) {                                 // (always: a scan has at least one position)
+                const uint32_t nzeros = (uint32_t)__builtin_popcountll(z);
+                zt.build(h, z, nzeros, ncorr, wr->lane);
+                uint64_t taken = 0;                          // table indices that received a new coefficient
+                uint32_t idx = 0, passed = 0;                // next table index; correction bits stepped over so far
+                uint32_t info, e;
+                do {
+                    // One straight line for all three kinds of symbol.  A new +-1 after r zeros (kSymCoef) or
+                    // sixteen zeros (r = 15): r zeros are passed, then one more position.  End of band: as if the
+                    // run went past every zero -- the sentinel entry says "all corrections, nothing left".
+                    info = wr->symbol();
+                    const uint32_t len = (info >> 8) & 63, r = (info >> 4) & 15;
+                    idx += r + ((info >> 8) & 64);           // kSymEob is bit 14: + 64
+                    idx = idx < nzeros ? idx : nzeros;       // past the last zero: the sentinel
+                    e = zt.at(idx);
+                    taken |= (uint64_t)((info >> 15) & 1) << idx;
+                    idx++;
+                    const uint32_t upto = (e >> 8) & 127;
+                    wr->consume(len + upto - passed);        // code, sign, corrections passed
+                    passed = upto;
+                } while ((e & kZtLast) == 0);
+                if (info & kSymEob) {                        // the block ended with an end-of-band (run) symbol
+                    bad |= (info & 0x3F00) ? 0u : 1u;        // length 0: no code at all
+                    eobrun = (1u << ((info >> 4) & 15)) + (info >> 16);
                 }
-                wr->consume(tot);
+                bad |= (uint32_t)(taken >> nzeros) & 1;      // a new coefficient with no zero left to take
+                newm = zt.positions(taken);
             }
             eobrun -= eobrun ? 1u : 0u;                      // the run counted this block
         } else {
-            wr->consume((uint32_t)__builtin_popcountll(h));
+            wr->consume(ncorr);
             eobrun--;
         }
         nzout[here] = newm;
