@@ -428,23 +428,25 @@ PCR_HD int decode_dc_first(DcWindowReader* wr, const LaneScan& ls, int tj0, int 
 // ---------------------------------------------------------------------------------------
 struct CoefSink {
     int16_t* plane;
+    int Al;                                                   // values are stored shifted left by this
     uint32_t lane, cnt;
     uint32_t vidx; int vval;                                  // device: one pending store per lane below cnt
-    PCR_HD void init(int16_t* p, uint32_t lane_id) { plane = p; lane = lane_id; cnt = 0; vidx = 0; vval = 0; }
-    PCR_HD void emit(uint32_t elem, int value, uint32_t count_it) {   // count_it = 0: the pair is dropped
+    PCR_HD void init(int16_t* p, int al, uint32_t lane_id) { plane = p; Al = al; lane = lane_id; cnt = 0; vidx = 0; vval = 0; }
+    // word: packed symbol word, its value in the top 16 bits; count_it = 0: the pair is dropped
+    PCR_HD void emit(uint32_t elem, int word, uint32_t count_it) {
 #if defined(__HIP_DEVICE_COMPILE__)
         // lane `cnt` of the two registers takes the pair (the lane select travels in m0: a vector
         // instruction of this chip reads at most one scalar register besides it)
         asm volatile("s_mov_b32 m0, %4\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
-                     : "+v"(vidx), "+v"(vval) : "s"(elem), "s"(value), "s"(cnt) : "m0");
+                     : "+v"(vidx), "+v"(vval) : "s"(elem), "s"(word), "s"(cnt) : "m0");
         cnt += count_it;
 #else
-        if (count_it) plane[elem] = (int16_t)value;
+        if (count_it) plane[elem] = (int16_t)((word >> 16) * (1 << Al));
 #endif
     }
     PCR_HD void flush() {
 #if defined(__HIP_DEVICE_COMPILE__)
-        if (lane < cnt) plane[vidx] = (int16_t)vval;
+        if (lane < cnt) plane[vidx] = (int16_t)((vval >> 16) * (1 << Al));
         cnt = 0;
 #endif
     }
@@ -474,26 +476,22 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
         }
         uint32_t window_end = 64;                            // set to 0 to leave the inner loop when the unit is done
         do {                                                 // symbols that start inside the current window
+            // One straight line for every symbol: a coefficient (run r, then the value) and sixteen zeros
+            // (r = 15) both move on by r + 1; the packed word goes to the sink in every case and is simply
+            // not counted unless it carries a coefficient.  Only a block change leaves the line.
             const uint32_t info = wr->peek();
-            const uint32_t tot = (info >> 8) & 63;
-            wr->consume(tot);
-            uint32_t adv;                                    // blocks to move on by
-            if (__builtin_expect((info & kSymEob) == 0, 1)) {
-                // A coefficient (run r, then the value) or sixteen zeros (r = 15): both move on by r + 1.  The
-                // pair is handed to the sink in both cases and simply not counted for a zero run: no branch,
-                // and one definition of the sink's registers per iteration.
-                const uint32_t isc = (info >> 15) & 1;       // 1 for a coefficient
-                const uint32_t k2 = k + ((info >> 4) & 15);
-                const uint32_t kk = k2 < Se ? k2 : Se;       // a run past the band is an error for a coefficient; stay in bounds
-                bad |= (k2 - kk) & (0u - isc);
-                sink->emit(base + kk, ((int32_t)info >> 16) * (1 << Al), isc);
-                k = k2 + 1;
-                adv = (Se - k) >> 31;                        // 1 if k > Se (k <= 80)
-            } else {                                         // end of band, run of 2^r + extra blocks; no code at all has length 0
-                bad |= (tot - 1) >> 31;
-                adv = (1u << ((info >> 4) & 15)) + (info >> 16);
-            }
-            if (adv != 0) {
+            wr->consume((info >> 8) & 63);
+            const uint32_t k2 = k + ((info >> 4) & 15);
+            sink->emit(base + (k2 & 63), (int)info, (info >> 15) & 1);   // & 63: stays inside the block whatever the stream says
+            k = k2 + 1;
+            if (__builtin_expect(((info & kSymEob) | ((Se - k) >> 31)) != 0, 0)) {
+                uint32_t adv = 1;                            // blocks to move on by
+                if (info & kSymEob) {                        // end of band, run of 2^r + extra blocks; no code at all has length 0
+                    bad |= (info & 0x3F00) ? 0u : 1u;
+                    adv = (1u << ((info >> 4) & 15)) + (info >> 16);
+                } else {
+                    bad |= (k2 > Se) ? ((info >> 15) & 1) : 0u;   // a coefficient beyond the band
+                }
                 adv = adv < left ? adv : left;
                 left = bad ? 0 : left - adv;                 // stop at the first damaged block
                 window_end = left ? 64 : 0;

@@ -266,7 +266,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x);
     CoefSink sink;
-    sink.init(L.plane[0], threadIdx.x);
+    sink.init(L.plane[0], L.ls.Al, threadIdx.x);
     int rc = decode_ac_first(&wr, L.ls, &sink);
     if (rc != kOk) R.status[un.img] = rc;
 }

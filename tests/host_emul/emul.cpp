@@ -87,7 +87,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 AcTab at; actab_build(&at, rec + sd.ac_off);
                 WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &at, sd.Ah == 0, 0);
                 if (sd.Ah == 0) {
-                    CoefSink sink; sink.init(cpl[0], 0);
+                    CoefSink sink; sink.init(cpl[0], ls.Al, 0);
                     rc = decode_ac_first(&wr, ls, &sink);
                     // what k_nz_masks does on the device: the scan's non-zero mask, read back from the coefficients
                     for (size_t blk = 0; blk < plane; blk++) masks[g][blk] = nz_mask_of_block(cpl[0] + blk * 64, sd.Ss, sd.Se);
