@@ -134,7 +134,6 @@ int pcr_decode_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size
  *   INDEX_PARSE    k_index + k_parse                 UNSTUFF        k_unstuff + zero fills
  *   DC_FIRST, AC_FIRST, AC_REFINE, REFINE_BLOCKS     one interval per launch of that kernel
  *   REFINE_APPLY   k_apply_prep + k_apply            PIXEL          k_pixel
- *   NZ_MASKS       k_nz_masks (history masks for the refinement scans, once per call that has any)
  * pcr_last_stage_ms: milliseconds per stage of the last pcr_decode_batch / pcr_decode_coefficients
  *   call on this handle (stage_ms: host, PCR_NUM_STAGES floats).
  * pcr_stage_ms_history: the same summed over the calls since timing was switched on (the 64 most
@@ -143,7 +142,7 @@ int pcr_decode_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size
  * Both block until the calls they report have finished; PCR_E_ARG if nothing was recorded. */
 enum { PCR_STAGE_INDEX_PARSE = 0, PCR_STAGE_UNSTUFF = 1, PCR_STAGE_DC_FIRST = 2, PCR_STAGE_AC_FIRST = 3,
        PCR_STAGE_AC_REFINE = 4, PCR_STAGE_REFINE_BLOCKS = 5, PCR_STAGE_REFINE_APPLY = 6, PCR_STAGE_PIXEL = 7,
-       PCR_STAGE_NZ_MASKS = 8, PCR_NUM_STAGES = 9 };
+       PCR_NUM_STAGES = 8 };
 int pcr_enable_stage_timing(pcr_record* rec, int on);
 int pcr_last_stage_ms(pcr_record* rec, float* stage_ms);
 int pcr_stage_ms_history(pcr_record* rec, double* sum_ms, uint32_t* launches, uint32_t* calls);

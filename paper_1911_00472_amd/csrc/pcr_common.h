@@ -19,7 +19,7 @@ namespace pcr {
 enum : int { kOk = 0, kEArg = -1, kEFormat = -2, kETruncated = -3, kEUnsupported = -4, kERange = -5, kENoMem = -6, kEDevice = -7 };
 
 constexpr int kMaxComp = 3;
-constexpr int kMaxHist = 6;      // earlier AC scans of the same component a refinement scan may build on
+constexpr int kMaxHist = 6;      // earlier AC refinement scans of the same component a refinement scan may build on
 
 // One image of a record (frame header + tables that hold for the whole image).
 struct ImgDesc {
@@ -48,7 +48,7 @@ struct ScanDesc {
     uint16_t ri;                           // restart interval in MCUs of this scan (0 = none)
     uint8_t ns, comp[kMaxComp];
     uint8_t Ss, Se, Ah, Al;
-    uint8_t nhist, hist[kMaxHist];         // AC refinement: earlier AC scans (indices) of the same component
+    uint8_t nhist, hist[kMaxHist];         // AC refinement: earlier AC REFINEMENT scans (indices) of the same component and band
     uint8_t valid;
     uint32_t mcus;                         // MCUs in this scan
     uint32_t mcu_w;                        // MCUs per row of this scan

@@ -527,17 +527,40 @@ PCR_HD uint64_t take_correction_bits(BitReader* br, int n) {    // n <= 63; firs
     return out;
 }
 
-// History planes of a refinement scan: masks written for the earlier AC scans of the component whose
-// band overlaps.  Entries beyond n repeat entry 0, so that the first three can be OR-ed without a test.
-struct HistPlanes { const uint64_t* p[kMaxHist]; int n; };
+// History of a refinement scan: the positions of its band that are non-zero when it starts.  What the
+// AC first scans made non-zero is read back from the coefficient plane (one coefficient per lane, a ballot
+// of "!= 0"); what earlier refinement scans added is in the nzout planes they wrote (p[0..n)).
+struct HistPlanes { const int16_t* coef; const uint64_t* p[kMaxHist]; int n; };
 
-struct HistWords { uint64_t a, b, c; };                       // three planes' words of one block, OR-ed only when used
-PCR_HD HistWords hist_fetch(const HistPlanes& hp, uint32_t blk) {
-    HistWords w; w.a = hp.p[0][blk]; w.b = hp.p[1][blk]; w.c = hp.p[2][blk];
-    if (__builtin_expect(hp.n > 3, 0)) w.a |= hp.p[3][blk] | hp.p[4][blk] | hp.p[5][blk];
+struct HistWords {                                            // one block's history, combined only when used
+    uint64_t a, b, c;
+#if defined(__HIP_DEVICE_COMPILE__)
+    int16_t mine;                                             // this lane's coefficient of the block
+#else
+    uint64_t first;
+#endif
+};
+PCR_HD HistWords hist_fetch(const HistPlanes& hp, uint32_t blk, uint32_t lane) {
+    HistWords w; w.a = 0; w.b = 0; w.c = 0;
+    if (hp.n > 0) {                                           // entries beyond n repeat entry 0
+        w.a = hp.p[0][blk]; w.b = hp.p[1][blk]; w.c = hp.p[2][blk];
+        if (__builtin_expect(hp.n > 3, 0)) w.a |= hp.p[3][blk] | hp.p[4][blk] | hp.p[5][blk];
+    }
+#if defined(__HIP_DEVICE_COMPILE__)
+    w.mine = hp.coef[(size_t)blk * 64 + lane];
+#else
+    (void)lane;
+    w.first = nz_mask_of_block(hp.coef + (size_t)blk * 64, 0, 63);
+#endif
     return w;
 }
-PCR_HD uint64_t hist_at(const HistPlanes& hp, uint32_t blk) { const HistWords w = hist_fetch(hp, blk); return w.a | w.b | w.c; }
+PCR_HD uint64_t hist_combine(const HistWords& w) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return w.a | w.b | w.c | __ballot(w.mine != 0);
+#else
+    return w.a | w.b | w.c | w.first;
+#endif
+}
 
 // Zero table of one block: entry n describes the n-th position of the band that is still zero
 // when the scan reaches the block (n = 0, 1, ...; zig-zag order):
@@ -606,11 +629,12 @@ struct ZeroTable {
 // zero table; the sign and correction bits themselves are not read.  Per block it writes
 //   nzout  positions that become non-zero in this scan (later scans need them as history),
 //   start  bit offset of the block inside the unit (low 32 bits) and the end-of-band run still
-//          pending when the block starts (high 32 bits).
+//          pending when the block starts (high 32 bits),
+//   hist   the history mask it worked on (restricted to the band).
 // The history of the next block is fetched while the current one is decoded.  Conditions are kept
 // as integer arithmetic and single compares: a boolean widened to an integer, or two conditions
 // and-ed together, cost the compiler a detour through the vector unit or through 64-bit lane masks.
-PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes& hp, uint64_t* nzout, uint64_t* start) {
+PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes& hp, uint64_t* nzout, uint64_t* start, uint64_t* hist_out) {
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     const uint64_t band = band_mask(ls.Ss, ls.Se);
     uint32_t left = ls.mcu1 - ls.mcu0;                       // blocks still to do
@@ -618,17 +642,18 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
     uint32_t blk = row * bw + col;
     uint32_t eobrun = 0;                                     // blocks still covered by an end-of-band run
     uint32_t bad = 0;
-    HistWords hnext = hist_fetch(hp, blk);
+    HistWords hnext = hist_fetch(hp, blk, wr->lane);
     ZeroTable zt;
     while (left != 0) {
-        const uint64_t h = (hnext.a | hnext.b | hnext.c) & band;   // already non-zero
+        const uint64_t h = hist_combine(hnext) & band;        // already non-zero
         const uint64_t z = h ^ band;                         // still zero
         const uint32_t here = blk;
         // the block after this one, and its history (the last block fetches its own again)
         if (++col == mcu_w) { col = 0; row++; }
         left--;
         blk = left ? row * bw + col : here;
-        hnext = hist_fetch(hp, blk);
+        hnext = hist_fetch(hp, blk, wr->lane);
+        hist_out[here] = h;                                  // phase 2 and the refinement replay work on the same history
         start[here] = ((uint64_t)eobrun << 32) | wr->position();
         const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
         uint64_t newm = 0;

@@ -150,18 +150,23 @@ PCR_HD int parse_region(const uint8_t* rec, uint32_t p, uint32_t end, int first_
             if (ns > 1) { sd->mcu_w = img->mcux; sd->mcus = (uint32_t)img->mcux * img->mcuy; }
             else { sd->mcu_w = img->cw[sd->comp[0]]; sd->mcus = (uint32_t)img->cw[sd->comp[0]] * img->ch[sd->comp[0]]; }
             sd->data_off = p; sd->data_len = end - p;
-            // earlier AC scans of the same component whose band overlaps: they define which
-            // coefficients are already non-zero when a refinement scan starts
+            // A refinement scan works on the positions of its band that are already non-zero.  Those made
+            // non-zero by AC first scans are read back from the coefficients; those added by earlier
+            // refinement scans of the component (not applied to the coefficients yet) come from the masks
+            // those scans leave, so they are listed here.
             sd->nhist = 0;
             if (sd->Ss > 0) {
+                bool has_first = false;
                 for (uint32_t q = 0; q < g; q++) {
                     const ScanDesc* e = &scans[q];
                     if (e->Ss > 0 && e->comp[0] == sd->comp[0] && e->Ss <= sd->Se && sd->Ss <= e->Se) {
+                        if (e->Ah == 0) { has_first = true; continue; }
                         if (sd->nhist >= kMaxHist) return kEUnsupported;
                         sd->hist[sd->nhist++] = (uint8_t)q;
                     }
                 }
-                if (sd->Ah > 0 && sd->nhist == 0) return kEFormat;
+                if (sd->Ah > 0 && !has_first) return kEFormat;
+                if (sd->Ah == 0) sd->nhist = 0;            // first scans need no history
             }
             sd->valid = 1;
             return kOk;

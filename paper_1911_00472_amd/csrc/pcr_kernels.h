@@ -271,52 +271,8 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     if (rc != kOk) R.status[un.img] = rc;
 }
 
-// --------------------------------------------------------------------------------------
-// k_nz_masks: after the AC first scans, before the first AC refinement scan.  For every
-// (image, component) that has refinement scans: one wavefront per block reads the block (one
-// coefficient per lane, zig-zag order) and writes, for each AC first scan of the component, the
-// mask of the positions of its band that are non-zero -- the history the refinement scans work
-// on.  grid: (chunks of kNzBlocks blocks, (image, component) pairs), 256 threads.
-// --------------------------------------------------------------------------------------
 struct ApplyUnit { uint32_t img; uint32_t comp; };
 constexpr int kApplyMaxScans = 16;
-constexpr uint32_t kNzBlocks = 256;
-constexpr int kNzMaxFirst = 8;               // AC first scans per component (they partition positions 1..63)
-
-struct NzList { uint32_t n; uint32_t pad; uint64_t off[kNzMaxFirst]; uint64_t band[kNzMaxFirst]; };   // AC first scans of one (image, component): mask plane, band
-
-__global__ void __launch_bounds__(256) k_nz_masks(DevRecord R, const ApplyUnit* __restrict__ au, const NzList* __restrict__ lists) {
-    const ApplyUnit a = au[blockIdx.y];
-    const ImgDesc* img = &R.img[a.img];
-    if (R.status[a.img] != kOk) return;
-    const uint32_t c = a.comp;
-    const uint32_t nblk = (uint32_t)img->bw[c] * img->bh[c];
-    const uint32_t first = blockIdx.x * kNzBlocks;
-    if (first >= nblk) return;
-    const NzList* L = &lists[blockIdx.y];
-    const uint32_t n = L->n;
-    const int16_t* pl = R.coef + R.coef_off[a.img];
-    for (uint32_t q = 0; q < c; q++) pl += (size_t)img->bw[q] * img->bh[q] * 64;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    // a wavefront takes 64 consecutive blocks: lane i keeps the mask of block i, so that the masks leave
-    // as one contiguous 512-byte store per AC first scan
-    const uint32_t w0 = first + wave * 64;
-    if (w0 >= nblk) return;
-    const uint32_t cnt = nblk - w0 < 64 ? nblk - w0 : 64;
-    uint64_t mine = 0;
-    for (uint32_t i0 = 0; i0 < cnt; i0 += 8) {               // eight loads in flight
-        int16_t v[8];
-#pragma unroll
-        for (uint32_t j = 0; j < 8; j++) v[j] = i0 + j < cnt ? pl[(size_t)(w0 + i0 + j) * 64 + lane] : (int16_t)0;
-#pragma unroll
-        for (uint32_t j = 0; j < 8; j++) {
-            const uint64_t nz = __ballot(v[j] != 0);
-            if (lane == i0 + j) mine = nz;
-        }
-    }
-    if (lane < cnt)
-        for (uint32_t e = 0; e < n; e++) R.masks[L->off[e] + w0 + lane] = mine & L->band[e];
-}
 
 __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
         const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {
@@ -335,6 +291,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
         for (uint32_t e = threadIdx.x; e < sizeof(AcTab) / 4; e += kEntropyLanes) dst[e] = src[e];
     }
     HistPlanes hp;
+    hp.coef = L.plane[0];
     hp.n = sd->nhist;
 #pragma unroll
     for (int q = 0; q < kMaxHist; q++) hp.p[q] = hist64 + uni((uint64_t)R.mask_off[(size_t)un.img * R.G + sd->hist[q < hp.n ? q : 0]]);
@@ -345,7 +302,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     uint64_t* mk = R.masks + uni((uint64_t)R.mask_off[ig]);
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tab, false, threadIdx.x);
-    int rc = skim_ac_refine(&wr, L.ls, hp, mk, mk + 3 * plane);
+    int rc = skim_ac_refine(&wr, L.ls, hp, mk, mk + 3 * plane, mk + 4 * plane);
     if (rc != kOk) R.status[un.img] = rc;
 }
 
@@ -373,9 +330,8 @@ __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const Refine
     const uint32_t bw = img->bw[c];
     const size_t blk = (size_t)(b / cw) * bw + (b % cw);
     const size_t plane = (size_t)bw * img->bh[c];
-    uint64_t h = 0;
-    for (int q = 0; q < sd->nhist; q++) h |= R.masks[R.mask_off[(size_t)a.img * R.G + sd->hist[q]] + blk];
     uint64_t* mk = R.masks + R.mask_off[ig];
+    const uint64_t h = mk[4 * plane + blk];                  // the history phase 1 worked on
     const uint32_t ivl = sd->ri ? b / sd->ri : 0;
     const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + clean_base(sd->data_off));
     uint64_t sgn, cb;
@@ -437,7 +393,7 @@ __global__ void __launch_bounds__(64) k_apply_prep(DevRecord R, const ApplyUnit*
             }
             if (j < 0) continue;
             e.before = (uint8_t)before; e.bpm = (uint8_t)bpm;
-        } else if (sd->comp[0] != c) continue;
+        } else if (sd->comp[0] != c || sd->Ah == 0) continue;  // AC first scans are in the planes already
         L->sc[n++] = e;
     }
     L->n = n;
@@ -469,18 +425,14 @@ __global__ void __launch_bounds__(256) k_apply(DevRecord R, const ApplyUnit* __r
         const bool covered = row < ch && col < cw;
         const int16_t v0 = pl[idx];
         int16_t v = v0;
-        uint64_t h = 0;
         for (uint32_t e = 0; e < n; e++) {
             const ApplyScan& S = L.sc[e];
             if (S.Ss == 0) {
                 if (k != 0) continue;
                 if (dc_refinement_bit(R, S, row, col, hs, vs, covered)) v |= (int16_t)(1 << S.Al);
-            } else if (k != 0 && covered) {
-                const uint64_t* mk = R.masks + S.mask_off;
-                const uint64_t nz = mk[b];
-                if (S.Ah != 0 && k >= S.Ss && k <= S.Se)
-                    v = refine_apply(v, k, h & band_mask(S.Ss, S.Se), nz, mk[plane + b], mk[2 * plane + b], S.Al);
-                h |= nz;
+            } else if (k != 0 && covered && k >= S.Ss && k <= S.Se) {
+                const uint64_t* mk = R.masks + S.mask_off;   // planes: nzout, sign, cbits, start, history
+                v = refine_apply(v, k, mk[4 * plane + b], mk[b], mk[plane + b], mk[2 * plane + b], S.Al);
             }
         }
         if (v != v0) pl[idx] = v;
@@ -634,33 +586,29 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
                         const bool covered = brow < chc && bcol < cwc;
                         const uint32_t b = brow * bwi[c] + bcol;       // block index in the component's plane
                         const uint32_t k0 = ch * 8;
-                        uint64_t h = 0;
                         for (uint32_t e = 0; e < nref; e++) {
                             const ApplyScan& S = rl[c].sc[e];
                             if (S.Ss == 0) {
                                 if (k0 == 0 && dc_refinement_bit(R, S, brow, bcol, hsc, vsc, covered)) v[0] |= (short)(1 << S.Al);
-                            } else if (covered) {
-                                const uint64_t* mk = R.masks + S.mask_off;
-                                const uint64_t nz = mk[b];
-                                if (S.Ah != 0 && k0 <= S.Se && k0 + 7 >= S.Ss) {
-                                    // the eight positions k0..k0+7 as 8-bit fields; the correction bit of position
-                                    // k0 + j is number (non-zero history positions below it) of the scan's string
-                                    const uint64_t band = band_mask(S.Ss, S.Se), hb = h & band;
-                                    const uint32_t h8 = (uint32_t)(hb >> k0) & 0xFF, n8 = (uint32_t)((nz & band) >> k0) & 0xFF;
-                                    const uint32_t s8 = (uint32_t)(mk[nplane + b] >> k0) & 0xFF;
-                                    const uint32_t below = (uint32_t)__builtin_popcountll(hb & ((1ull << k0) - 1));
-                                    const uint32_t c8 = (uint32_t)(mk[2 * (size_t)nplane + b] >> below) & 0xFF;
-                                    const int p1 = 1 << S.Al;
+                            } else if (covered && k0 <= S.Se && k0 + 7 >= S.Ss) {
+                                // the eight positions k0..k0+7 as 8-bit fields of the scan's masks (all restricted to
+                                // its band); the correction bit of position k0 + j is number (non-zero history
+                                // positions below it) of the scan's string
+                                const uint64_t* mk = R.masks + S.mask_off;       // planes: nzout, sign, cbits, start, history
+                                const uint64_t hb = mk[4 * (size_t)nplane + b];
+                                const uint32_t h8 = (uint32_t)(hb >> k0) & 0xFF, n8 = (uint32_t)(mk[b] >> k0) & 0xFF;
+                                const uint32_t s8 = (uint32_t)(mk[nplane + b] >> k0) & 0xFF;
+                                const uint32_t below = (uint32_t)__builtin_popcountll(hb & ((1ull << k0) - 1));
+                                const uint32_t c8 = (uint32_t)(mk[2 * (size_t)nplane + b] >> below) & 0xFF;
+                                const int p1 = 1 << S.Al;
 #pragma unroll
-                                    for (int j = 0; j < 8; j++) {
-                                        const uint32_t bj = 1u << j;
-                                        const int vj = v[j];
-                                        if (h8 & bj) {
-                                            if ((c8 >> __builtin_popcount(h8 & (bj - 1))) & 1) v[j] = (short)(vj > 0 ? vj + p1 : vj - p1);
-                                        } else if (n8 & bj) v[j] = (short)((s8 & bj) ? p1 : -p1);
-                                    }
+                                for (int j = 0; j < 8; j++) {
+                                    const uint32_t bj = 1u << j;
+                                    const int vj = v[j];
+                                    if (h8 & bj) {
+                                        if ((c8 >> __builtin_popcount(h8 & (bj - 1))) & 1) v[j] = (short)(vj > 0 ? vj + p1 : vj - p1);
+                                    } else if (n8 & bj) v[j] = (short)((s8 & bj) ? p1 : -p1);
                                 }
-                                h |= nz;
                             }
                         }
                     }

@@ -27,7 +27,7 @@ struct LevelList {
 
 struct Plan {                               // launch geometry for one scan group k
     std::vector<LevelList> levels;
-    ApplyUnit* d_apply = nullptr; ApplyList* d_apply_lists = nullptr; NzList* d_nz = nullptr; int32_t* d_list_idx = nullptr; uint32_t n_apply = 0, apply_grid_x = 0, nz_grid_x = 0;
+    ApplyUnit* d_apply = nullptr; ApplyList* d_apply_lists = nullptr; int32_t* d_list_idx = nullptr; uint32_t n_apply = 0, apply_grid_x = 0;
 };
 
 template <class T> int dev_alloc(T** p, size_t count) {
@@ -105,7 +105,7 @@ int build_plan(pcr_record* r, int k, Plan** out) {
     struct Item { Unit u; uint32_t bytes; };
     std::vector<std::vector<Item>> lists((size_t)r->max_level * kNumKinds);
     std::vector<std::vector<RefineScan>> rlists(r->max_level); std::vector<uint32_t> rmax(r->max_level, 0);
-    std::vector<ApplyUnit> apply; std::vector<NzList> nz; uint32_t max_blk = 0;
+    std::vector<ApplyUnit> apply; uint32_t max_blk = 0;
     for (uint32_t i = 0; i < n; i++) {
         const uint32_t upto = std::min<uint32_t>(r->img[i].nscans, (uint32_t)k);
         bool refine[kMaxComp] = {false, false, false};
@@ -125,16 +125,6 @@ int build_plan(pcr_record* r, int k, Plan** out) {
         }
         for (int c = 0; c < r->img[i].nc; c++) if (refine[c]) {
             apply.push_back(ApplyUnit{i, (uint32_t)c});
-            NzList nl{};                                       // the component's AC first scans among scans 1..k
-            for (uint32_t g = 0; g < upto; g++) {
-                const size_t ig = (size_t)i * G + g;
-                const ScanDesc& sd = r->scan[ig];
-                if (sd.Ss > 0 && sd.Ah == 0 && sd.comp[0] == c) {
-                    if (nl.n >= (uint32_t)kNzMaxFirst) return PCR_E_UNSUPPORTED;
-                    nl.off[nl.n] = r->mask_off[ig]; nl.band[nl.n] = band_mask(sd.Ss, sd.Se); nl.n++;
-                }
-            }
-            nz.push_back(nl);
             max_blk = std::max<uint32_t>(max_blk, (uint32_t)r->img[i].bw[c] * r->img[i].bh[c]);
         }
     }
@@ -155,10 +145,8 @@ int build_plan(pcr_record* r, int k, Plan** out) {
     }
     plan.n_apply = (uint32_t)apply.size();
     plan.apply_grid_x = (max_blk * 64 + kApplyChunk - 1) / kApplyChunk;
-    plan.nz_grid_x = (max_blk + kNzBlocks - 1) / kNzBlocks;
     if (plan.n_apply) {
         int rc = dev_upload(&plan.d_apply, apply); if (rc) return rc;
-        rc = dev_upload(&plan.d_nz, nz); if (rc) return rc;
         std::vector<int32_t> list_idx((size_t)n * kMaxComp, -1);
         for (size_t e = 0; e < apply.size(); e++) list_idx[(size_t)apply[e].img * kMaxComp + apply[e].comp] = (int32_t)e;
         rc = dev_upload(&plan.d_list_idx, list_idx); if (rc) return rc;
@@ -174,7 +162,6 @@ void free_plans(pcr_record* r) {
         for (auto& l : kv.second.levels) { if (l.d_units) (void)hipFree(l.d_units); if (l.d_refine) (void)hipFree(l.d_refine); }
         if (kv.second.d_apply) (void)hipFree(kv.second.d_apply);
         if (kv.second.d_apply_lists) (void)hipFree(kv.second.d_apply_lists);
-        if (kv.second.d_nz) (void)hipFree(kv.second.d_nz);
         if (kv.second.d_list_idx) (void)hipFree(kv.second.d_list_idx);
     }
     r->plans.clear();
@@ -240,7 +227,6 @@ int run_entropy_stages(pcr_record* r, int k, hipStream_t s, bool refine_in_memor
     hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
     if (r->n_masks) hipLaunchKernelGGL(k_fill_zero, dim3(1024), dim3(256), 0, s, (uint4*)r->d.masks, (r->n_masks * 8 + 15) / 16);
     mark(r, PCR_STAGE_UNSTUFF, s);
-    bool masks_done = false;
     const uint32_t* c32 = reinterpret_cast<const uint32_t*>(r->d.clean);
     const uint64_t* h64 = r->d.masks;
     for (auto& l : plan->levels) {
@@ -248,11 +234,6 @@ int run_entropy_stages(pcr_record* r, int k, hipStream_t s, bool refine_in_memor
         if (l.kind == kDcFirst) { hipLaunchKernelGGL(k_dc_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_DC_FIRST, s); }
         else if (l.kind == kAcFirst) { hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_AC_FIRST, s); }
         else {
-            if (!masks_done) {                               // history of the refinement scans: what the AC first scans made non-zero
-                hipLaunchKernelGGL(k_nz_masks, dim3(plan->nz_grid_x, plan->n_apply), dim3(256), 0, s, r->d, plan->d_apply, plan->d_nz);
-                mark(r, PCR_STAGE_NZ_MASKS, s);
-                masks_done = true;
-            }
             hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64);
             mark(r, PCR_STAGE_AC_REFINE, s);
             hipLaunchKernelGGL(k_refine_blocks, dim3(l.refine_grid_x, l.n_refine), dim3(256), 0, s, r->d, l.d_refine);
@@ -324,7 +305,7 @@ static int finish_open(pcr_record* r) {
             const ScanDesc& sd = r->scan[ig];
             if (sd.Ss > 0) {
                 r->mask_off[ig] = nm;
-                nm += (uint64_t)d.bw[sd.comp[0]] * d.bh[sd.comp[0]] * (sd.Ah ? 4 : 1);   // refinement: nzout, sign, cbits, start
+                nm += (uint64_t)d.bw[sd.comp[0]] * d.bh[sd.comp[0]] * (sd.Ah ? 5 : 0);   // refinement: nzout, sign, cbits, start, history
                 if (sd.Ah) tab_idx[ig] = ntabs++;
             }
             uint32_t cnt = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;

@@ -65,7 +65,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
         for (size_t e = 0; e + 3 < clean.size(); e += 4) { std::swap(clean[e], clean[e + 3]); std::swap(clean[e + 1], clean[e + 2]); }   // big-endian words
         int c0 = sd.comp[0];
         size_t plane = (size_t)img.bw[c0] * img.bh[c0];
-        if (sd.Ss > 0) masks[g].assign(plane * (sd.Ah ? 4 : 1), 0);
+        if (sd.Ss > 0 && sd.Ah) masks[g].assign(plane * 5, 0);   // nzout, sign, cbits, start, history
         if (sd.Ss == 0 && sd.Ah > 0) continue;                     // DC refinement: applied below, in place
         for (uint32_t j = 0; j < nint; j++) {
             LaneScan ls;
@@ -89,18 +89,15 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 if (sd.Ah == 0) {
                     CoefSink sink; sink.init(cpl[0], ls.Al, 0);
                     rc = decode_ac_first(&wr, ls, &sink);
-                    // what k_nz_masks does on the device: the scan's non-zero mask, read back from the coefficients
-                    for (size_t blk = 0; blk < plane; blk++) masks[g][blk] = nz_mask_of_block(cpl[0] + blk * 64, sd.Ss, sd.Se);
                 } else {
-                    HistPlanes hp; hp.n = sd.nhist;
-                    for (int q = 0; q < kMaxHist; q++) hp.p[q] = masks[sd.hist[q < sd.nhist ? q : 0]].data();
-                    rc = skim_ac_refine(&wr, ls, hp, masks[g].data(), masks[g].data() + 3 * plane);
+                    HistPlanes hp; hp.n = sd.nhist; hp.coef = cpl[0];
+                    for (int q = 0; q < kMaxHist; q++) hp.p[q] = sd.nhist ? masks[sd.hist[q < sd.nhist ? q : 0]].data() : nullptr;
+                    rc = skim_ac_refine(&wr, ls, hp, masks[g].data(), masks[g].data() + 3 * plane, masks[g].data() + 4 * plane);
                     if (rc) return rc;
                     // phase 2: every block of this interval on its own
                     for (uint32_t mm = ls.mcu0; mm < ls.mcu1; mm++) {
                         size_t blk = (size_t)(mm / sd.mcu_w) * img.bw[c0] + (mm % sd.mcu_w);
-                        uint64_t hh = 0;
-                        for (int q = 0; q < sd.nhist; q++) hh |= masks[sd.hist[q]][blk];
+                        const uint64_t hh = masks[g][4 * plane + blk];
                         refine_block(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], masks[g][3 * plane + blk], &at, hh, sd.Ss, sd.Se,
                                      &masks[g][plane + blk], &masks[g][2 * plane + blk]);
                     }
@@ -116,7 +113,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
             size_t blk = (size_t)row * img.bw[c] + col;
             bool covered = row < img.ch[c] && col < img.cw[c];
             int16_t* cp = coef.data() + poff[c] + blk * 64 + kk;     // internal order: element k = zig-zag position k
-            int16_t v = *cp; uint64_t hh = 0;
+            int16_t v = *cp;
             for (uint32_t g = 0; g < img.nscans; g++) {
                 const ScanDesc& sd = sc[g];
                 if (sd.Ss == 0) {
@@ -130,10 +127,9 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                     uint32_t ivl = sd.ri ? m / sd.ri : 0, bit = (m - ivl * sd.ri) * bpm + within;
                     if (bit >= (ivls[g][ivl + 1] - ivls[g][ivl]) * 8) return kEFormat;
                     if (dc_refine_bit(reinterpret_cast<const uint32_t*>(cleans[g].data()), ivls[g][ivl], bit)) v |= (int16_t)(1 << sd.Al);
-                } else if (kk != 0 && covered && sd.comp[0] == c) {
+                } else if (kk != 0 && covered && sd.comp[0] == c && sd.Ah != 0 && kk >= sd.Ss && kk <= sd.Se) {
                     const uint64_t* mk = masks[g].data();
-                    if (sd.Ah != 0 && kk >= sd.Ss && kk <= sd.Se) v = refine_apply(v, kk, hh & band_mask(sd.Ss, sd.Se), mk[blk], mk[plane + blk], mk[2 * plane + blk], sd.Al);
-                    hh |= mk[blk];
+                    v = refine_apply(v, kk, mk[4 * plane + blk], mk[blk], mk[plane + blk], mk[2 * plane + blk], sd.Al);
                 }
             }
             *cp = v;
