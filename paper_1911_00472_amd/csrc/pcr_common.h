@@ -98,7 +98,7 @@ PCR_HD uint32_t bitrev32(uint32_t v) {
 }
 
 // zig-zag position -> natural index, by walking the anti-diagonals (row + col = d)
-PCR_HD int zigzag_natural(int k) {
+PCR_HD constexpr int zigzag_natural(int k) {
     int d = 0, first = 0;
     while (true) {                                   // find diagonal d holding position k
         int len = d < 8 ? d + 1 : 15 - d;
@@ -110,6 +110,16 @@ PCR_HD int zigzag_natural(int k) {
     // even diagonals run bottom-left -> top-right (row decreasing), odd ones the other way
     int row = (d & 1) ? lo + j : (d < 8 ? d : 7) - j;
     return row * 8 + (d - row);
+}
+
+// the same as a table, filled in at compile time by the walk above (for code that looks positions up per lane)
+struct ZigzagTable {
+    uint8_t natural[64];
+    constexpr ZigzagTable() : natural{} { for (int k = 0; k < 64; k++) natural[k] = (uint8_t)zigzag_natural(k); }
+};
+PCR_HD uint32_t zigzag_lookup(uint32_t k) {
+    constexpr ZigzagTable t{};
+    return t.natural[k];
 }
 
 // Pointer to the unstuffed entropy data as the decoders read it.  The data was written by an earlier

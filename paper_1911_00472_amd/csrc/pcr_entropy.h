@@ -313,118 +313,14 @@ struct LaneScan {
     // interleaved DC scans: per scan component j
     int ns;
     uint32_t hs[kMaxComp], vs[kMaxComp], bw[kMaxComp];
+    uint32_t poff[kMaxComp];   // element offset of each scan component's plane inside the image's coefficient buffer
 };
 
 // ---------------------------------------------------------------------------------------
-// Window reader for DC first scans: as WindowReader, but an interleaved scan switches between up
-// to three DC tables (one per component), so every lane looks its offset up in each distinct
-// table and the serial part picks the word of the table of the block it is decoding.
-// packed word: difference (16 bits, signed) << 16 | total bits (6) << 8 | category (4)
-// ---------------------------------------------------------------------------------------
-PCR_HD uint32_t pack_dc(uint32_t e, uint32_t win) {          // e = (length << 4) | category, non-zero
-    const int len = (int)(e >> 4), t = (int)(e & 15);
-    const int diff = extend(field(win, len, t), t);
-    return ((uint32_t)(diff & 0xFFFF) << 16) | ((uint32_t)(len + t) << 8) | (uint32_t)t;
-}
-
-struct DcWindowReader {
-    StreamPtr p;
-    const DcTab* tab[kMaxComp];
-    uint32_t w0, w1, w2, n0, n1;
-    uint32_t o, wbase, mis_bits, total_bits, lane;
-    uint32_t vinfo[kMaxComp];
-    int ntab;
-
-    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const DcTab* t0, const DcTab* t1, const DcTab* t2,
-                     int ntables, uint32_t lane_id) {
-        tab[0] = t0; tab[1] = t1; tab[2] = t2; ntab = ntables; lane = lane_id;
-        mis_bits = (byte_off & 3) * 8;
-        p = stream_ptr(words + (byte_off >> 2));
-        w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
-        o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits;
-        vinfo[0] = vinfo[1] = vinfo[2] = 0;
-        fill();
-    }
-    PCR_HD void fill() {
-#if defined(__HIP_DEVICE_COMPILE__)
-        const uint32_t win = bits_at(w0, w1, w2, (int)lane);
-#pragma unroll
-        for (int j = 0; j < kMaxComp; j++) {
-            if (j < ntab) { const uint32_t e = tab[j]->lut[win >> 24]; vinfo[j] = e != 0xFF ? pack_dc(e, win) : 0; }
-        }
-#endif
-    }
-    // packed word of the symbol at the current position under table j; 0 if the bits there are no code
-    PCR_HD uint32_t symbol(int j) {
-        if (o >= 64) {
-            do { w0 = w2; w1 = n0; w2 = n1; n0 = p[0]; n1 = p[1]; p += 2; o -= 64; wbase += 64; } while (o >= 64);
-            fill();
-        }
-        uint32_t info;
-#if defined(__HIP_DEVICE_COMPILE__)
-        const uint32_t v = j == 0 ? vinfo[0] : (j == 1 ? vinfo[1] : vinfo[2]);
-        info = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)o);
-#else
-        { const uint32_t win = bits_at(w0, w1, w2, (int)o); const uint32_t e = tab[j]->lut[win >> 24]; info = e != 0xFF ? pack_dc(e, win) : 0; }
-#endif
-        if (__builtin_expect(info == 0, 0)) {                // a code longer than 8 bits, or garbage
-            const uint32_t win = bits_at(w0, w1, w2, (int)o);
-            const uint32_t e = dc_code(tab[j], win);
-            info = e ? pack_dc(e, win) : 0;
-        }
-        return info;
-    }
-    PCR_HD void consume(uint32_t n) { o += n; }
-    PCR_HD bool overrun() const { return wbase + o > total_bits; }
-};
-
-// ---------------------------------------------------------------------------------------
-// DC first scan.  Non-interleaved scans visit the blocks covering the component's own
-// samples, interleaved scans the MCU-padded grid, component by component inside each MCU.
-// coef0/1/2: planes of the scan's components ([bh][bw][64], DC at element 0 of each block);
-// tj0/1/2: which of the reader's tables each scan component uses.
-// ---------------------------------------------------------------------------------------
-PCR_HD int decode_dc_first(DcWindowReader* wr, const LaneScan& ls, int tj0, int tj1, int tj2,
-                           int16_t* coef0, int16_t* coef1, int16_t* coef2) {
-    int pred[kMaxComp] = {0, 0, 0};
-    const int tj[kMaxComp] = {tj0, tj1, tj2};
-    int16_t* coefs[kMaxComp] = {coef0, coef1, coef2};
-    uint32_t my = ls.mcu0 / ls.mcu_w, mx = ls.mcu0 % ls.mcu_w;
-    uint32_t bad = 0;
-    uint32_t m = ls.mcu0;
-    while (m < ls.mcu1) {
-#pragma unroll
-        for (int j = 0; j < kMaxComp; j++) {                 // unrolled: every index below is a constant
-            if (j < ls.ns) {
-                const uint32_t hs = ls.ns > 1 ? ls.hs[j] : 1, vs = ls.ns > 1 ? ls.vs[j] : 1, bw = ls.bw[j];
-                for (uint32_t by = 0; by < vs; by++) for (uint32_t bx = 0; bx < hs; bx++) {
-                    const uint32_t info = wr->symbol(tj[j]);
-                    bad |= (uint32_t)(info == 0);
-                    wr->consume((info >> 8) & 63);
-                    pred[j] += (int32_t)info >> 16;
-                    coefs[j][((size_t)(my * vs + by) * bw + mx * hs + bx) * 64] = (int16_t)(pred[j] * (1 << ls.Al));
-                }
-            }
-        }
-        bad |= (uint32_t)wr->overrun();
-        if (++mx == ls.mcu_w) { mx = 0; my++; }
-        m = bad ? ls.mcu1 : m + 1;
-    }
-    return bad ? kEFormat : kOk;
-}
-
-// ---------------------------------------------------------------------------------------
-// AC first scan of one component, band Ss..Se.  Writes coefficient values in ZIG-ZAG order
-// inside each 64-element block (element k of a block is zig-zag position k).  Blocks skipped by
-// an end-of-band run are not touched: coefficients must be zero-filled beforehand.
-//
-// The serial part handles one symbol per loop iteration and does no memory access: a decoded
-// coefficient goes, as (element index, value), into the next free lane of two vector registers
-// (CoefSink), and the lanes store them all at once each time the bit window slides.  A window
-// of 64 bits holds at most 32 coefficient symbols (each is at least 2 bits long), so the 64
-// lanes always suffice.  Control flow is structured -- flags and loop conditions instead of
-// returns and breaks -- because the compiler turns early exits from nested loops into a state
-// variable that is tested after every symbol.
+// CoefSink: keeps memory off the serial path.  A decoded coefficient goes, as (element index, word
+// with the value in its top 16 bits), into the next free lane of two vector registers; the lanes
+// store all pending pairs at once each time the bit window slides (at most 64 symbols start
+// inside a 64-bit window, so the lanes always suffice).
 // ---------------------------------------------------------------------------------------
 struct CoefSink {
     int16_t* plane;
@@ -452,6 +348,132 @@ struct CoefSink {
     }
 };
 
+// ---------------------------------------------------------------------------------------
+// Window reader for DC first scans: as WindowReader, but an interleaved scan switches between up
+// to three DC tables (one per component), so every lane looks its offset up in each distinct
+// table and the serial part picks the word of the table of the block it is decoding.
+// packed word: difference (16 bits, signed) << 16 | total bits (6) << 8 | category (4)
+// ---------------------------------------------------------------------------------------
+PCR_HD uint32_t pack_dc(uint32_t e, uint32_t win) {          // e = (length << 4) | category, non-zero
+    const int len = (int)(e >> 4), t = (int)(e & 15);
+    const int diff = extend(field(win, len, t), t);
+    return ((uint32_t)(diff & 0xFFFF) << 16) | ((uint32_t)(len + t) << 8) | (uint32_t)t;
+}
+
+struct DcWindowReader {
+    StreamPtr p;
+    const DcTab* tab[kMaxComp];
+    uint32_t w0, w1, w2, n0, n1;
+    uint32_t o, wbase, mis_bits, total_bits, lane;
+    uint32_t vinfo[kMaxComp];
+    uint32_t nocode;            // set when the bits at the current position are no code of the table
+    int ntab;
+
+    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const DcTab* t0, const DcTab* t1, const DcTab* t2,
+                     int ntables, uint32_t lane_id) {
+        tab[0] = t0; tab[1] = t1; tab[2] = t2; ntab = ntables; lane = lane_id;
+        mis_bits = (byte_off & 3) * 8;
+        p = stream_ptr(words + (byte_off >> 2));
+        w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
+        o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits; nocode = 0;
+        vinfo[0] = vinfo[1] = vinfo[2] = 0;
+        fill();
+    }
+    PCR_HD void fill() {
+#if defined(__HIP_DEVICE_COMPILE__)
+        const uint32_t win = bits_at(w0, w1, w2, (int)lane);
+#pragma unroll
+        for (int j = 0; j < kMaxComp; j++) {
+            if (j < ntab) { const uint32_t e = tab[j]->lut[win >> 24]; vinfo[j] = e != 0xFF ? pack_dc(e, win) : 0; }
+        }
+#endif
+    }
+    PCR_HD bool exhausted() const { return o >= 64; }
+    PCR_HD void refill() {
+        do { w0 = w2; w1 = n0; w2 = n1; n0 = p[0]; n1 = p[1]; p += 2; o -= 64; wbase += 64; } while (o >= 64);
+        fill();
+    }
+    // packed word of the symbol at the current position (inside the window) under table j; where the bits are
+    // no code at all it returns 0 (length 0, difference 0) and raises `nocode`
+    PCR_HD uint32_t peek(int j) {
+        uint32_t info;
+#if defined(__HIP_DEVICE_COMPILE__)
+        const uint32_t v = j == 0 ? vinfo[0] : (j == 1 ? vinfo[1] : vinfo[2]);
+        info = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)o);
+#else
+        { const uint32_t win = bits_at(w0, w1, w2, (int)o); const uint32_t e = tab[j]->lut[win >> 24]; info = e != 0xFF ? pack_dc(e, win) : 0; }
+#endif
+        if (__builtin_expect(info == 0, 0)) {                // a code longer than 8 bits, or garbage
+            const uint32_t win = bits_at(w0, w1, w2, (int)o);
+            const uint32_t e = dc_code(tab[j], win);
+            info = uni(e ? pack_dc(e, win) : 0u);            // (table reads come back in vector registers)
+            nocode |= uni(e ? 0u : 1u);
+        }
+        return info;
+    }
+    PCR_HD void consume(uint32_t n) { o += n; }
+    PCR_HD uint32_t overrun_bit() const { return (total_bits - (wbase + o)) >> 31; }
+};
+
+// ---------------------------------------------------------------------------------------
+// DC first scan.  Non-interleaved scans visit the blocks covering the component's own
+// samples, interleaved scans the MCU-padded grid, component by component inside each MCU.
+// The sink's plane is the image's coefficient buffer; ls.poff[j] locates the plane of scan component j
+// in it ([bh][bw][64] blocks, DC at element 0 of each block).  tj0/1/2: which of the reader's tables each
+// scan component uses.
+// ---------------------------------------------------------------------------------------
+PCR_HD int decode_dc_first(DcWindowReader* wr, const LaneScan& ls, int tj0, int tj1, int tj2, CoefSink* sink) {
+    int pred[kMaxComp] = {0, 0, 0};
+    const int tj[kMaxComp] = {tj0, tj1, tj2};
+    uint32_t my = ls.mcu0 / ls.mcu_w, mx = ls.mcu0 % ls.mcu_w;
+    uint32_t bad = 0;
+    uint32_t m = ls.mcu0;
+    while (m < ls.mcu1) {
+#pragma unroll
+        for (int j = 0; j < kMaxComp; j++) {                 // unrolled: every index below is a constant
+            if (j < ls.ns) {
+                const uint32_t hs = ls.ns > 1 ? ls.hs[j] : 1, vs = ls.ns > 1 ? ls.vs[j] : 1, bw = ls.bw[j];
+                uint32_t rowe = ls.poff[j] + ((my * vs) * bw + mx * hs) * 64;       // first block of this MCU in the plane
+                for (uint32_t by = 0; by < vs; by++) {
+                    uint32_t e = rowe;
+                    for (uint32_t bx = 0; bx < hs; bx++) {
+                        if (wr->exhausted()) {
+                            sink->flush();
+                            bad |= wr->overrun_bit();        // never walk far beyond the unit's data
+                            wr->refill();
+                        }
+                        const uint32_t info = wr->peek(tj[j]);
+                        wr->consume((info >> 8) & 63);
+                        pred[j] += (int32_t)info >> 16;
+                        sink->emit(e, (int)((uint32_t)pred[j] << 16), 1);
+                        e += 64;
+                    }
+                    rowe += bw * 64;
+                }
+            }
+        }
+        bad |= wr->nocode;
+        if (++mx == ls.mcu_w) { mx = 0; my++; }
+        m = bad ? ls.mcu1 : m + 1;
+    }
+    sink->flush();
+    bad |= wr->overrun_bit();
+    return bad ? kEFormat : kOk;
+}
+
+// ---------------------------------------------------------------------------------------
+// AC first scan of one component, band Ss..Se.  Writes coefficient values in ZIG-ZAG order
+// inside each 64-element block (element k of a block is zig-zag position k).  Blocks skipped by
+// an end-of-band run are not touched: coefficients must be zero-filled beforehand.
+//
+// The serial part handles one symbol per loop iteration and does no memory access: a decoded
+// coefficient goes, as (element index, value), into the next free lane of two vector registers
+// (CoefSink), and the lanes store them all at once each time the bit window slides.  A window
+// of 64 bits holds at most 32 coefficient symbols (each is at least 2 bits long), so the 64
+// lanes always suffice.  Control flow is structured -- flags and loop conditions instead of
+// returns and breaks -- because the compiler turns early exits from nested loops into a state
+// variable that is tested after every symbol.
+// ---------------------------------------------------------------------------------------
 // Non-zero mask of the band Ss..Se of one block in internal (zig-zag) order: what an AC first
 // scan over that band has made non-zero.
 PCR_HD uint64_t nz_mask_of_block(const int16_t* blk, int Ss, int Se) {

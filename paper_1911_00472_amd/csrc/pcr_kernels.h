@@ -196,6 +196,7 @@ struct UnitSetup {
     uint32_t byte_off, nbytes;
     LaneScan ls;
     int16_t* plane[kMaxComp];     // planes of the scan's components
+    int16_t* base;                // the image's coefficient buffer (all planes)
     bool ok;
 };
 
@@ -223,8 +224,11 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __rest
     for (int j = 0; j < kMaxComp; j++) {
         const int c = uni(j < ls.ns ? (int)sd->comp[j] : 0);
         ls.hs[j] = uni((uint32_t)img->hs[c]); ls.vs[j] = uni((uint32_t)img->vs[c]); ls.bw[j] = uni((uint32_t)img->bw[c]);
-        L->plane[j] = base + (c == 0 ? poff[0] : (c == 1 ? poff[1] : poff[2]));
+        const size_t po = c == 0 ? poff[0] : (c == 1 ? poff[1] : poff[2]);
+        ls.poff[j] = (uint32_t)po;
+        L->plane[j] = base + po;
     }
+    L->base = base;
     L->words = clean32 + (uni(clean_base(sd->data_off)) >> 2);
     L->byte_off = uni(b0); L->nbytes = uni(b1 > b0 ? b1 - b0 : 0);
     L->ok = true;
@@ -249,7 +253,9 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     __syncthreads();
     DcWindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tabs[0], &tabs[1], &tabs[2], uni(ntab), threadIdx.x);
-    int rc = decode_dc_first(&wr, L.ls, 0, uni(tj1), uni(tj2), L.plane[0], L.plane[1], L.plane[2]);
+    CoefSink sink;
+    sink.init(L.base, L.ls.Al, threadIdx.x);
+    int rc = decode_dc_first(&wr, L.ls, 0, uni(tj1), uni(tj2), &sink);
     if (rc != kOk) R.status[un.img] = rc;
 }
 
@@ -442,7 +448,7 @@ __global__ void __launch_bounds__(256) k_apply(DevRecord R, const ApplyUnit* __r
 // Parity hook: internal planes (zig-zag order inside each block) -> natural order.
 __global__ void __launch_bounds__(256) k_export_natural(const int16_t* in, int16_t* out, size_t n) {
     __shared__ uint8_t zz[64];
-    if (threadIdx.x < 64) zz[threadIdx.x] = (uint8_t)zigzag_natural(threadIdx.x);
+    if (threadIdx.x < 64) zz[threadIdx.x] = (uint8_t)zigzag_lookup(threadIdx.x);
     __syncthreads();
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * 256;
@@ -457,9 +463,8 @@ __global__ void __launch_bounds__(256) k_export_natural(const int16_t* in, int16
 //            has its DC gets one lane per block, which writes the flat block's value
 //   phase 2  row IDCT, one lane per (block, row)
 //   phase 3  column IDCT + level shift + clamp, one lane per (block, column)
-//   phase 4  chroma replication + colour + store: one lane per ALIGNED group of 12 bytes of an
-//            output row (three full dwords whatever the image width); for RGB such a group
-//            covers four pixels and, when the row starts off a pixel boundary, parts of a fifth
+//   phase 4  chroma replication + colour + store: one lane per group of 12 bytes of an output row
+//            (4 RGB pixels), written as one 12-byte store that need not be aligned
 // The measured limit of this kernel is vector-ALU issue, so the index arithmetic is kept off
 // the lanes: components are handled one after the other (their geometry is wave-uniform),
 // divisions by strip widths use a reciprocal computed once, and the zig-zag scatter offsets
@@ -543,7 +548,7 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
     for (uint32_t e = threadIdx.x; e < nc * 64; e += 256) {
         const uint32_t c = e >> 6, k = e & 63;
         const uint8_t* q = R.rec + img.qoff[img.tq[c]];
-        const uint32_t p = (uint32_t)zigzag_natural((int)k);
+        const uint32_t p = zigzag_lookup(k);
         qz[c][k] = img.qprec[img.tq[c]] ? (float)ld_be16(q + 2 * k) : (float)q[k];
         zoff[c][k] = (uint16_t)((p >> 3) * (c == 0 ? pstr[0] : (c == 1 ? pstr[1] : pstr[2])) + (p & 7));
     }
@@ -660,64 +665,54 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
         }
         __syncthreads();
     }
-    // phase 4: one lane per aligned group of 12 bytes of an output row of the strip
+    // phase 4: one lane per group of 12 bytes of an output row of the strip (4 RGB pixels or 12 gray ones),
+    // stored as three dwords.  Rows start wherever width x 3 puts them, so the stores are in general not
+    // 4-byte aligned: global memory takes unaligned dword accesses (a store that straddles a line is split
+    // by the memory pipeline), which is far cheaper than shifting every group into alignment.
     if (row_bytes == 0) return;
     const uint32_t shx0 = img.hs[0] == hmax ? 0 : 1, shy0 = img.vs[0] == vmax ? 0 : 1;     // sampling factors are 1 or 2
     const uint32_t shx1 = nc > 1 && img.hs[1] != hmax, shy1 = nc > 1 && img.vs[1] != vmax;
     const uint32_t shx2 = nc > 2 && img.hs[2] != hmax, shy2 = nc > 2 && img.vs[2] != vmax;
     const uint32_t m0 = flat[0] ? ~7u : ~0u, m1 = flat[1] ? ~7u : ~0u, m2 = flat[2] ? ~7u : ~0u;   // flat: read the block's corner
-    const uint32_t groups = (row_bytes + 14) / 12;         // per row, allowing for a row that starts 3 bytes into its first group
+    const uint32_t groups = (row_bytes + 11) / 12;         // per row; only the last one can be partial
     const uint32_t rcpg = recip16(groups);
     for (uint32_t it = threadIdx.x; it < rows * groups; it += 256) {
         const uint32_t ly = (it * rcpg) >> 16, g = it - ly * groups;
-        uint8_t* rowp = o + ((size_t)(y0 + ly) * W + x0) * nc;     // first byte of this row inside the strip
-        const uint32_t mis = (uint32_t)((uintptr_t)rowp & 3);
-        const int32_t r0 = (int32_t)(g * 12) - (int32_t)mis;       // byte offset of the group in the row (may be -3..-1)
-        if (r0 >= (int32_t)row_bytes) continue;
-        uint8_t* wp = rowp + r0;                                    // 4-byte aligned
-        uint32_t wd[3];
+        const uint32_t r0 = g * 12;                        // byte offset of the group in the row
+        uint8_t* wp = o + ((size_t)(y0 + ly) * W + x0) * nc + r0;
+        uint32_t wd[3] = {0, 0, 0};
         if (nc == 1) {
             const float* yrow = tile + poff[0] + ((ly >> shy0) & m0) * pstr[0];
-            wd[0] = wd[1] = wd[2] = 0;
 #pragma unroll
             for (int j = 0; j < 12; j++) {
-                const int32_t r = r0 + j;
-                const bool ok = r >= 0 && r < (int32_t)row_bytes && !dead;
-                const float s = ok ? yrow[((uint32_t)r >> shx0) & m0] : 0.f;
+                const uint32_t r = r0 + j;
+                const float s = (r < row_bytes && !dead) ? yrow[(r >> shx0) & m0] : 0.f;
                 wd[j >> 2] |= (uint32_t)round_u8(s) << (8 * (j & 3));
             }
         } else {
-            const uint32_t p0 = (uint32_t)(r0 < 0 ? 0 : r0) / 3;   // first pixel the group touches; it touches at most p0 .. p0+4
+            const uint32_t p0 = g * 4;                     // first of the group's four pixels
             const float* yrow = tile + poff[0] + ((ly >> shy0) & m0) * pstr[0];
             const float* brow = tile + poff[1] + ((ly >> shy1) & m1) * pstr[1];
             const float* rrow = tile + poff[2] + ((ly >> shy2) & m2) * pstr[2];
-            uint32_t three[5];                                      // R | G << 8 | B << 16 of the five pixels
+            uint32_t three[4];                             // R | G << 8 | B << 16 of the four pixels
 #pragma unroll
-            for (int q = 0; q < 5; q++) {
+            for (int q = 0; q < 4; q++) {
                 const uint32_t lx = p0 + q;
                 uint8_t px[3] = {0, 0, 0};
                 if (lx * 3 < row_bytes && !dead)
                     ycc_to_rgb(yrow[(lx >> shx0) & m0], brow[(lx >> shx1) & m1], rrow[(lx >> shx2) & m2], px);
                 three[q] = (uint32_t)px[0] | ((uint32_t)px[1] << 8) | ((uint32_t)px[2] << 16);
             }
-            // the fifteen bytes as four dwords, then shifted so that byte r0 of the row lands on byte 0
-            uint32_t d0 = three[0] | (three[1] << 24), d1 = (three[1] >> 8) | (three[2] << 16),
-                     d2 = (three[2] >> 16) | (three[3] << 8), d3 = three[4];
-            uint32_t sh = (uint32_t)r0 - p0 * 3;                    // 0..2
-            if (r0 < 0) { d3 = d2; d2 = d1; d1 = d0; d0 = 0; sh = (uint32_t)(4 + r0); }   // bytes before the row: shift the other way
-            wd[0] = __builtin_amdgcn_alignbyte(d1, d0, sh);
-            wd[1] = __builtin_amdgcn_alignbyte(d2, d1, sh);
-            wd[2] = __builtin_amdgcn_alignbyte(d3, d2, sh);
+            wd[0] = three[0] | (three[1] << 24); wd[1] = (three[1] >> 8) | (three[2] << 16); wd[2] = (three[2] >> 16) | (three[3] << 8);
         }
-        if (r0 >= 0 && r0 + 12 <= (int32_t)row_bytes) {
-            uint32_t* w32 = reinterpret_cast<uint32_t*>(wp);
-            w32[0] = wd[0]; w32[1] = wd[1]; w32[2] = wd[2];
+        if (r0 + 12 <= row_bytes) {
+            struct __attribute__((packed, aligned(1))) Twelve { uint32_t a, b, c; };
+            Twelve tw; tw.a = wd[0]; tw.b = wd[1]; tw.c = wd[2];
+            *reinterpret_cast<Twelve*>(wp) = tw;           // one (possibly unaligned) 12-byte store
         } else {
 #pragma unroll
-            for (int j = 0; j < 12; j++) {
-                const int32_t r = r0 + j;
-                if (r >= 0 && r < (int32_t)row_bytes) wp[j] = (uint8_t)(wd[j >> 2] >> (8 * (j & 3)));
-            }
+            for (int j = 0; j < 12; j++)
+                if (r0 + j < row_bytes) wp[j] = (uint8_t)(wd[j >> 2] >> (8 * (j & 3)));
         }
     }
 }

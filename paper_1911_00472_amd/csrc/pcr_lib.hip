@@ -299,6 +299,7 @@ static int finish_open(pcr_record* r) {
             if (elems >= (1ull << 32)) return PCR_E_UNSUPPORTED;       // the decoders index a plane with 32 bits
             cc += elems;
         }
+        if (cc >= (1ull << 32)) return PCR_E_UNSUPPORTED;               // ... and an image's planes together
         r->coef_off[i + 1] = r->coef_off[i] + cc;
         for (uint32_t g = 0; g < d.nscans; g++) {
             const size_t ig = (size_t)i * G + g;

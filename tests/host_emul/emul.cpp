@@ -75,14 +75,15 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
             int16_t* cpl[kMaxComp] = {nullptr, nullptr, nullptr};
             for (int q = 0; q < kMaxComp; q++) {
                 int c = q < sd.ns ? sd.comp[q] : 0;
-                ls.hs[q] = img.hs[c]; ls.vs[q] = img.vs[c]; ls.bw[q] = img.bw[c];
+                ls.hs[q] = img.hs[c]; ls.vs[q] = img.vs[c]; ls.bw[q] = img.bw[c]; ls.poff[q] = (uint32_t)poff[c];
                 cpl[q] = coef.data() + poff[c];
             }
             if (sd.Ss == 0) {
                 std::vector<DcTab> dt(3);
                 for (int q = 0; q < sd.ns; q++) dctab_build(&dt[q], rec + sd.dc_off[q]);
                 DcWindowReader dw; dw.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &dt[0], &dt[1], &dt[2], sd.ns, 0);
-                rc = decode_dc_first(&dw, ls, 0, 1, 2, cpl[0], cpl[1], cpl[2]);
+                CoefSink dsink; dsink.init(coef.data(), ls.Al, 0);
+                rc = decode_dc_first(&dw, ls, 0, 1, 2, &dsink);
             } else {
                 AcTab at; actab_build(&at, rec + sd.ac_off);
                 WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &at, sd.Ah == 0, 0);
