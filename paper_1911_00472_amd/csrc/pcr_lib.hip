@@ -28,6 +28,7 @@ struct LevelList {
 struct Plan {                               // launch geometry for one scan group k
     std::vector<LevelList> levels;
     ApplyUnit* d_apply = nullptr; ApplyList* d_apply_lists = nullptr; int32_t* d_list_idx = nullptr; uint32_t n_apply = 0, apply_grid_x = 0;
+    bool has_ac = false;                     // some scan <= k is an AC scan (else only element 0 of every block is ever touched)
 };
 
 template <class T> int dev_alloc(T** p, size_t count) {
@@ -113,6 +114,7 @@ int build_plan(pcr_record* r, int k, Plan** out) {
             const size_t ig = (size_t)i * G + g;
             const ScanDesc& sd = r->scan[ig];
             if (sd.Ah > 0) for (int j = 0; j < sd.ns; j++) refine[sd.comp[j]] = true;
+            if (sd.Ss > 0) plan.has_ac = true;
             if (sd.Ss == 0 && sd.Ah > 0) continue;             // DC refinement has no serial decode
             const int kind = sd.Ss == 0 ? kDcFirst : (sd.Ah == 0 ? kAcFirst : kAcRefine);
             if (kind == kAcRefine) {
@@ -224,8 +226,12 @@ int run_entropy_stages(pcr_record* r, int k, hipStream_t s, bool refine_in_memor
     mark(r, PCR_STAGE_INDEX_PARSE, s);
     hipLaunchKernelGGL(k_unstuff, dim3(n, k), dim3(256), 0, s, r->d, (uint32_t)k);
     const size_t coef_bytes = r->coef_off[n] * sizeof(int16_t);
-    hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
-    if (r->n_masks) hipLaunchKernelGGL(k_fill_zero, dim3(1024), dim3(256), 0, s, (uint4*)r->d.masks, (r->n_masks * 8 + 15) / 16);
+    // AC first scans only write the coefficients they decode: everything else must read as zero.  With DC scans
+    // only, the DC first scan writes element 0 of every block and the pixel kernel reads nothing else, so the
+    // fill is skipped (the coefficient export shows whole planes and always needs it).  The mask planes need no
+    // fill: every entry a kernel reads was written earlier in the same call.
+    if (plan->has_ac || refine_in_memory)
+        hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
     mark(r, PCR_STAGE_UNSTUFF, s);
     const uint32_t* c32 = reinterpret_cast<const uint32_t*>(r->d.clean);
     const uint64_t* h64 = r->d.masks;
