@@ -221,7 +221,8 @@ PCR_HD int extend(uint32_t v, int s) { return (s && v < (1u << (s - 1))) ? (int)
 // really lands on them.  The window is 96 bits of stream (w0,w1,w2): offsets 0..63 each with
 // 32 bits of look-ahead; two more words are always already loaded.
 //
-// packed word: value (16 bits, signed) << 16 | total bits (6) << 8 | run (4) << 4 | size (4)
+// packed word: value (16 bits, signed) << 16 | flags (bits 15, 14) | total bits (6) << 8 | run (4) << 4 | size (4)
+// (refinement scans: the low byte holds the table advance instead, see pack_symbol)
 // ---------------------------------------------------------------------------------------
 PCR_HD uint32_t bits_at(uint32_t w0, uint32_t w1, uint32_t w2, int j) {      // 32 bits from offset j (0..63)
     const uint32_t hi = j < 32 ? w0 : w1, lo = j < 32 ? w1 : w2;
@@ -241,7 +242,12 @@ PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
     const int value = (first && s) ? extend(extra, s) : (int)extra;
     // bit 15: the symbol carries a coefficient; bit 14: it is an end-of-band symbol
     const uint32_t flags = (s ? kSymCoef : 0u) | ((s == 0 && r != 15) ? kSymEob : 0u);
-    if (!first && s > 1) return kSymInvalid;                 // sizes above 1 do not exist in a refinement scan
+    if (!first) {
+        // refinement scans: the low byte is the number of table entries the symbol moves on by before the one
+        // it lands on -- the run r, or 64 + r ("past every zero") for an end-of-band symbol
+        if (s > 1) return kSymInvalid;                       // sizes above 1 do not exist in a refinement scan
+        return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | (uint32_t)(r + ((flags & kSymEob) ? 64 : 0));
+    }
     return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | ((uint32_t)r << 4) | (uint32_t)s;
 }
 
@@ -684,26 +690,26 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
                 const uint32_t nzeros = (uint32_t)__builtin_popcountll(z);
                 zt.build(h, z, nzeros, ncorr, wr->lane);
                 uint64_t taken = 0;                          // table indices that received a new coefficient
-                uint32_t idx = 0, passed = 0;                // next table index; correction bits stepped over so far
+                uint32_t idx = 0;                            // next table index
+                uint32_t ob = wr->o;                         // window offset not counting the correction bits stepped over in this block
                 uint32_t info, e;
                 do {
                     // One straight line for all three kinds of symbol.  A new +-1 after r zeros (kSymCoef) or
                     // sixteen zeros (r = 15): r zeros are passed, then one more position.  End of band: as if the
                     // run went past every zero -- the sentinel entry says "all corrections, nothing left".
-                    info = wr->symbol();
-                    const uint32_t len = (info >> 8) & 63, r = (info >> 4) & 15;
-                    idx += r + ((info >> 8) & 64);           // kSymEob is bit 14: + 64
+                    if (wr->exhausted()) { const uint32_t before = wr->o; wr->refill(); ob -= before - wr->o; }
+                    info = wr->peek();
+                    idx += info & 127;                       // the run, or 64 + run for an end of band
                     idx = idx < nzeros ? idx : nzeros;       // past the last zero: the sentinel
                     e = zt.at(idx);
                     taken |= (uint64_t)((info >> 15) & 1) << idx;
                     idx++;
-                    const uint32_t upto = (e >> 8) & 127;
-                    wr->consume(len + upto - passed);        // code, sign, corrections passed
-                    passed = upto;
+                    ob += (info >> 8) & 63;                  // code and sign
+                    wr->o = ob + ((e >> 8) & 127);           // ... and the corrections passed so far
                 } while ((e & kZtLast) == 0);
                 if (info & kSymEob) {                        // the block ended with an end-of-band (run) symbol
                     bad |= (info & 0x3F00) ? 0u : 1u;        // length 0: no code at all
-                    eobrun = (1u << ((info >> 4) & 15)) + (info >> 16);
+                    eobrun = (1u << (info & 15)) + (info >> 16);
                 }
                 bad |= (uint32_t)(taken >> nzeros) & 1;      // a new coefficient with no zero left to take
                 newm = zt.positions(taken);
