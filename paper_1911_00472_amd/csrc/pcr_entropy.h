@@ -221,8 +221,7 @@ PCR_HD int extend(uint32_t v, int s) { return (s && v < (1u << (s - 1))) ? (int)
 // really lands on them.  The window is 96 bits of stream (w0,w1,w2): offsets 0..63 each with
 // 32 bits of look-ahead; two more words are always already loaded.
 //
-// packed word: value (16 bits, signed) << 16 | flags (bits 15, 14) | total bits (6) << 8 | run (4) << 4 | size (4)
-// (refinement scans: the low byte holds the table advance instead, see pack_symbol)
+// packed word: value (16 bits, signed) << 16 | flags (bits 15, 14) | total bits (6) << 8 | advance (7 bits, see pack_symbol)
 // ---------------------------------------------------------------------------------------
 PCR_HD uint32_t bits_at(uint32_t w0, uint32_t w1, uint32_t w2, int j) {      // 32 bits from offset j (0..63)
     const uint32_t hi = j < 32 ? w0 : w1, lo = j < 32 ? w1 : w2;
@@ -242,13 +241,11 @@ PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
     const int value = (first && s) ? extend(extra, s) : (int)extra;
     // bit 15: the symbol carries a coefficient; bit 14: it is an end-of-band symbol
     const uint32_t flags = (s ? kSymCoef : 0u) | ((s == 0 && r != 15) ? kSymEob : 0u);
-    if (!first) {
-        // refinement scans: the low byte is the number of table entries the symbol moves on by before the one
-        // it lands on -- the run r, or 64 + r ("past every zero") for an end-of-band symbol
-        if (s > 1) return kSymInvalid;                       // sizes above 1 do not exist in a refinement scan
-        return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | (uint32_t)(r + ((flags & kSymEob) ? 64 : 0));
-    }
-    return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | ((uint32_t)r << 4) | (uint32_t)s;
+    // The low byte is how far the symbol moves on before the position it lands on: the run r, or 64 + r
+    // ("past everything") for an end-of-band symbol.  AC first scans add it to the position in the band,
+    // refinement scans to the index into the block's zero table.
+    if (!first && s > 1) return kSymInvalid;                 // sizes above 1 do not exist in a refinement scan
+    return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | (uint32_t)(r + ((flags & kSymEob) ? 64 : 0));
 }
 
 struct WindowReader {
@@ -509,14 +506,14 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
             // not counted unless it carries a coefficient.  Only a block change leaves the line.
             const uint32_t info = wr->peek();
             wr->consume((info >> 8) & 63);
-            const uint32_t k2 = k + ((info >> 4) & 15);
+            const uint32_t k2 = k + (info & 127);            // + run, or + 64 + run for an end of band
             sink->emit(base + (k2 & 63), (int)info, (info >> 15) & 1);   // & 63: stays inside the block whatever the stream says
             k = k2 + 1;
-            if (__builtin_expect(((info & kSymEob) | ((Se - k) >> 31)) != 0, 0)) {
+            if (__builtin_expect(k > Se, 0)) {               // the block is finished: band complete, or end of band
                 uint32_t adv = 1;                            // blocks to move on by
-                if (info & kSymEob) {                        // end of band, run of 2^r + extra blocks; no code at all has length 0
+                if (info & kSymEob) {                        // run of 2^r + extra blocks; no code at all has length 0
                     bad |= (info & 0x3F00) ? 0u : 1u;
-                    adv = (1u << ((info >> 4) & 15)) + (info >> 16);
+                    adv = (1u << (info & 15)) + (info >> 16);
                 } else {
                     bad |= (k2 > Se) ? ((info >> 15) & 1) : 0u;   // a coefficient beyond the band
                 }
