@@ -17,6 +17,16 @@
 namespace pcr {
 
 // Everything a kernel needs to find its data; passed by value.
+// Wave priority.  A decode call on one record usually shares the GPU with calls on other records (other
+// streams).  The AC entropy kernels then keep every SIMD busy with long-running wavefronts that issue
+// scalar instructions back to back, and instruction arbitration serves the oldest wavefronts first: a short
+// data-parallel kernel of another record (unstuff, fill, phase 2 of refinement, pixels) was measured to run
+// 3-8 times longer than alone, holding up its record's dependency chain.  These kernels therefore raise
+// their own wavefronts' issue priority (s_setprio; stream priorities are not touched); the DC first kernel,
+// few and latency-bound wavefronts, takes a middle value.  The AC entropy kernels stay at the default.
+PCR_D void short_kernel_priority() { __builtin_amdgcn_s_setprio(3); }
+PCR_D void dc_kernel_priority() { __builtin_amdgcn_s_setprio(2); }
+
 struct DevRecord {
     const uint8_t* rec;        // record bytes
     uint8_t* clean;            // unstuffed entropy data, same offsets as rec
@@ -90,6 +100,7 @@ __global__ void __launch_bounds__(64) k_parse(DevRecord R, uint32_t kmax) {
 constexpr int kUnstuffPer = 8;
 
 __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kmax) {
+    short_kernel_priority();
     __shared__ uint32_t part[256];
     __shared__ uint32_t s_stop;
     uint32_t i = blockIdx.x, g = blockIdx.y;
@@ -237,6 +248,7 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __rest
 __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
         const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {
     __shared__ DcTab tabs[kMaxComp];
+    dc_kernel_priority();
     const Unit un = units[blockIdx.x];
     UnitSetup L;
     unit_setup(R, un, clean32, &L);
@@ -317,6 +329,7 @@ struct RefineScan { uint32_t img; uint32_t scan; };
 
 __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const RefineScan* rs) {
     __shared__ AcTab tab;
+    short_kernel_priority();
     const RefineScan a = rs[blockIdx.y];
     if (R.status[a.img] != kOk) return;
     const ImgDesc* img = &R.img[a.img];
@@ -497,6 +510,7 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
     __shared__ __attribute__((aligned(16))) uint16_t zoff[kMaxComp][64];  // zig-zag index -> offset of that position from the block's corner in `tile`
     __shared__ ImgDesc img;                                // this image's descriptor, read many times below
     __shared__ ApplyList rl[kMaxComp];                     // refinement scan lists of the components (n = 0: none)
+    short_kernel_priority();
     const PixelTile t = tiles[blockIdx.x];
     {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.img[t.img]);
@@ -731,6 +745,7 @@ __global__ void __launch_bounds__(256) k_gather(DevRecord R, uint32_t i, uint32_
 }
 
 __global__ void __launch_bounds__(256) k_fill_zero(uint4* p, size_t n16) {
+    short_kernel_priority();
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * 256;
     for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
