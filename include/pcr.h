@@ -147,6 +147,12 @@ int pcr_enable_stage_timing(pcr_record* rec, int on);
 int pcr_last_stage_ms(pcr_record* rec, float* stage_ms);
 int pcr_stage_ms_history(pcr_record* rec, double* sum_ms, uint32_t* launches, uint32_t* calls);
 
+/* Diagnostics: the rate (10^9 instructions per second, whole device) at which `waves_per_cu` (1..32)
+ * resident wavefronts per compute unit issue chains of dependent scalar-ALU instructions -- the kind of
+ * work the wave-uniform entropy decoders consist of (Section 4.2 of the paper names the decode as the
+ * bottleneck; this is the ceiling of the design used here for it).  Synchronous; allocates a few KB. */
+int pcr_probe_scalar_issue_rate(int device_id, int waves_per_cu, double* ginst_per_s);
+
 const char* pcr_strerror(int code);
 
 #ifdef __cplusplus

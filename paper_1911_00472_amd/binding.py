@@ -34,6 +34,7 @@ SYMBOLS = {
     "pcr_decode_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_enable_stage_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
     "pcr_last_stage_ms": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_float)]),
+    "pcr_probe_scalar_issue_rate": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]),
     "pcr_stage_ms_history": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]),
     "pcr_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
@@ -179,6 +180,13 @@ class Record:
         calls = ctypes.c_uint32(0)
         _check(lib().pcr_stage_ms_history(self._h, ms, launches, ctypes.byref(calls)), "pcr_stage_ms_history")
         return int(calls.value), {n: (float(ms[i]), int(launches[i])) for i, n in enumerate(STAGE_NAMES)}
+
+
+def probe_scalar_issue_rate(waves_per_cu, device=0):
+    """10^9 dependent scalar-ALU instructions per second the device issues with that many wavefronts per CU."""
+    v = ctypes.c_double(0)
+    _check(lib().pcr_probe_scalar_issue_rate(device, waves_per_cu, ctypes.byref(v)), "pcr_probe_scalar_issue_rate")
+    return float(v.value)
 
 
 def pcr_open(data, device=0):

@@ -744,6 +744,24 @@ __global__ void __launch_bounds__(256) k_gather(DevRecord R, uint32_t i, uint32_
     if (add_eoi && blockIdx.x == 0 && threadIdx.x == 0) { dst[w] = 0xFF; dst[w + 1] = 0xD9; }
 }
 
+// --------------------------------------------------------------------------------------
+// k_probe_scalar: yardstick for the entropy kernels.  Every wavefront runs `iters` times a chain of 16
+// dependent scalar instructions, the same kind of work a wave-uniform decoder is made of; the host
+// turns the duration into scalar instructions per second for a given number of wavefronts per CU.
+// --------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(64) k_probe_scalar(uint32_t* out, uint32_t iters, uint32_t seed) {
+    uint32_t a = uni(seed + blockIdx.x), b = a * 3u + 1u;
+    for (uint32_t i = 0; i < iters; i++) {
+        asm volatile(
+            "s_add_u32 %0, %0, %1\n s_xor_b32 %1, %1, %0\n s_add_u32 %0, %0, %1\n s_xor_b32 %1, %1, %0\n"
+            "s_add_u32 %0, %0, %1\n s_xor_b32 %1, %1, %0\n s_add_u32 %0, %0, %1\n s_xor_b32 %1, %1, %0\n"
+            "s_add_u32 %0, %0, %1\n s_xor_b32 %1, %1, %0\n s_add_u32 %0, %0, %1\n s_xor_b32 %1, %1, %0\n"
+            "s_add_u32 %0, %0, %1\n s_xor_b32 %1, %1, %0\n s_add_u32 %0, %0, %1\n s_xor_b32 %1, %1, %0\n"
+            : "+s"(a), "+s"(b) : : "scc");
+    }
+    if (threadIdx.x == 0) out[blockIdx.x] = a ^ b;
+}
+
 __global__ void __launch_bounds__(256) k_fill_zero(uint4* p, size_t n16) {
     short_kernel_priority();
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;

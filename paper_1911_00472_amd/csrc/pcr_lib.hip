@@ -607,6 +607,31 @@ int pcr_decode_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* strea
     return PCR_OK;
 }
 
+int pcr_probe_scalar_issue_rate(int device_id, int waves_per_cu, double* ginst_per_s) {
+    if (!ginst_per_s || waves_per_cu < 1 || waves_per_cu > 32) return PCR_E_ARG;
+    HIP_TRY(hipSetDevice(device_id));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, device_id));
+    const uint32_t grid = (uint32_t)prop.multiProcessorCount * (uint32_t)waves_per_cu, iters = 20000;
+    uint32_t* d_out = nullptr;
+    if (hipMalloc((void**)&d_out, grid * sizeof(uint32_t)) != hipSuccess) return PCR_E_NOMEM;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = PCR_OK;
+    float ms = 0;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) rc = PCR_E_DEVICE;
+    for (int rep = 0; rep < 2 && rc == PCR_OK; rep++) {          // the first launch warms up
+        (void)hipEventRecord(e0, nullptr);
+        hipLaunchKernelGGL(k_probe_scalar, dim3(grid), dim3(64), 0, nullptr, d_out, iters, 1u);
+        (void)hipEventRecord(e1, nullptr);
+        if (hipEventSynchronize(e1) != hipSuccess || hipGetLastError() != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = PCR_E_DEVICE;
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(d_out);
+    if (rc == PCR_OK) *ginst_per_s = (double)grid * iters * 16.0 / (ms * 1e-3) / 1e9;
+    return rc;
+}
+
 const char* pcr_strerror(int code) {
     switch (code) {
         case PCR_OK: return "ok";

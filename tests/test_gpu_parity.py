@@ -280,3 +280,16 @@ def test_stage_timing_history(rgb_small):
         assert calls == 1 and hist["ac_first"][1] == 0 and hist["dc_first"][1] == 1
     finally:
         h.close()
+
+
+@pytest.mark.gpu
+def test_scalar_issue_probe():
+    """The diagnostic probe reports a plausible rate and rejects bad arguments."""
+    import paper_1911_00472_amd as pkg
+    lone = pkg.probe_scalar_issue_rate(1)
+    full = pkg.probe_scalar_issue_rate(16)
+    assert 10 < lone < full < 1000          # 10^9 instructions/s; the nominal ceiling is 614
+    with pytest.raises(pkg.PcrError):
+        pkg.probe_scalar_issue_rate(0)
+    with pytest.raises(pkg.PcrError):
+        pkg.probe_scalar_issue_rate(33)
