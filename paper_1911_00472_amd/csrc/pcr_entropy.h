@@ -603,8 +603,9 @@ constexpr uint32_t kZtLast = 1u << 16, kZtSentinel = 1u << 17;
 struct ZeroTable {
 #if defined(__HIP_DEVICE_COMPILE__)
     uint32_t ventry, vindex;                                  // lane n: entry n; lane i: table index of position i (64 if not a zero)
+    uint32_t vword;                                           // lane n: packed word of the symbol that landed on entry n (0: none)
 #else
-    uint32_t entry[64], index[64];
+    uint32_t entry[64], index[64], word[64];
 #endif
     PCR_HD void build(uint64_t h, uint64_t z, uint32_t nzeros, uint32_t ncorr, uint32_t lane) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -616,6 +617,7 @@ struct ZeroTable {
         const uint32_t dest = iz ? rank : nzeros + (lane - rank);       // a permutation of the 64 lanes
         ventry = (uint32_t)__builtin_amdgcn_ds_permute((int)(dest * 4), (int)data);
         vindex = iz ? rank : 64u;
+        vword = 0;
 #else
         (void)lane;
         uint32_t rank = 0, below = 0;
@@ -626,7 +628,23 @@ struct ZeroTable {
             entry[iz ? rank : nzeros + (i - rank)] = data;
             index[i] = iz ? rank : 64u;
             rank += iz; below += (h >> i) & 1;
+            word[i] = 0;
         }
+#endif
+    }
+    // remember which symbol landed on entry n (one scalar move and one lane write on the device)
+    PCR_HD void land(uint32_t n, uint32_t info) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("s_mov_b32 m0, %2\n\tv_writelane_b32 %0, %1, m0" : "+v"(vword) : "s"(info), "s"(n) : "m0");
+#else
+        word[n] = info;
+#endif
+    }
+    PCR_HD uint32_t landed(uint32_t n) const {
+#if defined(__HIP_DEVICE_COMPILE__)
+        return (uint32_t)__builtin_amdgcn_readlane((int)vword, (int)n);
+#else
+        return word[n];
 #endif
     }
     PCR_HD uint32_t at(uint32_t n) const {                    // n <= 63
@@ -636,13 +654,14 @@ struct ZeroTable {
         return entry[n];
 #endif
     }
-    // positions whose table index is set in `taken`
-    PCR_HD uint64_t positions(uint64_t taken) const {
+    // positions on which a symbol carrying a new coefficient (kSymCoef) landed
+    PCR_HD uint64_t new_positions() const {
 #if defined(__HIP_DEVICE_COMPILE__)
-        return __ballot(vindex < 64u && ((taken >> vindex) & 1));
+        const uint32_t w = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((vindex & 63u) * 4), (int)vword);
+        return __ballot(vindex < 64u && (w & kSymCoef));
 #else
         uint64_t m = 0;
-        for (uint32_t i = 0; i < 64; i++) if (index[i] < 64u && ((taken >> index[i]) & 1)) m |= 1ull << i;
+        for (uint32_t i = 0; i < 64; i++) if (index[i] < 64u && (word[index[i]] & kSymCoef)) m |= 1ull << i;
         return m;
 #endif
     }
@@ -686,7 +705,6 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
             if (band != 0) {                                 // (always: a scan has at least one position)
                 const uint32_t nzeros = (uint32_t)__builtin_popcountll(z);
                 zt.build(h, z, nzeros, ncorr, wr->lane);
-                uint64_t taken = 0;                          // table indices that received a new coefficient
                 uint32_t idx = 0;                            // next table index
                 uint32_t ob = wr->o;                         // window offset not counting the correction bits stepped over in this block
                 uint32_t info, e;
@@ -699,7 +717,7 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
                     idx += info & 127;                       // the run, or 64 + run for an end of band
                     idx = idx < nzeros ? idx : nzeros;       // past the last zero: the sentinel
                     e = zt.at(idx);
-                    taken |= (uint64_t)((info >> 15) & 1) << idx;
+                    zt.land(idx, info);
                     idx++;
                     ob += (info >> 8) & 63;                  // code and sign
                     wr->o = ob + ((e >> 8) & 127);           // ... and the corrections passed so far
@@ -708,8 +726,8 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
                     bad |= (info & 0x3F00) ? 0u : 1u;        // length 0: no code at all
                     eobrun = (1u << (info & 15)) + (info >> 16);
                 }
-                bad |= (uint32_t)(taken >> nzeros) & 1;      // a new coefficient with no zero left to take
-                newm = zt.positions(taken);
+                bad |= (zt.landed(nzeros) >> 15) & 1;        // a new coefficient with no zero left to take (the sentinel)
+                newm = zt.new_positions();
             }
             eobrun -= eobrun ? 1u : 0u;                      // the run counted this block
         } else {
