@@ -75,3 +75,11 @@ def test_lane_code_matches_oracle_headline_images(emul):
     """Large, noisy images: Huffman codes longer than the 8-bit look-ahead table, long streams."""
     records, _ = pcrgen.make_workload("imagenet_like", limit=6)
     _compare(emul, records[0], range(6), (1, 2, 5, 6, 10))
+
+
+def test_lane_code_matches_oracle_extreme_coefficients(emul, extreme_record):
+    """Hand-made planes: dense blocks, lone last coefficients, zero runs inside refinement scans, the
+    largest value sizes, end-of-band runs over hundreds of blocks."""
+    rec, files = extreme_record
+    G = oracle.record_header(rec)["G"]
+    _compare(emul, rec, range(len(files)), range(1, G + 1))

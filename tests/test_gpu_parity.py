@@ -293,3 +293,10 @@ def test_scalar_issue_probe():
         pkg.probe_scalar_issue_rate(0)
     with pytest.raises(pkg.PcrError):
         pkg.probe_scalar_issue_rate(33)
+
+
+def test_extreme_coefficient_planes(extreme_record):
+    """Hand-made planes that exercise the corners of the entropy decoders (see the fixture), every scan group."""
+    rec, files = extreme_record
+    G = oracle.record_header(rec)["G"]
+    _check_record(rec, range(1, G + 1))
