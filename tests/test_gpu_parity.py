@@ -300,3 +300,34 @@ def test_extreme_coefficient_planes(extreme_record):
     rec, files = extreme_record
     G = oracle.record_header(rec)["G"]
     _check_record(rec, range(1, G + 1))
+
+
+def test_headline_full_size_four_records_on_four_streams():
+    """The benchmark's configuration at full size: 4096 images in 4 records of 1024, all four records decoded
+    concurrently on one stream each; a sample of every record is checked against the oracle, and every image's
+    status must be clean."""
+    torch = _torch()
+    records, _ = pcrgen.make_workload("imagenet_like")
+    assert len(records) == 4
+    handles = [pkg.pcr_open(r, 0) for r in records]
+    try:
+        assert sum(h.n for h in handles) == 4096
+        streams = [torch.cuda.Stream() for _ in handles]
+        outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in handles]
+        stats = [torch.full((h.n,), 77, dtype=torch.int32, device="cuda") for h in handles]
+        rng = np.random.default_rng(11)
+        for k in (10, 2):
+            for h, o, st, s in zip(handles, outs, stats, streams):
+                h.decode_batch(k, out=o, status=st, stream=s.cuda_stream)
+            torch.cuda.synchronize()
+            for ri, (h, o, st) in enumerate(zip(handles, outs, stats)):
+                assert (st.cpu().numpy() == 0).all()
+                lay = h.output_layout()
+                host = o.cpu().numpy()
+                for i in sorted(rng.choice(h.n, size=3, replace=False).tolist()):
+                    _, p0, info = oracle.decode_record_image(records[ri], i, k, want_coef=False)
+                    got = host[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
+                    assert np.abs(got - p0).max() <= PIXEL_TOL, ("pixels", ri, i, k)
+    finally:
+        for h in handles:
+            h.close()
