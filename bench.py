@@ -209,6 +209,27 @@ def main():
         per_k[k] = timed(k, max(2, args.steps // 2), 1)
     per_k[args.scan_group] = timed(args.scan_group, args.steps, args.warmup)
 
+    # ---- fidelity upgrades: from the planes of scan group a to scan group b, decoding only the new scans ----
+    def upgrade_step(k):
+        for h, o, st in zip(handles, outs, streams):
+            h.upgrade_batch(k, out=o, stream=st.cuda_stream)
+
+    upgrades = {}
+    chain = [k for k in SCAN_GROUPS]
+    reps = max(2, args.steps // 2)
+    acc = {(a, b): 0.0 for a, b in zip(chain[:-1], chain[1:])}
+    for _ in range(reps + 1):                                   # the first round warms the plans up
+        step(chain[0])
+        torch.cuda.synchronize()
+        for a, b in zip(chain[:-1], chain[1:]):
+            t = time.perf_counter()
+            upgrade_step(b)
+            torch.cuda.synchronize()
+            if _ > 0:
+                acc[(a, b)] += (time.perf_counter() - t) / reps
+    for (a, b), sec_ab in acc.items():
+        upgrades["%d->%d" % (a, b)] = {"ms_per_step": sec_ab * 1e3, "fresh_decode_ms_per_step": per_k[b][0] * 1e3}
+
     def per_launch(d):
         return {n: (ms / launches if launches else 0.0) for n, (ms, launches) in d.items()}
 
@@ -264,6 +285,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "per_scan_group": report,
+        "fidelity_upgrade": upgrades,
     }
     for h in handles:
         h.close()

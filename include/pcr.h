@@ -129,6 +129,20 @@ int pcr_decode_coefficients(pcr_record* rec, int k, int16_t* d_coef, void* hip_s
 int pcr_decode_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
                      void* hip_stream, int32_t* d_status);
 
+/* Fidelity upgrade (Section 3 of the paper: a lower-fidelity read is a prefix of a higher-fidelity one, so
+ * "switching between data fidelities is lightweight"): raise the planes the last pcr_decode_batch /
+ * pcr_upgrade_batch call on this handle left on the device from its scan group to `scan_group` (>= it) by
+ * unstuffing and entropy-decoding only the scans of the new groups, then produce the pixels.  The output is
+ * bit-identical to pcr_decode_batch(rec, scan_group, ...); arguments, layout, stream order and d_status as
+ * there.  The earlier call must have completed or be ordered before this one on the same stream.
+ * pcr_resident_scan_group: the scan group an upgrade would start from; 0 if there is none (nothing decoded
+ * yet, the last call failed, or the last call was pcr_decode_coefficients, which rewrites the planes).
+ * Errors: PCR_E_ARG if nothing is resident or scan_group is lower than the resident group; otherwise as
+ * pcr_decode_batch. */
+int pcr_upgrade_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
+                      void* hip_stream, int32_t* d_status);
+int pcr_resident_scan_group(const pcr_record* rec, int* scan_group);
+
 /* Stage timing with HIP events recorded on the call's own stream (off by default; switching it on
  * starts a new history).  A stage is one kernel or a short run of kernels:
  *   INDEX_PARSE    k_index + k_parse                 UNSTUFF        k_unstuff + zero fills

@@ -32,6 +32,8 @@ SYMBOLS = {
     "pcr_coef_layout": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_decode_coefficients": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp]),
     "pcr_decode_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
+    "pcr_upgrade_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
+    "pcr_resident_scan_group": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
     "pcr_enable_stage_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
     "pcr_last_stage_ms": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_float)]),
     "pcr_probe_scalar_issue_rate": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]),
@@ -164,6 +166,23 @@ class Record:
         _check(lib().pcr_decode_batch(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
                "pcr_decode_batch")
         return out
+
+    def upgrade_batch(self, k, out=None, status=None, stream=None):
+        """As decode_batch, but decodes only the scan groups above resident_scan_group() on top of the planes the
+        previous decode_batch / upgrade_batch left on the device."""
+        import torch
+        total = int(self.output_layout()[-1])
+        if out is None:
+            out = torch.empty(total, dtype=torch.uint8, device="cuda:%d" % self.device)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_upgrade_batch(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
+               "pcr_upgrade_batch")
+        return out
+
+    def resident_scan_group(self):
+        v = ctypes.c_int(0)
+        _check(lib().pcr_resident_scan_group(self._h, ctypes.byref(v)), "pcr_resident_scan_group")
+        return int(v.value)
 
     def enable_stage_timing(self, on=True):
         _check(lib().pcr_enable_stage_timing(self._h, 1 if on else 0), "pcr_enable_stage_timing")

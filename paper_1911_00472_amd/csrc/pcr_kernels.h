@@ -85,11 +85,12 @@ __global__ void __launch_bounds__(256) k_index(DevRecord R, uint32_t kmax) {
 // --------------------------------------------------------------------------------------
 // k_parse: one lane per image walks the marker segments of its regions 1..kmax.
 // --------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(64) k_parse(DevRecord R, uint32_t kmax) {
+// keep_status: a fidelity upgrade builds on planes decoded earlier; an image those calls found damaged stays so
+__global__ void __launch_bounds__(64) k_parse(DevRecord R, uint32_t kmax, uint32_t keep_status) {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= R.n) return;
     parse_image(R.rec, R.off, R.len, R.n, i, R.nscans[i], kmax, &R.img[i], &R.scan[(size_t)i * R.G]);
-    R.status[i] = R.img[i].status;
+    if (!(keep_status && R.status[i] != kOk)) R.status[i] = R.img[i].status;
 }
 
 // --------------------------------------------------------------------------------------
@@ -99,11 +100,12 @@ __global__ void __launch_bounds__(64) k_parse(DevRecord R, uint32_t kmax) {
 // --------------------------------------------------------------------------------------
 constexpr int kUnstuffPer = 8;
 
-__global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kmax) {
+// grid: (images, scan groups kfrom .. kmax-1)
+__global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kfrom, uint32_t kmax) {
     short_kernel_priority();
     __shared__ uint32_t part[256];
     __shared__ uint32_t s_stop;
-    uint32_t i = blockIdx.x, g = blockIdx.y;
+    uint32_t i = blockIdx.x, g = kfrom + blockIdx.y;
     if (g >= kmax) return;
     const ImgDesc& img = R.img[i];
     if (img.status != kOk || g >= img.nscans) return;
@@ -760,6 +762,18 @@ __global__ void __launch_bounds__(64) k_probe_scalar(uint32_t* out, uint32_t ite
             : "+s"(a), "+s"(b) : : "scc");
     }
     if (threadIdx.x == 0) out[blockIdx.x] = a ^ b;
+}
+
+// zero every coefficient except element 0 of each 64-element block (n16: 16-byte units, 8 per block)
+__global__ void __launch_bounds__(256) k_fill_zero_keep_dc(uint4* p, size_t n16) {
+    short_kernel_priority();
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n16; i += stride) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if ((i & 7) == 0) v.x = p[i].x & 0xFFFFu;          // the DC coefficient is the low half of the block's first word
+        p[i] = v;
+    }
 }
 
 __global__ void __launch_bounds__(256) k_fill_zero(uint4* p, size_t n16) {

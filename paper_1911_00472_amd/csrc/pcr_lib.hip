@@ -29,6 +29,7 @@ struct Plan {                               // launch geometry for one scan grou
     std::vector<LevelList> levels;
     ApplyUnit* d_apply = nullptr; ApplyList* d_apply_lists = nullptr; int32_t* d_list_idx = nullptr; uint32_t n_apply = 0, apply_grid_x = 0;
     bool has_ac = false;                     // some scan <= k is an AC scan (else only element 0 of every block is ever touched)
+    bool had_ac = false;                     // ... some scan <= k0 (the fidelity an upgrade starts from)
 };
 
 template <class T> int dev_alloc(T** p, size_t count) {
@@ -69,6 +70,7 @@ struct pcr_record {
     uint8_t* d_gather = nullptr; size_t gather_cap = 0;
     std::map<int, Plan> plans;
     bool timing = false;
+    int resident_k = 0;                        // scan group whose planes and masks the last pixel decode left behind (0: none)
     bool borrowed = false;                  // record bytes belong to the caller (pcr_open_device)
     // stage timing: one list of events per call, the last kTimingRing calls are kept
     std::vector<CallTiming> ring;
@@ -98,8 +100,10 @@ void compute_levels(pcr_record* r) {
     }
 }
 
-int build_plan(pcr_record* r, int k, Plan** out) {
-    auto it = r->plans.find(k);
+// Launch geometry for decoding scan groups k0+1 .. k (k0 = 0: from scratch) and turning groups 1 .. k into pixels.
+int build_plan(pcr_record* r, int k0, int k, Plan** out) {
+    const int key = k0 * 256 + k;
+    auto it = r->plans.find(key);
     if (it != r->plans.end()) { *out = &it->second; return PCR_OK; }
     const uint32_t n = r->hdr.n, G = r->hdr.G;
     Plan plan;
@@ -114,7 +118,8 @@ int build_plan(pcr_record* r, int k, Plan** out) {
             const size_t ig = (size_t)i * G + g;
             const ScanDesc& sd = r->scan[ig];
             if (sd.Ah > 0) for (int j = 0; j < sd.ns; j++) refine[sd.comp[j]] = true;
-            if (sd.Ss > 0) plan.has_ac = true;
+            if (sd.Ss > 0) { plan.has_ac = true; if (g < (uint32_t)k0) plan.had_ac = true; }
+            if (g < (uint32_t)k0) continue;                    // decoded by an earlier call
             if (sd.Ss == 0 && sd.Ah > 0) continue;             // DC refinement has no serial decode
             const int kind = sd.Ss == 0 ? kDcFirst : (sd.Ah == 0 ? kAcFirst : kAcRefine);
             if (kind == kAcRefine) {
@@ -154,7 +159,7 @@ int build_plan(pcr_record* r, int k, Plan** out) {
         rc = dev_upload(&plan.d_list_idx, list_idx); if (rc) return rc;
         rc = dev_alloc(&plan.d_apply_lists, apply.size()); if (rc) return rc;
     }
-    auto ins = r->plans.emplace(k, plan);
+    auto ins = r->plans.emplace(key, plan);
     *out = &ins.first->second;
     return PCR_OK;
 }
@@ -214,24 +219,30 @@ int add_call_times(const CallTiming& c, double* ms, uint32_t* marks) {
 // Steps 1-5 of the path (index .. entropy decode + refinement) for scans 1..k.
 // refine_in_memory: also run k_apply, which leaves the refined coefficients in the planes (the coefficient
 // export needs that; the pixel kernel replays the refinement itself from the lists of k_apply_prep).
-int run_entropy_stages(pcr_record* r, int k, hipStream_t s, bool refine_in_memory, Plan** plan_out) {
+// k0 > 0: a fidelity upgrade -- groups 1 .. k0 are in the planes and masks already, only k0+1 .. k are decoded.
+int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_in_memory, Plan** plan_out) {
     Plan* plan = nullptr;
-    int rc = build_plan(r, k, &plan);
+    int rc = build_plan(r, k0, k, &plan);
     if (rc) return rc;
     *plan_out = plan;
     const uint32_t n = r->hdr.n;
     call_begin(r, s);
     hipLaunchKernelGGL(k_index, dim3(k), dim3(256), 0, s, r->d, (uint32_t)k);
-    hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, (uint32_t)k);
+    hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, (uint32_t)k, (uint32_t)(k0 > 0));
     mark(r, PCR_STAGE_INDEX_PARSE, s);
-    hipLaunchKernelGGL(k_unstuff, dim3(n, k), dim3(256), 0, s, r->d, (uint32_t)k);
+    if (k > k0) hipLaunchKernelGGL(k_unstuff, dim3(n, k - k0), dim3(256), 0, s, r->d, (uint32_t)k0, (uint32_t)k);
     const size_t coef_bytes = r->coef_off[n] * sizeof(int16_t);
     // AC first scans only write the coefficients they decode: everything else must read as zero.  With DC scans
     // only, the DC first scan writes element 0 of every block and the pixel kernel reads nothing else, so the
     // fill is skipped (the coefficient export shows whole planes and always needs it).  The mask planes need no
     // fill: every entry a kernel reads was written earlier in the same call.
-    if (plan->has_ac || refine_in_memory)
-        hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
+    // An upgrade keeps the planes; only when it brings the first AC scans must everything but the DCs be cleared.
+    if (k0 == 0) {
+        if (plan->has_ac || refine_in_memory)
+            hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
+    } else if (plan->has_ac && !plan->had_ac) {
+        hipLaunchKernelGGL(k_fill_zero_keep_dc, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
+    }
     mark(r, PCR_STAGE_UNSTUFF, s);
     const uint32_t* c32 = reinterpret_cast<const uint32_t*>(r->d.clean);
     const uint64_t* h64 = r->d.masks;
@@ -440,7 +451,7 @@ int pcr_open_device(const void* d_bytes, size_t nbytes, void* stream, pcr_record
     if (!rc) { r->d.rec = (const uint8_t*)d_bytes; rc = alloc_descriptor_buffers(r); }
     if (!rc) {
         hipLaunchKernelGGL(k_index, dim3(h.k_avail), dim3(256), 0, s, r->d, h.k_avail);
-        hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, h.k_avail);
+        hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, h.k_avail, 0u);
         r->img.resize(n); r->scan.resize((size_t)n * G);
         if (hipMemcpyAsync(r->img.data(), r->d.img, n * sizeof(ImgDesc), hipMemcpyDeviceToHost, s) != hipSuccess ||
             hipMemcpyAsync(r->scan.data(), r->d.scan, (size_t)n * G * sizeof(ScanDesc), hipMemcpyDeviceToHost, s) != hipSuccess ||
@@ -578,7 +589,8 @@ int pcr_decode_coefficients(pcr_record* r, int k, int16_t* d_coef, void* stream)
     HIP_TRY(hipSetDevice(r->device));
     hipStream_t s = (hipStream_t)stream;
     Plan* plan = nullptr;
-    rc = run_entropy_stages(r, k, s, true, &plan);
+    r->resident_k = 0;                                       // k_apply refines the planes in place: nothing to upgrade from afterwards
+    rc = run_entropy_stages(r, 0, k, s, true, &plan);
     if (rc) return rc;
     call_end(r);
     hipLaunchKernelGGL(k_export_natural, dim3(2048), dim3(256), 0, s, r->d.coef, d_coef, (size_t)r->coef_off[r->hdr.n]);
@@ -586,15 +598,14 @@ int pcr_decode_coefficients(pcr_record* r, int k, int16_t* d_coef, void* stream)
     return PCR_OK;
 }
 
-int pcr_decode_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status) {
-    if (!r || !out) return PCR_E_ARG;
-    int rc = check_scan_group(r, k);
-    if (rc) return rc;
+// k0 = 0: from scratch; k0 > 0: on top of the planes and masks a previous call left for scan group k0
+static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status) {
     if (cap < r->out_off[r->hdr.n]) return PCR_E_RANGE;
     HIP_TRY(hipSetDevice(r->device));
     hipStream_t s = (hipStream_t)stream;
     Plan* plan = nullptr;
-    rc = run_entropy_stages(r, k, s, false, &plan);
+    r->resident_k = 0;
+    int rc = run_entropy_stages(r, k0, k, s, false, &plan);
     if (rc) return rc;
     if (plan->n_apply)
         hipLaunchKernelGGL(k_pixel<true>, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx);
@@ -604,7 +615,29 @@ int pcr_decode_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* strea
     call_end(r);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
     if (d_status) HIP_TRY(hipMemcpyAsync(d_status, r->d.status, r->hdr.n * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+    r->resident_k = k;
     return PCR_OK;
+}
+
+int pcr_decode_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status) {
+    if (!r || !out) return PCR_E_ARG;
+    int rc = check_scan_group(r, k);
+    if (rc) return rc;
+    return decode_to_pixels(r, 0, k, out, cap, stream, d_status);
+}
+
+int pcr_resident_scan_group(const pcr_record* r, int* k) {
+    if (!r || !k) return PCR_E_ARG;
+    *k = r->resident_k;
+    return PCR_OK;
+}
+
+int pcr_upgrade_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status) {
+    if (!r || !out) return PCR_E_ARG;
+    int rc = check_scan_group(r, k);
+    if (rc) return rc;
+    if (r->resident_k < 1 || k < r->resident_k) return PCR_E_ARG;
+    return decode_to_pixels(r, r->resident_k, k, out, cap, stream, d_status);
 }
 
 int pcr_probe_scalar_issue_rate(int device_id, int waves_per_cu, double* ginst_per_s) {

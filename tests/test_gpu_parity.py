@@ -331,3 +331,36 @@ def test_headline_full_size_four_records_on_four_streams():
     finally:
         for h in handles:
             h.close()
+
+
+def test_fidelity_upgrade_equals_fresh_decode(rgb_small, extreme_record):
+    """pcr_upgrade_batch on top of resident planes gives the bytes pcr_decode_batch gives from scratch, for
+    chains of upgrades that cross every dependency level, and the oracle agrees with both."""
+    torch = _torch()
+    for rec in (rgb_small[0], extreme_record[0]):
+        with pkg.pcr_open(rec, 0) as r:
+            assert r.resident_scan_group() == 0
+            with pytest.raises(pkg.PcrError):
+                r.upgrade_batch(2)                                 # nothing to build on yet
+            G = r.G
+            fresh = {k: r.decode_batch(k).clone() for k in range(1, G + 1)}
+            for chain in ([1, 2, 5, G], [1, G], [3, 3, G - 1, G], list(range(1, G + 1)), [6, 7], [2, 9]):
+                chain = [min(k, G) for k in chain]
+                st = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
+                out = r.decode_batch(chain[0])
+                assert r.resident_scan_group() == chain[0]
+                for k in chain[1:]:
+                    out = r.upgrade_batch(k, status=st)
+                    assert r.resident_scan_group() == k
+                    assert torch.equal(out, fresh[k]), ("upgrade", chain, k)
+                    assert (st.cpu().numpy() == 0).all()
+            with pytest.raises(pkg.PcrError):
+                r.upgrade_batch(1)                                 # lower than what is resident
+            r.decode_coefficients(G)                               # rewrites the planes in place
+            assert r.resident_scan_group() == 0
+            lay = r.output_layout()
+            host = fresh[G].cpu().numpy()
+            for i in range(0, r.n, 5):
+                _, p0, info = oracle.decode_record_image(rec, i, G, want_coef=False)
+                got = host[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
+                assert np.abs(got - p0).max() <= PIXEL_TOL
