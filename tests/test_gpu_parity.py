@@ -364,3 +364,28 @@ def test_fidelity_upgrade_equals_fresh_decode(rgb_small, extreme_record):
                 _, p0, info = oracle.decode_record_image(rec, i, G, want_coef=False)
                 got = host[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
                 assert np.abs(got - p0).max() <= PIXEL_TOL
+
+
+def test_decode_call_replays_from_a_hip_graph(rgb_small):
+    """After a warm-up call (which builds the work lists) a decode call is kernel launches only and can be
+    captured; every replay, with other eager decodes in between, gives the eager result."""
+    torch = _torch()
+    rec, _ = rgb_small
+    with pkg.pcr_open(rec, 0) as r:
+        k = r.G
+        eager = r.decode_batch(k).clone()
+        status = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
+        out = torch.empty_like(eager)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            r.decode_batch(k, out=out, status=status)
+        for other in (1, 3, k - 1):
+            out.fill_(0)
+            status.fill_(77)
+            r.decode_batch(other)                                  # eager work in between changes planes and masks
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), ("replay after", other)
+            assert (status.cpu().numpy() == 0).all()
