@@ -552,9 +552,18 @@ PCR_HD uint64_t take_correction_bits(BitReader* br, int n) {    // n <= 63; firs
     return out;
 }
 
+// What an AC refinement scan leaves per block: one record of kRefWords 64-bit words (zig-zag bit order),
+//   [kRefNz]    positions that become non-zero in this scan (later scans need them as history)
+//   [kRefSign]  their signs, 1 = positive                          } written by phase 2
+//   [kRefCbits] the correction bits in reading order, bit 0 first   }
+//   [kRefStart] bit offset of the block inside its unit | end-of-band run pending at its start << 32
+//   [kRefHist]  positions of the band already non-zero when the scan starts
+// Records of consecutive blocks are contiguous, so everything a consumer needs for a block is one line.
+constexpr int kRefNz = 0, kRefSign = 1, kRefCbits = 2, kRefStart = 3, kRefHist = 4, kRefWords = 5;
+
 // History of a refinement scan: the positions of its band that are non-zero when it starts.  What the
 // AC first scans made non-zero is read back from the coefficient plane (one coefficient per lane, a ballot
-// of "!= 0"); what earlier refinement scans added is in the nzout planes they wrote (p[0..n)).
+// of "!= 0"); what earlier refinement scans added is in the records they wrote (p[0..n): their record arrays).
 struct HistPlanes { const int16_t* coef; const uint64_t* p[kMaxHist]; int n; };
 
 struct HistWords {                                            // one block's history, combined only when used
@@ -568,8 +577,9 @@ struct HistWords {                                            // one block's his
 PCR_HD HistWords hist_fetch(const HistPlanes& hp, uint32_t blk, uint32_t lane) {
     HistWords w; w.a = 0; w.b = 0; w.c = 0;
     if (hp.n > 0) {                                           // entries beyond n repeat entry 0
-        w.a = hp.p[0][blk]; w.b = hp.p[1][blk]; w.c = hp.p[2][blk];
-        if (__builtin_expect(hp.n > 3, 0)) w.a |= hp.p[3][blk] | hp.p[4][blk] | hp.p[5][blk];
+        const uint32_t e = blk * kRefWords + kRefNz;
+        w.a = hp.p[0][e]; w.b = hp.p[1][e]; w.c = hp.p[2][e];
+        if (__builtin_expect(hp.n > 3, 0)) w.a |= hp.p[3][e] | hp.p[4][e] | hp.p[5][e];
     }
 #if defined(__HIP_DEVICE_COMPILE__)
     w.mine = hp.coef[(size_t)blk * 64 + lane];
@@ -670,15 +680,12 @@ struct ZeroTable {
 // Phase 1 (serial, one wavefront per unit): walk the scan only as far as needed to know where
 // every block starts.  For each symbol that means: the code (length, run, size), the zero the run
 // ends on and the NUMBER of correction bits stepped over on the way -- both read from the block's
-// zero table; the sign and correction bits themselves are not read.  Per block it writes
-//   nzout  positions that become non-zero in this scan (later scans need them as history),
-//   start  bit offset of the block inside the unit (low 32 bits) and the end-of-band run still
-//          pending when the block starts (high 32 bits),
-//   hist   the history mask it worked on (restricted to the band).
+// zero table; the sign and correction bits themselves are not read.  Per block it writes the
+// kRefNz, kRefStart and kRefHist words of the block's record.
 // The history of the next block is fetched while the current one is decoded.  Conditions are kept
 // as integer arithmetic and single compares: a boolean widened to an integer, or two conditions
 // and-ed together, cost the compiler a detour through the vector unit or through 64-bit lane masks.
-PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes& hp, uint64_t* nzout, uint64_t* start, uint64_t* hist_out) {
+PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes& hp, uint64_t* recs) {
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     const uint64_t band = band_mask(ls.Ss, ls.Se);
     uint32_t left = ls.mcu1 - ls.mcu0;                       // blocks still to do
@@ -697,8 +704,9 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
         left--;
         blk = left ? row * bw + col : here;
         hnext = hist_fetch(hp, blk, wr->lane);
-        hist_out[here] = h;                                  // phase 2 and the refinement replay work on the same history
-        start[here] = ((uint64_t)eobrun << 32) | wr->position();
+        uint64_t* rec = recs + (size_t)here * kRefWords;
+        rec[kRefStart] = ((uint64_t)eobrun << 32) | wr->position();
+        rec[kRefHist] = h;                                   // phase 2 and the refinement replay work on the same history
         const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
         uint64_t newm = 0;
         if (eobrun == 0) {                                   // symbols are read only outside an end-of-band run
@@ -734,7 +742,7 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
             wr->consume(ncorr);
             eobrun--;
         }
-        nzout[here] = newm;
+        rec[kRefNz] = newm;
         bad |= wr->overrun_bit();
         left = bad ? 0 : left;                               // stop at the first damaged block
     }

@@ -322,7 +322,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     uint64_t* mk = R.masks + uni((uint64_t)R.mask_off[ig]);
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tab, false, threadIdx.x);
-    int rc = skim_ac_refine(&wr, L.ls, hp, mk, mk + 3 * plane, mk + 4 * plane);
+    int rc = skim_ac_refine(&wr, L.ls, hp, mk);
     if (rc != kOk) R.status[un.img] = rc;
 }
 
@@ -352,12 +352,13 @@ __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const Refine
     const size_t blk = (size_t)(b / cw) * bw + (b % cw);
     const size_t plane = (size_t)bw * img->bh[c];
     uint64_t* mk = R.masks + R.mask_off[ig];
-    const uint64_t h = mk[4 * plane + blk];                  // the history phase 1 worked on
+    uint64_t* rec = mk + blk * kRefWords;
+    const uint64_t h = rec[kRefHist];                        // the history phase 1 worked on
     const uint32_t ivl = sd->ri ? b / sd->ri : 0;
     const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + clean_base(sd->data_off));
     uint64_t sgn, cb;
-    refine_block(words, R.ivl_start[R.slot_base[ig] + ivl], mk[3 * plane + blk], &tab, h, sd->Ss, sd->Se, &sgn, &cb);
-    mk[plane + blk] = sgn; mk[2 * plane + blk] = cb;
+    refine_block(words, R.ivl_start[R.slot_base[ig] + ivl], rec[kRefStart], &tab, h, sd->Ss, sd->Se, &sgn, &cb);
+    rec[kRefSign] = sgn; rec[kRefCbits] = cb;
 }
 
 // --------------------------------------------------------------------------------------
@@ -452,8 +453,8 @@ __global__ void __launch_bounds__(256) k_apply(DevRecord R, const ApplyUnit* __r
                 if (k != 0) continue;
                 if (dc_refinement_bit(R, S, row, col, hs, vs, covered)) v |= (int16_t)(1 << S.Al);
             } else if (k != 0 && covered && k >= S.Ss && k <= S.Se) {
-                const uint64_t* mk = R.masks + S.mask_off;   // planes: nzout, sign, cbits, start, history
-                v = refine_apply(v, k, mk[4 * plane + b], mk[b], mk[plane + b], mk[2 * plane + b], S.Al);
+                const uint64_t* rec = R.masks + S.mask_off + (size_t)b * kRefWords;
+                v = refine_apply(v, k, rec[kRefHist], rec[kRefNz], rec[kRefSign], rec[kRefCbits], S.Al);
             }
         }
         if (v != v0) pl[idx] = v;
@@ -615,12 +616,12 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
                                 // the eight positions k0..k0+7 as 8-bit fields of the scan's masks (all restricted to
                                 // its band); the correction bit of position k0 + j is number (non-zero history
                                 // positions below it) of the scan's string
-                                const uint64_t* mk = R.masks + S.mask_off;       // planes: nzout, sign, cbits, start, history
-                                const uint64_t hb = mk[4 * (size_t)nplane + b];
-                                const uint32_t h8 = (uint32_t)(hb >> k0) & 0xFF, n8 = (uint32_t)(mk[b] >> k0) & 0xFF;
-                                const uint32_t s8 = (uint32_t)(mk[nplane + b] >> k0) & 0xFF;
+                                const uint64_t* rec = R.masks + S.mask_off + (size_t)b * kRefWords;   // the block's record
+                                const uint64_t hb = rec[kRefHist];
+                                const uint32_t h8 = (uint32_t)(hb >> k0) & 0xFF, n8 = (uint32_t)(rec[kRefNz] >> k0) & 0xFF;
+                                const uint32_t s8 = (uint32_t)(rec[kRefSign] >> k0) & 0xFF;
                                 const uint32_t below = (uint32_t)__builtin_popcountll(hb & ((1ull << k0) - 1));
-                                const uint32_t c8 = (uint32_t)(mk[2 * (size_t)nplane + b] >> below) & 0xFF;
+                                const uint32_t c8 = (uint32_t)(rec[kRefCbits] >> below) & 0xFF;
                                 const int p1 = 1 << S.Al;
 #pragma unroll
                                 for (int j = 0; j < 8; j++) {

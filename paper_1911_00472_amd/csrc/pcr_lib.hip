@@ -323,7 +323,7 @@ static int finish_open(pcr_record* r) {
             const ScanDesc& sd = r->scan[ig];
             if (sd.Ss > 0) {
                 r->mask_off[ig] = nm;
-                nm += (uint64_t)d.bw[sd.comp[0]] * d.bh[sd.comp[0]] * (sd.Ah ? 5 : 0);   // refinement: nzout, sign, cbits, start, history
+                nm += (uint64_t)d.bw[sd.comp[0]] * d.bh[sd.comp[0]] * (sd.Ah ? kRefWords : 0);   // one record per block of a refinement scan
                 if (sd.Ah) tab_idx[ig] = ntabs++;
             }
             uint32_t cnt = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;

@@ -65,7 +65,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
         for (size_t e = 0; e + 3 < clean.size(); e += 4) { std::swap(clean[e], clean[e + 3]); std::swap(clean[e + 1], clean[e + 2]); }   // big-endian words
         int c0 = sd.comp[0];
         size_t plane = (size_t)img.bw[c0] * img.bh[c0];
-        if (sd.Ss > 0 && sd.Ah) masks[g].assign(plane * 5, 0);   // nzout, sign, cbits, start, history
+        if (sd.Ss > 0 && sd.Ah) masks[g].assign(plane * kRefWords, 0);
         if (sd.Ss == 0 && sd.Ah > 0) continue;                     // DC refinement: applied below, in place
         for (uint32_t j = 0; j < nint; j++) {
             LaneScan ls;
@@ -93,14 +93,14 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 } else {
                     HistPlanes hp; hp.n = sd.nhist; hp.coef = cpl[0];
                     for (int q = 0; q < kMaxHist; q++) hp.p[q] = sd.nhist ? masks[sd.hist[q < sd.nhist ? q : 0]].data() : nullptr;
-                    rc = skim_ac_refine(&wr, ls, hp, masks[g].data(), masks[g].data() + 3 * plane, masks[g].data() + 4 * plane);
+                    rc = skim_ac_refine(&wr, ls, hp, masks[g].data());
                     if (rc) return rc;
                     // phase 2: every block of this interval on its own
                     for (uint32_t mm = ls.mcu0; mm < ls.mcu1; mm++) {
                         size_t blk = (size_t)(mm / sd.mcu_w) * img.bw[c0] + (mm % sd.mcu_w);
-                        const uint64_t hh = masks[g][4 * plane + blk];
-                        refine_block(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], masks[g][3 * plane + blk], &at, hh, sd.Ss, sd.Se,
-                                     &masks[g][plane + blk], &masks[g][2 * plane + blk]);
+                        uint64_t* rec = masks[g].data() + blk * kRefWords;
+                        refine_block(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], rec[kRefStart], &at, rec[kRefHist], sd.Ss, sd.Se,
+                                     &rec[kRefSign], &rec[kRefCbits]);
                     }
                 }
             }
@@ -130,7 +130,8 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                     if (dc_refine_bit(reinterpret_cast<const uint32_t*>(cleans[g].data()), ivls[g][ivl], bit)) v |= (int16_t)(1 << sd.Al);
                 } else if (kk != 0 && covered && sd.comp[0] == c && sd.Ah != 0 && kk >= sd.Ss && kk <= sd.Se) {
                     const uint64_t* mk = masks[g].data();
-                    v = refine_apply(v, kk, mk[4 * plane + blk], mk[blk], mk[plane + blk], mk[2 * plane + blk], sd.Al);
+                    const uint64_t* rec = mk + blk * kRefWords;
+                    v = refine_apply(v, kk, rec[kRefHist], rec[kRefNz], rec[kRefSign], rec[kRefCbits], sd.Al);
                 }
             }
             *cp = v;
