@@ -38,9 +38,12 @@ struct AcTab {
     uint16_t valptr[8];         // valptr[L-9]: index in huffval of the first code of length L
     uint32_t sh2;               // lut2 index = (code16 - limit[0]) >> sh2
     uint8_t huffval[256];
-    uint32_t pad;               // odd number of dwords: per-lane copies spread over the LDS banks
+    uint32_t pad;
+    // the 8-bit look-up again, pre-packed for the lanes of a window reader (see packed_entry): everything
+    // of a symbol's packed word that does not depend on the bits after the code
+    uint32_t lutp[256];
 };
-static_assert(sizeof(AcTab) == 1084, "AcTab layout");
+static_assert(sizeof(AcTab) == 1084 + 1024, "AcTab layout");
 
 struct DcTab {                  // DC symbols are categories 0..15
     uint8_t lut[256];           // (length << 4) | symbol for codes of <= 8 bits, 0xFF otherwise
@@ -248,6 +251,28 @@ PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
     return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | (uint32_t)(r + ((flags & kSymEob) ? 64 : 0));
 }
 
+// Pre-packed table entry for a symbol whose code has `len` bits: the low 16 bits are those of the packed
+// word (advance, total bits, flags), bits 16..20 the code length and bits 21..24 the number of appended
+// bits, which finish_packed() replaces by the appended value.  0 stays "not in this table".
+PCR_HD uint32_t packed_entry(uint32_t e, bool first) {
+    if (e == 0) return 0;
+    const uint32_t low = pack_symbol(e, 0, first) & 0xFFFFu;
+    if (low == kSymInvalid) return kSymInvalid;               // (no appended bits: finish_packed leaves it alone)
+    const uint32_t len = e >> 8, r = (e >> 4) & 15, s = e & 15;
+    const uint32_t nx = s ? (first ? s : 1u) : (r != 15 ? r : 0u);
+    return low | (len << 16) | (nx << 21);
+}
+PCR_HD uint32_t finish_packed(uint32_t p, uint32_t win, bool first) {
+    const uint32_t len = (p >> 16) & 31, nx = (p >> 21) & 15;
+    uint32_t x = ((win << len) >> 1) >> (31 - nx);            // the nx bits after the code (nx = 0: none)
+    if (first && (p & kSymCoef)) x = (uint32_t)extend(x, (int)nx) & 0xFFFFu;
+    return (p & 0xFFFFu) | (x << 16);
+}
+// fills lutp from lut: entry i by lane (i mod nlanes); call with every lane of the workgroup, after lut is complete
+PCR_HD void actab_pack(AcTab* t, bool first, uint32_t lane, uint32_t nlanes) {
+    for (uint32_t i = lane; i < 256; i += nlanes) t->lutp[i] = packed_entry(t->lut[i], first);
+}
+
 struct WindowReader {
     StreamPtr p;                // words after n1
     const AcTab* tab;
@@ -270,8 +295,8 @@ struct WindowReader {
     PCR_HD void fill() {
 #if defined(__HIP_DEVICE_COMPILE__)
         const uint32_t win = bits_at(w0, w1, w2, (int)lane);
-        const uint32_t e = tab->lut[win >> 24];
-        vinfo = e ? pack_symbol(e, win, first) : 0;
+        const uint32_t p = tab->lutp[win >> 24];
+        vinfo = p ? finish_packed(p, win, first) : 0;
 #endif
     }
     PCR_HD uint32_t lookup(uint32_t off) const {
@@ -279,8 +304,8 @@ struct WindowReader {
         return (uint32_t)__builtin_amdgcn_readlane((int)vinfo, (int)off);
 #else
         const uint32_t win = bits_at(w0, w1, w2, (int)off);
-        const uint32_t e = tab->lut[win >> 24];
-        return e ? pack_symbol(e, win, first) : 0;
+        const uint32_t p = tab->lutp[win >> 24];
+        return p ? finish_packed(p, win, first) : 0;
 #endif
     }
     PCR_HD bool exhausted() const { return o >= 64; }         // the next symbol starts beyond the window

@@ -283,6 +283,8 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     const size_t ig = (size_t)un.img * R.G + un.scan;
     if (threadIdx.x == 0) actab_build(&tab, R.rec + R.scan[ig].ac_off);
     __syncthreads();
+    actab_pack(&tab, true, threadIdx.x, kEntropyLanes);
+    __syncthreads();
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x);
     CoefSink sink;
@@ -304,6 +306,8 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     const size_t ig = (size_t)un.img * R.G + un.scan;
     const ScanDesc* sd = &R.scan[ig];
     if (threadIdx.x == 0) actab_build(&tab, R.rec + sd->ac_off);
+    __syncthreads();
+    actab_pack(&tab, false, threadIdx.x, kEntropyLanes);
     __syncthreads();
     if (un.interval == 0) {                                 // phase 2 needs the same table: keep a copy
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&tab);
