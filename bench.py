@@ -71,6 +71,14 @@ AC_REFINE_PMC = {
 }
 SALU_PEAK_GINSTS = 256 * 2.4      # one scalar instruction per cycle per compute unit, 256 CUs, 2.4 GHz
 
+# Algorithmic work of the entropy kernels: Huffman-coded symbols per launch, counted with the CPU build of the
+# decoders (tests/host_emul) on record 0 of the default workload, and the scalar operations the serial chain of
+# this design needs per symbol at the very least (fetch the packed word of the current bit offset, test it, take
+# its length, add it to the position, apply the position update, test for the end of the block and of the
+# window).  Everything else a symbol needs is data-parallel work of the lanes.
+SYMBOLS_RECORD0 = {"dc_first": [3981894], "ac_first": [62868359], "ac_refine": [53792045, 46598601]}
+CHAIN_OPS_PER_SYMBOL = 8
+
 
 def dominant_kernel_roofline(args, ends0, alone_ms, over_ms, alone, n_img, probe):
     """Roofline object for k_ac_refine, the kernel with the largest share of the step at scan group 10
@@ -86,21 +94,29 @@ def dominant_kernel_roofline(args, ends0, alone_ms, over_ms, alone, n_img, probe
     alg = float(sum(sizes[:, j - 1].sum() for j in scans if j <= k)) / launches_per_call
     default = args.images == 4096 and k == HEADLINE_K and name == "ac_refine"
     pmc = AC_REFINE_PMC if default else None
+    sym = (sum(SYMBOLS_RECORD0[name]) / len(SYMBOLS_RECORD0[name])) if (args.images == 4096 and k == HEADLINE_K) else None
+    achieved = (CHAIN_OPS_PER_SYMBOL * sym / (ms * 1e-3) / 1e9) if sym else None
     out = {
         "kernel": "k_%s (one record of %d images decoded alone, mean of its %d launches per decode)" % (name, ends0.shape[0], launches_per_call),
         "bound": "alu",
-        "achieved": (pmc["salu_insts_per_launch"] / (ms * 1e-3) / 1e9) if pmc else None,
-        "peak": SALU_PEAK_GINSTS, "unit": "G scalar instructions/s",
-        "frac": (pmc["salu_insts_per_launch"] / (ms * 1e-3) / 1e9 / SALU_PEAK_GINSTS) if pmc else None,
+        "achieved": achieved, "peak": SALU_PEAK_GINSTS, "unit": "G scalar operations/s",
+        "frac": (achieved / SALU_PEAK_GINSTS) if achieved else None,
         "traffic": (pmc["fetch_bytes_per_launch"] + pmc["write_bytes_per_launch"]) if pmc else None,
-        "peak_measured": probe, "frac_of_measured": (pmc["salu_insts_per_launch"] / (ms * 1e-3) / 1e9 / probe) if pmc else None,
+        "algorithmic": {"symbols_per_launch": sym, "chain_operations_per_symbol": CHAIN_OPS_PER_SYMBOL,
+                        "symbols_per_s": (sym / (ms * 1e-3)) if sym else None},
+        "issued": {"scalar_insts_per_launch": pmc["salu_insts_per_launch"] if pmc else None,
+                   "vector_insts_per_launch": pmc["valu_insts_per_launch"] if pmc else None,
+                   "G_scalar_insts_per_s": (pmc["salu_insts_per_launch"] / (ms * 1e-3) / 1e9) if pmc else None,
+                   "frac_of_peak": (pmc["salu_insts_per_launch"] / (ms * 1e-3) / 1e9 / SALU_PEAK_GINSTS) if pmc else None},
+        "peak_measured": probe,
         "ms_per_launch": ms, "ms_per_launch_overlapped": over_ms[name],
         "hbm_view": {"algorithmic_bytes_per_launch": alg, "achieved_GBps": alg / (ms * 1e-3) / 1e9,
                      "frac_of_8TBps": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "note": "a serial Huffman decoder is bound by scalar-ALU issue (one wavefront per stream), not by HBM; the "
-                "instruction and byte counts per launch are rocprofv3 counter readings (profiles/), the duration is "
-                "measured here with HIP events; peak = 256 CUs x 1 scalar instruction per cycle x 2.4 GHz, peak_measured = "
-                "the library's dependent-scalar-chain probe in this run",
+        "note": "a serial Huffman decoder is bound by scalar-ALU issue (one wavefront per stream), not by HBM.  achieved = "
+                "symbols per launch x the scalar operations the serial chain needs per symbol / the launch duration measured "
+                "here with HIP events (record alone); peak = 256 CUs x 1 scalar instruction per cycle x 2.4 GHz; peak_measured "
+                "= the library's dependent-scalar-chain probe in this run; issued = what the kernel really executes "
+                "(rocprofv3 counters, profiles/)",
     }
     return out
 
