@@ -70,6 +70,8 @@ AC_REFINE_PMC = {
     "write_bytes_per_launch": 0.5 * (160539.1 + 104374.0) * 1024 * 1.0,
 }
 SALU_PEAK_GINSTS = 256 * 2.4      # one scalar instruction per cycle per compute unit, 256 CUs, 2.4 GHz
+# all kernels of one decode of record 0 at scan group 10 (same counter run): scalar / vector instructions
+RECORD0_INSTS = {"scalar": 3786.4e6, "vector": 2102.0e6}
 
 # Algorithmic work of the entropy kernels: Huffman-coded symbols per launch, counted with the CPU build of the
 # decoders (tests/host_emul) on record 0 of the default workload, and the scalar operations the serial chain of
@@ -299,6 +301,13 @@ def main():
         "open_ms_per_record": open_ms,
         "path_roofline": {"bound": "hbm", "achieved": ab["path"] / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS},
+        "path_issue": ({"scalar_insts_per_step": RECORD0_INSTS["scalar"] * len(records), "vector_insts_per_step": RECORD0_INSTS["vector"] * len(records),
+                        "G_scalar_insts_per_s": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9,
+                        "frac_of_peak": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9 / SALU_PEAK_GINSTS,
+                        "frac_of_measured_peak": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9 / probe,
+                        "note": "instructions of one record (rocprofv3 counters of record 0) x records, over the timed step: how "
+                                "busy the scalar units are when the records overlap"}
+                       if (args.images == 4096 and args.scan_group == HEADLINE_K) else None),
         "roofline": roofline,
         "cpu_baseline": cpu,
         "per_scan_group": report,
