@@ -224,7 +224,9 @@ PCR_HD int extend(uint32_t v, int s) { return (s && v < (1u << (s - 1))) ? (int)
 // really lands on them.  The window is 96 bits of stream (w0,w1,w2): offsets 0..63 each with
 // 32 bits of look-ahead; two more words are always already loaded.
 //
-// packed word: value (16 bits, signed) << 16 | flags (bits 15, 14) | total bits (6) << 8 | advance (7 bits, see pack_symbol)
+// packed word: value (16 bits, signed) << 16 | kSymCoef | kSymEob | total bits (6) << 8 | kSymSpecial | advance (7 bits)
+// (see pack_symbol).  Offsets whose code the lanes cannot resolve carry kSymMiss, a word that makes the serial
+// part leave its straight line exactly as an end of band does, so that the common path tests nothing extra.
 // ---------------------------------------------------------------------------------------
 PCR_HD uint32_t bits_at(uint32_t w0, uint32_t w1, uint32_t w2, int j) {      // 32 bits from offset j (0..63)
     const uint32_t hi = j < 32 ? w0 : w1, lo = j < 32 ? w1 : w2;
@@ -234,8 +236,18 @@ PCR_HD uint32_t bits_at(uint32_t w0, uint32_t w1, uint32_t w2, int j) {      // 
 // e: table entry (length << 8 | symbol), non-zero.  first: AC first scan (size s = s value bits,
 // sign-extended here); otherwise refinement (size 1 = one sign bit).  An end-of-band symbol
 // (size 0, run r < 15) is followed by r bits of run length in both.
-constexpr uint32_t kSymCoef = 0x8000u, kSymEob = 0x4000u;
-constexpr uint32_t kSymInvalid = kSymEob;                    // "end of band" of length 0: what the AC decoders see where no code matches
+//
+// The low 7 bits are how far the symbol moves the decoder on, counted to the position AFTER the one it
+// lands on: run + 1 for a coefficient and for sixteen zeros, 65 + run ("past everything") for an end of
+// band.  AC first scans add it to the position in the band, refinement scans to the index into the
+// block's zero table.  kSymSpecial marks the words the straight line of a decoder cannot finish by itself:
+//   kSymMiss   no code of <= 8 bits starts here (a longer code, or no code at all): length 0, advance 127;
+//   in a refinement scan, sixteen zeros: it lands on a zero WITHOUT taking it, so it is given the advance
+//   of an end of band (80) and redone by hand.
+constexpr uint32_t kSymCoef = 0x8000u, kSymEob = 0x4000u, kSymSpecial = 0x80u;
+constexpr uint32_t kSymMiss = kSymSpecial | 127u;
+constexpr uint32_t kSymInvalid = kSymEob | 65u;              // "end of band" of length 0: what the AC decoders see where no code matches
+constexpr uint32_t kZrlAdvance = 16;
 
 PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
     const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
@@ -244,18 +256,18 @@ PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
     const int value = (first && s) ? extend(extra, s) : (int)extra;
     // bit 15: the symbol carries a coefficient; bit 14: it is an end-of-band symbol
     const uint32_t flags = (s ? kSymCoef : 0u) | ((s == 0 && r != 15) ? kSymEob : 0u);
-    // The low byte is how far the symbol moves on before the position it lands on: the run r, or 64 + r
-    // ("past everything") for an end-of-band symbol.  AC first scans add it to the position in the band,
-    // refinement scans to the index into the block's zero table.
     if (!first && s > 1) return kSymInvalid;                 // sizes above 1 do not exist in a refinement scan
-    return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | (uint32_t)(r + ((flags & kSymEob) ? 64 : 0));
+    uint32_t adv = (uint32_t)r + 1u;
+    if (flags & kSymEob) adv += 64u;
+    else if (!first && s == 0) adv = kSymSpecial | (64u + kZrlAdvance);
+    return ((uint32_t)(value & 0xFFFF) << 16) | flags | ((uint32_t)(len + nx) << 8) | adv;
 }
 
 // Pre-packed table entry for a symbol whose code has `len` bits: the low 16 bits are those of the packed
 // word (advance, total bits, flags), bits 16..20 the code length and bits 21..24 the number of appended
-// bits, which finish_packed() replaces by the appended value.  0 stays "not in this table".
+// bits, which finish_packed() replaces by the appended value.  "Not in this table" is kSymMiss.
 PCR_HD uint32_t packed_entry(uint32_t e, bool first) {
-    if (e == 0) return 0;
+    if (e == 0) return kSymMiss;
     const uint32_t low = pack_symbol(e, 0, first) & 0xFFFFu;
     if (low == kSymInvalid) return kSymInvalid;               // (no appended bits: finish_packed leaves it alone)
     const uint32_t len = e >> 8, r = (e >> 4) & 15, s = e & 15;
@@ -295,37 +307,28 @@ struct WindowReader {
     PCR_HD void fill() {
 #if defined(__HIP_DEVICE_COMPILE__)
         const uint32_t win = bits_at(w0, w1, w2, (int)lane);
-        const uint32_t p = tab->lutp[win >> 24];
-        vinfo = p ? finish_packed(p, win, first) : 0;
+        vinfo = finish_packed(tab->lutp[win >> 24], win, first);
 #endif
     }
+    // packed word of the offset `off` of the window (0..63); kSymMiss where no short code starts
     PCR_HD uint32_t lookup(uint32_t off) const {
 #if defined(__HIP_DEVICE_COMPILE__)
         return (uint32_t)__builtin_amdgcn_readlane((int)vinfo, (int)off);
 #else
         const uint32_t win = bits_at(w0, w1, w2, (int)off);
-        const uint32_t p = tab->lutp[win >> 24];
-        return p ? finish_packed(p, win, first) : 0;
+        return finish_packed(tab->lutp[win >> 24], win, first);
 #endif
+    }
+    // the same for an offset that lookup() answered with kSymMiss: a code longer than 8 bits, or garbage
+    PCR_HD uint32_t resolve(uint32_t off) const {
+        const uint32_t win = bits_at(w0, w1, w2, (int)off);
+        const uint32_t e = ac_long_code(tab, win);
+        return uni(e ? pack_symbol(e, win, first) : kSymInvalid);
     }
     PCR_HD bool exhausted() const { return o >= 64; }         // the next symbol starts beyond the window
     PCR_HD void refill() {
         do { w0 = w2; w1 = n0; w2 = n1; n0 = p[0]; n1 = p[1]; p += 2; o -= 64; wbase += 64; } while (o >= 64);
         fill();
-    }
-    // packed word of the symbol at the current position; 0 if the bits there are no code
-    PCR_HD uint32_t symbol() {
-        if (o >= 64) refill();
-        return peek();
-    }
-    PCR_HD uint32_t peek() {                                  // as symbol(), for a position known to lie inside the window
-        uint32_t info = lookup(o);
-        if (__builtin_expect(info == 0, 0)) {                // a code longer than 8 bits, or garbage
-            const uint32_t win = bits_at(w0, w1, w2, (int)o);
-            const uint32_t e = ac_long_code(tab, win);
-            info = e ? pack_symbol(e, win, first) : kSymInvalid;
-        }
-        return info;
     }
     PCR_HD void consume(uint32_t n) { o += n; }
     PCR_HD uint32_t position() const { return wbase + o - mis_bits; }       // bits consumed since the unit's first bit
@@ -345,33 +348,37 @@ struct LaneScan {
 };
 
 // ---------------------------------------------------------------------------------------
-// CoefSink: keeps memory off the serial path.  A decoded coefficient goes, as (element index, word
-// with the value in its top 16 bits), into the next free lane of two vector registers; the lanes
-// store all pending pairs at once each time the bit window slides (at most 64 symbols start
-// inside a 64-bit window, so the lanes always suffice).
+// CoefSink: keeps memory off the serial path.  Every symbol the serial part passes goes, as (element
+// index, packed word with the value in its top 16 bits), into two vector registers, in the lane whose
+// number is the window offset the symbol STARTS at: symbols that start inside one window start at
+// different offsets, so no counter is needed.  Each time the bit window slides the lanes whose word
+// carries kSymCoef store their value, and all words are cleared.  Words without kSymCoef (an end of
+// band, sixteen zeros, an unresolved code) are written too and simply never stored.  The element
+// index is checked against the plane's size by the lanes, so the serial part need not clamp what a
+// damaged stream makes of it.
 // ---------------------------------------------------------------------------------------
 struct CoefSink {
     int16_t* plane;
+    uint32_t limit;                                           // elements of `plane`
     int Al;                                                   // values are stored shifted left by this
-    uint32_t lane, cnt;
-    uint32_t vidx; int vval;                                  // device: one pending store per lane below cnt
-    PCR_HD void init(int16_t* p, int al, uint32_t lane_id) { plane = p; Al = al; lane = lane_id; cnt = 0; vidx = 0; vval = 0; }
-    // word: packed symbol word, its value in the top 16 bits; count_it = 0: the pair is dropped
-    PCR_HD void emit(uint32_t elem, int word, uint32_t count_it) {
+    uint32_t vidx; int vval;                                  // device: this lane's pending pair
+    PCR_HD void init(int16_t* p, uint32_t elems, int al) { plane = p; limit = elems; Al = al; vidx = 0; vval = 0; }
+    // slot: window offset the symbol starts at (0..63); word: packed symbol word
+    PCR_HD void emit(uint32_t slot, uint32_t elem, int word) {
 #if defined(__HIP_DEVICE_COMPILE__)
-        // lane `cnt` of the two registers takes the pair (the lane select travels in m0: a vector
-        // instruction of this chip reads at most one scalar register besides it)
+        // (the lane select travels in m0: a vector instruction of this chip reads at most one scalar
+        // register besides it)
         asm volatile("s_mov_b32 m0, %4\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
-                     : "+v"(vidx), "+v"(vval) : "s"(elem), "s"(word), "s"(cnt) : "m0");
-        cnt += count_it;
+                     : "+v"(vidx), "+v"(vval) : "s"(elem), "s"(word), "s"(slot) : "m0");
 #else
-        if (count_it) plane[elem] = (int16_t)((word >> 16) * (1 << Al));
+        (void)slot;
+        if (((uint32_t)word & kSymCoef) && elem < limit) plane[elem] = (int16_t)((word >> 16) * (1 << Al));
 #endif
     }
     PCR_HD void flush() {
 #if defined(__HIP_DEVICE_COMPILE__)
-        if (lane < cnt) plane[vidx] = (int16_t)((vval >> 16) * (1 << Al));
-        cnt = 0;
+        if (((uint32_t)vval & kSymCoef) && vidx < limit) plane[vidx] = (int16_t)((vval >> 16) * (1 << Al));
+        vval = 0;
 #endif
     }
 };
@@ -471,9 +478,9 @@ PCR_HD int decode_dc_first(DcWindowReader* wr, const LaneScan& ls, int tj0, int 
                             wr->refill();
                         }
                         const uint32_t info = wr->peek(tj[j]);
-                        wr->consume((info >> 8) & 63);
                         pred[j] += (int32_t)info >> 16;
-                        sink->emit(e, (int)((uint32_t)pred[j] << 16), 1);
+                        sink->emit(wr->o, e, (int)(((uint32_t)pred[j] << 16) | kSymCoef));
+                        wr->consume((info >> 8) & 63);
                         e += 64;
                     }
                     rowe += bw * 64;
@@ -511,12 +518,17 @@ PCR_HD uint64_t nz_mask_of_block(const int16_t* blk, int Ss, int Se) {
 }
 
 PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink) {
-    const uint32_t Ss = (uint32_t)ls.Ss, Se = (uint32_t)ls.Se; const int Al = ls.Al;
+    const uint32_t Ss = (uint32_t)ls.Ss, Se = (uint32_t)ls.Se;
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
+    // Positions are kept biased: kb = (zig-zag position of the next candidate) + bias with bias = 63 - Se,
+    // so that "the band is complete" reads kb >= 64 whatever Se is, the same bit that says "the window
+    // is used up" in the window offset.  After a symbol's advance (run + 1) kb is one past the position
+    // it landed on; base_b = element index of the block - bias - 1 makes base_b + kb that element.
+    const uint32_t bias = 63 - Se;
     uint32_t left = ls.mcu1 - ls.mcu0;                       // blocks of the unit not finished yet (the current one included)
     uint32_t row = ls.mcu0 / mcu_w, col = ls.mcu0 % mcu_w;
-    uint32_t base = (row * bw + col) * 64;                   // element index of the current block
-    uint32_t k = Ss;
+    uint32_t base_b = (row * bw + col) * 64 - bias - 1;
+    uint32_t kb = Ss + bias;
     uint32_t bad = 0;
     while (left != 0) {
         if (wr->exhausted()) {
@@ -524,32 +536,39 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
             bad |= wr->overrun_bit();                        // never walk far beyond the unit's data
             wr->refill();
         }
-        uint32_t window_end = 64;                            // set to 0 to leave the inner loop when the unit is done
+        uint32_t info;
         do {                                                 // symbols that start inside the current window
             // One straight line for every symbol: a coefficient (run r, then the value) and sixteen zeros
-            // (r = 15) both move on by r + 1; the packed word goes to the sink in every case and is simply
-            // not counted unless it carries a coefficient.  Only a block change leaves the line.
-            const uint32_t info = wr->peek();
+            // (r = 15) both move on by r + 1; every packed word goes to the sink, which stores only those that
+            // carry a coefficient.  An end of band and an unresolved code move "past everything".
+            info = wr->lookup(wr->o);
+            kb += info & 127;
+            sink->emit(wr->o, base_b + kb, (int)info);
             wr->consume((info >> 8) & 63);
-            const uint32_t k2 = k + (info & 127);            // + run, or + 64 + run for an end of band
-            sink->emit(base + (k2 & 63), (int)info, (info >> 15) & 1);   // & 63: stays inside the block whatever the stream says
-            k = k2 + 1;
-            if (__builtin_expect(k > Se, 0)) {               // the block is finished: band complete, or end of band
+        } while ((kb | wr->o) < 64);
+        if (kb >= 64) {                                      // the block is finished, or the lanes left the code to us
+            if (info & kSymSpecial) {                        // a code longer than 8 bits (or none): the same step by hand
+                kb -= kSymMiss & 127;
+                info = wr->resolve(wr->o);
+                kb += info & 127;
+                sink->emit(wr->o, base_b + kb, (int)info);
+                wr->consume((info >> 8) & 63);
+            }
+            if (kb >= 64) {                                  // band complete, or end of band
                 uint32_t adv = 1;                            // blocks to move on by
                 if (info & kSymEob) {                        // run of 2^r + extra blocks; no code at all has length 0
                     bad |= (info & 0x3F00) ? 0u : 1u;
-                    adv = (1u << (info & 15)) + (info >> 16);
+                    adv = (1u << ((info & 127) - 65)) + (info >> 16);
                 } else {
-                    bad |= (k2 > Se) ? ((info >> 15) & 1) : 0u;   // a coefficient beyond the band
+                    bad |= (kb > 64) ? ((info >> 15) & 1) : 0u;   // a coefficient beyond the band
                 }
                 adv = adv < left ? adv : left;
                 left = bad ? 0 : left - adv;                 // stop at the first damaged block
-                window_end = left ? 64 : 0;
-                col += adv; k = Ss;
+                col += adv; kb = Ss + bias;
                 while (col >= mcu_w) { col -= mcu_w; row++; }
-                base = (row * bw + col) * 64;
+                base_b = (row * bw + col) * 64 - bias - 1;
             }
-        } while (wr->o < window_end);
+        }
     }
     sink->flush();
     bad |= wr->overrun_bit();
@@ -624,23 +643,25 @@ PCR_HD uint64_t hist_combine(const HistWords& w) {
 
 // Zero table of one block: entry n describes the n-th position of the band that is still zero
 // when the scan reaches the block (n = 0, 1, ...; zig-zag order):
-//     position (bits 0..5) | non-zero-history positions below it (bits 8..14) | kZtLast | kZtSentinel
+//     position (bits 0..5) | non-zero-history positions below it (bits 8..13) | kZtLast | kZtSentinel
 // kZtLast marks the entry after which nothing is left in the block: the last zero if no non-zero
 // history position follows it, and every sentinel.  Entries from number-of-zeros on are sentinels:
 // "no such zero", with the count field = all non-zero-history positions of the band.
 // With the table the serial decoder does no bit arithmetic per symbol: a run of r zeros followed by
-// a new coefficient is "index += r, read the entry, index += 1", and the number of correction bits
-// to step over is the difference of two count fields.  The 64 lanes build the table in a handful
-// of vector instructions (a prefix count of the two masks and one permute); lane i also keeps the
-// index of ITS position so that the positions that were taken can be read back as a mask.
-constexpr uint32_t kZtLast = 1u << 16, kZtSentinel = 1u << 17;
+// a new coefficient is "index += r + 1, read the entry", and the number of correction bits to step
+// over is the difference of two count fields.  kZtLast sits directly above the count field, so that
+// the 7-bit field reads "count + 64" on a last entry: added to the window offset it pushes the offset
+// past the window, and the one test "offset < 64" ends the symbol loop for both reasons.
+// The 64 lanes build the table in a handful of vector instructions (a prefix count of the two masks
+// and one permute); lane i also keeps the index of ITS position so that the set of table entries
+// that were taken can be turned back into a mask of positions.
+constexpr uint32_t kZtLast = 1u << 14, kZtSentinel = 1u << 17;
 
 struct ZeroTable {
 #if defined(__HIP_DEVICE_COMPILE__)
     uint32_t ventry, vindex;                                  // lane n: entry n; lane i: table index of position i (64 if not a zero)
-    uint32_t vword;                                           // lane n: packed word of the symbol that landed on entry n (0: none)
 #else
-    uint32_t entry[64], index[64], word[64];
+    uint32_t entry[64], index[64];
 #endif
     PCR_HD void build(uint64_t h, uint64_t z, uint32_t nzeros, uint32_t ncorr, uint32_t lane) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -652,7 +673,6 @@ struct ZeroTable {
         const uint32_t dest = iz ? rank : nzeros + (lane - rank);       // a permutation of the 64 lanes
         ventry = (uint32_t)__builtin_amdgcn_ds_permute((int)(dest * 4), (int)data);
         vindex = iz ? rank : 64u;
-        vword = 0;
 #else
         (void)lane;
         uint32_t rank = 0, below = 0;
@@ -663,23 +683,7 @@ struct ZeroTable {
             entry[iz ? rank : nzeros + (i - rank)] = data;
             index[i] = iz ? rank : 64u;
             rank += iz; below += (h >> i) & 1;
-            word[i] = 0;
         }
-#endif
-    }
-    // remember which symbol landed on entry n (one scalar move and one lane write on the device)
-    PCR_HD void land(uint32_t n, uint32_t info) {
-#if defined(__HIP_DEVICE_COMPILE__)
-        asm volatile("s_mov_b32 m0, %2\n\tv_writelane_b32 %0, %1, m0" : "+v"(vword) : "s"(info), "s"(n) : "m0");
-#else
-        word[n] = info;
-#endif
-    }
-    PCR_HD uint32_t landed(uint32_t n) const {
-#if defined(__HIP_DEVICE_COMPILE__)
-        return (uint32_t)__builtin_amdgcn_readlane((int)vword, (int)n);
-#else
-        return word[n];
 #endif
     }
     PCR_HD uint32_t at(uint32_t n) const {                    // n <= 63
@@ -689,18 +693,41 @@ struct ZeroTable {
         return entry[n];
 #endif
     }
-    // positions on which a symbol carrying a new coefficient (kSymCoef) landed
-    PCR_HD uint64_t new_positions() const {
+    // taken: bit n set = a symbol carrying a new coefficient landed on entry n.  Returns those positions.
+    PCR_HD uint64_t positions_of(uint64_t taken) const {
 #if defined(__HIP_DEVICE_COMPILE__)
-        const uint32_t w = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((vindex & 63u) * 4), (int)vword);
-        return __ballot(vindex < 64u && (w & kSymCoef));
+        return __ballot(vindex < 64u && ((taken >> (vindex & 63u)) & 1));
 #else
         uint64_t m = 0;
-        for (uint32_t i = 0; i < 64; i++) if (index[i] < 64u && (word[index[i]] & kSymCoef)) m |= 1ull << i;
+        for (uint32_t i = 0; i < 64; i++) if (index[i] < 64u && ((taken >> index[i]) & 1)) m |= 1ull << i;
         return m;
 #endif
     }
 };
+
+// Hides where a value came from, so that the compiler keeps it in the register it is in instead of
+// re-deriving it from other values it would then have to keep alive through a hot loop.
+PCR_HD uint32_t opaque(uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("" : "+s"(v));
+#endif
+    return v;
+}
+// All LDS and scalar-memory results this wavefront is waiting for have arrived: stated once ahead of a
+// hot loop, the wait is not repeated inside it.
+PCR_HD void settle_lds() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0xC07F);                      // lgkmcnt(0), the other counters untouched
+#endif
+}
+// sets bit n (0..63) of a wave-uniform mask: one scalar instruction
+PCR_HD void set_bit(uint64_t* m, uint32_t n) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("s_bitset1_b64 %0, %1" : "+s"(*m) : "s"(n));
+#else
+    *m |= 1ull << n;
+#endif
+}
 
 // Phase 1 (serial, one wavefront per unit): walk the scan only as far as needed to know where
 // every block starts.  For each symbol that means: the code (length, run, size), the zero the run
@@ -735,33 +762,52 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
         const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
         uint64_t newm = 0;
         if (eobrun == 0) {                                   // symbols are read only outside an end-of-band run
-            if (band != 0) {                                 // (always: a scan has at least one position)
-                const uint32_t nzeros = (uint32_t)__builtin_popcountll(z);
-                zt.build(h, z, nzeros, ncorr, wr->lane);
-                uint32_t idx = 0;                            // next table index
-                uint32_t ob = wr->o;                         // window offset not counting the correction bits stepped over in this block
-                uint32_t info, e;
+            const uint32_t nzeros = (uint32_t)__builtin_popcountll(z);   // <= 63: a band never holds position 0
+            zt.build(h, z, nzeros, ncorr, wr->lane);
+            uint32_t at = ~0u;                               // table index the last symbol landed on (none yet)
+            uint32_t ob = wr->o;                             // window offset not counting the correction bits stepped over in this block
+            uint64_t taken = 0;                              // table entries a symbol landed on
+            uint32_t info, e, t;
+            for (;;) {
+                if (wr->exhausted()) { const uint32_t before = wr->o; wr->refill(); ob -= before - wr->o; }
+                settle_lds();
                 do {
-                    // One straight line for all three kinds of symbol.  A new +-1 after r zeros (kSymCoef) or
-                    // sixteen zeros (r = 15): r zeros are passed, then one more position.  End of band: as if the
-                    // run went past every zero -- the sentinel entry says "all corrections, nothing left".
-                    if (wr->exhausted()) { const uint32_t before = wr->o; wr->refill(); ob -= before - wr->o; }
-                    info = wr->peek();
-                    idx += info & 127;                       // the run, or 64 + run for an end of band
-                    idx = idx < nzeros ? idx : nzeros;       // past the last zero: the sentinel
-                    e = zt.at(idx);
-                    zt.land(idx, info);
-                    idx++;
+                    // One straight line for every symbol.  A new +-1 after r zeros: r zeros are passed, the next
+                    // one is taken.  End of band: as if the run went past every zero -- the sentinel entry says
+                    // "all corrections, nothing left".  Unresolved codes and sixteen-zero symbols behave like an
+                    // end of band here and are redone below.
+                    info = wr->lookup(wr->o);
+                    t = at + (info & 127);                   // run + 1, or 65 + run for an end of band
+                    at = t < nzeros ? t : nzeros;            // past the last zero: the sentinel
+                    e = zt.at(at);
+                    set_bit(&taken, at);
                     ob += (info >> 8) & 63;                  // code and sign
-                    wr->o = ob + ((e >> 8) & 127);           // ... and the corrections passed so far
-                } while ((e & kZtLast) == 0);
-                if (info & kSymEob) {                        // the block ended with an end-of-band (run) symbol
-                    bad |= (info & 0x3F00) ? 0u : 1u;        // length 0: no code at all
-                    eobrun = (1u << (info & 15)) + (info >> 16);
+                    wr->o = ob + ((e >> 8) & 127);           // ... the corrections passed so far, and 64 more after the block's last entry
+                } while (wr->o < 64);
+                if ((e & kZtLast) == 0) continue;            // the window ran out inside the block
+                wr->o -= 64;
+                if ((info & kSymSpecial) == 0) break;        // the block is complete
+                // By hand: the symbol again from where it started.
+                const uint32_t prev = opaque(t) - (info & 127);   // where the symbol before it had landed
+                if (info == kSymMiss) {                      // a code longer than 8 bits, or none
+                    const uint32_t passed = prev == ~0u ? 0u : (zt.at(prev & 63u) >> 8) & 63u;
+                    info = wr->resolve(ob + passed);         // (a miss has length 0: ob is still the symbol's)
+                    ob += (info >> 8) & 63;
                 }
-                bad |= (zt.landed(nzeros) >> 15) & 1;        // a new coefficient with no zero left to take (the sentinel)
-                newm = zt.new_positions();
+                const uint32_t zrl = info & kSymSpecial;     // sixteen zeros: lands on a zero and leaves it zero
+                t = prev + (zrl ? kZrlAdvance : (info & 127));
+                at = t < nzeros ? t : nzeros;
+                e = zt.at(at);
+                if (!zrl) set_bit(&taken, at);
+                wr->o = ob + ((e >> 8) & 63);
+                if (e & kZtLast) break;
             }
+            if (info & kSymEob) {                            // the block ended with an end-of-band (run) symbol
+                bad |= (info & 0x3F00) ? 0u : 1u;            // length 0: no code at all
+                eobrun = (1u << ((info & 127) - 65)) + (info >> 16);
+            }
+            bad |= (info >> 15) & (e >> 17) & 1;             // a new coefficient with no zero left to take (the sentinel)
+            newm = zt.positions_of(taken & ((1ull << nzeros) - 1));
             eobrun -= eobrun ? 1u : 0u;                      // the run counted this block
         } else {
             wr->consume(ncorr);

@@ -209,7 +209,9 @@ struct UnitSetup {
     uint32_t byte_off, nbytes;
     LaneScan ls;
     int16_t* plane[kMaxComp];     // planes of the scan's components
+    uint32_t plane_elems[kMaxComp];
     int16_t* base;                // the image's coefficient buffer (all planes)
+    uint32_t base_elems;
     bool ok;
 };
 
@@ -240,8 +242,10 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __rest
         const size_t po = c == 0 ? poff[0] : (c == 1 ? poff[1] : poff[2]);
         ls.poff[j] = (uint32_t)po;
         L->plane[j] = base + po;
+        L->plane_elems[j] = (uint32_t)((c == 0 ? poff[1] : (c == 1 ? poff[2] : poff[3])) - po);
     }
     L->base = base;
+    L->base_elems = (uint32_t)poff[kMaxComp];
     L->words = clean32 + (uni(clean_base(sd->data_off)) >> 2);
     L->byte_off = uni(b0); L->nbytes = uni(b1 > b0 ? b1 - b0 : 0);
     L->ok = true;
@@ -268,7 +272,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     DcWindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tabs[0], &tabs[1], &tabs[2], uni(ntab), threadIdx.x);
     CoefSink sink;
-    sink.init(L.base, L.ls.Al, threadIdx.x);
+    sink.init(L.base, L.base_elems, L.ls.Al);
     int rc = decode_dc_first(&wr, L.ls, 0, uni(tj1), uni(tj2), &sink);
     if (rc != kOk) R.status[un.img] = rc;
 }
@@ -288,7 +292,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x);
     CoefSink sink;
-    sink.init(L.plane[0], L.ls.Al, threadIdx.x);
+    sink.init(L.plane[0], L.plane_elems[0], L.ls.Al);
     int rc = decode_ac_first(&wr, L.ls, &sink);
     if (rc != kOk) R.status[un.img] = rc;
 }
