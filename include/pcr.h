@@ -7,7 +7,7 @@
  * Section 3, record figure).  This library opens such a byte prefix, rebuilds the index that
  * un-groups the scans, and decodes all images at a chosen scan group into uint8 pixels on the
  * GPU: each image's scans 1..k followed by an end-of-image marker are what a JPEG decoder is
- * given (Section 3, "Decoding").
+ * given (Section 5, "Decoding").
  *
  * Conventions
  *   - every function returns PCR_OK (0) or a negative PCR_E_* code; nothing throws or aborts;
@@ -51,7 +51,7 @@ enum {
 };
 
 /*
- * Open a record (Section 3, "Decoding": locate the scan-group offsets in the metadata).
+ * Open a record (Section 5, "Decoding": locate the scan-group offsets in the metadata).
  *   bytes, nbytes  host pointer to the record or to any prefix of it; groups that are not
  *                  wholly inside the prefix are unavailable, never partially used.
  *   device_id      HIP device that will hold the record and run the decode.
@@ -63,7 +63,7 @@ int pcr_open(const void* bytes, size_t nbytes, int device_id, pcr_record** out);
 
 /*
  * Open a record whose bytes are already in device memory (for loaders that stream record prefixes
- * to the GPU themselves; paper Section 3, "Loader": whole-record buffers that are re-used).
+ * to the GPU themselves; paper Section 5, "Loader": whole-record buffers that are re-used).
  *   d_bytes, nbytes  device pointer (16-byte aligned) to the record or a prefix of it.  The bytes are
  *                    BORROWED: they must stay valid and unchanged until pcr_close.
  *   hip_stream       stream the open-time kernels and copies run on; the call synchronises it.
@@ -73,6 +73,17 @@ int pcr_open(const void* bytes, size_t nbytes, int device_id, pcr_record** out);
  */
 int pcr_open_device(const void* d_bytes, size_t nbytes, void* hip_stream, pcr_record** out);
 
+/*
+ * Bind an existing handle to another record in device memory, re-using the handle's device buffers
+ * (they are re-allocated only when the new record needs more than the handle already holds), so that a
+ * loader that decodes record after record stops allocating after the first few (Section 5, "Loader":
+ * double buffering with re-used buffers).  Arguments and behaviour as pcr_open_device; every earlier call
+ * on the handle must have finished, or be ordered before this one on hip_stream.  Whatever the handle
+ * knew about its previous record is gone (layouts, resident planes, timing history is kept).  If the
+ * call fails the handle holds no record: only another pcr_rebind_device or pcr_close may follow.
+ */
+int pcr_rebind_device(pcr_record* rec, const void* d_bytes, size_t nbytes, void* hip_stream);
+
 /* Release a handle and all device memory it owns.  NULL is allowed. */
 void pcr_close(pcr_record* rec);
 
@@ -81,8 +92,8 @@ int pcr_num_scan_groups(const pcr_record* rec, int* G);            /* groups the
 int pcr_available_scan_groups(const pcr_record* rec, int* k_max);  /* groups inside the bytes given */
 
 /* Bytes that must be read from the start of the record for fidelity k (1..G): the absolute
- * offset one past scan group k (Section 3: "from the start of the PCR to the end of the
- * corresponding scan group"). */
+ * offset one past scan group k (Section 3: fidelity k is the byte prefix of the record that ends
+ * with scan group k). */
 int pcr_group_end_offset(const pcr_record* rec, int k, uint64_t* off);
 
 /* Width, height, channels (1 or 3) and the 32-bit label of image i.  Any out pointer may be NULL. */
@@ -95,14 +106,14 @@ int pcr_output_layout(const pcr_record* rec, uint64_t* offsets);
 
 /* ---- parity hooks: intermediate results, computed on the device, returned to the host ---- */
 
-/* The un-grouping index (Section 3, "Encoding": "an index must be created for ungrouping the
- * scans"): off[g*n+i] = absolute offset of region(i,g+1), len[g*n+i] its length, for the
+/* The un-grouping index (Section 5, "Encoding": grouping the scans needs an index that undoes
+ * it): off[g*n+i] = absolute offset of region(i,g+1), len[g*n+i] its length, for the
  * available groups g < k_max (entries of unavailable groups are left untouched).
  * Computed by the index kernel.  off, len: host, G*n entries. */
 int pcr_index(pcr_record* rec, uint64_t* off, uint32_t* len);
 
 /* The byte string of image i at fidelity k: regions 1..min(k, scans of i), followed by FF D9 if
- * and only if scans were left out (Section 3, "Decoding").  dst: host, cap bytes; *len receives
+ * and only if scans were left out (Section 5, "Decoding").  dst: host, cap bytes; *len receives
  * the length (also when dst is NULL, to query).  Gathered by a device kernel. */
 int pcr_reassemble(pcr_record* rec, int i, int k, uint8_t* dst, size_t cap, size_t* len);
 
@@ -130,7 +141,7 @@ int pcr_decode_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size
                      void* hip_stream, int32_t* d_status);
 
 /* Fidelity upgrade (Section 3 of the paper: a lower-fidelity read is a prefix of a higher-fidelity one, so
- * "switching between data fidelities is lightweight"): raise the planes the last pcr_decode_batch /
+ * changing fidelity costs little): raise the planes the last pcr_decode_batch /
  * pcr_upgrade_batch call on this handle left on the device from its scan group to `scan_group` (>= it) by
  * unstuffing and entropy-decoding only the scans of the new groups, then produce the pixels.  The output is
  * bit-identical to pcr_decode_batch(rec, scan_group, ...); arguments, layout, stream order and d_status as
@@ -142,6 +153,41 @@ int pcr_decode_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size
 int pcr_upgrade_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
                       void* hip_stream, int32_t* d_status);
 int pcr_resident_scan_group(const pcr_record* rec, int* scan_group);
+
+/* ---- loader: host bytes -> device -> pixels, double-buffered (Section 5, "Loader") ----
+ *
+ * pcr_prefix_length: how much of a record must be read for fidelity k, from the record's first bytes alone
+ *   (host pointer; 24 + 8*G bytes always suffice).  PCR_OK and *need = that length; PCR_E_TRUNCATED and
+ *   *need = how many first bytes are needed to tell.
+ *
+ * A loader owns `slots` sets of {pinned host staging buffer, device buffer, stream, record handle}, each of
+ * slot_bytes capacity, allocated once.  The caller reads a record prefix into a slot's staging buffer
+ * (pcr_loader_staging), then
+ *   pcr_loader_upload  copies nbytes of it to the device on the slot's stream and binds the slot's handle to
+ *                      them (pcr_open_device the first time, pcr_rebind_device afterwards).  It first waits
+ *                      for the slot's earlier work, and returns when the record's metadata is known: *rec
+ *                      (optional) is the slot's handle for layout queries, valid until the slot's next upload.
+ *   pcr_loader_decode  = pcr_decode_batch on the slot's handle and stream (asynchronous).
+ *   pcr_loader_wait    blocks until the slot's stream is idle; the staging buffer may be refilled after
+ *                      pcr_loader_upload has returned.
+ * While one slot's decode runs, another slot's upload and parse proceed on their own stream.  Streams have
+ * the default priority; pcr_loader_stream hands a slot's hipStream_t out so that consumers can order
+ * themselves after the decode.  One thread per loader.
+ *
+ * pcr_loader_set_rate: token bucket in front of the uploads, to imitate storage of limited bandwidth
+ *   (Section 6.6 limits each reader this way): bytes_per_second tokens arrive per second, at most
+ *   burst_bytes are saved up, an upload of nbytes blocks until it can pay nbytes.  0 = unlimited (default).
+ */
+typedef struct pcr_loader pcr_loader;
+int pcr_prefix_length(const void* first_bytes, size_t nbytes, int k, uint64_t* need);
+int pcr_loader_create(int device_id, int slots, size_t slot_bytes, pcr_loader** out);
+void pcr_loader_destroy(pcr_loader* ld);                      /* NULL is allowed; closes the slots' handles */
+int pcr_loader_staging(pcr_loader* ld, int slot, void** host, size_t* capacity);
+int pcr_loader_stream(pcr_loader* ld, int slot, void** hip_stream);
+int pcr_loader_set_rate(pcr_loader* ld, double bytes_per_second, double burst_bytes);
+int pcr_loader_upload(pcr_loader* ld, int slot, size_t nbytes, pcr_record** rec);
+int pcr_loader_decode(pcr_loader* ld, int slot, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity, int32_t* d_status);
+int pcr_loader_wait(pcr_loader* ld, int slot);
 
 /* Stage timing with HIP events recorded on the call's own stream (off by default; switching it on
  * starts a new history).  A stage is one kernel or a short run of kernels:

@@ -8,12 +8,12 @@
  * What it follows:
  *   - the record layout, the prefix rule ("read from the start of the record to the end of
  *     scan group k") and the re-serialisation of each image's scans followed by an
- *     end-of-image marker: paper Section 3 (record figure, "Encoding", "Decoding");
+ *     end-of-image marker: paper Section 3 (record figure) and Section 5 ("Encoding", "Decoding");
  *   - what the bytes of one image mean: the JPEG standard (ITU-T T.81) -- marker syntax
  *     (Annex B), Huffman table construction (Annex C), sequential Huffman decoding (F.2.2),
  *     progressive decoding with spectral selection and successive approximation (Annex G),
  *     the inverse DCT (A.3.3) -- and the JFIF colour convention.  The paper delegates this
- *     step to a stock decoder (Section 3, "Decoding"; Section 4.2).
+ *     step to a stock decoder (Section 5, "Decoding"; Section 4.2).
  * Where the standard leaves a choice (what to show for coefficients not yet received,
  * chroma up-sampling, rounding) the choices are: missing coefficients are zero and no
  * smoothing is applied; chroma samples are replicated; samples stay in floating point

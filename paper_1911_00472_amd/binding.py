@@ -20,6 +20,7 @@ _vp = ctypes.c_void_p
 SYMBOLS = {
     "pcr_open": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(_vp)]),
     "pcr_open_device": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.POINTER(_vp)]),
+    "pcr_rebind_device": (ctypes.c_int, [_vp, _vp, ctypes.c_size_t, _vp]),
     "pcr_close": (None, [_vp]),
     "pcr_num_images": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
     "pcr_num_scan_groups": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
@@ -38,6 +39,15 @@ SYMBOLS = {
     "pcr_last_stage_ms": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_float)]),
     "pcr_probe_scalar_issue_rate": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]),
     "pcr_stage_ms_history": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]),
+    "pcr_prefix_length": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_loader_create": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]),
+    "pcr_loader_destroy": (None, [_vp]),
+    "pcr_loader_staging": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_size_t)]),
+    "pcr_loader_stream": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(_vp)]),
+    "pcr_loader_set_rate": (ctypes.c_int, [_vp, ctypes.c_double, ctypes.c_double]),
+    "pcr_loader_upload": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]),
+    "pcr_loader_decode": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
+    "pcr_loader_wait": (ctypes.c_int, [_vp, ctypes.c_int]),
     "pcr_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
 
@@ -75,10 +85,13 @@ def _check(rc, what):
 class Record:
     """One opened PCR record (pcr_open ... pcr_close)."""
 
-    def __init__(self, data, device=0, stream=None):
+    def __init__(self, data, device=0, stream=None, _borrowed_handle=None):
         self._h = _vp()
         self._keep = None
-        if hasattr(data, "data_ptr"):                       # a CUDA uint8 tensor: bytes already on the device (borrowed)
+        self._owned = _borrowed_handle is None
+        if _borrowed_handle is not None:                    # a loader slot's handle: the loader closes it
+            self._h = _vp(_borrowed_handle)
+        elif hasattr(data, "data_ptr"):                       # a CUDA uint8 tensor: bytes already on the device (borrowed)
             import torch
             assert data.is_cuda and data.dtype == torch.uint8 and data.is_contiguous()
             device = data.device.index
@@ -89,14 +102,28 @@ class Record:
             buf = np.frombuffer(data, np.uint8) if not isinstance(data, np.ndarray) else data
             _check(lib().pcr_open(buf.ctypes.data_as(_vp), buf.size, device, ctypes.byref(self._h)), "pcr_open")
         self.device = device
+        self._refresh()
+
+    def _refresh(self):
         v = ctypes.c_int()
         _check(lib().pcr_num_images(self._h, ctypes.byref(v)), "pcr_num_images"); self.n = v.value
         _check(lib().pcr_num_scan_groups(self._h, ctypes.byref(v)), "pcr_num_scan_groups"); self.G = v.value
         _check(lib().pcr_available_scan_groups(self._h, ctypes.byref(v)), "pcr_available_scan_groups"); self.k_avail = v.value
 
+    def rebind_device(self, tensor, stream=None):
+        """Bind this handle to another record (a CUDA uint8 tensor, borrowed), re-using its device buffers."""
+        import torch
+        assert tensor.is_cuda and tensor.dtype == torch.uint8 and tensor.is_contiguous() and tensor.device.index == self.device
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        self.n = self.G = self.k_avail = 0
+        _check(lib().pcr_rebind_device(self._h, tensor.data_ptr(), tensor.numel(), s), "pcr_rebind_device")
+        self._keep = tensor
+        self._refresh()
+
     def close(self):
         if self._h:
-            lib().pcr_close(self._h)
+            if self._owned:
+                lib().pcr_close(self._h)
             self._h = _vp()
             self._keep = None
 
@@ -149,9 +176,8 @@ class Record:
     def decode_coefficients(self, k, out=None, stream=None):
         """int16 CUDA tensor of coef_layout()[n] elements (asynchronous on the stream)."""
         import torch
-        total = int(self.coef_layout()[-1])
         if out is None:
-            out = torch.empty(total, dtype=torch.int16, device="cuda:%d" % self.device)
+            out = torch.empty(int(self.coef_layout()[-1]), dtype=torch.int16, device="cuda:%d" % self.device)
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_decode_coefficients(self._h, k, out.data_ptr(), s), "pcr_decode_coefficients")
         return out
@@ -159,9 +185,8 @@ class Record:
     def decode_batch(self, k, out=None, status=None, stream=None):
         """uint8 CUDA tensor of output_layout()[n] bytes, ragged NHWC (asynchronous on the stream)."""
         import torch
-        total = int(self.output_layout()[-1])
         if out is None:
-            out = torch.empty(total, dtype=torch.uint8, device="cuda:%d" % self.device)
+            out = torch.empty(int(self.output_layout()[-1]), dtype=torch.uint8, device="cuda:%d" % self.device)
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_decode_batch(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
                "pcr_decode_batch")
@@ -171,9 +196,8 @@ class Record:
         """As decode_batch, but decodes only the scan groups above resident_scan_group() on top of the planes the
         previous decode_batch / upgrade_batch left on the device."""
         import torch
-        total = int(self.output_layout()[-1])
         if out is None:
-            out = torch.empty(total, dtype=torch.uint8, device="cuda:%d" % self.device)
+            out = torch.empty(int(self.output_layout()[-1]), dtype=torch.uint8, device="cuda:%d" % self.device)
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_upgrade_batch(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
                "pcr_upgrade_batch")
@@ -206,6 +230,73 @@ def probe_scalar_issue_rate(waves_per_cu, device=0):
     v = ctypes.c_double(0)
     _check(lib().pcr_probe_scalar_issue_rate(device, waves_per_cu, ctypes.byref(v)), "pcr_probe_scalar_issue_rate")
     return float(v.value)
+
+
+def prefix_length(first_bytes, k):
+    """Bytes of a record to read for scan group k, from its first bytes (24 + 8 G always suffice).  Returns
+    (True, length), or (False, number of first bytes needed to tell)."""
+    buf = np.frombuffer(first_bytes, np.uint8) if not isinstance(first_bytes, np.ndarray) else first_bytes
+    need = ctypes.c_uint64(0)
+    rc = lib().pcr_prefix_length(buf.ctypes.data_as(_vp), buf.size, k, ctypes.byref(need))
+    if rc == E_TRUNCATED:
+        return False, int(need.value)
+    _check(rc, "pcr_prefix_length")
+    return True, int(need.value)
+
+
+class Loader:
+    """pcr_loader_*: `slots` re-used sets of pinned staging buffer, device buffer, stream and record handle."""
+
+    def __init__(self, slots, slot_bytes, device=0):
+        self._h = _vp()
+        self.device, self.slots, self.slot_bytes = device, slots, slot_bytes
+        _check(lib().pcr_loader_create(device, slots, slot_bytes, ctypes.byref(self._h)), "pcr_loader_create")
+
+    def close(self):
+        if self._h:
+            lib().pcr_loader_destroy(self._h)
+            self._h = _vp()
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def staging(self, slot):
+        """The slot's pinned host buffer as a numpy uint8 array (a view, valid until close)."""
+        p, cap = _vp(), ctypes.c_size_t(0)
+        _check(lib().pcr_loader_staging(self._h, slot, ctypes.byref(p), ctypes.byref(cap)), "pcr_loader_staging")
+        return np.ctypeslib.as_array(ctypes.cast(p, _u8p), shape=(cap.value,))
+
+    def stream(self, slot):
+        p = _vp()
+        _check(lib().pcr_loader_stream(self._h, slot, ctypes.byref(p)), "pcr_loader_stream")
+        return p.value or 0
+
+    def set_rate(self, bytes_per_second, burst_bytes=0.0):
+        _check(lib().pcr_loader_set_rate(self._h, float(bytes_per_second), float(burst_bytes)), "pcr_loader_set_rate")
+
+    def upload(self, slot, nbytes):
+        """Upload the first nbytes of the slot's staging buffer and bind the slot's handle; returns it as a Record
+        (owned by the loader; valid until the slot's next upload)."""
+        h = _vp()
+        _check(lib().pcr_loader_upload(self._h, slot, nbytes, ctypes.byref(h)), "pcr_loader_upload")
+        return Record(None, device=self.device, _borrowed_handle=h.value)
+
+    def decode(self, slot, k, out, status=None):
+        _check(lib().pcr_loader_decode(self._h, slot, k, out.data_ptr(), out.numel(), status.data_ptr() if status is not None else None),
+               "pcr_loader_decode")
+        return out
+
+    def wait(self, slot):
+        _check(lib().pcr_loader_wait(self._h, slot), "pcr_loader_wait")
 
 
 def pcr_open(data, device=0):

@@ -557,7 +557,7 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
             if (kb >= 64) {                                  // band complete, or end of band
                 uint32_t adv = 1;                            // blocks to move on by
                 if (info & kSymEob) {                        // run of 2^r + extra blocks; no code at all has length 0
-                    bad |= (info & 0x3F00) ? 0u : 1u;
+                    bad |= ((info & 0x3F00) - 1u) >> 31;
                     adv = (1u << ((info & 127) - 65)) + (info >> 16);
                 } else {
                     bad |= (kb > 64) ? ((info >> 15) & 1) : 0u;   // a coefficient beyond the band
@@ -597,13 +597,13 @@ PCR_HD uint64_t take_correction_bits(BitReader* br, int n) {    // n <= 63; firs
 }
 
 // What an AC refinement scan leaves per block: one record of kRefWords 64-bit words (zig-zag bit order),
-//   [kRefNz]    positions that become non-zero in this scan (later scans need them as history)
-//   [kRefSign]  their signs, 1 = positive                          } written by phase 2
+//   [kRefNz]    positions that become non-zero in this scan (later scans need them as history)   } written by
+//   [kRefStart] bit offset of the block inside its unit | end-of-band run pending at its start << 32  } phase 1,
+//   [kRefHist]  positions of the band already non-zero when the scan starts                      } adjacent
+//   [kRefSign]  signs of the kRefNz positions, 1 = positive         } written by phase 2
 //   [kRefCbits] the correction bits in reading order, bit 0 first   }
-//   [kRefStart] bit offset of the block inside its unit | end-of-band run pending at its start << 32
-//   [kRefHist]  positions of the band already non-zero when the scan starts
 // Records of consecutive blocks are contiguous, so everything a consumer needs for a block is one line.
-constexpr int kRefNz = 0, kRefSign = 1, kRefCbits = 2, kRefStart = 3, kRefHist = 4, kRefWords = 5;
+constexpr int kRefNz = 0, kRefStart = 1, kRefHist = 2, kRefSign = 3, kRefCbits = 4, kRefWords = 5;
 
 // History of a refinement scan: the positions of its band that are non-zero when it starts.  What the
 // AC first scans made non-zero is read back from the coefficient plane (one coefficient per lane, a ballot
@@ -611,19 +611,24 @@ constexpr int kRefNz = 0, kRefSign = 1, kRefCbits = 2, kRefStart = 3, kRefHist =
 struct HistPlanes { const int16_t* coef; const uint64_t* p[kMaxHist]; int n; };
 
 struct HistWords {                                            // one block's history, combined only when used
-    uint64_t a, b, c;
+    uint64_t a;                                               // what earlier refinement scans added
 #if defined(__HIP_DEVICE_COMPILE__)
     int16_t mine;                                             // this lane's coefficient of the block
 #else
     uint64_t first;
 #endif
 };
+PCR_HD uint64_t hist_word(const uint64_t* recs, uint32_t byte_off) {        // (32-bit offsets: a scan's records stay far below 4 GiB)
+    return *reinterpret_cast<const uint64_t*>(reinterpret_cast<const char*>(recs) + byte_off);
+}
 PCR_HD HistWords hist_fetch(const HistPlanes& hp, uint32_t blk, uint32_t lane) {
-    HistWords w; w.a = 0; w.b = 0; w.c = 0;
-    if (hp.n > 0) {                                           // entries beyond n repeat entry 0
-        const uint32_t e = blk * kRefWords + kRefNz;
-        w.a = hp.p[0][e]; w.b = hp.p[1][e]; w.c = hp.p[2][e];
-        if (__builtin_expect(hp.n > 3, 0)) w.a |= hp.p[3][e] | hp.p[4][e] | hp.p[5][e];
+    HistWords w; w.a = 0;
+    if (hp.n > 0) {
+        const uint32_t off = (blk * kRefWords + kRefNz) * 8;
+        w.a = hist_word(hp.p[0], off);
+        if (__builtin_expect(hp.n > 1, 0)) {                 // scripts with more than two refinement passes over a band
+            for (int q = 1; q < kMaxHist; q++) if (q < hp.n) w.a |= hist_word(hp.p[q], off);
+        }
     }
 #if defined(__HIP_DEVICE_COMPILE__)
     w.mine = hp.coef[(size_t)blk * 64 + lane];
@@ -635,53 +640,63 @@ PCR_HD HistWords hist_fetch(const HistPlanes& hp, uint32_t blk, uint32_t lane) {
 }
 PCR_HD uint64_t hist_combine(const HistWords& w) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    return w.a | w.b | w.c | __ballot(w.mine != 0);
+    return w.a | __ballot(w.mine != 0);
 #else
-    return w.a | w.b | w.c | w.first;
+    return w.a | w.first;
 #endif
 }
 
-// Zero table of one block: entry n describes the n-th position of the band that is still zero
-// when the scan reaches the block (n = 0, 1, ...; zig-zag order):
-//     position (bits 0..5) | non-zero-history positions below it (bits 8..13) | kZtLast | kZtSentinel
-// kZtLast marks the entry after which nothing is left in the block: the last zero if no non-zero
-// history position follows it, and every sentinel.  Entries from number-of-zeros on are sentinels:
-// "no such zero", with the count field = all non-zero-history positions of the band.
+// Zero table of one block: entry n (n = 0, 1, ...) belongs to the n-th position of the band that is
+// still zero when the scan reaches the block (zig-zag order) and holds the number of non-zero-history
+// positions below it -- the correction bits a decoder has stepped over when it lands there -- plus
+// kZtLast if nothing is left in the block after it (the band's last position, if it is a zero).
+// Entries from number-of-zeros on are sentinels, "no such zero": all non-zero-history positions of the
+// band, plus kZtLast.
 // With the table the serial decoder does no bit arithmetic per symbol: a run of r zeros followed by
-// a new coefficient is "index += r + 1, read the entry", and the number of correction bits to step
-// over is the difference of two count fields.  kZtLast sits directly above the count field, so that
-// the 7-bit field reads "count + 64" on a last entry: added to the window offset it pushes the offset
-// past the window, and the one test "offset < 64" ends the symbol loop for both reasons.
+// a new coefficient is "index += r + 1, read the entry", and the entry is what to add to the window
+// offset.  kZtLast = 64 pushes that offset past the window, so the one test "offset < 64" ends the
+// symbol loop for both reasons, a used-up window and a finished block.
 // The 64 lanes build the table in a handful of vector instructions (a prefix count of the two masks
 // and one permute); lane i also keeps the index of ITS position so that the set of table entries
 // that were taken can be turned back into a mask of positions.
-constexpr uint32_t kZtLast = 1u << 14, kZtSentinel = 1u << 17;
+constexpr uint32_t kZtLast = 64;
+
+// v = lane's bit of the wave-uniform mask m ? a : b, without materialising the bit: the mask is used as
+// the select operand of a conditional move
+PCR_HD uint32_t select_by_mask(uint64_t m, uint32_t a, uint32_t b, uint32_t lane) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint32_t r;
+    (void)lane;
+    asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(b), "v"(a), "s"(m));
+    return r;
+#else
+    return ((m >> lane) & 1) ? a : b;
+#endif
+}
 
 struct ZeroTable {
 #if defined(__HIP_DEVICE_COMPILE__)
-    uint32_t ventry, vindex;                                  // lane n: entry n; lane i: table index of position i (64 if not a zero)
+    uint32_t ventry, vindex;                                  // lane n: entry n; lane i: table index of position i (63 if not a zero)
 #else
     uint32_t entry[64], index[64];
 #endif
-    PCR_HD void build(uint64_t h, uint64_t z, uint32_t nzeros, uint32_t ncorr, uint32_t lane) {
+    // top64: kZtLast in the lane of the band's last position, 0 elsewhere (the same for every block of a scan)
+    PCR_HD void build(uint64_t h, uint64_t z, uint32_t nzeros, uint32_t ncorr, uint32_t lane, uint32_t top64) {
 #if defined(__HIP_DEVICE_COMPILE__)
         const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(z >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)z, 0));
         const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(h >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)h, 0));
-        const bool iz = (z >> lane) & 1;
-        const uint32_t last = (rank + 1 == nzeros && below == ncorr) ? kZtLast : 0u;
-        const uint32_t data = iz ? (lane | (below << 8) | last) : (lane | (ncorr << 8) | kZtLast | kZtSentinel);
-        const uint32_t dest = iz ? rank : nzeros + (lane - rank);       // a permutation of the 64 lanes
+        const uint32_t data = select_by_mask(z, below + top64, ncorr + kZtLast, lane);
+        const uint32_t dest = select_by_mask(z, rank, nzeros + (lane - rank), lane);       // a permutation of the 64 lanes
         ventry = (uint32_t)__builtin_amdgcn_ds_permute((int)(dest * 4), (int)data);
-        vindex = iz ? rank : 64u;
+        vindex = select_by_mask(z, rank, 63u, lane);
 #else
-        (void)lane;
-        uint32_t rank = 0, below = 0;
+        (void)lane; (void)top64;
+        uint32_t rank = 0, below = 0, top = 0;
+        for (uint32_t i = 0; i < 64; i++) if ((z | h) >> i & 1) top = i;
         for (uint32_t i = 0; i < 64; i++) {
             const bool iz = (z >> i) & 1;
-            const uint32_t last = (rank + 1 == nzeros && below == ncorr) ? kZtLast : 0u;
-            const uint32_t data = iz ? (i | (below << 8) | last) : (i | (ncorr << 8) | kZtLast | kZtSentinel);
-            entry[iz ? rank : nzeros + (i - rank)] = data;
-            index[i] = iz ? rank : 64u;
+            entry[iz ? rank : nzeros + (i - rank)] = iz ? below + (i == top ? kZtLast : 0u) : ncorr + kZtLast;
+            index[i] = iz ? rank : 63u;
             rank += iz; below += (h >> i) & 1;
         }
 #endif
@@ -693,13 +708,14 @@ struct ZeroTable {
         return entry[n];
 #endif
     }
-    // taken: bit n set = a symbol carrying a new coefficient landed on entry n.  Returns those positions.
+    // taken: bit n set = a symbol carrying a new coefficient landed on entry n (n < number of zeros <= 63, so
+    // bit 63 is clear: positions that are no zeros point there).  Returns those positions.
     PCR_HD uint64_t positions_of(uint64_t taken) const {
 #if defined(__HIP_DEVICE_COMPILE__)
-        return __ballot(vindex < 64u && ((taken >> (vindex & 63u)) & 1));
+        return __ballot(((taken >> vindex) & 1) != 0);
 #else
         uint64_t m = 0;
-        for (uint32_t i = 0; i < 64; i++) if (index[i] < 64u && ((taken >> index[i]) & 1)) m |= 1ull << i;
+        for (uint32_t i = 0; i < 64; i++) if ((taken >> index[i]) & 1) m |= 1ull << i;
         return m;
 #endif
     }
@@ -740,9 +756,12 @@ PCR_HD void set_bit(uint64_t* m, uint32_t n) {
 PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes& hp, uint64_t* recs) {
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     const uint64_t band = band_mask(ls.Ss, ls.Se);
+    const uint32_t top64 = wr->lane == (uint32_t)ls.Se ? kZtLast : 0u;
     uint32_t left = ls.mcu1 - ls.mcu0;                       // blocks still to do
-    uint32_t row = ls.mcu0 / mcu_w, col = ls.mcu0 % mcu_w;
-    uint32_t blk = row * bw + col;
+    uint32_t col = ls.mcu0 % mcu_w;
+    uint32_t blk = (ls.mcu0 / mcu_w) * bw + col;
+    const uint32_t row_skip = bw - mcu_w;                    // blocks of the padded grid between two rows of the scan
+    const uint32_t last_blk = ((ls.mcu1 - 1) / mcu_w) * bw + (ls.mcu1 - 1) % mcu_w;
     uint32_t eobrun = 0;                                     // blocks still covered by an end-of-band run
     uint32_t bad = 0;
     HistWords hnext = hist_fetch(hp, blk, wr->lane);
@@ -750,20 +769,18 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
     while (left != 0) {
         const uint64_t h = hist_combine(hnext) & band;        // already non-zero
         const uint64_t z = h ^ band;                         // still zero
-        const uint32_t here = blk;
+        uint64_t* rec = recs + (size_t)blk * kRefWords;
         // the block after this one, and its history (the last block fetches its own again)
-        if (++col == mcu_w) { col = 0; row++; }
+        blk++;
+        if (++col == mcu_w) { col = 0; blk += row_skip; }
         left--;
-        blk = left ? row * bw + col : here;
-        hnext = hist_fetch(hp, blk, wr->lane);
-        uint64_t* rec = recs + (size_t)here * kRefWords;
-        rec[kRefStart] = ((uint64_t)eobrun << 32) | wr->position();
-        rec[kRefHist] = h;                                   // phase 2 and the refinement replay work on the same history
+        hnext = hist_fetch(hp, blk < last_blk ? blk : last_blk, wr->lane);
+        const uint64_t start = ((uint64_t)eobrun << 32) | wr->position();
         const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
         uint64_t newm = 0;
         if (eobrun == 0) {                                   // symbols are read only outside an end-of-band run
             const uint32_t nzeros = (uint32_t)__builtin_popcountll(z);   // <= 63: a band never holds position 0
-            zt.build(h, z, nzeros, ncorr, wr->lane);
+            zt.build(h, z, nzeros, ncorr, wr->lane, top64);
             uint32_t at = ~0u;                               // table index the last symbol landed on (none yet)
             uint32_t ob = wr->o;                             // window offset not counting the correction bits stepped over in this block
             uint64_t taken = 0;                              // table entries a symbol landed on
@@ -782,15 +799,15 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
                     e = zt.at(at);
                     set_bit(&taken, at);
                     ob += (info >> 8) & 63;                  // code and sign
-                    wr->o = ob + ((e >> 8) & 127);           // ... the corrections passed so far, and 64 more after the block's last entry
+                    wr->o = ob + e;                          // ... the corrections passed so far, and 64 more after the block's last entry
                 } while (wr->o < 64);
-                if ((e & kZtLast) == 0) continue;            // the window ran out inside the block
-                wr->o -= 64;
+                if (e < kZtLast) continue;                   // the window ran out inside the block
+                wr->o -= kZtLast;
                 if ((info & kSymSpecial) == 0) break;        // the block is complete
                 // By hand: the symbol again from where it started.
                 const uint32_t prev = opaque(t) - (info & 127);   // where the symbol before it had landed
                 if (info == kSymMiss) {                      // a code longer than 8 bits, or none
-                    const uint32_t passed = prev == ~0u ? 0u : (zt.at(prev & 63u) >> 8) & 63u;
+                    const uint32_t passed = prev == ~0u ? 0u : zt.at(prev & 63u) & 63u;
                     info = wr->resolve(ob + passed);         // (a miss has length 0: ob is still the symbol's)
                     ob += (info >> 8) & 63;
                 }
@@ -799,21 +816,21 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
                 at = t < nzeros ? t : nzeros;
                 e = zt.at(at);
                 if (!zrl) set_bit(&taken, at);
-                wr->o = ob + ((e >> 8) & 63);
-                if (e & kZtLast) break;
+                wr->o = ob + (e & 63);
+                if (e >= kZtLast) break;
             }
             if (info & kSymEob) {                            // the block ended with an end-of-band (run) symbol
-                bad |= (info & 0x3F00) ? 0u : 1u;            // length 0: no code at all
+                bad |= ((info & 0x3F00) - 1u) >> 31;            // length 0: no code at all
                 eobrun = (1u << ((info & 127) - 65)) + (info >> 16);
             }
-            bad |= (info >> 15) & (e >> 17) & 1;             // a new coefficient with no zero left to take (the sentinel)
+            bad |= (info >> 15) & ((nzeros - 1 - at) >> 31);  // a new coefficient with no zero left to take (it landed on the sentinel)
             newm = zt.positions_of(taken & ((1ull << nzeros) - 1));
             eobrun -= eobrun ? 1u : 0u;                      // the run counted this block
         } else {
             wr->consume(ncorr);
             eobrun--;
         }
-        rec[kRefNz] = newm;
+        rec[kRefNz] = newm; rec[kRefStart] = start; rec[kRefHist] = h;   // (phase 2 and the refinement replay work on the same history)
         bad |= wr->overrun_bit();
         left = bad ? 0 : left;                               // stop at the first damaged block
     }

@@ -1,11 +1,11 @@
 // Record header and JPEG marker parsing, compiled for host and device.
 //
 // Record layout (paper Section 3, record figure: metadata first, then the scan groups in
-// order of fidelity; "raw struct" serialisation, Section 3 "Loader"), little endian:
+// order of fidelity; raw struct serialisation, Section 5 "Loader"), little endian:
 //   "PCR1" | u32 version | u32 n | u32 G | u64 header_bytes | u64 group_end[G] | i32 label[n]
 //   | u32 n_scans[n] | u32 len[G][n] | padding | group 1 | group 2 | ...
 // Group g holds the g-th scan region of every image back to back.  A region is the slice of
-// the image's progressive JPEG file between the ends of two consecutive scans (Section 3,
+// the image's progressive JPEG file between the ends of two consecutive scans (Section 5,
 // "Encoding"): region 1 starts with SOI and carries the frame header and tables, every
 // later region carries the tables and the SOS header of its one scan followed by the
 // entropy-coded data.

@@ -5,9 +5,11 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstring>
 #include <map>
 #include <new>
+#include <thread>
 #include <vector>
 
 #include "../../include/pcr.h"
@@ -32,13 +34,48 @@ struct Plan {                               // launch geometry for one scan grou
     bool had_ac = false;                     // ... some scan <= k0 (the fidelity an upgrade starts from)
 };
 
-template <class T> int dev_alloc(T** p, size_t count) {
-    *p = nullptr;
-    if (count == 0) count = 1;
-    return hipMalloc((void**)p, count * sizeof(T)) == hipSuccess ? PCR_OK : PCR_E_NOMEM;
+// Device memory of a handle comes out of two arenas (one sized by the image and scan counts, one by the
+// images themselves): a block that is handed out front to back and re-used as a whole when the handle is
+// bound to another record.  An arena grows only when a record needs more than it holds, so that a loader
+// that binds record after record of similar size to one handle stops allocating after the first few.
+// What does not fit (work lists of a scan group first asked for when the arena is full) is allocated on
+// its own and released at the next reset.
+struct Arena {
+    uint8_t* base = nullptr; size_t cap = 0, used = 0;
+    std::vector<void*> extra;
+};
+constexpr size_t kArenaAlign = 256;
+size_t arena_round(size_t bytes) { return (bytes + kArenaAlign - 1) / kArenaAlign * kArenaAlign; }
+void arena_release_extra(Arena* a) { for (void* p : a->extra) (void)hipFree(p); a->extra.clear(); }
+void arena_free(Arena* a) { arena_release_extra(a); if (a->base) (void)hipFree(a->base); a->base = nullptr; a->cap = a->used = 0; }
+// Empties the arena and makes sure it holds at least `bytes`.  Nothing handed out earlier may still be in use.
+int arena_reset(Arena* a, size_t bytes) {
+    arena_release_extra(a);
+    a->used = 0;
+    if (a->cap >= bytes) return PCR_OK;
+    if (a->base) (void)hipFree(a->base);
+    a->base = nullptr; a->cap = 0;
+    const size_t want = bytes + bytes / 8;                    // some room for the next, slightly larger record
+    if (hipMalloc((void**)&a->base, want) != hipSuccess) {
+        (void)hipGetLastError();
+        if (hipMalloc((void**)&a->base, bytes) != hipSuccess) { (void)hipGetLastError(); return PCR_E_NOMEM; }
+        a->cap = bytes;
+    } else a->cap = want;
+    return PCR_OK;
 }
-template <class T> int dev_upload(T** p, const std::vector<T>& v) {
-    int rc = dev_alloc(p, v.size());
+template <class T> int arena_alloc(Arena* a, T** p, size_t count) {
+    *p = nullptr;
+    const size_t bytes = arena_round((count ? count : 1) * sizeof(T));
+    if (a->used + bytes <= a->cap) { *p = reinterpret_cast<T*>(a->base + a->used); a->used += bytes; return PCR_OK; }
+    void* q = nullptr;
+    if (hipMalloc(&q, bytes) != hipSuccess) { (void)hipGetLastError(); return PCR_E_NOMEM; }
+    a->extra.push_back(q);
+    *p = reinterpret_cast<T*>(q);
+    return PCR_OK;
+}
+// (a synchronous copy: the data is on the device when the call returns, whatever stream uses it next)
+template <class T> int arena_upload(Arena* a, T** p, const std::vector<T>& v) {
+    int rc = arena_alloc(a, p, v.size());
     if (rc) return rc;
     if (!v.empty() && hipMemcpy(*p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return PCR_E_DEVICE;
     return PCR_OK;
@@ -65,6 +102,7 @@ struct pcr_record {
     std::vector<uint32_t> slot_base, slot_cnt;
     uint64_t n_masks = 0; uint32_t n_slots = 0; uint32_t max_level = 0;
     DevRecord d{};
+    Arena small, big;                       // descriptor tables (sized by n and G) / everything sized by the images, and the work lists
     uint8_t* d_rec = nullptr;
     PixelTile* d_tiles = nullptr; uint32_t n_tiles = 0;
     uint8_t* d_gather = nullptr; size_t gather_cap = 0;
@@ -142,37 +180,29 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
         std::vector<Unit> units(l.size());
         for (size_t e = 0; e < l.size(); e++) units[e] = l[e].u;
         LevelList ll; ll.n = (uint32_t)units.size(); ll.kind = (int)(li % kNumKinds);
-        int rc = dev_upload(&ll.d_units, units); if (rc) return rc;
+        int rc = arena_upload(&r->big, &ll.d_units, units); if (rc) return rc;
         if (ll.kind == kAcRefine) {
             const auto& rl = rlists[li / kNumKinds];
             ll.n_refine = (uint32_t)rl.size(); ll.refine_grid_x = (rmax[li / kNumKinds] + 255) / 256;
-            rc = dev_upload(&ll.d_refine, rl); if (rc) return rc;
+            rc = arena_upload(&r->big, &ll.d_refine, rl); if (rc) return rc;
         }
         plan.levels.push_back(ll);
     }
     plan.n_apply = (uint32_t)apply.size();
     plan.apply_grid_x = (max_blk * 64 + kApplyChunk - 1) / kApplyChunk;
     if (plan.n_apply) {
-        int rc = dev_upload(&plan.d_apply, apply); if (rc) return rc;
+        int rc = arena_upload(&r->big, &plan.d_apply, apply); if (rc) return rc;
         std::vector<int32_t> list_idx((size_t)n * kMaxComp, -1);
         for (size_t e = 0; e < apply.size(); e++) list_idx[(size_t)apply[e].img * kMaxComp + apply[e].comp] = (int32_t)e;
-        rc = dev_upload(&plan.d_list_idx, list_idx); if (rc) return rc;
-        rc = dev_alloc(&plan.d_apply_lists, apply.size()); if (rc) return rc;
+        rc = arena_upload(&r->big, &plan.d_list_idx, list_idx); if (rc) return rc;
+        rc = arena_alloc(&r->big, &plan.d_apply_lists, apply.size()); if (rc) return rc;
     }
     auto ins = r->plans.emplace(key, plan);
     *out = &ins.first->second;
     return PCR_OK;
 }
 
-void free_plans(pcr_record* r) {
-    for (auto& kv : r->plans) {
-        for (auto& l : kv.second.levels) { if (l.d_units) (void)hipFree(l.d_units); if (l.d_refine) (void)hipFree(l.d_refine); }
-        if (kv.second.d_apply) (void)hipFree(kv.second.d_apply);
-        if (kv.second.d_apply_lists) (void)hipFree(kv.second.d_apply_lists);
-        if (kv.second.d_list_idx) (void)hipFree(kv.second.d_list_idx);
-    }
-    r->plans.clear();
-}
+void free_plans(pcr_record* r) { r->plans.clear(); }        // (their device arrays belong to the arena)
 
 int check_scan_group(const pcr_record* r, int k) {
     if (k < 1 || k > (int)r->hdr.G) return PCR_E_RANGE;
@@ -296,8 +326,9 @@ static int validate_index(const uint8_t* hdr, const RecordHeader& h, std::vector
 }
 
 // Everything after the image/scan descriptors are known (r->img, r->scan filled, r->d.rec set):
-// dependency levels, buffer layout, remaining device allocations.
-static int finish_open(pcr_record* r) {
+// dependency levels, buffer layout, the buffers themselves (out of r->big), their initial contents.
+// Fills are enqueued on s; the caller synchronises s before anything else uses the handle.
+static int finish_open(pcr_record* r, hipStream_t s) {
     const uint32_t n = r->hdr.n, G = r->hdr.G;
     const size_t nbytes = r->nbytes;
     for (uint32_t i = 0; i < n; i++) if (r->img[i].status != kOk) return r->img[i].status;
@@ -337,41 +368,51 @@ static int finish_open(pcr_record* r) {
     r->n_masks = nm; r->n_slots = (uint32_t)ns; r->n_tiles = (uint32_t)tiles.size();
 
     DevRecord& d = r->d;
-    int rc = PCR_OK;
     const size_t padded = nbytes + 1024;      // slack: bit readers look ahead
-    if (!rc) rc = dev_alloc(&d.clean, padded);
-    if (!rc) rc = dev_alloc(&d.coef, r->coef_off[n]);
-    if (!rc) rc = dev_alloc(&d.masks, nm + 2);
-    if (!rc) rc = dev_alloc(&d.ivl_start, ns);
+    // what the buffers below take, plus room for the work lists of a few scan groups (16 bytes per unit,
+    // 12 per image and component, ...): anything beyond that is allocated on its own
+    size_t need = arena_round(padded) + arena_round(r->coef_off[n] * sizeof(int16_t)) + arena_round((nm + 2) * sizeof(uint64_t)) +
+                  arena_round((ns + 1) * sizeof(uint32_t)) + 2 * arena_round((n + 1) * sizeof(uint64_t)) +
+                  4 * arena_round(((size_t)n * G + 1) * sizeof(uint64_t)) + arena_round((tiles.size() + 1) * sizeof(PixelTile)) +
+                  arena_round(((size_t)ntabs + 1) * sizeof(AcTab));
+    need += 8 * ((ns + (size_t)n * G) * sizeof(Unit) + (size_t)n * kMaxComp * 64) + (1u << 20);
+    int rc = arena_reset(&r->big, need);
+    if (!rc) rc = arena_alloc(&r->big, &d.clean, padded);
+    if (!rc) rc = arena_alloc(&r->big, &d.coef, r->coef_off[n]);
+    if (!rc) rc = arena_alloc(&r->big, &d.masks, nm + 2);
+    if (!rc) rc = arena_alloc(&r->big, &d.ivl_start, ns);
     uint64_t *d_coef_off = nullptr, *d_out_off = nullptr, *d_mask_off = nullptr; uint32_t *d_sb = nullptr, *d_sc = nullptr;
-    if (!rc) rc = dev_upload(&d_coef_off, r->coef_off);
-    if (!rc) rc = dev_upload(&d_out_off, r->out_off);
-    if (!rc) rc = dev_upload(&d_mask_off, r->mask_off);
-    if (!rc) rc = dev_upload(&d_sb, r->slot_base);
-    if (!rc) rc = dev_upload(&d_sc, r->slot_cnt);
-    if (!rc) rc = dev_upload(&r->d_tiles, tiles);
+    if (!rc) rc = arena_upload(&r->big, &d_coef_off, r->coef_off);
+    if (!rc) rc = arena_upload(&r->big, &d_out_off, r->out_off);
+    if (!rc) rc = arena_upload(&r->big, &d_mask_off, r->mask_off);
+    if (!rc) rc = arena_upload(&r->big, &d_sb, r->slot_base);
+    if (!rc) rc = arena_upload(&r->big, &d_sc, r->slot_cnt);
+    if (!rc) rc = arena_upload(&r->big, &r->d_tiles, tiles);
     uint32_t* d_tab_idx = nullptr;
-    if (!rc) rc = dev_upload(&d_tab_idx, tab_idx);
-    if (!rc) rc = dev_alloc(&d.tabs, (size_t)ntabs);
+    if (!rc) rc = arena_upload(&r->big, &d_tab_idx, tab_idx);
+    if (!rc) rc = arena_alloc(&r->big, &d.tabs, (size_t)ntabs);
     d.tab_idx = d_tab_idx;
     d.coef_off = d_coef_off; d.out_off = d_out_off; d.mask_off = d_mask_off; d.slot_base = d_sb; d.slot_cnt = d_sc;
-    if (!rc && hipMemset(d.clean, 0xFF, padded) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc && hipMemset(d.masks, 0, (nm ? nm : 1) * sizeof(uint64_t)) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc && hipMemset(d.ivl_start, 0, (ns ? ns : 1) * sizeof(uint32_t)) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemsetAsync(d.clean, 0xFF, padded, s) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemsetAsync(d.masks, 0, (nm ? nm : 1) * sizeof(uint64_t), s) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemsetAsync(d.ivl_start, 0, (ns ? ns : 1) * sizeof(uint32_t), s) != hipSuccess) rc = PCR_E_DEVICE;
     return rc;
 }
 
-// Buffers the index and parse kernels write; needed before the descriptors exist.
-static int alloc_descriptor_buffers(pcr_record* r) {
+// Buffers the index and parse kernels write (out of r->small); needed before the descriptors exist.
+static int alloc_descriptor_buffers(pcr_record* r, hipStream_t s) {
     const uint32_t n = r->hdr.n, G = r->hdr.G;
     DevRecord& d = r->d;
-    int rc = dev_alloc(&d.off, (size_t)G * n);
-    if (!rc) rc = dev_alloc(&d.img, n);
-    if (!rc) rc = dev_alloc(&d.scan, (size_t)n * G);
-    if (!rc) rc = dev_alloc(&d.status, n);
-    if (!rc && hipMemset(d.off, 0, (size_t)G * n * sizeof(uint32_t)) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc && hipMemset(d.scan, 0, (size_t)n * G * sizeof(ScanDesc)) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc && hipMemset(d.img, 0, (size_t)n * sizeof(ImgDesc)) != hipSuccess) rc = PCR_E_DEVICE;
+    const size_t ng = (size_t)G * n;
+    int rc = arena_reset(&r->small, arena_round((ng + 1) * sizeof(uint32_t)) + arena_round((n + 1) * sizeof(ImgDesc)) +
+                                    arena_round((ng + 1) * sizeof(ScanDesc)) + arena_round((n + 1) * sizeof(int32_t)));
+    if (!rc) rc = arena_alloc(&r->small, &d.off, ng);
+    if (!rc) rc = arena_alloc(&r->small, &d.img, n);
+    if (!rc) rc = arena_alloc(&r->small, &d.scan, ng);
+    if (!rc) rc = arena_alloc(&r->small, &d.status, n);
+    if (!rc && hipMemsetAsync(d.off, 0, ng * sizeof(uint32_t), s) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemsetAsync(d.scan, 0, ng * sizeof(ScanDesc), s) != hipSuccess) rc = PCR_E_DEVICE;
+    if (!rc && hipMemsetAsync(d.img, 0, (size_t)n * sizeof(ImgDesc), s) != hipSuccess) rc = PCR_E_DEVICE;
     d.n = n; d.G = G;
     d.len = (const uint32_t*)(d.rec + hdr_len_pos(n, G, 0, 0));
     d.nscans = (const uint32_t*)(d.rec + hdr_nscans_pos(n, G, 0));
@@ -405,26 +446,24 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
             rc = r->img[i].status;
         }
     }
-    if (!rc) rc = dev_alloc(&r->d_rec, nbytes + 64);
+    if (!rc && hipMalloc((void**)&r->d_rec, nbytes + 64) != hipSuccess) { (void)hipGetLastError(); rc = PCR_E_NOMEM; }
     if (!rc && hipMemcpy(r->d_rec, bytes, nbytes, hipMemcpyHostToDevice) != hipSuccess) rc = PCR_E_DEVICE;
     if (!rc && hipMemset(r->d_rec + nbytes, 0, 64) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc) { r->d.rec = r->d_rec; rc = alloc_descriptor_buffers(r); }
-    if (!rc) rc = finish_open(r);
+    if (!rc) { r->d.rec = r->d_rec; rc = alloc_descriptor_buffers(r, nullptr); }
+    if (!rc) rc = finish_open(r, nullptr);
+    if (!rc && hipStreamSynchronize(nullptr) != hipSuccess) rc = PCR_E_DEVICE;
     if (rc) { (void)hipGetLastError(); pcr_close(r); return rc; }
     *out = r;
     return PCR_OK;
 }
 
-int pcr_open_device(const void* d_bytes, size_t nbytes, void* stream, pcr_record** out) {
-    if (!d_bytes || !out) return PCR_E_ARG;
-    if (((uintptr_t)d_bytes & 15) != 0) return PCR_E_ARG;              // header tables are read as aligned words
-    if (nbytes < 24) return PCR_E_TRUNCATED;
-    if (nbytes >= (1ull << 32)) return PCR_E_UNSUPPORTED;
-    hipPointerAttribute_t attr;
-    if (hipPointerGetAttributes(&attr, d_bytes) != hipSuccess) { (void)hipGetLastError(); return PCR_E_ARG; }
-    if (attr.type != hipMemoryTypeDevice) return PCR_E_ARG;
-    HIP_TRY(hipSetDevice(attr.device));
-    hipStream_t s = (hipStream_t)stream;
+// Binds handle r (fresh, or one whose earlier work has finished) to record bytes in device memory: header
+// checks on the host, index and marker parse ON THE DEVICE (only the small descriptor tables come back),
+// buffer layout.  Everything is enqueued on s, which is synchronised before returning.  On failure the
+// handle holds no record (pcr_close is all that may follow).
+static int bind_device(pcr_record* r, const void* d_bytes, size_t nbytes, hipStream_t s) {
+    r->plans.clear(); r->resident_k = 0; r->hdr = RecordHeader{}; r->n_tiles = 0;
+    r->out_off.assign(1, 0); r->coef_off.assign(1, 0);        // until the bind succeeds the handle holds no record
     // fixed part of the header, then the whole metadata block
     uint8_t fixed[24];
     HIP_TRY(hipMemcpyAsync(fixed, d_bytes, 24, hipMemcpyDeviceToHost, s));
@@ -433,22 +472,19 @@ int pcr_open_device(const void* d_bytes, size_t nbytes, void* stream, pcr_record
     const uint64_t header_bytes = ld_le64(fixed + 16);
     if (header_bytes < 24 || header_bytes > (1ull << 31)) return PCR_E_FORMAT;
     if (header_bytes > nbytes) return PCR_E_TRUNCATED;
-    pcr_record* r = new (std::nothrow) pcr_record();
-    if (!r) return PCR_E_NOMEM;
     r->header.resize(header_bytes);
     if (hipMemcpyAsync(r->header.data(), d_bytes, header_bytes, hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) {
-        (void)hipGetLastError(); delete r; return PCR_E_DEVICE;
+        (void)hipGetLastError(); return PCR_E_DEVICE;
     }
     RecordHeader h;
     int rc = parse_record_header(r->header.data(), nbytes, &h);
     if (!rc && h.k_avail == 0) rc = PCR_E_TRUNCATED;
-    if (rc) { delete r; return rc; }
-    r->device = attr.device; r->nbytes = nbytes; r->hdr = h; r->borrowed = true;
+    if (rc) return rc;
+    r->nbytes = nbytes; r->hdr = h;
     const uint32_t n = h.n, G = h.G;
     std::vector<uint32_t> off, len, nsc;
     rc = validate_index(r->header.data(), h, &off, &len, &nsc);
-    // index and marker parse ON THE DEVICE; only the small descriptor tables come back
-    if (!rc) { r->d.rec = (const uint8_t*)d_bytes; rc = alloc_descriptor_buffers(r); }
+    if (!rc) { r->d.rec = (const uint8_t*)d_bytes; rc = alloc_descriptor_buffers(r, s); }
     if (!rc) {
         hipLaunchKernelGGL(k_index, dim3(h.k_avail), dim3(256), 0, s, r->d, h.k_avail);
         hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, h.k_avail, 0u);
@@ -457,10 +493,49 @@ int pcr_open_device(const void* d_bytes, size_t nbytes, void* stream, pcr_record
             hipMemcpyAsync(r->scan.data(), r->d.scan, (size_t)n * G * sizeof(ScanDesc), hipMemcpyDeviceToHost, s) != hipSuccess ||
             hipStreamSynchronize(s) != hipSuccess) rc = PCR_E_DEVICE;
     }
-    if (!rc) rc = finish_open(r);
-    if (rc) { (void)hipGetLastError(); pcr_close(r); return rc; }
+    if (!rc) rc = finish_open(r, s);
+    if (!rc && hipStreamSynchronize(s) != hipSuccess) rc = PCR_E_DEVICE;
+    if (rc) { (void)hipGetLastError(); r->hdr = RecordHeader{}; r->n_tiles = 0; }
+    return rc;
+}
+
+static int check_device_bytes(const void* d_bytes, size_t nbytes, int* device) {
+    if (!d_bytes) return PCR_E_ARG;
+    if (((uintptr_t)d_bytes & 15) != 0) return PCR_E_ARG;              // header tables are read as aligned words
+    if (nbytes < 24) return PCR_E_TRUNCATED;
+    if (nbytes >= (1ull << 32)) return PCR_E_UNSUPPORTED;
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, d_bytes) != hipSuccess) { (void)hipGetLastError(); return PCR_E_ARG; }
+    if (attr.type != hipMemoryTypeDevice) return PCR_E_ARG;
+    *device = attr.device;
+    return PCR_OK;
+}
+
+int pcr_open_device(const void* d_bytes, size_t nbytes, void* stream, pcr_record** out) {
+    if (!out) return PCR_E_ARG;
+    int device = 0;
+    int rc = check_device_bytes(d_bytes, nbytes, &device);
+    if (rc) return rc;
+    HIP_TRY(hipSetDevice(device));
+    pcr_record* r = new (std::nothrow) pcr_record();
+    if (!r) return PCR_E_NOMEM;
+    r->device = device; r->borrowed = true;
+    rc = bind_device(r, d_bytes, nbytes, (hipStream_t)stream);
+    if (rc) { pcr_close(r); return rc; }
     *out = r;
     return PCR_OK;
+}
+
+int pcr_rebind_device(pcr_record* r, const void* d_bytes, size_t nbytes, void* stream) {
+    if (!r) return PCR_E_ARG;
+    int device = 0;
+    int rc = check_device_bytes(d_bytes, nbytes, &device);
+    if (rc) return rc;
+    if (device != r->device) return PCR_E_ARG;
+    HIP_TRY(hipSetDevice(device));
+    if (!r->borrowed && r->d_rec) { (void)hipFree(r->d_rec); }             // the handle's own copy of its first record
+    r->d_rec = nullptr; r->borrowed = true;
+    return bind_device(r, d_bytes, nbytes, (hipStream_t)stream);
 }
 
 void pcr_close(pcr_record* r) {
@@ -468,10 +543,9 @@ void pcr_close(pcr_record* r) {
     (void)hipSetDevice(r->device);
     (void)hipDeviceSynchronize();
     free_plans(r);
-    DevRecord& d = r->d;
-    void* ptrs[] = { r->borrowed ? nullptr : r->d_rec, d.clean, d.off, d.img, d.scan, d.coef, d.masks, d.ivl_start, d.status, (void*)d.coef_off, (void*)d.out_off,
-                     (void*)d.mask_off, (void*)d.slot_base, (void*)d.slot_cnt, r->d_tiles, r->d_gather, d.tabs, (void*)d.tab_idx };
-    for (void* p : ptrs) if (p) (void)hipFree(p);
+    arena_free(&r->small); arena_free(&r->big);
+    if (!r->borrowed && r->d_rec) (void)hipFree(r->d_rec);
+    if (r->d_gather) (void)hipFree(r->d_gather);
     for (auto& c : r->ring) for (auto& e : c.ev) (void)hipEventDestroy(e);
     delete r;
 }
@@ -499,12 +573,14 @@ int pcr_image_info(const pcr_record* r, int i, int* w, int* h, int* c, int32_t* 
 
 int pcr_output_layout(const pcr_record* r, uint64_t* offsets) {
     if (!r || !offsets) return PCR_E_ARG;
+    if (r->out_off.size() != (size_t)r->hdr.n + 1) { offsets[0] = 0; return r->hdr.n ? PCR_E_ARG : PCR_OK; }   // (a handle without a record: n = 0)
     std::memcpy(offsets, r->out_off.data(), r->out_off.size() * sizeof(uint64_t));
     return PCR_OK;
 }
 
 int pcr_coef_layout(const pcr_record* r, uint64_t* offsets) {
     if (!r || !offsets) return PCR_E_ARG;
+    if (r->coef_off.size() != (size_t)r->hdr.n + 1) { offsets[0] = 0; return r->hdr.n ? PCR_E_ARG : PCR_OK; }
     std::memcpy(offsets, r->coef_off.data(), r->coef_off.size() * sizeof(uint64_t));
     return PCR_OK;
 }
@@ -663,6 +739,137 @@ int pcr_probe_scalar_issue_rate(int device_id, int waves_per_cu, double* ginst_p
     (void)hipFree(d_out);
     if (rc == PCR_OK) *ginst_per_s = (double)grid * iters * 16.0 / (ms * 1e-3) / 1e9;
     return rc;
+}
+
+int pcr_prefix_length(const void* first_bytes, size_t nbytes, int k, uint64_t* need) {
+    if (!first_bytes || !need) return PCR_E_ARG;
+    const uint8_t* b = (const uint8_t*)first_bytes;
+    if (nbytes < 24) { *need = 24; return PCR_E_TRUNCATED; }
+    if (b[0] != 'P' || b[1] != 'C' || b[2] != 'R' || b[3] != '1') return PCR_E_FORMAT;
+    if (ld_le32(b + 4) != 1) return PCR_E_UNSUPPORTED;
+    const uint32_t G = ld_le32(b + 12);
+    if (k < 1 || (uint32_t)k > G) return PCR_E_RANGE;
+    const size_t pos = hdr_group_end_pos((uint32_t)k - 1);
+    if (nbytes < pos + 8) { *need = pos + 8; return PCR_E_TRUNCATED; }
+    *need = ld_le64(b + pos);
+    return PCR_OK;
+}
+
+// ---- loader: re-used pinned staging buffers, device buffers, streams and handles ----
+struct pcr_loader_slot {
+    void* host = nullptr; uint8_t* dev = nullptr; hipStream_t stream = nullptr; pcr_record* rec = nullptr;
+};
+struct pcr_loader {
+    int device = 0; size_t slot_bytes = 0;
+    std::vector<pcr_loader_slot> slots;
+    // token bucket: `rate` bytes are granted per second, at most `burst` are saved up
+    double rate = 0, burst = 0, tokens = 0;
+    std::chrono::steady_clock::time_point last;
+};
+
+int pcr_loader_create(int device_id, int slots, size_t slot_bytes, pcr_loader** out) {
+    if (!out || slots < 1 || slots > 16 || slot_bytes < 24 || slot_bytes >= (1ull << 32)) return PCR_E_ARG;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device_id < 0 || device_id >= ndev) { (void)hipGetLastError(); return PCR_E_DEVICE; }
+    HIP_TRY(hipSetDevice(device_id));
+    pcr_loader* ld = new (std::nothrow) pcr_loader();
+    if (!ld) return PCR_E_NOMEM;
+    ld->device = device_id; ld->slot_bytes = slot_bytes; ld->slots.resize((size_t)slots);
+    ld->last = std::chrono::steady_clock::now();
+    int rc = PCR_OK;
+    for (auto& sl : ld->slots) {
+        if (hipHostMalloc(&sl.host, slot_bytes, hipHostMallocDefault) != hipSuccess) { rc = PCR_E_NOMEM; break; }
+        if (hipMalloc((void**)&sl.dev, slot_bytes + 64) != hipSuccess) { rc = PCR_E_NOMEM; break; }
+        if (hipStreamCreateWithFlags(&sl.stream, hipStreamNonBlocking) != hipSuccess) { rc = PCR_E_DEVICE; break; }
+    }
+    if (rc) { (void)hipGetLastError(); pcr_loader_destroy(ld); return rc; }
+    *out = ld;
+    return PCR_OK;
+}
+
+void pcr_loader_destroy(pcr_loader* ld) {
+    if (!ld) return;
+    (void)hipSetDevice(ld->device);
+    for (auto& sl : ld->slots) {
+        if (sl.stream) (void)hipStreamSynchronize(sl.stream);
+        if (sl.rec) pcr_close(sl.rec);
+        if (sl.stream) (void)hipStreamDestroy(sl.stream);
+        if (sl.dev) (void)hipFree(sl.dev);
+        if (sl.host) (void)hipHostFree(sl.host);
+    }
+    delete ld;
+}
+
+static pcr_loader_slot* loader_slot(pcr_loader* ld, int slot) {
+    return (ld && slot >= 0 && (size_t)slot < ld->slots.size()) ? &ld->slots[(size_t)slot] : nullptr;
+}
+
+int pcr_loader_staging(pcr_loader* ld, int slot, void** host, size_t* capacity) {
+    pcr_loader_slot* sl = loader_slot(ld, slot);
+    if (!sl || !host) return PCR_E_ARG;
+    *host = sl->host;
+    if (capacity) *capacity = ld->slot_bytes;
+    return PCR_OK;
+}
+
+int pcr_loader_stream(pcr_loader* ld, int slot, void** hip_stream) {
+    pcr_loader_slot* sl = loader_slot(ld, slot);
+    if (!sl || !hip_stream) return PCR_E_ARG;
+    *hip_stream = (void*)sl->stream;
+    return PCR_OK;
+}
+
+int pcr_loader_set_rate(pcr_loader* ld, double bytes_per_second, double burst_bytes) {
+    if (!ld || bytes_per_second < 0 || burst_bytes < 0) return PCR_E_ARG;
+    ld->rate = bytes_per_second; ld->burst = burst_bytes; ld->tokens = 0;
+    ld->last = std::chrono::steady_clock::now();
+    return PCR_OK;
+}
+
+// blocks until the bucket holds `bytes` tokens (a request larger than the burst size waits for the whole amount)
+static void loader_take_tokens(pcr_loader* ld, double bytes) {
+    if (ld->rate <= 0) return;
+    for (;;) {
+        const auto now = std::chrono::steady_clock::now();
+        ld->tokens += std::chrono::duration<double>(now - ld->last).count() * ld->rate;
+        ld->last = now;
+        const double cap = std::max(ld->burst, bytes);
+        if (ld->tokens > cap) ld->tokens = cap;
+        if (ld->tokens >= bytes) { ld->tokens -= bytes; return; }
+        std::this_thread::sleep_for(std::chrono::duration<double>((bytes - ld->tokens) / ld->rate));
+    }
+}
+
+int pcr_loader_upload(pcr_loader* ld, int slot, size_t nbytes, pcr_record** rec) {
+    pcr_loader_slot* sl = loader_slot(ld, slot);
+    if (!sl) return PCR_E_ARG;
+    if (nbytes < 24) return PCR_E_TRUNCATED;
+    if (nbytes > ld->slot_bytes) return PCR_E_RANGE;
+    HIP_TRY(hipSetDevice(ld->device));
+    HIP_TRY(hipStreamSynchronize(sl->stream));                // the slot's buffers and handle are free again
+    loader_take_tokens(ld, (double)nbytes);
+    HIP_TRY(hipMemcpyAsync(sl->dev, sl->host, nbytes, hipMemcpyHostToDevice, sl->stream));
+    HIP_TRY(hipMemsetAsync(sl->dev + nbytes, 0, 64, sl->stream));
+    int rc;
+    if (!sl->rec) rc = pcr_open_device(sl->dev, nbytes, (void*)sl->stream, &sl->rec);
+    else rc = pcr_rebind_device(sl->rec, sl->dev, nbytes, (void*)sl->stream);
+    if (rc) return rc;
+    if (rec) *rec = sl->rec;
+    return PCR_OK;
+}
+
+int pcr_loader_decode(pcr_loader* ld, int slot, int k, uint8_t* out, size_t cap, int32_t* d_status) {
+    pcr_loader_slot* sl = loader_slot(ld, slot);
+    if (!sl || !sl->rec) return PCR_E_ARG;
+    return pcr_decode_batch(sl->rec, k, out, cap, (void*)sl->stream, d_status);
+}
+
+int pcr_loader_wait(pcr_loader* ld, int slot) {
+    pcr_loader_slot* sl = loader_slot(ld, slot);
+    if (!sl) return PCR_E_ARG;
+    HIP_TRY(hipSetDevice(ld->device));
+    HIP_TRY(hipStreamSynchronize(sl->stream));
+    return PCR_OK;
 }
 
 const char* pcr_strerror(int code) {

@@ -7,7 +7,7 @@ writes and share nothing else.
 
 The record layout ("PCR1") follows the paper's description of a PCR (Section 3 and the
 record figure: metadata first, then scan group 1, 2, ...; scan group g holds scan g of every
-image) in "raw struct" form (Section 3, "Loader").  All integers little-endian:
+image) in raw struct form (Section 5, "Loader").  All integers little-endian:
 
     0   char[4]  "PCR1"
     4   u32      version = 1

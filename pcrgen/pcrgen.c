@@ -6,7 +6,7 @@
  *
  * This module only PRODUCES inputs.  It contains no decoder and is used by neither the CPU
  * oracle nor the GPU library; both merely consume the bytes it writes.  The paper builds its
- * records from progressive files written by a stock transcoder (Section 3, "Encoding"); this
+ * records from progressive files written by a stock transcoder (Section 5, "Encoding"); this
  * file stands in for that tool so that inputs can be made without any dataset.
  *
  * Plain C99, no dependencies beyond libm.  All entry points are re-entrant.
@@ -612,7 +612,7 @@ size_t pcrgen_make_jpeg(uint64_t seed, int kind, int W, int H, int nc, double si
 }
 
 /* ------------------------------------------------------------------------------------------
- * Scan splitter (paper Section 3, "Encoding": locate the markers that end each scan).
+ * Scan splitter (paper Section 5, "Encoding": locate the markers that end each scan).
  * After every SOS header the entropy-coded data runs to the first 0xFF that is followed by
  * something other than 0x00, 0xD0..0xD7 or another 0xFF; that position ends the scan's region.
  * The last region runs to the end of the file.  Returns the number of scans, writes the end

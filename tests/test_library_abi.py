@@ -62,6 +62,40 @@ def test_header_validation_precedes_any_device_call(rgb_small):
     assert not h.value
 
 
+def test_prefix_length_from_the_first_bytes(rgb_small, gray64):
+    """How much of a record to read for fidelity k, against the oracle's index (no GPU involved)."""
+    import oracle
+    for rec in (rgb_small[0], gray64[0]):
+        G = oracle.record_header(rec)["G"]
+        ge = oracle.record_index(rec)[4]
+        for k in range(1, G + 1):
+            assert pkg.prefix_length(rec[:24 + 8 * G], k) == (True, int(ge[k - 1]))
+            assert pkg.prefix_length(rec, k) == (True, int(ge[k - 1]))
+            assert pkg.prefix_length(rec[:24 + 8 * k - 1], k) == (False, 24 + 8 * k)
+        assert pkg.prefix_length(rec[:10], 1) == (False, 24)
+        for k in (0, G + 1):
+            with pytest.raises(pkg.PcrError) as e:
+                pkg.prefix_length(rec, k)
+            assert e.value.code == pkg.E_RANGE
+        with pytest.raises(pkg.PcrError) as e:
+            pkg.prefix_length(b"XCR1" + rec[4:], 1)
+        assert e.value.code == pkg.E_FORMAT
+
+
+def test_loader_and_rebind_reject_null_arguments():
+    L = pkg.lib()
+    assert L.pcr_rebind_device(None, None, 0, None) == pkg.E_ARG
+    assert L.pcr_loader_create(0, 0, 1 << 20, None) == pkg.E_ARG
+    h = ctypes.c_void_p()
+    assert L.pcr_loader_create(0, 0, 1 << 20, ctypes.byref(h)) == pkg.E_ARG          # no slots
+    assert L.pcr_loader_create(0, 2, 8, ctypes.byref(h)) == pkg.E_ARG                # slots too small for any record
+    assert L.pcr_loader_upload(None, 0, 100, None) == pkg.E_ARG
+    assert L.pcr_loader_decode(None, 0, 1, None, 0, None) == pkg.E_ARG
+    assert L.pcr_loader_wait(None, 0) == pkg.E_ARG
+    assert L.pcr_loader_set_rate(None, 1.0, 1.0) == pkg.E_ARG
+    L.pcr_loader_destroy(None)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     import paper_1911_00472_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)

@@ -1,4 +1,4 @@
-"""Pins for the oracle's record level (paper Section 3: record figure, "Encoding", "Decoding").
+"""Pins for the oracle's record level (paper Section 3: record figure; Section 5: "Encoding", "Decoding").
 
 What fixes the answers here is the paper, not the oracle: reading every scan group must give
 back the original progressive file byte for byte; reading k groups must give the file's
