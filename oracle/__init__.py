@@ -161,3 +161,40 @@ def idct(F, direct=False):
     dp = ctypes.POINTER(ctypes.c_double)
     (lib().orc_idct_direct if direct else lib().orc_idct_separable)(F.ctypes.data_as(dp), f.ctypes.data_as(dp))
     return f.reshape(8, 8)
+
+
+def crop_resize_normalize(pix, box, flip, out_h, out_w, mean, inv_std):
+    """Training tail of the paper's input pipeline (Section 6.1: crop, resize and horizontal flip, as is
+    usual for ImageNet training; its appendix trains on 160x160 or 224x224 crops), written out in float64.
+    The paper fixes no formula; the reading taken is the common one: the crop box is resized with bilinear
+    interpolation on pixel centres, without anti-aliasing, samples beyond the box's edge repeat the edge,
+    a flip mirrors the result left to right, and channel c becomes (v / 255 - mean[c]) * inv_std[c].
+
+    pix      uint8 [H, W, C]      box  (x0, y0, w, h) inside the image      flip  bool
+    returns  float64 [C, out_h, out_w]
+
+    Output sample (oy, ox) looks at source point
+        sy = y0 + (oy + 0.5) * h / out_h - 0.5,      sx = x0 + (ox' + 0.5) * w / out_w - 0.5,
+    with ox' = out_w - 1 - ox if flipped, else ox, and mixes the four pixels around it."""
+    x0, y0, w, h = (int(v) for v in box)
+    H, W, C = pix.shape
+    assert 0 <= x0 and 0 <= y0 and w >= 1 and h >= 1 and x0 + w <= W and y0 + h <= H
+    p = pix.astype(np.float64)
+    out = np.zeros((C, out_h, out_w), np.float64)
+    for oy in range(out_h):
+        sy = y0 + (oy + 0.5) * h / out_h - 0.5
+        yl = int(np.floor(sy))
+        fy = sy - yl
+        ya = min(max(yl, y0), y0 + h - 1)
+        yb = min(max(yl + 1, y0), y0 + h - 1)
+        for ox in range(out_w):
+            oxs = out_w - 1 - ox if flip else ox
+            sx = x0 + (oxs + 0.5) * w / out_w - 0.5
+            xl = int(np.floor(sx))
+            fx = sx - xl
+            xa = min(max(xl, x0), x0 + w - 1)
+            xb = min(max(xl + 1, x0), x0 + w - 1)
+            v = (1 - fy) * ((1 - fx) * p[ya, xa] + fx * p[ya, xb]) + fy * ((1 - fx) * p[yb, xa] + fx * p[yb, xb])
+            for c in range(C):
+                out[c, oy, ox] = (v[c] / 255.0 - mean[c]) * inv_std[c]
+    return out
