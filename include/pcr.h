@@ -154,6 +154,20 @@ int pcr_upgrade_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, siz
                       void* hip_stream, int32_t* d_status);
 int pcr_resident_scan_group(const pcr_record* rec, int* scan_group);
 
+/* Training tail (Section 6.1: the experiments crop, resize and flip the decoded images, as is usual for ImageNet
+ * training; the appendix trains on 160x160 and 224x224 crops).  For every image of the record one box of its
+ * decoded pixels is resized to out_h x out_w -- bilinear interpolation on pixel centres, no anti-aliasing, samples
+ * beyond the box's edge repeat the edge --, mirrored left to right if flip != 0, and channel c becomes
+ * (v / 255 - mean[c]) * inv_std[c], stored as IEEE half precision in a dense [n][C][out_h][out_w] tensor.
+ *   d_pixels   device: pixels in the layout of pcr_output_layout (what pcr_decode_batch wrote)
+ *   d_crops    device: n boxes in source pixels; a box reaching outside its image is clamped into it
+ *   mean, inv_std   host: C floats each (C = channels of the images, which must all agree: else UNSUPPORTED)
+ *   d_out_f16  device: n*C*out_h*out_w halfs; out_capacity in bytes
+ * Which box and whether to flip is the caller's (random) choice.  Asynchronous on hip_stream. */
+typedef struct { int32_t x0, y0, w, h, flip; } pcr_crop;
+int pcr_crop_resize_batch(pcr_record* rec, const uint8_t* d_pixels, const pcr_crop* d_crops, int out_h, int out_w,
+                          const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity, void* hip_stream);
+
 /* ---- loader: host bytes -> device -> pixels, double-buffered (Section 5, "Loader") ----
  *
  * pcr_prefix_length: how much of a record must be read for fidelity k, from the record's first bytes alone

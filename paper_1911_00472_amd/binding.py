@@ -39,6 +39,8 @@ SYMBOLS = {
     "pcr_last_stage_ms": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_float)]),
     "pcr_probe_scalar_issue_rate": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]),
     "pcr_stage_ms_history": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]),
+    "pcr_crop_resize_batch": (ctypes.c_int, [_vp, _vp, _vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
+                                             ctypes.POINTER(ctypes.c_float), _vp, ctypes.c_size_t, _vp]),
     "pcr_prefix_length": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_loader_create": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]),
     "pcr_loader_destroy": (None, [_vp]),
@@ -201,6 +203,21 @@ class Record:
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_upgrade_batch(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
                "pcr_upgrade_batch")
+        return out
+
+    def crop_resize_batch(self, pixels, crops, out_h, out_w, mean, inv_std, out=None, stream=None):
+        """pixels: uint8 CUDA tensor in output_layout(); crops: int32 CUDA tensor [n, 5] (x0, y0, w, h, flip).
+        Returns a float16 CUDA tensor [n, C, out_h, out_w] (asynchronous on the stream)."""
+        import torch
+        assert crops.is_cuda and crops.dtype == torch.int32 and crops.is_contiguous() and tuple(crops.shape) == (self.n, 5)
+        C = self.image_info(0)[2]
+        if out is None:
+            out = torch.empty((self.n, C, out_h, out_w), dtype=torch.float16, device="cuda:%d" % self.device)
+        m = (ctypes.c_float * 3)(*([float(v) for v in mean] + [0.0] * 3)[:3])
+        sd = (ctypes.c_float * 3)(*([float(v) for v in inv_std] + [1.0] * 3)[:3])
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_crop_resize_batch(self._h, pixels.data_ptr(), crops.data_ptr(), out_h, out_w, m, sd, out.data_ptr(),
+                                           out.numel() * 2, s), "pcr_crop_resize_batch")
         return out
 
     def resident_scan_group(self):

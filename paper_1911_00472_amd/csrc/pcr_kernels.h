@@ -9,6 +9,7 @@
 //   k_gather     materialise an image's scan prefix (parity hook)
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include "pcr_common.h"
 #include "pcr_format.h"
 #include "pcr_entropy.h"
@@ -477,6 +478,53 @@ __global__ void __launch_bounds__(256) k_export_natural(const int16_t* in, int16
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * 256;
     for (; i < n; i += stride) out[(i & ~(size_t)63) + zz[i & 63]] = in[i];
+}
+
+// --------------------------------------------------------------------------------------
+// k_crop_resize: the training tail.  For every image one box of the decoded pixels is resized to
+// out_h x out_w with bilinear interpolation on pixel centres (no anti-aliasing; samples beyond the
+// box's edge repeat the edge), optionally mirrored left to right, normalised per channel and written
+// as half precision, channel-planar: out[((i * C + c) * out_h + oy) * out_w + ox].
+// One lane per output sample position (all channels), grid (ceil(out_h * out_w / 256), n).  A box that
+// does not lie inside its image is clamped into it.
+// --------------------------------------------------------------------------------------
+struct CropBox { int32_t x0, y0, w, h, flip; };
+
+// dims: width and height per image and out_off: byte offset of every image in `in`, both as laid down when the
+// record was opened (the descriptors in device memory are only filled by a decode call).
+__global__ void __launch_bounds__(256) k_crop_resize(const uint32_t* __restrict__ dims, const uint64_t* __restrict__ out_off,
+        const uint8_t* __restrict__ in, const CropBox* __restrict__ boxes,
+        int out_h, int out_w, int C, float m0, float m1, float m2, float s0, float s1, float s2, __half* __restrict__ out) {
+    const uint32_t i = blockIdx.y;
+    const int o = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (o >= out_h * out_w) return;
+    const int oy = o / out_w, ox = o - oy * out_w;
+    const int W = (int)dims[2 * i], H = (int)dims[2 * i + 1];
+    if (W < 1 || H < 1) return;
+    CropBox b = boxes[i];
+    b.x0 = min(max(b.x0, 0), W - 1); b.y0 = min(max(b.y0, 0), H - 1);
+    b.w = min(max(b.w, 1), W - b.x0); b.h = min(max(b.h, 1), H - b.y0);
+    const int oxs = b.flip ? out_w - 1 - ox : ox;
+    // source point relative to the box, as an exact fraction: ((2 o + 1) * size - out) / (2 * out) pixels
+    const int ny = (2 * oy + 1) * b.h - out_h, dy = 2 * out_h, nx = (2 * oxs + 1) * b.w - out_w, dx = 2 * out_w;
+    const int yl = ny >= 0 ? ny / dy : -((dy - 1 - ny) / dy), xl = nx >= 0 ? nx / dx : -((dx - 1 - nx) / dx);      // floor
+    const float fy = (float)(ny - yl * dy) / (float)dy, fx = (float)(nx - xl * dx) / (float)dx;
+    const int ya = b.y0 + min(max(yl, 0), b.h - 1), yb = b.y0 + min(max(yl + 1, 0), b.h - 1);
+    const int xa = b.x0 + min(max(xl, 0), b.w - 1), xb = b.x0 + min(max(xl + 1, 0), b.w - 1);
+    const uint8_t* img = in + out_off[i];
+    const uint8_t* paa = img + ((size_t)ya * W + xa) * C; const uint8_t* pab = img + ((size_t)ya * W + xb) * C;
+    const uint8_t* pba = img + ((size_t)yb * W + xa) * C; const uint8_t* pbb = img + ((size_t)yb * W + xb) * C;
+    const float mean[3] = {m0, m1, m2}, istd[3] = {s0, s1, s2};
+    __half* dst = out + ((size_t)i * C * out_h + oy) * out_w + ox;
+#pragma unroll
+    for (int c = 0; c < 3; c++) {
+        if (c < C) {
+            const float top = (1.0f - fx) * (float)paa[c] + fx * (float)pab[c];
+            const float bot = (1.0f - fx) * (float)pba[c] + fx * (float)pbb[c];
+            const float v = (1.0f - fy) * top + fy * bot;
+            dst[(size_t)c * out_h * out_w] = __float2half_rn((v * (1.0f / 255.0f) - mean[c]) * istd[c]);
+        }
+    }
 }
 
 // --------------------------------------------------------------------------------------

@@ -105,6 +105,7 @@ struct pcr_record {
     Arena small, big;                       // descriptor tables (sized by n and G) / everything sized by the images, and the work lists
     uint8_t* d_rec = nullptr;
     PixelTile* d_tiles = nullptr; uint32_t n_tiles = 0;
+    uint32_t* d_dims = nullptr;             // [n][2] width, height (for kernels that run without a decode before them)
     uint8_t* d_gather = nullptr; size_t gather_cap = 0;
     std::map<int, Plan> plans;
     bool timing = false;
@@ -373,7 +374,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     // 12 per image and component, ...): anything beyond that is allocated on its own
     size_t need = arena_round(padded) + arena_round(r->coef_off[n] * sizeof(int16_t)) + arena_round((nm + 2) * sizeof(uint64_t)) +
                   arena_round((ns + 1) * sizeof(uint32_t)) + 2 * arena_round((n + 1) * sizeof(uint64_t)) +
-                  4 * arena_round(((size_t)n * G + 1) * sizeof(uint64_t)) + arena_round((tiles.size() + 1) * sizeof(PixelTile)) +
+                  4 * arena_round(((size_t)n * G + 1) * sizeof(uint64_t)) + arena_round((tiles.size() + 1) * sizeof(PixelTile)) + arena_round((n + 1) * 8) +
                   arena_round(((size_t)ntabs + 1) * sizeof(AcTab));
     need += 8 * ((ns + (size_t)n * G) * sizeof(Unit) + (size_t)n * kMaxComp * 64) + (1u << 20);
     int rc = arena_reset(&r->big, need);
@@ -388,6 +389,9 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     if (!rc) rc = arena_upload(&r->big, &d_sb, r->slot_base);
     if (!rc) rc = arena_upload(&r->big, &d_sc, r->slot_cnt);
     if (!rc) rc = arena_upload(&r->big, &r->d_tiles, tiles);
+    std::vector<uint32_t> dims((size_t)n * 2);
+    for (uint32_t i = 0; i < n; i++) { dims[2 * i] = (uint32_t)r->img[i].W; dims[2 * i + 1] = (uint32_t)r->img[i].H; }
+    if (!rc) rc = arena_upload(&r->big, &r->d_dims, dims);
     uint32_t* d_tab_idx = nullptr;
     if (!rc) rc = arena_upload(&r->big, &d_tab_idx, tab_idx);
     if (!rc) rc = arena_alloc(&r->big, &d.tabs, (size_t)ntabs);
@@ -464,6 +468,7 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
 static int bind_device(pcr_record* r, const void* d_bytes, size_t nbytes, hipStream_t s) {
     r->plans.clear(); r->resident_k = 0; r->hdr = RecordHeader{}; r->n_tiles = 0;
     r->out_off.assign(1, 0); r->coef_off.assign(1, 0);        // until the bind succeeds the handle holds no record
+    r->d_dims = nullptr;
     // fixed part of the header, then the whole metadata block
     uint8_t fixed[24];
     HIP_TRY(hipMemcpyAsync(fixed, d_bytes, 24, hipMemcpyDeviceToHost, s));
@@ -714,6 +719,26 @@ int pcr_upgrade_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* stre
     if (rc) return rc;
     if (r->resident_k < 1 || k < r->resident_k) return PCR_E_ARG;
     return decode_to_pixels(r, r->resident_k, k, out, cap, stream, d_status);
+}
+
+int pcr_crop_resize_batch(pcr_record* r, const uint8_t* d_pixels, const pcr_crop* d_crops, int out_h, int out_w,
+                          const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity, void* stream) {
+    if (!r || !d_pixels || !d_crops || !mean || !inv_std) return PCR_E_ARG;
+    if (out_h < 1 || out_w < 1 || out_h > 8192 || out_w > 8192) return PCR_E_RANGE;      // (the kernel's fractions stay inside 32 bits)
+    if (!d_out_f16) return PCR_E_ARG;
+    const uint32_t n = r->hdr.n;
+    if (n == 0 || !r->d_dims) return PCR_E_ARG;
+    const int C = r->img[0].nc;
+    for (uint32_t i = 1; i < n; i++) if (r->img[i].nc != C) return PCR_E_UNSUPPORTED;    // one tensor, one channel count
+    if (out_capacity < (size_t)n * C * out_h * out_w * sizeof(__half)) return PCR_E_RANGE;
+    HIP_TRY(hipSetDevice(r->device));
+    static_assert(sizeof(pcr_crop) == sizeof(CropBox), "crop box layout");
+    const dim3 grid(((uint32_t)(out_h * out_w) + 255) / 256, n);
+    hipLaunchKernelGGL(k_crop_resize, grid, dim3(256), 0, (hipStream_t)stream, r->d_dims, r->d.out_off, d_pixels, reinterpret_cast<const CropBox*>(d_crops),
+                       out_h, out_w, C, mean[0], C > 1 ? mean[1] : 0.f, C > 2 ? mean[2] : 0.f,
+                       inv_std[0], C > 1 ? inv_std[1] : 1.f, C > 2 ? inv_std[2] : 1.f, reinterpret_cast<__half*>(d_out_f16));
+    if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
+    return PCR_OK;
 }
 
 int pcr_probe_scalar_issue_rate(int device_id, int waves_per_cu, double* ginst_per_s) {
