@@ -485,20 +485,30 @@ __global__ void __launch_bounds__(256) k_export_natural(const int16_t* in, int16
 // out_h x out_w with bilinear interpolation on pixel centres (no anti-aliasing; samples beyond the
 // box's edge repeat the edge), optionally mirrored left to right, normalised per channel and written
 // as half precision, channel-planar: out[((i * C + c) * out_h + oy) * out_w + ox].
-// One lane per output sample position (all channels), grid (ceil(out_h * out_w / 256), n).  A box that
-// does not lie inside its image is clamped into it.
+// One lane per output sample position (all channels); a workgroup covers 32 columns of 8 rows (the usual
+// training sizes are multiples of 32), so a wavefront stores two runs of 64 contiguous bytes per channel.
+// grid (ceil(out_w / 32), ceil(out_h / 8), n).  A box that does not lie inside its image is clamped into it.
+// dims: width and height per image and out_off: byte offset of every image in `in`, both as laid down when the
+// record was opened (the descriptors in device memory are only filled by a decode call).
 // --------------------------------------------------------------------------------------
 struct CropBox { int32_t x0, y0, w, h, flip; };
 
-// dims: width and height per image and out_off: byte offset of every image in `in`, both as laid down when the
-// record was opened (the descriptors in device memory are only filled by a decode call).
+// floor(num / den) and the remainder in [0, den), den > 0, |num| < 2^31: the quotient is guessed in single
+// precision (off by one at most for the quotients that occur, below 2^17) and put right with the remainder
+PCR_D void floor_div(int num, int den, float inv_den, int* q, int* r) {
+    int g = (int)floorf((float)num * inv_den);
+    int rem = num - g * den;
+    if (rem < 0) { g--; rem += den; }
+    if (rem >= den) { g++; rem -= den; }
+    *q = g; *r = rem;
+}
+
 __global__ void __launch_bounds__(256) k_crop_resize(const uint32_t* __restrict__ dims, const uint64_t* __restrict__ out_off,
         const uint8_t* __restrict__ in, const CropBox* __restrict__ boxes,
         int out_h, int out_w, int C, float m0, float m1, float m2, float s0, float s1, float s2, __half* __restrict__ out) {
-    const uint32_t i = blockIdx.y;
-    const int o = (int)(blockIdx.x * 256 + threadIdx.x);
-    if (o >= out_h * out_w) return;
-    const int oy = o / out_w, ox = o - oy * out_w;
+    const uint32_t i = blockIdx.z;
+    const int ox = (int)(blockIdx.x * 32 + (threadIdx.x & 31)), oy = (int)(blockIdx.y * 8 + (threadIdx.x >> 5));
+    if (ox >= out_w || oy >= out_h) return;
     const int W = (int)dims[2 * i], H = (int)dims[2 * i + 1];
     if (W < 1 || H < 1) return;
     CropBox b = boxes[i];
@@ -506,9 +516,12 @@ __global__ void __launch_bounds__(256) k_crop_resize(const uint32_t* __restrict_
     b.w = min(max(b.w, 1), W - b.x0); b.h = min(max(b.h, 1), H - b.y0);
     const int oxs = b.flip ? out_w - 1 - ox : ox;
     // source point relative to the box, as an exact fraction: ((2 o + 1) * size - out) / (2 * out) pixels
-    const int ny = (2 * oy + 1) * b.h - out_h, dy = 2 * out_h, nx = (2 * oxs + 1) * b.w - out_w, dx = 2 * out_w;
-    const int yl = ny >= 0 ? ny / dy : -((dy - 1 - ny) / dy), xl = nx >= 0 ? nx / dx : -((dx - 1 - nx) / dx);      // floor
-    const float fy = (float)(ny - yl * dy) / (float)dy, fx = (float)(nx - xl * dx) / (float)dx;
+    const int dy = 2 * out_h, dx = 2 * out_w;
+    const float inv_dy = 1.0f / (float)dy, inv_dx = 1.0f / (float)dx;
+    int yl, ry, xl, rx;
+    floor_div((2 * oy + 1) * b.h - out_h, dy, inv_dy, &yl, &ry);
+    floor_div((2 * oxs + 1) * b.w - out_w, dx, inv_dx, &xl, &rx);
+    const float fy = (float)ry * inv_dy, fx = (float)rx * inv_dx;
     const int ya = b.y0 + min(max(yl, 0), b.h - 1), yb = b.y0 + min(max(yl + 1, 0), b.h - 1);
     const int xa = b.x0 + min(max(xl, 0), b.w - 1), xb = b.x0 + min(max(xl + 1, 0), b.w - 1);
     const uint8_t* img = in + out_off[i];

@@ -733,7 +733,8 @@ int pcr_crop_resize_batch(pcr_record* r, const uint8_t* d_pixels, const pcr_crop
     if (out_capacity < (size_t)n * C * out_h * out_w * sizeof(__half)) return PCR_E_RANGE;
     HIP_TRY(hipSetDevice(r->device));
     static_assert(sizeof(pcr_crop) == sizeof(CropBox), "crop box layout");
-    const dim3 grid(((uint32_t)(out_h * out_w) + 255) / 256, n);
+    if (n > 65535) return PCR_E_UNSUPPORTED;                  // (images are the grid's third dimension)
+    const dim3 grid(((uint32_t)out_w + 31) / 32, ((uint32_t)out_h + 7) / 8, n);
     hipLaunchKernelGGL(k_crop_resize, grid, dim3(256), 0, (hipStream_t)stream, r->d_dims, r->d.out_off, d_pixels, reinterpret_cast<const CropBox*>(d_crops),
                        out_h, out_w, C, mean[0], C > 1 ? mean[1] : 0.f, C > 2 ? mean[2] : 0.f,
                        inv_std[0], C > 1 ? inv_std[1] : 1.f, C > 2 ? inv_std[2] : 1.f, reinterpret_cast<__half*>(d_out_f16));
