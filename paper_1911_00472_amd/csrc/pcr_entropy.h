@@ -122,55 +122,9 @@ PCR_HD void actab_build(AcTab* t, const uint8_t* bits_vals) {
     }
 }
 
-// ---------------------------------------------------------------------------------------
-// Bit reader over the unstuffed data of one unit.  The data is stored as big-endian 32-bit
-// words (the unstuff step swaps the bytes of every aligned 4-byte group), so a word is usable
-// as loaded.  `acc` holds `cnt` valid bits left-aligned in 64 bits; `nxt` is the following
-// word, loaded one refill ahead so that the loop never waits on the load it has just issued.
-// The state is deliberately tiny (pointer, accumulator, one word, one count): when the unit is
-// wave-uniform all of it sits in scalar registers.  The buffer must stay readable for 16 bytes
-// past any position a decoder can reach before it checks overrun().
-// ---------------------------------------------------------------------------------------
-struct BitReader {
-    const uint32_t* p;          // word after nxt
-    const uint32_t* end_word;   // first word wholly past the unit
-    uint64_t acc;
-    uint32_t nxt;
-    int32_t cnt;
-    int32_t tail_bits;          // bits of the unit that lie in the words before end_word
-
-    // words: 4-byte aligned base of the segment; byte_off: where the unit starts inside it
-    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes) {
-        const uint32_t mis = byte_off & 3;
-        p = words + (byte_off >> 2);
-        const uint32_t total_bits = nbytes * 8 + mis * 8;    // from the first word's first bit
-        end_word = p + ((total_bits + 31) >> 5);
-        tail_bits = (int32_t)(((total_bits + 31) & ~31u) - total_bits);   // padding bits inside the last word
-        acc = ((uint64_t)p[0] << 32) | p[1]; cnt = 64;
-        nxt = p[2]; p += 3;
-        advance((int)(mis * 8));
-    }
-    PCR_HD uint32_t window() const { return (uint32_t)(acc >> 32); }     // the next 32 unread bits
-    PCR_HD void pop_word() {                                 // cnt <= 32: append one word, fetch the one after
-        acc |= (uint64_t)nxt << (32 - cnt); cnt += 32;
-        nxt = *p++;
-    }
-    PCR_HD void advance(int n) {                             // 0 <= n <= 32; afterwards cnt >= 33
-        acc <<= n; cnt -= n;
-        if (cnt <= 32) pop_word();
-    }
-    PCR_HD void advance_long(int n) {                        // any n >= 0
-        while (n > 32) { acc <<= 32; cnt -= 32; if (cnt <= 32) pop_word(); n -= 32; }
-        acc <<= n; cnt -= n;
-        if (cnt <= 32) pop_word();
-    }
-    // bits consumed so far, counted from the unit's first bit
-    PCR_HD int64_t unread_bits() const {                     // may be negative: bits taken beyond the unit
-        // words handed out so far: everything before p, minus nxt (32 bits) and the cnt bits still in acc
-        return (int64_t)(end_word - p) * 32 + 32 + cnt - tail_bits;
-    }
-    PCR_HD bool overrun() const { return unread_bits() < 0; }
-};
+// The unstuffed data of a unit is stored as big-endian 32-bit words (the unstuff step swaps the bytes of
+// every aligned 4-byte group), so a word is usable as loaded.  The buffer stays readable for some bytes
+// past any position a decoder can reach before it checks for an overrun.
 
 // bits [len, len+n) of a 32-bit window (n may be 0)
 PCR_HD uint32_t field(uint32_t win, int len, int n) { return n ? (win << len) >> (32 - n) : 0; }
@@ -584,18 +538,6 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
 // ---------------------------------------------------------------------------------------
 PCR_HD uint64_t band_mask(int Ss, int Se) { return ((Se >= 63) ? ~0ull : ((1ull << (Se + 1)) - 1)) & ~((1ull << Ss) - 1); }
 
-PCR_HD uint64_t take_correction_bits(BitReader* br, int n) {    // n <= 63; first bit read -> bit 0
-    uint64_t out = 0; int done = 0;
-    while (n > 0) {
-        const int t = n > 31 ? 31 : n;
-        const uint32_t v = br->window() >> (32 - t);            // first-read bit is the MSB of the t bits
-        br->advance(t);
-        out |= (uint64_t)(bitrev32(v) >> (32 - t)) << done;
-        done += t; n -= t;
-    }
-    return out;
-}
-
 // What an AC refinement scan leaves per block: one record of kRefWords 64-bit words (zig-zag bit order),
 //   [kRefNz]    positions that become non-zero in this scan (later scans need them as history)   } written by
 //   [kRefStart] bit offset of the block inside its unit | end-of-band run pending at its start << 32  } phase 1,
@@ -838,47 +780,68 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
 }
 
 // Phase 2 (data-parallel, one lane per block): decode one block completely from its start.
-//   words, byte_off  the unit's unstuffed data;  st  the block's entry of `start`;  h  history mask
+//   words, byte_off  the unit's unstuffed data;  st  the block's kRefStart word;  h  history mask;
+//   newm  the positions phase 1 found to become non-zero (kRefNz): the j-th symbol that carries a
+//         coefficient lands on the j-th of them, so no zero run has to be counted here
 // Returns the sign mask (1 = positive) of the positions that become non-zero and the correction
 // bits in reading order (first bit read = bit 0): exactly one per history-non-zero position of
 // the band, in zig-zag order.
-PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, const AcTab* tab, uint64_t h, int Ss, int Se,
+// The position in the stream is a plain bit offset; the 32 bits at it are fetched from two words.
+PCR_HD uint32_t stream_bits(const uint32_t* words, uint32_t bit) {          // the 32 bits that start at bit offset `bit`
+    const uint32_t w = bit >> 5, sh = bit & 31;
+    const uint64_t two = ((uint64_t)words[w] << 32) | words[w + 1];
+    return (uint32_t)((two << sh) >> 32);
+}
+PCR_HD uint64_t correction_bits(const uint32_t* words, uint32_t bit, uint32_t n) {   // n <= 63 bits from `bit`; first bit read -> bit 0
+    uint64_t out = 0; uint32_t done = 0;
+    while (n > 0) {
+        const uint32_t t = n > 32 ? 32 : n;
+        out |= (uint64_t)(bitrev32(stream_bits(words, bit + done)) & (t == 32 ? ~0u : (1u << t) - 1)) << done;   // reversed: the first bit read becomes bit 0
+        done += t; n -= t;
+    }
+    return out;
+}
+
+PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, const AcTab* tab, uint64_t h, uint64_t newm, int Ss, int Se,
                          uint64_t* sign_out, uint64_t* cbits_out) {
     const uint64_t band = band_mask(Ss, Se);
     h &= band;
-    const uint32_t bitpos = (uint32_t)st;
-    uint32_t eobrun = (uint32_t)(st >> 32);
-    BitReader br;
-    br.init(words, byte_off + (bitpos >> 3), 1u << 20);
-    br.advance((int)(bitpos & 7));
-    uint64_t sgn = 0, cb = 0; int ncb = 0;
-    int k = Ss;
-    if (eobrun == 0) {
+    uint32_t p = byte_off * 8 + (uint32_t)st;                // bit offset of the next unread bit
+    const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
+    uint64_t sgn = 0, cb = 0;
+    uint32_t taken = 0;                                      // correction bits read so far
+    uint32_t n = ncorr;                                      // inside an end-of-band run: all of them, nothing else
+    if ((uint32_t)(st >> 32) == 0) {
+        uint64_t rem = newm & band;                          // positions still to receive their coefficient
+        int k = Ss;                                          // first position not yet passed
+        n = 0;
         while (k <= Se) {
-            const uint32_t win = br.window();
+            const uint32_t win = stream_bits(words, p);
             const uint32_t e = ac_code(tab, win);
             if (!e) break;                                   // phase 1 has already flagged the image
-            const int len = (int)(e >> 8), r = (int)((e >> 4) & 15), s = (int)(e & 15);
-            const bool eob = (s == 0) & (r != 15);
-            const int nx = s ? 1 : (eob ? r : 0);
-            const uint32_t sbit = field(win, len, nx);
-            br.advance(len + nx);
-            if (eob) { eobrun = 1; break; }
-            const uint64_t from_k = band & ~((1ull << k) - 1);
-            uint64_t z = ~h & from_k;
-            for (int q = 0; q < r && z; q++) z &= z - 1;
-            const int pos = z ? __builtin_ctzll(z) : Se + 1;
-            const uint64_t upto = (pos >= 64) ? ~0ull : ((1ull << pos) - 1);
-            const int n = __builtin_popcountll(h & from_k & upto);
-            if (n) { cb |= take_correction_bits(&br, n) << ncb; ncb += n; }
-            if (s && pos <= Se) sgn |= (uint64_t)(sbit & 1) << pos;
+            const uint32_t len = e >> 8, r = (e >> 4) & 15, s = e & 15;
+            int pos;
+            if (s) {                                         // code, sign bit, then the corrections passed on the way
+                if (!rem) break;
+                pos = __builtin_ctzll(rem); rem &= rem - 1;
+                sgn |= (uint64_t)((win << len) >> 31) << pos;
+                p += len + 1;
+            } else if (r == 15) {                            // sixteen zeros: lands on the sixteenth zero from k, which stays zero
+                p += len;
+                uint64_t z = ~h & band & ~((1ull << k) - 1);
+                for (int q = 0; q < 15 && z; q++) z &= z - 1;
+                pos = z ? __builtin_ctzll(z) : Se;
+            } else {                                         // end of band: code, run-length bits, then every correction left
+                p += len + r;
+                n = ncorr - taken;
+                break;
+            }
+            const uint32_t upto = (uint32_t)__builtin_popcountll(h & ((2ull << pos) - 1));   // corrections at positions <= pos (pos itself is a zero)
+            if (upto > taken) { cb |= correction_bits(words, p, upto - taken) << taken; p += upto - taken; taken = upto; }
             k = pos + 1;
         }
     }
-    if (eobrun > 0 && k <= Se) {
-        const int n = __builtin_popcountll(h & ~((1ull << k) - 1));
-        if (n) cb |= take_correction_bits(&br, n) << ncb;
-    }
+    if (n) cb |= correction_bits(words, p, n) << taken;
     *sign_out = sgn; *cbits_out = cb;
 }
 

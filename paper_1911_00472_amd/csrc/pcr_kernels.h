@@ -366,7 +366,7 @@ __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const Refine
     const uint32_t ivl = sd->ri ? b / sd->ri : 0;
     const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + clean_base(sd->data_off));
     uint64_t sgn, cb;
-    refine_block(words, R.ivl_start[R.slot_base[ig] + ivl], rec[kRefStart], &tab, h, sd->Ss, sd->Se, &sgn, &cb);
+    refine_block(words, R.ivl_start[R.slot_base[ig] + ivl], rec[kRefStart], &tab, h, rec[kRefNz], sd->Ss, sd->Se, &sgn, &cb);
     rec[kRefSign] = sgn; rec[kRefCbits] = cb;
 }
 

@@ -99,7 +99,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                     for (uint32_t mm = ls.mcu0; mm < ls.mcu1; mm++) {
                         size_t blk = (size_t)(mm / sd.mcu_w) * img.bw[c0] + (mm % sd.mcu_w);
                         uint64_t* rec = masks[g].data() + blk * kRefWords;
-                        refine_block(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], rec[kRefStart], &at, rec[kRefHist], sd.Ss, sd.Se,
+                        refine_block(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], rec[kRefStart], &at, rec[kRefHist], rec[kRefNz], sd.Ss, sd.Se,
                                      &rec[kRefSign], &rec[kRefCbits]);
                     }
                 }
