@@ -338,9 +338,11 @@ struct CoefSink {
 };
 
 // ---------------------------------------------------------------------------------------
-// Window reader for DC first scans: as WindowReader, but an interleaved scan switches between up
-// to three DC tables (one per component), so every lane looks its offset up in each distinct
-// table and the serial part picks the word of the table of the block it is decoding.
+// Window reader for DC first scans: as WindowReader, but an interleaved scan switches between the
+// DC tables of its components, so every lane looks its offset up in the table of each scan
+// component (once per distinct table) and the serial part picks the word of the component whose
+// block it is decoding.  Everything is indexed by scan component with constants: a run-time index
+// into the reader would pin it to memory.
 // packed word: difference (16 bits, signed) << 16 | total bits (6) << 8 | category (4)
 // ---------------------------------------------------------------------------------------
 PCR_HD uint32_t pack_dc(uint32_t e, uint32_t win) {          // e = (length << 4) | category, non-zero
@@ -351,16 +353,16 @@ PCR_HD uint32_t pack_dc(uint32_t e, uint32_t win) {          // e = (length << 4
 
 struct DcWindowReader {
     StreamPtr p;
-    const DcTab* tab[kMaxComp];
+    const DcTab* tab[kMaxComp];     // table of scan component j
     uint32_t w0, w1, w2, n0, n1;
     uint32_t o, wbase, mis_bits, total_bits, lane;
-    uint32_t vinfo[kMaxComp];
-    uint32_t nocode;            // set when the bits at the current position are no code of the table
-    int ntab;
+    uint32_t vinfo[kMaxComp];       // this lane's packed word under the table of scan component j
+    uint32_t nocode;                // set when the bits at the current position are no code of the table
+    int ncomp;
 
     PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const DcTab* t0, const DcTab* t1, const DcTab* t2,
-                     int ntables, uint32_t lane_id) {
-        tab[0] = t0; tab[1] = t1; tab[2] = t2; ntab = ntables; lane = lane_id;
+                     int ncomponents, uint32_t lane_id) {
+        tab[0] = t0; tab[1] = t1; tab[2] = t2; ncomp = ncomponents; lane = lane_id;
         mis_bits = (byte_off & 3) * 8;
         p = stream_ptr(words + (byte_off >> 2));
         w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
@@ -368,13 +370,13 @@ struct DcWindowReader {
         vinfo[0] = vinfo[1] = vinfo[2] = 0;
         fill();
     }
+    PCR_HD uint32_t word_of(const DcTab* t, uint32_t win) const { const uint32_t e = t->lut[win >> 24]; return e != 0xFF ? pack_dc(e, win) : 0; }
     PCR_HD void fill() {
 #if defined(__HIP_DEVICE_COMPILE__)
         const uint32_t win = bits_at(w0, w1, w2, (int)lane);
-#pragma unroll
-        for (int j = 0; j < kMaxComp; j++) {
-            if (j < ntab) { const uint32_t e = tab[j]->lut[win >> 24]; vinfo[j] = e != 0xFF ? pack_dc(e, win) : 0; }
-        }
+        vinfo[0] = word_of(tab[0], win);
+        if (ncomp > 1) vinfo[1] = tab[1] == tab[0] ? vinfo[0] : word_of(tab[1], win);
+        if (ncomp > 2) vinfo[2] = tab[2] == tab[1] ? vinfo[1] : (tab[2] == tab[0] ? vinfo[0] : word_of(tab[2], win));
 #endif
     }
     PCR_HD bool exhausted() const { return o >= 64; }
@@ -382,19 +384,18 @@ struct DcWindowReader {
         do { w0 = w2; w1 = n0; w2 = n1; n0 = p[0]; n1 = p[1]; p += 2; o -= 64; wbase += 64; } while (o >= 64);
         fill();
     }
-    // packed word of the symbol at the current position (inside the window) under table j; where the bits are
-    // no code at all it returns 0 (length 0, difference 0) and raises `nocode`
-    PCR_HD uint32_t peek(int j) {
+    // packed word of the symbol at the current position (inside the window) for scan component J; where the bits
+    // are no code at all it returns 0 (length 0, difference 0) and raises `nocode`
+    template <int J> PCR_HD uint32_t peek() {
         uint32_t info;
 #if defined(__HIP_DEVICE_COMPILE__)
-        const uint32_t v = j == 0 ? vinfo[0] : (j == 1 ? vinfo[1] : vinfo[2]);
-        info = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)o);
+        info = (uint32_t)__builtin_amdgcn_readlane((int)vinfo[J], (int)o);
 #else
-        { const uint32_t win = bits_at(w0, w1, w2, (int)o); const uint32_t e = tab[j]->lut[win >> 24]; info = e != 0xFF ? pack_dc(e, win) : 0; }
+        info = word_of(tab[J], bits_at(w0, w1, w2, (int)o));
 #endif
         if (__builtin_expect(info == 0, 0)) {                // a code longer than 8 bits, or garbage
             const uint32_t win = bits_at(w0, w1, w2, (int)o);
-            const uint32_t e = dc_code(tab[j], win);
+            const uint32_t e = dc_code(tab[J], win);
             info = uni(e ? pack_dc(e, win) : 0u);            // (table reads come back in vector registers)
             nocode |= uni(e ? 0u : 1u);
         }
@@ -411,36 +412,77 @@ struct DcWindowReader {
 // in it ([bh][bw][64] blocks, DC at element 0 of each block).  tj0/1/2: which of the reader's tables each
 // scan component uses.
 // ---------------------------------------------------------------------------------------
-PCR_HD int decode_dc_first(DcWindowReader* wr, const LaneScan& ls, int tj0, int tj1, int tj2, CoefSink* sink) {
-    int pred[kMaxComp] = {0, 0, 0};
-    const int tj[kMaxComp] = {tj0, tj1, tj2};
+// One DC symbol of scan component J for the block at element e.
+template <int J>
+PCR_HD void dc_first_block(DcWindowReader* wr, CoefSink* sink, int* pred, uint32_t e, uint32_t* bad) {
+    if (wr->exhausted()) {
+        sink->flush();
+        *bad |= wr->overrun_bit();                           // never walk far beyond the unit's data
+        wr->refill();
+    }
+    const uint32_t info = wr->peek<J>();
+    *pred += (int32_t)info >> 16;
+    sink->emit(wr->o, e, (int)(((uint32_t)*pred << 16) | kSymCoef));
+    wr->consume((info >> 8) & 63);
+}
+
+// The common shapes with everything about the MCU known at compile time: NS components, the first one
+// HS0 x VS0 blocks per MCU, the others one block (a non-interleaved scan is NS = 1, one block per "MCU" and
+// only the blocks that cover the component's samples).  Element indices run along instead of being
+// recomputed per MCU.
+template <int NS, int HS0, int VS0>
+PCR_HD int decode_dc_first_shape(DcWindowReader* wr, const LaneScan& ls, CoefSink* sink) {
+    int pred0 = 0, pred1 = 0, pred2 = 0;
+    const uint32_t mcu_w = ls.mcu_w;
+    const uint32_t my0 = ls.mcu0 / mcu_w;
+    uint32_t mx = ls.mcu0 % mcu_w;
+    const uint32_t bw0 = ls.bw[0];
+    uint32_t e0 = ls.poff[0] + ((my0 * VS0) * bw0 + mx * HS0) * 64;
+    uint32_t e1 = NS > 1 ? ls.poff[1] + (my0 * ls.bw[1] + mx) * 64 : 0;
+    uint32_t e2 = NS > 2 ? ls.poff[2] + (my0 * ls.bw[2] + mx) * 64 : 0;
+    // at the end of a row of MCUs: on to the first block of the next row of MCUs
+    const uint32_t wrap0 = (VS0 * bw0 - mcu_w * HS0) * 64;
+    const uint32_t wrap1 = NS > 1 ? (ls.bw[1] - mcu_w) * 64 : 0, wrap2 = NS > 2 ? (ls.bw[2] - mcu_w) * 64 : 0;
+    uint32_t bad = 0;
+    uint32_t left = ls.mcu1 - ls.mcu0;
+    while (left != 0) {
+#pragma unroll
+        for (int by = 0; by < VS0; by++) {
+#pragma unroll
+            for (int bx = 0; bx < HS0; bx++) dc_first_block<0>(wr, sink, &pred0, e0 + (by * bw0 + bx) * 64, &bad);
+        }
+        if (NS > 1) dc_first_block<1>(wr, sink, &pred1, e1, &bad);
+        if (NS > 2) dc_first_block<2>(wr, sink, &pred2, e2, &bad);
+        bad |= wr->nocode;
+        e0 += HS0 * 64; e1 += 64; e2 += 64;
+        if (++mx == mcu_w) { mx = 0; e0 += wrap0; e1 += wrap1; e2 += wrap2; }
+        left = bad ? 0 : left - 1;
+    }
+    sink->flush();
+    bad |= wr->overrun_bit();
+    return bad ? kEFormat : kOk;
+}
+
+// Any other shape.
+template <int J>
+PCR_HD void dc_first_component(DcWindowReader* wr, const LaneScan& ls, CoefSink* sink, uint32_t mx, uint32_t my, int* pred, uint32_t* bad) {
+    const uint32_t hs = ls.ns > 1 ? ls.hs[J] : 1, vs = ls.ns > 1 ? ls.vs[J] : 1, bw = ls.bw[J];
+    uint32_t rowe = ls.poff[J] + ((my * vs) * bw + mx * hs) * 64;       // first block of this MCU in the plane
+    for (uint32_t by = 0; by < vs; by++) {
+        uint32_t e = rowe;
+        for (uint32_t bx = 0; bx < hs; bx++) { dc_first_block<J>(wr, sink, pred, e, bad); e += 64; }
+        rowe += bw * 64;
+    }
+}
+PCR_HD int decode_dc_first_any(DcWindowReader* wr, const LaneScan& ls, CoefSink* sink) {
+    int pred0 = 0, pred1 = 0, pred2 = 0;
     uint32_t my = ls.mcu0 / ls.mcu_w, mx = ls.mcu0 % ls.mcu_w;
     uint32_t bad = 0;
     uint32_t m = ls.mcu0;
     while (m < ls.mcu1) {
-#pragma unroll
-        for (int j = 0; j < kMaxComp; j++) {                 // unrolled: every index below is a constant
-            if (j < ls.ns) {
-                const uint32_t hs = ls.ns > 1 ? ls.hs[j] : 1, vs = ls.ns > 1 ? ls.vs[j] : 1, bw = ls.bw[j];
-                uint32_t rowe = ls.poff[j] + ((my * vs) * bw + mx * hs) * 64;       // first block of this MCU in the plane
-                for (uint32_t by = 0; by < vs; by++) {
-                    uint32_t e = rowe;
-                    for (uint32_t bx = 0; bx < hs; bx++) {
-                        if (wr->exhausted()) {
-                            sink->flush();
-                            bad |= wr->overrun_bit();        // never walk far beyond the unit's data
-                            wr->refill();
-                        }
-                        const uint32_t info = wr->peek(tj[j]);
-                        pred[j] += (int32_t)info >> 16;
-                        sink->emit(wr->o, e, (int)(((uint32_t)pred[j] << 16) | kSymCoef));
-                        wr->consume((info >> 8) & 63);
-                        e += 64;
-                    }
-                    rowe += bw * 64;
-                }
-            }
-        }
+        dc_first_component<0>(wr, ls, sink, mx, my, &pred0, &bad);
+        if (ls.ns > 1) dc_first_component<1>(wr, ls, sink, mx, my, &pred1, &bad);
+        if (ls.ns > 2) dc_first_component<2>(wr, ls, sink, mx, my, &pred2, &bad);
         bad |= wr->nocode;
         if (++mx == ls.mcu_w) { mx = 0; my++; }
         m = bad ? ls.mcu1 : m + 1;
@@ -448,6 +490,37 @@ PCR_HD int decode_dc_first(DcWindowReader* wr, const LaneScan& ls, int tj0, int 
     sink->flush();
     bad |= wr->overrun_bit();
     return bad ? kEFormat : kOk;
+}
+
+// Which of the decoders above fits a scan: 0 = decode_dc_first_any, else an instance of decode_dc_first_shape
+// (kDcShapes of them).  ns: components of the scan; hs, vs: their sampling factors in scan order (passed one by
+// one: an array argument would pin the caller's copy of them to memory).
+constexpr int kDcShapes = 5;
+PCR_HD int dc_shape(int ns, uint32_t hs0, uint32_t vs0, uint32_t hs1, uint32_t vs1, uint32_t hs2, uint32_t vs2) {
+    if (ns == 1) return 1;
+    if (ns == 3 && hs1 == 1 && vs1 == 1 && hs2 == 1 && vs2 == 1) {
+        if (hs0 == 2 && vs0 == 2) return 2;
+        if (hs0 == 1 && vs0 == 1) return 3;
+        if (hs0 == 2 && vs0 == 1) return 4;
+    }
+    return 0;
+}
+template <int SHAPE>
+PCR_HD int decode_dc_first_as(DcWindowReader* wr, const LaneScan& ls, CoefSink* sink) {
+    if (SHAPE == 1) return decode_dc_first_shape<1, 1, 1>(wr, ls, sink);
+    if (SHAPE == 2) return decode_dc_first_shape<3, 2, 2>(wr, ls, sink);
+    if (SHAPE == 3) return decode_dc_first_shape<3, 1, 1>(wr, ls, sink);
+    if (SHAPE == 4) return decode_dc_first_shape<3, 2, 1>(wr, ls, sink);
+    return decode_dc_first_any(wr, ls, sink);
+}
+PCR_HD int decode_dc_first(DcWindowReader* wr, const LaneScan& ls, CoefSink* sink) {
+    switch (dc_shape(ls.ns, ls.hs[0], ls.vs[0], ls.hs[1], ls.vs[1], ls.hs[2], ls.vs[2])) {
+        case 1: return decode_dc_first_as<1>(wr, ls, sink);
+        case 2: return decode_dc_first_as<2>(wr, ls, sink);
+        case 3: return decode_dc_first_as<3>(wr, ls, sink);
+        case 4: return decode_dc_first_as<4>(wr, ls, sink);
+        default: return decode_dc_first_as<0>(wr, ls, sink);
+    }
 }
 
 // ---------------------------------------------------------------------------------------

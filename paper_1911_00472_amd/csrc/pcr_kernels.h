@@ -252,6 +252,8 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __rest
     L->ok = true;
 }
 
+// SHAPE: which DC decoder (dc_shape) the units of this launch take; the host sorts the units by it.
+template <int SHAPE>
 __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
         const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {
     __shared__ DcTab tabs[kMaxComp];
@@ -270,11 +272,12 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     if (threadIdx.x == 1 && tj1 == 1) dctab_build(&tabs[1], R.rec + o1);
     if (threadIdx.x == 2 && tj2 != 0 && tj2 != tj1) dctab_build(&tabs[tj2], R.rec + o2);
     __syncthreads();
-    DcWindowReader wr;
-    wr.init(L.words, L.byte_off, L.nbytes, &tabs[0], &tabs[1], &tabs[2], uni(ntab), threadIdx.x);
+    DcWindowReader wr;                                      // tables by scan component
+    wr.init(L.words, L.byte_off, L.nbytes, &tabs[0], &tabs[uni(tj1)], &tabs[uni(tj2)], L.ls.ns, threadIdx.x);
     CoefSink sink;
     sink.init(L.base, L.base_elems, L.ls.Al);
-    int rc = decode_dc_first(&wr, L.ls, 0, uni(tj1), uni(tj2), &sink);
+    int rc = kEFormat;                                      // (a unit in the wrong launch: the descriptors disagree with the host's)
+    if (dc_shape(L.ls.ns, L.ls.hs[0], L.ls.vs[0], L.ls.hs[1], L.ls.vs[1], L.ls.hs[2], L.ls.vs[2]) == SHAPE) rc = decode_dc_first_as<SHAPE>(&wr, L.ls, &sink);
     if (rc != kOk) R.status[un.img] = rc;
 }
 

@@ -24,6 +24,7 @@ namespace {
 enum Kind { kDcFirst = 0, kAcFirst = 1, kAcRefine = 2, kNumKinds = 3 };
 struct LevelList {
     Unit* d_units = nullptr; uint32_t n = 0; int kind = 0;
+    int shape = 0;                                                               // DC first scans: dc_shape of the units
     RefineScan* d_refine = nullptr; uint32_t n_refine = 0, refine_grid_x = 0;   // phase 2 of an AC refinement launch
 };
 
@@ -147,7 +148,8 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
     const uint32_t n = r->hdr.n, G = r->hdr.G;
     Plan plan;
     struct Item { Unit u; uint32_t bytes; };
-    std::vector<std::vector<Item>> lists((size_t)r->max_level * kNumKinds);
+    // one list per (dependency level, kind of scan, DC decoder shape: 0 for the AC kinds)
+    std::vector<std::vector<Item>> lists((size_t)r->max_level * kNumKinds * kDcShapes);
     std::vector<std::vector<RefineScan>> rlists(r->max_level); std::vector<uint32_t> rmax(r->max_level, 0);
     std::vector<ApplyUnit> apply; uint32_t max_blk = 0;
     for (uint32_t i = 0; i < n; i++) {
@@ -165,9 +167,15 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
                 rlists[r->level[ig] - 1].push_back(RefineScan{i, g});
                 rmax[r->level[ig] - 1] = std::max<uint32_t>(rmax[r->level[ig] - 1], (uint32_t)r->img[i].cw[sd.comp[0]] * r->img[i].ch[sd.comp[0]]);
             }
+            int shape = 0;
+            if (kind == kDcFirst) {
+                uint32_t hs[kMaxComp] = {1, 1, 1}, vs[kMaxComp] = {1, 1, 1};
+                for (int j = 0; j < sd.ns && j < kMaxComp; j++) { hs[j] = r->img[i].hs[sd.comp[j]]; vs[j] = r->img[i].vs[sd.comp[j]]; }
+                shape = dc_shape(sd.ns, hs[0], vs[0], hs[1], vs[1], hs[2], vs[2]);
+            }
             const uint32_t cnt = r->slot_cnt[ig];
             for (uint32_t j = 0; j < cnt; j++)
-                lists[(size_t)(r->level[ig] - 1) * kNumKinds + kind].push_back(Item{Unit{i, g, j, r->slot_base[ig]}, sd.data_len / cnt});
+                lists[((size_t)(r->level[ig] - 1) * kNumKinds + kind) * kDcShapes + shape].push_back(Item{Unit{i, g, j, r->slot_base[ig]}, sd.data_len / cnt});
         }
         for (int c = 0; c < r->img[i].nc; c++) if (refine[c]) {
             apply.push_back(ApplyUnit{i, (uint32_t)c});
@@ -180,11 +188,12 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
         std::stable_sort(l.begin(), l.end(), [](const Item& a, const Item& b) { return a.bytes > b.bytes; });   // longest first
         std::vector<Unit> units(l.size());
         for (size_t e = 0; e < l.size(); e++) units[e] = l[e].u;
-        LevelList ll; ll.n = (uint32_t)units.size(); ll.kind = (int)(li % kNumKinds);
+        LevelList ll; ll.n = (uint32_t)units.size(); ll.kind = (int)((li / kDcShapes) % kNumKinds); ll.shape = (int)(li % kDcShapes);
         int rc = arena_upload(&r->big, &ll.d_units, units); if (rc) return rc;
         if (ll.kind == kAcRefine) {
-            const auto& rl = rlists[li / kNumKinds];
-            ll.n_refine = (uint32_t)rl.size(); ll.refine_grid_x = (rmax[li / kNumKinds] + 255) / 256;
+            const size_t lv = li / kDcShapes / kNumKinds;
+            const auto& rl = rlists[lv];
+            ll.n_refine = (uint32_t)rl.size(); ll.refine_grid_x = (rmax[lv] + 255) / 256;
             rc = arena_upload(&r->big, &ll.d_refine, rl); if (rc) return rc;
         }
         plan.levels.push_back(ll);
@@ -279,7 +288,16 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
     const uint64_t* h64 = r->d.masks;
     for (auto& l : plan->levels) {
         const dim3 grid(l.n), block(kEntropyLanes);
-        if (l.kind == kDcFirst) { hipLaunchKernelGGL(k_dc_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_DC_FIRST, s); }
+        if (l.kind == kDcFirst) {
+            switch (l.shape) {
+                case 1: hipLaunchKernelGGL(k_dc_first<1>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
+                case 2: hipLaunchKernelGGL(k_dc_first<2>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
+                case 3: hipLaunchKernelGGL(k_dc_first<3>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
+                case 4: hipLaunchKernelGGL(k_dc_first<4>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
+                default: hipLaunchKernelGGL(k_dc_first<0>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
+            }
+            mark(r, PCR_STAGE_DC_FIRST, s);
+        }
         else if (l.kind == kAcFirst) { hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_AC_FIRST, s); }
         else {
             hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64);

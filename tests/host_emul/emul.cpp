@@ -83,7 +83,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 for (int q = 0; q < sd.ns; q++) dctab_build(&dt[q], rec + sd.dc_off[q]);
                 DcWindowReader dw; dw.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &dt[0], &dt[1], &dt[2], sd.ns, 0);
                 CoefSink dsink; dsink.init(coef.data(), (uint32_t)coef.size(), ls.Al);
-                rc = decode_dc_first(&dw, ls, 0, 1, 2, &dsink);
+                rc = decode_dc_first(&dw, ls, &dsink);
             } else {
                 AcTab at; actab_build(&at, rec + sd.ac_off); actab_pack(&at, sd.Ah == 0, 0, 1);
                 WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &at, sd.Ah == 0, 0);
