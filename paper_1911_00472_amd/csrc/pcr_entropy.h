@@ -779,17 +779,24 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
     const uint32_t last_blk = ((ls.mcu1 - 1) / mcu_w) * bw + (ls.mcu1 - 1) % mcu_w;
     uint32_t eobrun = 0;                                     // blocks still covered by an end-of-band run
     uint32_t bad = 0;
-    HistWords hnext = hist_fetch(hp, blk, wr->lane);
+    // The history of a block is fetched two blocks ahead (a block of a dozen symbols is shorter than a trip to
+    // memory): h0 belongs to the current block, h1 to the next one, and the fetch cursor (fblk, fcol) runs two
+    // ahead, stopping at the unit's last block.
+    uint32_t fblk = blk, fcol = col;
+    HistWords h0 = hist_fetch(hp, fblk, wr->lane);
+    fblk++; if (++fcol == mcu_w) { fcol = 0; fblk += row_skip; }
+    HistWords h1 = hist_fetch(hp, fblk < last_blk ? fblk : last_blk, wr->lane);
     ZeroTable zt;
     while (left != 0) {
-        const uint64_t h = hist_combine(hnext) & band;        // already non-zero
+        const uint64_t h = hist_combine(h0) & band;           // already non-zero
         const uint64_t z = h ^ band;                         // still zero
         uint64_t* rec = recs + (size_t)blk * kRefWords;
-        // the block after this one, and its history (the last block fetches its own again)
         blk++;
         if (++col == mcu_w) { col = 0; blk += row_skip; }
         left--;
-        hnext = hist_fetch(hp, blk < last_blk ? blk : last_blk, wr->lane);
+        fblk++; if (++fcol == mcu_w) { fcol = 0; fblk += row_skip; }
+        h0 = h1;
+        h1 = hist_fetch(hp, fblk < last_blk ? fblk : last_blk, wr->lane);
         const uint64_t start = ((uint64_t)eobrun << 32) | wr->position();
         const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
         uint64_t newm = 0;
