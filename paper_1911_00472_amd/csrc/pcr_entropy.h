@@ -626,36 +626,42 @@ constexpr int kRefNz = 0, kRefStart = 1, kRefHist = 2, kRefSign = 3, kRefCbits =
 struct HistPlanes { const int16_t* coef; const uint64_t* p[kMaxHist]; int n; };
 
 struct HistWords {                                            // one block's history, combined only when used
-    uint64_t a;                                               // what earlier refinement scans added
 #if defined(__HIP_DEVICE_COMPILE__)
+    uint32_t half;                                            // even lanes: low half, odd lanes: high half of what earlier refinement scans added
     int16_t mine;                                             // this lane's coefficient of the block
 #else
-    uint64_t first;
+    uint64_t a, first;
 #endif
 };
-PCR_HD uint64_t hist_word(const uint64_t* recs, uint32_t byte_off) {        // (32-bit offsets: a scan's records stay far below 4 GiB)
-    return *reinterpret_cast<const uint64_t*>(reinterpret_cast<const char*>(recs) + byte_off);
-}
+// On the device the record word is fetched by the vector unit (every lane one half of it) although it is the
+// same for all lanes: scalar loads return out of order, so a wait for any LDS result -- there is one ahead of
+// every symbol loop -- would also wait for a scalar load issued just before it for two blocks later, and expose
+// a trip to memory per block.  Vector loads return in order and have a counter of their own.
 PCR_HD HistWords hist_fetch(const HistPlanes& hp, uint32_t blk, uint32_t lane) {
-    HistWords w; w.a = 0;
+    HistWords w;
+    const uint32_t off = (blk * kRefWords + kRefNz) * 8;      // (32-bit offsets: a scan's records stay far below 4 GiB)
+#if defined(__HIP_DEVICE_COMPILE__)
+    w.half = 0;
     if (hp.n > 0) {
-        const uint32_t off = (blk * kRefWords + kRefNz) * 8;
-        w.a = hist_word(hp.p[0], off);
+        const uint32_t sel = off + (lane & 1) * 4;
+        w.half = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(hp.p[0]) + sel);
         if (__builtin_expect(hp.n > 1, 0)) {                 // scripts with more than two refinement passes over a band
-            for (int q = 1; q < kMaxHist; q++) if (q < hp.n) w.a |= hist_word(hp.p[q], off);
+            for (int q = 1; q < kMaxHist; q++) if (q < hp.n) w.half |= *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(hp.p[q]) + sel);
         }
     }
-#if defined(__HIP_DEVICE_COMPILE__)
     w.mine = hp.coef[(size_t)blk * 64 + lane];
 #else
     (void)lane;
+    w.a = 0;
+    for (int q = 0; q < kMaxHist; q++) if (q < hp.n) w.a |= *reinterpret_cast<const uint64_t*>(reinterpret_cast<const char*>(hp.p[q]) + off);
     w.first = nz_mask_of_block(hp.coef + (size_t)blk * 64, 0, 63);
 #endif
     return w;
 }
 PCR_HD uint64_t hist_combine(const HistWords& w) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    return w.a | __ballot(w.mine != 0);
+    const uint64_t a = (uint32_t)__builtin_amdgcn_readlane((int)w.half, 0) | ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)w.half, 1) << 32);
+    return a | __ballot(w.mine != 0);
 #else
     return w.a | w.first;
 #endif
@@ -787,16 +793,18 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
     fblk++; if (++fcol == mcu_w) { fcol = 0; fblk += row_skip; }
     HistWords h1 = hist_fetch(hp, fblk < last_blk ? fblk : last_blk, wr->lane);
     ZeroTable zt;
-    while (left != 0) {
-        const uint64_t h = hist_combine(h0) & band;           // already non-zero
+    // One block.  hw: the block's history on entry; on return the fetch for the block two further on is under way in it.
+    // (Two copies of this body alternate below, each with its own history registers: handing the words from one
+    // variable to the next would mean waiting for the fetch that is still in flight.)
+    auto one_block = [&](HistWords& hw) {
+        const uint64_t h = hist_combine(hw) & band;           // already non-zero
         const uint64_t z = h ^ band;                         // still zero
         uint64_t* rec = recs + (size_t)blk * kRefWords;
         blk++;
         if (++col == mcu_w) { col = 0; blk += row_skip; }
         left--;
         fblk++; if (++fcol == mcu_w) { fcol = 0; fblk += row_skip; }
-        h0 = h1;
-        h1 = hist_fetch(hp, fblk < last_blk ? fblk : last_blk, wr->lane);
+        hw = hist_fetch(hp, fblk < last_blk ? fblk : last_blk, wr->lane);
         const uint64_t start = ((uint64_t)eobrun << 32) | wr->position();
         const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
         uint64_t newm = 0;
@@ -855,6 +863,11 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
         rec[kRefNz] = newm; rec[kRefStart] = start; rec[kRefHist] = h;   // (phase 2 and the refinement replay work on the same history)
         bad |= wr->overrun_bit();
         left = bad ? 0 : left;                               // stop at the first damaged block
+    };
+    while (left != 0) {
+        one_block(h0);
+        if (left == 0) break;
+        one_block(h1);
     }
     return bad ? kEFormat : kOk;
 }
