@@ -248,15 +248,42 @@ struct WindowReader {
     uint32_t mis_bits, total_bits;
     uint32_t lane;              // this lane's offset (device); unused on the host
     uint32_t vinfo;             // this lane's packed word (device)
+    const uint32_t* g;          // p again, for the vector memory path
+    uint32_t vnext;             // device: even lanes p[0], odd lanes p[1], fetched one window ahead (see slide)
     bool first;
+    bool vfeed;                 // fetch the stream through the vector memory path (see fetch_next)
 
-    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const AcTab* t, bool first_scan, uint32_t lane_id) {
-        tab = t; first = first_scan; lane = lane_id;
+    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const AcTab* t, bool first_scan, uint32_t lane_id, bool vector_feed) {
+        tab = t; first = first_scan; lane = lane_id; vfeed = vector_feed;
         mis_bits = (byte_off & 3) * 8;
         p = stream_ptr(words + (byte_off >> 2));
         w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
+        g = words + (byte_off >> 2) + 5;
         o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits;
+        vnext = 0;
+        fetch_next();
         fill();
+    }
+    // With vfeed the two words after n1 are fetched by the vector unit, one per lane parity, although they are the
+    // same for all lanes: a scalar load is waited for together with the LDS look-up that follows it in fill()
+    // (scalar loads and LDS share a counter and scalar loads return out of order), a window before it is needed.
+    // A decoder that keeps other vector loads in flight (the refinement history) is better off with the scalar
+    // load: the vector counter is in order, and the wait for these words would take the younger loads with it.
+    PCR_HD void fetch_next() {
+#if defined(__HIP_DEVICE_COMPILE__)
+        if (vfeed) vnext = g[lane & 1];
+#endif
+    }
+    PCR_HD void slide() {                                     // on by 64 bits
+        w0 = w2; w1 = n0; w2 = n1;
+#if defined(__HIP_DEVICE_COMPILE__)
+        if (vfeed) { n0 = (uint32_t)__builtin_amdgcn_readlane((int)vnext, 0); n1 = (uint32_t)__builtin_amdgcn_readlane((int)vnext, 1); }
+        else { n0 = p[0]; n1 = p[1]; }
+#else
+        n0 = p[0]; n1 = p[1];
+#endif
+        p += 2; g += 2; o -= 64; wbase += 64;
+        fetch_next();
     }
     PCR_HD void fill() {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -281,7 +308,7 @@ struct WindowReader {
     }
     PCR_HD bool exhausted() const { return o >= 64; }         // the next symbol starts beyond the window
     PCR_HD void refill() {
-        do { w0 = w2; w1 = n0; w2 = n1; n0 = p[0]; n1 = p[1]; p += 2; o -= 64; wbase += 64; } while (o >= 64);
+        do slide(); while (o >= 64);
         fill();
     }
     PCR_HD void consume(uint32_t n) { o += n; }
@@ -359,6 +386,8 @@ struct DcWindowReader {
     uint32_t vinfo[kMaxComp];       // this lane's packed word under the table of scan component j
     uint32_t nocode;                // set when the bits at the current position are no code of the table
     int ncomp;
+    const uint32_t* g;              // p again, for the vector memory path (as in WindowReader)
+    uint32_t vnext;
 
     PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const DcTab* t0, const DcTab* t1, const DcTab* t2,
                      int ncomponents, uint32_t lane_id) {
@@ -366,9 +395,26 @@ struct DcWindowReader {
         mis_bits = (byte_off & 3) * 8;
         p = stream_ptr(words + (byte_off >> 2));
         w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
+        g = words + (byte_off >> 2) + 5;
         o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits; nocode = 0;
         vinfo[0] = vinfo[1] = vinfo[2] = 0;
+        fetch_next();
         fill();
+    }
+    PCR_HD void fetch_next() {
+#if defined(__HIP_DEVICE_COMPILE__)
+        vnext = g[lane & 1];
+#endif
+    }
+    PCR_HD void slide() {                                     // on by 64 bits
+        w0 = w2; w1 = n0; w2 = n1;
+#if defined(__HIP_DEVICE_COMPILE__)
+        n0 = (uint32_t)__builtin_amdgcn_readlane((int)vnext, 0); n1 = (uint32_t)__builtin_amdgcn_readlane((int)vnext, 1);
+#else
+        n0 = p[0]; n1 = p[1];
+#endif
+        p += 2; g += 2; o -= 64; wbase += 64;
+        fetch_next();
     }
     PCR_HD uint32_t word_of(const DcTab* t, uint32_t win) const { const uint32_t e = t->lut[win >> 24]; return e != 0xFF ? pack_dc(e, win) : 0; }
     PCR_HD void fill() {
@@ -381,7 +427,7 @@ struct DcWindowReader {
     }
     PCR_HD bool exhausted() const { return o >= 64; }
     PCR_HD void refill() {
-        do { w0 = w2; w1 = n0; w2 = n1; n0 = p[0]; n1 = p[1]; p += 2; o -= 64; wbase += 64; } while (o >= 64);
+        do slide(); while (o >= 64);
         fill();
     }
     // packed word of the symbol at the current position (inside the window) for scan component J; where the bits
@@ -416,9 +462,9 @@ struct DcWindowReader {
 template <int J>
 PCR_HD void dc_first_block(DcWindowReader* wr, CoefSink* sink, int* pred, uint32_t e, uint32_t* bad) {
     if (wr->exhausted()) {
-        sink->flush();
         *bad |= wr->overrun_bit();                           // never walk far beyond the unit's data
-        wr->refill();
+        wr->refill();                                        // (before the flush: the wait for the words fetched a window ago must not include these stores)
+        sink->flush();
     }
     const uint32_t info = wr->peek<J>();
     *pred += (int32_t)info >> 16;
@@ -559,9 +605,9 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
     uint32_t bad = 0;
     while (left != 0) {
         if (wr->exhausted()) {
-            sink->flush();
             bad |= wr->overrun_bit();                        // never walk far beyond the unit's data
-            wr->refill();
+            wr->refill();                                    // (before the flush: the wait for the words fetched a window ago must not include these stores)
+            sink->flush();
         }
         uint32_t info;
         do {                                                 // symbols that start inside the current window

@@ -294,7 +294,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     actab_pack(&tab, true, threadIdx.x, kEntropyLanes);
     __syncthreads();
     WindowReader wr;
-    wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x);
+    wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x, true);
     CoefSink sink;
     sink.init(L.plane[0], L.plane_elems[0], L.ls.Al);
     int rc = decode_ac_first(&wr, L.ls, &sink);
@@ -333,7 +333,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     const size_t plane = (size_t)uni((uint32_t)img->bw[c]) * uni((uint32_t)img->bh[c]);
     uint64_t* mk = R.masks + uni((uint64_t)R.mask_off[ig]);
     WindowReader wr;
-    wr.init(L.words, L.byte_off, L.nbytes, &tab, false, threadIdx.x);
+    wr.init(L.words, L.byte_off, L.nbytes, &tab, false, threadIdx.x, false);
     int rc = skim_ac_refine(&wr, L.ls, hp, mk);
     if (rc != kOk) R.status[un.img] = rc;
 }
