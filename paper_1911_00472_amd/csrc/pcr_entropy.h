@@ -633,7 +633,7 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
                     bad |= ((info & 0x3F00) - 1u) >> 31;
                     adv = (1u << ((info & 127) - 65)) + (info >> 16);
                 } else {
-                    bad |= (kb > 64) ? ((info >> 15) & 1) : 0u;   // a coefficient beyond the band
+                    bad |= ((64u - kb) >> 31) & (info >> 15);   // a coefficient beyond the band (kb > 64)
                 }
                 adv = adv < left ? adv : left;
                 left = bad ? 0 : left - adv;                 // stop at the first damaged block
