@@ -416,7 +416,8 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     d.tab_idx = d_tab_idx;
     d.coef_off = d_coef_off; d.out_off = d_out_off; d.mask_off = d_mask_off; d.slot_base = d_sb; d.slot_cnt = d_sc;
     if (!rc && hipMemsetAsync(d.clean, 0xFF, padded, s) != hipSuccess) rc = PCR_E_DEVICE;
-    if (!rc && hipMemsetAsync(d.masks, 0, (nm ? nm : 1) * sizeof(uint64_t), s) != hipSuccess) rc = PCR_E_DEVICE;
+    // (the refinement records need no initial contents: every word a kernel reads was written earlier in the same
+    // call, or by the call an upgrade builds on; consumers skip blocks outside the scans' own grids)
     if (!rc && hipMemsetAsync(d.ivl_start, 0, (ns ? ns : 1) * sizeof(uint32_t), s) != hipSuccess) rc = PCR_E_DEVICE;
     return rc;
 }
