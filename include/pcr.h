@@ -168,6 +168,16 @@ typedef struct { int32_t x0, y0, w, h, flip; } pcr_crop;
 int pcr_crop_resize_batch(pcr_record* rec, const uint8_t* d_pixels, const pcr_crop* d_crops, int out_h, int out_w,
                           const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity, void* hip_stream);
 
+/* Decode and training tail in one call: pcr_decode_batch at scan_group followed by pcr_crop_resize_batch with the
+ * same boxes, except that the pixel kernel skips every strip of an image that does not touch the image's box --
+ * the tail reads nothing else.  d_pixels (device, layout of pcr_output_layout, pixel_capacity bytes) is working
+ * memory: afterwards it holds the decoded pixels of the strips that touch the boxes and whatever it held before
+ * elsewhere.  The half-precision output is bit-identical to the two calls made one after the other.  The planes
+ * left on the device are complete (pcr_upgrade_batch may follow).  Other arguments and errors as in the two calls. */
+int pcr_decode_crop_batch(pcr_record* rec, int scan_group, const pcr_crop* d_crops, uint8_t* d_pixels, size_t pixel_capacity,
+                          int out_h, int out_w, const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity,
+                          void* hip_stream, int32_t* d_status);
+
 /* ---- loader: host bytes -> device -> pixels, double-buffered (Section 5, "Loader") ----
  *
  * pcr_prefix_length: how much of a record must be read for fidelity k, from the record's first bytes alone

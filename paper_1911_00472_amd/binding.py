@@ -41,6 +41,8 @@ SYMBOLS = {
     "pcr_stage_ms_history": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]),
     "pcr_crop_resize_batch": (ctypes.c_int, [_vp, _vp, _vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
                                              ctypes.POINTER(ctypes.c_float), _vp, ctypes.c_size_t, _vp]),
+    "pcr_decode_crop_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
+                                             ctypes.POINTER(ctypes.c_float), _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_prefix_length": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_loader_create": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]),
     "pcr_loader_destroy": (None, [_vp]),
@@ -218,6 +220,24 @@ class Record:
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_crop_resize_batch(self._h, pixels.data_ptr(), crops.data_ptr(), out_h, out_w, m, sd, out.data_ptr(),
                                            out.numel() * 2, s), "pcr_crop_resize_batch")
+        return out
+
+    def decode_crop_batch(self, k, crops, out_h, out_w, mean, inv_std, pixels=None, out=None, status=None, stream=None):
+        """decode_batch(k) + crop_resize_batch in one call; the pixel kernel skips strips outside the boxes.
+        pixels: uint8 CUDA working buffer of output_layout()[n] bytes.  Returns the float16 tensor."""
+        import torch
+        assert crops.is_cuda and crops.dtype == torch.int32 and crops.is_contiguous() and tuple(crops.shape) == (self.n, 5)
+        C = self.image_info(0)[2]
+        if pixels is None:
+            pixels = torch.empty(int(self.output_layout()[-1]), dtype=torch.uint8, device="cuda:%d" % self.device)
+        if out is None:
+            out = torch.empty((self.n, C, out_h, out_w), dtype=torch.float16, device="cuda:%d" % self.device)
+        m = (ctypes.c_float * 3)(*([float(v) for v in mean] + [0.0] * 3)[:3])
+        sd = (ctypes.c_float * 3)(*([float(v) for v in inv_std] + [1.0] * 3)[:3])
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_decode_crop_batch(self._h, k, crops.data_ptr(), pixels.data_ptr(), pixels.numel(), out_h, out_w, m, sd,
+                                           out.data_ptr(), out.numel() * 2, s, status.data_ptr() if status is not None else None),
+               "pcr_decode_crop_batch")
         return out
 
     def resident_scan_group(self):

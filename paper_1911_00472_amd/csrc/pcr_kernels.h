@@ -574,9 +574,12 @@ PCR_HD uint32_t recip16(uint32_t d) { return d ? 65536u / d + 1u : 0u; }
 // refined values in memory).  lists / list_idx: the per-(image, component) scan lists of k_apply_prep and
 // their index by image * 3 + component (-1: nothing to refine); both null if no scan <= k refines.
 // kRefine = false compiles the replay out (scan groups without refinement scans: fewer registers).
+// boxes (optional): one box per image; strips that do not touch their image's box are skipped altogether (their
+// pixels are left as they are): for callers that go on to read only the boxes (pcr_decode_crop_batch).
 template <bool kRefine>
 __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out,
-                                               const ApplyList* __restrict__ lists, const int32_t* __restrict__ list_idx) {
+                                               const ApplyList* __restrict__ lists, const int32_t* __restrict__ list_idx,
+                                               const CropBox* __restrict__ boxes) {
     // samples of the strip, one row-major plane per component (so that neighbouring pixels are
     // neighbouring words of LDS in phase 4); rows are one word longer than the data, which
     // spreads the rows of a block over the banks for phase 2
@@ -607,6 +610,12 @@ __global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __r
     const uint32_t xe = x0 + sw < W ? x0 + sw : W;         // visible part of the strip
     const uint32_t rows = y0 + mcu_px_h < H ? mcu_px_h : H - y0;
     const uint32_t row_bytes = (xe - x0) * nc;
+    if (boxes) {                                            // (clamped into the image exactly as k_crop_resize clamps it)
+        CropBox b = boxes[t.img];
+        b.x0 = min(max(b.x0, 0), (int)W - 1); b.y0 = min(max(b.y0, 0), (int)H - 1);
+        b.w = min(max(b.w, 1), (int)W - b.x0); b.h = min(max(b.h, 1), (int)H - b.y0);
+        if ((int)x0 >= b.x0 + b.w || (int)xe <= b.x0 || (int)y0 >= b.y0 + b.h || (int)(y0 + rows) <= b.y0) return;
+    }
     const bool dead = R.status[t.img] != kOk;
     // per component (all wave-uniform): blocks per strip row, blocks in the strip, row stride and plane
     // offset in `tile`, reciprocal of the blocks per row, first block of the strip in the coefficient buffer

@@ -699,7 +699,7 @@ int pcr_decode_coefficients(pcr_record* r, int k, int16_t* d_coef, void* stream)
 }
 
 // k0 = 0: from scratch; k0 > 0: on top of the planes and masks a previous call left for scan group k0
-static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status) {
+static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status, const CropBox* boxes = nullptr) {
     if (cap < r->out_off[r->hdr.n]) return PCR_E_RANGE;
     HIP_TRY(hipSetDevice(r->device));
     hipStream_t s = (hipStream_t)stream;
@@ -708,9 +708,9 @@ static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t c
     int rc = run_entropy_stages(r, k0, k, s, false, &plan);
     if (rc) return rc;
     if (plan->n_apply)
-        hipLaunchKernelGGL(k_pixel<true>, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx);
+        hipLaunchKernelGGL(k_pixel<true>, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
     else
-        hipLaunchKernelGGL(k_pixel<false>, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr);
+        hipLaunchKernelGGL(k_pixel<false>, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
     mark(r, PCR_STAGE_PIXEL, s);
     call_end(r);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
@@ -759,6 +759,24 @@ int pcr_crop_resize_batch(pcr_record* r, const uint8_t* d_pixels, const pcr_crop
                        inv_std[0], C > 1 ? inv_std[1] : 1.f, C > 2 ? inv_std[2] : 1.f, reinterpret_cast<__half*>(d_out_f16));
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
     return PCR_OK;
+}
+
+int pcr_decode_crop_batch(pcr_record* r, int k, const pcr_crop* d_crops, uint8_t* d_pixels, size_t pixel_capacity, int out_h, int out_w,
+                          const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity, void* stream, int32_t* d_status) {
+    if (!r || !d_crops || !d_pixels || !mean || !inv_std) return PCR_E_ARG;
+    int rc = check_scan_group(r, k);
+    if (rc) return rc;
+    // argument checks of the tail before anything is enqueued (it repeats them)
+    if (out_h < 1 || out_w < 1 || out_h > 8192 || out_w > 8192) return PCR_E_RANGE;
+    if (!d_out_f16 || !r->d_dims) return PCR_E_ARG;
+    const uint32_t n = r->hdr.n;
+    const int C = r->img[0].nc;
+    for (uint32_t i = 1; i < n; i++) if (r->img[i].nc != C) return PCR_E_UNSUPPORTED;
+    if (n > 65535) return PCR_E_UNSUPPORTED;
+    if (out_capacity < (size_t)n * C * out_h * out_w * sizeof(__half)) return PCR_E_RANGE;
+    rc = decode_to_pixels(r, 0, k, d_pixels, pixel_capacity, stream, d_status, reinterpret_cast<const CropBox*>(d_crops));
+    if (rc) return rc;
+    return pcr_crop_resize_batch(r, d_pixels, d_crops, out_h, out_w, mean, inv_std, d_out_f16, out_capacity, stream);
 }
 
 int pcr_probe_scalar_issue_rate(int device_id, int waves_per_cu, double* ginst_per_s) {

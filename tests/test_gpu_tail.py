@@ -109,6 +109,42 @@ def test_decode_and_tail_end_to_end_headline_sample():
         assert (np.abs(got[i].astype(np.float64) - want) <= tol).all(), i
 
 
+def test_fused_decode_and_tail_equals_the_two_calls():
+    """pcr_decode_crop_batch: same half-precision output, bit for bit, as decode followed by the tail; strips outside
+    the boxes are not decoded (the working buffer keeps what it held there), strips that touch them are."""
+    torch = _torch()
+    records, _ = pcrgen.make_workload("imagenet_like", limit=48)
+    rec = records[0]
+    with pkg.pcr_open(rec, 0) as r:
+        shapes = [r.image_info(i)[:2] for i in range(r.n)]
+        boxes = _boxes(np.random.default_rng(23), shapes)
+        boxes[5] = (shapes[5][0] - 3, shapes[5][1] - 2, 3, 2, 1)                   # a tiny box in the last corner
+        tb = torch.from_numpy(boxes).cuda()
+        lay = r.output_layout()
+        for k in (1, 5, 10):
+            dec = r.decode_batch(k)
+            want = r.crop_resize_batch(dec, tb, 64, 48, MEAN, ISTD)
+            work = torch.full((int(lay[-1]),), 7, dtype=torch.uint8, device="cuda")
+            st = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
+            got = r.decode_crop_batch(k, tb, 64, 48, MEAN, ISTD, pixels=work, status=st)
+            torch.cuda.synchronize()
+            assert (st.cpu().numpy() == 0).all()
+            assert torch.equal(got, want), k
+            full, part = dec.cpu().numpy(), work.cpu().numpy()
+            untouched = 0
+            for i, (W, H) in enumerate(shapes):
+                a = full[int(lay[i]):int(lay[i + 1])].reshape(H, W, 3); b = part[int(lay[i]):int(lay[i + 1])].reshape(H, W, 3)
+                x0, y0, w, h, _ = boxes[i]
+                assert np.array_equal(a[y0:y0 + h, x0:x0 + w], b[y0:y0 + h, x0:x0 + w]), (i, k)   # the box itself is decoded
+                same = (a == b).all(axis=2)
+                assert ((b == 7).all(axis=2) | same).all()                          # everything else: decoded, or left alone
+                untouched += int((~same).sum())
+            assert untouched > 0                                                    # and something was skipped
+            # the planes are complete: an upgrade on top of the fused call gives the full picture
+            if k < 10:
+                assert torch.equal(r.upgrade_batch(10), r.decode_batch(10))
+
+
 def test_tail_argument_errors(gray64):
     torch = _torch()
     g = [pcrgen.make_jpeg(i, 0, 40, 24, 1, 8.0, 1, 1, 90) for i in range(2)]
