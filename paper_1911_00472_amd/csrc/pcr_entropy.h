@@ -129,6 +129,32 @@ PCR_HD void actab_build(AcTab* t, const uint8_t* bits_vals) {
 // bits [len, len+n) of a 32-bit window (n may be 0)
 PCR_HD uint32_t field(uint32_t win, int len, int n) { return n ? (win << len) >> (32 - n) : 0; }
 
+// Hides where a value came from, so that the compiler keeps it in the register it is in instead of
+// re-deriving it from other values it would then have to keep alive through a hot loop.
+PCR_HD uint32_t opaque(uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("" : "+s"(v));
+#endif
+    return v;
+}
+// Bits [pos, pos + width) of v with the field packed as (width << 16) | pos in a register (one instruction).
+PCR_HD uint32_t bit_field(uint32_t v, uint32_t packed) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint32_t r;
+    asm("s_bfe_u32 %0, %1, %2" : "=s"(r) : "s"(v), "s"(packed) : "scc");
+    return r;
+#else
+    return (v >> (packed & 31)) & ((1u << (packed >> 16)) - 1);
+#endif
+}
+// The code that follows starts on a 64-byte line of the instruction cache: a lone wavefront runs a short loop
+// visibly faster when the loop does not straddle lines (measured: 10 % on the AC first kernel).
+PCR_HD void align_hot_loop() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile(".p2align 6");
+#endif
+}
+
 // Resolve a code of more than 8 bits.  Returns (length << 8) | symbol, or 0 if it is no code.
 PCR_HD uint32_t ac_long_code(const AcTab* t, uint32_t win) {
     const uint32_t c16 = win >> 16;
@@ -197,10 +223,12 @@ PCR_HD uint32_t bits_at(uint32_t w0, uint32_t w1, uint32_t w2, int j) {      // 
 // block's zero table.  kSymSpecial marks the words the straight line of a decoder cannot finish by itself:
 //   kSymMiss   no code of <= 8 bits starts here (a longer code, or no code at all): length 0, advance 127;
 //   in a refinement scan, sixteen zeros: it lands on a zero WITHOUT taking it, so it is given the advance
-//   of an end of band (80) and redone by hand.
+//   of an end of band (80) and redone by hand;
+//   kSymInvalid  no code at all (or one that cannot occur in the scan): flags the stream as damaged.
 constexpr uint32_t kSymCoef = 0x8000u, kSymEob = 0x4000u, kSymSpecial = 0x80u;
 constexpr uint32_t kSymMiss = kSymSpecial | 127u;
-constexpr uint32_t kSymInvalid = kSymEob | 65u;              // "end of band" of length 0: what the AC decoders see where no code matches
+constexpr uint32_t kSymInvalid = kSymEob | kSymSpecial | 65u;   // what the AC decoders see where no code matches: an "end of band" of
+                                                             // length 0, marked special so that only the by-hand paths need to know it
 constexpr uint32_t kZrlAdvance = 16;
 
 PCR_HD uint32_t pack_symbol(uint32_t e, uint32_t win, bool first) {
@@ -603,6 +631,9 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
     uint32_t base_b = (row * bw + col) * 64 - bias - 1;
     uint32_t kb = Ss + bias;
     uint32_t bad = 0;
+    // (constants of the symbol loop kept in registers: as literals they would make the loop longer than one
+    // 64-byte line of the instruction cache)
+    const uint32_t adv_mask = opaque(127u), tot_field = opaque((6u << 16) | 8u);
     while (left != 0) {
         if (wr->exhausted()) {
             bad |= wr->overrun_bit();                        // never walk far beyond the unit's data
@@ -610,27 +641,28 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
             sink->flush();
         }
         uint32_t info;
+        align_hot_loop();
         do {                                                 // symbols that start inside the current window
             // One straight line for every symbol: a coefficient (run r, then the value) and sixteen zeros
             // (r = 15) both move on by r + 1; every packed word goes to the sink, which stores only those that
             // carry a coefficient.  An end of band and an unresolved code move "past everything".
             info = wr->lookup(wr->o);
-            kb += info & 127;
+            kb += info & adv_mask;
             sink->emit(wr->o, base_b + kb, (int)info);
-            wr->consume((info >> 8) & 63);
+            wr->consume(bit_field(info, tot_field));
         } while ((kb | wr->o) < 64);
         if (kb >= 64) {                                      // the block is finished, or the lanes left the code to us
             if (info & kSymSpecial) {                        // a code longer than 8 bits (or none): the same step by hand
                 kb -= kSymMiss & 127;
                 info = wr->resolve(wr->o);
+                if (info == kSymInvalid) bad |= 1u;          // no code at all
                 kb += info & 127;
                 sink->emit(wr->o, base_b + kb, (int)info);
                 wr->consume((info >> 8) & 63);
             }
             if (kb >= 64) {                                  // band complete, or end of band
                 uint32_t adv = 1;                            // blocks to move on by
-                if (info & kSymEob) {                        // run of 2^r + extra blocks; no code at all has length 0
-                    bad |= ((info & 0x3F00) - 1u) >> 31;
+                if (info & kSymEob) {                        // run of 2^r + extra blocks
                     adv = (1u << ((info & 127) - 65)) + (info >> 16);
                 } else {
                     bad |= ((64u - kb) >> 31) & (info >> 15);   // a coefficient beyond the band (kb > 64)
@@ -775,8 +807,8 @@ struct ZeroTable {
         return entry[n];
 #endif
     }
-    // taken: bit n set = a symbol carrying a new coefficient landed on entry n (n < number of zeros <= 63, so
-    // bit 63 is clear: positions that are no zeros point there).  Returns those positions.
+    // taken: bit n set = a symbol landed on entry n.  Returns the positions of those entries; positions that are
+    // no zeros all point at entry 63 and must be masked off by the caller.
     PCR_HD uint64_t positions_of(uint64_t taken) const {
 #if defined(__HIP_DEVICE_COMPILE__)
         return __ballot(((taken >> vindex) & 1) != 0);
@@ -788,14 +820,6 @@ struct ZeroTable {
     }
 };
 
-// Hides where a value came from, so that the compiler keeps it in the register it is in instead of
-// re-deriving it from other values it would then have to keep alive through a hot loop.
-PCR_HD uint32_t opaque(uint32_t v) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm("" : "+s"(v));
-#endif
-    return v;
-}
 // All LDS and scalar-memory results this wavefront is waiting for have arrived: stated once ahead of a
 // hot loop, the wait is not repeated inside it.
 PCR_HD void settle_lds() {
@@ -824,33 +848,35 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     const uint64_t band = band_mask(ls.Ss, ls.Se);
     const uint32_t top64 = wr->lane == (uint32_t)ls.Se ? kZtLast : 0u;
+    const uint32_t adv_mask = opaque(127u), tot_field = opaque((6u << 16) | 8u);   // (in registers: see decode_ac_first)
     uint32_t left = ls.mcu1 - ls.mcu0;                       // blocks still to do
-    uint32_t col = ls.mcu0 % mcu_w;
-    uint32_t blk = (ls.mcu0 / mcu_w) * bw + col;
     const uint32_t row_skip = bw - mcu_w;                    // blocks of the padded grid between two rows of the scan
     const uint32_t last_blk = ((ls.mcu1 - 1) / mcu_w) * bw + (ls.mcu1 - 1) % mcu_w;
     uint32_t eobrun = 0;                                     // blocks still covered by an end-of-band run
     uint32_t bad = 0;
     // The history of a block is fetched two blocks ahead (a block of a dozen symbols is shorter than a trip to
-    // memory): h0 belongs to the current block, h1 to the next one, and the fetch cursor (fblk, fcol) runs two
-    // ahead, stopping at the unit's last block.
-    uint32_t fblk = blk, fcol = col;
-    HistWords h0 = hist_fetch(hp, fblk, wr->lane);
+    // memory).  One cursor (fblk, fcol) walks the unit's blocks for the fetches, stopping at the last one; b0 / b1
+    // remember which block the words under way in h0 / h1 belong to: the block each body works on next.
+    uint32_t fcol = ls.mcu0 % mcu_w;
+    uint32_t fblk = (ls.mcu0 / mcu_w) * bw + fcol;
+    uint32_t b0 = fblk;
+    HistWords h0 = hist_fetch(hp, b0, wr->lane);
     fblk++; if (++fcol == mcu_w) { fcol = 0; fblk += row_skip; }
-    HistWords h1 = hist_fetch(hp, fblk < last_blk ? fblk : last_blk, wr->lane);
+    uint32_t b1 = fblk < last_blk ? fblk : last_blk;
+    HistWords h1 = hist_fetch(hp, b1, wr->lane);
     ZeroTable zt;
-    // One block.  hw: the block's history on entry; on return the fetch for the block two further on is under way in it.
-    // (Two copies of this body alternate below, each with its own history registers: handing the words from one
-    // variable to the next would mean waiting for the fetch that is still in flight.)
-    auto one_block = [&](HistWords& hw) {
+    // One block.  hw, bcur: the block's history and index on entry; on return the fetch for the block two further on
+    // is under way in hw and bcur is that block.  (Two copies of this body alternate below, each with its own
+    // history registers: handing the words from one variable to the next would mean waiting for the fetch that is
+    // still in flight.)
+    auto one_block = [&](HistWords& hw, uint32_t& bcur) {
         const uint64_t h = hist_combine(hw) & band;           // already non-zero
         const uint64_t z = h ^ band;                         // still zero
-        uint64_t* rec = recs + (size_t)blk * kRefWords;
-        blk++;
-        if (++col == mcu_w) { col = 0; blk += row_skip; }
+        uint64_t* rec = recs + (size_t)bcur * kRefWords;
         left--;
         fblk++; if (++fcol == mcu_w) { fcol = 0; fblk += row_skip; }
-        hw = hist_fetch(hp, fblk < last_blk ? fblk : last_blk, wr->lane);
+        bcur = fblk < last_blk ? fblk : last_blk;
+        hw = hist_fetch(hp, bcur, wr->lane);
         const uint64_t start = ((uint64_t)eobrun << 32) | wr->position();
         const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
         uint64_t newm = 0;
@@ -870,11 +896,11 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
                     // "all corrections, nothing left".  Unresolved codes and sixteen-zero symbols behave like an
                     // end of band here and are redone below.
                     info = wr->lookup(wr->o);
-                    t = at + (info & 127);                   // run + 1, or 65 + run for an end of band
+                    t = at + (info & adv_mask);              // run + 1, or 65 + run for an end of band
                     at = t < nzeros ? t : nzeros;            // past the last zero: the sentinel
                     e = zt.at(at);
                     set_bit(&taken, at);
-                    ob += (info >> 8) & 63;                  // code and sign
+                    ob += bit_field(info, tot_field);        // code and sign
                     wr->o = ob + e;                          // ... the corrections passed so far, and 64 more after the block's last entry
                 } while (wr->o < 64);
                 if (e < kZtLast) continue;                   // the window ran out inside the block
@@ -887,6 +913,7 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
                     info = wr->resolve(ob + passed);         // (a miss has length 0: ob is still the symbol's)
                     ob += (info >> 8) & 63;
                 }
+                if (info == kSymInvalid) { bad |= 1u; wr->o = ob; break; }   // no code at all, or one a refinement scan cannot hold
                 const uint32_t zrl = info & kSymSpecial;     // sixteen zeros: lands on a zero and leaves it zero
                 t = prev + (zrl ? kZrlAdvance : (info & 127));
                 at = t < nzeros ? t : nzeros;
@@ -896,11 +923,10 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
                 if (e >= kZtLast) break;
             }
             if (info & kSymEob) {                            // the block ended with an end-of-band (run) symbol
-                bad |= ((info & 0x3F00) - 1u) >> 31;            // length 0: no code at all
                 eobrun = (1u << ((info & 127) - 65)) + (info >> 16);
             }
             bad |= (info >> 15) & ((nzeros - 1 - at) >> 31);  // a new coefficient with no zero left to take (it landed on the sentinel)
-            newm = zt.positions_of(taken & ((1ull << nzeros) - 1));
+            newm = zt.positions_of(taken) & z;                 // (& z: lanes that are no zeros share index 63, which the sentinel can be)
             eobrun -= eobrun ? 1u : 0u;                      // the run counted this block
         } else {
             wr->consume(ncorr);
@@ -911,9 +937,9 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
         left = bad ? 0 : left;                               // stop at the first damaged block
     };
     while (left != 0) {
-        one_block(h0);
+        one_block(h0, b0);
         if (left == 0) break;
-        one_block(h1);
+        one_block(h1, b1);
     }
     return bad ? kEFormat : kOk;
 }
