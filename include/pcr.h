@@ -192,6 +192,7 @@ int pcr_decode_crop_batch(pcr_record* rec, int scan_group, const pcr_crop* d_cro
  *                      for the slot's earlier work, and returns when the record's metadata is known: *rec
  *                      (optional) is the slot's handle for layout queries, valid until the slot's next upload.
  *   pcr_loader_decode  = pcr_decode_batch on the slot's handle and stream (asynchronous).
+ *   pcr_loader_decode_crop  = pcr_decode_crop_batch there: from the bytes read to half-precision training tensors.
  *   pcr_loader_wait    blocks until the slot's stream is idle; the staging buffer may be refilled after
  *                      pcr_loader_upload has returned.
  * While one slot's decode runs, another slot's upload and parse proceed on their own stream.  Streams have
@@ -211,6 +212,9 @@ int pcr_loader_stream(pcr_loader* ld, int slot, void** hip_stream);
 int pcr_loader_set_rate(pcr_loader* ld, double bytes_per_second, double burst_bytes);
 int pcr_loader_upload(pcr_loader* ld, int slot, size_t nbytes, pcr_record** rec);
 int pcr_loader_decode(pcr_loader* ld, int slot, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity, int32_t* d_status);
+int pcr_loader_decode_crop(pcr_loader* ld, int slot, int scan_group, const pcr_crop* d_crops, uint8_t* d_pixels, size_t pixel_capacity,
+                           int out_h, int out_w, const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity,
+                           int32_t* d_status);
 int pcr_loader_wait(pcr_loader* ld, int slot);
 
 /* Stage timing with HIP events recorded on the call's own stream (off by default; switching it on

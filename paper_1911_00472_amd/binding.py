@@ -51,6 +51,8 @@ SYMBOLS = {
     "pcr_loader_set_rate": (ctypes.c_int, [_vp, ctypes.c_double, ctypes.c_double]),
     "pcr_loader_upload": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]),
     "pcr_loader_decode": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
+    "pcr_loader_decode_crop": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, _vp, _vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                              ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float), _vp, ctypes.c_size_t, _vp]),
     "pcr_loader_wait": (ctypes.c_int, [_vp, ctypes.c_int]),
     "pcr_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
@@ -330,6 +332,15 @@ class Loader:
     def decode(self, slot, k, out, status=None):
         _check(lib().pcr_loader_decode(self._h, slot, k, out.data_ptr(), out.numel(), status.data_ptr() if status is not None else None),
                "pcr_loader_decode")
+        return out
+
+    def decode_crop(self, slot, k, crops, out_h, out_w, mean, inv_std, pixels, out, status=None):
+        """decode_crop_batch on the slot's handle and stream: pixels is the uint8 working buffer, out the float16 result."""
+        m = (ctypes.c_float * 3)(*([float(v) for v in mean] + [0.0] * 3)[:3])
+        sd = (ctypes.c_float * 3)(*([float(v) for v in inv_std] + [1.0] * 3)[:3])
+        _check(lib().pcr_loader_decode_crop(self._h, slot, k, crops.data_ptr(), pixels.data_ptr(), pixels.numel(), out_h, out_w, m, sd,
+                                            out.data_ptr(), out.numel() * 2, status.data_ptr() if status is not None else None),
+               "pcr_loader_decode_crop")
         return out
 
     def wait(self, slot):

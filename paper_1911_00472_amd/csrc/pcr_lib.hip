@@ -927,6 +927,14 @@ int pcr_loader_decode(pcr_loader* ld, int slot, int k, uint8_t* out, size_t cap,
     return pcr_decode_batch(sl->rec, k, out, cap, (void*)sl->stream, d_status);
 }
 
+int pcr_loader_decode_crop(pcr_loader* ld, int slot, int k, const pcr_crop* d_crops, uint8_t* d_pixels, size_t pixel_capacity, int out_h, int out_w,
+                           const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity, int32_t* d_status) {
+    pcr_loader_slot* sl = loader_slot(ld, slot);
+    if (!sl || !sl->rec) return PCR_E_ARG;
+    return pcr_decode_crop_batch(sl->rec, k, d_crops, d_pixels, pixel_capacity, out_h, out_w, mean, inv_std, d_out_f16, out_capacity,
+                                 (void*)sl->stream, d_status);
+}
+
 int pcr_loader_wait(pcr_loader* ld, int slot) {
     pcr_loader_slot* sl = loader_slot(ld, slot);
     if (!sl) return PCR_E_ARG;

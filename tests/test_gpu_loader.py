@@ -134,6 +134,33 @@ def test_loader_double_buffered_prefix_uploads():
             assert np.abs(got - p0).max() <= 1
 
 
+def test_loader_to_training_tensors():
+    """Staging buffer -> upload -> decode + crop / resize / normalise in one call, against the same steps on a fresh handle."""
+    torch = _torch()
+    _, files = pcrgen.make_workload("imagenet_like", limit=24)
+    rec = pcrgen.write_record(files)
+    mean, istd = (0.485, 0.456, 0.406), (1 / 0.229, 1 / 0.224, 1 / 0.225)
+    rng = np.random.default_rng(3)
+    with pkg.pcr_open(rec, 0) as r:
+        boxes = np.array([(int(rng.integers(0, 100)), int(rng.integers(0, 100)), int(rng.integers(50, 200)), int(rng.integers(50, 200)), i % 2)
+                          for i in range(r.n)], np.int32)
+        tb = torch.from_numpy(boxes).cuda()
+        want = r.crop_resize_batch(r.decode_batch(5), tb, 96, 96, mean, istd)
+        total = int(r.output_layout()[-1])
+    with pkg.Loader(2, len(rec)) as ld:
+        for slot in (0, 1, 0):
+            ok, need = pkg.prefix_length(rec[:24 + 80], 5)
+            ld.staging(slot)[:need] = np.frombuffer(rec, np.uint8)[:need]
+            h = ld.upload(slot, need)
+            work = torch.zeros(total, dtype=torch.uint8, device="cuda")
+            out = torch.empty((h.n, 3, 96, 96), dtype=torch.float16, device="cuda")
+            st = torch.full((h.n,), 5, dtype=torch.int32, device="cuda")
+            ld.decode_crop(slot, 5, tb, 96, 96, mean, istd, work, out, status=st)
+            ld.wait(slot)
+            assert (st.cpu().numpy() == 0).all()
+            assert torch.equal(out, want)
+
+
 def test_loader_rate_limit_and_errors():
     torch = _torch()
     gray, _ = pcrgen.make_workload("gray64")
