@@ -629,7 +629,6 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
     uint32_t left = ls.mcu1 - ls.mcu0;                       // blocks of the unit not finished yet (the current one included)
     uint32_t row = ls.mcu0 / mcu_w, col = ls.mcu0 % mcu_w;
     uint32_t base_b = (row * bw + col) * 64 - bias - 1;
-    const uint32_t row_skip64 = (bw - mcu_w) * 64;           // from the last block of a row of the scan to the first of the next
     uint32_t kb = Ss + bias;
     uint32_t bad = 0;
     // (constants of the symbol loop kept in registers: as literals they would make the loop longer than one
@@ -662,21 +661,17 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
                 wr->consume((info >> 8) & 63);
             }
             if (kb >= 64) {                                  // band complete, or end of band
-                bad |= ((64u - kb) >> 31) & (info >> 15);    // a coefficient beyond the band (kb > 64; an end of band carries none)
-                // An end of band covers 2^r + extra blocks, this one included (advance field 65 + r).  One compare tells
-                // "band complete, or end of band with r = 0" -- on to the next block, the usual case, kept short -- from a run.
-                if (__builtin_expect((info & (kSymEob | 127u)) <= (kSymEob | 65u), 1)) {
-                    left--; col++; base_b += 64;
-                    if (col == mcu_w) { col = 0; row++; base_b += row_skip64; }
+                uint32_t adv = 1;                            // blocks to move on by
+                if (info & kSymEob) {                        // run of 2^r + extra blocks
+                    adv = (1u << ((info & 127) - 65)) + (info >> 16);
                 } else {
-                    uint32_t adv = (1u << ((info & 127) - 65)) + (info >> 16);
-                    adv = adv < left ? adv : left;
-                    left -= adv; col += adv;
-                    while (col >= mcu_w) { col -= mcu_w; row++; }
-                    base_b = (row * bw + col) * 64 - bias - 1;
+                    bad |= ((64u - kb) >> 31) & (info >> 15);   // a coefficient beyond the band (kb > 64)
                 }
-                left = bad ? 0 : left;                       // stop at the first damaged block
-                kb = Ss + bias;
+                adv = adv < left ? adv : left;
+                left = bad ? 0 : left - adv;                 // stop at the first damaged block
+                col += adv; kb = Ss + bias;
+                while (col >= mcu_w) { col -= mcu_w; row++; }
+                base_b = (row * bw + col) * 64 - bias - 1;
             }
         }
     }
