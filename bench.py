@@ -395,6 +395,19 @@ def main():
     # what the chip sustains on chains of dependent scalar instructions (the library's own probe kernel), best of
     # 8, 16 and 32 wavefronts per CU: the practical ceiling next to the nominal one
     probe = max(pkg.probe_scalar_issue_rate(w) for w in (8, 16, 32))
+    # what a plain device-to-device copy reaches on this machine (the second denominator for the HBM figures)
+    ca = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cb = torch.empty_like(ca)
+    cb.copy_(ca)
+    torch.cuda.synchronize()
+    ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ce0.record()
+    for _ in range(5):
+        cb.copy_(ca)
+    ce1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * ca.numel() / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
+    del ca, cb
     roofline = dominant_kernel_roofline(args, ends[:n0], per_launch(alone), per_launch(over), alone, n_img, probe)
 
     cpu = None
@@ -422,7 +435,8 @@ def main():
         "output_GBps": ab["out"] / sec / 1e9,
         "open_ms_per_record": open_ms,
         "path_roofline": {"bound": "hbm", "achieved": ab["path"] / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                          "frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS},
+                          "frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS, "device_copy_GBps_measured": copy_gbps,
+                          "frac_of_measured_copy": ab["path"] / sec / 1e9 / copy_gbps},
         "path_issue": ({"scalar_insts_per_step": RECORD0_INSTS["scalar"] * len(records), "vector_insts_per_step": RECORD0_INSTS["vector"] * len(records),
                         "G_scalar_insts_per_s": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9,
                         "frac_of_peak": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9 / SALU_PEAK_GINSTS,
