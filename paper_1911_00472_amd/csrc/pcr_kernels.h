@@ -104,7 +104,7 @@ constexpr int kUnstuffPer = 8;
 // grid: (images, scan groups kfrom .. kmax-1)
 __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kfrom, uint32_t kmax) {
     short_kernel_priority();
-    __shared__ uint32_t part[256];
+    __shared__ uint32_t part[4];
     __shared__ uint32_t s_stop;
     uint32_t i = blockIdx.x, g = kfrom + blockIdx.y;
     if (g >= kmax) return;
@@ -150,22 +150,27 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kfrom, ui
         if (stop_all != 0xFFFFFFFFu) {
             for (int j = 0; j < kUnstuffPer; j++) if (p0 + j >= stop_all) { keep &= ~(1u << j); rst &= ~(1u << j); }
         }
-        uint32_t mine = (uint32_t)__builtin_popcount(keep) | ((uint32_t)__builtin_popcount(rst) << 16);
-        part[threadIdx.x] = mine;
-        __syncthreads();
-        for (uint32_t d = 1; d < 256; d <<= 1) {
-            uint32_t t = threadIdx.x >= d ? part[threadIdx.x - d] : 0;
-            __syncthreads();
-            part[threadIdx.x] += t;
-            __syncthreads();
+        // prefix sums of (bytes kept | restart markers << 16) over the 256 lanes: inside each wavefront by lane
+        // shuffles, then the four wavefront totals through LDS
+        const uint32_t mine = (uint32_t)__builtin_popcount(keep) | ((uint32_t)__builtin_popcount(rst) << 16);
+        const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        uint32_t incl = mine;
+#pragma unroll
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint32_t t = (uint32_t)__shfl_up((int)incl, d, 64);
+            if (lane >= d) incl += t;
         }
-        uint32_t excl = part[threadIdx.x] - mine;
+        if (lane == 63) part[wave] = incl;
+        __syncthreads();
+        const uint32_t w0 = part[0], w1 = part[1], w2 = part[2], w3 = part[3];
+        const uint32_t before = (wave > 0 ? w0 : 0) + (wave > 1 ? w1 : 0) + (wave > 2 ? w2 : 0);
+        const uint32_t excl = before + incl - mine;
         uint32_t o = out_total + (excl & 0xFFFF), r = rst_total + (excl >> 16);
         for (int j = 0; j < kUnstuffPer; j++) {
             if (keep & (1u << j)) { dst[o ^ 3u] = b[j + 1]; o++; }
             if (rst & (1u << j)) { r++; if (r < sc) R.ivl_start[sb + r] = o; }
         }
-        uint32_t tot = part[255];
+        const uint32_t tot = w0 + w1 + w2 + w3;
         out_total += tot & 0xFFFF; rst_total += tot >> 16;
         __syncthreads();
         if (stop_all != 0xFFFFFFFFu) break;
