@@ -198,3 +198,70 @@ def crop_resize_normalize(pix, box, flip, out_h, out_w, mean, inv_std):
             for c in range(C):
                 out[c, oy, ox] = (v[c] / 255.0 - mean[c]) * inv_std[c]
     return out
+
+
+# ---- image similarity (paper Section 6.4: MSSIM between a scan group's picture and the full one) ----
+MSSSIM_WEIGHTS = (0.0448, 0.2856, 0.3001, 0.2363, 0.1333)
+
+
+def luma(pix):
+    """float64 [H, W]: 0.299 R + 0.587 G + 0.114 B of uint8 [H, W, 3] (or the single channel), not rounded."""
+    p = pix.astype(np.float64)
+    return p[:, :, 0] if p.shape[2] == 1 else 0.299 * p[:, :, 0] + 0.587 * p[:, :, 1] + 0.114 * p[:, :, 2]
+
+
+def _gauss11():
+    x = np.arange(-5, 6, dtype=np.float64)
+    g = np.exp(-x * x / (2 * 1.5 * 1.5))
+    return g / g.sum()
+
+
+def ssim_maps(a, b):
+    """The luminance and contrast-structure terms of SSIM at every position where the 11 x 11 Gaussian window
+    (sigma 1.5, weights summing to 1) fits: float64 [H-10, W-10] each.  Constants for 8-bit data: C1 = (0.01*255)^2,
+    C2 = (0.03*255)^2."""
+    from numpy.lib.stride_tricks import sliding_window_view
+    g = _gauss11()
+    w2 = np.outer(g, g)
+    C1, C2 = (0.01 * 255) ** 2, (0.03 * 255) ** 2
+
+    def blur(x):
+        return np.einsum("ijkl,kl->ij", sliding_window_view(x, (11, 11)), w2)
+
+    mu_a, mu_b = blur(a), blur(b)
+    va = blur(a * a) - mu_a * mu_a
+    vb = blur(b * b) - mu_b * mu_b
+    cab = blur(a * b) - mu_a * mu_b
+    lum = (2 * mu_a * mu_b + C1) / (mu_a * mu_a + mu_b * mu_b + C1)
+    cs = (2 * cab + C2) / (va + vb + C2)
+    return lum, cs
+
+
+def halve(x):
+    """2 x 2 averages; an odd last row or column is dropped."""
+    H, W = x.shape[0] // 2 * 2, x.shape[1] // 2 * 2
+    return x[:H, :W].reshape(H // 2, 2, W // 2, 2).mean(axis=(1, 3))
+
+
+def msssim(pix_a, pix_b):
+    """Multi-scale structural similarity (Wang, Simoncelli and Bovik 2003) of two uint8 pictures of one size, on
+    luma: the contrast-structure term averaged at scales 1 .. M-1, luminance x contrast-structure at scale M,
+    combined as a product of powers with the published exponents; successive scales by 2 x 2 averaging.
+    Readings where the method's paper leaves a choice: M = 5, or as many scales as keep the smaller side at
+    least 11 samples (the exponents of the scales used are rescaled to sum to 1); a negative scale mean counts
+    as 0 (a power of it would not be real)."""
+    a, b = luma(pix_a), luma(pix_b)
+    assert a.shape == b.shape
+    M = 1
+    while M < 5 and min(a.shape) // (1 << M) >= 11:
+        M += 1
+    assert min(a.shape) >= 11
+    w = np.array(MSSSIM_WEIGHTS[:M]) / sum(MSSSIM_WEIGHTS[:M])
+    out = 1.0
+    for j in range(M):
+        lum, cs = ssim_maps(a, b)
+        term = (lum * cs).mean() if j == M - 1 else cs.mean()
+        out *= max(term, 0.0) ** w[j]
+        if j < M - 1:
+            a, b = halve(a), halve(b)
+    return float(out)
