@@ -168,6 +168,22 @@ typedef struct { int32_t x0, y0, w, h, flip; } pcr_crop;
 int pcr_crop_resize_batch(pcr_record* rec, const uint8_t* d_pixels, const pcr_crop* d_crops, int out_h, int out_w,
                           const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity, void* hip_stream);
 
+/* Fidelity estimate (Section 6.4: MSSIM between the picture of a scan group and the full picture tracks the
+ * accuracy a model reaches on that scan group, which is what Section 4.3's choice of scan group rests on).  For
+ * every image of the record, the multi-scale structural similarity (Wang, Simoncelli and Bovik 2003) of its
+ * pictures in two decoded batches, computed on luma (0.299 R + 0.587 G + 0.114 B, not rounded): 11 x 11
+ * Gaussian window of sigma 1.5 at the positions where it fits, C1 = (0.01*255)^2, C2 = (0.03*255)^2, five scales
+ * by 2 x 2 averaging with the published exponents 0.0448, 0.2856, 0.3001, 0.2363, 0.1333.  An image whose
+ * smaller side is below 176 uses as many scales as keep that side at 11 samples or more, their exponents
+ * rescaled to sum to 1; a negative scale mean counts as 0; an image smaller than 11 on a side scores NaN.
+ *   d_a, d_b   device: two pixel batches in the layout of pcr_output_layout (say scan group k and scan group G)
+ *   d_scores   device: n floats
+ * Computed in single precision from exact integer block sums; agrees with a double-precision evaluation to
+ * about 1e-4.  The first call on a handle allocates n x (tiles per image) x 8 bytes of working memory (which
+ * pcr_rebind_device releases).  Asynchronous on hip_stream; calls on one handle must not overlap.
+ * Errors: PCR_E_ARG (null argument), PCR_E_UNSUPPORTED (channel counts differ between images), PCR_E_NOMEM. */
+int pcr_msssim_batch(pcr_record* rec, const uint8_t* d_a, const uint8_t* d_b, float* d_scores, void* hip_stream);
+
 /* Decode and training tail in one call: pcr_decode_batch at scan_group followed by pcr_crop_resize_batch with the
  * same boxes, except that the pixel kernel skips every strip of an image that does not touch the image's box --
  * the tail reads nothing else.  d_pixels (device, layout of pcr_output_layout, pixel_capacity bytes) is working

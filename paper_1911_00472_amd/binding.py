@@ -43,6 +43,7 @@ SYMBOLS = {
                                              ctypes.POINTER(ctypes.c_float), _vp, ctypes.c_size_t, _vp]),
     "pcr_decode_crop_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
                                              ctypes.POINTER(ctypes.c_float), _vp, ctypes.c_size_t, _vp, _vp]),
+    "pcr_msssim_batch": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp]),
     "pcr_prefix_length": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_loader_create": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]),
     "pcr_loader_destroy": (None, [_vp]),
@@ -222,6 +223,19 @@ class Record:
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_crop_resize_batch(self._h, pixels.data_ptr(), crops.data_ptr(), out_h, out_w, m, sd, out.data_ptr(),
                                            out.numel() * 2, s), "pcr_crop_resize_batch")
+        return out
+
+    def msssim_batch(self, a, b, out=None, stream=None):
+        """Multi-scale structural similarity of every image's pictures in two decoded batches (uint8 CUDA tensors
+        in output_layout()).  Returns a float32 CUDA tensor [n] (asynchronous on the stream)."""
+        import torch
+        total = int(self.output_layout()[-1])
+        for t in (a, b):
+            assert t.is_cuda and t.dtype == torch.uint8 and t.is_contiguous() and t.numel() >= total
+        if out is None:
+            out = torch.empty(self.n, dtype=torch.float32, device="cuda:%d" % self.device)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_msssim_batch(self._h, a.data_ptr(), b.data_ptr(), out.data_ptr(), s), "pcr_msssim_batch")
         return out
 
     def decode_crop_batch(self, k, crops, out_h, out_w, mean, inv_std, pixels=None, out=None, status=None, stream=None):

@@ -14,6 +14,7 @@
 
 #include "../../include/pcr.h"
 #include "pcr_kernels.h"
+#include "pcr_similarity.h"
 
 using namespace pcr;
 
@@ -107,6 +108,8 @@ struct pcr_record {
     uint8_t* d_rec = nullptr;
     PixelTile* d_tiles = nullptr; uint32_t n_tiles = 0;
     uint32_t* d_dims = nullptr;             // [n][2] width, height (for kernels that run without a decode before them)
+    float2* d_ssim_part = nullptr;          // per-tile sums of the similarity kernels (allocated at their first call)
+    uint32_t ssim_tiles_max = 0;
     uint8_t* d_gather = nullptr; size_t gather_cap = 0;
     std::map<int, Plan> plans;
     bool timing = false;
@@ -487,7 +490,7 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
 static int bind_device(pcr_record* r, const void* d_bytes, size_t nbytes, hipStream_t s) {
     r->plans.clear(); r->resident_k = 0; r->hdr = RecordHeader{}; r->n_tiles = 0;
     r->out_off.assign(1, 0); r->coef_off.assign(1, 0);        // until the bind succeeds the handle holds no record
-    r->d_dims = nullptr;
+    r->d_dims = nullptr; r->d_ssim_part = nullptr; r->ssim_tiles_max = 0;
     // fixed part of the header, then the whole metadata block
     uint8_t fixed[24];
     HIP_TRY(hipMemcpyAsync(fixed, d_bytes, 24, hipMemcpyDeviceToHost, s));
@@ -777,6 +780,29 @@ int pcr_decode_crop_batch(pcr_record* r, int k, const pcr_crop* d_crops, uint8_t
     rc = decode_to_pixels(r, 0, k, d_pixels, pixel_capacity, stream, d_status, reinterpret_cast<const CropBox*>(d_crops));
     if (rc) return rc;
     return pcr_crop_resize_batch(r, d_pixels, d_crops, out_h, out_w, mean, inv_std, d_out_f16, out_capacity, stream);
+}
+
+int pcr_msssim_batch(pcr_record* r, const uint8_t* d_a, const uint8_t* d_b, float* d_scores, void* stream) {
+    if (!r || !d_a || !d_b || !d_scores) return PCR_E_ARG;
+    const uint32_t n = r->hdr.n;
+    if (n == 0 || !r->d_dims) return PCR_E_ARG;
+    const int C = r->img[0].nc;
+    if (C != 1 && C != 3) return PCR_E_UNSUPPORTED;
+    for (uint32_t i = 1; i < n; i++) if (r->img[i].nc != C) return PCR_E_UNSUPPORTED;
+    if (n > 65535) return PCR_E_UNSUPPORTED;                  // (images are the grid's second dimension)
+    HIP_TRY(hipSetDevice(r->device));
+    if (!r->d_ssim_part) {
+        uint32_t tmax = 1;
+        for (uint32_t i = 0; i < n; i++) tmax = std::max(tmax, ssim_tiles_all((uint32_t)r->img[i].W, (uint32_t)r->img[i].H));
+        int rc = arena_alloc(&r->big, &r->d_ssim_part, (size_t)n * tmax);
+        if (rc) return rc;
+        r->ssim_tiles_max = tmax;
+    }
+    hipLaunchKernelGGL(k_ssim_tiles, dim3(r->ssim_tiles_max, n), dim3(256), 0, (hipStream_t)stream, r->d_dims, r->d.out_off, C, d_a, d_b,
+                       r->d_ssim_part, r->ssim_tiles_max);
+    hipLaunchKernelGGL(k_ssim_score, dim3(n), dim3(64), 0, (hipStream_t)stream, r->d_dims, r->d_ssim_part, r->ssim_tiles_max, d_scores);
+    if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
+    return PCR_OK;
 }
 
 int pcr_probe_scalar_issue_rate(int device_id, int waves_per_cu, double* ginst_per_s) {

@@ -1,0 +1,126 @@
+"""GPU parity of pcr_msssim_batch against the float64 oracle (the fidelity estimate of the paper's Section 6.4).
+
+Tolerance, written out: both sides take the same uint8 pixels.  The kernel's samples are exact integer block sums
+turned into fp32 luma (relative error 2e-7), centred on 128; the five window sums are 22-term fp32 dot products
+(relative error about 2e-6 of sums up to 128^2, so about 0.03 absolute in a variance, against C2 = 58.5 in every
+denominator: under 1e-3 per position in the worst case, random in sign and averaged over the positions); the
+scale means and the powers are taken in double.  Bound used: |gpu - oracle| <= 3e-4 on the final score."""
+import numpy as np
+import pytest
+
+import oracle
+import pcrgen
+import paper_1911_00472_amd as pkg
+
+pytestmark = pytest.mark.gpu
+TOL = 3e-4
+
+SIZES = [(30, 10), (11, 11), (40, 12), (22, 23), (90, 45), (100, 88), (176, 180), (351, 177), (300, 260), (175, 400)]
+
+
+def _torch():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def _record(C):
+    files = [pcrgen.make_jpeg(900 + i, 1 + (i % 2), w, h, C, 6.0, 2 if C == 3 else 1, 2 if C == 3 else 1, 90) for i, (w, h) in enumerate(SIZES)]
+    return pcrgen.write_record(files, labels=list(range(len(files))))
+
+
+def _pixels(rec, k):
+    return [t[1] for t in oracle.decode_record(rec, k, threads=8, want_coef=False)]
+
+
+def _flat(torch, pix_list, total):
+    buf = np.zeros(total, np.uint8)
+    o = 0
+    for p in pix_list:
+        buf[o:o + p.size] = p.reshape(-1); o += p.size
+    return torch.from_numpy(buf).cuda()
+
+
+def _check(got, pa, pb):
+    for i, (a, b) in enumerate(zip(pa, pb)):
+        if min(a.shape[:2]) < 11:
+            assert np.isnan(got[i]), (i, got[i])
+            continue
+        want = oracle.msssim(a, b)
+        assert abs(float(got[i]) - want) <= TOL, (i, a.shape, float(got[i]), want)
+
+
+@pytest.mark.parametrize("C", [3, 1])
+def test_scan_group_against_full_picture_on_the_oracles_pixels(C):
+    """Every scale count from none to five, odd sizes, colour and gray; the pictures are the oracle's decodes."""
+    torch = _torch()
+    rec = _record(C)
+    G = oracle.record_header(rec)["G"]
+    full = _pixels(rec, G)
+    with pkg.Record(rec) as r:
+        total = int(r.output_layout()[-1])
+        d_full = _flat(torch, full, total)
+        for k in (1, 2, G):
+            low = _pixels(rec, k)
+            got = r.msssim_batch(_flat(torch, low, total), d_full).cpu().numpy()
+            _check(got, low, full)
+            if k == G:
+                assert all(g == 1.0 for g, p in zip(got, full) if min(p.shape[:2]) >= 11)
+
+
+def test_unrelated_noise_and_flat_pictures():
+    """Scores near zero (negative scale means are clamped), and flat pictures (zero variance everywhere)."""
+    torch = _torch()
+    rec = _record(3)
+    rng = np.random.default_rng(77)
+    shapes = [(h, w, 3) for (w, h) in SIZES]
+    with pkg.Record(rec) as r:
+        total = int(r.output_layout()[-1])
+        a = [rng.integers(0, 256, size=s, dtype=np.uint8) for s in shapes]
+        b = [rng.integers(0, 256, size=s, dtype=np.uint8) for s in shapes]
+        got = r.msssim_batch(_flat(torch, a, total), _flat(torch, b, total)).cpu().numpy()
+        _check(got, a, b)
+        fa = [np.full(s, 3 + 20 * i, np.uint8) for i, s in enumerate(shapes)]
+        fb = [np.full(s, 250 - 20 * i, np.uint8) for i, s in enumerate(shapes)]
+        got = r.msssim_batch(_flat(torch, fa, total), _flat(torch, fb, total)).cpu().numpy()
+        _check(got, fa, fb)
+        # a second call on the same handle re-uses the working memory
+        got2 = r.msssim_batch(_flat(torch, a, total), _flat(torch, b, total)).cpu().numpy()
+        _check(got2, a, b)
+
+
+def test_on_the_decoders_own_output_and_scores_rise_with_the_scan_group():
+    """The whole chain on the device: decode at k and at G, score.  The two decoders' pixels may differ by one LSB,
+    so the comparison with the oracle (on ITS pixels) gets a looser bound; fidelity must not fall as k grows."""
+    torch = _torch()
+    records, _ = pcrgen.make_workload("imagenet_like", limit=24)
+    rec = records[0]
+    G = oracle.record_header(rec)["G"]
+    full = _pixels(rec, G)
+    with pkg.Record(rec) as r:
+        d_full = r.decode_batch(G).clone()
+        prev = None
+        for k in (1, 2, 5, G):
+            d_low = r.decode_batch(k).clone()
+            got = r.msssim_batch(d_low, d_full).cpu().numpy()
+            low = _pixels(rec, k)
+            for i in range(0, len(full), 5):
+                assert abs(float(got[i]) - oracle.msssim(low[i], full[i])) <= 2e-3, (k, i)
+            if prev is not None:
+                assert (got >= prev - 1e-3).all()
+            prev = got
+        assert (prev == 1.0).all()
+
+
+def test_argument_errors(rgb_small):
+    torch = _torch()
+    rec, _ = rgb_small
+    import ctypes
+    with pkg.Record(rec) as r:
+        total = int(r.output_layout()[-1])
+        x = torch.zeros(total, dtype=torch.uint8, device="cuda")
+        out = torch.zeros(r.n, dtype=torch.float32, device="cuda")
+        L = pkg.lib()
+        assert L.pcr_msssim_batch(r._h, None, x.data_ptr(), out.data_ptr(), None) == pkg.E_ARG
+        assert L.pcr_msssim_batch(r._h, x.data_ptr(), x.data_ptr(), None, None) == pkg.E_ARG
+        assert L.pcr_msssim_batch(None, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == pkg.E_ARG
