@@ -236,7 +236,7 @@ int pcr_loader_wait(pcr_loader* ld, int slot);
 /* Stage timing with HIP events recorded on the call's own stream (off by default; switching it on
  * starts a new history).  A stage is one kernel or a short run of kernels:
  *   INDEX_PARSE    k_index + k_parse                 UNSTUFF        k_unstuff + zero fills
- *   DC_FIRST, AC_FIRST, AC_REFINE, REFINE_BLOCKS     one interval per launch of that kernel
+ *   DC_FIRST, AC_FIRST, AC_REFINE, REFINE_BLOCKS, SEQUENTIAL     one interval per launch of that kernel
  *   REFINE_APPLY   k_apply_prep + k_apply            PIXEL          k_pixel
  * pcr_last_stage_ms: milliseconds per stage of the last pcr_decode_batch / pcr_decode_coefficients
  *   call on this handle (stage_ms: host, PCR_NUM_STAGES floats).
@@ -246,7 +246,7 @@ int pcr_loader_wait(pcr_loader* ld, int slot);
  * Both block until the calls they report have finished; PCR_E_ARG if nothing was recorded. */
 enum { PCR_STAGE_INDEX_PARSE = 0, PCR_STAGE_UNSTUFF = 1, PCR_STAGE_DC_FIRST = 2, PCR_STAGE_AC_FIRST = 3,
        PCR_STAGE_AC_REFINE = 4, PCR_STAGE_REFINE_BLOCKS = 5, PCR_STAGE_REFINE_APPLY = 6, PCR_STAGE_PIXEL = 7,
-       PCR_NUM_STAGES = 8 };
+       PCR_STAGE_SEQUENTIAL = 8, PCR_NUM_STAGES = 9 };
 int pcr_enable_stage_timing(pcr_record* rec, int on);
 int pcr_last_stage_ms(pcr_record* rec, float* stage_ms);
 int pcr_stage_ms_history(pcr_record* rec, double* sum_ms, uint32_t* launches, uint32_t* calls);

@@ -11,8 +11,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpcr.so")
 
 OK, E_ARG, E_FORMAT, E_TRUNCATED, E_UNSUPPORTED, E_RANGE, E_NOMEM, E_DEVICE = 0, -1, -2, -3, -4, -5, -6, -7
-NUM_STAGES = 8
-STAGE_NAMES = ("index_parse", "unstuff", "dc_first", "ac_first", "ac_refine", "refine_blocks", "refine_apply", "pixel")
+NUM_STAGES = 9
+STAGE_NAMES = ("index_parse", "unstuff", "dc_first", "ac_first", "ac_refine", "refine_blocks", "refine_apply", "pixel", "sequential")
 
 # every symbol include/pcr.h declares: name -> (restype, argtypes)
 _u8p = ctypes.POINTER(ctypes.c_uint8)

@@ -52,7 +52,11 @@ struct ScanDesc {
     uint8_t valid;
     uint32_t mcus;                         // MCUs in this scan
     uint32_t mcu_w;                        // MCUs per row of this scan
+    uint32_t ac_offc[kMaxComp];            // sequential scans: record offset of BITS[16] of the AC table of scan component j
 };
+
+// A scan of a sequential (baseline) file carries whole blocks: DC difference, then the AC run/size pairs.
+PCR_HD bool is_sequential_scan(const ScanDesc& sd) { return sd.Ss == 0 && sd.Se == 63; }
 
 struct Unit {                              // one independently decodable piece: a restart interval of a scan
     uint32_t img;

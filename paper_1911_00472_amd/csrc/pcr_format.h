@@ -137,15 +137,26 @@ PCR_HD int parse_region(const uint8_t* rec, uint32_t p, uint32_t end, int first_
                 if (td[j] > 3 || ta[j] > 3) return kEFormat;
             }
             sd->Ss = rec[s + 1 + 2 * ns]; sd->Se = rec[s + 2 + 2 * ns]; sd->Ah = rec[s + 3 + 2 * ns] >> 4; sd->Al = rec[s + 3 + 2 * ns] & 15;
-            if (!img->progressive) return kEUnsupported;       // sequential files are not PCR input
-            if (sd->Ss > sd->Se || sd->Se > 63 || (sd->Ss == 0 && sd->Se != 0) || (sd->Ss > 0 && ns != 1) || sd->Al > 13) return kEFormat;
-            if (sd->Ah != 0 && sd->Ah != sd->Al + 1) return kEFormat;
-            for (uint32_t j = 0; j < ns; j++) {
-                sd->dc_off[j] = 0;
-                if (sd->Ss == 0 && sd->Ah == 0) { if (!st->dht[0][td[j]]) return kEFormat; sd->dc_off[j] = st->dht[0][td[j]]; }
+            for (int j = 0; j < kMaxComp; j++) sd->ac_offc[j] = 0;
+            if (!img->progressive) {
+                // Sequential (baseline) file, the format a record of non-progressive images holds (one scan group, or
+                // one per component): the scan header must say "all 64 coefficients, full precision".
+                if (sd->Ss != 0 || sd->Se != 63 || sd->Ah != 0 || sd->Al != 0) return kEFormat;
+                for (uint32_t j = 0; j < ns; j++) {
+                    if (!st->dht[0][td[j]] || !st->dht[1][ta[j]]) return kEFormat;
+                    sd->dc_off[j] = st->dht[0][td[j]]; sd->ac_offc[j] = st->dht[1][ta[j]];
+                }
+                sd->ac_off = sd->ac_offc[0];
+            } else {
+                if (sd->Ss > sd->Se || sd->Se > 63 || (sd->Ss == 0 && sd->Se != 0) || (sd->Ss > 0 && ns != 1) || sd->Al > 13) return kEFormat;
+                if (sd->Ah != 0 && sd->Ah != sd->Al + 1) return kEFormat;
+                for (uint32_t j = 0; j < ns; j++) {
+                    sd->dc_off[j] = 0;
+                    if (sd->Ss == 0 && sd->Ah == 0) { if (!st->dht[0][td[j]]) return kEFormat; sd->dc_off[j] = st->dht[0][td[j]]; }
+                }
+                sd->ac_off = 0;
+                if (sd->Ss > 0) { if (!st->dht[1][ta[0]]) return kEFormat; sd->ac_off = st->dht[1][ta[0]]; }
             }
-            sd->ac_off = 0;
-            if (sd->Ss > 0) { if (!st->dht[1][ta[0]]) return kEFormat; sd->ac_off = st->dht[1][ta[0]]; }
             sd->ri = st->ri;
             if (ns > 1) { sd->mcu_w = img->mcux; sd->mcus = (uint32_t)img->mcux * img->mcuy; }
             else { sd->mcu_w = img->cw[sd->comp[0]]; sd->mcus = (uint32_t)img->cw[sd->comp[0]] * img->ch[sd->comp[0]]; }

@@ -306,6 +306,45 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     if (rc != kOk) R.status[un.img] = rc;
 }
 
+// Sequential (baseline) scans: the DC and AC tables of every scan component, once per distinct table.
+__global__ void __launch_bounds__(kEntropyLanes) k_sequential(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
+        const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {
+    __shared__ DcTab dtabs[kMaxComp];
+    __shared__ AcTab atabs[kMaxComp];
+    const Unit un = units[blockIdx.x];
+    UnitSetup L;
+    unit_setup(R, un, clean32, &L);
+    if (!L.ok) return;
+    const ScanDesc* sd = &R.scan[(size_t)un.img * R.G + un.scan];
+    if (!is_sequential_scan(*sd)) { R.status[un.img] = kEFormat; return; }      // (a unit in the wrong launch)
+    const uint32_t d0 = sd->dc_off[0], d1 = L.ls.ns > 1 ? sd->dc_off[1] : d0, d2 = L.ls.ns > 2 ? sd->dc_off[2] : d0;
+    const uint32_t a0 = sd->ac_offc[0], a1 = L.ls.ns > 1 ? sd->ac_offc[1] : a0, a2 = L.ls.ns > 2 ? sd->ac_offc[2] : a0;
+    int dj1 = 0, dj2 = 0, nd = 1, aj1 = 0, aj2 = 0, na = 1;
+    if (d1 != d0) { dj1 = 1; nd = 2; }
+    if (d2 == d1) dj2 = dj1; else if (d2 != d0) { dj2 = nd; nd++; }
+    if (a1 != a0) { aj1 = 1; na = 2; }
+    if (a2 == a1) aj2 = aj1; else if (a2 != a0) { aj2 = na; na++; }
+    if (threadIdx.x == 0) { dctab_build(&dtabs[0], R.rec + d0); actab_build(&atabs[0], R.rec + a0); }
+    if (threadIdx.x == 1) {
+        if (dj1 == 1) dctab_build(&dtabs[1], R.rec + d1);
+        if (aj1 == 1) actab_build(&atabs[1], R.rec + a1);
+    }
+    if (threadIdx.x == 2) {
+        if (dj2 != 0 && dj2 != dj1) dctab_build(&dtabs[dj2], R.rec + d2);
+        if (aj2 != 0 && aj2 != aj1) actab_build(&atabs[aj2], R.rec + a2);
+    }
+    __syncthreads();
+    for (int t = 0; t < na; t++) actab_pack(&atabs[t], true, threadIdx.x, kEntropyLanes);
+    __syncthreads();
+    SeqWindowReader wr;
+    wr.init(L.words, L.byte_off, L.nbytes, &dtabs[0], &dtabs[uni(dj1)], &dtabs[uni(dj2)], &atabs[0], &atabs[uni(aj1)], &atabs[uni(aj2)],
+            L.ls.ns, threadIdx.x);
+    CoefSink sink;
+    sink.init(L.base, L.base_elems, 0);
+    const int rc = decode_sequential(&wr, L.ls, &sink);
+    if (rc != kOk) R.status[un.img] = rc;
+}
+
 struct ApplyUnit { uint32_t img; uint32_t comp; };
 constexpr int kApplyMaxScans = 16;
 

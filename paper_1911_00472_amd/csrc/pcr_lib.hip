@@ -22,7 +22,7 @@ using namespace pcr;
 
 namespace {
 
-enum Kind { kDcFirst = 0, kAcFirst = 1, kAcRefine = 2, kNumKinds = 3 };
+enum Kind { kDcFirst = 0, kAcFirst = 1, kAcRefine = 2, kSequential = 3, kNumKinds = 4 };
 struct LevelList {
     Unit* d_units = nullptr; uint32_t n = 0; int kind = 0;
     int shape = 0;                                                               // DC first scans: dc_shape of the units
@@ -162,10 +162,11 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
             const size_t ig = (size_t)i * G + g;
             const ScanDesc& sd = r->scan[ig];
             if (sd.Ah > 0) for (int j = 0; j < sd.ns; j++) refine[sd.comp[j]] = true;
-            if (sd.Ss > 0) { plan.has_ac = true; if (g < (uint32_t)k0) plan.had_ac = true; }
+            const bool seq = is_sequential_scan(sd);
+            if (sd.Ss > 0 || seq) { plan.has_ac = true; if (g < (uint32_t)k0) plan.had_ac = true; }
             if (g < (uint32_t)k0) continue;                    // decoded by an earlier call
             if (sd.Ss == 0 && sd.Ah > 0) continue;             // DC refinement has no serial decode
-            const int kind = sd.Ss == 0 ? kDcFirst : (sd.Ah == 0 ? kAcFirst : kAcRefine);
+            const int kind = seq ? kSequential : (sd.Ss == 0 ? kDcFirst : (sd.Ah == 0 ? kAcFirst : kAcRefine));
             if (kind == kAcRefine) {
                 rlists[r->level[ig] - 1].push_back(RefineScan{i, g});
                 rmax[r->level[ig] - 1] = std::max<uint32_t>(rmax[r->level[ig] - 1], (uint32_t)r->img[i].cw[sd.comp[0]] * r->img[i].ch[sd.comp[0]]);
@@ -301,6 +302,7 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
             }
             mark(r, PCR_STAGE_DC_FIRST, s);
         }
+        else if (l.kind == kSequential) { hipLaunchKernelGGL(k_sequential, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_SEQUENTIAL, s); }
         else if (l.kind == kAcFirst) { hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_AC_FIRST, s); }
         else {
             hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64);

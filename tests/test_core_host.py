@@ -83,3 +83,16 @@ def test_lane_code_matches_oracle_extreme_coefficients(emul, extreme_record):
     rec, files = extreme_record
     G = oracle.record_header(rec)["G"]
     _compare(emul, rec, range(len(files)), range(1, G + 1))
+
+
+def test_lane_code_matches_oracle_sequential_files(emul):
+    """Baseline files: interleaved 4:2:0, 4:4:4 and 4:2:2, gray, with and without restart intervals, small and
+    noisy enough for codes longer than the look-ahead table."""
+    files = []
+    for i, (w, h, c, hs, vs, q, rst) in enumerate([(77, 53, 3, 2, 2, 90, 0), (64, 64, 1, 1, 1, 85, 0), (129, 65, 3, 1, 1, 95, 1),
+                                                   (40, 200, 3, 2, 1, 75, 1), (1, 1, 3, 2, 2, 90, 0), (333, 211, 3, 2, 2, 98, 0)]):
+        img = pcrgen.synth(700 + i, 1 + (i % 2), w, h, c, 6.0 if i < 5 else 30.0)
+        files.append(pcrgen.encode_pixels(img, hs, vs, q, "sequential", restart=rst))
+    rec = pcrgen.write_record(files)
+    assert oracle.record_header(rec)["G"] == 1
+    _compare(emul, rec, range(len(files)), (1,))

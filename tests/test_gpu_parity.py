@@ -107,6 +107,30 @@ def test_ham_like_444():
     _check_record(records[0], (1, 4, 7, 10), check_bytes=False)
 
 
+def _sequential_files():
+    out = []
+    for i, (w, h, c, hs, vs, q, rst) in enumerate([(77, 53, 3, 2, 2, 90, 0), (64, 64, 1, 1, 1, 85, 0), (129, 65, 3, 1, 1, 95, 1),
+                                                   (40, 200, 3, 2, 1, 75, 1), (1, 1, 3, 2, 2, 90, 0), (333, 211, 3, 2, 2, 98, 0),
+                                                   (500, 375, 3, 2, 2, 90, 0), (17, 9, 3, 1, 2, 90, 2)]):
+        img = pcrgen.synth(700 + i, 1 + (i % 2), w, h, c, 6.0 if i != 5 else 30.0)
+        out.append(pcrgen.encode_pixels(img, hs, vs, q, "sequential", restart=rst))
+    return out
+
+
+def test_sequential_baseline_files_in_a_record():
+    """Records of non-progressive files (the baseline the paper compares against, Section 6.1): one scan group.
+    Interleaved 4:2:0 / 4:4:4 / 4:2:2 / 4:4:0, gray, restart intervals, codes longer than the look-ahead table."""
+    rec = pcrgen.write_record(_sequential_files())
+    assert oracle.record_header(rec)["G"] == 1
+    _check_record(rec, (1,))
+
+
+def test_progressive_and_sequential_files_mixed_in_one_record(rgb_small):
+    files = _sequential_files()[:4] + list(rgb_small[1][:6])
+    rec = pcrgen.write_record([files[j] for j in (4, 0, 5, 1, 6, 7, 2, 8, 3, 9)])
+    _check_record(rec, (1, 2, 6, 10))
+
+
 def test_truncated_record_prefix(rgb_small):
     """Reading only up to the end of group k (paper Section 3) serves fidelities 1..k with the
     same results as the whole record, and refuses k+1."""
@@ -167,8 +191,13 @@ def test_corrupt_entropy_data_flags_the_image_only(rgb_small):
 def test_unsupported_and_malformed_images_are_refused_at_open():
     good = pcrgen.make_jpeg(1, 1, 40, 24, 3, 6.0, 2, 2, 90)
     arith = good.replace(b"\xff\xc2", b"\xff\xca", 1)
+    deep = good.replace(b"\xff\xc2\x00\x11\x08", b"\xff\xc2\x00\x11\x0c", 1)              # 12-bit samples
+    assert deep != good
     seq = pcrgen.encode_pixels(pcrgen.synth(1, 1, 40, 24, 3, 6.0), 2, 2, 90, "sequential")
-    for bad, code in ((arith, pkg.E_UNSUPPORTED), (seq, pkg.E_UNSUPPORTED)):
+    i = seq.index(b"\xff\xda")
+    L = int.from_bytes(seq[i + 2:i + 4], "big")
+    cut_band = seq[:i + 2 + L - 2] + b"\x3e" + seq[i + 2 + L - 1:]                             # a baseline scan that stops at position 62
+    for bad, code in ((arith, pkg.E_UNSUPPORTED), (deep, pkg.E_UNSUPPORTED), (cut_band, pkg.E_FORMAT)):
         rec = pcrgen.write_record([good, bad])
         with pytest.raises(pkg.PcrError) as e:
             pkg.pcr_open(rec, 0)
