@@ -6,7 +6,7 @@ of scans 1..k, refinement, de-quantise, IDCT, chroma replication, YCbCr->RGB, st
 whole workload: 4096 variable-size progressive JPEGs in 4 records of 1024, record bytes already
 resident in device memory.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--images N] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--images N] [--no-cpu-baseline] [--no-baseline-files]
 """
 import argparse
 import json
@@ -130,6 +130,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--images", type=int, default=4096, help="images of the workload to use (default: all 4096)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-baseline-files", action="store_true", help="skip the leg that decodes the same images as non-progressive files")
     ap.add_argument("--scan-group", type=int, default=HEADLINE_K)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise copy of 256 MiB (untimed), the yardstick for rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -382,6 +383,44 @@ def main():
                          "note": "pixel_GBps counts both batches read once; the kernel reads every scale from the uint8 pixels (about 5 x 1.7 reads with tile halos)"}
     del full0
 
+    # ---- the same images as baseline (non-progressive) files: what the decode of a progressive file costs over it ----
+    baseline = None
+    if not args.no_baseline_files:
+        seq_records, seq_files = pcrgen.make_workload("imagenet_like", limit=args.images, script="sequential")
+        seq_handles = [pkg.pcr_open(r, 0) for r in seq_records]
+        torch.cuda.synchronize()
+
+        def seq_step():
+            for h, o, st in zip(seq_handles, outs, streams):
+                h.decode_batch(1, out=o, stream=st.cuda_stream)
+
+        seq_step()
+        torch.cuda.synchronize()
+        lay_s = seq_handles[0].output_layout()
+        host = outs[0].cpu().numpy()
+        for i in (0, min(5, seq_handles[0].n - 1)):
+            _, p0, info = oracle.decode_record_image(seq_records[0], i, 1, want_coef=False)
+            got = host[int(lay_s[i]):int(lay_s[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
+            assert np.abs(got - p0).max() <= 1, "parity check failed for baseline image %d" % i
+        reps_b = max(5, args.steps)
+        t = time.perf_counter()
+        for _ in range(reps_b):
+            seq_step()
+        torch.cuda.synchronize()
+        dt_seq = (time.perf_counter() - t) / reps_b
+        seq_handles[0].enable_stage_timing(True)
+        for _ in range(3):
+            seq_handles[0].decode_batch(1, out=outs[0], stream=streams[0].cuda_stream)
+        torch.cuda.synchronize()
+        calls_b, alone_b = seq_handles[0].stage_ms_history()
+        baseline = {"files": "the same %d images (same quantised coefficients) as sequential Huffman files, mean %.1f kB" % (n_img, np.mean([len(f) for f in seq_files]) / 1e3),
+                    "images_per_s": n_img / dt_seq, "ms_per_step": dt_seq * 1e3,
+                    "stage_ms_one_record_alone": {n: v[0] / calls_b for n, v in alone_b.items() if v[1]},
+                    "note": "one wavefront per image (no restart intervals): a single pass, no refinement scans"}
+        for h in seq_handles:
+            h.close()
+        del seq_handles, seq_records, seq_files
+
     per_k = {}
     for k in SCAN_GROUPS:
         if k == args.scan_group:
@@ -473,6 +512,7 @@ def main():
         "from_pinned_host_memory": streamed,
         "training_tail": training_tail,
         "fidelity_estimate": fidelity_estimate,
+        "baseline_sequential_files": baseline,
     }
     for h in handles:
         h.close()

@@ -26,7 +26,11 @@
  *
  * Not supported (PCR_E_UNSUPPORTED): arithmetic coding, 12-bit samples, lossless and
  * hierarchical modes, DNL, component counts other than 1 or 3, sampling factors other than 1
- * or 2, sequential (non-progressive) files, records of 4 GiB or more.
+ * or 2, records of 4 GiB or more.
+ *
+ * Sequential (baseline, non-progressive) Huffman files are accepted too: such a file is one scan (or one
+ * per component), so a record of them has that many scan groups and no lower fidelities.  They are what
+ * the paper's baseline layouts hold (Section 6.1); the same calls decode them.
  */
 #ifndef PCR_H
 #define PCR_H

@@ -66,6 +66,8 @@ def lib():
         L.pcrgen_make_jpeg.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, u8p, ctypes.c_size_t]
         L.pcrgen_make_jpeg.restype = ctypes.c_size_t
+        L.pcrgen_make_jpeg_sequential.argtypes = L.pcrgen_make_jpeg.argtypes
+        L.pcrgen_make_jpeg_sequential.restype = ctypes.c_size_t
         L.pcrgen_split_scans.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int]
         L.pcrgen_split_scans.restype = ctypes.c_int
         _lib = L
@@ -141,10 +143,11 @@ def encode_pixels(pix, hsub=2, vsub=2, quality=90, script=None, restart=0, retur
     return (data, coef) if return_coefs else data
 
 
-def make_jpeg(seed, kind, W, H, C, sigma, hsub, vsub, quality, restart=0):
+def make_jpeg(seed, kind, W, H, C, sigma, hsub, vsub, quality, restart=0, sequential=False):
     cap = W * H * C * 2 + 65536
     out = np.empty(cap, np.uint8)
-    n = lib().pcrgen_make_jpeg(seed, kind, W, H, C, float(sigma), hsub, vsub, quality, restart, _p(out, ctypes.c_uint8), cap)
+    fn = lib().pcrgen_make_jpeg_sequential if sequential else lib().pcrgen_make_jpeg
+    n = fn(seed, kind, W, H, C, float(sigma), hsub, vsub, quality, restart, _p(out, ctypes.c_uint8), cap)
     assert n > 0
     return out[:n].tobytes()
 
@@ -216,9 +219,11 @@ def workload_shapes(name, seed=191100472, limit=None):
     return Ws, Hs
 
 
-def make_workload(name, seed=191100472, limit=None, threads=None):
+def make_workload(name, seed=191100472, limit=None, threads=None, script=None):
     """Generate a workload: returns (records: list[bytes], files: list[bytes]).  `limit`
-    keeps only the first `limit` images (records stay `per_record` long, the last may be short)."""
+    keeps only the first `limit` images (records stay `per_record` long, the last may be short).
+    script: None for the workload's progressive files; "sequential" encodes the same images (same quantised
+    coefficients) as baseline files, the non-progressive layout the paper compares against."""
     w = WORKLOADS[name]
     Ws, Hs = workload_shapes(name, seed, limit)
     n = len(Ws)
@@ -226,6 +231,11 @@ def make_workload(name, seed=191100472, limit=None, threads=None):
     lib()
 
     def one(i):
+        if script == "sequential":
+            return make_jpeg(_mix(seed, i), w["kind"], int(Ws[i]), int(Hs[i]), w["C"], w["sigma"], hs, vs, w["quality"], w["restart"], sequential=True)
+        if script is not None:
+            pix = synth(_mix(seed, i), w["kind"], int(Ws[i]), int(Hs[i]), w["C"], w["sigma"])
+            return encode_pixels(pix, hs, vs, w["quality"], script, w["restart"])
         return make_jpeg(_mix(seed, i), w["kind"], int(Ws[i]), int(Hs[i]), w["C"], w["sigma"], hs, vs, w["quality"], w["restart"])
 
     threads = threads or min(16, os.cpu_count() or 1)

@@ -611,6 +611,16 @@ size_t pcrgen_make_jpeg(uint64_t seed, int kind, int W, int H, int nc, double si
     return n;
 }
 
+/* the same image as a sequential (baseline) file */
+size_t pcrgen_make_jpeg_sequential(uint64_t seed, int kind, int W, int H, int nc, double sigma, int hsub, int vsub,
+                                   int quality, int restart, uint8_t* out, size_t cap) {
+    uint8_t* pix = (uint8_t*)malloc((size_t)W * H * nc);
+    pcrgen_synth(seed, kind, W, H, nc, sigma, pix);
+    size_t n = pcrgen_encode_pixels(pix, W, H, nc, hsub, vsub, quality, NULL, -1, restart, out, cap, NULL);
+    free(pix);
+    return n;
+}
+
 /* ------------------------------------------------------------------------------------------
  * Scan splitter (paper Section 5, "Encoding": locate the markers that end each scan).
  * After every SOS header the entropy-coded data runs to the first 0xFF that is followed by
