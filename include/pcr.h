@@ -237,6 +237,32 @@ int pcr_loader_decode_crop(pcr_loader* ld, int slot, int scan_group, const pcr_c
                            int32_t* d_status);
 int pcr_loader_wait(pcr_loader* ld, int slot);
 
+/* Record creation (Section 5, "Encoding"), on the host.
+ * pcr_scan_ends: where each scan of a JPEG file ends.  ends[s] is the offset one past region s: the scan's
+ *   entropy-coded data runs to the first 0xFF not followed by 0x00, a restart marker or more 0xFF fill before one
+ *   of these; the last region runs to the end of the file (so ends[n_scans - 1] == nbytes).  These are the
+ *   offsets the record's index is made of.  PCR_E_FORMAT: not a well-formed file, or more than max_ends scans.
+ * pcr_record_size / pcr_record_write: group the scans of n files (host pointers, sizes in bytes) into one record
+ *   in the layout at the top of this header -- region g of every file back to back in group g, the index and
+ *   the labels (NULL: zeros) in front, the header padded to a multiple of 64 bytes.  Files may have different
+ *   scan counts (progressive and baseline files may be mixed): G is the largest.  out: host, capacity bytes;
+ *   *written receives the record size also when the capacity is too small (PCR_E_RANGE).
+ *   PCR_E_UNSUPPORTED: the record would reach 4 GiB.
+ * pcr_transcode_progressive: the lossless transcode that precedes grouping: the quantised coefficients of a
+ *   file (coef: host, the file's slice of pcr_decode_coefficients' output at its last scan group, layout of
+ *   pcr_coef_layout) written out as a progressive file with the frame header and quantisation tables of
+ *   src_jpeg, the usual scan script (10 scans for three components, 6 for one: DC without its last bit, low
+ *   luma band, chroma, rest of luma, then the held-back bit planes) and Huffman tables optimised per scan; no
+ *   restart intervals, application segments are dropped.  Decoding the result gives the same coefficients on
+ *   every block that covers image samples, hence the same pixels.  out: host; *written receives the size also
+ *   when out is NULL or too small (PCR_E_RANGE).  PCR_E_RANGE also when coef_count does not fit the frame. */
+int pcr_scan_ends(const void* jpeg, size_t nbytes, uint64_t* ends, int max_ends, int* n_scans);
+int pcr_record_size(const void* const* files, const size_t* sizes, uint32_t n, uint64_t* record_bytes, uint32_t* scan_groups);
+int pcr_record_write(const void* const* files, const size_t* sizes, const int32_t* labels, uint32_t n, void* out, size_t capacity,
+                     uint64_t* written);
+int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, void* out, size_t capacity,
+                              uint64_t* written);
+
 /* Stage timing with HIP events recorded on the call's own stream (off by default; switching it on
  * starts a new history).  A stage is one kernel or a short run of kernels:
  *   INDEX_PARSE    k_index + k_parse                 UNSTUFF        k_unstuff + zero fills

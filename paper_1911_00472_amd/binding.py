@@ -44,6 +44,12 @@ SYMBOLS = {
     "pcr_decode_crop_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
                                              ctypes.POINTER(ctypes.c_float), _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_msssim_batch": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp]),
+    "pcr_scan_ends": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]),
+    "pcr_record_size": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_size_t), ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint64),
+                                       ctypes.POINTER(ctypes.c_uint32)]),
+    "pcr_record_write": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_size_t), _vp, ctypes.c_uint32, _vp, ctypes.c_size_t,
+                                        ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_transcode_progressive": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.c_size_t, _vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_prefix_length": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_loader_create": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]),
     "pcr_loader_destroy": (None, [_vp]),
@@ -295,6 +301,64 @@ def prefix_length(first_bytes, k):
         return False, int(need.value)
     _check(rc, "pcr_prefix_length")
     return True, int(need.value)
+
+
+def scan_ends(jpeg):
+    """End offset of every scan region of a JPEG file (the last equals len(jpeg))."""
+    buf = np.frombuffer(jpeg, np.uint8)
+    ends = (ctypes.c_uint64 * 64)()
+    n = ctypes.c_int(0)
+    _check(lib().pcr_scan_ends(buf.ctypes.data_as(_vp), buf.size, ends, 64, ctypes.byref(n)), "pcr_scan_ends")
+    return [int(ends[i]) for i in range(n.value)]
+
+
+def _file_table(files):
+    bufs = [np.frombuffer(f, np.uint8) for f in files]
+    ptrs = (_vp * len(bufs))(*[b.ctypes.data for b in bufs])
+    sizes = (ctypes.c_size_t * len(bufs))(*[b.size for b in bufs])
+    return bufs, ptrs, sizes
+
+
+def record_write(files, labels=None):
+    """One record (bytes) from JPEG files (bytes objects): pcr_record_size + pcr_record_write."""
+    bufs, ptrs, sizes = _file_table(files)
+    total, G = ctypes.c_uint64(0), ctypes.c_uint32(0)
+    _check(lib().pcr_record_size(ptrs, sizes, len(bufs), ctypes.byref(total), ctypes.byref(G)), "pcr_record_size")
+    out = np.empty(int(total.value), np.uint8)
+    lab = None if labels is None else np.ascontiguousarray(labels, np.int32)
+    assert lab is None or lab.size == len(bufs)
+    written = ctypes.c_uint64(0)
+    _check(lib().pcr_record_write(ptrs, sizes, lab.ctypes.data_as(_vp) if lab is not None else None, len(bufs), out.ctypes.data_as(_vp),
+                                  out.size, ctypes.byref(written)), "pcr_record_write")
+    assert written.value == out.size
+    return out.tobytes()
+
+
+def transcode_progressive(src_jpeg, coef):
+    """Progressive file (bytes) holding the quantised coefficients `coef` (int16 numpy array in the layout of
+    coef_layout() for this one image) under the frame header and quantisation tables of src_jpeg."""
+    src = np.frombuffer(src_jpeg, np.uint8)
+    coef = np.ascontiguousarray(coef, np.int16)
+    out = np.empty(src.size + src.size // 2 + 4096, np.uint8)
+    written = ctypes.c_uint64(0)
+    rc = lib().pcr_transcode_progressive(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, out.ctypes.data_as(_vp), out.size,
+                                         ctypes.byref(written))
+    if rc == E_RANGE and written.value > out.size:
+        out = np.empty(int(written.value), np.uint8)
+        rc = lib().pcr_transcode_progressive(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, out.ctypes.data_as(_vp), out.size,
+                                             ctypes.byref(written))
+    _check(rc, "pcr_transcode_progressive")
+    return out[:int(written.value)].tobytes()
+
+
+def transcode_files(files, device=0):
+    """The paper's encoding step for a list of JPEG files (baseline or progressive): their coefficients are decoded
+    on the device, re-coded as progressive files on the host.  Returns the progressive files; record_write() groups them."""
+    rec = record_write(files)
+    with pcr_open(rec, device) as r:
+        lay = r.coef_layout()
+        coef = r.decode_coefficients(r.G).cpu().numpy()
+    return [transcode_progressive(f, coef[int(lay[i]):int(lay[i + 1])]) for i, f in enumerate(files)]
 
 
 class Loader:

@@ -15,6 +15,7 @@
 #include "../../include/pcr.h"
 #include "pcr_kernels.h"
 #include "pcr_similarity.h"
+#include "pcr_encode.h"
 
 using namespace pcr;
 
@@ -804,6 +805,49 @@ int pcr_msssim_batch(pcr_record* r, const uint8_t* d_a, const uint8_t* d_b, floa
                        r->d_ssim_part, r->ssim_tiles_max);
     hipLaunchKernelGGL(k_ssim_score, dim3(n), dim3(64), 0, (hipStream_t)stream, r->d_dims, r->d_ssim_part, r->ssim_tiles_max, d_scores);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
+    return PCR_OK;
+}
+
+// ---- record creation (host only) ----
+int pcr_scan_ends(const void* jpeg, size_t nbytes, uint64_t* ends, int max_ends, int* n_scans) {
+    if (!jpeg || !ends || !n_scans || max_ends < 1) return PCR_E_ARG;
+    const int s = enc::scan_ends((const uint8_t*)jpeg, nbytes, ends, max_ends);
+    if (s <= 0) return PCR_E_FORMAT;
+    *n_scans = s;
+    return PCR_OK;
+}
+
+int pcr_record_size(const void* const* files, const size_t* sizes, uint32_t n, uint64_t* record_bytes, uint32_t* scan_groups) {
+    if (!files || !sizes || !record_bytes) return PCR_E_ARG;
+    enc::RecordPlan P;
+    const int rc = enc::plan_record(files, sizes, n, &P);
+    if (rc) return rc;
+    *record_bytes = P.total;
+    if (scan_groups) *scan_groups = P.G;
+    return PCR_OK;
+}
+
+int pcr_record_write(const void* const* files, const size_t* sizes, const int32_t* labels, uint32_t n, void* out, size_t capacity, uint64_t* written) {
+    if (!files || !sizes || !out) return PCR_E_ARG;
+    enc::RecordPlan P;
+    const int rc = enc::plan_record(files, sizes, n, &P);
+    if (rc) return rc;
+    if (written) *written = P.total;
+    if (capacity < P.total) return PCR_E_RANGE;
+    enc::write_record(P, files, labels, (uint8_t*)out);
+    return PCR_OK;
+}
+
+int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, void* out, size_t capacity,
+                              uint64_t* written) {
+    if (!src_jpeg || !coef || !written) return PCR_E_ARG;
+    std::vector<uint8_t> bytes;
+    bytes.reserve(src_bytes + src_bytes / 4 + 1024);
+    const int rc = enc::transcode_progressive((const uint8_t*)src_jpeg, src_bytes, coef, coef_count, &bytes);
+    if (rc) return rc;
+    *written = bytes.size();
+    if (!out || capacity < bytes.size()) return PCR_E_RANGE;
+    memcpy(out, bytes.data(), bytes.size());
     return PCR_OK;
 }
 

@@ -1,0 +1,140 @@
+"""Record creation on the host (paper Section 5, "Encoding"): scan splitter, record writer and the lossless
+transcode to progressive files, through the C ABI.  No GPU: the coefficients the transcode starts from come from
+the oracle here.  Checked against the oracle (which reads what was written), against the input generator's own
+writer (a second implementation of the same layout), and against Pillow (which must accept the files)."""
+import io
+
+import numpy as np
+import pytest
+
+import oracle
+import pcrgen
+import paper_1911_00472_amd as pkg
+
+
+def _files():
+    out = [pcrgen.make_jpeg(100 + i, 1 + (i % 2), w, h, 3, 6.0, 2, 2, 90, restart=(i % 3 == 2))
+           for i, (w, h) in enumerate([(77, 53), (16, 16), (17, 9), (1, 1), (129, 65), (40, 200)])]
+    out.append(pcrgen.encode_pixels(pcrgen.synth(5, 1, 60, 40, 3, 6.0), 2, 2, 90, "sequential"))
+    out.append(pcrgen.encode_pixels(pcrgen.synth(6, 2, 90, 41, 3, 10.0), 1, 1, 95, "sequential", restart=1))
+    out.append(pcrgen.encode_pixels(pcrgen.synth(7, 2, 33, 70, 3, 10.0), 2, 1, 80, None))
+    out.append(pcrgen.make_jpeg(9, 0, 40, 24, 1, 8.0, 1, 1, 90))
+    return out
+
+
+def test_scan_ends_are_where_the_oracle_can_cut_the_file():
+    for f in _files():
+        ends = pkg.scan_ends(f)
+        assert ends == pcrgen.split_scans(f) and ends[-1] == len(f) and ends == sorted(set(ends))
+        for e in ends[:-1]:
+            assert f[e] == 0xFF and f[e + 1] not in (0x00, 0xFF) and not 0xD0 <= f[e + 1] <= 0xD7     # a marker starts every later region
+    with pytest.raises(pkg.PcrError) as e:
+        pkg.scan_ends(b"\x00\x01\x02\x03\x04")
+    assert e.value.code == pkg.E_FORMAT
+    with pytest.raises(pkg.PcrError):
+        pkg.scan_ends(_files()[0][:400])                          # entropy-coded data runs off the end
+
+
+def test_written_record_reads_back_through_the_oracle():
+    files = _files()
+    labels = [7 * i - 3 for i in range(len(files))]
+    rec = pkg.record_write(files, labels)
+    assert rec == pcrgen.write_record(files, labels)              # the generator's writer: same layout, written separately
+    h = oracle.record_header(rec)
+    assert h["n"] == len(files) and h["G"] == 10 and h["k_avail"] == 10 and h["header_bytes"] % 64 == 0
+    off, ln, lab, ns, ge = oracle.record_index(rec)
+    assert list(lab) == labels and list(ns) == [len(pkg.scan_ends(f)) for f in files] and int(ge[-1]) == len(rec)
+    for i, f in enumerate(files):
+        assert oracle.reassemble(rec, i, 10) == f                 # every file comes back byte for byte
+        k = min(3, int(ns[i]))
+        assert oracle.reassemble(rec, i, k)[:pkg.scan_ends(f)[k - 1]] == f[:pkg.scan_ends(f)[k - 1]]
+    assert pkg.record_write(files) == pcrgen.write_record(files)  # no labels: zeros
+
+
+def test_record_writer_errors():
+    import ctypes
+    files = _files()[:2]
+    with pytest.raises(pkg.PcrError) as e:
+        pkg.record_write([files[0], b"not a jpeg file at all"])
+    assert e.value.code == pkg.E_FORMAT
+    L = pkg.lib()
+    bufs = [np.frombuffer(f, np.uint8) for f in files]
+    ptrs = (ctypes.c_void_p * 2)(*[b.ctypes.data for b in bufs])
+    sizes = (ctypes.c_size_t * 2)(*[b.size for b in bufs])
+    out = np.zeros(100, np.uint8)
+    written = ctypes.c_uint64(0)
+    assert L.pcr_record_write(ptrs, sizes, None, 2, out.ctypes.data_as(ctypes.c_void_p), out.size, ctypes.byref(written)) == pkg.E_RANGE
+    assert written.value == len(pcrgen.write_record(files)) and not out.any()
+    assert L.pcr_record_size(None, sizes, 2, ctypes.byref(written), None) == pkg.E_ARG
+    assert L.pcr_record_size(ptrs, sizes, 0, ctypes.byref(written), None) == pkg.E_RANGE
+
+
+def _decode_file(f):
+    rec = pcrgen.write_record([f])
+    G = oracle.record_header(rec)["G"]
+    return oracle.decode_record_image(rec, 0, G), G
+
+
+def _covered(coef, info):
+    """Coefficients of the blocks that cover image samples (the others are not coded by non-interleaved scans)."""
+    out, o = [], 0
+    hmax, vmax = max(info.hs[:info.nc]), max(info.vs[:info.nc])
+    for c in range(info.nc):
+        bw, bh = info.bw[c], info.bh[c]
+        cw = ((info.W * info.hs[c] + hmax - 1) // hmax + 7) // 8
+        ch = ((info.H * info.vs[c] + vmax - 1) // vmax + 7) // 8
+        pl = coef[o:o + bw * bh * 64].reshape(bh, bw, 64)
+        out.append(pl[:ch, :cw].copy()); o += bw * bh * 64
+    return out
+
+
+def _check_transcode(f):
+    from PIL import Image
+    (c0, p0, info), _ = _decode_file(f)
+    t = pkg.transcode_progressive(f, c0)
+    (c1, p1, info1), G1 = _decode_file(t)
+    assert G1 == (10 if info.nc == 3 else 6)
+    assert (info1.W, info1.H, info1.nc) == (info.W, info.H, info.nc)
+    assert np.array_equal(p0, p1)                                  # same pixels, exactly
+    for a, b in zip(_covered(c0, info), _covered(c1, info1)):
+        assert np.array_equal(a, b)
+    im = Image.open(io.BytesIO(t))
+    im.load()
+    assert im.size == (info.W, info.H) and im.info.get("progressive")
+    # lower fidelities of the new file are real pictures too: DC only is block-constant luma
+    rec = pcrgen.write_record([t])
+    _, p_dc, _ = oracle.decode_record_image(rec, 0, 1)
+    assert p_dc.shape == p0.shape
+    return t
+
+
+def test_transcode_is_lossless_for_baseline_and_progressive_sources():
+    for f in _files():
+        _check_transcode(f)
+
+
+def test_transcode_of_extreme_coefficient_planes(extreme_record):
+    """Dense blocks, lone last coefficients, zero runs inside refinement scans, the largest sizes, end-of-band runs
+    over hundreds of blocks: every path of the progressive coder."""
+    _, files = extreme_record
+    for f in files:
+        _check_transcode(f)
+
+
+def test_transcode_end_of_band_run_longer_than_one_symbol_can_say():
+    """More than 32767 blocks in a row without AC coefficients: the run has to be split."""
+    pix = np.full((1456, 1464, 1), 97, np.uint8)
+    pix[:8, :8, 0] = np.arange(64, dtype=np.uint8).reshape(8, 8) * 3       # one busy block, then nothing
+    f = pcrgen.encode_pixels(pix, 1, 1, 90, "sequential")
+    _check_transcode(f)
+
+
+def test_transcode_argument_errors():
+    f = _files()[0]
+    (c0, _, _), _ = _decode_file(f)
+    with pytest.raises(pkg.PcrError) as e:
+        pkg.transcode_progressive(f, c0[:-64])
+    assert e.value.code == pkg.E_RANGE
+    with pytest.raises(pkg.PcrError) as e:
+        pkg.transcode_progressive(b"\xff\xd8\xff\xd9", c0)
+    assert e.value.code == pkg.E_FORMAT
