@@ -351,14 +351,16 @@ def transcode_progressive(src_jpeg, coef):
     return out[:int(written.value)].tobytes()
 
 
-def transcode_files(files, device=0):
+def transcode_files(files, device=0, threads=None):
     """The paper's encoding step for a list of JPEG files (baseline or progressive): their coefficients are decoded
     on the device, re-coded as progressive files on the host.  Returns the progressive files; record_write() groups them."""
     rec = record_write(files)
     with pcr_open(rec, device) as r:
         lay = r.coef_layout()
         coef = r.decode_coefficients(r.G).cpu().numpy()
-    return [transcode_progressive(f, coef[int(lay[i]):int(lay[i + 1])]) for i, f in enumerate(files)]
+    from concurrent.futures import ThreadPoolExecutor                 # (the C call releases the interpreter lock)
+    with ThreadPoolExecutor(threads or min(16, os.cpu_count() or 1)) as ex:
+        return list(ex.map(lambda i: transcode_progressive(files[i], coef[int(lay[i]):int(lay[i + 1])]), range(len(files))))
 
 
 class Loader:

@@ -198,6 +198,9 @@ public:
     std::vector<Token> tokens;
 
     void run() {
+        size_t blocks = 0;
+        for (int j = 0; j < S_.ns; j++) blocks += (size_t)F_.bw[S_.comp[j]] * F_.bh[S_.comp[j]];
+        tokens.reserve(blocks * (S_.Ss == 0 ? 1 : 12));
         if (S_.Ss == 0) dc_scan(); else ac_scan();
     }
 
@@ -206,6 +209,7 @@ private:
     // end-of-band run shared by the blocks of an AC scan, and the correction bits that wait behind it
     uint32_t eobrun_ = 0;
     std::vector<uint8_t> pending_;
+    std::vector<uint8_t> corr_;                                // correction bits met since the last symbol of the current block
 
     void push(uint8_t slot, uint8_t sym, int nbits, uint32_t bits) { tokens.push_back(Token{slot, sym, (uint8_t)nbits, (uint16_t)(bits & 0xFFFFu)}); }
     void push_bits(const std::vector<uint8_t>& b) {
@@ -287,7 +291,8 @@ private:
             if (mag[k] == 1) last_new = k;
         }
         int run = 0;
-        std::vector<uint8_t> corr;                             // correction bits met since the last symbol of this block
+        std::vector<uint8_t>& corr = corr_;
+        corr.clear();
         for (int k = S_.Ss; k <= S_.Se; k++) {
             if (mag[k] == 0) { run++; continue; }
             while (run > 15 && k <= last_new) {                // sixteen zeros, only where a new coefficient still follows
