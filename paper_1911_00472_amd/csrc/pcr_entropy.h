@@ -683,32 +683,30 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
 // ---------------------------------------------------------------------------------------
 // Sequential (baseline) scan: every block is a DC difference followed by AC run/size pairs up to an end of
 // block, the blocks of the components interleaved MCU by MCU (or one component alone).  The reader keeps,
-// for each of the 64 window offsets, the packed DC word and the packed AC word under the tables of every
-// scan component (once per distinct table); the serial part is the DC step of the DC first scan followed by
-// the symbol loop of the AC first scan over the band 1..63, with the component's words.
+// for each of the 64 window offsets, the packed AC word under ONE table, that of the component being decoded;
+// when the next block belongs to a component with another AC table the words of the current window are looked
+// up again (twice per MCU of a colour image).  The DC symbol, one per block, is decoded by hand at its
+// position.  The serial part is then the DC step of the DC first scan followed by the symbol loop of the AC
+// first scan over the band 1..63.
 // ---------------------------------------------------------------------------------------
 struct SeqWindowReader {
     StreamPtr p;
-    const DcTab* dtab[kMaxComp];
-    const AcTab* atab[kMaxComp];
+    const AcTab* atab;                            // table the lanes' words are for
     uint32_t w0, w1, w2, n0, n1;
     uint32_t o, wbase, mis_bits, total_bits, lane;
-    uint32_t vdc[kMaxComp], vac[kMaxComp];       // this lane's packed words under the tables of scan component j
+    uint32_t vac;                                 // this lane's packed AC word
     uint32_t nocode;
-    int ncomp;
     const uint32_t* g;
     uint32_t vnext;
 
-    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const DcTab* d0, const DcTab* d1, const DcTab* d2,
-                     const AcTab* a0, const AcTab* a1, const AcTab* a2, int ncomponents, uint32_t lane_id) {
-        dtab[0] = d0; dtab[1] = d1; dtab[2] = d2; atab[0] = a0; atab[1] = a1; atab[2] = a2; ncomp = ncomponents; lane = lane_id;
+    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const AcTab* a0, uint32_t lane_id) {
+        atab = a0; lane = lane_id;
         mis_bits = (byte_off & 3) * 8;
         p = stream_ptr(words + (byte_off >> 2));
         w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
         g = words + (byte_off >> 2) + 5;
         o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits; nocode = 0;
-        vdc[0] = vdc[1] = vdc[2] = 0; vac[0] = vac[1] = vac[2] = 0;
-        vnext = 0;
+        vac = 0; vnext = 0;
         fetch_next();
         fill();
     }
@@ -727,70 +725,55 @@ struct SeqWindowReader {
         p += 2; g += 2; o -= 64; wbase += 64;
         fetch_next();
     }
-    PCR_HD uint32_t dc_word_of(const DcTab* t, uint32_t win) const { const uint32_t e = t->lut[win >> 24]; return e != 0xFF ? pack_dc(e, win) : 0; }
-    PCR_HD uint32_t ac_word_of(const AcTab* t, uint32_t win) const { return finish_packed(t->lutp[win >> 24], win, true); }
     PCR_HD void fill() {
 #if defined(__HIP_DEVICE_COMPILE__)
         const uint32_t win = bits_at(w0, w1, w2, (int)lane);
-        vdc[0] = dc_word_of(dtab[0], win);
-        vac[0] = ac_word_of(atab[0], win);
-        if (ncomp > 1) {
-            vdc[1] = dtab[1] == dtab[0] ? vdc[0] : dc_word_of(dtab[1], win);
-            vac[1] = atab[1] == atab[0] ? vac[0] : ac_word_of(atab[1], win);
-        }
-        if (ncomp > 2) {
-            vdc[2] = dtab[2] == dtab[1] ? vdc[1] : (dtab[2] == dtab[0] ? vdc[0] : dc_word_of(dtab[2], win));
-            vac[2] = atab[2] == atab[1] ? vac[1] : (atab[2] == atab[0] ? vac[0] : ac_word_of(atab[2], win));
-        }
+        vac = finish_packed(atab->lutp[win >> 24], win, true);
 #endif
     }
+    PCR_HD void use_table(const AcTab* t) { if (t != atab) { atab = t; fill(); } }
     PCR_HD bool exhausted() const { return o >= 64; }
     PCR_HD void refill() {
         do slide(); while (o >= 64);
         fill();
     }
-    // packed DC word at the current position for scan component J; 0 (and `nocode` raised) where there is no code
-    template <int J> PCR_HD uint32_t dc_word() {
-        uint32_t info;
-#if defined(__HIP_DEVICE_COMPILE__)
-        info = (uint32_t)__builtin_amdgcn_readlane((int)vdc[J], (int)o);
-#else
-        info = dc_word_of(dtab[J], bits_at(w0, w1, w2, (int)o));
-#endif
-        if (__builtin_expect(info == 0, 0)) {
-            const uint32_t win = bits_at(w0, w1, w2, (int)o);
-            const uint32_t e = dc_code(dtab[J], win);
-            info = uni(e ? pack_dc(e, win) : 0u);
-            nocode |= uni(e ? 0u : 1u);
-        }
-        return info;
+    // packed DC word (pack_dc) of the symbol at the current position; 0 (and `nocode` raised) where there is no code
+    PCR_HD uint32_t dc_word(const DcTab* t) {
+        const uint32_t win = bits_at(w0, w1, w2, (int)o);
+        const uint32_t e = dc_code(t, win);
+        nocode |= uni(e ? 0u : 1u);
+        return uni(e ? pack_dc(e, win) : 0u);                  // (table reads come back in vector registers)
     }
-    // packed AC word of window offset `off` for scan component J; kSymMiss where no short code starts
-    template <int J> PCR_HD uint32_t ac_lookup(uint32_t off) const {
+    // packed AC word of window offset `off`; kSymMiss where no short code starts
+    PCR_HD uint32_t ac_lookup(uint32_t off) const {
 #if defined(__HIP_DEVICE_COMPILE__)
-        return (uint32_t)__builtin_amdgcn_readlane((int)vac[J], (int)off);
+        return (uint32_t)__builtin_amdgcn_readlane((int)vac, (int)off);
 #else
-        return ac_word_of(atab[J], bits_at(w0, w1, w2, (int)off));
-#endif
-    }
-    template <int J> PCR_HD uint32_t ac_resolve(uint32_t off) const {
         const uint32_t win = bits_at(w0, w1, w2, (int)off);
-        const uint32_t e = ac_long_code(atab[J], win);
+        return finish_packed(atab->lutp[win >> 24], win, true);
+#endif
+    }
+    PCR_HD uint32_t ac_resolve(uint32_t off) const {
+        const uint32_t win = bits_at(w0, w1, w2, (int)off);
+        const uint32_t e = ac_long_code(atab, win);
         return uni(e ? pack_symbol(e, win, true) : kSymInvalid);
     }
     PCR_HD void consume(uint32_t n) { o += n; }
     PCR_HD uint32_t overrun_bit() const { return (total_bits - (wbase + o)) >> 31; }
 };
 
-// One block of scan component J at element e (its DC), coefficients in zig-zag order behind it.
-template <int J>
-PCR_HD void sequential_block(SeqWindowReader* wr, CoefSink* sink, int* pred, uint32_t e, uint32_t* bad) {
+// Tables of the scan's components (pointers into LDS on the device).
+struct SeqTables { const DcTab* dc[kMaxComp]; const AcTab* ac[kMaxComp]; };
+
+// One block at element e (its DC), coefficients in zig-zag order behind it.
+PCR_HD void sequential_block(SeqWindowReader* wr, CoefSink* sink, const DcTab* dt, const AcTab* at, int* pred, uint32_t e, uint32_t* bad) {
     if (wr->exhausted()) {
         *bad |= wr->overrun_bit();
         wr->refill();
         sink->flush();
     }
-    uint32_t info = wr->template dc_word<J>();
+    wr->use_table(at);
+    uint32_t info = wr->dc_word(dt);
     *pred += (int32_t)info >> 16;
     sink->emit(wr->o, e, (int)(((uint32_t)*pred << 16) | kSymCoef));
     wr->consume((info >> 8) & 63);
@@ -804,7 +787,7 @@ PCR_HD void sequential_block(SeqWindowReader* wr, CoefSink* sink, int* pred, uin
             sink->flush();
         }
         do {
-            info = wr->template ac_lookup<J>(wr->o);
+            info = wr->ac_lookup(wr->o);
             kb += info & 127u;
             sink->emit(wr->o, base_b + kb, (int)info);
             wr->consume((info >> 8) & 63);
@@ -812,7 +795,7 @@ PCR_HD void sequential_block(SeqWindowReader* wr, CoefSink* sink, int* pred, uin
         if (kb >= 64) {
             if (info & kSymSpecial) {                        // a code longer than 8 bits (or none): the same step by hand
                 kb -= kSymMiss & 127;
-                info = wr->template ac_resolve<J>(wr->o);
+                info = wr->ac_resolve(wr->o);
                 if (info == kSymInvalid) *bad |= 1u;
                 kb += info & 127u;
                 sink->emit(wr->o, base_b + kb, (int)info);
@@ -827,13 +810,13 @@ PCR_HD void sequential_block(SeqWindowReader* wr, CoefSink* sink, int* pred, uin
 }
 
 template <int J>
-PCR_HD void sequential_component(SeqWindowReader* wr, const LaneScan& ls, CoefSink* sink, uint32_t mx, uint32_t my, int* pred, uint32_t* bad) {
+PCR_HD void sequential_component(SeqWindowReader* wr, const LaneScan& ls, const SeqTables& tb, CoefSink* sink, uint32_t mx, uint32_t my, int* pred, uint32_t* bad) {
     const uint32_t hs = ls.ns > 1 ? ls.hs[J] : 1, vs = ls.ns > 1 ? ls.vs[J] : 1, bw = ls.bw[J];
     uint32_t rowe = ls.poff[J] + ((my * vs) * bw + mx * hs) * 64;
     for (uint32_t by = 0; by < vs; by++) {
         uint32_t e = rowe;
         for (uint32_t bx = 0; bx < hs; bx++) {
-            if (!*bad) sequential_block<J>(wr, sink, pred, e, bad);      // (stop at the first damaged block)
+            if (!*bad) sequential_block(wr, sink, tb.dc[J], tb.ac[J], pred, e, bad);      // (stop at the first damaged block)
             *bad |= wr->nocode;
             e += 64;
         }
@@ -842,15 +825,16 @@ PCR_HD void sequential_component(SeqWindowReader* wr, const LaneScan& ls, CoefSi
 }
 
 // The sink's plane is the image's coefficient buffer; ls.poff[j] locates the plane of scan component j in it.
-PCR_HD int decode_sequential(SeqWindowReader* wr, const LaneScan& ls, CoefSink* sink) {
+// The reader must have been initialised with tb.ac[0].
+PCR_HD int decode_sequential(SeqWindowReader* wr, const LaneScan& ls, const SeqTables& tb, CoefSink* sink) {
     int pred0 = 0, pred1 = 0, pred2 = 0;
     uint32_t my = ls.mcu0 / ls.mcu_w, mx = ls.mcu0 % ls.mcu_w;
     uint32_t bad = 0;
     uint32_t m = ls.mcu0;
     while (m < ls.mcu1) {
-        sequential_component<0>(wr, ls, sink, mx, my, &pred0, &bad);
-        if (ls.ns > 1) sequential_component<1>(wr, ls, sink, mx, my, &pred1, &bad);
-        if (ls.ns > 2) sequential_component<2>(wr, ls, sink, mx, my, &pred2, &bad);
+        sequential_component<0>(wr, ls, tb, sink, mx, my, &pred0, &bad);
+        if (ls.ns > 1) sequential_component<1>(wr, ls, tb, sink, mx, my, &pred1, &bad);
+        if (ls.ns > 2) sequential_component<2>(wr, ls, tb, sink, mx, my, &pred2, &bad);
         if (++mx == ls.mcu_w) { mx = 0; my++; }
         m = bad ? ls.mcu1 : m + 1;
     }

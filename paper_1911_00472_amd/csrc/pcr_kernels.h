@@ -336,12 +336,14 @@ __global__ void __launch_bounds__(kEntropyLanes) k_sequential(DevRecord R, const
     __syncthreads();
     for (int t = 0; t < na; t++) actab_pack(&atabs[t], true, threadIdx.x, kEntropyLanes);
     __syncthreads();
+    SeqTables tb;
+    tb.dc[0] = &dtabs[0]; tb.dc[1] = &dtabs[uni(dj1)]; tb.dc[2] = &dtabs[uni(dj2)];
+    tb.ac[0] = &atabs[0]; tb.ac[1] = &atabs[uni(aj1)]; tb.ac[2] = &atabs[uni(aj2)];
     SeqWindowReader wr;
-    wr.init(L.words, L.byte_off, L.nbytes, &dtabs[0], &dtabs[uni(dj1)], &dtabs[uni(dj2)], &atabs[0], &atabs[uni(aj1)], &atabs[uni(aj2)],
-            L.ls.ns, threadIdx.x);
+    wr.init(L.words, L.byte_off, L.nbytes, tb.ac[0], threadIdx.x);
     CoefSink sink;
     sink.init(L.base, L.base_elems, 0);
-    const int rc = decode_sequential(&wr, L.ls, &sink);
+    const int rc = decode_sequential(&wr, L.ls, tb, &sink);
     if (rc != kOk) R.status[un.img] = rc;
 }
 

@@ -84,10 +84,12 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                     dctab_build(&dt[q], rec + sd.dc_off[q]);
                     actab_build(&at[q], rec + sd.ac_offc[q]); actab_pack(&at[q], true, 0, 1);
                 }
+                SeqTables tb;
+                for (int q = 0; q < kMaxComp; q++) { tb.dc[q] = &dt[q]; tb.ac[q] = &at[q]; }
                 SeqWindowReader sw;
-                sw.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &dt[0], &dt[1], &dt[2], &at[0], &at[1], &at[2], sd.ns, 0);
+                sw.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], tb.ac[0], 0);
                 CoefSink ssink; ssink.init(coef.data(), (uint32_t)coef.size(), 0);
-                rc = decode_sequential(&sw, ls, &ssink);
+                rc = decode_sequential(&sw, ls, tb, &ssink);
             } else if (sd.Ss == 0) {
                 std::vector<DcTab> dt(3);
                 for (int q = 0; q < sd.ns; q++) dctab_build(&dt[q], rec + sd.dc_off[q]);
