@@ -188,6 +188,20 @@ int pcr_crop_resize_batch(pcr_record* rec, const uint8_t* d_pixels, const pcr_cr
  * Errors: PCR_E_ARG (null argument), PCR_E_UNSUPPORTED (channel counts differ between images), PCR_E_NOMEM. */
 int pcr_msssim_batch(pcr_record* rec, const uint8_t* d_a, const uint8_t* d_b, float* d_scores, void* hip_stream);
 
+/* Choosing a scan group by image quality (Section 6.4: scan groups whose MSSIM against the full picture is high
+ * train about as well as the full data, so the score can pick the level of compression; Section 4.3 leaves the
+ * choice to a tuner).  Returns in *scan_group the lowest scan group whose mean pcr_msssim_batch score over the
+ * record's images, against the pictures of the highest available scan group, is at least min_mean_score (the
+ * highest available group itself if none is).  Scan groups are tried in order, each obtained from the one before
+ * by pcr_upgrade_batch, so the whole search costs about one full decode plus the scores.
+ *   d_work_a, d_work_b   device: two pixel buffers of work_capacity >= pcr_output_layout's total bytes each
+ *   d_scores             device: n floats (scores of the last group tried)
+ *   mean_by_group        host, optional: G floats; entry g-1 receives the mean score of group g, -1 if not tried
+ * Synchronous (each group's scores are read back); enqueues on hip_stream and waits for it.  Afterwards the
+ * handle's resident scan group is the last one tried and d_work_a holds its pixels.  Errors as the calls it makes. */
+int pcr_select_scan_group(pcr_record* rec, float min_mean_score, uint8_t* d_work_a, uint8_t* d_work_b, size_t work_capacity,
+                          float* d_scores, float* mean_by_group, int* scan_group, void* hip_stream);
+
 /* Decode and training tail in one call: pcr_decode_batch at scan_group followed by pcr_crop_resize_batch with the
  * same boxes, except that the pixel kernel skips every strip of an image that does not touch the image's box --
  * the tail reads nothing else.  d_pixels (device, layout of pcr_output_layout, pixel_capacity bytes) is working

@@ -50,6 +50,8 @@ SYMBOLS = {
     "pcr_record_write": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_size_t), _vp, ctypes.c_uint32, _vp, ctypes.c_size_t,
                                         ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_transcode_progressive": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.c_size_t, _vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_select_scan_group": (ctypes.c_int, [_vp, ctypes.c_float, _vp, _vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_float),
+                                             ctypes.POINTER(ctypes.c_int), _vp]),
     "pcr_prefix_length": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_loader_create": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]),
     "pcr_loader_destroy": (None, [_vp]),
@@ -243,6 +245,22 @@ class Record:
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_msssim_batch(self._h, a.data_ptr(), b.data_ptr(), out.data_ptr(), s), "pcr_msssim_batch")
         return out
+
+    def select_scan_group(self, min_mean_score, stream=None):
+        """Lowest scan group whose mean MS-SSIM against the highest available group reaches min_mean_score.
+        Returns (scan_group, {group: mean score} for the groups tried)."""
+        import torch
+        total = int(self.output_layout()[-1])
+        dev = "cuda:%d" % self.device
+        a = torch.empty(total, dtype=torch.uint8, device=dev)
+        b = torch.empty(total, dtype=torch.uint8, device=dev)
+        scores = torch.empty(self.n, dtype=torch.float32, device=dev)
+        means = (ctypes.c_float * self.G)()
+        k = ctypes.c_int(0)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_select_scan_group(self._h, float(min_mean_score), a.data_ptr(), b.data_ptr(), total, scores.data_ptr(), means,
+                                           ctypes.byref(k), s), "pcr_select_scan_group")
+        return int(k.value), {g + 1: float(means[g]) for g in range(self.G) if means[g] >= 0}
 
     def decode_crop_batch(self, k, crops, out_h, out_w, mean, inv_std, pixels=None, out=None, status=None, stream=None):
         """decode_batch(k) + crop_resize_batch in one call; the pixel kernel skips strips outside the boxes.

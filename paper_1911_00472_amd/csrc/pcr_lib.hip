@@ -851,6 +851,33 @@ int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int1
     return PCR_OK;
 }
 
+int pcr_select_scan_group(pcr_record* r, float min_mean_score, uint8_t* d_work_a, uint8_t* d_work_b, size_t work_capacity, float* d_scores,
+                          float* mean_by_group, int* scan_group, void* stream) {
+    if (!r || !d_work_a || !d_work_b || !d_scores || !scan_group) return PCR_E_ARG;
+    const uint32_t n = r->hdr.n;
+    const int top = (int)r->hdr.k_avail;
+    if (n == 0 || top < 1) return PCR_E_ARG;
+    if (mean_by_group) for (int g = 0; g < (int)r->hdr.G; g++) mean_by_group[g] = -1.0f;
+    int rc = pcr_decode_batch(r, top, d_work_b, work_capacity, stream, nullptr);              // the reference pictures
+    if (rc) return rc;
+    std::vector<float> host(n);
+    *scan_group = top;
+    for (int k = 1; k < top; k++) {
+        rc = k == 1 ? pcr_decode_batch(r, 1, d_work_a, work_capacity, stream, nullptr) : pcr_upgrade_batch(r, k, d_work_a, work_capacity, stream, nullptr);
+        if (!rc) rc = pcr_msssim_batch(r, d_work_a, d_work_b, d_scores, stream);
+        if (rc) return rc;
+        if (hipMemcpyAsync(host.data(), d_scores, n * sizeof(float), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess ||
+            hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return PCR_E_DEVICE;
+        double sum = 0; uint32_t cnt = 0;
+        for (uint32_t i = 0; i < n; i++) if (host[i] == host[i]) { sum += host[i]; cnt++; }   // (images too small to score are NaN)
+        const float mean = cnt ? (float)(sum / cnt) : 1.0f;
+        if (mean_by_group) mean_by_group[k - 1] = mean;
+        if (mean >= min_mean_score) { *scan_group = k; return PCR_OK; }
+    }
+    if (mean_by_group) mean_by_group[top - 1] = 1.0f;
+    return PCR_OK;
+}
+
 int pcr_probe_scalar_issue_rate(int device_id, int waves_per_cu, double* ginst_per_s) {
     if (!ginst_per_s || waves_per_cu < 1 || waves_per_cu > 32) return PCR_E_ARG;
     HIP_TRY(hipSetDevice(device_id));

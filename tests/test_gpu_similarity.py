@@ -124,3 +124,26 @@ def test_argument_errors(rgb_small):
         assert L.pcr_msssim_batch(r._h, None, x.data_ptr(), out.data_ptr(), None) == pkg.E_ARG
         assert L.pcr_msssim_batch(r._h, x.data_ptr(), x.data_ptr(), None, None) == pkg.E_ARG
         assert L.pcr_msssim_batch(None, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == pkg.E_ARG
+
+
+def test_scan_group_chosen_by_score():
+    """The search against the oracle's scores: the lowest group whose mean reaches the threshold."""
+    _torch()
+    records, _ = pcrgen.make_workload("rgb256", limit=6)
+    rec = records[0]
+    G = oracle.record_header(rec)["G"]
+    full = _pixels(rec, G)
+    want = {}
+    for k in range(1, G):
+        low = _pixels(rec, k)
+        want[k] = float(np.mean([oracle.msssim(a, b) for a, b in zip(low, full)]))
+    with pkg.Record(rec) as r:
+        k_all, means = r.select_scan_group(2.0)                  # unreachable: every group is tried
+        assert k_all == G and sorted(means) == list(range(1, G + 1)) and means[G] == 1.0
+        for k in range(1, G):
+            assert abs(means[k] - want[k]) <= 2e-3, (k, means[k], want[k])      # (the two decoders' pixels differ by up to 1 LSB)
+        for thr in (0.0, want[2] - 0.01, want[5] - 0.003, 0.999):
+            k_sel, tried = r.select_scan_group(thr)
+            expect = next((k for k in range(1, G) if means[k] >= thr), G)
+            assert k_sel == expect and max(tried) == k_sel and r.resident_scan_group() in (k_sel, G - 1)
+        assert r.select_scan_group(0.0)[0] == 1
