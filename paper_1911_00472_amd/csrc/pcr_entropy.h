@@ -267,6 +267,14 @@ PCR_HD void actab_pack(AcTab* t, bool first, uint32_t lane, uint32_t nlanes) {
     for (uint32_t i = lane; i < 256; i += nlanes) t->lutp[i] = packed_entry(t->lut[i], first);
 }
 
+// v[lane] = value, lane and value the same in every lane (the lane select travels in m0: a vector instruction of
+// this chip reads at most one scalar register besides it)
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ inline void write_lane(uint32_t& v, uint32_t value, uint32_t lane) {
+    asm volatile("s_mov_b32 m0, %2\n\tv_writelane_b32 %0, %1, m0" : "+v"(v) : "s"(value), "s"(lane) : "m0");
+}
+#endif
+
 struct WindowReader {
     StreamPtr p;                // words after n1
     const AcTab* tab;
@@ -339,6 +347,20 @@ struct WindowReader {
         do slide(); while (o >= 64);
         fill();
     }
+    // refill() that returns the lanes' words of the window being left (device; 0 on the host)
+    PCR_HD uint32_t refill_keep() {
+        const uint32_t old = vinfo;
+        refill();
+        return old;
+    }
+    // replaces the word of offset `off` (a symbol the serial part resolved by hand)
+    PCR_HD void set_word(uint32_t off, uint32_t word) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        write_lane(vinfo, word, off);
+#else
+        (void)off; (void)word;
+#endif
+    }
     PCR_HD void consume(uint32_t n) { o += n; }
     PCR_HD uint32_t position() const { return wbase + o - mis_bits; }       // bits consumed since the unit's first bit
     PCR_HD bool overrun() const { return wbase + o > total_bits; }
@@ -388,6 +410,31 @@ struct CoefSink {
 #if defined(__HIP_DEVICE_COMPILE__)
         if (((uint32_t)vval & kSymCoef) && vidx < limit) plane[vidx] = (int16_t)((vval >> 16) * (1 << Al));
         vval = 0;
+#endif
+    }
+};
+
+// IndexSink: the same for the AC first scan, with one register instead of two.  The lane of a window offset
+// already holds the packed word of the symbol that starts there (the reader's look-up), so all the serial
+// part has to leave in that lane is the element index; a lane stores if it was given an index and its word
+// carries a coefficient.  A symbol the serial part resolved by hand is written back into the reader's words.
+struct IndexSink {
+    int16_t* plane;
+    uint32_t limit;
+    int Al;
+    uint32_t vidx;                                            // device: this lane's element index, ~0 = none
+    PCR_HD void init(int16_t* p, uint32_t elems, int al) { plane = p; limit = elems; Al = al; vidx = ~0u; }
+    // host build: store at once (there are no lanes to hold anything back)
+    PCR_HD void store_now(uint32_t elem, uint32_t word) {
+        if ((word & kSymCoef) && elem < limit) plane[elem] = (int16_t)(((int32_t)word >> 16) * (1 << Al));
+    }
+    // words: the lanes' packed words of the window the indices belong to
+    PCR_HD void flush(uint32_t words) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        if ((words & kSymCoef) && vidx < limit) plane[vidx] = (int16_t)(((int32_t)words >> 16) * (1 << Al));
+        vidx = ~0u;
+#else
+        (void)words;
 #endif
     }
 };
@@ -618,7 +665,59 @@ PCR_HD uint64_t nz_mask_of_block(const int16_t* blk, int Ss, int Se) {
     return m;
 }
 
-PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink) {
+// Leaves element `elem` in the sink's lane `slot` (device), or stores the word's coefficient there at once (host).
+PCR_HD void sink_index(IndexSink* sink, uint32_t slot, uint32_t elem, uint32_t word) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    (void)word;
+    write_lane(sink->vidx, elem, slot);
+#else
+    (void)slot;
+    sink->store_now(elem, word);
+#endif
+}
+
+// The symbols that start inside the current window, one straight line each: a coefficient (run r, then the
+// value) and sixteen zeros (r = 15) both move on by r + 1; an end of band and an unresolved code move "past
+// everything".  Every symbol leaves the element it landed on in the sink's lane of its offset.  On the device
+// the loop is written out by hand: the window offset lives in m0, which is what selects the lane for the
+// cross-lane read and write, so that no instruction is spent on moving it there (ten instructions per
+// symbol: seven scalar, two cross-lane, the branch; 48 bytes, inside one line of the instruction cache).
+// Returns the word of the last symbol.
+PCR_HD uint32_t ac_first_symbols(WindowReader* wr, IndexSink* sink, uint32_t* kb_io, uint32_t base_b, uint32_t adv_mask, uint32_t tot_field) {
+    uint32_t info, kb = *kb_io, o = wr->o;
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint32_t t0, t1;
+    asm volatile(
+        "s_mov_b32 m0, %[o]\n\t"
+        ".p2align 6\n"
+        "1:\n\t"
+        "v_readlane_b32 %[info], %[vinfo], m0\n\t"
+        "s_and_b32 %[t0], %[info], %[advm]\n\t"
+        "s_bfe_u32 %[t1], %[info], %[totf]\n\t"
+        "s_add_i32 %[kb], %[kb], %[t0]\n\t"
+        "s_add_i32 %[t0], %[kb], %[base]\n\t"
+        "v_writelane_b32 %[vidx], %[t0], m0\n\t"
+        "s_add_i32 m0, m0, %[t1]\n\t"
+        "s_or_b32 %[t0], m0, %[kb]\n\t"
+        "s_cmp_lt_u32 %[t0], 64\n\t"
+        "s_cbranch_scc1 1b\n\t"
+        "s_mov_b32 %[o], m0"
+        : [info] "=&s"(info), [t0] "=&s"(t0), [t1] "=&s"(t1), [kb] "+s"(kb), [vidx] "+v"(sink->vidx), [o] "+s"(o)
+        : [vinfo] "v"(wr->vinfo), [base] "s"(base_b), [advm] "s"(adv_mask), [totf] "s"(tot_field)
+        : "m0", "scc");
+#else
+    do {
+        info = wr->lookup(o);
+        kb += info & adv_mask;
+        sink->store_now(base_b + kb, info);
+        o += bit_field(info, tot_field);
+    } while ((kb | o) < 64);
+#endif
+    wr->o = o; *kb_io = kb;
+    return info;
+}
+
+PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, IndexSink* sink) {
     const uint32_t Ss = (uint32_t)ls.Ss, Se = (uint32_t)ls.Se;
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     // Positions are kept biased: kb = (zig-zag position of the next candidate) + bias with bias = 63 - Se,
@@ -631,33 +730,22 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
     uint32_t base_b = (row * bw + col) * 64 - bias - 1;
     uint32_t kb = Ss + bias;
     uint32_t bad = 0;
-    // (constants of the symbol loop kept in registers: as literals they would make the loop longer than one
-    // 64-byte line of the instruction cache)
     const uint32_t adv_mask = opaque(127u), tot_field = opaque((6u << 16) | 8u);
     while (left != 0) {
         if (wr->exhausted()) {
             bad |= wr->overrun_bit();                        // never walk far beyond the unit's data
-            wr->refill();                                    // (before the flush: the wait for the words fetched a window ago must not include these stores)
-            sink->flush();
+            const uint32_t words = wr->refill_keep();        // (before the flush: the wait for the words fetched a window ago must not include these stores)
+            sink->flush(words);
         }
-        uint32_t info;
-        align_hot_loop();
-        do {                                                 // symbols that start inside the current window
-            // One straight line for every symbol: a coefficient (run r, then the value) and sixteen zeros
-            // (r = 15) both move on by r + 1; every packed word goes to the sink, which stores only those that
-            // carry a coefficient.  An end of band and an unresolved code move "past everything".
-            info = wr->lookup(wr->o);
-            kb += info & adv_mask;
-            sink->emit(wr->o, base_b + kb, (int)info);
-            wr->consume(bit_field(info, tot_field));
-        } while ((kb | wr->o) < 64);
+        uint32_t info = ac_first_symbols(wr, sink, &kb, base_b, adv_mask, tot_field);
         if (kb >= 64) {                                      // the block is finished, or the lanes left the code to us
             if (info & kSymSpecial) {                        // a code longer than 8 bits (or none): the same step by hand
                 kb -= kSymMiss & 127;
                 info = wr->resolve(wr->o);
                 if (info == kSymInvalid) bad |= 1u;          // no code at all
                 kb += info & 127;
-                sink->emit(wr->o, base_b + kb, (int)info);
+                wr->set_word(wr->o, info);                   // (the index left in this lane a moment ago is replaced too)
+                sink_index(sink, wr->o, base_b + kb, info);
                 wr->consume((info >> 8) & 63);
             }
             if (kb >= 64) {                                  // band complete, or end of band
@@ -675,7 +763,7 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, CoefSink* sink)
             }
         }
     }
-    sink->flush();
+    sink->flush(wr->vinfo);
     bad |= wr->overrun_bit();
     return bad ? kEFormat : kOk;
 }

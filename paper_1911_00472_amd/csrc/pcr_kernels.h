@@ -300,7 +300,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     __syncthreads();
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x, true);
-    CoefSink sink;
+    IndexSink sink;
     sink.init(L.plane[0], L.plane_elems[0], L.ls.Al);
     int rc = decode_ac_first(&wr, L.ls, &sink);
     if (rc != kOk) R.status[un.img] = rc;

@@ -100,7 +100,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 AcTab at; actab_build(&at, rec + sd.ac_off); actab_pack(&at, sd.Ah == 0, 0, 1);
                 WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &at, sd.Ah == 0, 0, sd.Ah == 0);
                 if (sd.Ah == 0) {
-                    CoefSink sink; sink.init(cpl[0], (uint32_t)plane * 64, ls.Al);
+                    IndexSink sink; sink.init(cpl[0], (uint32_t)plane * 64, ls.Al);
                     rc = decode_ac_first(&wr, ls, &sink);
                 } else {
                     HistPlanes hp; hp.n = sd.nhist; hp.coef = cpl[0];
