@@ -188,6 +188,41 @@ def test_corrupt_entropy_data_flags_the_image_only(rgb_small):
         assert st[victim] != 0 and not out[int(lay[victim]):int(lay[victim + 1])].any()
 
 
+def test_corrupt_baseline_data_flags_the_image_only():
+    """The same for a sequential file: damage in the middle of one image's only scan."""
+    files = _sequential_files()
+    rec = pcrgen.write_record(files)
+    torch = _torch()
+    off, ln, _, _, _ = oracle.record_index(rec)
+    with pkg.pcr_open(rec, 0) as r:
+        good = r.decode_batch(1).cpu().numpy()
+        lay = r.output_layout()
+    for victim, where in ((6, 0.5), (0, 0.9), (3, 0.7)):
+        a = bytearray(rec)
+        p = int(off[0, victim]) + int(int(ln[0, victim]) * where)
+        for j in range(24):
+            a[p + j] = 0x55 if a[p + j] != 0x55 else 0xAA
+        bad = bytes(a)
+        with pkg.pcr_open(bad, 0) as r:
+            status = torch.zeros(r.n, dtype=torch.int32, device="cuda")
+            out = r.decode_batch(1, status=status).cpu().numpy()
+            st = status.cpu().numpy()
+        for i in range(len(files)):
+            sl = slice(int(lay[i]), int(lay[i + 1]))
+            if i != victim:
+                assert st[i] == 0 and np.array_equal(out[sl], good[sl])
+        try:
+            oracle.decode_record_image(bad, victim, 1)
+            oracle_ok = True
+        except oracle.OracleError:
+            oracle_ok = False
+        sl = slice(int(lay[victim]), int(lay[victim + 1]))
+        if not oracle_ok:
+            assert st[victim] != 0
+        if st[victim] != 0:
+            assert not out[sl].any()                              # a flagged image is zero-filled
+
+
 def test_unsupported_and_malformed_images_are_refused_at_open():
     good = pcrgen.make_jpeg(1, 1, 40, 24, 3, 6.0, 2, 2, 90)
     arith = good.replace(b"\xff\xc2", b"\xff\xca", 1)
