@@ -147,14 +147,6 @@ PCR_HD uint32_t bit_field(uint32_t v, uint32_t packed) {
     return (v >> (packed & 31)) & ((1u << (packed >> 16)) - 1);
 #endif
 }
-// The code that follows starts on a 64-byte line of the instruction cache: a lone wavefront runs a short loop
-// visibly faster when the loop does not straddle lines (measured: 10 % on the AC first kernel).
-PCR_HD void align_hot_loop() {
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile(".p2align 6");
-#endif
-}
-
 // Resolve a code of more than 8 bits.  Returns (length << 8) | symbol, or 0 if it is no code.
 PCR_HD uint32_t ac_long_code(const AcTab* t, uint32_t win) {
     const uint32_t c16 = win >> 16;
@@ -681,7 +673,8 @@ PCR_HD void sink_index(IndexSink* sink, uint32_t slot, uint32_t elem, uint32_t w
 // everything".  Every symbol leaves the element it landed on in the sink's lane of its offset.  On the device
 // the loop is written out by hand: the window offset lives in m0, which is what selects the lane for the
 // cross-lane read and write, so that no instruction is spent on moving it there (ten instructions per
-// symbol: seven scalar, two cross-lane, the branch; 48 bytes, inside one line of the instruction cache).
+// symbol: seven scalar, two cross-lane, the branch; 48 bytes, placed on one 64-byte line of the instruction
+// cache: a lone wavefront runs a short loop visibly faster when it does not straddle lines, 10 % here).
 // Returns the word of the last symbol.
 PCR_HD uint32_t ac_first_symbols(WindowReader* wr, IndexSink* sink, uint32_t* kb_io, uint32_t base_b, uint32_t adv_mask, uint32_t tot_field) {
     uint32_t info, kb = *kb_io, o = wr->o;
