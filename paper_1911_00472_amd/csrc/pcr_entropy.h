@@ -259,6 +259,13 @@ PCR_HD void actab_pack(AcTab* t, bool first, uint32_t lane, uint32_t nlanes) {
     for (uint32_t i = lane; i < 256; i += nlanes) t->lutp[i] = packed_entry(t->lut[i], first);
 }
 
+// packed DC word: difference (16 bits, signed) << 16 | total bits (6) << 8 | category (4)
+PCR_HD uint32_t pack_dc(uint32_t e, uint32_t win) {          // e = (length << 4) | category, non-zero
+    const int len = (int)(e >> 4), t = (int)(e & 15);
+    const int diff = extend(field(win, len, t), t);
+    return ((uint32_t)(diff & 0xFFFF) << 16) | ((uint32_t)(len + t) << 8) | (uint32_t)t;
+}
+
 // v[lane] = value, lane and value the same in every lane (the lane select travels in m0: a vector instruction of
 // this chip reads at most one scalar register besides it)
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -338,6 +345,15 @@ struct WindowReader {
     PCR_HD void refill() {
         do slide(); while (o >= 64);
         fill();
+    }
+    // Sequential scans switch tables between blocks: the words of the current window are looked up again.
+    PCR_HD void use_table(const AcTab* t) { tab = t; fill(); }
+    // Sequential scans: packed DC word (pack_dc) of the symbol at the current position, decoded on the spot;
+    // 0 where the bits are no code of the table.
+    PCR_HD uint32_t dc_word(const DcTab* t) const {
+        const uint32_t win = bits_at(w0, w1, w2, (int)o);
+        const uint32_t e = dc_code(t, win);
+        return uni(e ? pack_dc(e, win) : 0u);                 // (table reads come back in vector registers)
     }
     // refill() that returns the lanes' words of the window being left (device; 0 on the host)
     PCR_HD uint32_t refill_keep() {
@@ -439,11 +455,6 @@ struct IndexSink {
 // into the reader would pin it to memory.
 // packed word: difference (16 bits, signed) << 16 | total bits (6) << 8 | category (4)
 // ---------------------------------------------------------------------------------------
-PCR_HD uint32_t pack_dc(uint32_t e, uint32_t win) {          // e = (length << 4) | category, non-zero
-    const int len = (int)(e >> 4), t = (int)(e & 15);
-    const int diff = extend(field(win, len, t), t);
-    return ((uint32_t)(diff & 0xFFFF) << 16) | ((uint32_t)(len + t) << 8) | (uint32_t)t;
-}
 
 struct DcWindowReader {
     StreamPtr p;
@@ -763,100 +774,34 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, IndexSink* sink
 
 // ---------------------------------------------------------------------------------------
 // Sequential (baseline) scan: every block is a DC difference followed by AC run/size pairs up to an end of
-// block, the blocks of the components interleaved MCU by MCU (or one component alone).  The reader keeps,
-// for each of the 64 window offsets, the packed AC word under ONE table, that of the component being decoded;
-// when the next block belongs to a component with another AC table the words of the current window are looked
-// up again (twice per MCU of a colour image).  The DC symbol, one per block, is decoded by hand at its
-// position.  The serial part is then the DC step of the DC first scan followed by the symbol loop of the AC
-// first scan over the band 1..63.
+// block, the blocks of the components interleaved MCU by MCU (or one component alone).  It is read with the
+// AC first scan's reader and symbol loop over the band 1..63: the lanes hold the packed AC word of every
+// window offset under ONE table, that of the component being decoded; when the next block belongs to a
+// component with another AC table the words of the current window are looked up again (twice per MCU of a
+// colour image).  The DC symbol, one per block, is decoded by hand at its position and its word (the running
+// DC value) put into the lane of its offset like any other coefficient.
 // ---------------------------------------------------------------------------------------
-struct SeqWindowReader {
-    StreamPtr p;
-    const AcTab* atab;                            // table the lanes' words are for
-    uint32_t w0, w1, w2, n0, n1;
-    uint32_t o, wbase, mis_bits, total_bits, lane;
-    uint32_t vac;                                 // this lane's packed AC word
-    uint32_t nocode;
-    const uint32_t* g;
-    uint32_t vnext;
-
-    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const AcTab* a0, uint32_t lane_id) {
-        atab = a0; lane = lane_id;
-        mis_bits = (byte_off & 3) * 8;
-        p = stream_ptr(words + (byte_off >> 2));
-        w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
-        g = words + (byte_off >> 2) + 5;
-        o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits; nocode = 0;
-        vac = 0; vnext = 0;
-        fetch_next();
-        fill();
-    }
-    PCR_HD void fetch_next() {
-#if defined(__HIP_DEVICE_COMPILE__)
-        vnext = g[lane & 1];
-#endif
-    }
-    PCR_HD void slide() {
-        w0 = w2; w1 = n0; w2 = n1;
-#if defined(__HIP_DEVICE_COMPILE__)
-        n0 = (uint32_t)__builtin_amdgcn_readlane((int)vnext, 0); n1 = (uint32_t)__builtin_amdgcn_readlane((int)vnext, 1);
-#else
-        n0 = p[0]; n1 = p[1];
-#endif
-        p += 2; g += 2; o -= 64; wbase += 64;
-        fetch_next();
-    }
-    PCR_HD void fill() {
-#if defined(__HIP_DEVICE_COMPILE__)
-        const uint32_t win = bits_at(w0, w1, w2, (int)lane);
-        vac = finish_packed(atab->lutp[win >> 24], win, true);
-#endif
-    }
-    PCR_HD void use_table(const AcTab* t) { if (t != atab) { atab = t; fill(); } }
-    PCR_HD bool exhausted() const { return o >= 64; }
-    PCR_HD void refill() {
-        do slide(); while (o >= 64);
-        fill();
-    }
-    // packed DC word (pack_dc) of the symbol at the current position; 0 (and `nocode` raised) where there is no code
-    PCR_HD uint32_t dc_word(const DcTab* t) {
-        const uint32_t win = bits_at(w0, w1, w2, (int)o);
-        const uint32_t e = dc_code(t, win);
-        nocode |= uni(e ? 0u : 1u);
-        return uni(e ? pack_dc(e, win) : 0u);                  // (table reads come back in vector registers)
-    }
-    // packed AC word of window offset `off`; kSymMiss where no short code starts
-    PCR_HD uint32_t ac_lookup(uint32_t off) const {
-#if defined(__HIP_DEVICE_COMPILE__)
-        return (uint32_t)__builtin_amdgcn_readlane((int)vac, (int)off);
-#else
-        const uint32_t win = bits_at(w0, w1, w2, (int)off);
-        return finish_packed(atab->lutp[win >> 24], win, true);
-#endif
-    }
-    PCR_HD uint32_t ac_resolve(uint32_t off) const {
-        const uint32_t win = bits_at(w0, w1, w2, (int)off);
-        const uint32_t e = ac_long_code(atab, win);
-        return uni(e ? pack_symbol(e, win, true) : kSymInvalid);
-    }
-    PCR_HD void consume(uint32_t n) { o += n; }
-    PCR_HD uint32_t overrun_bit() const { return (total_bits - (wbase + o)) >> 31; }
-};
-
 // Tables of the scan's components (pointers into LDS on the device).
 struct SeqTables { const DcTab* dc[kMaxComp]; const AcTab* ac[kMaxComp]; };
 
 // One block at element e (its DC), coefficients in zig-zag order behind it.
-PCR_HD void sequential_block(SeqWindowReader* wr, CoefSink* sink, const DcTab* dt, const AcTab* at, int* pred, uint32_t e, uint32_t* bad) {
+PCR_HD void sequential_block(WindowReader* wr, IndexSink* sink, const DcTab* dt, const AcTab* at, int* pred, uint32_t e, uint32_t* bad,
+                             uint32_t adv_mask, uint32_t tot_field) {
     if (wr->exhausted()) {
         *bad |= wr->overrun_bit();
-        wr->refill();
-        sink->flush();
+        const uint32_t words = wr->refill_keep();
+        sink->flush(words);
     }
-    wr->use_table(at);
+    if (at != wr->tab) {                                     // (what the lanes still hold goes out before their words change)
+        sink->flush(wr->vinfo);
+        wr->use_table(at);
+    }
     uint32_t info = wr->dc_word(dt);
+    if (info == 0) *bad |= 1u;                               // no code at all
     *pred += (int32_t)info >> 16;
-    sink->emit(wr->o, e, (int)(((uint32_t)*pred << 16) | kSymCoef));
+    const uint32_t dcw = ((uint32_t)*pred << 16) | kSymCoef;
+    wr->set_word(wr->o, dcw);
+    sink_index(sink, wr->o, e, dcw);
     wr->consume((info >> 8) & 63);
     // kb: one past the zig-zag position the last symbol landed on (the band 1..63 needs no bias)
     uint32_t kb = 1;
@@ -864,22 +809,18 @@ PCR_HD void sequential_block(SeqWindowReader* wr, CoefSink* sink, const DcTab* d
     while (kb < 64) {
         if (wr->exhausted()) {
             *bad |= wr->overrun_bit();
-            wr->refill();
-            sink->flush();
+            const uint32_t words = wr->refill_keep();
+            sink->flush(words);
         }
-        do {
-            info = wr->ac_lookup(wr->o);
-            kb += info & 127u;
-            sink->emit(wr->o, base_b + kb, (int)info);
-            wr->consume((info >> 8) & 63);
-        } while ((kb | wr->o) < 64);
+        info = ac_first_symbols(wr, sink, &kb, base_b, adv_mask, tot_field);
         if (kb >= 64) {
             if (info & kSymSpecial) {                        // a code longer than 8 bits (or none): the same step by hand
                 kb -= kSymMiss & 127;
-                info = wr->ac_resolve(wr->o);
+                info = wr->resolve(wr->o);
                 if (info == kSymInvalid) *bad |= 1u;
                 kb += info & 127u;
-                sink->emit(wr->o, base_b + kb, (int)info);
+                wr->set_word(wr->o, info);
+                sink_index(sink, wr->o, base_b + kb, info);
                 wr->consume((info >> 8) & 63);
             }
             if (kb >= 64) {
@@ -891,14 +832,14 @@ PCR_HD void sequential_block(SeqWindowReader* wr, CoefSink* sink, const DcTab* d
 }
 
 template <int J>
-PCR_HD void sequential_component(SeqWindowReader* wr, const LaneScan& ls, const SeqTables& tb, CoefSink* sink, uint32_t mx, uint32_t my, int* pred, uint32_t* bad) {
+PCR_HD void sequential_component(WindowReader* wr, const LaneScan& ls, const SeqTables& tb, IndexSink* sink, uint32_t mx, uint32_t my, int* pred,
+                                 uint32_t* bad, uint32_t adv_mask, uint32_t tot_field) {
     const uint32_t hs = ls.ns > 1 ? ls.hs[J] : 1, vs = ls.ns > 1 ? ls.vs[J] : 1, bw = ls.bw[J];
     uint32_t rowe = ls.poff[J] + ((my * vs) * bw + mx * hs) * 64;
     for (uint32_t by = 0; by < vs; by++) {
         uint32_t e = rowe;
         for (uint32_t bx = 0; bx < hs; bx++) {
-            if (!*bad) sequential_block(wr, sink, tb.dc[J], tb.ac[J], pred, e, bad);      // (stop at the first damaged block)
-            *bad |= wr->nocode;
+            if (!*bad) sequential_block(wr, sink, tb.dc[J], tb.ac[J], pred, e, bad, adv_mask, tot_field);      // (stop at the first damaged block)
             e += 64;
         }
         rowe += bw * 64;
@@ -906,20 +847,21 @@ PCR_HD void sequential_component(SeqWindowReader* wr, const LaneScan& ls, const 
 }
 
 // The sink's plane is the image's coefficient buffer; ls.poff[j] locates the plane of scan component j in it.
-// The reader must have been initialised with tb.ac[0].
-PCR_HD int decode_sequential(SeqWindowReader* wr, const LaneScan& ls, const SeqTables& tb, CoefSink* sink) {
+// The reader must have been initialised with tb.ac[0] as a first-scan reader.
+PCR_HD int decode_sequential(WindowReader* wr, const LaneScan& ls, const SeqTables& tb, IndexSink* sink) {
     int pred0 = 0, pred1 = 0, pred2 = 0;
     uint32_t my = ls.mcu0 / ls.mcu_w, mx = ls.mcu0 % ls.mcu_w;
     uint32_t bad = 0;
     uint32_t m = ls.mcu0;
+    const uint32_t adv_mask = opaque(127u), tot_field = opaque((6u << 16) | 8u);
     while (m < ls.mcu1) {
-        sequential_component<0>(wr, ls, tb, sink, mx, my, &pred0, &bad);
-        if (ls.ns > 1) sequential_component<1>(wr, ls, tb, sink, mx, my, &pred1, &bad);
-        if (ls.ns > 2) sequential_component<2>(wr, ls, tb, sink, mx, my, &pred2, &bad);
+        sequential_component<0>(wr, ls, tb, sink, mx, my, &pred0, &bad, adv_mask, tot_field);
+        if (ls.ns > 1) sequential_component<1>(wr, ls, tb, sink, mx, my, &pred1, &bad, adv_mask, tot_field);
+        if (ls.ns > 2) sequential_component<2>(wr, ls, tb, sink, mx, my, &pred2, &bad, adv_mask, tot_field);
         if (++mx == ls.mcu_w) { mx = 0; my++; }
         m = bad ? ls.mcu1 : m + 1;
     }
-    sink->flush();
+    sink->flush(wr->vinfo);
     bad |= wr->overrun_bit();
     return bad ? kEFormat : kOk;
 }

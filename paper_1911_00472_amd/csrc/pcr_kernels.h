@@ -339,9 +339,9 @@ __global__ void __launch_bounds__(kEntropyLanes) k_sequential(DevRecord R, const
     SeqTables tb;
     tb.dc[0] = &dtabs[0]; tb.dc[1] = &dtabs[uni(dj1)]; tb.dc[2] = &dtabs[uni(dj2)];
     tb.ac[0] = &atabs[0]; tb.ac[1] = &atabs[uni(aj1)]; tb.ac[2] = &atabs[uni(aj2)];
-    SeqWindowReader wr;
-    wr.init(L.words, L.byte_off, L.nbytes, tb.ac[0], threadIdx.x);
-    CoefSink sink;
+    WindowReader wr;
+    wr.init(L.words, L.byte_off, L.nbytes, tb.ac[0], true, threadIdx.x, true);
+    IndexSink sink;
     sink.init(L.base, L.base_elems, 0);
     const int rc = decode_sequential(&wr, L.ls, tb, &sink);
     if (rc != kOk) R.status[un.img] = rc;

@@ -86,9 +86,9 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 }
                 SeqTables tb;
                 for (int q = 0; q < kMaxComp; q++) { tb.dc[q] = &dt[q]; tb.ac[q] = &at[q]; }
-                SeqWindowReader sw;
-                sw.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], tb.ac[0], 0);
-                CoefSink ssink; ssink.init(coef.data(), (uint32_t)coef.size(), 0);
+                WindowReader sw;
+                sw.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], tb.ac[0], true, 0, true);
+                IndexSink ssink; ssink.init(coef.data(), (uint32_t)coef.size(), 0);
                 rc = decode_sequential(&sw, ls, tb, &ssink);
             } else if (sd.Ss == 0) {
                 std::vector<DcTab> dt(3);
