@@ -421,6 +421,49 @@ def main():
             h.close()
         del seq_handles, seq_records, seq_files
 
+    # ---- the same images with restart intervals in every scan: more independent streams per image ----
+    with_restarts = None
+    if not args.no_baseline_files:
+        RI = 512
+        rst_records, rst_files = pcrgen.make_workload("imagenet_like", limit=args.images, restart=RI)
+        rst_handles = [pkg.pcr_open(r, 0) for r in rst_records]
+        torch.cuda.synchronize()
+        rst_rates = {}
+        for k in SCAN_GROUPS:
+            def rst_step():
+                for h, o, st in zip(rst_handles, outs, streams):
+                    h.decode_batch(k, out=o, stream=st.cuda_stream)
+            rst_step(); rst_step()
+            torch.cuda.synchronize()
+            if k == HEADLINE_K:
+                host = outs[0].cpu().numpy()
+                lay_r = rst_handles[0].output_layout()
+                _, p0, info = oracle.decode_record_image(rst_records[0], 3, k, want_coef=False)
+                got = host[int(lay_r[3]):int(lay_r[4])].reshape(info.H, info.W, info.nc).astype(int)
+                assert np.abs(got - p0).max() <= 1, "parity check failed for the image with restart intervals"
+            reps_r = max(5, args.steps)
+            t = time.perf_counter()
+            for _ in range(reps_r):
+                rst_step()
+            torch.cuda.synchronize()
+            dt_r = (time.perf_counter() - t) / reps_r
+            rst_handles[0].enable_stage_timing(True)
+            for _ in range(3):
+                rst_handles[0].decode_batch(k, out=outs[0], stream=streams[0].cuda_stream)
+            torch.cuda.synchronize()
+            calls_r, alone_r = rst_handles[0].stage_ms_history()
+            rst_handles[0].enable_stage_timing(False)
+            rst_rates[str(k)] = {"images_per_s": n_img / dt_r, "ms_per_step": dt_r * 1e3,
+                                 "ms_one_record_alone": sum(v[0] for v in alone_r.values()) / calls_r}
+        with_restarts = {"files": "the same %d images, same scans, a restart marker every %d MCUs of each scan; mean %.1f kB (%.2f %% more bytes)"
+                                  % (n_img, RI, np.mean([len(f) for f in rst_files]) / 1e3, 100.0 * (sum(map(len, rst_files)) / float(ends[:, -1].sum()) - 1.0)),
+                         "per_scan_group": rst_rates,
+                         "note": "what an encoder that knows the decoder can add: each restart interval is a stream of its own, so one image's "
+                                 "scan is decoded by several wavefronts; not the headline workload (stock encoders write no restart markers)"}
+        for h in rst_handles:
+            h.close()
+        del rst_handles, rst_records, rst_files
+
     per_k = {}
     for k in SCAN_GROUPS:
         if k == args.scan_group:
@@ -513,6 +556,7 @@ def main():
         "training_tail": training_tail,
         "fidelity_estimate": fidelity_estimate,
         "baseline_sequential_files": baseline,
+        "with_restart_intervals": with_restarts,
     }
     for h in handles:
         h.close()

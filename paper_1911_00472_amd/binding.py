@@ -49,7 +49,8 @@ SYMBOLS = {
                                        ctypes.POINTER(ctypes.c_uint32)]),
     "pcr_record_write": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_size_t), _vp, ctypes.c_uint32, _vp, ctypes.c_size_t,
                                         ctypes.POINTER(ctypes.c_uint64)]),
-    "pcr_transcode_progressive": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.c_size_t, _vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_transcode_progressive": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.c_size_t, ctypes.c_uint32, _vp, ctypes.c_size_t,
+                                                 ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_select_scan_group": (ctypes.c_int, [_vp, ctypes.c_float, _vp, _vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_float),
                                              ctypes.POINTER(ctypes.c_int), _vp]),
     "pcr_prefix_length": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
@@ -352,24 +353,24 @@ def record_write(files, labels=None):
     return out.tobytes()
 
 
-def transcode_progressive(src_jpeg, coef):
+def transcode_progressive(src_jpeg, coef, restart_interval=0):
     """Progressive file (bytes) holding the quantised coefficients `coef` (int16 numpy array in the layout of
     coef_layout() for this one image) under the frame header and quantisation tables of src_jpeg."""
     src = np.frombuffer(src_jpeg, np.uint8)
     coef = np.ascontiguousarray(coef, np.int16)
     out = np.empty(src.size + src.size // 2 + 4096, np.uint8)
     written = ctypes.c_uint64(0)
-    rc = lib().pcr_transcode_progressive(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, out.ctypes.data_as(_vp), out.size,
-                                         ctypes.byref(written))
+    rc = lib().pcr_transcode_progressive(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, restart_interval,
+                                         out.ctypes.data_as(_vp), out.size, ctypes.byref(written))
     if rc == E_RANGE and written.value > out.size:
         out = np.empty(int(written.value), np.uint8)
-        rc = lib().pcr_transcode_progressive(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, out.ctypes.data_as(_vp), out.size,
-                                             ctypes.byref(written))
+        rc = lib().pcr_transcode_progressive(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, restart_interval,
+                                             out.ctypes.data_as(_vp), out.size, ctypes.byref(written))
     _check(rc, "pcr_transcode_progressive")
     return out[:int(written.value)].tobytes()
 
 
-def transcode_files(files, device=0, threads=None):
+def transcode_files(files, device=0, threads=None, restart_interval=0):
     """The paper's encoding step for a list of JPEG files (baseline or progressive): their coefficients are decoded
     on the device, re-coded as progressive files on the host.  Returns the progressive files; record_write() groups them."""
     rec = record_write(files)
@@ -378,7 +379,7 @@ def transcode_files(files, device=0, threads=None):
         coef = r.decode_coefficients(r.G).cpu().numpy()
     from concurrent.futures import ThreadPoolExecutor                 # (the C call releases the interpreter lock)
     with ThreadPoolExecutor(threads or min(16, os.cpu_count() or 1)) as ex:
-        return list(ex.map(lambda i: transcode_progressive(files[i], coef[int(lay[i]):int(lay[i + 1])]), range(len(files))))
+        return list(ex.map(lambda i: transcode_progressive(files[i], coef[int(lay[i]):int(lay[i + 1])], restart_interval), range(len(files))))
 
 
 class Loader:

@@ -114,8 +114,8 @@ inline void write_record(const RecordPlan& P, const void* const* files, const in
 // ---- progressive encoder --------------------------------------------------------------------------------
 // A scan is first turned into tokens (Huffman symbol of one of two table slots + appended bits, or appended
 // bits alone), the symbol counts give the scan its own optimal tables, then the tokens are written out.
-struct Token { uint8_t slot; uint8_t sym; uint8_t nbits; uint16_t bits; };   // slot 0/1: Huffman table of the scan; 2: bits only
-constexpr uint8_t kRawBits = 2;
+struct Token { uint8_t slot; uint8_t sym; uint8_t nbits; uint16_t bits; };   // slot 0/1: Huffman table of the scan; 2: bits only; 3: restart marker number sym
+constexpr uint8_t kRawBits = 2, kRestartMark = 3;
 
 struct HuffSpec { uint8_t counts[17]; uint8_t symbols[256]; int nsym; uint16_t code[256]; uint8_t size[256]; };
 
@@ -176,6 +176,7 @@ public:
         }
     }
     void finish() { if (have_) put((1u << (8 - have_)) - 1u, 8 - have_); }      // pad with 1-bits
+    void marker(uint8_t m) { finish(); out_->push_back(0xFF); out_->push_back(m); }
 private:
     std::vector<uint8_t>* out_;
     uint64_t acc_ = 0; int have_ = 0;
@@ -194,7 +195,8 @@ inline int bit_length(int v) { int n = 0; while (v) { n++; v >>= 1; } return n; 
 
 class ScanCoder {
 public:
-    ScanCoder(const Frame& F, const ScanSpec& S) : F_(F), S_(S) {}
+    // restart_mcus: MCUs of this scan per restart interval (0: no restart markers)
+    ScanCoder(const Frame& F, const ScanSpec& S, uint32_t restart_mcus) : F_(F), S_(S), ri_(restart_mcus) {}
     std::vector<Token> tokens;
 
     void run() {
@@ -206,6 +208,8 @@ public:
 
 private:
     const Frame& F_; const ScanSpec& S_;
+    uint32_t ri_, mcu_ = 0, marks_ = 0;                        // restart interval, MCUs begun, markers written
+    int pred_[kMaxComp] = {0, 0, 0};                           // DC predictions
     // end-of-band run shared by the blocks of an AC scan, and the correction bits that wait behind it
     uint32_t eobrun_ = 0;
     std::vector<uint8_t> pending_;
@@ -222,26 +226,36 @@ private:
     }
     const int16_t* block(int c, int row, int col) const { return F_.plane[c] + ((size_t)row * F_.bw[c] + col) * 64; }
 
+    // A restart interval ends: whatever is pending goes out, a marker follows, predictions start again.
+    void begin_mcu() {
+        if (ri_ && mcu_ && mcu_ % ri_ == 0) {
+            flush_eobrun();
+            push(kRestartMark, (uint8_t)(marks_++ & 7), 0, 0);
+            pred_[0] = pred_[1] = pred_[2] = 0;
+        }
+        mcu_++;
+    }
     template <class Fn> void for_each_block(Fn fn) {
         if (S_.ns > 1) {
-            for (int my = 0; my < F_.mcuy; my++) for (int mx = 0; mx < F_.mcux; mx++)
+            for (int my = 0; my < F_.mcuy; my++) for (int mx = 0; mx < F_.mcux; mx++) {
+                begin_mcu();
                 for (int j = 0; j < S_.ns; j++) {
                     const int c = S_.comp[j];
                     for (int by = 0; by < F_.vs[c]; by++) for (int bx = 0; bx < F_.hs[c]; bx++)
                         fn(j, c, block(c, my * F_.vs[c] + by, mx * F_.hs[c] + bx));
                 }
+            }
         } else {
             const int c = S_.comp[0];
-            for (int row = 0; row < F_.ch[c]; row++) for (int col = 0; col < F_.cw[c]; col++) fn(0, c, block(c, row, col));
+            for (int row = 0; row < F_.ch[c]; row++) for (int col = 0; col < F_.cw[c]; col++) { begin_mcu(); fn(0, c, block(c, row, col)); }
         }
     }
 
     void dc_scan() {
-        int pred[kMaxComp] = {0, 0, 0};
         for_each_block([&](int j, int c, const int16_t* b) {
             const int v = (int)b[0] >> S_.Al;                  // arithmetic shift: the point transform of DC
             if (S_.Ah == 0) {
-                int diff = v - pred[c]; pred[c] = v;
+                int diff = v - pred_[c]; pred_[c] = v;
                 const int nb = bit_length(diff < 0 ? -diff : diff);
                 push((uint8_t)(j == 0 ? 0 : 1), (uint8_t)nb, nb, (uint32_t)(diff < 0 ? diff - 1 : diff));
             } else {
@@ -354,8 +368,11 @@ inline std::vector<ScanSpec> default_script(int nc) {
 // src: a JPEG file (baseline or progressive) whose frame header and quantisation tables are kept; coef: its
 // quantised coefficients, component planes one after the other, each [bh][bw][64] in natural order over the
 // MCU-padded block grid.  Appends the progressive file to *out.
-inline int transcode_progressive(const uint8_t* src, size_t src_bytes, const int16_t* coef, size_t coef_count, std::vector<uint8_t>* out) {
+// restart_interval: MCUs of each scan between restart markers (0: none; a scan of one component counts its blocks).
+inline int transcode_progressive(const uint8_t* src, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
+                                 std::vector<uint8_t>* out) {
     if (src_bytes >= (1ull << 32)) return kEUnsupported;
+    if (restart_interval > 65535) return kERange;
     ParseState st;
     for (int a = 0; a < 2; a++) for (int b = 0; b < 4; b++) st.dht[a][b] = 0;
     st.ri = 0; st.have_frame = 0;
@@ -391,8 +408,12 @@ inline int transcode_progressive(const uint8_t* src, size_t src_bytes, const int
     put_be16(&o, (uint32_t)(8 + 3 * img.nc));
     o.push_back(8); put_be16(&o, img.H); put_be16(&o, img.W); o.push_back((uint8_t)img.nc);
     for (int c = 0; c < img.nc; c++) { o.push_back((uint8_t)F.cid[c]); o.push_back((uint8_t)((img.nc == 1 ? 1 : F.hs[c]) << 4 | (img.nc == 1 ? 1 : F.vs[c]))); o.push_back((uint8_t)F.tq[c]); }
+    if (restart_interval) {
+        o.push_back(0xFF); o.push_back(0xDD);
+        put_be16(&o, 4); put_be16(&o, restart_interval);
+    }
     for (const ScanSpec& S : default_script(img.nc)) {
-        ScanCoder coder(F, S);
+        ScanCoder coder(F, S, restart_interval);
         coder.run();
         uint32_t freq[2][256];
         memset(freq, 0, sizeof freq);
@@ -412,6 +433,7 @@ inline int transcode_progressive(const uint8_t* src, size_t src_bytes, const int
         o.push_back((uint8_t)S.Ss); o.push_back((uint8_t)S.Se); o.push_back((uint8_t)((S.Ah << 4) | S.Al));
         BitWriter bw(&o);
         for (const Token& t : coder.tokens) {
+            if (t.slot == kRestartMark) { bw.marker((uint8_t)(0xD0 + t.sym)); continue; }
             if (t.slot < kRawBits) bw.put(H[t.slot].code[t.sym], H[t.slot].size[t.sym]);
             bw.put(t.bits, t.nbits);
         }

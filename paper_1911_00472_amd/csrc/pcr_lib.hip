@@ -838,12 +838,12 @@ int pcr_record_write(const void* const* files, const size_t* sizes, const int32_
     return PCR_OK;
 }
 
-int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, void* out, size_t capacity,
-                              uint64_t* written) {
+int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
+                              void* out, size_t capacity, uint64_t* written) {
     if (!src_jpeg || !coef || !written) return PCR_E_ARG;
     std::vector<uint8_t> bytes;
     bytes.reserve(src_bytes + src_bytes / 4 + 1024);
-    const int rc = enc::transcode_progressive((const uint8_t*)src_jpeg, src_bytes, coef, coef_count, &bytes);
+    const int rc = enc::transcode_progressive((const uint8_t*)src_jpeg, src_bytes, coef, coef_count, restart_interval, &bytes);
     if (rc) return rc;
     *written = bytes.size();
     if (!out || capacity < bytes.size()) return PCR_E_RANGE;

@@ -219,24 +219,26 @@ def workload_shapes(name, seed=191100472, limit=None):
     return Ws, Hs
 
 
-def make_workload(name, seed=191100472, limit=None, threads=None, script=None):
+def make_workload(name, seed=191100472, limit=None, threads=None, script=None, restart=None):
     """Generate a workload: returns (records: list[bytes], files: list[bytes]).  `limit`
     keeps only the first `limit` images (records stay `per_record` long, the last may be short).
     script: None for the workload's progressive files; "sequential" encodes the same images (same quantised
-    coefficients) as baseline files, the non-progressive layout the paper compares against."""
+    coefficients) as baseline files, the non-progressive layout the paper compares against.
+    restart: overrides the workload's restart interval (MCU rows per interval in every scan; 0 = none)."""
     w = WORKLOADS[name]
     Ws, Hs = workload_shapes(name, seed, limit)
     n = len(Ws)
     hs, vs = w["sub"]
+    rst = w["restart"] if restart is None else restart          # restart interval in MCU rows of each scan (0: none)
     lib()
 
     def one(i):
         if script == "sequential":
-            return make_jpeg(_mix(seed, i), w["kind"], int(Ws[i]), int(Hs[i]), w["C"], w["sigma"], hs, vs, w["quality"], w["restart"], sequential=True)
+            return make_jpeg(_mix(seed, i), w["kind"], int(Ws[i]), int(Hs[i]), w["C"], w["sigma"], hs, vs, w["quality"], rst, sequential=True)
         if script is not None:
             pix = synth(_mix(seed, i), w["kind"], int(Ws[i]), int(Hs[i]), w["C"], w["sigma"])
-            return encode_pixels(pix, hs, vs, w["quality"], script, w["restart"])
-        return make_jpeg(_mix(seed, i), w["kind"], int(Ws[i]), int(Hs[i]), w["C"], w["sigma"], hs, vs, w["quality"], w["restart"])
+            return encode_pixels(pix, hs, vs, w["quality"], script, rst)
+        return make_jpeg(_mix(seed, i), w["kind"], int(Ws[i]), int(Hs[i]), w["C"], w["sigma"], hs, vs, w["quality"], rst)
 
     threads = threads or min(16, os.cpu_count() or 1)
     with ThreadPoolExecutor(threads) as ex:

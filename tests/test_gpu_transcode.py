@@ -29,3 +29,19 @@ def test_baseline_files_become_a_progressive_record():
     again = pkg.transcode_files(prog[:3])
     for f0, f1 in zip(prog[:3], again):
         assert f0 == f1
+
+
+def test_restart_intervals_written_by_the_transcoder_decode_the_same():
+    """The transcoder's restart markers split every scan into streams of their own; the pictures do not change."""
+    import torch
+    assert torch.cuda.is_available()
+    files = _sequential_files()
+    rec_b = pkg.record_write(files)
+    with pkg.pcr_open(rec_b, 0) as rb:
+        want = rb.decode_batch(1).cpu().numpy()
+    for ri in (5, 64):
+        prog = pkg.transcode_files(files, restart_interval=ri)
+        rec_p = pkg.record_write(prog)
+        with pkg.pcr_open(rec_p, 0) as rp:
+            assert np.array_equal(rp.decode_batch(10).cpu().numpy(), want)
+        _check_record(rec_p, (1, 6, 10), check_bytes=False)

@@ -88,10 +88,11 @@ def _covered(coef, info):
     return out
 
 
-def _check_transcode(f):
+def _check_transcode(f, restart_interval=0):
     from PIL import Image
     (c0, p0, info), _ = _decode_file(f)
-    t = pkg.transcode_progressive(f, c0)
+    t = pkg.transcode_progressive(f, c0, restart_interval)
+    assert (b"\xff\xdd\x00\x04" in t) == (restart_interval > 0)
     (c1, p1, info1), G1 = _decode_file(t)
     assert G1 == (10 if info.nc == 3 else 6)
     assert (info1.W, info1.H, info1.nc) == (info.W, info.H, info.nc)
@@ -113,12 +114,31 @@ def test_transcode_is_lossless_for_baseline_and_progressive_sources():
         _check_transcode(f)
 
 
+def test_transcode_with_restart_intervals():
+    """Restart markers every 1, 7 and 60 MCUs of each scan: predictions and end-of-band runs start again at each, the
+    pixels do not change, and the file grows by a few bytes per marker."""
+    files = _files()
+    for ri in (1, 7, 60):
+        for f in (files[0], files[4], files[6], files[9]):
+            t = _check_transcode(f, ri)
+            plain = pkg.transcode_progressive(f, _decode_file(f)[0][0])
+            assert len(t) > len(plain)
+            n_marks = sum(t.count(bytes([0xFF, 0xD0 + m])) for m in range(8))
+            info = _decode_file(f)[0][2]
+            assert (n_marks > 0) == (info.bw[0] * info.bh[0] > ri)    # (the smallest pictures have fewer blocks than the longest interval)
+    with pytest.raises(pkg.PcrError) as e:
+        pkg.transcode_progressive(files[0], _decode_file(files[0])[0][0], 70000)
+    assert e.value.code == pkg.E_RANGE
+
+
 def test_transcode_of_extreme_coefficient_planes(extreme_record):
     """Dense blocks, lone last coefficients, zero runs inside refinement scans, the largest sizes, end-of-band runs
     over hundreds of blocks: every path of the progressive coder."""
     _, files = extreme_record
-    for f in files:
+    for j, f in enumerate(files):
         _check_transcode(f)
+        if j % 3 == 0:
+            _check_transcode(f, 11)
 
 
 def test_transcode_end_of_band_run_longer_than_one_symbol_can_say():
