@@ -424,7 +424,7 @@ def main():
     # ---- the same images with restart intervals in every scan: more independent streams per image ----
     with_restarts = None
     if not args.no_baseline_files:
-        RI = 512
+        RI = 128
         rst_records, rst_files = pcrgen.make_workload("imagenet_like", limit=args.images, restart=RI)
         rst_handles = [pkg.pcr_open(r, 0) for r in rst_records]
         torch.cuda.synchronize()

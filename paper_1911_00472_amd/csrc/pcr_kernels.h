@@ -46,8 +46,10 @@ struct DevRecord {
     int16_t* coef;
     uint64_t* masks;
     int32_t* status;           // [n]
-    AcTab* tabs;               // Huffman tables of the AC refinement scans (written by phase 1, read by phase 2)
+    AcTab* tabs;               // Huffman tables of the AC scans: those of the refinement scans are written by phase 1 for phase 2;
+                               // with tabs_prebuilt, k_build_tables has written all of them before the entropy kernels start
     const uint32_t* tab_idx;   // [n][G] index into tabs
+    uint32_t tabs_prebuilt;    // set per call by the host (records whose scans have restart intervals)
 };
 
 // segment of a scan in the clean buffer: 4-byte aligned base (big-endian words)
@@ -286,6 +288,41 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     if (rc != kOk) R.status[un.img] = rc;
 }
 
+// The AC table of a unit's scan into LDS: copied from the pre-built one (k_build_tables), or built here from the
+// table definition in the record by one lane and packed by all.  Call with every lane of the wavefront.
+PCR_D void load_ac_table(const DevRecord& R, size_t ig, bool first, AcTab* tab) {
+    if (R.tabs_prebuilt) {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.tabs[R.tab_idx[ig]]);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(tab);
+        for (uint32_t e = threadIdx.x; e < sizeof(AcTab) / 4; e += kEntropyLanes) dst[e] = src[e];
+        __syncthreads();
+        return;
+    }
+    if (threadIdx.x == 0) actab_build(tab, R.rec + R.scan[ig].ac_off);
+    __syncthreads();
+    actab_pack(tab, first, threadIdx.x, kEntropyLanes);
+    __syncthreads();
+}
+
+// One wavefront per (image, scan): the scan's AC table, built once for all its restart intervals.
+// grid: (n, scans), scans k0 .. k0 + gridDim.y - 1.
+__global__ void __launch_bounds__(kEntropyLanes) k_build_tables(DevRecord R, uint32_t k0) {
+    __shared__ AcTab tab;
+    short_kernel_priority();
+    const uint32_t i = blockIdx.x, g = k0 + blockIdx.y;
+    if (R.status[i] != kOk || g >= R.img[i].nscans) return;
+    const size_t ig = (size_t)i * R.G + g;
+    const ScanDesc* sd = &R.scan[ig];
+    if (!sd->valid || sd->Ss == 0) return;                  // (DC scans and sequential scans build their own)
+    if (threadIdx.x == 0) actab_build(&tab, R.rec + sd->ac_off);
+    __syncthreads();
+    actab_pack(&tab, sd->Ah == 0, threadIdx.x, kEntropyLanes);
+    __syncthreads();
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(&tab);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(&R.tabs[R.tab_idx[ig]]);
+    for (uint32_t e = threadIdx.x; e < sizeof(AcTab) / 4; e += kEntropyLanes) dst[e] = src[e];
+}
+
 __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
         const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {
     __shared__ AcTab tab;
@@ -294,10 +331,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     unit_setup(R, un, clean32, &L);
     if (!L.ok) return;
     const size_t ig = (size_t)un.img * R.G + un.scan;
-    if (threadIdx.x == 0) actab_build(&tab, R.rec + R.scan[ig].ac_off);
-    __syncthreads();
-    actab_pack(&tab, true, threadIdx.x, kEntropyLanes);
-    __syncthreads();
+    load_ac_table(R, ig, true, &tab);
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x, true);
     IndexSink sink;
@@ -359,11 +393,8 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     if (!L.ok) return;
     const size_t ig = (size_t)un.img * R.G + un.scan;
     const ScanDesc* sd = &R.scan[ig];
-    if (threadIdx.x == 0) actab_build(&tab, R.rec + sd->ac_off);
-    __syncthreads();
-    actab_pack(&tab, false, threadIdx.x, kEntropyLanes);
-    __syncthreads();
-    if (un.interval == 0) {                                 // phase 2 needs the same table: keep a copy
+    load_ac_table(R, ig, false, &tab);
+    if (un.interval == 0 && !R.tabs_prebuilt) {             // phase 2 needs the same table: keep a copy
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&tab);
         uint32_t* dst = reinterpret_cast<uint32_t*>(&R.tabs[R.tab_idx[ig]]);
         for (uint32_t e = threadIdx.x; e < sizeof(AcTab) / 4; e += kEntropyLanes) dst[e] = src[e];

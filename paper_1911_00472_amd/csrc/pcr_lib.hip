@@ -109,6 +109,7 @@ struct pcr_record {
     uint8_t* d_rec = nullptr;
     PixelTile* d_tiles = nullptr; uint32_t n_tiles = 0;
     uint32_t* d_dims = nullptr;             // [n][2] width, height (for kernels that run without a decode before them)
+    bool prebuild_tables = false;           // some AC scan has restart intervals: k_build_tables runs before the entropy kernels
     float2* d_ssim_part = nullptr;          // per-tile sums of the similarity kernels (allocated at their first call)
     uint32_t ssim_tiles_max = 0;
     uint8_t* d_gather = nullptr; size_t gather_cap = 0;
@@ -274,6 +275,8 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
     call_begin(r, s);
     hipLaunchKernelGGL(k_index, dim3(k), dim3(256), 0, s, r->d, (uint32_t)k);
     hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, (uint32_t)k, (uint32_t)(k0 > 0));
+    r->d.tabs_prebuilt = r->prebuild_tables ? 1u : 0u;
+    if (r->prebuild_tables && k > k0) hipLaunchKernelGGL(k_build_tables, dim3(n, k - k0), dim3(kEntropyLanes), 0, s, r->d, (uint32_t)k0);
     mark(r, PCR_STAGE_INDEX_PARSE, s);
     if (k > k0) hipLaunchKernelGGL(k_unstuff, dim3(n, k - k0), dim3(256), 0, s, r->d, (uint32_t)k0, (uint32_t)k);
     const size_t coef_bytes = r->coef_off[n] * sizeof(int16_t);
@@ -363,6 +366,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     std::vector<PixelTile> tiles;
     uint64_t nm = 0; uint64_t ns = 0;
     std::vector<uint32_t> tab_idx((size_t)n * G, 0); uint32_t ntabs = 0;
+    r->prebuild_tables = false;
     for (uint32_t i = 0; i < n; i++) {
         const ImgDesc& d = r->img[i];
         r->out_off[i + 1] = r->out_off[i] + (uint64_t)d.W * d.H * d.nc;
@@ -380,9 +384,10 @@ static int finish_open(pcr_record* r, hipStream_t s) {
             if (sd.Ss > 0) {
                 r->mask_off[ig] = nm;
                 nm += (uint64_t)d.bw[sd.comp[0]] * d.bh[sd.comp[0]] * (sd.Ah ? kRefWords : 0);   // one record per block of a refinement scan
-                if (sd.Ah) tab_idx[ig] = ntabs++;
+                tab_idx[ig] = ntabs++;                       // (first scans use theirs only when the tables are built ahead)
             }
             uint32_t cnt = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;
+            if (cnt > 1 && sd.Ss > 0) r->prebuild_tables = true;     // several units share a scan's table: build it once
             r->slot_base[ig] = (uint32_t)ns; r->slot_cnt[ig] = cnt;
             ns += cnt + 1;
         }
