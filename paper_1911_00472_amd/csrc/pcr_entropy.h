@@ -741,7 +741,7 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, IndexSink* sink
             const uint32_t words = wr->refill_keep();        // (before the flush: the wait for the words fetched a window ago must not include these stores)
             sink->flush(words);
         }
-        uint32_t info = ac_first_symbols(wr, sink, &kb, base_b, adv_mask, tot_field);
+        uint32_t info = opaque(ac_first_symbols(wr, sink, &kb, base_b, adv_mask, tot_field));   // (a scalar: tested on the scalar unit)
         if (kb >= 64) {                                      // the block is finished, or the lanes left the code to us
             if (info & kSymSpecial) {                        // a code longer than 8 bits (or none): the same step by hand
                 kb -= kSymMiss & 127;
@@ -812,7 +812,7 @@ PCR_HD void sequential_block(WindowReader* wr, IndexSink* sink, const DcTab* dt,
             const uint32_t words = wr->refill_keep();
             sink->flush(words);
         }
-        info = ac_first_symbols(wr, sink, &kb, base_b, adv_mask, tot_field);
+        info = opaque(ac_first_symbols(wr, sink, &kb, base_b, adv_mask, tot_field));
         if (kb >= 64) {
             if (info & kSymSpecial) {                        // a code longer than 8 bits (or none): the same step by hand
                 kb -= kSymMiss & 127;
