@@ -96,3 +96,12 @@ def test_lane_code_matches_oracle_sequential_files(emul):
     rec = pcrgen.write_record(files)
     assert oracle.record_header(rec)["G"] == 1
     _compare(emul, rec, range(len(files)), (1,))
+
+
+def test_lane_code_matches_oracle_baseline_file_with_one_scan_per_component(emul):
+    """Non-interleaved baseline files: three scans, hence three scan groups, each a whole component."""
+    from jpeg_files import planar_sequential
+    files = [planar_sequential(5, 45, 30), planar_sequential(6, 64, 64, restart=1), planar_sequential(7, 17, 90, 75)]
+    rec = pcrgen.write_record(files)
+    assert oracle.record_header(rec)["G"] == 3
+    _compare(emul, rec, range(len(files)), (1, 2, 3))

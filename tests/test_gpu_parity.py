@@ -125,6 +125,14 @@ def test_sequential_baseline_files_in_a_record():
     _check_record(rec, (1,))
 
 
+def test_baseline_files_with_one_scan_per_component():
+    """Non-interleaved baseline files have three scans, so their record has three scan groups (one component each)."""
+    from jpeg_files import planar_sequential
+    files = [planar_sequential(5, 45, 30), planar_sequential(6, 64, 64, restart=1), planar_sequential(7, 17, 90, 75),
+             planar_sequential(8, 300, 200)]
+    _check_record(pcrgen.write_record(files), (1, 2, 3))
+
+
 def test_progressive_and_sequential_files_mixed_in_one_record(rgb_small):
     files = _sequential_files()[:4] + list(rgb_small[1][:6])
     rec = pcrgen.write_record([files[j] for j in (4, 0, 5, 1, 6, 7, 2, 8, 3, 9)])
