@@ -225,6 +225,13 @@ int pcr_decode_crop_batch(pcr_record* rec, int scan_group, const pcr_crop* d_cro
  *                      them (pcr_open_device the first time, pcr_rebind_device afterwards).  It first waits
  *                      for the slot's earlier work, and returns when the record's metadata is known: *rec
  *                      (optional) is the slot's handle for layout queries, valid until the slot's next upload.
+ *   pcr_loader_read_file  does the reading as well: of the record file at `path` exactly the prefix scan group k
+ *                      needs (Section 3: a fidelity is a byte prefix; Section 4.1: reading less is where the
+ *                      speed-up comes from) -- the first bytes, which say how long it is, then the rest -- into the
+ *                      slot's staging buffer with pread, then pcr_loader_upload.  It waits for the slot's earlier
+ *                      work first.  *nbytes (optional) receives the bytes read.  PCR_E_ARG: the file cannot be
+ *                      opened or read; PCR_E_TRUNCATED: it ends before the prefix does; PCR_E_RANGE: the prefix
+ *                      does not fit the slot, or k is no scan group of the record.
  *   pcr_loader_decode  = pcr_decode_batch on the slot's handle and stream (asynchronous).
  *   pcr_loader_decode_crop  = pcr_decode_crop_batch there: from the bytes read to half-precision training tensors.
  *   pcr_loader_wait    blocks until the slot's stream is idle; the staging buffer may be refilled after
@@ -245,6 +252,7 @@ int pcr_loader_staging(pcr_loader* ld, int slot, void** host, size_t* capacity);
 int pcr_loader_stream(pcr_loader* ld, int slot, void** hip_stream);
 int pcr_loader_set_rate(pcr_loader* ld, double bytes_per_second, double burst_bytes);
 int pcr_loader_upload(pcr_loader* ld, int slot, size_t nbytes, pcr_record** rec);
+int pcr_loader_read_file(pcr_loader* ld, int slot, const char* path, int scan_group, size_t* nbytes, pcr_record** rec);
 int pcr_loader_decode(pcr_loader* ld, int slot, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity, int32_t* d_status);
 int pcr_loader_decode_crop(pcr_loader* ld, int slot, int scan_group, const pcr_crop* d_crops, uint8_t* d_pixels, size_t pixel_capacity,
                            int out_h, int out_w, const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity,

@@ -60,6 +60,7 @@ SYMBOLS = {
     "pcr_loader_stream": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(_vp)]),
     "pcr_loader_set_rate": (ctypes.c_int, [_vp, ctypes.c_double, ctypes.c_double]),
     "pcr_loader_upload": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]),
+    "pcr_loader_read_file": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_char_p, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(_vp)]),
     "pcr_loader_decode": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
     "pcr_loader_decode_crop": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, _vp, _vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
                                               ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float), _vp, ctypes.c_size_t, _vp]),
@@ -427,6 +428,14 @@ class Loader:
         h = _vp()
         _check(lib().pcr_loader_upload(self._h, slot, nbytes, ctypes.byref(h)), "pcr_loader_upload")
         return Record(None, device=self.device, _borrowed_handle=h.value)
+
+    def read_file(self, slot, path, k):
+        """Read from the record file at `path` exactly the prefix scan group k needs into the slot's staging buffer,
+        upload it and bind the slot's handle.  Returns (Record, bytes read)."""
+        h = _vp()
+        n = ctypes.c_size_t(0)
+        _check(lib().pcr_loader_read_file(self._h, slot, os.fsencode(path), k, ctypes.byref(n), ctypes.byref(h)), "pcr_loader_read_file")
+        return Record(None, device=self.device, _borrowed_handle=h.value), int(n.value)
 
     def decode(self, slot, k, out, status=None):
         _check(lib().pcr_loader_decode(self._h, slot, k, out.data_ptr(), out.numel(), status.data_ptr() if status is not None else None),

@@ -3,6 +3,8 @@
 // intervals, and the kernel launches.  Everything data-dependent runs in the kernels of
 // pcr_kernels.h; the host parse done in pcr_open only sizes buffers and rejects bad input early.
 #include <hip/hip_runtime.h>
+#include <fcntl.h>
+#include <unistd.h>
 
 #include <algorithm>
 #include <chrono>
@@ -1023,6 +1025,43 @@ int pcr_loader_upload(pcr_loader* ld, int slot, size_t nbytes, pcr_record** rec)
     if (rc) return rc;
     if (rec) *rec = sl->rec;
     return PCR_OK;
+}
+
+// pread until `count` bytes are in or the file ends; returns the bytes read, or -1
+static ssize_t read_fully(int fd, uint8_t* dst, size_t count, off_t at) {
+    size_t got = 0;
+    while (got < count) {
+        const ssize_t r = pread(fd, dst + got, count - got, at + (off_t)got);
+        if (r < 0) return -1;
+        if (r == 0) break;
+        got += (size_t)r;
+    }
+    return (ssize_t)got;
+}
+
+int pcr_loader_read_file(pcr_loader* ld, int slot, const char* path, int k, size_t* nbytes, pcr_record** rec) {
+    pcr_loader_slot* sl = loader_slot(ld, slot);
+    if (!sl || !path) return PCR_E_ARG;
+    HIP_TRY(hipSetDevice(ld->device));
+    HIP_TRY(hipStreamSynchronize(sl->stream));                // the staging buffer is free again
+    const int fd = open(path, O_RDONLY | O_CLOEXEC);
+    if (fd < 0) return PCR_E_ARG;
+    uint8_t* host = (uint8_t*)sl->host;
+    const size_t head = std::min<size_t>(24 + 8 * 64, ld->slot_bytes);
+    const ssize_t got = read_fully(fd, host, head, 0);
+    int rc = got < 0 ? PCR_E_ARG : PCR_OK;
+    uint64_t need = 0;
+    if (!rc) rc = pcr_prefix_length(host, (size_t)got, k, &need);   // (a file that ends inside its header: TRUNCATED)
+    if (!rc && need > ld->slot_bytes) rc = PCR_E_RANGE;
+    if (!rc && need > (uint64_t)got) {
+        const ssize_t more = read_fully(fd, host + got, (size_t)(need - (uint64_t)got), (off_t)got);
+        if (more < 0) rc = PCR_E_ARG;
+        else if ((uint64_t)got + (uint64_t)more < need) rc = PCR_E_TRUNCATED;
+    }
+    (void)close(fd);
+    if (rc) return rc;
+    if (nbytes) *nbytes = (size_t)need;
+    return pcr_loader_upload(ld, slot, (size_t)need, rec);
 }
 
 int pcr_loader_decode(pcr_loader* ld, int slot, int k, uint8_t* out, size_t cap, int32_t* d_status) {

@@ -187,3 +187,34 @@ def test_loader_rate_limit_and_errors():
         ld.set_rate(0, 0)
         ld.decode(0, 6, out); ld.wait(0)
         assert np.array_equal(out.cpu().numpy(), want)
+
+
+def test_record_files_are_read_only_as_far_as_the_scan_group_needs(tmp_path, rgb_small):
+    """pcr_loader_read_file: the prefix of a record file on disk -> pinned staging -> device -> pixels."""
+    torch = _torch()
+    rec, files = rgb_small
+    path = tmp_path / "small.pcr"
+    path.write_bytes(rec)
+    short = tmp_path / "cut.pcr"
+    ge = oracle.record_index(rec)[4]
+    short.write_bytes(rec[:int(ge[3]) - 5])                        # ends inside scan group 4
+    with pkg.pcr_open(rec, 0) as r0:
+        want = {k: r0.decode_batch(k).cpu().numpy() for k in (1, 2, 10)}
+    with pkg.Loader(2, len(rec)) as ld:
+        for j, k in enumerate((2, 10, 1, 10)):
+            r, nbytes = ld.read_file(j % 2, str(path), k)
+            assert nbytes == int(ge[k - 1]) and r.k_avail == k
+            out = torch.empty(int(r.output_layout()[-1]), dtype=torch.uint8, device="cuda")
+            ld.decode(j % 2, k, out)
+            ld.wait(j % 2)
+            assert np.array_equal(out.cpu().numpy(), want[k])
+        r, nbytes = ld.read_file(0, str(short), 3)                   # what the short file still holds
+        assert nbytes == int(ge[2])
+        for bad_path, k, code in ((str(short), 4, pkg.E_TRUNCATED), (str(tmp_path / "missing.pcr"), 1, pkg.E_ARG), (str(path), 11, pkg.E_RANGE)):
+            with pytest.raises(pkg.PcrError) as e:
+                ld.read_file(1, bad_path, k)
+            assert e.value.code == code
+    with pkg.Loader(1, 4096) as small:                               # a slot too small for the prefix
+        with pytest.raises(pkg.PcrError) as e:
+            small.read_file(0, str(path), 10)
+        assert e.value.code == pkg.E_RANGE

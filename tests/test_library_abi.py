@@ -91,6 +91,7 @@ def test_loader_and_rebind_reject_null_arguments():
     assert L.pcr_loader_create(0, 2, 8, ctypes.byref(h)) == pkg.E_ARG                # slots too small for any record
     assert L.pcr_loader_upload(None, 0, 100, None) == pkg.E_ARG
     assert L.pcr_loader_decode(None, 0, 1, None, 0, None) == pkg.E_ARG
+    assert L.pcr_loader_read_file(None, 0, b"/nonexistent", 1, None, None) == pkg.E_ARG
     assert L.pcr_loader_wait(None, 0) == pkg.E_ARG
     assert L.pcr_loader_set_rate(None, 1.0, 1.0) == pkg.E_ARG
     L.pcr_loader_destroy(None)
