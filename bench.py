@@ -383,6 +383,57 @@ def main():
                          "note": "pixel_GBps counts both batches read once; the kernel reads every scale from the uint8 pixels (about 5 x 1.7 reads with tile halos)"}
     del full0
 
+    per_k = {}
+    for k in SCAN_GROUPS:
+        if k == args.scan_group:
+            continue
+        per_k[k] = timed(k, max(2, args.steps // 2), 1)
+    per_k[args.scan_group] = timed(args.scan_group, args.steps, args.warmup)
+
+    upgrades = {}
+    for (a, b), sec_ab in acc.items():
+        upgrades["%d->%d" % (a, b)] = {"ms_per_step": sec_ab * 1e3, "fresh_decode_ms_per_step": per_k[b][0] * 1e3}
+
+    def per_launch(d):
+        return {n: (ms / launches if launches else 0.0) for n, (ms, launches) in d.items()}
+
+    report = {}
+    for k in sorted(per_k):
+        sec, over, alone, calls = per_k[k]
+        ab = algorithmic_bytes(ends, shapes, k)
+        report[str(k)] = {
+            "images_per_s": n_img / sec,
+            "ms_per_step": sec * 1e3,
+            "output_GBps": ab["out"] / sec / 1e9,
+            "algorithmic_GBps": ab["path"] / sec / 1e9,
+            "hbm_roofline_frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS,
+            "must_move_floor_GBps": (ab["compressed"] + ab["out"]) / sec / 1e9,
+            "stage_ms_one_record_alone": {n: ms / calls for n, (ms, launches) in alone.items()},
+            "kernel_ms_per_launch_alone": per_launch(alone),
+            "kernel_ms_per_launch_overlapped": per_launch(over),
+        }
+    sec, over, alone, calls = per_k[args.scan_group]
+    ab = algorithmic_bytes(ends, shapes, args.scan_group)
+    n0 = handles[0].n
+    # what the chip sustains on chains of dependent scalar instructions (the library's own probe kernel), best of
+    # 8, 16 and 32 wavefronts per CU: the practical ceiling next to the nominal one
+    probe = max(pkg.probe_scalar_issue_rate(w) for w in (8, 16, 32))
+    # what a plain device-to-device copy reaches on this box (the second denominator for the HBM figures)
+    ca = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cb = torch.empty_like(ca)
+    cb.copy_(ca)
+    torch.cuda.synchronize()
+    ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ce0.record()
+    for _ in range(5):
+        cb.copy_(ca)
+    ce1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * ca.numel() / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
+    del ca, cb
+    roofline = dominant_kernel_roofline(args, ends[:n0], per_launch(alone), per_launch(over), alone, n_img, probe)
+
+    # (the two legs below come after everything the headline figures are taken from)
     # ---- the same images as baseline (non-progressive) files: what the decode of a progressive file costs over it ----
     baseline = None
     if not args.no_baseline_files:
@@ -463,56 +514,6 @@ def main():
         for h in rst_handles:
             h.close()
         del rst_handles, rst_records, rst_files
-
-    per_k = {}
-    for k in SCAN_GROUPS:
-        if k == args.scan_group:
-            continue
-        per_k[k] = timed(k, max(2, args.steps // 2), 1)
-    per_k[args.scan_group] = timed(args.scan_group, args.steps, args.warmup)
-
-    upgrades = {}
-    for (a, b), sec_ab in acc.items():
-        upgrades["%d->%d" % (a, b)] = {"ms_per_step": sec_ab * 1e3, "fresh_decode_ms_per_step": per_k[b][0] * 1e3}
-
-    def per_launch(d):
-        return {n: (ms / launches if launches else 0.0) for n, (ms, launches) in d.items()}
-
-    report = {}
-    for k in sorted(per_k):
-        sec, over, alone, calls = per_k[k]
-        ab = algorithmic_bytes(ends, shapes, k)
-        report[str(k)] = {
-            "images_per_s": n_img / sec,
-            "ms_per_step": sec * 1e3,
-            "output_GBps": ab["out"] / sec / 1e9,
-            "algorithmic_GBps": ab["path"] / sec / 1e9,
-            "hbm_roofline_frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS,
-            "must_move_floor_GBps": (ab["compressed"] + ab["out"]) / sec / 1e9,
-            "stage_ms_one_record_alone": {n: ms / calls for n, (ms, launches) in alone.items()},
-            "kernel_ms_per_launch_alone": per_launch(alone),
-            "kernel_ms_per_launch_overlapped": per_launch(over),
-        }
-    sec, over, alone, calls = per_k[args.scan_group]
-    ab = algorithmic_bytes(ends, shapes, args.scan_group)
-    n0 = handles[0].n
-    # what the chip sustains on chains of dependent scalar instructions (the library's own probe kernel), best of
-    # 8, 16 and 32 wavefronts per CU: the practical ceiling next to the nominal one
-    probe = max(pkg.probe_scalar_issue_rate(w) for w in (8, 16, 32))
-    # what a plain device-to-device copy reaches on this box (the second denominator for the HBM figures)
-    ca = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-    cb = torch.empty_like(ca)
-    cb.copy_(ca)
-    torch.cuda.synchronize()
-    ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ce0.record()
-    for _ in range(5):
-        cb.copy_(ca)
-    ce1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 5 * 2 * ca.numel() / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
-    del ca, cb
-    roofline = dominant_kernel_roofline(args, ends[:n0], per_launch(alone), per_launch(over), alone, n_img, probe)
 
     cpu = None
     if not args.no_cpu_baseline:

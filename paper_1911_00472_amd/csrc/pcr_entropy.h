@@ -147,6 +147,14 @@ PCR_HD uint32_t bit_field(uint32_t v, uint32_t packed) {
     return (v >> (packed & 31)) & ((1u << (packed >> 16)) - 1);
 #endif
 }
+// The loop that follows starts on a 64-byte line of the instruction cache (a lone wavefront runs a short loop
+// visibly faster when it does not straddle lines); the padding is jumped over, not executed.
+PCR_HD void align_loop() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_branch 1f\n\t.p2align 6\n1:");
+#endif
+}
+
 // Resolve a code of more than 8 bits.  Returns (length << 8) | symbol, or 0 if it is no code.
 PCR_HD uint32_t ac_long_code(const AcTab* t, uint32_t win) {
     const uint32_t c16 = win >> 16;
@@ -693,6 +701,7 @@ PCR_HD uint32_t ac_first_symbols(WindowReader* wr, IndexSink* sink, uint32_t* kb
     uint32_t t0, t1;
     asm volatile(
         "s_mov_b32 m0, %[o]\n\t"
+        "s_branch 1f\n\t"                                     // (over the padding)
         ".p2align 6\n"
         "1:\n\t"
         "v_readlane_b32 %[info], %[vinfo], m0\n\t"
@@ -1076,6 +1085,7 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
             for (;;) {
                 if (wr->exhausted()) { const uint32_t before = wr->o; wr->refill(); ob -= before - wr->o; }
                 settle_lds();
+                align_loop();
                 do {
                     // One straight line for every symbol.  A new +-1 after r zeros: r zeros are passed, the next
                     // one is taken.  End of band: as if the run went past every zero -- the sentinel entry says
