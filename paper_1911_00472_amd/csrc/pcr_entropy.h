@@ -739,8 +739,9 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, IndexSink* sink
     // it landed on; base_b = element index of the block - bias - 1 makes base_b + kb that element.
     const uint32_t bias = 63 - Se;
     uint32_t left = ls.mcu1 - ls.mcu0;                       // blocks of the unit not finished yet (the current one included)
-    uint32_t row = ls.mcu0 / mcu_w, col = ls.mcu0 % mcu_w;
-    uint32_t base_b = (row * bw + col) * 64 - bias - 1;
+    uint32_t col = ls.mcu0 % mcu_w;
+    uint32_t base_b = ((ls.mcu0 / mcu_w) * bw + col) * 64 - bias - 1;
+    const uint32_t row_skip = (bw - mcu_w) * 64;             // elements of the padded grid between two rows of the scan
     uint32_t kb = Ss + bias;
     uint32_t bad = 0;
     const uint32_t adv_mask = opaque(127u), tot_field = opaque((6u << 16) | 8u);
@@ -770,9 +771,8 @@ PCR_HD int decode_ac_first(WindowReader* wr, const LaneScan& ls, IndexSink* sink
                 }
                 adv = adv < left ? adv : left;
                 left = bad ? 0 : left - adv;                 // stop at the first damaged block
-                col += adv; kb = Ss + bias;
-                while (col >= mcu_w) { col -= mcu_w; row++; }
-                base_b = (row * bw + col) * 64 - bias - 1;
+                col += adv; base_b += adv * 64; kb = Ss + bias;
+                while (col >= mcu_w) { col -= mcu_w; base_b += row_skip; }
             }
         }
     }
