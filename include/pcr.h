@@ -188,6 +188,17 @@ int pcr_crop_resize_batch(pcr_record* rec, const uint8_t* d_pixels, const pcr_cr
  * Errors: PCR_E_ARG (null argument), PCR_E_UNSUPPORTED (channel counts differ between images), PCR_E_NOMEM. */
 int pcr_msssim_batch(pcr_record* rec, const uint8_t* d_a, const uint8_t* d_b, float* d_scores, void* hip_stream);
 
+/* pcr_msssim_batch for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical scores; the per-tile
+ * sums live in a fixed 4 MiB array inside the library's code object (one copy per GPU, held until the process
+ * ends) instead of the handle's working memory, and the call makes no hipMalloc / hipFree or any other
+ * allocating call.  Limit: n x (largest tile count of an image of the record) <= 524288 entries (for instance
+ * 1024 images of up to 500 x 500 pixels, 341 tiles each); beyond it PCR_E_RANGE, nothing enqueued.  All calls on
+ * one GPU share that GPU's array: calls that overlap in time on one GPU (other streams, other handles, other
+ * threads) race and must be ordered by the caller.  Nothing in the array has to be cleared between calls.
+ * Other errors as pcr_msssim_batch. */
+int pcr_msssim_batch_static(pcr_record* rec, const uint8_t* d_a, const uint8_t* d_b, float* d_scores, void* hip_stream);
+
 /* Choosing a scan group by image quality (Section 6.4: scan groups whose MSSIM against the full picture is high
  * train about as well as the full data, so the score can pick the level of compression; Section 4.3 leaves the
  * choice to a tuner).  Returns in *scan_group the lowest scan group whose mean pcr_msssim_batch score over the

@@ -44,6 +44,7 @@ SYMBOLS = {
     "pcr_decode_crop_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
                                              ctypes.POINTER(ctypes.c_float), _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_msssim_batch": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp]),
+    "pcr_msssim_batch_static": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp]),
     "pcr_scan_ends": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]),
     "pcr_record_size": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_size_t), ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint64),
                                        ctypes.POINTER(ctypes.c_uint32)]),
@@ -246,6 +247,15 @@ class Record:
             out = torch.empty(self.n, dtype=torch.float32, device="cuda:%d" % self.device)
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_msssim_batch(self._h, a.data_ptr(), b.data_ptr(), out.data_ptr(), s), "pcr_msssim_batch")
+        return out
+
+    def msssim_batch_static(self, a, b, out, stream=None):
+        """msssim_batch through the entry point that allocates nothing: `out` (float32 CUDA tensor [n]) is the
+        caller's; PcrError(E_RANGE) when the record's tile sums exceed the library's fixed array."""
+        import torch
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() >= self.n
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_msssim_batch_static(self._h, a.data_ptr(), b.data_ptr(), out.data_ptr(), s), "pcr_msssim_batch_static")
         return out
 
     def select_scan_group(self, min_mean_score, stream=None):

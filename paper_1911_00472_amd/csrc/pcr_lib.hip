@@ -10,6 +10,7 @@
 #include <chrono>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -811,6 +812,52 @@ int pcr_msssim_batch(pcr_record* r, const uint8_t* d_a, const uint8_t* d_b, floa
     hipLaunchKernelGGL(k_ssim_tiles, dim3(r->ssim_tiles_max, n), dim3(256), 0, (hipStream_t)stream, r->d_dims, r->d.out_off, C, d_a, d_b,
                        r->d_ssim_part, r->ssim_tiles_max);
     hipLaunchKernelGGL(k_ssim_score, dim3(n), dim3(64), 0, (hipStream_t)stream, r->d_dims, r->d_ssim_part, r->ssim_tiles_max, d_scores);
+    if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
+    return PCR_OK;
+}
+
+// ---- similarity scores without any allocation ----
+// The per-tile sums of the similarity kernels in a fixed array of the code object instead of the handle's
+// arena, for callers that must not allocate (HIP graph capture, serving loops).  Every GPU holds its own copy
+// of the array at its own address; host code never uses the array's name as an address, only the pointer
+// hipGetSymbolAddress returned for that device.
+constexpr size_t kStaticSsimTiles = 512 * 1024;                       // 4 MiB of float2 per device
+static __device__ __align__(256) float2 scratch[kStaticSsimTiles];
+constexpr int kStaticMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static float2* g_scratch_ptr[kStaticMaxDevices] = {};
+
+// the array's address on `device` (which must be current), looked up once per device
+static int static_scratch(int device, float2** p) {
+    if (device < 0 || device >= kStaticMaxDevices) return PCR_E_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void* q = nullptr;
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) { (void)hipGetLastError(); return PCR_E_DEVICE; }
+        g_scratch_ptr[device] = reinterpret_cast<float2*>(q);
+    }
+    *p = g_scratch_ptr[device];
+    return PCR_OK;
+}
+
+int pcr_msssim_batch_static(pcr_record* r, const uint8_t* d_a, const uint8_t* d_b, float* d_scores, void* stream) {
+    if (!r || !d_a || !d_b || !d_scores) return PCR_E_ARG;
+    const uint32_t n = r->hdr.n;
+    if (n == 0 || !r->d_dims) return PCR_E_ARG;
+    const int C = r->img[0].nc;
+    if (C != 1 && C != 3) return PCR_E_UNSUPPORTED;
+    for (uint32_t i = 1; i < n; i++) if (r->img[i].nc != C) return PCR_E_UNSUPPORTED;
+    if (n > 65535) return PCR_E_UNSUPPORTED;
+    uint32_t tmax = 1;
+    for (uint32_t i = 0; i < n; i++) tmax = std::max(tmax, ssim_tiles_all((uint32_t)r->img[i].W, (uint32_t)r->img[i].H));
+    if ((uint64_t)n * tmax > kStaticSsimTiles) return PCR_E_RANGE;   // the record's tile sums do not fit the fixed array
+    HIP_TRY(hipSetDevice(r->device));
+    float2* part = nullptr;
+    int rc = static_scratch(r->device, &part);
+    if (rc) return rc;
+    // (nothing to clear: every entry k_ssim_score reads is written by k_ssim_tiles in the same call)
+    hipLaunchKernelGGL(k_ssim_tiles, dim3(tmax, n), dim3(256), 0, (hipStream_t)stream, r->d_dims, r->d.out_off, C, d_a, d_b, part, tmax);
+    hipLaunchKernelGGL(k_ssim_score, dim3(n), dim3(64), 0, (hipStream_t)stream, r->d_dims, part, tmax, d_scores);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
     return PCR_OK;
 }
