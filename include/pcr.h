@@ -177,9 +177,9 @@ int pcr_crop_resize_batch(pcr_record* rec, const uint8_t* d_pixels, const pcr_cr
  * every image of the record, the multi-scale structural similarity (Wang, Simoncelli and Bovik 2003) of its
  * pictures in two decoded batches, computed on luma (0.299 R + 0.587 G + 0.114 B, not rounded): 11 x 11
  * Gaussian window of sigma 1.5 at the positions where it fits, C1 = (0.01*255)^2, C2 = (0.03*255)^2, five scales
- * by 2 x 2 averaging with the published exponents 0.0448, 0.2856, 0.3001, 0.2363, 0.1333.  An image whose
- * smaller side is below 176 uses as many scales as keep that side at 11 samples or more, their exponents
- * rescaled to sum to 1; a negative scale mean counts as 0; an image smaller than 11 on a side scores NaN.
+ * by 2 x 2 averaging with the published exponents 0.0448, 0.2856, 0.3001, 0.2363, 0.1333 (used as they are: they
+ * sum to 1.0001).  An image whose smaller side is below 176 uses as many scales as keep that side at 11 samples or
+ * more, their exponents rescaled to sum to 1; a negative scale mean counts as 0; an image smaller than 11 on a side scores NaN.
  *   d_a, d_b   device: two pixel batches in the layout of pcr_output_layout (say scan group k and scan group G)
  *   d_scores   device: n floats
  * Computed in single precision from exact integer block sums; agrees with a double-precision evaluation to

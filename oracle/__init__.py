@@ -248,15 +248,17 @@ def msssim(pix_a, pix_b):
     luma: the contrast-structure term averaged at scales 1 .. M-1, luminance x contrast-structure at scale M,
     combined as a product of powers with the published exponents; successive scales by 2 x 2 averaging.
     Readings where the method's paper leaves a choice: M = 5, or as many scales as keep the smaller side at
-    least 11 samples (the exponents of the scales used are rescaled to sum to 1); a negative scale mean counts
-    as 0 (a power of it would not be real)."""
+    least 11 samples (with fewer than five scales their exponents are rescaled to sum to 1); a negative scale
+    mean counts as 0 (a power of it would not be real)."""
     a, b = luma(pix_a), luma(pix_b)
     assert a.shape == b.shape
     M = 1
     while M < 5 and min(a.shape) // (1 << M) >= 11:
         M += 1
     assert min(a.shape) >= 11
-    w = np.array(MSSSIM_WEIGHTS[:M]) / sum(MSSSIM_WEIGHTS[:M])
+    w = np.array(MSSSIM_WEIGHTS[:M])
+    if M < 5:
+        w = w / w.sum()                         # (all five are used as published: they sum to 1.0001)
     out = 1.0
     for j in range(M):
         lum, cs = ssim_maps(a, b)

@@ -5,8 +5,8 @@
 // sigma 1.5 at every position where it fits, C1 = (0.01*255)^2, C2 = (0.03*255)^2; the contrast-structure term
 // averaged at scales 1 .. M-1 and luminance x contrast-structure at scale M, combined as a product of powers
 // with the published exponents; each further scale is the 2 x 2 average of the one before.  M = 5, or as many
-// scales as keep the smaller side at least 11 samples (the exponents used are rescaled to sum to 1); a
-// negative scale mean counts as 0.
+// scales as keep the smaller side at least 11 samples (with fewer than five, the exponents used are rescaled to
+// sum to 1); a negative scale mean counts as 0.
 //
 // Layout of the work: one workgroup per 32 x 32 tile of window positions of one scale of one picture.  A
 // sample of scale j is the mean of an aligned 2^j x 2^j block of the picture (what j rounds of 2 x 2 averaging
@@ -149,6 +149,7 @@ __global__ void __launch_bounds__(64) k_ssim_score(const uint32_t* __restrict__ 
     if (M == 0) { if (lane == 0) scores[i] = __builtin_nanf(""); return; }
     double wsum = 0;
     for (int j = 0; j < M; j++) wsum += weight[j];
+    if (M == kSsimScales) wsum = 1.0;                       // all five scales: the exponents as published (they sum to 1.0001)
     double score = 1.0;
     uint32_t first = 0;
     for (int j = 0; j < M; j++) {
