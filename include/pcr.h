@@ -105,7 +105,8 @@ int pcr_image_info(const pcr_record* rec, int i, int* width, int* height, int* c
 
 /* Output layout: image i occupies bytes [offsets[i], offsets[i+1]) of the output buffer as
  * H_i x W_i x C_i uint8, row-major, channel-interleaved (NHWC; a dense [N,H,W,C] tensor when all
- * images have one size).  offsets: host, n+1 entries. */
+ * images have one size).  offsets: host, n+1 entries, n as pcr_num_images reports it NOW: a handle that was
+ * bound to another record since (pcr_rebind_device, a loader slot's next upload) has another n. */
 int pcr_output_layout(const pcr_record* rec, uint64_t* offsets);
 
 /* ---- parity hooks: intermediate results, computed on the device, returned to the host ---- */
@@ -114,11 +115,12 @@ int pcr_output_layout(const pcr_record* rec, uint64_t* offsets);
  * it): off[g*n+i] = absolute offset of region(i,g+1), len[g*n+i] its length, for the
  * available groups g < k_max (entries of unavailable groups are left untouched).
  * Computed by the index kernel.  off, len: host, G*n entries. */
-int pcr_index(pcr_record* rec, uint64_t* off, uint32_t* len);
+int pcr_index(const pcr_record* rec, uint64_t* off, uint32_t* len);
 
 /* The byte string of image i at fidelity k: regions 1..min(k, scans of i), followed by FF D9 if
  * and only if scans were left out (Section 5, "Decoding").  dst: host, cap bytes; *len receives
- * the length (also when dst is NULL, to query).  Gathered by a device kernel. */
+ * the length (also when dst is NULL, to query).  Gathered by a device kernel.  (The handle is not const: it keeps
+ * the device staging buffer of the gather between calls.) */
 int pcr_reassemble(pcr_record* rec, int i, int k, uint8_t* dst, size_t cap, size_t* len);
 
 /* Coefficient layout: image i occupies int16 elements [offsets[i], offsets[i+1]); inside, the
@@ -140,6 +142,10 @@ int pcr_decode_coefficients(pcr_record* rec, int k, int16_t* d_coef, void* hip_s
  * decode of scans 1..k, refinement, de-quantisation, inverse DCT, chroma replication and
  * YCbCr->RGB.  Coefficients not yet received count as zero; no smoothing is applied.
  * Asynchronous and stream-ordered; argument errors are returned before anything is enqueued.
+ * Decoding several records at a time (one handle and one stream each) is how the GPU is filled: a record alone
+ * is bound by its longest serial streams.  HIP maps streams onto GPU_MAX_HW_QUEUES hardware queues (default 4,
+ * one of them the null stream's); streams that share a queue run one after the other, so a process that overlaps
+ * R records wants that environment variable set to R + 1 or more before the HIP runtime starts.
  */
 int pcr_decode_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
                      void* hip_stream, int32_t* d_status);

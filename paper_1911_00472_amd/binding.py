@@ -168,11 +168,13 @@ class Record:
         return w.value, h.value, c.value, lab.value
 
     def output_layout(self):
+        self._refresh()                                      # (a loader slot's handle may have been bound to another record)
         o = np.zeros(self.n + 1, np.uint64)
         _check(lib().pcr_output_layout(self._h, o.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))), "pcr_output_layout")
         return o
 
     def coef_layout(self):
+        self._refresh()
         o = np.zeros(self.n + 1, np.uint64)
         _check(lib().pcr_coef_layout(self._h, o.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))), "pcr_coef_layout")
         return o

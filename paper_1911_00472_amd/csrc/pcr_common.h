@@ -20,6 +20,8 @@ enum : int { kOk = 0, kEArg = -1, kEFormat = -2, kETruncated = -3, kEUnsupported
 
 constexpr int kMaxComp = 3;
 constexpr int kMaxHist = 6;      // earlier AC refinement scans of the same component a refinement scan may build on
+constexpr int kApplyMaxScans = 16;   // refinement scans (DC and AC together) of one component that are replayed when the
+                                     // coefficients are loaded; a file with more is refused when its headers are parsed
 
 // One image of a record (frame header + tables that hold for the whole image).
 struct ImgDesc {

@@ -209,6 +209,15 @@ PCR_HD void parse_image(const uint8_t* rec, const uint32_t* off, const uint32_t*
         }
     }
     if (img->nscans == 0) { img->status = kEFormat; return; }
+    // the refinement scans of a component are replayed from a list of fixed length when its coefficients are loaded
+    for (int c = 0; c < img->nc; c++) {
+        int nref = 0;
+        for (uint32_t g = 0; g < img->nscans; g++) {
+            if (scans[g].Ah == 0) continue;
+            for (int j = 0; j < scans[g].ns; j++) if (scans[g].comp[j] == c) nref++;
+        }
+        if (nref > kApplyMaxScans) { img->status = kEUnsupported; return; }
+    }
     for (int c = 0; c < img->nc; c++) if (!img->qoff[img->tq[c]]) { img->status = kEFormat; return; }
 }
 

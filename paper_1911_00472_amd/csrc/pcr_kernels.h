@@ -2,8 +2,9 @@
 //   k_index      scan-group index (prefix sums of region lengths)
 //   k_parse      JPEG marker parsing, one lane per image
 //   k_unstuff    byte un-stuffing + restart-interval location, one workgroup per (image, scan)
-//   k_dc_first, k_ac_first, k_ac_refine   progressive Huffman decode, one lane per restart
-//                interval of a scan
+//   k_dc_first, k_ac_first, k_ac_refine   progressive Huffman decode, one wavefront per restart
+//                interval of a scan (per scan where there are no restart markers)
+//   k_refine_blocks   second phase of AC refinement, one lane per block
 //   k_apply      data-parallel refinement (DC bits, AC corrections and new coefficients)
 //   k_pixel      de-quantise + IDCT + chroma replication + YCbCr->RGB + store
 //   k_gather     materialise an image's scan prefix (parity hook)
@@ -382,7 +383,6 @@ __global__ void __launch_bounds__(kEntropyLanes) k_sequential(DevRecord R, const
 }
 
 struct ApplyUnit { uint32_t img; uint32_t comp; };
-constexpr int kApplyMaxScans = 16;
 
 __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
         const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {

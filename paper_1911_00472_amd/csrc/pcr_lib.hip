@@ -611,19 +611,27 @@ int pcr_image_info(const pcr_record* r, int i, int* w, int* h, int* c, int32_t* 
 
 int pcr_output_layout(const pcr_record* r, uint64_t* offsets) {
     if (!r || !offsets) return PCR_E_ARG;
-    if (r->out_off.size() != (size_t)r->hdr.n + 1) { offsets[0] = 0; return r->hdr.n ? PCR_E_ARG : PCR_OK; }   // (a handle without a record: n = 0)
+    if (r->out_off.size() != (size_t)r->hdr.n + 1) {           // a handle without a record (n = 0) has the one entry 0
+        if (r->hdr.n) return PCR_E_ARG;
+        offsets[0] = 0;
+        return PCR_OK;
+    }
     std::memcpy(offsets, r->out_off.data(), r->out_off.size() * sizeof(uint64_t));
     return PCR_OK;
 }
 
 int pcr_coef_layout(const pcr_record* r, uint64_t* offsets) {
     if (!r || !offsets) return PCR_E_ARG;
-    if (r->coef_off.size() != (size_t)r->hdr.n + 1) { offsets[0] = 0; return r->hdr.n ? PCR_E_ARG : PCR_OK; }
+    if (r->coef_off.size() != (size_t)r->hdr.n + 1) {
+        if (r->hdr.n) return PCR_E_ARG;
+        offsets[0] = 0;
+        return PCR_OK;
+    }
     std::memcpy(offsets, r->coef_off.data(), r->coef_off.size() * sizeof(uint64_t));
     return PCR_OK;
 }
 
-int pcr_index(pcr_record* r, uint64_t* off, uint32_t* len) {
+int pcr_index(const pcr_record* r, uint64_t* off, uint32_t* len) {
     if (!r || !off || !len) return PCR_E_ARG;
     HIP_TRY(hipSetDevice(r->device));
     const uint32_t n = r->hdr.n, G = r->hdr.G, k = r->hdr.k_avail;

@@ -105,3 +105,77 @@ def test_lane_code_matches_oracle_baseline_file_with_one_scan_per_component(emul
     rec = pcrgen.write_record(files)
     assert oracle.record_header(rec)["G"] == 3
     _compare(emul, rec, range(len(files)), (1, 2, 3))
+
+
+def _variant_files():
+    from jpeg_files import VARIANTS, sof0_as_sof1
+    from test_oracle_variants import _bases
+    files = []
+    for f in _bases():
+        files.append(f)
+        files += [fn(f) for fn in VARIANTS.values()]
+        files.append(VARIANTS["fill"](VARIANTS["com_app"](VARIANTS["dqt16"](f))))
+    files.append(sof0_as_sof1(_bases()[3]))
+    return files
+
+
+def test_lane_code_decodes_other_spellings_of_a_file_identically(emul):
+    """16-bit quantisation tables, SOF1, comment / application segments between scans, fill bytes ahead of restart
+    markers and scan headers: the same coefficients and pixels as the plain file, and as the oracle."""
+    files = _variant_files()
+    progressive = [f for f in files if b"\xff\xc2" in f[:700]]
+    baseline = [f for f in files if b"\xff\xc2" not in f[:700]]
+    for group in (progressive, baseline):
+        for f in group:
+            rec = pcrgen.write_record([f])
+            G = oracle.record_header(rec)["G"]
+            _compare(emul, rec, [0], range(1, G + 1))
+
+
+def test_lane_code_matches_oracle_on_files_from_an_independent_encoder(emul):
+    """Progressive and baseline files written by Pillow (libjpeg-turbo): application segments, several tables per
+    DHT segment, the stock encoder's restart placement and end-of-band statistics."""
+    pytest.importorskip("PIL.Image")
+    from jpeg_files import pillow_baseline, pillow_files
+    files = pillow_files()
+    gray = [f for f in files if oracle.image_info(f).nc == 1]
+    colour = [f for f in files if oracle.image_info(f).nc == 3]
+    for group in (gray, colour):
+        rec = pcrgen.write_record(group)
+        G = oracle.record_header(rec)["G"]
+        _compare(emul, rec, range(len(group)), range(1, G + 1))
+    base = [pillow_baseline(3000 + j, w, h, c, sub, q, **extra) for j, (w, h, c, sub, q, extra) in enumerate(
+        [(93, 61, 3, 2, 90, {}), (64, 64, 1, 0, 80, {}), (130, 47, 3, 1, 95, {"restart_marker_rows": 1}), (50, 50, 3, 0, 75, {"optimize": True})])]
+    rec = pcrgen.write_record(base)
+    assert oracle.record_header(rec)["G"] == 1
+    _compare(emul, rec, range(len(base)), (1,))
+
+
+def many_refinement_scans_file(extra_dc=8):
+    """A gray file whose single component has 10 AC refinement scans (two bands, five bit planes each) and
+    `extra_dc` DC refinement scans: 18 refinement scans with the default, two more than the library replays."""
+    rows = [(1, 0, 0, 0, 0, 0, 0, extra_dc)]
+    rows += [(1, 0, 0, 0, 1, 5, 0, 5), (1, 0, 0, 0, 6, 63, 0, 5)]
+    for al in range(4, -1, -1):
+        rows += [(1, 0, 0, 0, 1, 5, al + 1, al), (1, 0, 0, 0, 6, 63, al + 1, al)]
+    rows += [(1, 0, 0, 0, 0, 0, al + 1, al) for al in range(extra_dc - 1, -1, -1)]
+    img = pcrgen.synth(55, 1, 48, 40, 1, 12.0)
+    return pcrgen.encode_pixels(img, 1, 1, 95, rows, 0), len(rows)
+
+
+def test_more_refinement_scans_than_the_replay_list_holds_are_refused_not_misdecoded(emul):
+    f, nscans = many_refinement_scans_file()
+    assert nscans == 21
+    rec = pcrgen.write_record([f])
+    info = oracle.record_image_info(rec, 0)
+    c0, p0, _ = oracle.decode_record_image(rec, 0, nscans)             # the oracle has no such limit
+    assert np.abs(p0.astype(int) - pcrgen.synth(55, 1, 48, 40, 1, 12.0)).max() < 12
+    with pytest.raises(AssertionError, match="-4"):
+        emul(rec, 0, nscans, info)
+    # with 16 refinement scans (6 DC bit planes) the same script decodes, at every scan group
+    f2, n2 = many_refinement_scans_file(extra_dc=6)
+    rec2 = pcrgen.write_record([f2])
+    _compare(emul, rec2, [0], range(1, n2 + 1))
+    # a prefix that stops before the 17th refinement scan is still served
+    k_ok = 3 + 10 + 6
+    _compare(emul, rec, [0], (1, 5, k_ok))

@@ -27,7 +27,8 @@ def _check_record(rec, ks, images=None, threads=16, check_bytes=True):
         assert (r.n, r.G, r.k_avail) == (h["n"], h["G"], h["k_avail"])
         off0, len0, label0, ns0, ge0 = oracle.record_index(rec)
         off1, len1 = r.index()
-        assert np.array_equal(off0, off1) and np.array_equal(len0, len1)
+        ka = r.k_avail                                             # (a record cut at a group boundary: the groups it holds)
+        assert np.array_equal(off0[:ka], off1[:ka]) and np.array_equal(len0[:ka], len1[:ka])
         for k in range(1, r.G + 1):
             assert r.group_end_offset(k) == ge0[k - 1]
         lay, clay = r.output_layout(), r.coef_layout()
@@ -470,3 +471,66 @@ def test_decode_call_replays_from_a_hip_graph(rgb_small):
             torch.cuda.synchronize()
             assert torch.equal(out, eager), ("replay after", other)
             assert (status.cpu().numpy() == 0).all()
+
+
+def test_other_spellings_of_a_file_decode_identically():
+    """16-bit quantisation tables (Pq = 1), SOF1, comment and application segments between scans, 0xFF fill bytes
+    ahead of restart markers and scan headers: one record of plain files and their variants; every variant's
+    coefficients and pixels equal the plain file's and the oracle's at every scan group."""
+    from test_core_host import _variant_files
+    files = _variant_files()
+    progressive = [f for f in files if oracle.image_info(f).progressive]
+    baseline = [f for f in files if not oracle.image_info(f).progressive]
+    _check_record(pcrgen.write_record(baseline), (1,))
+    ten = [f for f in progressive if oracle.image_info(f).nscans == 10]
+    rest = [f for f in progressive if oracle.image_info(f).nscans != 10]
+    _check_record(pcrgen.write_record(ten), range(1, 11))
+    rec = pcrgen.write_record(rest)
+    _check_record(rec, range(1, oracle.record_header(rec)["G"] + 1))
+    # the variants of a file give the very same device output as the file itself
+    torch = _torch()
+    with pkg.pcr_open(pcrgen.write_record(ten), 0) as r:
+        lay = r.output_layout()
+        out = r.decode_batch(10).cpu().numpy()
+        per = len(ten)                                             # one base file and its four variants
+        assert per == 5
+        for i in range(1, per):
+            assert np.array_equal(out[int(lay[i]):int(lay[i + 1])], out[int(lay[0]):int(lay[1])]), i
+
+
+def test_files_from_an_independent_encoder_every_scan_group():
+    """Records built from files Pillow (libjpeg-turbo) wrote -- the kind of file the paper's transcoding step
+    produces (Section 5, "Encoding") -- gray, 4:4:4, 4:2:2, 4:2:0, plain, a restart marker per MCU row, one every
+    7 MCUs, odd sizes: index, bytes, coefficients and pixels against the oracle at every scan group; the same for
+    baseline files."""
+    pytest.importorskip("PIL.Image")
+    from jpeg_files import pillow_baseline, pillow_files
+    files = pillow_files()
+    gray = [f for f in files if oracle.image_info(f).nc == 1]
+    colour = [f for f in files if oracle.image_info(f).nc == 3]
+    _check_record(pcrgen.write_record(gray), range(1, 7))
+    _check_record(pcrgen.write_record(colour), range(1, 11))
+    _check_record(pcrgen.write_record(files), range(1, 11))        # gray and colour mixed
+    base = [pillow_baseline(3000 + j, w, h, c, sub, q, **extra) for j, (w, h, c, sub, q, extra) in enumerate(
+        [(93, 61, 3, 2, 90, {}), (64, 64, 1, 0, 80, {}), (130, 47, 3, 1, 95, {"restart_marker_rows": 1}), (50, 50, 3, 0, 75, {"optimize": True}),
+         (500, 375, 3, 2, 92, {})])]
+    _check_record(pcrgen.write_record(base), (1,))
+    # the library's own record writer groups such files the same way
+    assert pkg.record_write(colour) == pcrgen.write_record(colour)
+
+
+def test_more_refinement_scans_than_the_replay_list_holds():
+    """A legal file with 18 refinement scans of one component is refused at open (the lists the pixel kernel replays
+    hold 16), never decoded wrongly; a prefix of the record that stops before the 17th is served; with 16 the whole
+    file decodes."""
+    from test_core_host import many_refinement_scans_file
+    f, nscans = many_refinement_scans_file()
+    rec = pcrgen.write_record([f])
+    with pytest.raises(pkg.PcrError) as e:
+        pkg.pcr_open(rec, 0)
+    assert e.value.code == pkg.E_UNSUPPORTED
+    _, _, _, _, ge = oracle.record_index(rec)
+    k_ok = 3 + 10 + 6
+    _check_record(rec[:int(ge[k_ok - 1])], (1, 5, k_ok), check_bytes=False)
+    f2, n2 = many_refinement_scans_file(extra_dc=6)
+    _check_record(pcrgen.write_record([f2]), range(1, n2 + 1))
