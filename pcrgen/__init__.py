@@ -68,6 +68,10 @@ def lib():
         L.pcrgen_make_jpeg.restype = ctypes.c_size_t
         L.pcrgen_make_jpeg_sequential.argtypes = L.pcrgen_make_jpeg.argtypes
         L.pcrgen_make_jpeg_sequential.restype = ctypes.c_size_t
+        L.pcrgen_symbol_counts.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                           ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.POINTER(ctypes.c_uint64), ctypes.c_int]
+        L.pcrgen_symbol_counts.restype = ctypes.c_int
         L.pcrgen_split_scans.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int]
         L.pcrgen_split_scans.restype = ctypes.c_int
         _lib = L
@@ -150,6 +154,29 @@ def make_jpeg(seed, kind, W, H, C, sigma, hsub, vsub, quality, restart=0, sequen
     n = fn(seed, kind, W, H, C, float(sigma), hsub, vsub, quality, restart, _p(out, ctypes.c_uint8), cap)
     assert n > 0
     return out[:n].tobytes()
+
+
+def symbol_counts(seed, kind, W, H, C, sigma, hsub, vsub, quality, restart=0, sequential=False):
+    """Huffman-coded symbols per scan of the file make_jpeg writes for the same arguments (work accounting)."""
+    cnt = np.zeros(16, np.uint64)
+    n = lib().pcrgen_symbol_counts(seed, kind, W, H, C, float(sigma), hsub, vsub, quality, restart, 1 if sequential else 0,
+                                   _p(cnt, ctypes.c_uint64), 16)
+    assert n > 0
+    return cnt[:n].astype(np.int64)
+
+
+def workload_symbol_counts(name, seed=191100472, limit=None, threads=None, restart=None, sequential=False):
+    """int64 [images, scans]: Huffman-coded symbols per scan of every file make_workload(name, ...) writes."""
+    w = WORKLOADS[name]
+    Ws, Hs = workload_shapes(name, seed, limit)
+    hs, vs = w["sub"]
+    rst = w["restart"] if restart is None else restart
+    lib()
+    threads = threads or min(16, os.cpu_count() or 1)
+    with ThreadPoolExecutor(threads) as ex:
+        rows = list(ex.map(lambda i: symbol_counts(_mix(seed, i), w["kind"], int(Ws[i]), int(Hs[i]), w["C"], w["sigma"], hs, vs,
+                                                   w["quality"], rst, sequential), range(len(Ws))))
+    return np.stack(rows)
 
 
 def split_scans(jpeg):

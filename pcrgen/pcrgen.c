@@ -611,6 +611,45 @@ size_t pcrgen_make_jpeg(uint64_t seed, int kind, int W, int H, int nc, double si
     return n;
 }
 
+/* Work accounting for benchmarks: the number of Huffman-coded symbols in every scan of the file pcrgen_make_jpeg
+ * (sequential = 0) or pcrgen_make_jpeg_sequential (1) writes for the same arguments -- the symbols a decoder has to
+ * decode one after the other.  Bits appended to a symbol and DC refinement bits are not symbols.  Returns the number
+ * of scans (counts[0 .. scans-1] filled), or -1 if max_scans is too small. */
+int pcrgen_symbol_counts(uint64_t seed, int kind, int W, int H, int nc, double sigma, int hsub, int vsub, int quality,
+                         int restart, int sequential, uint64_t* counts, int max_scans) {
+    frame_t F; frame_init(&F, W, H, nc, hsub, vsub);
+    const int* script = sequential ? NULL : (nc == 3 ? script_color10 : script_gray6);
+    static const int seq_gray[SCRIPT_STRIDE] = {1, 0, 0, 0, 0, 63, 0, 0};
+    static const int seq_col[SCRIPT_STRIDE] = {3, 0, 1, 2, 0, 63, 0, 0};
+    int n_scans = sequential ? 1 : (nc == 3 ? 10 : 6);
+    if (sequential) script = nc == 3 ? seq_col : seq_gray;
+    if (n_scans > max_scans) return -1;
+    size_t nb = 0; for (int c = 0; c < nc; c++) nb += (size_t)F.bw[c] * F.bh[c];
+    uint8_t* pix = (uint8_t*)malloc((size_t)W * H * nc);
+    int16_t* coef = (int16_t*)malloc(nb * 64 * sizeof(int16_t));
+    uint16_t q[128];
+    pcrgen_quant_table(0, quality, q); pcrgen_quant_table(1, quality, q + 64);
+    pcrgen_synth(seed, kind, W, H, nc, sigma, pix);
+    pcrgen_pixels_to_coefs(pix, W, H, nc, hsub, vsub, q, coef);
+    size_t o = 0;
+    for (int c = 0; c < nc; c++) { F.coef[c] = coef + o; o += (size_t)F.bw[c] * F.bh[c] * 64; }
+    toks_t T; memset(&T, 0, sizeof T);
+    for (int sc = 0; sc < n_scans; sc++) {
+        const int* e = script + sc * SCRIPT_STRIDE;
+        int ns = e[0]; const int* comps = e + 1;
+        int Ri = 0;
+        if (restart == 1) Ri = ns > 1 ? F.mcux : F.cw[comps[0]];
+        else if (restart > 1) Ri = restart;
+        T.n = 0;
+        scan_tokens(&F, ns, comps, e[4], e[5], e[6], e[7], Ri, sequential, &T);
+        uint64_t cnt = 0;
+        for (size_t i = 0; i < T.n; i++) if (T.t[i].sym >= 0 && T.t[i].tbl < 4) cnt++;
+        counts[sc] = cnt;
+    }
+    free(T.t); free(coef); free(pix);
+    return n_scans;
+}
+
 /* the same image as a sequential (baseline) file */
 size_t pcrgen_make_jpeg_sequential(uint64_t seed, int kind, int W, int H, int nc, double sigma, int hsub, int vsub,
                                    int quality, int restart, uint8_t* out, size_t cap) {

@@ -375,11 +375,38 @@ def test_extreme_coefficient_planes(extreme_record):
     _check_record(rec, range(1, G + 1))
 
 
+def _decode_on_streams(torch, handles, outs, stats, streams, k):
+    for h, o, st, s in zip(handles, outs, stats, streams):
+        st.fill_(77)
+        h.decode_batch(k, out=o, status=st, stream=s.cuda_stream)
+    torch.cuda.synchronize()
+    for st in stats:
+        assert (st.cpu().numpy() == 0).all()
+
+
+def _compare_pixels(rec, h, host, k, idx):
+    lay = h.output_layout()
+    ref = oracle.decode_record(rec, k, images=idx, threads=16, want_coef=False)
+    for i, (_, p0, info) in zip(idx, ref):
+        got = host[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc)
+        assert np.abs(got.astype(np.int16) - p0.astype(np.int16)).max() <= PIXEL_TOL, ("pixels", i, k)
+
+
+def _compare_coefficients(rec, h, k, idx=None):
+    clay = h.coef_layout()
+    coef = h.decode_coefficients(k).cpu().numpy()
+    idx = list(range(h.n)) if idx is None else idx
+    ref = oracle.decode_record(rec, k, images=idx, threads=16, want_pix=False)
+    for i, (c0, _, _) in zip(idx, ref):
+        assert np.array_equal(coef[int(clay[i]):int(clay[i + 1])], c0), ("coefficients", i, k)
+
+
 def test_headline_full_size_four_records_on_four_streams():
     """The benchmark's configuration at full size: 4096 images in 4 records of 1024, all four records decoded
-    concurrently on one stream each.  At scan group 10 EVERY image's pixels are checked against the oracle (which
-    takes a few seconds on the machine's host threads), at scan group 2 a sample of every record; every image's status
-    must be clean."""
+    concurrently on one stream each, at EVERY scan group 1..10.  At scan group 10 every image's pixels are checked
+    against the oracle, at every other scan group a seeded sample of 64 images of every record; every image's
+    status must be clean.  The coefficient planes of one whole record are compared bit for bit at scan groups 5
+    and 10, and those of a sample of another record at every scan group."""
     torch = _torch()
     records, _ = pcrgen.make_workload("imagenet_like")
     assert len(records) == 4
@@ -390,26 +417,80 @@ def test_headline_full_size_four_records_on_four_streams():
         outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in handles]
         stats = [torch.full((h.n,), 77, dtype=torch.int32, device="cuda") for h in handles]
         rng = np.random.default_rng(11)
-        for k in (10, 2):
-            for h, o, st, s in zip(handles, outs, stats, streams):
-                h.decode_batch(k, out=o, status=st, stream=s.cuda_stream)
-            torch.cuda.synchronize()
-            for ri, (h, o, st) in enumerate(zip(handles, outs, stats)):
-                assert (st.cpu().numpy() == 0).all()
-                lay = h.output_layout()
-                host = o.cpu().numpy()
-                idx = list(range(h.n)) if k == 10 else sorted(rng.choice(h.n, size=3, replace=False).tolist())
-                ref = oracle.decode_record(records[ri], k, images=idx, threads=16, want_coef=False)
-                for i, (_, p0, info) in zip(idx, ref):
-                    got = host[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc)
-                    assert np.abs(got.astype(np.int16) - p0.astype(np.int16)).max() <= PIXEL_TOL, ("pixels", ri, i, k)
-                del ref
-        # and the coefficient planes of a whole record, bit for bit
-        clay = handles[0].coef_layout()
-        coef = handles[0].decode_coefficients(10).cpu().numpy()
-        ref = oracle.decode_record(records[0], 10, threads=16, want_pix=False)
-        for i, (c0, _, _) in enumerate(ref):
-            assert np.array_equal(coef[int(clay[i]):int(clay[i + 1])], c0), ("coefficients", i)
+        for k in range(10, 0, -1):
+            _decode_on_streams(torch, handles, outs, stats, streams, k)
+            for ri, (h, o) in enumerate(zip(handles, outs)):
+                idx = list(range(h.n)) if k == 10 else sorted(rng.choice(h.n, size=64, replace=False).tolist())
+                _compare_pixels(records[ri], h, o.cpu().numpy(), k, idx)
+        for k in (5, 10):
+            _compare_coefficients(records[0], handles[0], k)
+        for k in range(1, 11):
+            _compare_coefficients(records[3], handles[3], k, sorted(rng.choice(handles[3].n, size=24, replace=False).tolist()))
+    finally:
+        for h in handles:
+            h.close()
+
+
+def test_rgb256_full_size_every_scan_group():
+    """All 1024 images of the 256 x 256 workload, one record, every scan group: every pixel of every image and, at
+    scan groups 2, 6 and 10, every coefficient."""
+    torch = _torch()
+    records, _ = pcrgen.make_workload("rgb256")
+    assert len(records) == 1
+    rec = records[0]
+    with pkg.pcr_open(rec, 0) as r:
+        assert r.n == 1024 and r.G == 10
+        st = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
+        for k in range(1, 11):
+            out = r.decode_batch(k, status=st).cpu().numpy()
+            assert (st.cpu().numpy() == 0).all()
+            _compare_pixels(rec, r, out, k, list(range(r.n)))
+        for k in (2, 6, 10):
+            _compare_coefficients(rec, r, k)
+
+
+def test_hires1024_one_whole_record_and_two_records_overlapped():
+    """One whole record of the high-resolution workload (128 images of 1024 x 1024, a restart interval per MCU row
+    of every scan: 64 or 128 units per scan and image) at scan groups 1, 5 and 10, every pixel; a second record
+    decoded at the same time on its own stream; coefficients of a sample."""
+    torch = _torch()
+    records, _ = pcrgen.make_workload("hires1024", limit=256)
+    assert len(records) == 2
+    handles = [pkg.pcr_open(r, 0) for r in records]
+    try:
+        assert handles[0].n == 128
+        streams = [torch.cuda.Stream() for _ in handles]
+        outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in handles]
+        stats = [torch.full((h.n,), 77, dtype=torch.int32, device="cuda") for h in handles]
+        for k in (1, 5, 10):
+            _decode_on_streams(torch, handles, outs, stats, streams, k)
+            _compare_pixels(records[0], handles[0], outs[0].cpu().numpy(), k, list(range(128)))
+            _compare_pixels(records[1], handles[1], outs[1].cpu().numpy(), k, list(range(0, 128, 9)))
+            _compare_coefficients(records[0], handles[0], k, list(range(0, 128, 16)))
+    finally:
+        for h in handles:
+            h.close()
+
+
+def test_ham_like_at_size_opened_on_the_device():
+    """256 images of the 600 x 450 4:4:4 quality-95 workload as two records of 128 brought to the device as a loader
+    would bring them, opened from device memory (index and markers parsed on the device), both decoded at every scan
+    group on their own streams: every pixel of one record, a sample of the other; coefficients of a sample."""
+    torch = _torch()
+    _, files = pcrgen.make_workload("ham_like", limit=256)
+    records = [pcrgen.write_record(files[:128], labels=list(range(128))), pcrgen.write_record(files[128:], labels=list(range(128)))]
+    devs = [torch.frombuffer(bytearray(r), dtype=torch.uint8).cuda() for r in records]
+    handles = [pkg.pcr_open_device(d) for d in devs]
+    try:
+        streams = [torch.cuda.Stream() for _ in handles]
+        outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in handles]
+        stats = [torch.full((h.n,), 77, dtype=torch.int32, device="cuda") for h in handles]
+        for k in range(1, 11):
+            _decode_on_streams(torch, handles, outs, stats, streams, k)
+            _compare_pixels(records[0], handles[0], outs[0].cpu().numpy(), k, list(range(128)))
+            _compare_pixels(records[1], handles[1], outs[1].cpu().numpy(), k, list(range(0, 128, 11)))
+        for k in (3, 7, 10):
+            _compare_coefficients(records[1], handles[1], k, list(range(0, 128, 8)))
     finally:
         for h in handles:
             h.close()
