@@ -1,282 +1,366 @@
 #!/usr/bin/env python3
 """Benchmark of the PCR decode path on one MI355X.
 
-A step is one pass of the whole path (index, marker parse, unstuff, progressive Huffman decode
-of scans 1..k, refinement, de-quantise, IDCT, chroma replication, YCbCr->RGB, store) over the
-whole workload: 4096 variable-size progressive JPEGs in 4 records of 1024, record bytes already
-resident in device memory.  Prints one JSON line.
+A step is one pass of the whole path (index, marker parse, unstuff, progressive Huffman decode of scans 1..k,
+refinement, de-quantise, IDCT, chroma replication, YCbCr->RGB, store) over the whole workload, record bytes already
+resident in device memory, every record on a HIP stream of its own.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--images N] [--no-cpu-baseline] [--no-baseline-files]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--scan-group k] [--images N]
+                    [--extras] [--no-cpu-baseline] [--no-default-queues]
+
+Workloads (synthetic stand-ins for the paper's datasets, Table 1 / Table 3):
+    imagenet_like (default, the headline)  4096 RGB images 300..500 px, 4:2:0, 4 records, scan groups 1..10
+    rgb256        1024 RGB 256 x 256, 1 record, scan groups 1..10
+    gray64        64 gray 64 x 64, 1 record, scan groups 1, 3, 6
+    hires1024     1024 RGB 1024 x 1024 with a restart interval per MCU row, 8 records, scan groups 1, 5, 10
+    ham_like      2048 RGB 600 x 450, 4:4:4, quality 95, 2 records, scan groups 1..10; also streamed from pinned host
+                  memory with the record parsed on the device
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
+import tempfile
 import time
 
 import numpy as np
-
-# The records of a step are decoded on one HIP stream each.  HIP multiplexes its streams over
-# GPU_MAX_HW_QUEUES hardware queues (default 4); with four, pairs of the record streams were measured to
-# share a queue and run one after the other.  Sixteen queues give the four record streams and the four
-# streams of the loader measured further down one each.  Must be set before the HIP runtime starts.
-if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 16:
-    os.environ["GPU_MAX_HW_QUEUES"] = "16"
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# The records of a step are decoded on one HIP stream each.  HIP multiplexes its streams over GPU_MAX_HW_QUEUES
+# hardware queues (default 4); streams that share a queue run one after the other.  Sixteen queues give every record
+# stream (and the loader's) one of its own.  Must be set before the HIP runtime starts; `--keep-queues` (used by the
+# child process that measures HIP's default) leaves the environment alone.
+if "--keep-queues" not in sys.argv and int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 16:
+    os.environ["GPU_MAX_HW_QUEUES"] = "16"
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-SCAN_GROUPS = (1, 2, 5, 10)    # the scan groups the paper tabulates (Tables 1 and 2)
-HEADLINE_K = 10
+SALU_PEAK_GINSTS = 256 * 2.4   # one scalar instruction per cycle per compute unit, 256 CUs, 2.4 GHz
+WORKLOAD_SCAN_GROUPS = {"imagenet_like": tuple(range(1, 11)), "rgb256": tuple(range(1, 11)), "gray64": (1, 3, 6),
+                        "hires1024": (1, 5, 10), "ham_like": tuple(range(1, 11))}
+TABLE_SCAN_GROUPS = (1, 2, 5, 10)     # the scan groups the paper tabulates (Tables 1 and 2)
 
-
-def scan_tables(files):
-    """Per file: cumulative compressed bytes per scan; per image: geometry for byte accounting."""
-    import pcrgen
-    return np.array([pcrgen.split_scans(f) for f in files], dtype=np.int64)
-
-
-def algorithmic_bytes(ends, shapes, k):
-    """Bytes the method itself must move for scan group k (per image, summed):
-    compressed prefix read once, each coefficient position covered by scans <= k written once and
-    read once (2 bytes each), pixels written once.  10-scan 4:2:0 script: DC for all components
-    at k=1, luma positions 1..5 at k=2, Cr 1..63 at k=3, Cb 1..63 at k=4, all luma from k=5."""
-    comp = ends[:, k - 1].sum()
-    out = 0
-    touched = 0          # int16 elements
-    for (W, H) in shapes:
-        mx, my = -(-W // 16), -(-H // 16)
-        yb, cb = 4 * mx * my, mx * my
-        ycov = (1 if k >= 1 else 0) + (5 if k >= 2 else 0) + (58 if k >= 5 else 0)
-        crcov = 1 + (63 if k >= 3 else 0)
-        cbcov = 1 + (63 if k >= 4 else 0)
-        touched += yb * ycov + cb * (crcov + cbcov)
-        out += W * H * 3
-    return dict(compressed=int(comp), touched=int(2 * touched), out=int(out),
-                path=int(comp + 2 * 2 * touched + out), entropy=int(comp + 2 * touched))
-
-
-# rocprofv3 counters of the dominant kernel, k_ac_refine, per launch (mean of its two launches per
-# record: scans 6, 8, 9, then scan 10) for record 0 of the default workload at scan group 10; summaries
-# under profiles/.  FETCH_SIZE reads 0.5 KiB per KiB a plain copy kernel fetches and WRITE_SIZE 1.0, so the
-# fetch figure is scaled by 2.  They describe the kernel as it stood when they were taken and are set to
-# None whenever k_ac_refine changes, until the counters are read again.
-AC_REFINE_PMC = {
-    "salu_insts_per_launch": 0.5 * (831.8e6 + 634.4e6),
-    "valu_insts_per_launch": 0.5 * (267.3e6 + 207.4e6),
-    "fetch_bytes_per_launch": 0.5 * (278348.8 + 240598.3) * 1024 * 2.0,
-    "write_bytes_per_launch": 0.5 * (160126.8 + 103962.1) * 1024 * 1.0,
+# rocprofv3 counters of the kernels of ONE decode of record 0 of the default workload at scan group 10, read off the
+# summaries under profiles/ (which give the commands).  FETCH_SIZE reads 0.5 KiB per KiB a plain copy kernel fetches
+# and WRITE_SIZE 1.0 (profiles/), so fetched bytes are the counter x 2.  They describe the kernels as they stood when
+# the counters were taken: an entry is removed (-> null in the output) whenever its kernel changes.
+PMC = {
 }
-SALU_PEAK_GINSTS = 256 * 2.4      # one scalar instruction per cycle per compute unit, 256 CUs, 2.4 GHz
-# all kernels of one decode of record 0 at scan group 10 (same counter run): scalar / vector instructions
-RECORD0_INSTS = {"scalar": 2881.7e6, "vector": 1708.8e6}
+RECORD0_INSTS = None           # {"scalar": ..., "vector": ...} of all kernels of that decode, same counter run
 
-# Algorithmic work of the entropy kernels: Huffman-coded symbols per launch, counted with the CPU build of the
-# decoders (tests/host_emul) on record 0 of the default workload, and the scalar operations the serial chain of
-# this design needs per symbol at the very least (fetch the packed word of the current bit offset, test it, take
-# its length, add it to the position, apply the position update, test for the end of the block and of the
-# window).  Everything else a symbol needs is data-parallel work of the lanes.
-SYMBOLS_RECORD0 = {"dc_first": [3981894], "ac_first": [62868359], "ac_refine": [53792045, 46598601]}
+# The serial chain of one Huffman-coded symbol in this design, at the very least: fetch the packed word of the current
+# bit offset, test it, take its length, add it to the position, apply the position update, test for the end of the
+# block and of the window (8 scalar operations); everything else a symbol needs is data-parallel work of the lanes.
 CHAIN_OPS_PER_SYMBOL = 8
 
 
-def dominant_kernel_roofline(args, ends0, alone_ms, over_ms, alone, n_img, probe):
-    """Roofline object for k_ac_refine, the kernel with the largest share of the step at scan group 10
-    (at scan groups without AC refinement scans: k_ac_first, else k_dc_first)."""
-    k = args.scan_group
-    name = "ac_refine" if alone["ac_refine"][1] else ("ac_first" if alone["ac_first"][1] else "dc_first")
-    ms = alone_ms[name]
-    # what the method itself makes this kernel move: the entropy-coded bytes of its scans, read once
-    # (refinement scans of the 10-scan script: 6, 8, 9, 10; AC first: 2..5; DC first: 1)
-    scans = {"ac_refine": [6, 8, 9, 10], "ac_first": [2, 3, 4, 5], "dc_first": [1]}[name]
-    sizes = np.diff(np.concatenate([np.zeros((ends0.shape[0], 1), dtype=np.int64), ends0], axis=1), axis=1)
-    launches_per_call = max(1, alone[name][1] // 3)
-    alg = float(sum(sizes[:, j - 1].sum() for j in scans if j <= k)) / launches_per_call
-    default = args.images == 4096 and k == HEADLINE_K and name == "ac_refine"
-    pmc = AC_REFINE_PMC if default else None
-    sym = (sum(SYMBOLS_RECORD0[name]) / len(SYMBOLS_RECORD0[name])) if (args.images == 4096 and k == HEADLINE_K) else None
-    achieved = (CHAIN_OPS_PER_SYMBOL * sym / (ms * 1e-3) / 1e9) if sym else None
-    out = {
-        "kernel": "k_%s (one record of %d images decoded alone, mean of its %d launches per decode)" % (name, ends0.shape[0], launches_per_call),
-        "bound": "alu",
-        "achieved": achieved, "peak": SALU_PEAK_GINSTS, "unit": "G scalar operations/s",
-        "frac": (achieved / SALU_PEAK_GINSTS) if achieved else None,
-        "traffic": (pmc["fetch_bytes_per_launch"] + pmc["write_bytes_per_launch"]) if pmc else None,
-        "algorithmic": {"symbols_per_launch": sym, "chain_operations_per_symbol": CHAIN_OPS_PER_SYMBOL,
-                        "symbols_per_s": (sym / (ms * 1e-3)) if sym else None},
-        "issued": {"scalar_insts_per_launch": pmc["salu_insts_per_launch"] if pmc else None,
-                   "vector_insts_per_launch": pmc["valu_insts_per_launch"] if pmc else None,
-                   "G_scalar_insts_per_s": (pmc["salu_insts_per_launch"] / (ms * 1e-3) / 1e9) if pmc else None,
-                   "frac_of_peak": (pmc["salu_insts_per_launch"] / (ms * 1e-3) / 1e9 / SALU_PEAK_GINSTS) if pmc else None},
-        "peak_measured": probe,
-        "ms_per_launch": ms, "ms_per_launch_overlapped": over_ms[name],
-        "hbm_view": {"algorithmic_bytes_per_launch": alg, "achieved_GBps": alg / (ms * 1e-3) / 1e9,
-                     "frac_of_8TBps": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "note": "a serial Huffman decoder is bound by scalar-ALU issue (one wavefront per stream), not by HBM.  achieved = "
-                "symbols per launch x the scalar operations the serial chain needs per symbol / the launch duration measured "
-                "here with HIP events (record alone); peak = 256 CUs x 1 scalar instruction per cycle x 2.4 GHz; peak_measured "
-                "= the library's dependent-scalar-chain probe in this run; issued = what the kernel really executes "
-                "(rocprofv3 counters, profiles/)",
-    }
-    return out
+def read_scan_script(jpeg):
+    """[(components, Ss, Se, Ah, Al)] of a file's scans and its component sampling factors, from its SOF / SOS headers."""
+    p, comps, scans = 2, {}, []
+    order = []
+    while p + 4 <= len(jpeg):
+        assert jpeg[p] == 0xFF
+        m = jpeg[p + 1]
+        if m == 0xFF:
+            p += 1
+            continue
+        if m == 0xD9:
+            break
+        L = int.from_bytes(jpeg[p + 2:p + 4], "big")
+        s = p + 4
+        if m in (0xC0, 0xC1, 0xC2):
+            for c in range(jpeg[s + 5]):
+                comps[jpeg[s + 6 + 3 * c]] = (jpeg[s + 7 + 3 * c] >> 4, jpeg[s + 7 + 3 * c] & 15)
+                order.append(jpeg[s + 6 + 3 * c])
+        p += 2 + L
+        if m == 0xDA:
+            ns = jpeg[s]
+            cs = [order.index(jpeg[s + 1 + 2 * j]) for j in range(ns)]
+            scans.append((cs, jpeg[s + 1 + 2 * ns], jpeg[s + 2 + 2 * ns], jpeg[s + 3 + 2 * ns] >> 4, jpeg[s + 3 + 2 * ns] & 15))
+            while True:                                   # skip the entropy-coded data
+                p = jpeg.index(b"\xff", p)
+                if jpeg[p + 1] == 0 or 0xD0 <= jpeg[p + 1] <= 0xD7 or jpeg[p + 1] == 0xFF:
+                    p += 2 if jpeg[p + 1] != 0xFF else 1
+                    continue
+                break
+    return scans, [comps[c] for c in order]
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--images", type=int, default=4096, help="images of the workload to use (default: all 4096)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-baseline-files", action="store_true", help="skip the leg that decodes the same images as non-progressive files")
-    ap.add_argument("--scan-group", type=int, default=HEADLINE_K)
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain elementwise copy of 256 MiB (untimed), the yardstick for rocprofv3's FETCH_SIZE / WRITE_SIZE")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the decode path shards by record with no exchange between GPUs, "
-              "and this build runs on a single MI355X; --gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
+def algorithmic_bytes(ends, shapes, script, sampling, k):
+    """Bytes the method itself must move for scan group k (summed over the images): compressed prefix read once, each
+    coefficient position covered by scans <= k written once and read once (2 bytes each), pixels written once."""
+    nc = len(sampling)
+    hmax, vmax = max(h for h, _ in sampling), max(v for _, v in sampling)
+    cov = [set() for _ in range(nc)]
+    for cs, Ss, Se, Ah, Al in script[:k]:
+        for c in cs:
+            cov[c].update(range(Ss, Se + 1))
+    comp = int(ends[:, min(k, ends.shape[1]) - 1].sum())
+    out = touched = 0
+    for (W, H) in shapes:
+        mx, my = -(-W // (8 * hmax)), -(-H // (8 * vmax))
+        for c in range(nc):
+            touched += mx * sampling[c][0] * my * sampling[c][1] * len(cov[c])
+        out += W * H * nc
+    return dict(compressed=comp, touched=int(2 * touched), out=int(out), path=int(comp + 2 * 2 * touched + out), entropy=int(comp + 2 * touched))
 
-    import torch
-    import pcrgen
-    import paper_1911_00472_amd as pkg
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    pkg.lib()
 
-    t0 = time.time()
-    records, files = pcrgen.make_workload("imagenet_like", limit=args.images)
-    Ws, Hs = pcrgen.workload_shapes("imagenet_like", limit=args.images)
-    shapes = list(zip((int(w) for w in Ws), (int(h) for h in Hs)))
-    ends = scan_tables(files)
-    n_img = len(files)
-    gen_s = time.time() - t0
-    print("[bench] generated %d images (mean %.1f kB) in %d records, %.1f s" % (n_img, ends[:, -1].mean() / 1000, len(records), gen_s),
-          file=sys.stderr, flush=True)
+def scan_levels(script):
+    """Dependency level (1-based) of every scan: one more than the deepest earlier scan that shares a component and
+    overlaps in band -- the launches of the entropy kernels follow these levels."""
+    lv = []
+    for g, (cs, Ss, Se, Ah, Al) in enumerate(script):
+        d = 1
+        for q in range(g):
+            cq, sq, eq, _, _ = script[q]
+            if set(cs) & set(cq) and sq <= Se and Ss <= eq:
+                d = max(d, lv[q] + 1)
+        lv.append(d)
+    return lv
 
-    t0 = time.perf_counter()
-    handles = [pkg.pcr_open(r, 0) for r in records]
-    torch.cuda.synchronize()
-    open_ms = (time.perf_counter() - t0) * 1e3 / len(records)
-    outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in handles]
-    # one stream per record: records are independent, so their kernels may overlap (default priority)
-    streams = [torch.cuda.Stream() for _ in handles]
 
-    def step(k):
-        for h, o, st in zip(handles, outs, streams):
+def stage_of(scan):
+    cs, Ss, Se, Ah, Al = scan
+    if Ss == 0 and Se == 63:
+        return "sequential"
+    if Ss == 0:
+        return "dc_first" if Ah == 0 else None            # DC refinement has no serial decode
+    return "ac_first" if Ah == 0 else "ac_refine"
+
+
+class Job:
+    """One workload resident on the device: handles, output buffers, one stream per record."""
+
+    def __init__(self, torch, pkg, records, on_device=False):
+        self.torch, self.pkg, self.records = torch, pkg, records
+        t0 = time.perf_counter()
+        if on_device:                                       # bytes already in device memory: index and markers parsed on the device
+            self.dev = [torch.frombuffer(bytearray(r), dtype=torch.uint8).cuda() for r in records]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.handles = [pkg.pcr_open_device(d) for d in self.dev]
+        else:
+            self.handles = [pkg.pcr_open(r, 0) for r in records]
+        torch.cuda.synchronize()
+        self.open_ms = (time.perf_counter() - t0) * 1e3 / len(records)
+        self.outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in self.handles]
+        self.streams = [torch.cuda.Stream() for _ in self.handles]          # default priority
+        self.n_img = sum(h.n for h in self.handles)
+
+    def step(self, k):
+        for h, o, st in zip(self.handles, self.outs, self.streams):
             h.decode_batch(k, out=o, stream=st.cuda_stream)
 
-    if args.calibrate_copy:
-        # a kernel that reads 256 MiB and writes 256 MiB, nothing else: what the HBM counters read for it
-        # gives the factor by which the same counters of the decode kernels are scaled
-        a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
-        b = torch.empty_like(a)
-        torch.cuda.synchronize()
-        torch.add(a, 1, out=b)
-        torch.cuda.synchronize()
-        print("[bench] calibration copy: elementwise kernel, %d bytes read, %d bytes written" % (a.numel(), b.numel()), file=sys.stderr, flush=True)
-        del a, b
+    def close(self):
+        for h in self.handles:
+            h.close()
 
-    # ---- parity spot check against the oracle before anything is timed ----
-    import oracle
-    step(HEADLINE_K)
-    torch.cuda.synchronize()
-    lay = handles[0].output_layout()
-    host = outs[0].cpu().numpy()
-    for i in (0, 1, min(7, handles[0].n - 1)):
-        _, p0, info = oracle.decode_record_image(records[0], i, HEADLINE_K, want_coef=False)
-        got = host[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
-        assert np.abs(got - p0).max() <= 1, "parity check failed for image %d" % i
-
-    def timed(k, steps, warmup):
+    def timed(self, k, steps, warmup, single_steps=10):
+        """(mean s per step over `steps` steps in one bracket, [s of single steps], stage times overlapped, stage times
+        of record 0 decoded alone, calls)."""
+        torch, pkg = self.torch, self.pkg
         for _ in range(warmup):
-            step(k)
+            self.step(k)
         torch.cuda.synchronize()
-        for h in handles:
-            h.enable_stage_timing(True)          # starts a new event history on every handle
+        for h in self.handles:
+            h.enable_stage_timing(False)
         t = time.perf_counter()
         for _ in range(steps):
-            step(k)
+            self.step(k)
         torch.cuda.synchronize()
-        dt = time.perf_counter() - t
-        # HIP events the library recorded on each record's own stream around every kernel of the timed
-        # steps.  The records of a step overlap, so an interval here also holds the time a kernel spent
-        # sharing the GPU with the other records' kernels.
+        dt = (time.perf_counter() - t) / steps
+        singles = []
+        for _ in range(single_steps):
+            t = time.perf_counter()
+            self.step(k)
+            torch.cuda.synchronize()
+            singles.append(time.perf_counter() - t)
+        # HIP events the library records on each record's own stream around every kernel.  The records of a step
+        # overlap, so an interval here also holds the time a kernel spent sharing the GPU with the other records'.
+        for h in self.handles:
+            h.enable_stage_timing(True)
+        for _ in range(3):
+            self.step(k)
+        torch.cuda.synchronize()
         over = {n: [0.0, 0] for n in pkg.STAGE_NAMES}
-        for h in handles:
+        for h in self.handles:
             calls, hist = h.stage_ms_history()
             for n, (ms, launches) in hist.items():
                 over[n][0] += ms
                 over[n][1] += launches
-        # the same with record 0 decoded ALONE on its stream: every kernel has the GPU to itself, which is
-        # also what rocprofv3 reports (it serialises dispatches)
-        handles[0].enable_stage_timing(True)
+        # the same with record 0 decoded ALONE: every kernel has the GPU to itself (what rocprofv3 reports as well)
+        h0 = self.handles[0]
+        h0.enable_stage_timing(True)
         for _ in range(3):
-            handles[0].decode_batch(k, out=outs[0], stream=streams[0].cuda_stream)
+            h0.decode_batch(k, out=self.outs[0], stream=self.streams[0].cuda_stream)
         torch.cuda.synchronize()
-        calls, alone = handles[0].stage_ms_history()
-        return dt / steps, over, alone, calls
+        calls, alone = h0.stage_ms_history()
+        for h in self.handles:
+            h.enable_stage_timing(False)
+        return dt, singles, over, alone, calls
 
-    # ---- fidelity upgrades: from the planes of scan group a to scan group b, decoding only the new scans ----
-    def upgrade_step(k):
-        for h, o, st in zip(handles, outs, streams):
-            h.upgrade_batch(k, out=o, stream=st.cuda_stream)
 
-    chain = [k for k in SCAN_GROUPS]
-    reps = max(2, args.steps // 2)
-    acc = {(a, b): 0.0 for a, b in zip(chain[:-1], chain[1:])}
-    for _ in range(reps + 1):                                   # the first round warms the plans up
-        step(chain[0])
-        torch.cuda.synchronize()
-        for a, b in zip(chain[:-1], chain[1:]):
-            t = time.perf_counter()
-            upgrade_step(b)
-            torch.cuda.synchronize()
-            if _ > 0:
-                acc[(a, b)] += (time.perf_counter() - t) / reps
+def per_launch(d):
+    return {n: (ms / launches if launches else 0.0) for n, (ms, launches) in d.items()}
 
-    # ---- from pinned host memory: upload of the prefix fidelity k needs + bind + decode, one loader slot per record ----
-    # (the record bytes sit in the slots' pinned staging buffers before the clock starts: what a reader
-    # with O_DIRECT would have put there; every step uploads them again and re-binds the slots' handles)
+
+def dominant_kernel_roofline(workload, k, script, symbols0, ends0, alone, calls, over, probe, default_config):
+    """Roofline object for the kernel with the largest share of a record's decode at scan group k."""
+    stage_ms = {n: ms / calls for n, (ms, launches) in alone.items()}
+    name = max(stage_ms, key=lambda n: stage_ms[n])
+    launches_per_call = max(1, alone[name][1] // calls)
+    ms = alone[name][0] / max(1, alone[name][1])
+    over_ms = per_launch(over)[name]
+    entropy = name in ("dc_first", "ac_first", "ac_refine", "sequential")
+    scans = [g for g, sc in enumerate(script[:k]) if stage_of(sc) == name]
+    sizes = np.diff(np.concatenate([np.zeros((ends0.shape[0], 1), dtype=np.int64), ends0], axis=1), axis=1)
+    alg_bytes = float(sum(sizes[:, g].sum() for g in scans)) / launches_per_call if entropy else None
+    sym = (float(sum(symbols0[:, g].sum() for g in scans)) / launches_per_call) if (entropy and symbols0 is not None) else None
+    pmc = PMC.get(name) if default_config else None
+    out = {"kernel": "k_%s (record 0 decoded alone, mean of its %d launches per decode)" % (name, launches_per_call),
+           "share_of_a_lone_record_decode": stage_ms[name] / sum(stage_ms.values()),
+           "ms_per_launch": ms, "ms_per_launch_overlapped": over_ms, "peak_measured_G_scalar_insts_per_s": probe}
+    if entropy:
+        achieved = CHAIN_OPS_PER_SYMBOL * sym / (ms * 1e-3) / 1e9 if sym else None
+        out.update({
+            "bound": "alu", "achieved": achieved, "peak": SALU_PEAK_GINSTS, "unit": "G scalar operations/s",
+            "frac": achieved / SALU_PEAK_GINSTS if achieved else None,
+            "frac_is": "algorithmic scalar operations (symbols x %d operations of the serial chain) / launch duration / nominal scalar "
+                       "issue peak (256 CUs x 1 per cycle x 2.4 GHz); `issued` and `hbm_view` give the same launch by executed "
+                       "instructions and by algorithmic bytes" % CHAIN_OPS_PER_SYMBOL,
+            "traffic": (pmc["fetch_bytes"] + pmc["write_bytes"]) if pmc else None,
+            "algorithmic": {"symbols_per_launch": sym, "chain_operations_per_symbol": CHAIN_OPS_PER_SYMBOL,
+                            "symbols_per_s": sym / (ms * 1e-3) if sym else None,
+                            "source": "pcrgen.workload_symbol_counts (the encoder's own count of the Huffman-coded symbols of the scans of this launch)"},
+            "issued": ({"scalar_insts_per_launch": pmc["salu"], "vector_insts_per_launch": pmc["valu"],
+                        "scalar_insts_per_symbol": pmc["salu"] / sym if sym else None,
+                        "G_scalar_insts_per_s": pmc["salu"] / (ms * 1e-3) / 1e9,
+                        "frac_of_peak": pmc["salu"] / (ms * 1e-3) / 1e9 / SALU_PEAK_GINSTS, "source": pmc["source"]} if pmc else None),
+            "hbm_view": {"algorithmic_bytes_per_launch": alg_bytes, "achieved_GBps": alg_bytes / (ms * 1e-3) / 1e9,
+                         "frac_of_8TBps": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "note": "the entropy-coded bytes of the launch's scans, read once"},
+        })
+    else:                                                   # a data-parallel kernel: bytes against HBM (achieved is filled in by the caller)
+        out.update({"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                    "frac_is": "algorithmic bytes of the kernel / launch duration / 8 TB/s",
+                    "traffic": (pmc["fetch_bytes"] + pmc["write_bytes"]) if pmc else None})
+    return out, name
+
+
+def oracle_rates(oracle, records, k, threads, per_record):
+    """Oracle images/s at scan group k on the first `per_record` images of every record."""
+    t = time.perf_counter()
+    n = 0
+    for rec in records:
+        cnt = min(per_record, oracle.record_header(rec)["n"])
+        oracle.decode_record(rec, k, images=range(cnt), threads=threads, want_coef=False)
+        n += cnt
+    dt = time.perf_counter() - t
+    return n / dt, n, dt
+
+
+def measure_default_queues(records, k, steps, warmup):
+    """The same step in a child process that leaves GPU_MAX_HW_QUEUES at HIP's default (4): what a program measures
+    that does not set it.  The records travel through a temporary file."""
+    with tempfile.TemporaryDirectory() as tmp:
+        path = os.path.join(tmp, "records.bin")
+        with open(path, "wb") as f:
+            for r in records:
+                f.write(len(r).to_bytes(8, "little"))
+                f.write(r)
+        env = dict(os.environ)
+        env.pop("GPU_MAX_HW_QUEUES", None)
+        try:
+            out = subprocess.run([sys.executable, os.path.abspath(__file__), "--keep-queues", "--child-records", path, "--scan-group", str(k),
+                                  "--steps", str(steps), "--warmup", str(warmup)], env=env, capture_output=True, text=True, timeout=300)
+            return json.loads(out.stdout.strip().splitlines()[-1])
+        except Exception as e:                              # the figure is a side note: never fail the benchmark over it
+            return {"error": repr(e)[:200]}
+
+
+def child_main(args):
+    import torch
+    import paper_1911_00472_amd as pkg
+    records = []
+    with open(args.child_records, "rb") as f:
+        while True:
+            head = f.read(8)
+            if len(head) < 8:
+                break
+            records.append(f.read(int.from_bytes(head, "little")))
+    job = Job(torch, pkg, records)
+    for _ in range(args.warmup):
+        job.step(args.scan_group)
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for _ in range(args.steps):
+        job.step(args.scan_group)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t) / args.steps
+    job.close()
+    print(json.dumps({"GPU_MAX_HW_QUEUES": os.environ.get("GPU_MAX_HW_QUEUES", "unset (HIP default 4)"), "ms_per_step": dt * 1e3,
+                      "images_per_s": job.n_img / dt}))
+
+
+def streamed_from_pinned(torch, pkg, records, outs, scan_groups, n_img, steps):
+    """From pinned host memory: upload of the prefix fidelity k needs + bind (index and markers parsed on the device)
+    + decode, one loader slot per record; every step uploads the bytes again and re-binds the slots' handles."""
     streamed = {}
     cap = max(len(r) for r in records)
     with pkg.Loader(len(records), cap) as ld:
-        for k in SCAN_GROUPS:
+        for k in scan_groups:
             need = []
             for j, rec in enumerate(records):
                 ok, nb = pkg.prefix_length(rec[:24 + 8 * 64], k)
                 assert ok
                 need.append(nb)
                 ld.staging(j)[:nb] = np.frombuffer(rec, np.uint8)[:nb]
-            host_s = [0.0]
 
             def stream_step():
                 for j in range(len(records)):
-                    t1 = time.perf_counter()
                     ld.upload(j, need[j])
-                    host_s[0] += time.perf_counter() - t1
                     ld.decode(j, k, outs[j])
 
             stream_step()
             for j in range(len(records)):
                 ld.wait(j)
-            reps_s = max(5, args.steps)
-            host_s[0] = 0.0
+            reps = max(5, steps)
             t = time.perf_counter()
-            for _ in range(reps_s):
+            for _ in range(reps):
                 stream_step()
             for j in range(len(records)):
                 ld.wait(j)
-            dt = (time.perf_counter() - t) / reps_s
+            dt = (time.perf_counter() - t) / reps
             streamed[str(k)] = {"images_per_s": n_img / dt, "ms_per_step": dt * 1e3, "uploaded_MB_per_step": sum(need) / 1e6,
-                                "host_to_device_GBps": sum(need) / dt / 1e9, "ms_per_step_inside_upload_calls": host_s[0] / reps_s * 1e3}
+                                "host_to_device_GBps": sum(need) / dt / 1e9}
     torch.cuda.synchronize()
+    return streamed
 
-    # ---- training tail: decode, then one random box per image resized to 224 x 224, flipped, normalised, fp16 NCHW ----
+
+def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms):
+    """Measurements beyond the decode path proper (fidelity upgrade, training tail, similarity scores, the same images
+    as baseline files and with restart intervals); imagenet_like only, with --extras."""
+    handles, outs, streams, records, n_img = job.handles, job.outs, job.streams, job.records, job.n_img
+    res = {}
+    chain = list(TABLE_SCAN_GROUPS)
+    reps = max(2, args.steps // 2)
+    acc = {(a, b): 0.0 for a, b in zip(chain[:-1], chain[1:])}
+    for it in range(reps + 1):                                   # the first round warms the plans up
+        job.step(chain[0])
+        torch.cuda.synchronize()
+        for a, b in zip(chain[:-1], chain[1:]):
+            t = time.perf_counter()
+            for h, o, st in zip(handles, outs, streams):
+                h.upgrade_batch(b, out=o, stream=st.cuda_stream)
+            torch.cuda.synchronize()
+            if it > 0:
+                acc[(a, b)] += (time.perf_counter() - t) / reps
+    res["fidelity_upgrade"] = {"%d->%d" % ab: {"ms_per_step": s * 1e3, "fresh_decode_ms_per_step": per_k_ms.get(ab[1])} for ab, s in acc.items()}
+
+    # training tail: one random box per image resized to 224 x 224, flipped, normalised, fp16 NCHW
     rng = np.random.default_rng(1911_00472)
     crop_t, tails = [], []
     box_bytes = 0
@@ -292,31 +376,27 @@ def main():
         crop_t.append(torch.from_numpy(bx).cuda())
         tails.append(torch.empty((h.n, 3, 224, 224), dtype=torch.float16, device="cuda"))
     MEAN, ISTD = (0.485, 0.456, 0.406), (1 / 0.229, 1 / 0.224, 1 / 0.225)
+    k = args.scan_group
 
-    def tail_step(k):                                               # (one call: the pixel kernel skips strips outside the boxes)
+    def tail_step():
         for h, o, st, c, t in zip(handles, outs, streams, crop_t, tails):
             h.decode_crop_batch(k, c, 224, 224, MEAN, ISTD, pixels=o, out=t, stream=st.cuda_stream)
 
-    def tail_step_two_calls(k):
+    def tail_step_two_calls():
         for h, o, st, c, t in zip(handles, outs, streams, crop_t, tails):
             h.decode_batch(k, out=o, stream=st.cuda_stream)
             h.crop_resize_batch(o, c, 224, 224, MEAN, ISTD, out=t, stream=st.cuda_stream)
 
-    tail_step(args.scan_group)
-    torch.cuda.synchronize()
-    reps_t = max(3, args.steps)
-    t = time.perf_counter()
-    for _ in range(reps_t):
-        tail_step(args.scan_group)
-    torch.cuda.synchronize()
-    dt_tail = (time.perf_counter() - t) / reps_t
-    tail_step_two_calls(args.scan_group)
-    torch.cuda.synchronize()
-    t = time.perf_counter()
-    for _ in range(reps_t):
-        tail_step_two_calls(args.scan_group)
-    torch.cuda.synchronize()
-    dt_tail2 = (time.perf_counter() - t) / reps_t
+    times = []
+    for fn in (tail_step, tail_step_two_calls):
+        fn()
+        torch.cuda.synchronize()
+        reps_t = max(3, args.steps)
+        t = time.perf_counter()
+        for _ in range(reps_t):
+            fn()
+        torch.cuda.synchronize()
+        times.append((time.perf_counter() - t) / reps_t)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     with torch.cuda.stream(streams[0]):
         e0.record()
@@ -326,16 +406,12 @@ def main():
     torch.cuda.synchronize()
     tail_ms = e0.elapsed_time(e1) / 10
     tail_bytes = box_bytes / len(handles) + handles[0].n * 3 * 224 * 224 * 2
-    training_tail = {"out": "float16 [n, 3, 224, 224]", "images_per_s_decode_plus_tail": n_img / dt_tail, "ms_per_step_decode_plus_tail": dt_tail * 1e3,
-                     "ms_per_step_decode_then_tail_as_two_calls": dt_tail2 * 1e3,
-                     "scan_group": args.scan_group, "tail_kernel_ms_per_record_alone": tail_ms,
-                     "tail_kernel_algorithmic_GBps": tail_bytes / (tail_ms * 1e-3) / 1e9,
-                     "tail_kernel_frac_of_hbm_peak": tail_bytes / (tail_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "note": "algorithmic bytes of the tail kernel: the pixels of each image's box read once + the half-precision output written once"}
-
-    # ---- the whole input pipeline: pinned host bytes -> upload + bind -> decode -> crop / resize / normalise -> fp16 ----
+    res["training_tail"] = {"out": "float16 [n, 3, 224, 224]", "scan_group": k, "images_per_s_decode_plus_tail": n_img / times[0],
+                            "ms_per_step_decode_plus_tail": times[0] * 1e3, "ms_per_step_decode_then_tail_as_two_calls": times[1] * 1e3,
+                            "tail_kernel_ms_per_record_alone": tail_ms, "tail_kernel_algorithmic_GBps": tail_bytes / (tail_ms * 1e-3) / 1e9,
+                            "tail_kernel_frac_of_hbm_peak": tail_bytes / (tail_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    cap = max(len(r) for r in records)
     with pkg.Loader(len(records), cap) as ld:
-        k = args.scan_group
         need = []
         for j, rec in enumerate(records):
             ok, nb = pkg.prefix_length(rec[:24 + 8 * 64], k)
@@ -357,68 +433,158 @@ def main():
         for j in range(len(records)):
             ld.wait(j)
         dt_pipe = (time.perf_counter() - t) / reps_p
-    training_tail["images_per_s_from_pinned_host_memory"] = n_img / dt_pipe
-    training_tail["ms_per_step_from_pinned_host_memory"] = dt_pipe * 1e3
+    res["training_tail"]["images_per_s_from_pinned_host_memory"] = n_img / dt_pipe
     torch.cuda.synchronize()
 
-    # ---- fidelity estimate: similarity of each scan group's pictures to the full ones (record 0) ----
+    # fidelity estimate: similarity of each scan group's pictures to the full ones (record 0)
     G0 = handles[0].G
     with torch.cuda.stream(streams[0]):
         full0 = handles[0].decode_batch(G0, stream=streams[0].cuda_stream).clone()
         scores0 = torch.empty(handles[0].n, dtype=torch.float32, device="cuda")
         mean_score = {}
-        for k in [g for g in SCAN_GROUPS if g < G0]:
-            handles[0].decode_batch(k, out=outs[0], stream=streams[0].cuda_stream)
+        for kk in [g for g in TABLE_SCAN_GROUPS if g < G0]:
+            handles[0].decode_batch(kk, out=outs[0], stream=streams[0].cuda_stream)
             handles[0].msssim_batch(outs[0], full0, out=scores0, stream=streams[0].cuda_stream)
-            mean_score[str(k)] = float(scores0.mean().item())
+            mean_score[str(kk)] = float(scores0.mean().item())
         e0.record()
         for _ in range(5):
             handles[0].msssim_batch(outs[0], full0, out=scores0, stream=streams[0].cuda_stream)
         e1.record()
     torch.cuda.synchronize()
-    sim_ms = e0.elapsed_time(e1) / 5
-    fidelity_estimate = {"measure": "multi-scale structural similarity on luma against scan group %d, mean over the record's images" % G0,
-                         "mean_score_by_scan_group": mean_score, "ms_per_record": sim_ms,
-                         "pixel_GBps": 2 * full0.numel() / (sim_ms * 1e-3) / 1e9,
-                         "note": "pixel_GBps counts both batches read once; the kernel reads every scale from the uint8 pixels (about 5 x 1.7 reads with tile halos)"}
+    res["fidelity_estimate"] = {"measure": "multi-scale structural similarity on luma against scan group %d, mean over record 0" % G0,
+                                "mean_score_by_scan_group": mean_score, "ms_per_record": e0.elapsed_time(e1) / 5}
     del full0
 
+    # the same images as baseline (non-progressive) files, and with restart intervals in every scan
+    for label, kw, ks in (("baseline_sequential_files", dict(script="sequential"), (1,)), ("with_restart_intervals", dict(restart=128), TABLE_SCAN_GROUPS)):
+        recs, files = pcrgen.make_workload("imagenet_like", limit=args.images, **kw)
+        hs = [pkg.pcr_open(r, 0) for r in recs]
+        torch.cuda.synchronize()
+        rates = {}
+        for kk in ks:
+            def other_step():
+                for h, o, st in zip(hs, outs, streams):
+                    h.decode_batch(kk, out=o, stream=st.cuda_stream)
+            other_step(); other_step()
+            torch.cuda.synchronize()
+            lay = hs[0].output_layout()
+            host = outs[0].cpu().numpy()
+            _, p0, info = oracle.decode_record_image(recs[0], 3, kk, want_coef=False)
+            got = host[int(lay[3]):int(lay[4])].reshape(info.H, info.W, info.nc).astype(int)
+            assert np.abs(got - p0).max() <= 1, "parity check failed (%s)" % label
+            reps_b = max(5, args.steps)
+            t = time.perf_counter()
+            for _ in range(reps_b):
+                other_step()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t) / reps_b
+            rates[str(kk)] = {"images_per_s": n_img / dt, "ms_per_step": dt * 1e3}
+        res[label] = {"mean_file_kB": float(np.mean([len(f) for f in files]) / 1e3), "per_scan_group": rates}
+        for h in hs:
+            h.close()
+        del hs, recs, files
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="imagenet_like", choices=sorted(WORKLOAD_SCAN_GROUPS))
+    ap.add_argument("--images", type=int, default=None, help="use only the first N images of the workload")
+    ap.add_argument("--scan-group", type=int, default=None, help="the scan group `value` is quoted at (default: the highest)")
+    ap.add_argument("--extras", action="store_true", help="also: fidelity upgrades, training tail, similarity scores, baseline files, restart intervals")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-default-queues", action="store_true", help="skip the child process that measures the step with HIP's default number of hardware queues")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain elementwise copy of 256 MiB (untimed), the yardstick for rocprofv3's FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--keep-queues", action="store_true", help=argparse.SUPPRESS)
+    ap.add_argument("--child-records", default=None, help=argparse.SUPPRESS)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the decode path shards by record with no exchange between GPUs, "
+              "and this build runs on a single MI355X; --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if args.child_records:
+        return child_main(args)
+
+    import torch
+    import pcrgen
+    import paper_1911_00472_amd as pkg
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    pkg.lib()
+    name = args.workload
+    scan_groups = WORKLOAD_SCAN_GROUPS[name]
+    headline_k = args.scan_group or scan_groups[-1]
+    if headline_k not in scan_groups:
+        scan_groups = tuple(sorted(set(scan_groups) | {headline_k}))
+
+    t0 = time.time()
+    records, files = pcrgen.make_workload(name, limit=args.images)
+    Ws, Hs = pcrgen.workload_shapes(name, limit=args.images)
+    shapes = list(zip((int(w) for w in Ws), (int(h) for h in Hs)))
+    ends = np.array([pcrgen.split_scans(f) for f in files], dtype=np.int64)
+    script, sampling = read_scan_script(files[0])
+    n0 = len(files) if len(records) == 1 else pcrgen.WORKLOADS[name]["per_record"]
+    symbols0 = pcrgen.workload_symbol_counts(name, limit=min(n0, len(files)))          # record 0's images
+    print("[bench] %s: %d images (mean %.1f kB) in %d records, generated in %.1f s" % (name, len(files), ends[:, -1].mean() / 1000, len(records), time.time() - t0),
+          file=sys.stderr, flush=True)
+
+    job = Job(torch, pkg, records, on_device=(name == "ham_like"))
+    n_img = job.n_img
+
+    if args.calibrate_copy:
+        a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        torch.add(a, 1, out=b)
+        torch.cuda.synchronize()
+        print("[bench] calibration copy: elementwise kernel, %d bytes read, %d bytes written" % (a.numel(), b.numel()), file=sys.stderr, flush=True)
+        del a, b
+
+    # ---- parity spot check against the oracle before anything is timed ----
+    import oracle
+    job.step(headline_k)
+    torch.cuda.synchronize()
+    lay = job.handles[0].output_layout()
+    host = job.outs[0].cpu().numpy()
+    for i in (0, 1, min(7, job.handles[0].n - 1)):
+        _, p0, info = oracle.decode_record_image(records[0], i, headline_k, want_coef=False)
+        got = host[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
+        assert np.abs(got - p0).max() <= 1, "parity check failed for image %d" % i
+
     per_k = {}
-    for k in SCAN_GROUPS:
-        if k == args.scan_group:
-            continue
-        per_k[k] = timed(k, max(2, args.steps // 2), 1)
-    per_k[args.scan_group] = timed(args.scan_group, args.steps, args.warmup)
+    for k in scan_groups:
+        if k != headline_k:
+            per_k[k] = job.timed(k, max(3, args.steps // 2), 2)
+    per_k[headline_k] = job.timed(headline_k, args.steps, args.warmup)      # EXACTLY --steps steps after --warmup warm-up steps
 
-    upgrades = {}
-    for (a, b), sec_ab in acc.items():
-        upgrades["%d->%d" % (a, b)] = {"ms_per_step": sec_ab * 1e3, "fresh_decode_ms_per_step": per_k[b][0] * 1e3}
-
-    def per_launch(d):
-        return {n: (ms / launches if launches else 0.0) for n, (ms, launches) in d.items()}
-
+    threads = min(16, os.cpu_count() or 1)
     report = {}
     for k in sorted(per_k):
-        sec, over, alone, calls = per_k[k]
-        ab = algorithmic_bytes(ends, shapes, k)
+        sec, singles, over, alone, calls = per_k[k]
+        ab = algorithmic_bytes(ends, shapes, script, sampling, k)
         report[str(k)] = {
-            "images_per_s": n_img / sec,
-            "ms_per_step": sec * 1e3,
-            "output_GBps": ab["out"] / sec / 1e9,
-            "algorithmic_GBps": ab["path"] / sec / 1e9,
+            "images_per_s": n_img / sec, "ms_per_step": sec * 1e3,
+            "ms_per_step_median_of_single_steps": float(np.median(singles)) * 1e3, "ms_per_step_min_of_single_steps": float(np.min(singles)) * 1e3,
+            "output_GBps": ab["out"] / sec / 1e9, "algorithmic_GBps": ab["path"] / sec / 1e9,
             "hbm_roofline_frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS,
             "must_move_floor_GBps": (ab["compressed"] + ab["out"]) / sec / 1e9,
-            "stage_ms_one_record_alone": {n: ms / calls for n, (ms, launches) in alone.items()},
-            "kernel_ms_per_launch_alone": per_launch(alone),
-            "kernel_ms_per_launch_overlapped": per_launch(over),
+            "compressed_MB": ab["compressed"] / 1e6,
+            "stage_ms_one_record_alone": {n: ms / calls for n, (ms, launches) in alone.items() if launches},
+            "kernel_ms_per_launch_overlapped": {n: v for n, v in per_launch(over).items() if v},
         }
-    sec, over, alone, calls = per_k[args.scan_group]
-    ab = algorithmic_bytes(ends, shapes, args.scan_group)
-    n0 = handles[0].n
-    # what the chip sustains on chains of dependent scalar instructions (the library's own probe kernel), best of
-    # 8, 16 and 32 wavefronts per CU: the practical ceiling next to the nominal one
+        if not args.no_cpu_baseline:
+            rate, cnt, dt = oracle_rates(oracle, records, k, threads, max(16, 256 // len(records)))
+            report[str(k)]["oracle_images_per_s"] = rate
+            report[str(k)]["gpu_over_oracle"] = n_img / sec / rate
+    sec, singles, over, alone, calls = per_k[headline_k]
+    ab = algorithmic_bytes(ends, shapes, script, sampling, headline_k)
+
     probe = max(pkg.probe_scalar_issue_rate(w) for w in (8, 16, 32))
-    # what a plain device-to-device copy reaches on this machine (the second denominator for the HBM figures)
     ca = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     cb = torch.empty_like(ca)
     cb.copy_(ca)
@@ -431,136 +597,69 @@ def main():
     torch.cuda.synchronize()
     copy_gbps = 5 * 2 * ca.numel() / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
     del ca, cb
-    roofline = dominant_kernel_roofline(args, ends[:n0], per_launch(alone), per_launch(over), alone, n_img, probe)
 
-    # (the two legs below come after everything the headline figures are taken from)
-    # ---- the same images as baseline (non-progressive) files: what the decode of a progressive file costs over it ----
-    baseline = None
-    if not args.no_baseline_files:
-        seq_records, seq_files = pcrgen.make_workload("imagenet_like", limit=args.images, script="sequential")
-        seq_handles = [pkg.pcr_open(r, 0) for r in seq_records]
-        torch.cuda.synchronize()
-
-        def seq_step():
-            for h, o, st in zip(seq_handles, outs, streams):
-                h.decode_batch(1, out=o, stream=st.cuda_stream)
-
-        seq_step()
-        torch.cuda.synchronize()
-        lay_s = seq_handles[0].output_layout()
-        host = outs[0].cpu().numpy()
-        for i in (0, min(5, seq_handles[0].n - 1)):
-            _, p0, info = oracle.decode_record_image(seq_records[0], i, 1, want_coef=False)
-            got = host[int(lay_s[i]):int(lay_s[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
-            assert np.abs(got - p0).max() <= 1, "parity check failed for baseline image %d" % i
-        reps_b = max(5, args.steps)
-        t = time.perf_counter()
-        for _ in range(reps_b):
-            seq_step()
-        torch.cuda.synchronize()
-        dt_seq = (time.perf_counter() - t) / reps_b
-        seq_handles[0].enable_stage_timing(True)
-        for _ in range(3):
-            seq_handles[0].decode_batch(1, out=outs[0], stream=streams[0].cuda_stream)
-        torch.cuda.synchronize()
-        calls_b, alone_b = seq_handles[0].stage_ms_history()
-        baseline = {"files": "the same %d images (same quantised coefficients) as sequential Huffman files, mean %.1f kB" % (n_img, np.mean([len(f) for f in seq_files]) / 1e3),
-                    "images_per_s": n_img / dt_seq, "ms_per_step": dt_seq * 1e3,
-                    "stage_ms_one_record_alone": {n: v[0] / calls_b for n, v in alone_b.items() if v[1]},
-                    "note": "one wavefront per image (no restart intervals): a single pass, no refinement scans"}
-        for h in seq_handles:
-            h.close()
-        del seq_handles, seq_records, seq_files
-
-    # ---- the same images with restart intervals in every scan: more independent streams per image ----
-    with_restarts = None
-    if not args.no_baseline_files:
-        RI = 128
-        rst_records, rst_files = pcrgen.make_workload("imagenet_like", limit=args.images, restart=RI)
-        rst_handles = [pkg.pcr_open(r, 0) for r in rst_records]
-        torch.cuda.synchronize()
-        rst_rates = {}
-        for k in SCAN_GROUPS:
-            def rst_step():
-                for h, o, st in zip(rst_handles, outs, streams):
-                    h.decode_batch(k, out=o, stream=st.cuda_stream)
-            rst_step(); rst_step()
-            torch.cuda.synchronize()
-            if k == HEADLINE_K:
-                host = outs[0].cpu().numpy()
-                lay_r = rst_handles[0].output_layout()
-                _, p0, info = oracle.decode_record_image(rst_records[0], 3, k, want_coef=False)
-                got = host[int(lay_r[3]):int(lay_r[4])].reshape(info.H, info.W, info.nc).astype(int)
-                assert np.abs(got - p0).max() <= 1, "parity check failed for the image with restart intervals"
-            reps_r = max(5, args.steps)
-            t = time.perf_counter()
-            for _ in range(reps_r):
-                rst_step()
-            torch.cuda.synchronize()
-            dt_r = (time.perf_counter() - t) / reps_r
-            rst_handles[0].enable_stage_timing(True)
-            for _ in range(3):
-                rst_handles[0].decode_batch(k, out=outs[0], stream=streams[0].cuda_stream)
-            torch.cuda.synchronize()
-            calls_r, alone_r = rst_handles[0].stage_ms_history()
-            rst_handles[0].enable_stage_timing(False)
-            rst_rates[str(k)] = {"images_per_s": n_img / dt_r, "ms_per_step": dt_r * 1e3,
-                                 "ms_one_record_alone": sum(v[0] for v in alone_r.values()) / calls_r}
-        with_restarts = {"files": "the same %d images, same scans, a restart marker every %d MCUs of each scan; mean %.1f kB (%.2f %% more bytes)"
-                                  % (n_img, RI, np.mean([len(f) for f in rst_files]) / 1e3, 100.0 * (sum(map(len, rst_files)) / float(ends[:, -1].sum()) - 1.0)),
-                         "per_scan_group": rst_rates,
-                         "note": "what an encoder that knows the decoder can add: each restart interval is a stream of its own, so one image's "
-                                 "scan is decoded by several wavefronts; not the headline workload (stock encoders write no restart markers)"}
-        for h in rst_handles:
-            h.close()
-        del rst_handles, rst_records, rst_files
+    default_config = name == "imagenet_like" and args.images is None and headline_k == 10
+    nrec0 = job.handles[0].n
+    roofline, dom = dominant_kernel_roofline(name, headline_k, script, symbols0, ends[:nrec0], alone, calls, over, probe, default_config)
+    if roofline["bound"] == "hbm":                            # data-parallel kernel: its algorithmic bytes for record 0
+        ab0 = algorithmic_bytes(ends[:nrec0], shapes[:nrec0], script, sampling, headline_k)
+        kb = {"pixel": ab0["touched"] + ab0["out"], "unstuff": 2 * ab0["compressed"]}.get(dom)
+        if kb:
+            roofline["achieved"] = kb / (roofline["ms_per_launch"] * 1e-3) / 1e9
+            roofline["frac"] = roofline["achieved"] / HBM_PEAK_GBS
+    # the pixel kernel on its own against HBM (the one stage the byte model calls bandwidth-bound)
+    ab0 = algorithmic_bytes(ends[:nrec0], shapes[:nrec0], script, sampling, headline_k)
+    pix_ms = alone["pixel"][0] / max(1, alone["pixel"][1])
+    pixel_kernel = {"ms_per_launch_alone": pix_ms, "algorithmic_bytes": ab0["touched"] + ab0["out"],
+                    "achieved_GBps": (ab0["touched"] + ab0["out"]) / (pix_ms * 1e-3) / 1e9,
+                    "frac_of_8TBps": (ab0["touched"] + ab0["out"]) / (pix_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "note": "coefficients covered by scans <= k read once (2 bytes each) + pixels written once, record 0 alone"}
 
     cpu = None
     if not args.no_cpu_baseline:
-        threads = min(16, os.cpu_count() or 1)
-        # bounded sample: every record of the workload once, a few seconds of wall time on 16 threads
-        t = time.perf_counter()
-        sample = 0
-        for rec_bytes, h in zip(records, handles):
-            oracle.decode_record(rec_bytes, args.scan_group, images=range(h.n), threads=threads, want_coef=False)
-            sample += h.n
-        dt = time.perf_counter() - t
-        cpu = {"value": sample / dt, "unit": "images/s", "cores": threads, "kind": "oracle",
-               "sample": "all %d images of the workload once at scan group %d, %d threads, %.1f s wall (%.0f CPU-seconds)"
-                         % (sample, args.scan_group, threads, dt, dt * threads)}
+        rate16, cnt16, dt16 = oracle_rates(oracle, records, headline_k, threads, 1 << 30 if name == "imagenet_like" else max(64, 1024 // len(records)))
+        rate1, cnt1, dt1 = oracle_rates(oracle, records, headline_k, 1, max(4, 96 // len(records)))
+        cpu = {"value": rate16, "unit": "images/s", "cores": threads, "kind": "oracle",
+               "sample": "%d images of the workload (the first of every record) once at scan group %d, %d threads, %.1f s wall" % (cnt16, headline_k, threads, dt16),
+               "one_thread": {"value": rate1, "unit": "images/s", "cores": 1,
+                              "sample": "%d images at scan group %d, %.1f s" % (cnt1, headline_k, dt1)}}
 
     line = {
-        "metric": "decoded_images_per_sec_at_scan_group_%d" % args.scan_group,
+        "metric": "decoded_images_per_sec_at_scan_group_%d" % headline_k,
         "value": n_img / sec, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int16 coefficients, fp32 IDCT/colour, u8 pixels", "data": "synthetic",
-        "config": {"workload": "imagenet_like: %d RGB images, width/height uniform in [300,500], 4:2:0, quality 90, "
-                               "10-scan progressive, mean %.0f kB, %d records of <=1024" % (n_img, ends[:, -1].mean() / 1000, len(records)),
-                   "scan_group": args.scan_group, "images": n_img, "records": len(records)},
+        "config": {"workload": "%s: %d images, mean %.0f kB, %d records, sampling %s, %d scans" % (name, n_img, ends[:, -1].mean() / 1000, len(records),
+                                                                                                  "x".join("%d%d" % s for s in sampling), len(script)),
+                   "scan_group": headline_k, "images": n_img, "records": len(records),
+                   "records_opened": "from device memory (index and markers parsed on the device)" if name == "ham_like" else "from host bytes"},
+        "ms_per_step_median_of_single_steps": float(np.median(singles)) * 1e3, "ms_per_step_min_of_single_steps": float(np.min(singles)) * 1e3,
         "output_GBps": ab["out"] / sec / 1e9,
-        "open_ms_per_record": open_ms,
+        "open_ms_per_record": job.open_ms,
         "path_roofline": {"bound": "hbm", "achieved": ab["path"] / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": ab["path"] / sec / 1e9 / HBM_PEAK_GBS, "device_copy_GBps_measured": copy_gbps,
-                          "frac_of_measured_copy": ab["path"] / sec / 1e9 / copy_gbps},
+                          "frac_of_measured_copy": ab["path"] / sec / 1e9 / copy_gbps,
+                          "by_scan_group": {k: v["hbm_roofline_frac"] for k, v in report.items()}},
         "path_issue": ({"scalar_insts_per_step": RECORD0_INSTS["scalar"] * len(records), "vector_insts_per_step": RECORD0_INSTS["vector"] * len(records),
                         "G_scalar_insts_per_s": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9,
                         "frac_of_peak": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9 / SALU_PEAK_GINSTS,
-                        "frac_of_measured_peak": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9 / probe,
-                        "note": "instructions of one record (rocprofv3 counters of record 0) x records, over the timed step: how "
-                                "busy the scalar units are when the records overlap"}
-                       if (args.images == 4096 and args.scan_group == HEADLINE_K) else None),
+                        "frac_of_measured_peak": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9 / probe}
+                       if (default_config and RECORD0_INSTS) else None),
         "roofline": roofline,
+        "pixel_kernel": pixel_kernel,
         "cpu_baseline": cpu,
         "per_scan_group": report,
-        "fidelity_upgrade": upgrades,
-        "from_pinned_host_memory": streamed,
-        "training_tail": training_tail,
-        "fidelity_estimate": fidelity_estimate,
-        "baseline_sequential_files": baseline,
-        "with_restart_intervals": with_restarts,
     }
-    for h in handles:
-        h.close()
+    if name == "ham_like" or args.extras:
+        line["from_pinned_host_memory"] = streamed_from_pinned(torch, pkg, records, job.outs, scan_groups if name == "ham_like" else TABLE_SCAN_GROUPS,
+                                                               n_img, args.steps)
+    if args.extras and name == "imagenet_like":
+        line.update(extras(torch, pkg, pcrgen, oracle, job, args, ends, {k: v[0] * 1e3 for k, v in per_k.items()}))
+    job.close()
+    del job
+    torch.cuda.synchronize()
+    if not args.no_default_queues and len(records) > 1:
+        line["with_default_hardware_queues"] = measure_default_queues(records, headline_k, args.steps, args.warmup)
     print(json.dumps(line))
 
 
