@@ -23,6 +23,9 @@
  *   group 1 | ... | group G,   group g = region(0,g) | region(1,g) | ... | region(n-1,g)
  * region(i,g) is the slice of image i's progressive JPEG file from the end of its scan g-1
  * (or the file start) to the end of its scan g (or the file end for its last scan).
+ * Version 2 (pcr_record_write_indexed) has, behind len[G][n],  u32 entry_interval | u32 0 | u16 ecount[G][n],  and
+ * every group ends with its entry points, ecount[g][i] entries for image i one image after the other, each
+ *   u32 mcu | u32 bit | i16 pred[3] | u16 0   (see pcr_record_write_indexed); group_end[g] includes them.
  *
  * Not supported (PCR_E_UNSUPPORTED): arithmetic coding, 12-bit samples, lossless and
  * hierarchical modes, DNL, component counts other than 1 or 3, sampling factors other than 1
@@ -302,6 +305,20 @@ int pcr_scan_ends(const void* jpeg, size_t nbytes, uint64_t* ends, int max_ends,
 int pcr_record_size(const void* const* files, const size_t* sizes, uint32_t n, uint64_t* record_bytes, uint32_t* scan_groups);
 int pcr_record_write(const void* const* files, const size_t* sizes, const int32_t* labels, uint32_t n, void* out, size_t capacity,
                      uint64_t* written);
+/* pcr_record_write with entry points (record version 2).  The paper's metadata says where every scan group starts;
+ * its Section 4.2 names the decode as the bottleneck, and each scan of a stock file is one serial stream.  This
+ * writer walks every scan once and stores, about every entry_interval MCUs of the scan (blocks, for a scan of one
+ * component), a place where a decoder may start: a block boundary outside any end-of-band run, its bit offset in
+ * the scan's data without the stuffed bytes, and the DC predictions there (16 bytes per entry, kept at the end of
+ * the scan's own scan group, so a read at fidelity k brings only the entries of scans 1..k; about 1.5 % of the
+ * record at an interval of 128).  The image bytes are those pcr_record_write writes, byte for byte, and every call
+ * of this library gives the same results for both records; the decoder gives every entry a wavefront of its own
+ * (as it does for restart intervals), which shortens the decode of a record without touching the files.  Scans with
+ * restart markers and files the walk cannot follow get no entries.  entry_interval: 1 .. 2^20 (PCR_E_RANGE); other
+ * arguments and errors as pcr_record_write; the size cannot be known before the walk: on PCR_E_RANGE *written says
+ * how much is needed (sum of the file sizes + 2 % + the header always suffices for intervals of 64 and more). */
+int pcr_record_write_indexed(const void* const* files, const size_t* sizes, const int32_t* labels, uint32_t n, uint32_t entry_interval,
+                             void* out, size_t capacity, uint64_t* written);
 int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
                               void* out, size_t capacity, uint64_t* written);
 

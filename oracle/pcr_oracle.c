@@ -46,10 +46,12 @@ static uint64_t rd64(const uint8_t* p) { return (uint64_t)rd32(p) | ((uint64_t)r
 int orc_record_header(const uint8_t* rec, size_t nbytes, uint32_t* n, uint32_t* G, uint64_t* header_bytes, int* k_avail) {
     if (!rec || nbytes < 24) return ORC_E_TRUNCATED;
     if (memcmp(rec, "PCR1", 4) != 0) return ORC_E_FORMAT;
-    if (rd32(rec + 4) != 1) return ORC_E_UNSUPPORTED;
+    uint32_t version = rd32(rec + 4);
+    if (version != 1 && version != 2) return ORC_E_UNSUPPORTED;
     *n = rd32(rec + 8); *G = rd32(rec + 12); *header_bytes = rd64(rec + 16);
     if (*n == 0 || *G == 0) return ORC_E_FORMAT;
     uint64_t need = 24 + 8ull * *G + 8ull * *n + 4ull * *G * *n;
+    if (version == 2) need += 8 + 2ull * *G * *n;            /* entry interval, reserved word, entry counts */
     if (*header_bytes < need) return ORC_E_FORMAT;
     if (nbytes < *header_bytes) return ORC_E_TRUNCATED;
     int k = 0; uint64_t prev = *header_bytes;
@@ -75,6 +77,10 @@ int orc_record_index(const uint8_t* rec, size_t nbytes, uint64_t* off, uint32_t*
     const uint8_t* pn = pl + 4 * (size_t)n;
     const uint8_t* pz = pn + 4 * (size_t)n;
     for (uint32_t i = 0; i < n; i++) { if (label) label[i] = (int32_t)rd32(pl + 4 * i); if (nscans) nscans[i] = rd32(pn + 4 * i); }
+    /* Version 2 records end every group with decoder hints (places inside the scans where a decoder may start),
+     * 16 bytes each, as many per image as the count table behind the length table says.  A plain decoder has
+     * no use for them: they are skipped, and only their size enters the check that the group is tiled. */
+    const uint8_t* pe = rd32(rec + 4) == 2 ? pz + 4 * (size_t)G * n + 8 : NULL;
     uint64_t start = hb;
     for (uint32_t g = 0; g < G; g++) {
         uint64_t pos = start;
@@ -82,7 +88,8 @@ int orc_record_index(const uint8_t* rec, size_t nbytes, uint64_t* off, uint32_t*
             uint32_t L = rd32(pz + 4 * ((size_t)g * n + i));
             off[(size_t)g * n + i] = pos; len[(size_t)g * n + i] = L; pos += L;
         }
-        if (pos != rd64(p + 8 * g)) return ORC_E_FORMAT;      /* regions must tile the group */
+        if (pe) for (uint32_t i = 0; i < n; i++) { const uint8_t* c = pe + 2 * ((size_t)g * n + i); pos += 16ull * (c[0] | ((uint32_t)c[1] << 8)); }
+        if (pos != rd64(p + 8 * g)) return ORC_E_FORMAT;      /* regions (and hints) must tile the group */
         start = pos;
     }
     return ORC_OK;

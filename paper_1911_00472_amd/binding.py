@@ -50,6 +50,8 @@ SYMBOLS = {
                                        ctypes.POINTER(ctypes.c_uint32)]),
     "pcr_record_write": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_size_t), _vp, ctypes.c_uint32, _vp, ctypes.c_size_t,
                                         ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_record_write_indexed": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_size_t), _vp, ctypes.c_uint32, ctypes.c_uint32, _vp,
+                                                ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_transcode_progressive": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.c_size_t, ctypes.c_uint32, _vp, ctypes.c_size_t,
                                                  ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_select_scan_group": (ctypes.c_int, [_vp, ctypes.c_float, _vp, _vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_float),
@@ -86,6 +88,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libpcr.so is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                                "(or paper_1911_00472_amd/build.py) first; there is no fallback path")
+        try:
+            import torch  # noqa: F401  (PyTorch brings its own copy of the HIP runtime; it must be the first one this process
+        except ImportError:                  # loads, or its later initialisation finds no GPU: libpcr.so then binds to the same copy)
+            pass
         L = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in SYMBOLS.items():
             f = getattr(L, name)
@@ -364,6 +370,26 @@ def record_write(files, labels=None):
                                   out.size, ctypes.byref(written)), "pcr_record_write")
     assert written.value == out.size
     return out.tobytes()
+
+
+def record_write_indexed(files, labels=None, entry_interval=128):
+    """A version-2 record (bytes) from JPEG files: as record_write, plus entry points about every entry_interval MCUs
+    of every scan, which the decoder uses as it uses restart intervals (pcr_record_write_indexed)."""
+    bufs, ptrs, sizes = _file_table(files)
+    lab = None if labels is None else np.ascontiguousarray(labels, np.int32)
+    assert lab is None or lab.size == len(bufs)
+    total = sum(b.size for b in bufs)
+    cap = total + total // 50 + 64 * 1024 + 64 * len(bufs) * 4
+    written = ctypes.c_uint64(0)
+    for _ in range(2):
+        out = np.empty(cap, np.uint8)
+        rc = lib().pcr_record_write_indexed(ptrs, sizes, lab.ctypes.data_as(_vp) if lab is not None else None, len(bufs), entry_interval,
+                                            out.ctypes.data_as(_vp), out.size, ctypes.byref(written))
+        if rc != E_RANGE or written.value <= cap:
+            break
+        cap = int(written.value)
+    _check(rc, "pcr_record_write_indexed")
+    return out[:int(written.value)].tobytes()
 
 
 def transcode_progressive(src_jpeg, coef, restart_interval=0):

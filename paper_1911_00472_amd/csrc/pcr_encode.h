@@ -7,10 +7,14 @@
 // starts from come from the device decoder (pcr_decode_coefficients), which reads baseline and progressive
 // sources alike.
 #pragma once
+#include <algorithm>
+#include <atomic>
 #include <cstring>
+#include <thread>
 #include <vector>
 
 #include "pcr_format.h"
+#include "pcr_entropy.h"
 
 namespace pcr {
 namespace enc {
@@ -102,6 +106,235 @@ inline void write_record(const RecordPlan& P, const void* const* files, const in
                 pos += len;
             }
             st_le32(out + hdr_len_pos(n, G, g, i), len);
+        }
+        st_le64(out + hdr_group_end_pos(g), pos);
+    }
+    for (uint32_t i = 0; i < n; i++) {
+        st_le32(out + hdr_label_pos(G, i), labels ? (uint32_t)labels[i] : 0u);
+        st_le32(out + hdr_nscans_pos(n, G, i), P.nscans[i]);
+    }
+}
+
+// ---- entry points (record version 2) ----------------------------------------------------------------------
+// A scan of a stock file is one serial stream.  The record writer walks every scan once and notes, about every
+// `interval` MCUs, a place where a decoder may start: a block boundary outside any end-of-band run, the bit
+// offset of that place in the scan's data without the stuffed bytes, and the DC predictions there.  The walk
+// needs no coefficient values, only which positions of every block are non-zero so far (the refinement scans'
+// zero runs skip those).  Scans with restart markers need no entries: every restart interval is a start already.
+struct EntryPoint { uint32_t mcu, bit; int16_t pred[3]; uint16_t zero; };
+static_assert(sizeof(EntryPoint) == kEntryBytes, "entry layout");
+
+struct BitCursor {
+    const uint8_t* d; uint64_t nbits, pos; bool bad;
+    // the 32 bits at the cursor (the buffer is padded beyond its end)
+    uint32_t peek() const {
+        const uint8_t* p = d + (pos >> 3);
+        const uint64_t v = ((uint64_t)p[0] << 32) | ((uint64_t)p[1] << 24) | ((uint64_t)p[2] << 16) | ((uint64_t)p[3] << 8) | p[4];
+        return (uint32_t)(v >> (8 - (pos & 7)));
+    }
+    void skip(uint32_t n) { pos += n; if (pos > nbits) bad = true; }
+    uint32_t take(uint32_t n) { const uint32_t v = n ? peek() >> (32 - n) : 0; skip(n); return v; }
+};
+
+// Entropy-coded data of a scan without stuffed zeros, fill bytes and restart markers; starts[j] = first byte of
+// restart interval j.  Stops at the first other marker.
+inline void unstuff_scan(const uint8_t* src, uint32_t L, std::vector<uint8_t>* out, std::vector<uint32_t>* starts) {
+    out->clear(); starts->assign(1, 0);
+    for (uint32_t q = 0; q < L; q++) {
+        const uint8_t cur = src[q];
+        if (cur != 0xFF) { out->push_back(cur); continue; }
+        if (q + 1 >= L) break;
+        const uint8_t nx = src[q + 1];
+        if (nx == 0x00) { out->push_back(0xFF); q++; }
+        else if (nx >= 0xD0 && nx <= 0xD7) { starts->push_back((uint32_t)out->size()); q++; }
+        else if (nx == 0xFF) continue;
+        else break;
+    }
+}
+
+// ent[g]: entry points of scan g of the file (empty where there are none, also for every scan from the first one
+// this walk cannot follow).  ends: the file's region ends (scan_ends).  Returns kOk, or why the frame was refused.
+inline int find_entry_points(const uint8_t* file, const uint64_t* ends, uint32_t nscans, uint32_t interval, std::vector<EntryPoint>* ent) {
+    for (uint32_t g = 0; g < nscans; g++) ent[g].clear();
+    if (interval == 0 || nscans > (uint32_t)kMaxScansPerFile) return kOk;
+    uint32_t off[kMaxScansPerFile], len[kMaxScansPerFile];
+    for (uint32_t g = 0; g < nscans; g++) { off[g] = g ? (uint32_t)ends[g - 1] : 0u; len[g] = (uint32_t)ends[g] - off[g]; }
+    ImgDesc img; std::vector<ScanDesc> sc(nscans);
+    memset(&img, 0, sizeof img); memset(sc.data(), 0, sizeof(ScanDesc) * nscans);
+    parse_image(file, off, len, 1, 0, nscans, nscans, &img, sc.data());
+    if (img.status != kOk) return img.status;
+    std::vector<uint64_t> nz[kMaxComp];
+    for (int c = 0; c < img.nc; c++) nz[c].assign((size_t)img.bw[c] * img.bh[c], 0);
+    std::vector<uint8_t> clean; std::vector<uint32_t> starts;
+    std::vector<DcTab> dt(kMaxComp); std::vector<AcTab> at(kMaxComp);
+    for (uint32_t g = 0; g < nscans; g++) {
+        const ScanDesc& sd = sc[g];
+        const bool seq = !img.progressive;
+        if (!seq && sd.Ss == 0 && sd.Ah > 0) continue;               // DC refinement: one bit per block, nothing to walk
+        unstuff_scan(file + sd.data_off, sd.data_len, &clean, &starts);
+        const uint32_t nint = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;
+        if (starts.size() != nint) return kOk;                        // damaged: the decoder will say so
+        starts.push_back((uint32_t)clean.size());
+        const uint64_t total_bits = (uint64_t)clean.size() * 8;
+        clean.resize(clean.size() + 16, 0xFF);
+        if (seq || sd.Ss == 0) for (int j = 0; j < sd.ns; j++) dctab_build(&dt[j], file + sd.dc_off[j]);
+        if (seq) for (int j = 0; j < sd.ns; j++) actab_build(&at[j], file + sd.ac_offc[j]);
+        else if (sd.Ss > 0) actab_build(&at[0], file + sd.ac_off);
+        const int c0 = sd.comp[0];
+        const uint64_t band = (sd.Se >= 63 ? ~0ull : ((1ull << (sd.Se + 1)) - 1)) & ~((1ull << sd.Ss) - 1);
+        std::vector<EntryPoint>& E = ent[g];
+        BitCursor b{clean.data(), total_bits, 0, false};
+        for (uint32_t iv = 0; iv < nint && !b.bad; iv++) {
+            b.pos = (uint64_t)starts[iv] * 8;
+            b.nbits = (uint64_t)starts[iv + 1] * 8;
+            int pred[kMaxComp] = {0, 0, 0};
+            uint32_t eobrun = 0;
+            const uint32_t m0 = sd.ri ? iv * sd.ri : 0, m1 = sd.ri ? std::min(m0 + sd.ri, sd.mcus) : sd.mcus;
+            uint32_t next_entry = interval;
+            for (uint32_t m = m0; m < m1 && !b.bad; m++) {
+                if (sd.ri == 0 && m >= next_entry && eobrun == 0 && E.size() < 65535) {
+                    EntryPoint e; e.mcu = m; e.bit = (uint32_t)b.pos; e.zero = 0;
+                    for (int j = 0; j < kMaxComp; j++) e.pred[j] = (int16_t)pred[j];
+                    E.push_back(e);
+                    next_entry = (m / interval + 1) * interval;
+                }
+                if (seq || sd.Ss == 0) {                             // blocks of every scan component of the MCU
+                    for (int j = 0; j < sd.ns && !b.bad; j++) {
+                        const int c = sd.comp[j];
+                        const uint32_t nb = sd.ns > 1 ? (uint32_t)img.hs[c] * img.vs[c] : 1u;
+                        for (uint32_t q = 0; q < nb && !b.bad; q++) {
+                            const uint32_t e = dc_code(&dt[j], b.peek());
+                            if (!e) { b.bad = true; break; }
+                            b.skip(e >> 4);
+                            pred[j] += extend(b.take(e & 15), (int)(e & 15));
+                            if (!seq) continue;
+                            for (int k = 1; k < 64 && !b.bad;) {
+                                const uint32_t a = ac_code(&at[j], b.peek());
+                                if (!a) { b.bad = true; break; }
+                                const uint32_t r = (a >> 4) & 15, sz = a & 15;
+                                b.skip(a >> 8);
+                                if (sz) { k += (int)r + 1; b.skip(sz); }
+                                else if (r == 15) k += 16;
+                                else break;
+                            }
+                        }
+                    }
+                    continue;
+                }
+                uint64_t& h = nz[c0][(size_t)(m / sd.mcu_w) * img.bw[c0] + m % sd.mcu_w];
+                if (sd.Ah == 0) {                                    // AC first
+                    if (eobrun) { eobrun--; continue; }
+                    for (int k = sd.Ss; k <= sd.Se && !b.bad;) {
+                        const uint32_t a = ac_code(&at[0], b.peek());
+                        if (!a) { b.bad = true; break; }
+                        const uint32_t r = (a >> 4) & 15, sz = a & 15;
+                        b.skip(a >> 8);
+                        if (sz) {
+                            k += (int)r;
+                            if (k > sd.Se) { b.bad = true; break; }
+                            b.skip(sz); h |= 1ull << k; k++;
+                        } else if (r == 15) k += 16;
+                        else { eobrun = (1u << r) - 1 + b.take(r); break; }
+                    }
+                } else {                                             // AC refinement
+                    int k = sd.Ss;
+                    if (eobrun == 0) {
+                        while (k <= sd.Se && !b.bad) {
+                            const uint32_t a = ac_code(&at[0], b.peek());
+                            if (!a) { b.bad = true; break; }
+                            uint32_t r = (a >> 4) & 15; const uint32_t sz = a & 15;
+                            b.skip(a >> 8);
+                            if (sz > 1) { b.bad = true; break; }
+                            if (sz == 0 && r < 15) { eobrun = (1u << r) + b.take(r); break; }   // (counts this block)
+                            if (sz) b.skip(1);                       // the sign
+                            while (k <= sd.Se) {                     // over r zeros; a correction bit at every non-zero on the way
+                                if ((h >> k) & 1) b.skip(1);
+                                else { if (r == 0) break; r--; }
+                                k++;
+                            }
+                            if (sz) { if (k > sd.Se) { b.bad = true; break; } h |= 1ull << k; }
+                            k++;
+                        }
+                    }
+                    if (eobrun) {                                    // the rest of the block: corrections only
+                        const uint64_t rest = k <= 63 ? (h & band & ~((1ull << k) - 1)) : 0;
+                        b.skip((uint32_t)__builtin_popcountll(rest));
+                        eobrun--;
+                    }
+                }
+            }
+        }
+        if (b.bad) { E.clear(); return kOk; }                         // no entries from here on: later scans build on this one
+    }
+    return kOk;
+}
+
+struct IndexedPlan {
+    RecordPlan P;
+    uint32_t interval = 0;
+    std::vector<std::vector<EntryPoint>> ent;                    // [n * kMaxScansPerFile]
+};
+
+inline int plan_record_indexed(const void* const* files, const size_t* sizes, uint32_t n, uint32_t interval, IndexedPlan* Q) {
+    int rc = plan_record(files, sizes, n, &Q->P);
+    if (rc) return rc;
+    Q->interval = interval;
+    Q->ent.assign((size_t)n * kMaxScansPerFile, std::vector<EntryPoint>());
+    std::atomic<uint32_t> next(0);
+    auto work = [&]() {
+        for (;;) {
+            const uint32_t i = next.fetch_add(1);
+            if (i >= n) break;
+            (void)find_entry_points((const uint8_t*)files[i], &Q->P.ends[(size_t)i * kMaxScansPerFile], Q->P.nscans[i], interval,
+                                    &Q->ent[(size_t)i * kMaxScansPerFile]);   // (a file the walk refuses simply has no entries)
+        }
+    };
+    const uint32_t nthreads = std::max(1u, std::min({16u, std::thread::hardware_concurrency(), n}));
+    std::vector<std::thread> pool;
+    for (uint32_t t = 1; t < nthreads; t++) pool.emplace_back(work);
+    work();
+    for (auto& t : pool) t.join();
+    uint64_t entries = 0;
+    for (const auto& e : Q->ent) entries += e.size();
+    const uint64_t raw = hdr_ecount_pos(n, Q->P.G, Q->P.G, 0);
+    Q->P.header_bytes = (raw + 63) / 64 * 64;
+    uint64_t payload = 0;
+    for (uint32_t i = 0; i < n; i++) payload += sizes[i];
+    Q->P.total = Q->P.header_bytes + payload + entries * kEntryBytes;
+    if (Q->P.total >= (1ull << 32)) return kEUnsupported;
+    return kOk;
+}
+
+inline void write_record_indexed(const IndexedPlan& Q, const void* const* files, const int32_t* labels, uint8_t* out) {
+    const RecordPlan& P = Q.P;
+    const uint32_t n = P.n, G = P.G;
+    memset(out, 0, P.header_bytes);
+    memcpy(out, "PCR1", 4);
+    st_le32(out + 4, 2); st_le32(out + 8, n); st_le32(out + 12, G); st_le64(out + 16, P.header_bytes);
+    st_le32(out + hdr_entry_interval_pos(n, G), Q.interval);
+    uint64_t pos = P.header_bytes;
+    for (uint32_t g = 0; g < G; g++) {
+        for (uint32_t i = 0; i < n; i++) {
+            uint32_t len = 0;
+            if (g < P.nscans[i]) {
+                const uint64_t* e = &P.ends[(size_t)i * kMaxScansPerFile];
+                const uint64_t from = g ? e[g - 1] : 0;
+                len = (uint32_t)(e[g] - from);
+                memcpy(out + pos, (const uint8_t*)files[i] + from, len);
+                pos += len;
+            }
+            st_le32(out + hdr_len_pos(n, G, g, i), len);
+        }
+        for (uint32_t i = 0; i < n; i++) {                          // the group's entries behind its regions
+            const std::vector<EntryPoint>& E = Q.ent[(size_t)i * kMaxScansPerFile + g];
+            uint8_t* c = out + hdr_ecount_pos(n, G, g, i);
+            c[0] = (uint8_t)E.size(); c[1] = (uint8_t)(E.size() >> 8);
+            for (const EntryPoint& e : E) {
+                st_le32(out + pos, e.mcu); st_le32(out + pos + 4, e.bit);
+                for (int j = 0; j < 3; j++) { out[pos + 8 + 2 * j] = (uint8_t)(uint16_t)e.pred[j]; out[pos + 9 + 2 * j] = (uint8_t)((uint16_t)e.pred[j] >> 8); }
+                out[pos + 14] = out[pos + 15] = 0;
+                pos += kEntryBytes;
+            }
         }
         st_le64(out + hdr_group_end_pos(g), pos);
     }

@@ -296,13 +296,17 @@ struct WindowReader {
     bool first;
     bool vfeed;                 // fetch the stream through the vector memory path (see fetch_next)
 
-    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const AcTab* t, bool first_scan, uint32_t lane_id, bool vector_feed) {
+    // The unit starts sub_bits (0..7) bits into byte byte_off of the segment and holds nbits bits counted from that
+    // byte's first bit; pos0: what position() reports for the byte's first bit (0: positions relative to the unit's
+    // first byte, as for restart intervals; byte_off * 8: positions in the scan, as for units that start at entry points).
+    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t sub_bits, uint32_t nbits, uint32_t pos0, const AcTab* t, bool first_scan,
+                     uint32_t lane_id, bool vector_feed) {
         tab = t; first = first_scan; lane = lane_id; vfeed = vector_feed;
         mis_bits = (byte_off & 3) * 8;
         p = stream_ptr(words + (byte_off >> 2));
         w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
         g = words + (byte_off >> 2) + 5;
-        o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits;
+        o = mis_bits + sub_bits; wbase = pos0; total_bits = pos0 + nbits + mis_bits;
         vnext = 0;
         fetch_next();
         fill();
@@ -392,6 +396,7 @@ struct LaneScan {
     int ns;
     uint32_t hs[kMaxComp], vs[kMaxComp], bw[kMaxComp];
     uint32_t poff[kMaxComp];   // element offset of each scan component's plane inside the image's coefficient buffer
+    int pred[kMaxComp];        // DC predictions at the unit's first MCU (0 after a restart marker; an entry point brings its own)
 };
 
 // ---------------------------------------------------------------------------------------
@@ -475,14 +480,14 @@ struct DcWindowReader {
     const uint32_t* g;              // p again, for the vector memory path (as in WindowReader)
     uint32_t vnext;
 
-    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t nbytes, const DcTab* t0, const DcTab* t1, const DcTab* t2,
-                     int ncomponents, uint32_t lane_id) {
+    PCR_HD void init(const uint32_t* words, uint32_t byte_off, uint32_t sub_bits, uint32_t nbits, const DcTab* t0, const DcTab* t1, const DcTab* t2,
+                     int ncomponents, uint32_t lane_id) {                  // (byte_off, sub_bits, nbits: as WindowReader::init)
         tab[0] = t0; tab[1] = t1; tab[2] = t2; ncomp = ncomponents; lane = lane_id;
         mis_bits = (byte_off & 3) * 8;
         p = stream_ptr(words + (byte_off >> 2));
         w0 = p[0]; w1 = p[1]; w2 = p[2]; n0 = p[3]; n1 = p[4]; p += 5;
         g = words + (byte_off >> 2) + 5;
-        o = mis_bits; wbase = 0; total_bits = nbytes * 8 + mis_bits; nocode = 0;
+        o = mis_bits + sub_bits; wbase = 0; total_bits = nbits + mis_bits; nocode = 0;
         vinfo[0] = vinfo[1] = vinfo[2] = 0;
         fetch_next();
         fill();
@@ -564,7 +569,7 @@ PCR_HD void dc_first_block(DcWindowReader* wr, CoefSink* sink, int* pred, uint32
 // recomputed per MCU.
 template <int NS, int HS0, int VS0>
 PCR_HD int decode_dc_first_shape(DcWindowReader* wr, const LaneScan& ls, CoefSink* sink) {
-    int pred0 = 0, pred1 = 0, pred2 = 0;
+    int pred0 = ls.pred[0], pred1 = ls.pred[1], pred2 = ls.pred[2];
     const uint32_t mcu_w = ls.mcu_w;
     const uint32_t my0 = ls.mcu0 / mcu_w;
     uint32_t mx = ls.mcu0 % mcu_w;
@@ -607,7 +612,7 @@ PCR_HD void dc_first_component(DcWindowReader* wr, const LaneScan& ls, CoefSink*
     }
 }
 PCR_HD int decode_dc_first_any(DcWindowReader* wr, const LaneScan& ls, CoefSink* sink) {
-    int pred0 = 0, pred1 = 0, pred2 = 0;
+    int pred0 = ls.pred[0], pred1 = ls.pred[1], pred2 = ls.pred[2];
     uint32_t my = ls.mcu0 / ls.mcu_w, mx = ls.mcu0 % ls.mcu_w;
     uint32_t bad = 0;
     uint32_t m = ls.mcu0;
@@ -858,7 +863,7 @@ PCR_HD void sequential_component(WindowReader* wr, const LaneScan& ls, const Seq
 // The sink's plane is the image's coefficient buffer; ls.poff[j] locates the plane of scan component j in it.
 // The reader must have been initialised with tb.ac[0] as a first-scan reader.
 PCR_HD int decode_sequential(WindowReader* wr, const LaneScan& ls, const SeqTables& tb, IndexSink* sink) {
-    int pred0 = 0, pred1 = 0, pred2 = 0;
+    int pred0 = ls.pred[0], pred1 = ls.pred[1], pred2 = ls.pred[2];
     uint32_t my = ls.mcu0 / ls.mcu_w, mx = ls.mcu0 % ls.mcu_w;
     uint32_t bad = 0;
     uint32_t m = ls.mcu0;

@@ -9,6 +9,18 @@
 // "Encoding"): region 1 starts with SOI and carries the frame header and tables, every
 // later region carries the tables and the SOS header of its one scan followed by the
 // entropy-coded data.
+//
+// Version 2 adds entry points, an index INTO the scans (the paper's metadata only says where each scan group
+// starts; Section 4.2 names the decode of a scan as the bottleneck, and a scan of a stock file is one serial
+// stream): after len[G][n] the header carries
+//   u32 entry_interval | u32 0 | u16 ecount[G][n]
+// and group g ends with the entries of its scans, image after image, ecount[g][i] entries of 16 bytes each:
+//   u32 mcu | u32 bit | i16 pred[3] | u16 0
+// "decoding of this scan may start at MCU `mcu` of the scan (block `mcu` of a scan of one component), at bit `bit`
+// of its entropy-coded data counted without the stuffed zero bytes, with the DC predictions `pred` of the scan's
+// components (scans that code DC differences), and no end-of-band run is pending there".  Entries are in
+// increasing order; scans with restart markers and DC refinement scans have none.  The image bytes are exactly
+// those of version 1: region lengths and offsets do not change, group_end[g] includes the group's entries.
 #pragma once
 #include "pcr_common.h"
 
@@ -18,23 +30,31 @@ struct RecordHeader {
     uint32_t n, G;
     uint64_t header_bytes;
     uint32_t k_avail;                      // scan groups wholly inside the bytes given
+    uint32_t version;                      // 1, or 2: with entry points
+    uint32_t entry_interval;               // version 2: MCUs between entry points the writer aimed at (informative)
 };
+constexpr uint32_t kEntryBytes = 16;
 
 PCR_HD uint64_t hdr_group_end_pos(uint32_t g) { return 24 + 8ull * g; }
 PCR_HD uint64_t hdr_label_pos(uint32_t G, uint32_t i) { return 24 + 8ull * G + 4ull * i; }
 PCR_HD uint64_t hdr_nscans_pos(uint32_t n, uint32_t G, uint32_t i) { return 24 + 8ull * G + 4ull * n + 4ull * i; }
 PCR_HD uint64_t hdr_len_pos(uint32_t n, uint32_t G, uint32_t g, uint32_t i) { return 24 + 8ull * G + 8ull * n + 4ull * ((uint64_t)g * n + i); }
+PCR_HD uint64_t hdr_entry_interval_pos(uint32_t n, uint32_t G) { return hdr_len_pos(n, G, G, 0); }                  // version 2
+PCR_HD uint64_t hdr_ecount_pos(uint32_t n, uint32_t G, uint32_t g, uint32_t i) { return hdr_len_pos(n, G, G, 0) + 8 + 2ull * ((uint64_t)g * n + i); }
+PCR_HD uint32_t ld_le16(const uint8_t* p) { return (uint32_t)p[0] | ((uint32_t)p[1] << 8); }
 
 // Validate the fixed part of the header.  `bytes` must hold at least min(nbytes, header).
 PCR_HD int parse_record_header(const uint8_t* bytes, uint64_t nbytes, RecordHeader* h) {
     if (nbytes < 24) return kETruncated;
     if (bytes[0] != 'P' || bytes[1] != 'C' || bytes[2] != 'R' || bytes[3] != '1') return kEFormat;
-    if (ld_le32(bytes + 4) != 1) return kEUnsupported;
+    h->version = ld_le32(bytes + 4);
+    if (h->version != 1 && h->version != 2) return kEUnsupported;
     h->n = ld_le32(bytes + 8); h->G = ld_le32(bytes + 12); h->header_bytes = ld_le64(bytes + 16);
     if (h->n == 0 || h->G == 0 || h->G > 64 || h->n > (1u << 24)) return kEFormat;
-    uint64_t need = hdr_len_pos(h->n, h->G, h->G, 0);
+    uint64_t need = h->version == 2 ? hdr_ecount_pos(h->n, h->G, h->G, 0) : hdr_len_pos(h->n, h->G, h->G, 0);
     if (h->header_bytes < need) return kEFormat;
     if (nbytes < h->header_bytes) return kETruncated;
+    h->entry_interval = h->version == 2 ? ld_le32(bytes + hdr_entry_interval_pos(h->n, h->G)) : 0;
     uint64_t prev = h->header_bytes; uint32_t k = 0;
     for (uint32_t g = 0; g < h->G; g++) {
         uint64_t e = ld_le64(bytes + hdr_group_end_pos(g));

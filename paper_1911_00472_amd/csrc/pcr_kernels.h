@@ -50,6 +50,7 @@ struct DevRecord {
     AcTab* tabs;               // Huffman tables of the AC scans: those of the refinement scans are written by phase 1 for phase 2;
                                // with tabs_prebuilt, k_build_tables has written all of them before the entropy kernels start
     const uint32_t* tab_idx;   // [n][G] index into tabs
+    const uint32_t* ent_off;   // [n][G] record offset of the scan's entry points (0: none; then slot_cnt - 1 of them)
     uint32_t tabs_prebuilt;    // set per call by the host (records whose scans have restart intervals)
 };
 
@@ -182,7 +183,7 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kfrom, ui
         // intervals whose restart marker never showed up get an empty range; the end goes last
         for (uint32_t r = rst_total + 1; r <= sc; r++) R.ivl_start[sb + r] = out_total;
         R.ivl_start[sb + sc] = out_total;
-        if (rst_total + 1 != sc) R.status[i] = kEFormat;
+        if (rst_total + 1 != (sd.ri ? sc : 1u)) R.status[i] = kEFormat;      // (without restart intervals the units of a scan start at entry points)
         if (sd.Ss == 0 && sd.Ah != 0) {
             // DC refinement is read in place later (one bit per block): check every interval is long enough
             uint32_t bpm = 0;
@@ -215,7 +216,7 @@ constexpr int kEntropyLanes = 64;
 
 struct UnitSetup {
     const uint32_t* words;        // segment base, unit start and length for the window readers
-    uint32_t byte_off, nbytes;
+    uint32_t byte_off, sub_bits, nbits, pos0;
     LaneScan ls;
     int16_t* plane[kMaxComp];     // planes of the scan's components
     uint32_t plane_elems[kMaxComp];
@@ -232,13 +233,32 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __rest
     const ScanDesc* sd = &R.scan[ig];
     if (!sd->valid) return;
     const uint32_t sb = R.slot_base[ig];
-    const uint32_t b0 = R.ivl_start[sb + un.interval], b1 = R.ivl_start[sb + un.interval + 1];
     const uint32_t ri = sd->ri, mcus = sd->mcus;
     LaneScan& ls = L->ls;
     ls.mcu_w = uni(sd->mcu_w);
-    ls.mcu0 = uni(ri ? un.interval * ri : 0);
-    ls.mcu1 = uni(ri ? (ls.mcu0 + ri < mcus ? ls.mcu0 + ri : mcus) : mcus);
-    if (ls.mcu0 >= mcus) return;
+    ls.pred[0] = ls.pred[1] = ls.pred[2] = 0;
+    const uint32_t sc = R.slot_cnt[ig];
+    if (ri == 0 && sc > 1) {
+        // Units of a scan without restart markers start at the record's entry points: unit j runs from entry j-1
+        // (the scan's start for j = 0) to entry j (the scan's end for the last unit).
+        const uint8_t* e = R.rec + uni(R.ent_off[ig]) + (size_t)kEntryBytes * un.interval;        // entry j; entry j-1 lies 16 bytes before it
+        const uint32_t total = uni(R.ivl_start[sb + sc]) * 8;                                    // bits of the scan's unstuffed data
+        uint32_t m0 = 0, bit0 = 0, m1 = mcus, bit1 = total;
+        if (un.interval > 0) {
+            m0 = uni(ld_le32(e - 16)); bit0 = uni(ld_le32(e - 12));
+            ls.pred[0] = uni((int)(int16_t)ld_le16(e - 8)); ls.pred[1] = uni((int)(int16_t)ld_le16(e - 6)); ls.pred[2] = uni((int)(int16_t)ld_le16(e - 4));
+        }
+        if (un.interval + 1 < sc) { m1 = uni(ld_le32(e)); bit1 = uni(ld_le32(e + 4)); }
+        if (!(m0 < m1 && m1 <= mcus && bit0 <= bit1 && bit1 <= total)) { R.status[un.img] = kEFormat; return; }   // entries out of order or out of range
+        ls.mcu0 = m0; ls.mcu1 = m1;
+        L->byte_off = bit0 >> 3; L->sub_bits = bit0 & 7; L->nbits = bit1 - (bit0 & ~7u); L->pos0 = bit0 & ~7u;
+    } else {
+        const uint32_t b0 = R.ivl_start[sb + un.interval], b1 = R.ivl_start[sb + un.interval + 1];
+        ls.mcu0 = uni(ri ? un.interval * ri : 0);
+        ls.mcu1 = uni(ri ? (ls.mcu0 + ri < mcus ? ls.mcu0 + ri : mcus) : mcus);
+        if (ls.mcu0 >= mcus) return;
+        L->byte_off = uni(b0); L->sub_bits = 0; L->nbits = uni(b1 > b0 ? b1 - b0 : 0) * 8; L->pos0 = 0;
+    }
     ls.Ss = uni((int)sd->Ss); ls.Se = uni((int)sd->Se); ls.Al = uni((int)sd->Al); ls.ns = uni((int)sd->ns);
     int16_t* base = R.coef + uni((uint64_t)R.coef_off[un.img]);
     size_t poff[kMaxComp + 1]; poff[0] = 0;
@@ -256,7 +276,6 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __rest
     L->base = base;
     L->base_elems = (uint32_t)poff[kMaxComp];
     L->words = clean32 + (uni(clean_base(sd->data_off)) >> 2);
-    L->byte_off = uni(b0); L->nbytes = uni(b1 > b0 ? b1 - b0 : 0);
     L->ok = true;
 }
 
@@ -281,7 +300,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     if (threadIdx.x == 2 && tj2 != 0 && tj2 != tj1) dctab_build(&tabs[tj2], R.rec + o2);
     __syncthreads();
     DcWindowReader wr;                                      // tables by scan component
-    wr.init(L.words, L.byte_off, L.nbytes, &tabs[0], &tabs[uni(tj1)], &tabs[uni(tj2)], L.ls.ns, threadIdx.x);
+    wr.init(L.words, L.byte_off, L.sub_bits, L.nbits, &tabs[0], &tabs[uni(tj1)], &tabs[uni(tj2)], L.ls.ns, threadIdx.x);
     CoefSink sink;
     sink.init(L.base, L.base_elems, L.ls.Al);
     int rc = kEFormat;                                      // (a unit in the wrong launch: the descriptors disagree with the host's)
@@ -334,7 +353,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     const size_t ig = (size_t)un.img * R.G + un.scan;
     load_ac_table(R, ig, true, &tab);
     WindowReader wr;
-    wr.init(L.words, L.byte_off, L.nbytes, &tab, true, threadIdx.x, true);
+    wr.init(L.words, L.byte_off, L.sub_bits, L.nbits, L.pos0, &tab, true, threadIdx.x, true);
     IndexSink sink;
     sink.init(L.plane[0], L.plane_elems[0], L.ls.Al);
     int rc = decode_ac_first(&wr, L.ls, &sink);
@@ -375,7 +394,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_sequential(DevRecord R, const
     tb.dc[0] = &dtabs[0]; tb.dc[1] = &dtabs[uni(dj1)]; tb.dc[2] = &dtabs[uni(dj2)];
     tb.ac[0] = &atabs[0]; tb.ac[1] = &atabs[uni(aj1)]; tb.ac[2] = &atabs[uni(aj2)];
     WindowReader wr;
-    wr.init(L.words, L.byte_off, L.nbytes, tb.ac[0], true, threadIdx.x, true);
+    wr.init(L.words, L.byte_off, L.sub_bits, L.nbits, L.pos0, tb.ac[0], true, threadIdx.x, true);
     IndexSink sink;
     sink.init(L.base, L.base_elems, 0);
     const int rc = decode_sequential(&wr, L.ls, tb, &sink);
@@ -410,7 +429,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     const size_t plane = (size_t)uni((uint32_t)img->bw[c]) * uni((uint32_t)img->bh[c]);
     uint64_t* mk = R.masks + uni((uint64_t)R.mask_off[ig]);
     WindowReader wr;
-    wr.init(L.words, L.byte_off, L.nbytes, &tab, false, threadIdx.x, false);
+    wr.init(L.words, L.byte_off, L.sub_bits, L.nbits, L.pos0, &tab, false, threadIdx.x, false);
     int rc = skim_ac_refine(&wr, L.ls, hp, mk);
     if (rc != kOk) R.status[un.img] = rc;
 }

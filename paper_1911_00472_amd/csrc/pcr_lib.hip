@@ -344,6 +344,8 @@ static int validate_index(const uint8_t* hdr, const RecordHeader& h, std::vector
             uint32_t L = ld_le32(hdr + hdr_len_pos(n, G, g, i));
             (*off)[(size_t)g * n + i] = (uint32_t)pos; (*len)[(size_t)g * n + i] = L; pos += L;
         }
+        if (h.version == 2)                                       // the group's entry points lie behind its regions
+            for (uint32_t i = 0; i < n; i++) pos += (uint64_t)kEntryBytes * ld_le16(hdr + hdr_ecount_pos(n, G, g, i));
         if (pos != ld_le64(hdr + hdr_group_end_pos(g))) return PCR_E_FORMAT;
         start = pos;
     }
@@ -370,6 +372,21 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     uint64_t nm = 0; uint64_t ns = 0;
     std::vector<uint32_t> tab_idx((size_t)n * G, 0); uint32_t ntabs = 0;
     r->prebuild_tables = false;
+    // version 2: where the entry points of every scan lie (behind the regions of the scan's group)
+    std::vector<uint32_t> ent_off((size_t)n * G, 0), ent_cnt((size_t)n * G, 0);
+    if (r->hdr.version == 2) {
+        const uint8_t* hdr = r->header.data();
+        for (uint32_t g = 0; g < r->hdr.k_avail; g++) {
+            uint64_t cnt = 0;
+            for (uint32_t i = 0; i < n; i++) cnt += ld_le16(hdr + hdr_ecount_pos(n, G, g, i));
+            uint64_t at = ld_le64(hdr + hdr_group_end_pos(g)) - cnt * kEntryBytes;      // (validate_index: this is where the regions end)
+            for (uint32_t i = 0; i < n; i++) {
+                const uint32_t c = ld_le16(hdr + hdr_ecount_pos(n, G, g, i));
+                ent_off[(size_t)i * G + g] = (uint32_t)at; ent_cnt[(size_t)i * G + g] = c;
+                at += (uint64_t)c * kEntryBytes;
+            }
+        }
+    }
     for (uint32_t i = 0; i < n; i++) {
         const ImgDesc& d = r->img[i];
         r->out_off[i + 1] = r->out_off[i] + (uint64_t)d.W * d.H * d.nc;
@@ -390,6 +407,9 @@ static int finish_open(pcr_record* r, hipStream_t s) {
                 tab_idx[ig] = ntabs++;                       // (first scans use theirs only when the tables are built ahead)
             }
             uint32_t cnt = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;
+            const bool serial = !(d.progressive && sd.Ss == 0 && sd.Ah > 0);          // (DC refinement is read in place, without units)
+            if (sd.ri == 0 && serial && ent_cnt[ig] > 0) cnt = 1 + ent_cnt[ig];         // units start at the entry points
+            else ent_off[ig] = 0;
             if (cnt > 1 && sd.Ss > 0) r->prebuild_tables = true;     // several units share a scan's table: build it once
             r->slot_base[ig] = (uint32_t)ns; r->slot_cnt[ig] = cnt;
             ns += cnt + 1;
@@ -407,7 +427,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     size_t need = arena_round(padded) + arena_round(r->coef_off[n] * sizeof(int16_t)) + arena_round((nm + 2) * sizeof(uint64_t)) +
                   arena_round((ns + 1) * sizeof(uint32_t)) + 2 * arena_round((n + 1) * sizeof(uint64_t)) +
                   4 * arena_round(((size_t)n * G + 1) * sizeof(uint64_t)) + arena_round((tiles.size() + 1) * sizeof(PixelTile)) + arena_round((n + 1) * 8) +
-                  arena_round(((size_t)ntabs + 1) * sizeof(AcTab));
+                  arena_round(((size_t)ntabs + 1) * sizeof(AcTab)) + arena_round(((size_t)n * G + 1) * sizeof(uint32_t));
     need += 8 * ((ns + (size_t)n * G) * sizeof(Unit) + (size_t)n * kMaxComp * 64) + (1u << 20);
     int rc = arena_reset(&r->big, need);
     if (!rc) rc = arena_alloc(&r->big, &d.clean, padded);
@@ -426,6 +446,9 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     if (!rc) rc = arena_upload(&r->big, &r->d_dims, dims);
     uint32_t* d_tab_idx = nullptr;
     if (!rc) rc = arena_upload(&r->big, &d_tab_idx, tab_idx);
+    uint32_t* d_ent_off = nullptr;
+    if (!rc) rc = arena_upload(&r->big, &d_ent_off, ent_off);
+    d.ent_off = d_ent_off;
     if (!rc) rc = arena_alloc(&r->big, &d.tabs, (size_t)ntabs);
     d.tab_idx = d_tab_idx;
     d.coef_off = d_coef_off; d.out_off = d_out_off; d.mask_off = d_mask_off; d.slot_base = d_sb; d.slot_cnt = d_sc;
@@ -900,6 +923,19 @@ int pcr_record_write(const void* const* files, const size_t* sizes, const int32_
     return PCR_OK;
 }
 
+int pcr_record_write_indexed(const void* const* files, const size_t* sizes, const int32_t* labels, uint32_t n, uint32_t entry_interval,
+                             void* out, size_t capacity, uint64_t* written) {
+    if (!files || !sizes || !out) return PCR_E_ARG;
+    if (entry_interval < 1 || entry_interval > (1u << 20)) return PCR_E_RANGE;
+    enc::IndexedPlan Q;
+    const int rc = enc::plan_record_indexed(files, sizes, n, entry_interval, &Q);
+    if (rc) return rc;
+    if (written) *written = Q.P.total;
+    if (capacity < Q.P.total) return PCR_E_RANGE;
+    enc::write_record_indexed(Q, files, labels, (uint8_t*)out);
+    return PCR_OK;
+}
+
 int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
                               void* out, size_t capacity, uint64_t* written) {
     if (!src_jpeg || !coef || !written) return PCR_E_ARG;
@@ -970,7 +1006,7 @@ int pcr_prefix_length(const void* first_bytes, size_t nbytes, int k, uint64_t* n
     const uint8_t* b = (const uint8_t*)first_bytes;
     if (nbytes < 24) { *need = 24; return PCR_E_TRUNCATED; }
     if (b[0] != 'P' || b[1] != 'C' || b[2] != 'R' || b[3] != '1') return PCR_E_FORMAT;
-    if (ld_le32(b + 4) != 1) return PCR_E_UNSUPPORTED;
+    if (ld_le32(b + 4) != 1 && ld_le32(b + 4) != 2) return PCR_E_UNSUPPORTED;
     const uint32_t G = ld_le32(b + 12);
     if (k < 1 || (uint32_t)k > G) return PCR_E_RANGE;
     const size_t pos = hdr_group_end_pos((uint32_t)k - 1);

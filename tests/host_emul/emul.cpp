@@ -39,6 +39,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
     for (uint32_t g = 0; g < h.k_avail; g++) {
         uint64_t pos = start;
         for (uint32_t i = 0; i < n; i++) { uint32_t L = ld_le32(rec + hdr_len_pos(n, G, g, i)); off[(size_t)g * n + i] = (uint32_t)pos; len[(size_t)g * n + i] = L; pos += L; }
+        if (h.version == 2) for (uint32_t i = 0; i < n; i++) pos += (uint64_t)kEntryBytes * ld_le16(rec + hdr_ecount_pos(n, G, g, i));
         start = pos;
     }
     uint32_t i = (uint32_t)want_img;
@@ -61,6 +62,18 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
         uint32_t nint = sd.ri ? (sd.mcus + sd.ri - 1) / sd.ri : 1;
         if (starts.size() != nint) return kEFormat;
         starts.push_back((uint32_t)clean.size());
+        // version 2: the units of a scan without restart markers start at its entry points
+        const uint8_t* ent = nullptr;
+        if (h.version == 2 && sd.ri == 0 && !(img.progressive && sd.Ss == 0 && sd.Ah > 0)) {
+            const uint32_t ec = ld_le16(rec + hdr_ecount_pos(n, G, g, i));
+            if (ec) {
+                uint64_t cnt = 0, before = 0;
+                for (uint32_t q = 0; q < n; q++) { const uint32_t c = ld_le16(rec + hdr_ecount_pos(n, G, g, q)); cnt += c; if (q < i) before += c; }
+                ent = rec + ld_le64(rec + hdr_group_end_pos(g)) - cnt * kEntryBytes + before * kEntryBytes;
+                nint = 1 + ec;
+            }
+        }
+        const uint32_t total_bits = (uint32_t)clean.size() * 8;
         clean.resize((clean.size() + 3) / 4 * 4 + 64, 0xFF);      // look-ahead slack
         for (size_t e = 0; e + 3 < clean.size(); e += 4) { std::swap(clean[e], clean[e + 3]); std::swap(clean[e + 1], clean[e + 2]); }   // big-endian words
         int c0 = sd.comp[0];
@@ -71,6 +84,18 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
             LaneScan ls;
             ls.mcu_w = sd.mcu_w; ls.mcu0 = sd.ri ? j * sd.ri : 0;
             ls.mcu1 = sd.ri ? (ls.mcu0 + sd.ri < sd.mcus ? ls.mcu0 + sd.ri : sd.mcus) : sd.mcus;
+            ls.pred[0] = ls.pred[1] = ls.pred[2] = 0;
+            uint32_t byte_off, sub_bits = 0, nbits, pos0 = 0;
+            if (ent) {
+                const uint8_t* e = ent + (size_t)kEntryBytes * j;
+                uint32_t bit0 = 0, bit1 = total_bits;
+                ls.mcu0 = 0; ls.mcu1 = sd.mcus;
+                if (j > 0) { ls.mcu0 = ld_le32(e - 16); bit0 = ld_le32(e - 12); for (int q = 0; q < 3; q++) ls.pred[q] = (int16_t)ld_le16(e - 8 + 2 * q); }
+                if (j + 1 < nint) { ls.mcu1 = ld_le32(e); bit1 = ld_le32(e + 4); }
+                if (!(ls.mcu0 < ls.mcu1 && ls.mcu1 <= sd.mcus && bit0 <= bit1 && bit1 <= total_bits)) return kEFormat;
+                byte_off = bit0 >> 3; sub_bits = bit0 & 7; nbits = bit1 - (bit0 & ~7u); pos0 = bit0 & ~7u;
+            } else { byte_off = starts[j]; nbits = (starts[j + 1] - starts[j]) * 8; }
+            const uint32_t unit_base = ent ? 0u : starts[j];           // what phase 2 of a refinement scan adds to a block's recorded start
             ls.Ss = sd.Ss; ls.Se = sd.Se; ls.Al = sd.Al; ls.ns = sd.ns;
             int16_t* cpl[kMaxComp] = {nullptr, nullptr, nullptr};
             for (int q = 0; q < kMaxComp; q++) {
@@ -87,18 +112,18 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 SeqTables tb;
                 for (int q = 0; q < kMaxComp; q++) { tb.dc[q] = &dt[q]; tb.ac[q] = &at[q]; }
                 WindowReader sw;
-                sw.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], tb.ac[0], true, 0, true);
+                sw.init(reinterpret_cast<const uint32_t*>(clean.data()), byte_off, sub_bits, nbits, pos0, tb.ac[0], true, 0, true);
                 IndexSink ssink; ssink.init(coef.data(), (uint32_t)coef.size(), 0);
                 rc = decode_sequential(&sw, ls, tb, &ssink);
             } else if (sd.Ss == 0) {
                 std::vector<DcTab> dt(3);
                 for (int q = 0; q < sd.ns; q++) dctab_build(&dt[q], rec + sd.dc_off[q]);
-                DcWindowReader dw; dw.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &dt[0], &dt[1], &dt[2], sd.ns, 0);
+                DcWindowReader dw; dw.init(reinterpret_cast<const uint32_t*>(clean.data()), byte_off, sub_bits, nbits, &dt[0], &dt[1], &dt[2], sd.ns, 0);
                 CoefSink dsink; dsink.init(coef.data(), (uint32_t)coef.size(), ls.Al);
                 rc = decode_dc_first(&dw, ls, &dsink);
             } else {
                 AcTab at; actab_build(&at, rec + sd.ac_off); actab_pack(&at, sd.Ah == 0, 0, 1);
-                WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], starts[j + 1] - starts[j], &at, sd.Ah == 0, 0, sd.Ah == 0);
+                WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), byte_off, sub_bits, nbits, pos0, &at, sd.Ah == 0, 0, sd.Ah == 0);
                 if (sd.Ah == 0) {
                     IndexSink sink; sink.init(cpl[0], (uint32_t)plane * 64, ls.Al);
                     rc = decode_ac_first(&wr, ls, &sink);
@@ -111,7 +136,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                     for (uint32_t mm = ls.mcu0; mm < ls.mcu1; mm++) {
                         size_t blk = (size_t)(mm / sd.mcu_w) * img.bw[c0] + (mm % sd.mcu_w);
                         uint64_t* rec = masks[g].data() + blk * kRefWords;
-                        refine_block(reinterpret_cast<const uint32_t*>(clean.data()), starts[j], rec[kRefStart], &at, rec[kRefHist], rec[kRefNz], sd.Ss, sd.Se,
+                        refine_block(reinterpret_cast<const uint32_t*>(clean.data()), unit_base, rec[kRefStart], &at, rec[kRefHist], rec[kRefNz], sd.Ss, sd.Se,
                                      &rec[kRefSign], &rec[kRefCbits]);
                     }
                 }

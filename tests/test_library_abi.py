@@ -53,12 +53,14 @@ def test_header_validation_precedes_any_device_call(rgb_small):
     assert try_open(b"XCR1" + rec[4:]) == pkg.E_FORMAT
     assert try_open(rec[:20]) == pkg.E_TRUNCATED
     assert try_open(rec[:200]) == pkg.E_TRUNCATED                  # header itself cut short
-    bad_version = rec[:4] + (2).to_bytes(4, "little") + rec[8:]
+    bad_version = rec[:4] + (3).to_bytes(4, "little") + rec[8:]
     assert try_open(bad_version) == pkg.E_UNSUPPORTED
     zero_images = rec[:8] + (0).to_bytes(4, "little") + rec[12:]
     assert try_open(zero_images) == pkg.E_FORMAT
     hb = int.from_bytes(rec[16:24], "little")
     assert try_open(rec[:hb]) == pkg.E_TRUNCATED                   # metadata only: no scan group available
+    as_version_2 = rec[:4] + (2).to_bytes(4, "little") + rec[8:]   # a version-1 header is too short to be a version-2 one
+    assert try_open(as_version_2) == pkg.E_FORMAT
     assert not h.value
 
 
