@@ -494,6 +494,7 @@ def main():
     ap.add_argument("--workload", default="imagenet_like", choices=sorted(WORKLOAD_SCAN_GROUPS))
     ap.add_argument("--images", type=int, default=None, help="use only the first N images of the workload")
     ap.add_argument("--scan-group", type=int, default=None, help="the scan group `value` is quoted at (default: the highest)")
+    ap.add_argument("--entry-interval", type=int, default=128, help="MCUs between the entry points the record writer stores (record version 2)")
     ap.add_argument("--extras", action="store_true", help="also: fidelity upgrades, training tail, similarity scores, baseline files, restart intervals")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-default-queues", action="store_true", help="skip the child process that measures the step with HIP's default number of hardware queues")
@@ -532,6 +533,17 @@ def main():
     symbols0 = pcrgen.workload_symbol_counts(name, limit=min(n0, len(files)))          # record 0's images
     print("[bench] %s: %d images (mean %.1f kB) in %d records, generated in %.1f s" % (name, len(files), ends[:, -1].mean() / 1000, len(records), time.time() - t0),
           file=sys.stderr, flush=True)
+
+    # The records the library's own writer makes of these files: the same image bytes, plus entry points about every
+    # 128 MCUs of every scan (record version 2), which the decoder uses as it uses restart intervals.  `value` is
+    # measured on them; the plain records (no entry points: one serial stream per scan) are timed further down.
+    plain_records = records
+    per_record = pcrgen.WORKLOADS[name]["per_record"]
+    labels = (np.arange(len(files)) * 7919) % 1000
+    t0 = time.time()
+    records = [pkg.record_write_indexed(files[a:a + per_record], labels[a:a + per_record], args.entry_interval) for a in range(0, len(files), per_record)]
+    index_s = time.time() - t0
+    entry_bytes = sum(len(r) for r in records) - sum(len(r) for r in plain_records)
 
     job = Job(torch, pkg, records, on_device=(name == "ham_like"))
     n_img = job.n_img
@@ -632,7 +644,9 @@ def main():
         "config": {"workload": "%s: %d images, mean %.0f kB, %d records, sampling %s, %d scans" % (name, n_img, ends[:, -1].mean() / 1000, len(records),
                                                                                                   "x".join("%d%d" % s for s in sampling), len(script)),
                    "scan_group": headline_k, "images": n_img, "records": len(records),
-                   "records_opened": "from device memory (index and markers parsed on the device)" if name == "ham_like" else "from host bytes"},
+                   "records_opened": "from device memory (index and markers parsed on the device)" if name == "ham_like" else "from host bytes",
+                   "record_version": 2, "entry_interval_mcus": args.entry_interval, "entry_point_bytes_share": entry_bytes / float(sum(len(r) for r in records)),
+                   "record_writer_s": index_s},
         "ms_per_step_median_of_single_steps": float(np.median(singles)) * 1e3, "ms_per_step_min_of_single_steps": float(np.min(singles)) * 1e3,
         "output_GBps": ab["out"] / sec / 1e9,
         "open_ms_per_record": job.open_ms,
@@ -658,6 +672,16 @@ def main():
     job.close()
     del job
     torch.cuda.synchronize()
+    # the same files in plain records (version 1, what the input generator writes: no entry points)
+    pjob = Job(torch, pkg, plain_records)
+    plain = {}
+    for k in sorted(set(TABLE_SCAN_GROUPS) & set(scan_groups)):
+        psec, psingles, _, palone, pcalls = pjob.timed(k, max(3, args.steps // 2), 2, single_steps=5)
+        plain[str(k)] = {"images_per_s": n_img / psec, "ms_per_step": psec * 1e3,
+                         "ms_one_record_alone": sum(ms for ms, _ in palone.values()) / pcalls}
+    pjob.close()
+    del pjob
+    line["plain_records_without_entry_points"] = plain
     if not args.no_default_queues and len(records) > 1:
         line["with_default_hardware_queues"] = measure_default_queues(records, headline_k, args.steps, args.warmup)
     print(json.dumps(line))

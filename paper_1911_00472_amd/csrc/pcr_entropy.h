@@ -890,13 +890,14 @@ PCR_HD int decode_sequential(WindowReader* wr, const LaneScan& ls, const SeqTabl
 PCR_HD uint64_t band_mask(int Ss, int Se) { return ((Se >= 63) ? ~0ull : ((1ull << (Se + 1)) - 1)) & ~((1ull << Ss) - 1); }
 
 // What an AC refinement scan leaves per block: one record of kRefWords 64-bit words (zig-zag bit order),
-//   [kRefNz]    positions that become non-zero in this scan (later scans need them as history)   } written by
-//   [kRefStart] bit offset of the block inside its unit | end-of-band run pending at its start << 32  } phase 1,
-//   [kRefHist]  positions of the band already non-zero when the scan starts                      } adjacent
-//   [kRefSign]  signs of the kRefNz positions, 1 = positive         } written by phase 2
-//   [kRefCbits] the correction bits in reading order, bit 0 first   }
-// Records of consecutive blocks are contiguous, so everything a consumer needs for a block is one line.
-constexpr int kRefNz = 0, kRefStart = 1, kRefHist = 2, kRefSign = 3, kRefCbits = 4, kRefWords = 5;
+//   [kRefNz]    positions that become non-zero in this scan (later scans need them as history)   } written by phase 1
+//   [kRefSign]  signs of the kRefNz positions, 1 = positive                                       } written by
+//   [kRefPlus]  positions whose correction bit is 1 (their magnitude grows by 2^Al)              } phase 2
+//   [kRefStart] bit offset of the block inside its unit | end-of-band run pending at its start << 32  } written by
+//   [kRefHist]  positions of the band already non-zero when the scan starts                      } phase 1
+// Records of consecutive blocks are contiguous; what the consumers of a finished scan need (the replay of the
+// refinement on the coefficients) is the first three words.
+constexpr int kRefNz = 0, kRefSign = 1, kRefPlus = 2, kRefStart = 3, kRefHist = 4, kRefWords = 5;
 
 // History of a refinement scan: the positions of its band that are non-zero when it starts.  What the
 // AC first scans made non-zero is read back from the coefficient plane (one coefficient per lane, a ballot
@@ -1149,9 +1150,9 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
 //   words, byte_off  the unit's unstuffed data;  st  the block's kRefStart word;  h  history mask;
 //   newm  the positions phase 1 found to become non-zero (kRefNz): the j-th symbol that carries a
 //         coefficient lands on the j-th of them, so no zero run has to be counted here
-// Returns the sign mask (1 = positive) of the positions that become non-zero and the correction
-// bits in reading order (first bit read = bit 0): exactly one per history-non-zero position of
-// the band, in zig-zag order.
+// Returns the sign mask (1 = positive) of the positions that become non-zero and the mask of the positions whose
+// correction bit is 1.  The stream holds exactly one correction bit per history-non-zero position of the band, in
+// zig-zag order; the bits read between two symbols are dealt out to the history positions passed on the way.
 // The position in the stream is a plain bit offset; the 32 bits at it are fetched from two words.
 PCR_HD uint32_t stream_bits(const uint32_t* words, uint32_t bit) {          // the 32 bits that start at bit offset `bit`
     const uint32_t w = bit >> 5, sh = bit & 31;
@@ -1168,13 +1169,24 @@ PCR_HD uint64_t correction_bits(const uint32_t* words, uint32_t bit, uint32_t n)
     return out;
 }
 
+// bits (first bit read = bit 0) dealt out to the set bits of `where`, lowest position first
+PCR_HD uint64_t deal_bits(uint64_t bits, uint64_t where) {
+    uint64_t out = 0;
+    while (where) {
+        out |= (bits & 1) << __builtin_ctzll(where);
+        where &= where - 1; bits >>= 1;
+    }
+    return out;
+}
+
 PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, const AcTab* tab, uint64_t h, uint64_t newm, int Ss, int Se,
-                         uint64_t* sign_out, uint64_t* cbits_out) {
+                         uint64_t* sign_out, uint64_t* plus_out) {
     const uint64_t band = band_mask(Ss, Se);
     h &= band;
     uint32_t p = byte_off * 8 + (uint32_t)st;                // bit offset of the next unread bit
     const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
-    uint64_t sgn = 0, cb = 0;
+    uint64_t sgn = 0, plus = 0;
+    uint64_t todo = h;                                       // history positions whose correction bit has not been read yet
     uint32_t taken = 0;                                      // correction bits read so far
     uint32_t n = ncorr;                                      // inside an end-of-band run: all of them, nothing else
     if ((uint32_t)(st >> 32) == 0) {
@@ -1203,27 +1215,27 @@ PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, 
                 break;
             }
             const uint32_t upto = (uint32_t)__builtin_popcountll(h & ((2ull << pos) - 1));   // corrections at positions <= pos (pos itself is a zero)
-            if (upto > taken) { cb |= correction_bits(words, p, upto - taken) << taken; p += upto - taken; taken = upto; }
+            if (upto > taken) {
+                const uint64_t span = todo & ((2ull << pos) - 1);         // the history positions up to pos not yet served
+                plus |= deal_bits(correction_bits(words, p, upto - taken), span);
+                todo &= ~span; p += upto - taken; taken = upto;
+            }
             k = pos + 1;
         }
     }
-    if (n) cb |= correction_bits(words, p, n) << taken;
-    *sign_out = sgn; *cbits_out = cb;
+    if (n) plus |= deal_bits(correction_bits(words, p, n), todo);
+    *sign_out = sgn; *plus_out = plus;
 }
 
 // ---------------------------------------------------------------------------------------
 // Data-parallel part of AC refinement for one coefficient at zig-zag position k of a block.
-//   h       mask of positions non-zero before the scan (restricted to the band)
+//   newm, sgn, plus   the block's kRefNz, kRefSign and kRefPlus words of the scan
 // ---------------------------------------------------------------------------------------
-PCR_HD int16_t refine_apply(int16_t v, int k, uint64_t h, uint64_t newm, uint64_t sgn, uint64_t cb, int Al) {
+PCR_HD int16_t refine_apply(int16_t v, int k, uint64_t newm, uint64_t sgn, uint64_t plus, int Al) {
     uint64_t bit = 1ull << k;
     int p = 1 << Al;
-    if (h & bit) {
-        int j = __builtin_popcountll(h & (bit - 1));
-        if ((cb >> j) & 1) v = (int16_t)(v > 0 ? v + p : v - p);
-    } else if (newm & bit) {
-        v = (int16_t)((sgn & bit) ? p : -p);
-    }
+    if (plus & bit) v = (int16_t)(v > 0 ? v + p : v - p);
+    else if (newm & bit) v = (int16_t)((sgn & bit) ? p : -p);
     return v;
 }
 

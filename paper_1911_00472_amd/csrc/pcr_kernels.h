@@ -464,9 +464,9 @@ __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const Refine
     const uint64_t h = rec[kRefHist];                        // the history phase 1 worked on
     const uint32_t ivl = sd->ri ? b / sd->ri : 0;
     const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + clean_base(sd->data_off));
-    uint64_t sgn, cb;
-    refine_block(words, R.ivl_start[R.slot_base[ig] + ivl], rec[kRefStart], &tab, h, rec[kRefNz], sd->Ss, sd->Se, &sgn, &cb);
-    rec[kRefSign] = sgn; rec[kRefCbits] = cb;
+    uint64_t sgn, plus;
+    refine_block(words, R.ivl_start[R.slot_base[ig] + ivl], rec[kRefStart], &tab, h, rec[kRefNz], sd->Ss, sd->Se, &sgn, &plus);
+    rec[kRefSign] = sgn; rec[kRefPlus] = plus;
 }
 
 // --------------------------------------------------------------------------------------
@@ -562,7 +562,7 @@ __global__ void __launch_bounds__(256) k_apply(DevRecord R, const ApplyUnit* __r
                 if (dc_refinement_bit(R, S, row, col, hs, vs, covered)) v |= (int16_t)(1 << S.Al);
             } else if (k != 0 && covered && k >= S.Ss && k <= S.Se) {
                 const uint64_t* rec = R.masks + S.mask_off + (size_t)b * kRefWords;
-                v = refine_apply(v, k, rec[kRefHist], rec[kRefNz], rec[kRefSign], rec[kRefCbits], S.Al);
+                v = refine_apply(v, k, rec[kRefNz], rec[kRefSign], rec[kRefPlus], S.Al);
             }
         }
         if (v != v0) pl[idx] = v;
@@ -640,273 +640,362 @@ __global__ void __launch_bounds__(256) k_crop_resize(const uint32_t* __restrict_
 }
 
 // --------------------------------------------------------------------------------------
-// k_pixel: one workgroup per strip of MCUs (128 pixels wide at most) of one MCU row of one image.
-//   phase 1  coefficients -> LDS: every lane loads 16 contiguous bytes (8 coefficients in
-//            zig-zag order), de-quantises and scatters them to their natural positions; chunks
-//            that no scan <= k can have touched are not read at all; a component that only
-//            has its DC gets one lane per block, which writes the flat block's value
-//   phase 2  row IDCT, one lane per (block, row)
-//   phase 3  column IDCT + level shift + clamp, one lane per (block, column)
-//   phase 4  chroma replication + colour + store: one lane per group of 12 bytes of an output row
-//            (4 RGB pixels), written as one 12-byte store that need not be aligned
-// The measured limit of this kernel is vector-ALU issue, so the index arithmetic is kept off
-// the lanes: components are handled one after the other (their geometry is wave-uniform),
-// divisions by strip widths use a reciprocal computed once, and the zig-zag scatter offsets
-// and quantiser steps come from two small LDS tables.
+// k_pixel: one workgroup per run of consecutive MCUs of one image (raster order over its MCU grid, across the
+// ends of MCU rows), ONE LANE PER 8x8 BLOCK.
+//   phase A  the lane loads its block's 64 coefficients (eight 16-byte loads; chunks that no scan <= k can have
+//            touched are not read), replays the component's refinement scans on them, de-quantises, and runs the
+//            whole 8x8 inverse DCT in registers: zig-zag order becomes register naming, the row and the column
+//            pass need no exchange between lanes, no LDS and no barrier.  The constant factors of the transform
+//            (1/2 per pass, cos(pi/4) on terms 0 and 4) are folded into the de-quantisation table.  The clamped
+//            samples go to LDS, MCU by MCU: per MCU the blocks of each component as one small row-major plane.
+//            A component that only has its DC writes one sample per block (the block is flat).
+//   phase B  chroma replication + colour + one rounding + store: one lane per group of 12 output bytes (4 RGB
+//            pixels; 8 gray ones) of one pixel row of one MCU, lanes ordered along the image rows, the samples
+//            read from LDS as 16- and 8-byte vectors, the group written with one (possibly unaligned) store.
+// The kernel is bound by memory latency times occupancy, not by arithmetic, so the chain of dependent trips to
+// memory is kept short: the image's descriptor is read with scalar loads (no copy through LDS, no barrier), and
+// the coefficient loads are issued before the tables of the prologue are built.  kFlat (every component of every
+// image has only its DC: scan groups without any AC scan) needs one sample per block instead of 64 and runs
+// with four times the occupancy.
+// The refinement is applied here, on the way in: the coefficient planes hold what the first scans wrote, and the
+// lane replays the component's refinement scans from the records the refinement kernels left (exactly what k_apply
+// does for the coefficient export, the only caller that needs the refined values in memory).  lists / list_idx:
+// the per-(image, component) scan lists of k_apply_prep and their index by image * 3 + component (-1: nothing to
+// refine); both null if no scan <= k refines.  kRefine = false compiles the replay out.
+// boxes (optional): one box per image; runs of MCUs that do not touch their image's box are skipped altogether
+// (their pixels are left as they are): for callers that go on to read only the boxes (pcr_decode_crop_batch).
 // --------------------------------------------------------------------------------------
-constexpr int kStripPx = 128;              // strip width in pixels
-constexpr int kMaxStripBlocks = 96;        // worst sampling: 16 MCUs x 6 blocks or 8 MCUs x 12 blocks (4:2:0: 48)
-constexpr int kStripMcus = 8;              // MCUs per strip when the MCU is 16 pixels wide (tiles are built for this)
+constexpr int kPixLanes = 128;             // blocks per workgroup (the samples of a run take kPixLanes * 256 bytes of LDS)
 
-struct PixelTile { uint32_t img; uint16_t mcu_row; uint16_t mcu_col0; };
+struct PixelTile { uint32_t img; uint32_t mcu0; };          // first MCU of the run
 typedef short short8 __attribute__((ext_vector_type(8)));
 
 // w / d as (w * recip16(d)) >> 16, exact while w * d < 65536
 PCR_HD uint32_t recip16(uint32_t d) { return d ? 65536u / d + 1u : 0u; }
 
-// Refinement is applied here, on the way in: the coefficient planes hold what the first scans wrote, and a
-// lane that loads eight coefficients replays the component's refinement scans on them from the mask planes
-// (exactly what k_apply does for the coefficient export, which is the only caller that still needs the
-// refined values in memory).  lists / list_idx: the per-(image, component) scan lists of k_apply_prep and
-// their index by image * 3 + component (-1: nothing to refine); both null if no scan <= k refines.
-// kRefine = false compiles the replay out (scan groups without refinement scans: fewer registers).
-// boxes (optional): one box per image; strips that do not touch their image's box are skipped altogether (their
-// pixels are left as they are): for callers that go on to read only the boxes (pcr_decode_crop_batch).
-template <bool kRefine>
-__global__ void __launch_bounds__(256) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out,
-                                               const ApplyList* __restrict__ lists, const int32_t* __restrict__ list_idx,
-                                               const CropBox* __restrict__ boxes) {
-    // samples of the strip, one row-major plane per component (so that neighbouring pixels are
-    // neighbouring words of LDS in phase 4); rows are one word longer than the data, which
-    // spreads the rows of a block over the banks for phase 2
-    __shared__ float tile[kMaxStripBlocks * 64 + 64];
-    __shared__ __attribute__((aligned(16))) float qz[kMaxComp][64];       // quantiser steps, zig-zag order
-    __shared__ __attribute__((aligned(16))) uint16_t zoff[kMaxComp][64];  // zig-zag index -> offset of that position from the block's corner in `tile`
-    __shared__ ImgDesc img;                                // this image's descriptor, read many times below
-    __shared__ ApplyList rl[kMaxComp];                     // refinement scan lists of the components (n = 0: none)
-    short_kernel_priority();
-    const PixelTile t = tiles[blockIdx.x];
-    {
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.img[t.img]);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(&img);
-        if (threadIdx.x < sizeof(ImgDesc) / 4) dst[threadIdx.x] = src[threadIdx.x];
-    }
-    __syncthreads();
-    const uint32_t nc = img.nc;
-    const uint32_t W = img.W, H = img.H;
-    uint8_t* o = out + R.out_off[t.img];
-    const uint32_t hmax = img.hmax, vmax = img.vmax;
-    const uint32_t mcu_px_w = 8 * hmax, mcu_px_h = 8 * vmax;
-    const uint32_t per = kStripPx / mcu_px_w;              // MCUs per strip: 8 (16-px MCUs) or 16 (8-px MCUs)
-    const uint32_t col0 = t.mcu_col0 * (per / kStripMcus);
-    if (col0 >= img.mcux) return;                          // tiles are laid out for 8 MCUs per strip; wider strips need fewer
-    const uint32_t nm = img.mcux - col0 < per ? img.mcux - col0 : per;
-    const uint32_t x0 = col0 * mcu_px_w, y0 = t.mcu_row * mcu_px_h;
-    const uint32_t sw = nm * mcu_px_w;                     // strip width in pixels
-    const uint32_t xe = x0 + sw < W ? x0 + sw : W;         // visible part of the strip
-    const uint32_t rows = y0 + mcu_px_h < H ? mcu_px_h : H - y0;
-    const uint32_t row_bytes = (xe - x0) * nc;
-    if (boxes) {                                            // (clamped into the image exactly as k_crop_resize clamps it)
-        CropBox b = boxes[t.img];
-        b.x0 = min(max(b.x0, 0), (int)W - 1); b.y0 = min(max(b.y0, 0), (int)H - 1);
-        b.w = min(max(b.w, 1), (int)W - b.x0); b.h = min(max(b.h, 1), (int)H - b.y0);
-        if ((int)x0 >= b.x0 + b.w || (int)xe <= b.x0 || (int)y0 >= b.y0 + b.h || (int)(y0 + rows) <= b.y0) return;
-    }
-    const bool dead = R.status[t.img] != kOk;
-    // per component (all wave-uniform): blocks per strip row, blocks in the strip, row stride and plane
-    // offset in `tile`, reciprocal of the blocks per row, first block of the strip in the coefficient buffer
-    uint32_t bwc[kMaxComp], nbc[kMaxComp], pstr[kMaxComp], poff[kMaxComp], rcp[kMaxComp], first_blk[kMaxComp], bwi[kMaxComp], zmx[kMaxComp];
+PCR_HD uint32_t blocks_per_mcu(const ImgDesc& d) {
+    uint32_t b = 0;
+    for (int c = 0; c < d.nc; c++) b += (uint32_t)d.hs[c] * d.vs[c];
+    return b;
+}
+PCR_HD uint32_t pixel_mcus_per_tile(const ImgDesc& d) { return (uint32_t)kPixLanes / blocks_per_mcu(d); }   // >= 10: an MCU has at most 12 blocks
+
+// 8-point inverse transform with the constant factors taken out: in[u] must already carry the 1/2 of the pass and,
+// for u = 0 and 4, cos(pi/4).  out[x] = sum_u in'[u] cos((2x+1) u pi / 16).
+PCR_D void idct8_scaled(float& x0, float& x1, float& x2, float& x3, float& x4, float& x5, float& x6, float& x7) {
+    const float c1 = 0.98078528040323044913f, c2 = 0.92387953251128675613f, c3 = 0.83146961230254523708f,
+                c5 = 0.55557023301960222474f, c6 = 0.38268343236508977173f, c7 = 0.19509032201612826785f;
+    const float a = x0 + x4, b = x0 - x4;
+    const float p = x2 * c2 + x6 * c6, q = x2 * c6 - x6 * c2;
+    const float e0 = a + p, e1 = b + q, e2 = b - q, e3 = a - p;
+    const float o0 = x1 * c1 + x3 * c3 + x5 * c5 + x7 * c7;
+    const float o1 = x1 * c3 - x3 * c7 - x5 * c1 - x7 * c5;
+    const float o2 = x1 * c5 - x3 * c1 + x5 * c7 + x7 * c3;
+    const float o3 = x1 * c7 - x3 * c5 + x5 * c3 - x7 * c1;
+    x0 = e0 + o0; x7 = e0 - o0; x1 = e1 + o1; x6 = e1 - o1;
+    x2 = e2 + o2; x5 = e2 - o2; x3 = e3 + o3; x4 = e3 - o3;
+}
+// the factor folded into the quantiser step of zig-zag position k: 1/2 per pass, cos(pi/4) for row or column 0 and 4
+PCR_D float idct_fold(uint32_t k) {
+    const uint32_t p = zigzag_lookup(k), u = p & 7, v = p >> 3;
+    const float c4 = 0.70710678118654752440f;
+    return 0.25f * ((u & 3) == 0 ? c4 : 1.0f) * ((v & 3) == 0 ? c4 : 1.0f);
+}
+
+// byte `which` of `word` := v rounded half up and clamped to [0, 255] (v is finite); the other bytes are kept.
+// (The conversion instruction saturates and is exact on integers, which floor(v + 1/2) is.)
+PCR_D uint32_t put_u8(float v, uint32_t which, uint32_t word) {
+    return __builtin_amdgcn_cvt_pk_u8_f32(__builtin_floorf(v + 0.5f), which, word);
+}
+
+// a value per component, picked by a per-lane component number out of three wave-uniform ones
+PCR_D uint32_t pick3(uint32_t c, uint32_t a0, uint32_t a1, uint32_t a2) { return c == 0 ? a0 : (c == 1 ? a1 : a2); }
+
+// What the pixel kernels need to know about an image, all wave-uniform (read through a wave-uniform pointer, so
+// with scalar loads): sampling, blocks per MCU, where a component's samples start inside an MCU's part of the
+// sample tile (rb) and their row length there (rs), first block of its plane in the image's coefficient buffer.
+struct PixGeom {
+    uint32_t nc, W, H, hmax, vmax, mcux, mcuy, bpm;
+    uint32_t hs[kMaxComp], vs[kMaxComp], nbl[kMaxComp], rb[kMaxComp], rs[kMaxComp], plane0[kMaxComp], bw[kMaxComp], zmx[kMaxComp], cw[kMaxComp], ch[kMaxComp];
     bool flat[kMaxComp];
-    {
-        uint32_t plane0 = 0, lds = 0;
+};
+PCR_D void pix_geom(const ImgDesc* ip, PixGeom* g) {
+    g->nc = ip->nc; g->W = ip->W; g->H = ip->H; g->hmax = ip->hmax; g->vmax = ip->vmax; g->mcux = ip->mcux; g->mcuy = ip->mcuy;
+    uint32_t bpm = 0, p0 = 0;
 #pragma unroll
-        for (uint32_t c = 0; c < kMaxComp; c++) {
-            const uint32_t hs = c < nc ? img.hs[c] : 0, vs = c < nc ? img.vs[c] : 0;
-            bwi[c] = c < nc ? img.bw[c] : 0;
-            bwc[c] = nm * hs; nbc[c] = bwc[c] * vs; pstr[c] = bwc[c] * 8 + 1; poff[c] = lds; lds += vs * 8 * pstr[c];
-            rcp[c] = recip16(bwc[c]);
-            first_blk[c] = plane0 + (t.mcu_row * vs) * bwi[c] + col0 * hs;
-            plane0 += c < nc ? bwi[c] * (uint32_t)img.bh[c] : 0;
-            zmx[c] = c < nc ? img.zmax[c] : 0;
-            flat[c] = c < nc && zmx[c] <= 1;
+    for (uint32_t c = 0; c < kMaxComp; c++) {
+        const bool on = c < g->nc;
+        g->hs[c] = on ? ip->hs[c] : 0; g->vs[c] = on ? ip->vs[c] : 0;
+        g->nbl[c] = g->hs[c] * g->vs[c]; g->rb[c] = bpm * 64; g->rs[c] = g->hs[c] * 8; bpm += g->nbl[c];
+        g->bw[c] = on ? ip->bw[c] : 0;
+        g->plane0[c] = p0; p0 += on ? g->bw[c] * (uint32_t)ip->bh[c] : 0;
+        g->zmx[c] = on ? ip->zmax[c] : 0; g->cw[c] = on ? ip->cw[c] : 0; g->ch[c] = on ? ip->ch[c] : 0;
+        g->flat[c] = on && g->zmx[c] <= 1;
+    }
+    g->bpm = bpm;
+}
+
+// The lane's block: component c, block (brow, bcol) of the component's plane.
+struct PixBlock { uint32_t c, hs, vs, brow, bcol, b, zm; const int16_t* coef; bool covered; };
+// j: number of the block inside its MCU (components one after the other, each vs rows of hs blocks); (my, mx): the MCU
+PCR_D void pix_block(const DevRecord& R, const PixGeom& G, uint32_t img, uint32_t j, uint32_t my, uint32_t mx, PixBlock* B, uint32_t* by_out, uint32_t* bx_out) {
+    const uint32_t c = j < G.nbl[0] ? 0u : (j < G.nbl[0] + G.nbl[1] ? 1u : 2u);
+    const uint32_t jj = j - pick3(c, 0u, G.nbl[0], G.nbl[0] + G.nbl[1]);
+    B->c = c; B->hs = pick3(c, G.hs[0], G.hs[1], G.hs[2]); B->vs = pick3(c, G.vs[0], G.vs[1], G.vs[2]);
+    const uint32_t bx = jj & (B->hs - 1), by = jj >> (B->hs - 1);                  // (sampling factors are 1 or 2)
+    B->brow = my * B->vs + by; B->bcol = mx * B->hs + bx;
+    B->b = B->brow * pick3(c, G.bw[0], G.bw[1], G.bw[2]) + B->bcol;
+    B->zm = pick3(c, G.zmx[0], G.zmx[1], G.zmx[2]);
+    B->coef = R.coef + R.coef_off[img] + ((size_t)pick3(c, G.plane0[0], G.plane0[1], G.plane0[2]) + B->b) * 64;
+    B->covered = B->brow < pick3(c, G.ch[0], G.ch[1], G.ch[2]) && B->bcol < pick3(c, G.cw[0], G.cw[1], G.cw[2]);
+    *by_out = by; *bx_out = bx;
+}
+// the block's coefficients as they lie in memory (zig-zag order), chunks beyond zm left zero
+PCR_D void pix_load(const PixBlock& B, short8 v[8]) {
+#pragma unroll
+    for (int ch = 0; ch < 8; ch++) {
+        v[ch] = short8{0, 0, 0, 0, 0, 0, 0, 0};
+        if ((uint32_t)ch * 8 < B.zm) v[ch] = *reinterpret_cast<const short8*>(B.coef + ch * 8);
+    }
+}
+// DC of the block after the component's DC refinement scans
+template <bool kRefine>
+PCR_D int pix_dc(const DevRecord& R, const PixBlock& B, int dcv, const ApplyList* rlc) {
+    const uint32_t nref = kRefine ? rlc->n : 0;
+    for (uint32_t e = 0; e < nref; e++)
+        if (rlc->sc[e].Ss == 0 && dc_refinement_bit(R, rlc->sc[e], B.brow, B.bcol, B.hs, B.vs, B.covered)) dcv |= 1 << rlc->sc[e].Al;
+    return dcv;
+}
+// Refinement replay, de-quantisation and the 8x8 inverse transform of the lane's block; the clamped samples go to
+// dst[y * row_len + x].  qc: the component's folded quantiser steps (zig-zag order); rlc: its refinement scan list.
+template <bool kRefine>
+PCR_D void pix_finish(const DevRecord& R, const PixBlock& B, const short8 v[8], const float* qc, const ApplyList* rlc, float* dst, uint32_t row_len) {
+    int ci[64];
+#pragma unroll
+    for (int ch = 0; ch < 8; ch++) {
+#pragma unroll
+        for (int q = 0; q < 8; q++) ci[ch * 8 + q] = v[ch][q];
+    }
+    const uint32_t nref = kRefine ? rlc->n : 0;
+    for (uint32_t e = 0; e < nref; e++) {
+        const ApplyScan& S = rlc->sc[e];
+        if (S.Ss == 0) {
+            if (dc_refinement_bit(R, S, B.brow, B.bcol, B.hs, B.vs, B.covered)) ci[0] |= 1 << S.Al;
+        } else if (B.covered) {
+            // the three words of the block's record: positions that become non-zero, their signs, positions
+            // whose magnitude grows (all inside the scan's band)
+            const uint64_t* rec = R.masks + S.mask_off + (size_t)B.b * kRefWords;
+            const uint64_t nzm = rec[kRefNz], sgm = rec[kRefSign], plm = rec[kRefPlus];
+            const int p1 = 1 << S.Al;
+#pragma unroll
+            for (int k = 1; k < 64; k++) {
+                const uint32_t nzw = k < 32 ? (uint32_t)nzm : (uint32_t)(nzm >> 32), sgw = k < 32 ? (uint32_t)sgm : (uint32_t)(sgm >> 32),
+                               plw = k < 32 ? (uint32_t)plm : (uint32_t)(plm >> 32);
+                const int bit = k & 31;
+                const int grow = ((int)(plw << (31 - bit))) >> 31;          // all ones where the magnitude grows
+                const int isnew = ((int)(nzw << (31 - bit))) >> 31, pos = ((int)(sgw << (31 - bit))) >> 31;
+                const int x = ci[k], s = x >> 31;
+                const int stepped = x + (((p1 ^ s) - s) & grow);          // + p1 with the sign of x
+                const int fresh = ((-p1) ^ pos) - pos;                    // + p1 if the sign bit is set, else - p1
+                ci[k] = (stepped & ~isnew) | (fresh & isnew);
+            }
         }
     }
-    for (uint32_t c = 0; kRefine && c < nc; c++) {
-        const int32_t li = list_idx ? list_idx[t.img * kMaxComp + c] : -1;
+    float F[64];                                             // natural order: F[8 v + u]
+#pragma unroll
+    for (int k4 = 0; k4 < 16; k4++) {
+        const float4 qq = *reinterpret_cast<const float4*>(qc + 4 * k4);
+        F[zigzag_lookup(4 * k4)] = (float)ci[4 * k4] * qq.x; F[zigzag_lookup(4 * k4 + 1)] = (float)ci[4 * k4 + 1] * qq.y;
+        F[zigzag_lookup(4 * k4 + 2)] = (float)ci[4 * k4 + 2] * qq.z; F[zigzag_lookup(4 * k4 + 3)] = (float)ci[4 * k4 + 3] * qq.w;
+    }
+#pragma unroll
+    for (int r = 0; r < 8; r++)
+        idct8_scaled(F[8 * r], F[8 * r + 1], F[8 * r + 2], F[8 * r + 3], F[8 * r + 4], F[8 * r + 5], F[8 * r + 6], F[8 * r + 7]);
+#pragma unroll
+    for (int x = 0; x < 8; x++)
+        idct8_scaled(F[x], F[8 + x], F[16 + x], F[24 + x], F[32 + x], F[40 + x], F[48 + x], F[56 + x]);
+#pragma unroll
+    for (int y = 0; y < 8; y++) {
+        float4 lo, hi;
+        lo.x = clamp255(F[8 * y] + 128.f); lo.y = clamp255(F[8 * y + 1] + 128.f); lo.z = clamp255(F[8 * y + 2] + 128.f); lo.w = clamp255(F[8 * y + 3] + 128.f);
+        hi.x = clamp255(F[8 * y + 4] + 128.f); hi.y = clamp255(F[8 * y + 5] + 128.f); hi.z = clamp255(F[8 * y + 6] + 128.f); hi.w = clamp255(F[8 * y + 7] + 128.f);
+        *reinterpret_cast<float4*>(dst + y * row_len) = lo;
+        *reinterpret_cast<float4*>(dst + y * row_len + 4) = hi;
+    }
+}
+// the component's folded quantiser steps into LDS; every lane of the workgroup calls it
+PCR_D void pix_quant_table(const DevRecord& R, const ImgDesc* ip, uint32_t nc, float (*qz)[68], uint32_t tid, uint32_t nthreads) {
+    for (uint32_t e = tid; e < nc * 64; e += nthreads) {
+        const uint32_t c = e >> 6, k = e & 63;
+        const uint32_t tq = ip->tq[c];
+        const uint8_t* q = R.rec + ip->qoff[tq];
+        qz[c][k] = (ip->qprec[tq] ? (float)ld_be16(q + 2 * k) : (float)q[k]) * idct_fold(k);
+    }
+}
+// the refinement scan lists of the image's components into LDS
+PCR_D void pix_lists(const ApplyList* __restrict__ lists, const int32_t* __restrict__ list_idx, uint32_t img, uint32_t nc, ApplyList* rl, uint32_t tid, uint32_t nthreads) {
+    for (uint32_t c = 0; c < nc; c++) {
+        const int32_t li = list_idx ? list_idx[img * kMaxComp + c] : -1;
         uint32_t* dst = reinterpret_cast<uint32_t*>(&rl[c]);
         if (li >= 0) {
             const uint32_t* src = reinterpret_cast<const uint32_t*>(&lists[li]);
-            for (uint32_t e = threadIdx.x; e < sizeof(ApplyList) / 4; e += 256) dst[e] = src[e];
-        } else if (threadIdx.x == 0) dst[0] = 0;           // n = 0
+            for (uint32_t e = tid; e < sizeof(ApplyList) / 4; e += nthreads) dst[e] = src[e];
+        } else if (tid == 0) dst[0] = 0;                    // n = 0
     }
-    for (uint32_t e = threadIdx.x; e < nc * 64; e += 256) {
-        const uint32_t c = e >> 6, k = e & 63;
-        const uint8_t* q = R.rec + img.qoff[img.tq[c]];
-        const uint32_t p = zigzag_lookup(k);
-        qz[c][k] = img.qprec[img.tq[c]] ? (float)ld_be16(q + 2 * k) : (float)q[k];
-        zoff[c][k] = (uint16_t)((p >> 3) * (c == 0 ? pstr[0] : (c == 1 ? pstr[1] : pstr[2])) + (p & 7));
+}
+
+// four consecutive samples of a component for the output pixels x0 .. x0+3 of a pixel row (x0 a multiple of 4):
+// row: the component's row of the MCU; sh: 1 if the component has half the horizontal resolution
+PCR_D void four_samples(const float* row, uint32_t x0, uint32_t sh, float v[4]) {
+    if (sh == 0) { const float4 t = *reinterpret_cast<const float4*>(row + x0); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
+    else { const float2 t = *reinterpret_cast<const float2*>(row + (x0 >> 1)); v[0] = v[1] = t.x; v[2] = v[3] = t.y; }
+}
+
+template <bool kRefine, bool kFlat>
+__global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out,
+                                                     const ApplyList* __restrict__ lists, const int32_t* __restrict__ list_idx,
+                                                     const CropBox* __restrict__ boxes) {
+    // samples of the run: 64 per block (kFlat: one per block, in the same order of blocks)
+    __shared__ __attribute__((aligned(16))) float tile[kFlat ? kPixLanes : kPixLanes * 64];
+    // quantiser steps in zig-zag order times the folded transform factors; the rows of the three components start
+    // four banks apart, so that lanes of different components read them without bank conflicts
+    __shared__ __attribute__((aligned(16))) float qz[kFlat ? 1 : kMaxComp][68];
+    __shared__ ApplyList rl[kRefine ? kMaxComp : 1];       // refinement scan lists of the components (n = 0: none)
+    __shared__ uint32_t org[kPixLanes];                    // per MCU of the run: its first pixel, counted in pixels from the image's first (< 2^32)
+    __shared__ uint16_t visw[kPixLanes], vish[kPixLanes];  // ... and how many of its pixel columns / rows lie inside the image
+    short_kernel_priority();
+    const uint32_t timg = uni(tiles[blockIdx.x].img), mcu0 = uni(tiles[blockIdx.x].mcu0);
+    const uint32_t tid = threadIdx.x;
+    const ImgDesc* ip = R.img + timg;
+    PixGeom G;
+    pix_geom(ip, &G);
+    const uint32_t nc = G.nc, W = G.W, H = G.H, mcux = G.mcux, bpm = G.bpm;
+    const uint32_t mcu_px_w = 8 * G.hmax, mcu_px_h = 8 * G.vmax;
+    if (bpm == 0 || bpm > 12) return;                       // (cannot happen for an image the parser accepted)
+    if (kFlat && !(G.flat[0] && (nc < 2 || (G.flat[1] && G.flat[2])))) return;   // (the host launches this variant only for such records)
+    const uint32_t per = (uint32_t)kPixLanes / bpm;
+    const uint32_t total = mcux * G.mcuy;
+    if (mcu0 >= total) return;
+    const uint32_t nm = total - mcu0 < per ? total - mcu0 : per;      // MCUs of this run
+    if (boxes) {                                            // (clamped into the image exactly as k_crop_resize clamps it)
+        CropBox b = boxes[timg];
+        b.x0 = min(max(b.x0, 0), (int)W - 1); b.y0 = min(max(b.y0, 0), (int)H - 1);
+        b.w = min(max(b.w, 1), (int)W - b.x0); b.h = min(max(b.h, 1), (int)H - b.y0);
+        const uint32_t r0 = mcu0 / mcux, r1 = (mcu0 + nm - 1) / mcux;          // MCU rows the run touches
+        if ((int)(r0 * mcu_px_h) >= b.y0 + b.h || (int)((r1 + 1) * mcu_px_h) <= b.y0) return;
+        if (r0 == r1) {
+            const uint32_t c0 = mcu0 - r0 * mcux;
+            if ((int)(c0 * mcu_px_w) >= b.x0 + b.w || (int)((c0 + nm) * mcu_px_w) <= b.x0) return;
+        }
+    }
+    const bool dead = uni((uint32_t)(R.status[timg] != kOk)) != 0;
+    // ---- phase A, first half: the lane's block and its loads ----
+    const uint32_t m = (tid * recip16(bpm)) >> 16, j = tid - m * bpm;
+    const bool mine = !dead && m < nm;
+    PixBlock B;
+    uint32_t by = 0, bx = 0;
+    short8 v[8];
+    float q0 = 0.f;
+    if (mine) {
+        const uint32_t M = mcu0 + m, my = M / mcux, mx = M - my * mcux;
+        pix_block(R, G, timg, j, my, mx, &B, &by, &bx);
+        if (kFlat || B.zm <= 1) {
+            v[0] = short8{0, 0, 0, 0, 0, 0, 0, 0};
+            v[0][0] = B.coef[0];
+            if (kFlat) {                                    // (no table: the one step a flat block needs)
+                const uint32_t tq = pick3(B.c, ip->tq[0], ip->tq[1], ip->tq[2]);
+                const uint8_t* q = R.rec + pick3(tq, ip->qoff[0], ip->qoff[1], tq == 2 ? ip->qoff[2] : ip->qoff[3]);
+                q0 = (pick3(tq, ip->qprec[0], ip->qprec[1], tq == 2 ? ip->qprec[2] : ip->qprec[3]) ? (float)ld_be16(q) : (float)q[0]) * 0.125f;
+            }
+        } else pix_load(B, v);
+    }
+    // ---- prologue tables (the loads above are under way meanwhile) ----
+    if (kRefine) pix_lists(lists, list_idx, timg, nc, rl, tid, kPixLanes);
+    if (!kFlat) pix_quant_table(R, ip, nc, qz, tid, kPixLanes);
+    if (tid < nm) {
+        const uint32_t M = mcu0 + tid, my = M / mcux, mx = M - my * mcux;
+        org[tid] = my * mcu_px_h * W + mx * mcu_px_w;
+        const uint32_t x = mx * mcu_px_w, y = my * mcu_px_h;
+        visw[tid] = (uint16_t)(x >= W ? 0 : (W - x < mcu_px_w ? W - x : mcu_px_w));
+        vish[tid] = (uint16_t)(y >= H ? 0 : (H - y < mcu_px_h ? H - y : mcu_px_h));
+    }
+    if (kRefine || !kFlat) __syncthreads();
+    // ---- phase A, second half ----
+    if (mine) {
+        const ApplyList* rlc = &rl[kRefine ? B.c : 0];
+        if (kFlat) {
+            tile[tid] = clamp255((float)pix_dc<kRefine>(R, B, v[0][0], rlc) * q0 + 128.f);
+        } else {
+            const uint32_t row_len = B.hs * 8;
+            float* dst = tile + m * bpm * 64 + pick3(B.c, G.rb[0], G.rb[1], G.rb[2]) + by * 8 * row_len + bx * 8;
+            if (B.zm <= 1) dst[0] = clamp255((float)pix_dc<kRefine>(R, B, v[0][0], rlc) * qz[B.c][0] + 128.f);   // flat: one sample stands for the block
+            else pix_finish<kRefine>(R, B, v, qz[B.c], rlc, dst, row_len);
+        }
     }
     __syncthreads();
-    if (!dead) {
-        const int16_t* coef = R.coef + R.coef_off[t.img];
-        // phase 1: chunk = 8 consecutive coefficients (zig-zag order) of a block.  Component c starts
-        // at wave c, so that the small chroma planes of a 4:2:0 strip do not all land on wave 0.
-#pragma unroll
-        for (uint32_t c = 0; c < kMaxComp; c++) {
-            if (c >= nc) continue;
-            const uint32_t tt = (threadIdx.x - 64 * c) & 255;
-            const int16_t* pl = coef + (size_t)first_blk[c] * 64;
-            float* plane = tile + poff[c];
-            const uint32_t nref = kRefine ? rl[c].n : 0;   // scans to replay (0: the planes are final)
-            const uint32_t hsc = img.hs[c], vsc = img.vs[c], cwc = img.cw[c], chc = img.ch[c];
-            const uint32_t nplane = bwi[c] * (uint32_t)img.bh[c];
-            if (flat[c]) {                                 // only the DC: the block is flat
-                const float q0 = qz[c][0];
-                for (uint32_t lb = tt; lb < nbc[c]; lb += 256) {
-                    const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
-                    int dcv = pl[((size_t)lrow * bwi[c] + lcol) * 64];
-                    if (kRefine && nref != 0) {
-                        const uint32_t brow = t.mcu_row * vsc + lrow, bcol = col0 * hsc + lcol;
-                        for (uint32_t e = 0; e < nref; e++)
-                            if (rl[c].sc[e].Ss == 0 && dc_refinement_bit(R, rl[c].sc[e], brow, bcol, hsc, vsc, brow < chc && bcol < cwc)) dcv |= 1 << rl[c].sc[e].Al;
-                    }
-                    plane[lrow * 8 * pstr[c] + lcol * 8] = clamp255((float)dcv * q0 * 0.125f + 128.f);
-                }
-                continue;
-            }
-            for (uint32_t w = tt; w < nbc[c] * 8; w += 256) {
-                const uint32_t lb = w >> 3, ch = w & 7;
-                const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
-                short8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (ch * 8 < zmx[c]) {
-                    v = *reinterpret_cast<const short8*>(pl + ((size_t)lrow * bwi[c] + lcol) * 64 + ch * 8);
-                    if (kRefine && nref != 0) {
-                        const uint32_t brow = t.mcu_row * vsc + lrow, bcol = col0 * hsc + lcol;
-                        const bool covered = brow < chc && bcol < cwc;
-                        const uint32_t b = brow * bwi[c] + bcol;       // block index in the component's plane
-                        const uint32_t k0 = ch * 8;
-                        for (uint32_t e = 0; e < nref; e++) {
-                            const ApplyScan& S = rl[c].sc[e];
-                            if (S.Ss == 0) {
-                                if (k0 == 0 && dc_refinement_bit(R, S, brow, bcol, hsc, vsc, covered)) v[0] |= (short)(1 << S.Al);
-                            } else if (covered && k0 <= S.Se && k0 + 7 >= S.Ss) {
-                                // the eight positions k0..k0+7 as 8-bit fields of the scan's masks (all restricted to
-                                // its band); the correction bit of position k0 + j is number (non-zero history
-                                // positions below it) of the scan's string
-                                const uint64_t* rec = R.masks + S.mask_off + (size_t)b * kRefWords;   // the block's record
-                                const uint64_t hb = rec[kRefHist];
-                                const uint32_t h8 = (uint32_t)(hb >> k0) & 0xFF, n8 = (uint32_t)(rec[kRefNz] >> k0) & 0xFF;
-                                const uint32_t s8 = (uint32_t)(rec[kRefSign] >> k0) & 0xFF;
-                                const uint32_t below = (uint32_t)__builtin_popcountll(hb & ((1ull << k0) - 1));
-                                const uint32_t c8 = (uint32_t)(rec[kRefCbits] >> below) & 0xFF;
-                                const int p1 = 1 << S.Al;
-#pragma unroll
-                                for (int j = 0; j < 8; j++) {
-                                    const uint32_t bj = 1u << j;
-                                    const int vj = v[j];
-                                    if (h8 & bj) {
-                                        if ((c8 >> __builtin_popcount(h8 & (bj - 1))) & 1) v[j] = (short)(vj > 0 ? vj + p1 : vj - p1);
-                                    } else if (n8 & bj) v[j] = (short)((s8 & bj) ? p1 : -p1);
-                                }
-                            }
-                        }
-                    }
-                }
-                float* blk = plane + lrow * 8 * pstr[c] + lcol * 8;               // sample (0,0) of the block
-                const float4 qa = *reinterpret_cast<const float4*>(&qz[c][ch * 8]), qb = *reinterpret_cast<const float4*>(&qz[c][ch * 8 + 4]);
-                const uint4 zo = *reinterpret_cast<const uint4*>(&zoff[c][ch * 8]);
-                blk[zo.x & 0xFFFF] = (float)v[0] * qa.x; blk[zo.x >> 16] = (float)v[1] * qa.y;
-                blk[zo.y & 0xFFFF] = (float)v[2] * qa.z; blk[zo.y >> 16] = (float)v[3] * qa.w;
-                blk[zo.z & 0xFFFF] = (float)v[4] * qb.x; blk[zo.z >> 16] = (float)v[5] * qb.y;
-                blk[zo.w & 0xFFFF] = (float)v[6] * qb.z; blk[zo.w >> 16] = (float)v[7] * qb.w;
-            }
-        }
-        __syncthreads();
-        // phase 2: rows
-#pragma unroll
-        for (uint32_t c = 0; c < kMaxComp; c++) {
-            if (c >= nc || flat[c]) continue;
-            const uint32_t tt = (threadIdx.x - 64 * c) & 255;
-            for (uint32_t w = tt; w < nbc[c] * 8; w += 256) {
-                const uint32_t lb = w >> 3, v = w & 7;
-                const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
-                float* rowp = tile + poff[c] + (lrow * 8 + v) * pstr[c] + lcol * 8;
-                float in[8], res[8];
-#pragma unroll
-                for (int u = 0; u < 8; u++) in[u] = rowp[u];
-                idct8(in, res);
-#pragma unroll
-                for (int x = 0; x < 8; x++) rowp[x] = res[x];
-            }
-        }
-        __syncthreads();
-        // phase 3: columns
-#pragma unroll
-        for (uint32_t c = 0; c < kMaxComp; c++) {
-            if (c >= nc || flat[c]) continue;
-            const uint32_t tt = (threadIdx.x - 64 * c) & 255;
-            for (uint32_t w = tt; w < nbc[c] * 8; w += 256) {
-                const uint32_t lb = w >> 3, x = w & 7;
-                const uint32_t lrow = (lb * rcp[c]) >> 16, lcol = lb - lrow * bwc[c];
-                float* colp = tile + poff[c] + (lrow * 8) * pstr[c] + lcol * 8 + x;
-                float in[8], res[8];
-#pragma unroll
-                for (int v = 0; v < 8; v++) in[v] = colp[v * pstr[c]];
-                idct8(in, res);
-#pragma unroll
-                for (int y = 0; y < 8; y++) colp[y * pstr[c]] = clamp255(res[y] + 128.f);
-            }
-        }
-        __syncthreads();
-    }
-    // phase 4: one lane per group of 12 bytes of an output row of the strip (4 RGB pixels or 12 gray ones),
-    // stored as three dwords.  Rows start wherever width x 3 puts them, so the stores are in general not
-    // 4-byte aligned: global memory takes unaligned dword accesses (a store that straddles a line is split
-    // by the memory pipeline), which is far cheaper than shifting every group into alignment.
-    if (row_bytes == 0) return;
-    const uint32_t shx0 = img.hs[0] == hmax ? 0 : 1, shy0 = img.vs[0] == vmax ? 0 : 1;     // sampling factors are 1 or 2
-    const uint32_t shx1 = nc > 1 && img.hs[1] != hmax, shy1 = nc > 1 && img.vs[1] != vmax;
-    const uint32_t shx2 = nc > 2 && img.hs[2] != hmax, shy2 = nc > 2 && img.vs[2] != vmax;
-    const uint32_t m0 = flat[0] ? ~7u : ~0u, m1 = flat[1] ? ~7u : ~0u, m2 = flat[2] ? ~7u : ~0u;   // flat: read the block's corner
-    const uint32_t groups = (row_bytes + 11) / 12;         // per row; only the last one can be partial
-    const uint32_t rcpg = recip16(groups);
-    for (uint32_t it = threadIdx.x; it < rows * groups; it += 256) {
-        const uint32_t ly = (it * rcpg) >> 16, g = it - ly * groups;
-        const uint32_t r0 = g * 12;                        // byte offset of the group in the row
-        uint8_t* wp = o + ((size_t)(y0 + ly) * W + x0) * nc + r0;
-        uint32_t wd[3] = {0, 0, 0};
+    // ---- phase B: one lane per group of output bytes of one pixel row of one MCU ----
+    const uint32_t shx0 = G.hs[0] == G.hmax ? 0 : 1, shy0 = G.vs[0] == G.vmax ? 0 : 1;       // sampling factors are 1 or 2
+    const uint32_t shx1 = nc > 1 && G.hs[1] != G.hmax, shy1 = nc > 1 && G.vs[1] != G.vmax;
+    const uint32_t shx2 = nc > 2 && G.hs[2] != G.hmax, shy2 = nc > 2 && G.vs[2] != G.vmax;
+    const uint32_t ppg = nc == 1 ? 8u : 4u;                 // pixels per group: 8 gray bytes, or 12 bytes of RGB
+    const uint32_t gpm = mcu_px_w / ppg;                    // groups per pixel row of an MCU: 1, 2 or 4
+    const uint32_t lg = gpm == 4 ? 2u : (gpm == 2 ? 1u : 0u);
+    const uint32_t items = nm * mcu_px_h * gpm;
+    const uint32_t rcpn = nm > 1 ? 0xFFFFFFFFu / nm + 1u : 0u;       // q / nm as the high word of q * rcpn: exact while q * nm < 2^32
+    // component c's four samples for pixels x0.. of row ly of MCU mm: a flat component has one per block
+    auto fetch = [&](uint32_t c, uint32_t mm, uint32_t ly, uint32_t x0, uint32_t shx, uint32_t shy, float s[4]) {
+        if (kFlat || G.flat[c]) {
+            const uint32_t brow_in = (ly >> shy) >> 3, bcol_in = (x0 >> shx) >> 3;
+            const float f = kFlat ? tile[mm * bpm + (G.rb[c] >> 6) + brow_in * G.hs[c] + bcol_in]
+                                  : tile[mm * bpm * 64 + G.rb[c] + brow_in * 8 * G.rs[c] + bcol_in * 8];
+            s[0] = s[1] = s[2] = s[3] = f;
+        } else four_samples(tile + mm * bpm * 64 + G.rb[c] + (ly >> shy) * G.rs[c], x0, shx, s);
+    };
+    for (uint32_t it = tid; it < items; it += kPixLanes) {
+        // lanes run along the image rows: group, then MCU, then pixel row
+        const uint32_t g = it & (gpm - 1), q = it >> lg;
+        const uint32_t ly = nm > 1 ? __umulhi(q, rcpn) : q, mm = q - ly * nm;
+        const uint32_t x0 = g * ppg, vw = visw[mm];
+        if (ly >= vish[mm] || x0 >= vw) continue;
+        uint8_t* wp = out + R.out_off[timg] + ((size_t)org[mm] + (size_t)ly * W + x0) * nc;
+        const uint32_t left = vw - x0;                      // pixels of the group inside the image
         if (nc == 1) {
-            const float* yrow = tile + poff[0] + ((ly >> shy0) & m0) * pstr[0];
-#pragma unroll
-            for (int j = 0; j < 12; j++) {
-                const uint32_t r = r0 + j;
-                const float s = (r < row_bytes && !dead) ? yrow[(r >> shx0) & m0] : 0.f;
-                wd[j >> 2] |= (uint32_t)round_u8(s) << (8 * (j & 3));
+            float a[4], bq[4];
+            fetch(0, mm, ly, x0, 0, 0, a); fetch(0, mm, ly, x0 + 4, 0, 0, bq);
+            uint32_t w0 = 0, w1 = 0;
+            if (!dead) {
+                w0 = put_u8(a[0], 0, w0); w0 = put_u8(a[1], 1, w0); w0 = put_u8(a[2], 2, w0); w0 = put_u8(a[3], 3, w0);
+                w1 = put_u8(bq[0], 0, w1); w1 = put_u8(bq[1], 1, w1); w1 = put_u8(bq[2], 2, w1); w1 = put_u8(bq[3], 3, w1);
+            }
+            if (left >= 8) {
+                struct __attribute__((packed, aligned(1))) Eight { uint32_t a, b; };
+                Eight e8; e8.a = w0; e8.b = w1;
+                *reinterpret_cast<Eight*>(wp) = e8;
+            } else {
+                for (uint32_t i = 0; i < left; i++) wp[i] = (uint8_t)((i < 4 ? w0 : w1) >> (8 * (i & 3)));
             }
         } else {
-            const uint32_t p0 = g * 4;                     // first of the group's four pixels
-            const float* yrow = tile + poff[0] + ((ly >> shy0) & m0) * pstr[0];
-            const float* brow = tile + poff[1] + ((ly >> shy1) & m1) * pstr[1];
-            const float* rrow = tile + poff[2] + ((ly >> shy2) & m2) * pstr[2];
-            uint32_t three[4];                             // R | G << 8 | B << 16 of the four pixels
+            float ys[4], cb[4], cr[4];
+            uint32_t w0 = 0, w1 = 0, w2 = 0;
+            if (!dead) {
+                fetch(0, mm, ly, x0, shx0, shy0, ys); fetch(1, mm, ly, x0, shx1, shy1, cb); fetch(2, mm, ly, x0, shx2, shy2, cr);
+                float r[4], gg[4], bb[4];
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
-                const uint32_t lx = p0 + q;
-                uint8_t px[3] = {0, 0, 0};
-                if (lx * 3 < row_bytes && !dead)
-                    ycc_to_rgb(yrow[(lx >> shx0) & m0], brow[(lx >> shx1) & m1], rrow[(lx >> shx2) & m2], px);
-                three[q] = (uint32_t)px[0] | ((uint32_t)px[1] << 8) | ((uint32_t)px[2] << 16);
+                for (int i = 0; i < 4; i++) {
+                    const float u = cb[i] - 128.f, w = cr[i] - 128.f;
+                    r[i] = ys[i] + 1.402f * w; gg[i] = ys[i] - 0.344136f * u - 0.714136f * w; bb[i] = ys[i] + 1.772f * u;
+                }
+                w0 = put_u8(r[0], 0, w0); w0 = put_u8(gg[0], 1, w0); w0 = put_u8(bb[0], 2, w0); w0 = put_u8(r[1], 3, w0);
+                w1 = put_u8(gg[1], 0, w1); w1 = put_u8(bb[1], 1, w1); w1 = put_u8(r[2], 2, w1); w1 = put_u8(gg[2], 3, w1);
+                w2 = put_u8(bb[2], 0, w2); w2 = put_u8(r[3], 1, w2); w2 = put_u8(gg[3], 2, w2); w2 = put_u8(bb[3], 3, w2);
             }
-            wd[0] = three[0] | (three[1] << 24); wd[1] = (three[1] >> 8) | (three[2] << 16); wd[2] = (three[2] >> 16) | (three[3] << 8);
-        }
-        if (r0 + 12 <= row_bytes) {
-            struct __attribute__((packed, aligned(1))) Twelve { uint32_t a, b, c; };
-            Twelve tw; tw.a = wd[0]; tw.b = wd[1]; tw.c = wd[2];
-            *reinterpret_cast<Twelve*>(wp) = tw;           // one (possibly unaligned) 12-byte store
-        } else {
-#pragma unroll
-            for (int j = 0; j < 12; j++)
-                if (r0 + j < row_bytes) wp[j] = (uint8_t)(wd[j >> 2] >> (8 * (j & 3)));
+            if (left >= 4) {
+                struct __attribute__((packed, aligned(1))) Twelve { uint32_t a, b, c; };
+                Twelve tw; tw.a = w0; tw.b = w1; tw.c = w2;
+                *reinterpret_cast<Twelve*>(wp) = tw;           // one (possibly unaligned) 12-byte store
+            } else {
+                for (uint32_t i = 0; i < left * 3; i++) wp[i] = (uint8_t)((i < 4 ? w0 : (i < 8 ? w1 : w2)) >> (8 * (i & 3)));
+            }
         }
     }
 }

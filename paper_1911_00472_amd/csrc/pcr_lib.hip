@@ -414,8 +414,8 @@ static int finish_open(pcr_record* r, hipStream_t s) {
             r->slot_base[ig] = (uint32_t)ns; r->slot_cnt[ig] = cnt;
             ns += cnt + 1;
         }
-        for (uint32_t my = 0; my < d.mcuy; my++)
-            for (uint32_t mx = 0; mx < d.mcux; mx += kStripMcus) tiles.push_back(PixelTile{i, (uint16_t)my, (uint16_t)mx});
+        const uint32_t per = pixel_mcus_per_tile(d), mcus = (uint32_t)d.mcux * d.mcuy;       // runs of MCUs, one lane per block
+        for (uint32_t m0 = 0; m0 < mcus; m0 += per) tiles.push_back(PixelTile{i, m0});
     }
     if (ns >= (1ull << 32)) return PCR_E_UNSUPPORTED;
     r->n_masks = nm; r->n_slots = (uint32_t)ns; r->n_tiles = (uint32_t)tiles.size();
@@ -753,9 +753,11 @@ static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t c
     int rc = run_entropy_stages(r, k0, k, s, false, &plan);
     if (rc) return rc;
     if (plan->n_apply)
-        hipLaunchKernelGGL(k_pixel<true>, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
-    else
-        hipLaunchKernelGGL(k_pixel<false>, dim3(r->n_tiles), dim3(256), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
+        hipLaunchKernelGGL((k_pixel<true, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
+    else if (plan->has_ac)
+        hipLaunchKernelGGL((k_pixel<false, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
+    else                                                     // DC scans only: every block is flat
+        hipLaunchKernelGGL((k_pixel<false, true>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
     mark(r, PCR_STAGE_PIXEL, s);
     call_end(r);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;

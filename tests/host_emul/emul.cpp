@@ -137,7 +137,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                         size_t blk = (size_t)(mm / sd.mcu_w) * img.bw[c0] + (mm % sd.mcu_w);
                         uint64_t* rec = masks[g].data() + blk * kRefWords;
                         refine_block(reinterpret_cast<const uint32_t*>(clean.data()), unit_base, rec[kRefStart], &at, rec[kRefHist], rec[kRefNz], sd.Ss, sd.Se,
-                                     &rec[kRefSign], &rec[kRefCbits]);
+                                     &rec[kRefSign], &rec[kRefPlus]);
                     }
                 }
             }
@@ -168,7 +168,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 } else if (kk != 0 && covered && sd.comp[0] == c && sd.Ah != 0 && kk >= sd.Ss && kk <= sd.Se) {
                     const uint64_t* mk = masks[g].data();
                     const uint64_t* rec = mk + blk * kRefWords;
-                    v = refine_apply(v, kk, rec[kRefHist], rec[kRefNz], rec[kRefSign], rec[kRefCbits], sd.Al);
+                    v = refine_apply(v, kk, rec[kRefNz], rec[kRefSign], rec[kRefPlus], sd.Al);
                 }
             }
             *cp = v;
