@@ -222,12 +222,21 @@ int pcr_msssim_batch_static(pcr_record* rec, const uint8_t* d_a, const uint8_t* 
 int pcr_select_scan_group(pcr_record* rec, float min_mean_score, uint8_t* d_work_a, uint8_t* d_work_b, size_t work_capacity,
                           float* d_scores, float* mean_by_group, int* scan_group, void* hip_stream);
 
-/* Decode and training tail in one call: pcr_decode_batch at scan_group followed by pcr_crop_resize_batch with the
- * same boxes, except that the pixel kernel skips every strip of an image that does not touch the image's box --
- * the tail reads nothing else.  d_pixels (device, layout of pcr_output_layout, pixel_capacity bytes) is working
- * memory: afterwards it holds the decoded pixels of the strips that touch the boxes and whatever it held before
- * elsewhere.  The half-precision output is bit-identical to the two calls made one after the other.  The planes
- * left on the device are complete (pcr_upgrade_batch may follow).  Other arguments and errors as in the two calls. */
+/* Decode and training tail in one call; the half-precision output is bit-identical to pcr_decode_batch at scan_group
+ * followed by pcr_crop_resize_batch with the same boxes.
+ *   d_pixels == NULL   decode and tail run in ONE kernel and the full-resolution pixels never reach memory: one
+ *                      workgroup decodes one MCU row of an image into on-chip memory and interpolates from it every output
+ *                      sample whose two source rows lie in that MCU row; only the first and last pixel row of every MCU
+ *                      row (1/8 of the pixels for 4:2:0 images) go to a side buffer of the handle, from which a second,
+ *                      small kernel interpolates the remaining output rows.  MCUs that do not touch an image's box are
+ *                      not decoded.  Every image must be at most 256 / (blocks per MCU) MCUs wide (672 pixels for
+ *                      4:2:0 and 4:4:4, 1024 for 4:2:2, 2048 for gray), else PCR_E_UNSUPPORTED (give a working buffer).
+ *                      The first such call on a record allocates the side buffer.
+ *   d_pixels != NULL   (device, layout of pcr_output_layout, pixel_capacity bytes) working memory: the pixel kernel
+ *                      writes the runs of MCUs that touch an image's box there (what it held elsewhere stays), and
+ *                      pcr_crop_resize_batch reads them.
+ * The planes left on the device are complete (pcr_upgrade_batch may follow).  Other arguments and errors as in the two
+ * calls. */
 int pcr_decode_crop_batch(pcr_record* rec, int scan_group, const pcr_crop* d_crops, uint8_t* d_pixels, size_t pixel_capacity,
                           int out_h, int out_w, const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity,
                           void* hip_stream, int32_t* d_status);

@@ -283,19 +283,19 @@ class Record:
         return int(k.value), {g + 1: float(means[g]) for g in range(self.G) if means[g] >= 0}
 
     def decode_crop_batch(self, k, crops, out_h, out_w, mean, inv_std, pixels=None, out=None, status=None, stream=None):
-        """decode_batch(k) + crop_resize_batch in one call; the pixel kernel skips strips outside the boxes.
-        pixels: uint8 CUDA working buffer of output_layout()[n] bytes.  Returns the float16 tensor."""
+        """decode_batch(k) + crop_resize_batch in one call.  pixels=None: one fused kernel, the full-resolution pixels
+        never reach memory; otherwise a uint8 CUDA working buffer of output_layout()[n] bytes that receives the parts of
+        the pictures the boxes touch.  Returns the float16 tensor."""
         import torch
         assert crops.is_cuda and crops.dtype == torch.int32 and crops.is_contiguous() and tuple(crops.shape) == (self.n, 5)
         C = self.image_info(0)[2]
-        if pixels is None:
-            pixels = torch.empty(int(self.output_layout()[-1]), dtype=torch.uint8, device="cuda:%d" % self.device)
         if out is None:
             out = torch.empty((self.n, C, out_h, out_w), dtype=torch.float16, device="cuda:%d" % self.device)
         m = (ctypes.c_float * 3)(*([float(v) for v in mean] + [0.0] * 3)[:3])
         sd = (ctypes.c_float * 3)(*([float(v) for v in inv_std] + [1.0] * 3)[:3])
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
-        _check(lib().pcr_decode_crop_batch(self._h, k, crops.data_ptr(), pixels.data_ptr(), pixels.numel(), out_h, out_w, m, sd,
+        _check(lib().pcr_decode_crop_batch(self._h, k, crops.data_ptr(), pixels.data_ptr() if pixels is not None else None,
+                                           pixels.numel() if pixels is not None else 0, out_h, out_w, m, sd,
                                            out.data_ptr(), out.numel() * 2, s, status.data_ptr() if status is not None else None),
                "pcr_decode_crop_batch")
         return out
@@ -484,7 +484,8 @@ class Loader:
         """decode_crop_batch on the slot's handle and stream: pixels is the uint8 working buffer, out the float16 result."""
         m = (ctypes.c_float * 3)(*([float(v) for v in mean] + [0.0] * 3)[:3])
         sd = (ctypes.c_float * 3)(*([float(v) for v in inv_std] + [1.0] * 3)[:3])
-        _check(lib().pcr_loader_decode_crop(self._h, slot, k, crops.data_ptr(), pixels.data_ptr(), pixels.numel(), out_h, out_w, m, sd,
+        _check(lib().pcr_loader_decode_crop(self._h, slot, k, crops.data_ptr(), pixels.data_ptr() if pixels is not None else None,
+                                            pixels.numel() if pixels is not None else 0, out_h, out_w, m, sd,
                                             out.data_ptr(), out.numel() * 2, status.data_ptr() if status is not None else None),
                "pcr_loader_decode_crop")
         return out

@@ -411,10 +411,11 @@ struct LaneScan {
 // ---------------------------------------------------------------------------------------
 struct CoefSink {
     int16_t* plane;
+    int16_t* dense;                                           // optional second copy, one value per block: dense[element index / 64]
     uint32_t limit;                                           // elements of `plane`
     int Al;                                                   // values are stored shifted left by this
     uint32_t vidx; int vval;                                  // device: this lane's pending pair
-    PCR_HD void init(int16_t* p, uint32_t elems, int al) { plane = p; limit = elems; Al = al; vidx = 0; vval = 0; }
+    PCR_HD void init(int16_t* p, uint32_t elems, int al, int16_t* per_block = nullptr) { plane = p; dense = per_block; limit = elems; Al = al; vidx = 0; vval = 0; }
     // slot: window offset the symbol starts at (0..63); word: packed symbol word
     PCR_HD void emit(uint32_t slot, uint32_t elem, int word) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -424,12 +425,16 @@ struct CoefSink {
                      : "+v"(vidx), "+v"(vval) : "s"(elem), "s"(word), "s"(slot) : "m0");
 #else
         (void)slot;
-        if (((uint32_t)word & kSymCoef) && elem < limit) plane[elem] = (int16_t)((word >> 16) * (1 << Al));
+        if (((uint32_t)word & kSymCoef) && elem < limit) { plane[elem] = (int16_t)((word >> 16) * (1 << Al)); if (dense) dense[elem >> 6] = plane[elem]; }
 #endif
     }
     PCR_HD void flush() {
 #if defined(__HIP_DEVICE_COMPILE__)
-        if (((uint32_t)vval & kSymCoef) && vidx < limit) plane[vidx] = (int16_t)((vval >> 16) * (1 << Al));
+        if (((uint32_t)vval & kSymCoef) && vidx < limit) {
+            const int16_t val = (int16_t)((vval >> 16) * (1 << Al));
+            plane[vidx] = val;
+            if (dense) dense[vidx >> 6] = val;
+        }
         vval = 0;
 #endif
     }

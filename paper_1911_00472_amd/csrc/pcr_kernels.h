@@ -45,6 +45,8 @@ struct DevRecord {
     const uint32_t* slot_cnt;  // [n][G] intervals of the scan
     uint32_t* ivl_start;       // per scan: intervals+1 offsets into the clean segment
     int16_t* coef;
+    int16_t* dc;               // the DC coefficients once more, one per block in the order of the blocks of `coef` (written by the DC first
+                               // scans of progressive files): what a decode of DC scans alone reads instead of every 64th element
     uint64_t* masks;
     int32_t* status;           // [n]
     AcTab* tabs;               // Huffman tables of the AC scans: those of the refinement scans are written by phase 1 for phase 2;
@@ -302,7 +304,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     DcWindowReader wr;                                      // tables by scan component
     wr.init(L.words, L.byte_off, L.sub_bits, L.nbits, &tabs[0], &tabs[uni(tj1)], &tabs[uni(tj2)], L.ls.ns, threadIdx.x);
     CoefSink sink;
-    sink.init(L.base, L.base_elems, L.ls.Al);
+    sink.init(L.base, L.base_elems, L.ls.Al, R.dc + (uni((uint64_t)R.coef_off[un.img]) >> 6));
     int rc = kEFormat;                                      // (a unit in the wrong launch: the descriptors disagree with the host's)
     if (dc_shape(L.ls.ns, L.ls.hs[0], L.ls.vs[0], L.ls.hs[1], L.ls.vs[1], L.ls.hs[2], L.ls.vs[2]) == SHAPE) rc = decode_dc_first_as<SHAPE>(&wr, L.ls, &sink);
     if (rc != kOk) R.status[un.img] = rc;
@@ -602,6 +604,43 @@ PCR_D void floor_div(int num, int den, float inv_den, int* q, int* r) {
     *q = g; *r = rem;
 }
 
+// Where output sample (oy, ox) of a resize looks: the two source rows and columns (absolute, the box's edge samples
+// repeated) and the weights of the second row / column, as exact fractions of 2 * out size.
+struct TailTaps { int ya, yb, xa, xb; float fy, fx; };
+PCR_D void tail_rows(const CropBox& b, int oy, int out_h, int* ya, int* yb, float* fy) {
+    const int dy = 2 * out_h;
+    const float inv_dy = 1.0f / (float)dy;
+    int yl, ry;
+    floor_div((2 * oy + 1) * b.h - out_h, dy, inv_dy, &yl, &ry);
+    *fy = (float)ry * inv_dy;
+    *ya = b.y0 + min(max(yl, 0), b.h - 1); *yb = b.y0 + min(max(yl + 1, 0), b.h - 1);
+}
+PCR_D void tail_cols(const CropBox& b, int ox, int out_w, int* xa, int* xb, float* fx) {
+    const int oxs = b.flip ? out_w - 1 - ox : ox;
+    const int dx = 2 * out_w;
+    const float inv_dx = 1.0f / (float)dx;
+    int xl, rx;
+    floor_div((2 * oxs + 1) * b.w - out_w, dx, inv_dx, &xl, &rx);
+    *fx = (float)rx * inv_dx;
+    *xa = b.x0 + min(max(xl, 0), b.w - 1); *xb = b.x0 + min(max(xl + 1, 0), b.w - 1);
+}
+// A box as the tail uses it: clamped into its W x H image.
+PCR_D CropBox clamp_box(CropBox b, int W, int H) {
+    b.x0 = min(max(b.x0, 0), W - 1); b.y0 = min(max(b.y0, 0), H - 1);
+    b.w = min(max(b.w, 1), W - b.x0); b.h = min(max(b.h, 1), H - b.y0);
+    return b;
+}
+// One channel of one output sample from its four source values (whole numbers 0..255), normalised, as half precision.
+// The operations are spelled out one by one (no contraction left to the compiler), so that every kernel that
+// interpolates gives the very same bits.
+PCR_D __half tail_value(float aa, float ab, float ba, float bb, float fx, float fy, float mean, float istd) {
+    const float gx = __fsub_rn(1.0f, fx), gy = __fsub_rn(1.0f, fy);
+    const float top = __fmaf_rn(fx, ab, __fmul_rn(gx, aa));
+    const float bot = __fmaf_rn(fx, bb, __fmul_rn(gx, ba));
+    const float v = __fmaf_rn(fy, bot, __fmul_rn(gy, top));
+    return __float2half_rn(__fmul_rn(__fsub_rn(__fmul_rn(v, 1.0f / 255.0f), mean), istd));
+}
+
 __global__ void __launch_bounds__(256) k_crop_resize(const uint32_t* __restrict__ dims, const uint64_t* __restrict__ out_off,
         const uint8_t* __restrict__ in, const CropBox* __restrict__ boxes,
         int out_h, int out_w, int C, float m0, float m1, float m2, float s0, float s1, float s2, __half* __restrict__ out) {
@@ -610,19 +649,11 @@ __global__ void __launch_bounds__(256) k_crop_resize(const uint32_t* __restrict_
     if (ox >= out_w || oy >= out_h) return;
     const int W = (int)dims[2 * i], H = (int)dims[2 * i + 1];
     if (W < 1 || H < 1) return;
-    CropBox b = boxes[i];
-    b.x0 = min(max(b.x0, 0), W - 1); b.y0 = min(max(b.y0, 0), H - 1);
-    b.w = min(max(b.w, 1), W - b.x0); b.h = min(max(b.h, 1), H - b.y0);
-    const int oxs = b.flip ? out_w - 1 - ox : ox;
+    const CropBox b = clamp_box(boxes[i], W, H);
     // source point relative to the box, as an exact fraction: ((2 o + 1) * size - out) / (2 * out) pixels
-    const int dy = 2 * out_h, dx = 2 * out_w;
-    const float inv_dy = 1.0f / (float)dy, inv_dx = 1.0f / (float)dx;
-    int yl, ry, xl, rx;
-    floor_div((2 * oy + 1) * b.h - out_h, dy, inv_dy, &yl, &ry);
-    floor_div((2 * oxs + 1) * b.w - out_w, dx, inv_dx, &xl, &rx);
-    const float fy = (float)ry * inv_dy, fx = (float)rx * inv_dx;
-    const int ya = b.y0 + min(max(yl, 0), b.h - 1), yb = b.y0 + min(max(yl + 1, 0), b.h - 1);
-    const int xa = b.x0 + min(max(xl, 0), b.w - 1), xb = b.x0 + min(max(xl + 1, 0), b.w - 1);
+    int ya, yb, xa, xb; float fy, fx;
+    tail_rows(b, oy, out_h, &ya, &yb, &fy);
+    tail_cols(b, ox, out_w, &xa, &xb, &fx);
     const uint8_t* img = in + out_off[i];
     const uint8_t* paa = img + ((size_t)ya * W + xa) * C; const uint8_t* pab = img + ((size_t)ya * W + xb) * C;
     const uint8_t* pba = img + ((size_t)yb * W + xa) * C; const uint8_t* pbb = img + ((size_t)yb * W + xb) * C;
@@ -630,12 +661,7 @@ __global__ void __launch_bounds__(256) k_crop_resize(const uint32_t* __restrict_
     __half* dst = out + ((size_t)i * C * out_h + oy) * out_w + ox;
 #pragma unroll
     for (int c = 0; c < 3; c++) {
-        if (c < C) {
-            const float top = (1.0f - fx) * (float)paa[c] + fx * (float)pab[c];
-            const float bot = (1.0f - fx) * (float)pba[c] + fx * (float)pbb[c];
-            const float v = (1.0f - fy) * top + fy * bot;
-            dst[(size_t)c * out_h * out_w] = __float2half_rn((v * (1.0f / 255.0f) - mean[c]) * istd[c]);
-        }
+        if (c < C) dst[(size_t)c * out_h * out_w] = tail_value((float)paa[c], (float)pab[c], (float)pba[c], (float)pbb[c], fx, fy, mean[c], istd[c]);
     }
 }
 
@@ -699,7 +725,8 @@ PCR_D void idct8_scaled(float& x0, float& x1, float& x2, float& x3, float& x4, f
 PCR_D float idct_fold(uint32_t k) {
     const uint32_t p = zigzag_lookup(k), u = p & 7, v = p >> 3;
     const float c4 = 0.70710678118654752440f;
-    return 0.25f * ((u & 3) == 0 ? c4 : 1.0f) * ((v & 3) == 0 ? c4 : 1.0f);
+    const bool a = (u & 3) == 0, b = (v & 3) == 0;
+    return a && b ? 0.125f : (a || b ? 0.25f * c4 : 0.25f);            // (cos(pi/4) squared is exactly 1/2: a block with only its DC is exactly DC x step / 8)
 }
 
 // byte `which` of `word` := v rounded half up and clamped to [0, 255] (v is finite); the other bytes are kept.
@@ -901,7 +928,7 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
         pix_block(R, G, timg, j, my, mx, &B, &by, &bx);
         if (kFlat || B.zm <= 1) {
             v[0] = short8{0, 0, 0, 0, 0, 0, 0, 0};
-            v[0][0] = B.coef[0];
+            v[0][0] = kFlat ? R.dc[(R.coef_off[timg] >> 6) + pick3(B.c, G.plane0[0], G.plane0[1], G.plane0[2]) + B.b] : B.coef[0];
             if (kFlat) {                                    // (no table: the one step a flat block needs)
                 const uint32_t tq = pick3(B.c, ip->tq[0], ip->tq[1], ip->tq[2]);
                 const uint8_t* q = R.rec + pick3(tq, ip->qoff[0], ip->qoff[1], tq == 2 ? ip->qoff[2] : ip->qoff[3]);
@@ -997,6 +1024,152 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
                 for (uint32_t i = 0; i < left * 3; i++) wp[i] = (uint8_t)((i < 4 ? w0 : (i < 8 ? w1 : w2)) >> (8 * (i & 3)));
             }
         }
+    }
+}
+
+// --------------------------------------------------------------------------------------
+// k_pixel_tail: decode and training tail in one kernel, so that the full-resolution pixels never reach memory.
+// One workgroup per MCU row of one image (all its MCUs: the image must be at most kTailLanes / blocks-per-MCU MCUs
+// wide), one lane per block as in k_pixel; the samples of the MCU row lie in LDS as one row-major plane per component.
+// Phase B is replaced by the tail: the output samples whose two source rows both lie in this MCU row are interpolated
+// from pixels computed on the fly from the samples (colour conversion and rounding exactly as k_pixel does them, since
+// the tail is defined on the rounded pixels).  Output rows whose two source rows lie in two MCU rows cannot be served
+// by either workgroup: every workgroup leaves its first and last pixel row (1/8 of the pixels for 16-row MCUs) in a
+// side buffer, and k_tail_edges interpolates those rows from it afterwards.
+//   edge: side buffer; image i's part starts at edge_off[i] and holds, per MCU row r, its first pixel row at
+//         (2 r) * W * C and its last one at (2 r + 1) * W * C.
+// MCU rows (and MCUs) that do not touch the image's box are not decoded at all.
+// --------------------------------------------------------------------------------------
+constexpr int kTailLanes = 256;
+struct TailParams { int out_h, out_w; float mean[3], istd[3]; };
+
+// the rounded pixel (x, y) of the MCU row, y counted from the MCU row's first pixel row: up to three whole numbers
+struct TailView {
+    const float* plane[kMaxComp]; uint32_t len[kMaxComp], shx[kMaxComp], shy[kMaxComp], fm[kMaxComp]; uint32_t nc; bool dead;
+};
+PCR_D void tail_pixel(const TailView& V, uint32_t x, uint32_t y, float px[3]) {
+    if (V.dead) { px[0] = px[1] = px[2] = 0.f; return; }
+    const float s0 = V.plane[0][((y >> V.shy[0]) & V.fm[0]) * V.len[0] + ((x >> V.shx[0]) & V.fm[0])];
+    if (V.nc == 1) { px[0] = fminf(fmaxf(__builtin_floorf(s0 + 0.5f), 0.f), 255.f); px[1] = px[2] = 0.f; return; }
+    const float u = V.plane[1][((y >> V.shy[1]) & V.fm[1]) * V.len[1] + ((x >> V.shx[1]) & V.fm[1])] - 128.f;
+    const float w = V.plane[2][((y >> V.shy[2]) & V.fm[2]) * V.len[2] + ((x >> V.shx[2]) & V.fm[2])] - 128.f;
+    px[0] = fminf(fmaxf(__builtin_floorf(s0 + 1.402f * w + 0.5f), 0.f), 255.f);
+    px[1] = fminf(fmaxf(__builtin_floorf(s0 - 0.344136f * u - 0.714136f * w + 0.5f), 0.f), 255.f);
+    px[2] = fminf(fmaxf(__builtin_floorf(s0 + 1.772f * u + 0.5f), 0.f), 255.f);
+}
+
+template <bool kRefine>
+__global__ void __launch_bounds__(kTailLanes) k_pixel_tail(DevRecord R, const PixelTile* __restrict__ tiles, const ApplyList* __restrict__ lists,
+                                                           const int32_t* __restrict__ list_idx, const CropBox* __restrict__ boxes, TailParams P,
+                                                           __half* __restrict__ out, uint8_t* __restrict__ edge, const uint64_t* __restrict__ edge_off) {
+    __shared__ __attribute__((aligned(16))) float tile[kTailLanes * 64];
+    __shared__ __attribute__((aligned(16))) float qz[kMaxComp][68];
+    __shared__ ApplyList rl[kRefine ? kMaxComp : 1];
+    __shared__ uint32_t row_lo, row_hi;                    // output rows served here: [row_lo, row_hi)
+    short_kernel_priority();
+    const uint32_t timg = uni(tiles[blockIdx.x].img), mcu0 = uni(tiles[blockIdx.x].mcu0);
+    const uint32_t tid = threadIdx.x;
+    const ImgDesc* ip = R.img + timg;
+    PixGeom G;
+    pix_geom(ip, &G);
+    const uint32_t nc = G.nc, W = G.W, H = G.H, mcux = G.mcux, bpm = G.bpm;
+    const uint32_t mcu_px_w = 8 * G.hmax, mcu_px_h = 8 * G.vmax;
+    if (bpm == 0 || mcux * bpm > (uint32_t)kTailLanes) return;          // (the host refuses such records before launching)
+    const uint32_t my = mcu0 / mcux;
+    const uint32_t ylo = my * mcu_px_h, yhi = ylo + mcu_px_h < H ? ylo + mcu_px_h : H;   // pixel rows of this MCU row
+    const CropBox b = clamp_box(boxes[timg], (int)W, (int)H);
+    if ((int)ylo >= b.y0 + b.h || (int)yhi <= b.y0) return;
+    const uint32_t mc0 = (uint32_t)b.x0 / mcu_px_w, mc1 = (uint32_t)(b.x0 + b.w - 1) / mcu_px_w;   // MCUs the box touches
+    const bool dead = uni((uint32_t)(R.status[timg] != kOk)) != 0;
+    const uint32_t m = (tid * recip16(bpm)) >> 16, j = tid - m * bpm;
+    const bool mine = !dead && m >= mc0 && m <= mc1 && m < mcux;
+    PixBlock B;
+    uint32_t by = 0, bx = 0;
+    short8 v[8];
+    if (mine) {
+        pix_block(R, G, timg, j, my, m, &B, &by, &bx);
+        if (B.zm <= 1) { v[0] = short8{0, 0, 0, 0, 0, 0, 0, 0}; v[0][0] = B.coef[0]; }
+        else pix_load(B, v);
+    }
+    if (kRefine) pix_lists(lists, list_idx, timg, nc, rl, tid, kTailLanes);
+    pix_quant_table(R, ip, nc, qz, tid, kTailLanes);
+    if (tid == 0) { row_lo = 0xFFFFFFFFu; row_hi = 0; }
+    __syncthreads();
+    // output rows both of whose source rows lie in [ylo, yhi): they form one interval
+    for (int oy = (int)tid; oy < P.out_h; oy += kTailLanes) {
+        int ya, yb; float fy;
+        tail_rows(b, oy, P.out_h, &ya, &yb, &fy);
+        if (ya >= (int)ylo && yb < (int)yhi) { atomicMin(&row_lo, (uint32_t)oy); atomicMax(&row_hi, (uint32_t)oy + 1); }
+    }
+    if (mine) {
+        const ApplyList* rlc = &rl[kRefine ? B.c : 0];
+        const uint32_t row_len = mcux * B.hs * 8;
+        float* dst = tile + mcux * pick3(B.c, G.rb[0], G.rb[1], G.rb[2]) + by * 8 * row_len + (m * B.hs + bx) * 8;
+        if (B.zm <= 1) dst[0] = clamp255((float)pix_dc<kRefine>(R, B, v[0][0], rlc) * qz[B.c][0] + 128.f);
+        else pix_finish<kRefine>(R, B, v, qz[B.c], rlc, dst, row_len);
+    }
+    __syncthreads();
+    TailView V;
+    V.nc = nc; V.dead = dead;
+#pragma unroll
+    for (uint32_t c = 0; c < kMaxComp; c++) {
+        V.plane[c] = tile + mcux * G.rb[c]; V.len[c] = mcux * G.rs[c];
+        V.shx[c] = c < nc && G.hs[c] != G.hmax; V.shy[c] = c < nc && G.vs[c] != G.vmax;
+        V.fm[c] = G.flat[c] ? ~7u : ~0u;
+    }
+    // the first and the last pixel row, for the output rows that need a neighbouring MCU row as well
+    {
+        uint8_t* e = edge + edge_off[timg] + (size_t)(2 * my) * W * nc;
+        for (uint32_t it = tid; it < 2 * (uint32_t)b.w; it += kTailLanes) {
+            const uint32_t which = it >= (uint32_t)b.w, x = (uint32_t)b.x0 + (which ? it - (uint32_t)b.w : it);
+            float px[3];
+            tail_pixel(V, x, which ? yhi - 1 - ylo : 0u, px);
+            uint8_t* wp = e + ((size_t)which * W + x) * nc;
+            for (uint32_t c = 0; c < nc; c++) wp[c] = (uint8_t)px[c];
+        }
+    }
+    const uint32_t lo = row_lo, hi = row_hi;
+    if (lo >= hi) return;
+    const uint32_t ow = (uint32_t)P.out_w, items = (hi - lo) * ow;
+    const uint32_t rcpw = ow > 1 ? 0xFFFFFFFFu / ow + 1u : 0u;
+    for (uint32_t it = tid; it < items; it += kTailLanes) {
+        const uint32_t r = ow > 1 ? __umulhi(it, rcpw) : it, ox = it - r * ow, oy = lo + r;
+        int ya, yb, xa, xb; float fy, fx;
+        tail_rows(b, (int)oy, P.out_h, &ya, &yb, &fy);
+        tail_cols(b, (int)ox, P.out_w, &xa, &xb, &fx);
+        float aa[3], ab[3], ba[3], bb[3];
+        tail_pixel(V, (uint32_t)xa, (uint32_t)ya - ylo, aa); tail_pixel(V, (uint32_t)xb, (uint32_t)ya - ylo, ab);
+        tail_pixel(V, (uint32_t)xa, (uint32_t)yb - ylo, ba); tail_pixel(V, (uint32_t)xb, (uint32_t)yb - ylo, bb);
+        __half* dst = out + ((size_t)timg * nc * P.out_h + oy) * ow + ox;
+#pragma unroll
+        for (uint32_t c = 0; c < kMaxComp; c++)
+            if (c < nc) dst[(size_t)c * P.out_h * ow] = tail_value(aa[c], ab[c], ba[c], bb[c], fx, fy, P.mean[c], P.istd[c]);
+    }
+}
+
+// The output rows k_pixel_tail could not serve: their two source rows are the last pixel row of one MCU row and the first
+// of the next, both in the side buffer.  One workgroup per (output row, image); rows served already leave at once.
+__global__ void __launch_bounds__(64) k_tail_edges(const uint32_t* __restrict__ dims, const uint32_t* __restrict__ mcu_rows_px, int C,
+                                                   const CropBox* __restrict__ boxes, TailParams P, const uint8_t* __restrict__ edge,
+                                                   const uint64_t* __restrict__ edge_off, __half* __restrict__ out) {
+    const uint32_t i = blockIdx.y, oy = blockIdx.x;
+    const int W = (int)dims[2 * i], H = (int)dims[2 * i + 1];
+    const uint32_t mh = mcu_rows_px[i];                     // pixel rows per MCU row of this image (8 or 16)
+    const CropBox b = clamp_box(boxes[i], W, H);
+    int ya, yb; float fy;
+    tail_rows(b, (int)oy, P.out_h, &ya, &yb, &fy);
+    const uint32_t ra = (uint32_t)ya / mh, rb = (uint32_t)yb / mh;
+    if (ra == rb) return;                                   // both rows in one MCU row: done by k_pixel_tail
+    const uint8_t* e = edge + edge_off[i];
+    const uint8_t* rowa = e + (size_t)(2 * ra + 1) * W * C;  // ya is the last row of MCU row ra, yb the first of rb = ra + 1
+    const uint8_t* rowb = e + (size_t)(2 * rb) * W * C;
+    for (int ox = (int)threadIdx.x; ox < P.out_w; ox += 64) {
+        int xa, xb; float fx;
+        tail_cols(b, ox, P.out_w, &xa, &xb, &fx);
+        __half* dst = out + ((size_t)i * C * P.out_h + oy) * P.out_w + ox;
+        for (int c = 0; c < C; c++)
+            dst[(size_t)c * P.out_h * P.out_w] = tail_value((float)rowa[xa * C + c], (float)rowa[xb * C + c], (float)rowb[xa * C + c], (float)rowb[xb * C + c],
+                                                            fx, fy, P.mean[c], P.istd[c]);
     }
 }
 

@@ -113,6 +113,10 @@ struct pcr_record {
     PixelTile* d_tiles = nullptr; uint32_t n_tiles = 0;
     uint32_t* d_dims = nullptr;             // [n][2] width, height (for kernels that run without a decode before them)
     bool prebuild_tables = false;           // some AC scan has restart intervals: k_build_tables runs before the entropy kernels
+    // decode fused with the training tail (allocated at its first call): one tile per MCU row, the side buffer of first
+    // and last pixel rows, where each image's part of it starts, pixel rows per MCU row of every image
+    PixelTile* d_tail_tiles = nullptr; uint32_t n_tail_tiles = 0;
+    uint8_t* d_edge = nullptr; uint64_t* d_edge_off = nullptr; uint32_t* d_mcu_px_h = nullptr;
     float2* d_ssim_part = nullptr;          // per-tile sums of the similarity kernels (allocated at their first call)
     uint32_t ssim_tiles_max = 0;
     uint8_t* d_gather = nullptr; size_t gather_cap = 0;
@@ -424,7 +428,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     const size_t padded = nbytes + 1024;      // slack: bit readers look ahead
     // what the buffers below take, plus room for the work lists of a few scan groups (16 bytes per unit,
     // 12 per image and component, ...): anything beyond that is allocated on its own
-    size_t need = arena_round(padded) + arena_round(r->coef_off[n] * sizeof(int16_t)) + arena_round((nm + 2) * sizeof(uint64_t)) +
+    size_t need = arena_round(padded) + arena_round(r->coef_off[n] * sizeof(int16_t)) + arena_round((r->coef_off[n] / 64 + 1) * sizeof(int16_t)) + arena_round((nm + 2) * sizeof(uint64_t)) +
                   arena_round((ns + 1) * sizeof(uint32_t)) + 2 * arena_round((n + 1) * sizeof(uint64_t)) +
                   4 * arena_round(((size_t)n * G + 1) * sizeof(uint64_t)) + arena_round((tiles.size() + 1) * sizeof(PixelTile)) + arena_round((n + 1) * 8) +
                   arena_round(((size_t)ntabs + 1) * sizeof(AcTab)) + arena_round(((size_t)n * G + 1) * sizeof(uint32_t));
@@ -432,6 +436,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     int rc = arena_reset(&r->big, need);
     if (!rc) rc = arena_alloc(&r->big, &d.clean, padded);
     if (!rc) rc = arena_alloc(&r->big, &d.coef, r->coef_off[n]);
+    if (!rc) rc = arena_alloc(&r->big, &d.dc, r->coef_off[n] / 64 + 1);
     if (!rc) rc = arena_alloc(&r->big, &d.masks, nm + 2);
     if (!rc) rc = arena_alloc(&r->big, &d.ivl_start, ns);
     uint64_t *d_coef_off = nullptr, *d_out_off = nullptr, *d_mask_off = nullptr; uint32_t *d_sb = nullptr, *d_sc = nullptr;
@@ -525,6 +530,7 @@ static int bind_device(pcr_record* r, const void* d_bytes, size_t nbytes, hipStr
     r->plans.clear(); r->resident_k = 0; r->hdr = RecordHeader{}; r->n_tiles = 0;
     r->out_off.assign(1, 0); r->coef_off.assign(1, 0);        // until the bind succeeds the handle holds no record
     r->d_dims = nullptr; r->d_ssim_part = nullptr; r->ssim_tiles_max = 0;
+    r->d_tail_tiles = nullptr; r->n_tail_tiles = 0; r->d_edge = nullptr; r->d_edge_off = nullptr; r->d_mcu_px_h = nullptr;
     // fixed part of the header, then the whole metadata block
     uint8_t fixed[24];
     HIP_TRY(hipMemcpyAsync(fixed, d_bytes, 24, hipMemcpyDeviceToHost, s));
@@ -808,9 +814,71 @@ int pcr_crop_resize_batch(pcr_record* r, const uint8_t* d_pixels, const pcr_crop
     return PCR_OK;
 }
 
+// Tiles, side buffer and tables of the fused decode + tail (once per bound record).  PCR_E_UNSUPPORTED if an image is
+// too wide for one workgroup per MCU row.
+static int prepare_fused_tail(pcr_record* r) {
+    if (r->d_tail_tiles) return PCR_OK;
+    const uint32_t n = r->hdr.n;
+    std::vector<PixelTile> tiles; std::vector<uint64_t> eoff(n + 1, 0); std::vector<uint32_t> mh(n);
+    for (uint32_t i = 0; i < n; i++) {
+        const ImgDesc& d = r->img[i];
+        if ((uint32_t)d.mcux * blocks_per_mcu(d) > (uint32_t)kTailLanes) return PCR_E_UNSUPPORTED;
+        for (uint32_t my = 0; my < d.mcuy; my++) tiles.push_back(PixelTile{i, my * d.mcux});
+        eoff[i + 1] = eoff[i] + (uint64_t)2 * d.mcuy * d.W * d.nc;
+        mh[i] = 8u * d.vmax;
+    }
+    int rc = arena_upload(&r->big, &r->d_edge_off, eoff);
+    if (!rc) rc = arena_upload(&r->big, &r->d_mcu_px_h, mh);
+    if (!rc) rc = arena_alloc(&r->big, &r->d_edge, (size_t)eoff[n] + 16);
+    PixelTile* dt = nullptr;
+    if (!rc) rc = arena_upload(&r->big, &dt, tiles);
+    if (rc) return rc;
+    r->d_tail_tiles = dt; r->n_tail_tiles = (uint32_t)tiles.size();
+    return PCR_OK;
+}
+
 int pcr_decode_crop_batch(pcr_record* r, int k, const pcr_crop* d_crops, uint8_t* d_pixels, size_t pixel_capacity, int out_h, int out_w,
                           const float* mean, const float* inv_std, void* d_out_f16, size_t out_capacity, void* stream, int32_t* d_status) {
-    if (!r || !d_crops || !d_pixels || !mean || !inv_std) return PCR_E_ARG;
+    if (!r || !d_crops || !mean || !inv_std) return PCR_E_ARG;
+    if (!d_pixels) {
+        // No working buffer: decode and tail in one kernel, the full-resolution pixels stay on the chip.
+        int rc = check_scan_group(r, k);
+        if (rc) return rc;
+        if (out_h < 1 || out_w < 1 || out_h > 8192 || out_w > 8192) return PCR_E_RANGE;
+        if (!d_out_f16 || !r->d_dims) return PCR_E_ARG;
+        const uint32_t n = r->hdr.n;
+        const int C = r->img[0].nc;
+        for (uint32_t i = 1; i < n; i++) if (r->img[i].nc != C) return PCR_E_UNSUPPORTED;
+        if (n > 65535) return PCR_E_UNSUPPORTED;
+        if (out_capacity < (size_t)n * C * out_h * out_w * sizeof(__half)) return PCR_E_RANGE;
+        HIP_TRY(hipSetDevice(r->device));
+        rc = prepare_fused_tail(r);
+        if (rc) return rc;
+        hipStream_t s = (hipStream_t)stream;
+        Plan* plan = nullptr;
+        r->resident_k = 0;
+        rc = run_entropy_stages(r, 0, k, s, false, &plan);
+        if (rc) return rc;
+        TailParams P;
+        P.out_h = out_h; P.out_w = out_w;
+        for (int c = 0; c < 3; c++) { P.mean[c] = c < C ? mean[c] : 0.f; P.istd[c] = c < C ? inv_std[c] : 1.f; }
+        static_assert(sizeof(pcr_crop) == sizeof(CropBox), "crop box layout");
+        const CropBox* boxes = reinterpret_cast<const CropBox*>(d_crops);
+        if (plan->n_apply)
+            hipLaunchKernelGGL(k_pixel_tail<true>, dim3(r->n_tail_tiles), dim3(kTailLanes), 0, s, r->d, r->d_tail_tiles, plan->d_apply_lists, plan->d_list_idx,
+                               boxes, P, reinterpret_cast<__half*>(d_out_f16), r->d_edge, r->d_edge_off);
+        else
+            hipLaunchKernelGGL(k_pixel_tail<false>, dim3(r->n_tail_tiles), dim3(kTailLanes), 0, s, r->d, r->d_tail_tiles, (const ApplyList*)nullptr,
+                               (const int32_t*)nullptr, boxes, P, reinterpret_cast<__half*>(d_out_f16), r->d_edge, r->d_edge_off);
+        hipLaunchKernelGGL(k_tail_edges, dim3((uint32_t)out_h, n), dim3(64), 0, s, r->d_dims, r->d_mcu_px_h, C, boxes, P, r->d_edge, r->d_edge_off,
+                           reinterpret_cast<__half*>(d_out_f16));
+        mark(r, PCR_STAGE_PIXEL, s);
+        call_end(r);
+        if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
+        if (d_status) HIP_TRY(hipMemcpyAsync(d_status, r->d.status, n * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+        r->resident_k = k;
+        return PCR_OK;
+    }
     int rc = check_scan_group(r, k);
     if (rc) return rc;
     // argument checks of the tail before anything is enqueued (it repeats them)

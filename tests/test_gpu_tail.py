@@ -145,6 +145,55 @@ def test_fused_decode_and_tail_equals_the_two_calls():
                 assert torch.equal(r.upgrade_batch(10), r.decode_batch(10))
 
 
+def test_decode_and_tail_in_one_kernel_equals_the_two_calls(rgb_small, gray64):
+    """pcr_decode_crop_batch without a working buffer: one kernel decodes an MCU row into on-chip memory and interpolates
+    from it, a second one serves the output rows that need two MCU rows from the side buffer of first and last pixel
+    rows.  The half-precision output must be the two calls' output bit for bit: every scan group kind, down- and
+    up-scaling, boxes in every corner, flips, odd image sizes (1 x 1 included), gray, 4:4:4 and 4:2:0."""
+    torch = _torch()
+    big, _ = pcrgen.make_workload("imagenet_like", limit=40)
+    ham, _ = pcrgen.make_workload("ham_like", limit=6)
+    for rec, ks, mean, istd in ((big[0], (1, 2, 5, 7, 10), MEAN, ISTD), (rgb_small[0], (1, 4, 10), MEAN, ISTD), (ham[0], (3, 10), MEAN, ISTD),
+                                (gray64[0], (1, 3, 6), MEAN[:1], ISTD[:1])):
+        with pkg.pcr_open(rec, 0) as r:
+            shapes = [r.image_info(i)[:2] for i in range(r.n)]
+            for si, (oh, ow) in enumerate(((64, 48), (224, 224), (5, 301))):
+                boxes = _boxes(np.random.default_rng(31 + si), shapes)
+                tb = torch.from_numpy(boxes).cuda()
+                for k in ks:
+                    want = r.crop_resize_batch(r.decode_batch(k), tb, oh, ow, mean, istd)
+                    st = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
+                    got = torch.full_like(want, 9.0)
+                    r.decode_crop_batch(k, tb, oh, ow, mean, istd, pixels=None, out=got, status=st)
+                    torch.cuda.synchronize()
+                    assert (st.cpu().numpy() == 0).all()
+                    assert torch.equal(got, want), (r.n, oh, ow, k, int((got != want).sum()))
+                    assert r.resident_scan_group() == k
+            k0 = ks[0]
+            r.decode_crop_batch(k0, tb, 16, 16, mean, istd)
+            assert torch.equal(r.upgrade_batch(r.G), r.decode_batch(r.G))       # the planes under the fused call are complete
+    # end to end against the oracle, and a damaged image (zero pixels in, so a constant out)
+    rec = big[0]
+    ref = oracle.decode_record(rec, 10, images=[3, 21], threads=8, want_coef=False)
+    with pkg.pcr_open(rec, 0) as r:
+        shapes = [r.image_info(i)[:2] for i in range(r.n)]
+        boxes = _boxes(np.random.default_rng(77), shapes)
+        got = r.decode_crop_batch(10, torch.from_numpy(boxes).cuda(), 160, 160, MEAN, ISTD).float().cpu().numpy()
+        for i, (_, pix, _) in zip([3, 21], ref):
+            want = oracle.crop_resize_normalize(pix, boxes[i][:4], bool(boxes[i][4]), 160, 160, MEAN, ISTD)
+            tol = 2.0 ** -11 * np.abs(want) + 4e-6 + max(ISTD) / 255.0
+            assert (np.abs(got[i].astype(np.float64) - want) <= tol).all(), i
+    # an image wider than one workgroup per MCU row can hold is refused when no working buffer is given
+    wide = pcrgen.write_record([pcrgen.make_jpeg(900, 1, 2000, 8, 3, 6.0, 2, 2, 90)])
+    with pkg.pcr_open(wide, 0) as r:
+        tb = torch.tensor([[0, 0, 2000, 8, 0]], dtype=torch.int32, device="cuda")
+        with pytest.raises(pkg.PcrError) as e:
+            r.decode_crop_batch(1, tb, 8, 8, MEAN, ISTD)
+        assert e.value.code == pkg.E_UNSUPPORTED
+        work = torch.empty(int(r.output_layout()[-1]), dtype=torch.uint8, device="cuda")
+        r.decode_crop_batch(1, tb, 8, 8, MEAN, ISTD, pixels=work)                 # with one, it is served
+
+
 def test_tail_argument_errors(gray64):
     torch = _torch()
     g = [pcrgen.make_jpeg(i, 0, 40, 24, 1, 8.0, 1, 1, 90) for i in range(2)]
