@@ -340,7 +340,7 @@ def streamed_from_pinned(torch, pkg, records, outs, scan_groups, n_img, steps):
     return streamed
 
 
-def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms):
+def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms, k):
     """Measurements beyond the decode path proper (fidelity upgrade, training tail, similarity scores, the same images
     as baseline files and with restart intervals); imagenet_like only, with --extras."""
     handles, outs, streams, records, n_img = job.handles, job.outs, job.streams, job.records, job.n_img
@@ -376,9 +376,11 @@ def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms):
         crop_t.append(torch.from_numpy(bx).cuda())
         tails.append(torch.empty((h.n, 3, 224, 224), dtype=torch.float16, device="cuda"))
     MEAN, ISTD = (0.485, 0.456, 0.406), (1 / 0.229, 1 / 0.224, 1 / 0.225)
-    k = args.scan_group
+    def tail_step():                                               # one kernel: the full-resolution pixels never reach memory
+        for h, st, c, t in zip(handles, streams, crop_t, tails):
+            h.decode_crop_batch(k, c, 224, 224, MEAN, ISTD, pixels=None, out=t, stream=st.cuda_stream)
 
-    def tail_step():
+    def tail_step_working_buffer():
         for h, o, st, c, t in zip(handles, outs, streams, crop_t, tails):
             h.decode_crop_batch(k, c, 224, 224, MEAN, ISTD, pixels=o, out=t, stream=st.cuda_stream)
 
@@ -388,7 +390,7 @@ def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms):
             h.crop_resize_batch(o, c, 224, 224, MEAN, ISTD, out=t, stream=st.cuda_stream)
 
     times = []
-    for fn in (tail_step, tail_step_two_calls):
+    for fn in (tail_step, tail_step_working_buffer, tail_step_two_calls):
         fn()
         torch.cuda.synchronize()
         reps_t = max(3, args.steps)
@@ -407,7 +409,8 @@ def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms):
     tail_ms = e0.elapsed_time(e1) / 10
     tail_bytes = box_bytes / len(handles) + handles[0].n * 3 * 224 * 224 * 2
     res["training_tail"] = {"out": "float16 [n, 3, 224, 224]", "scan_group": k, "images_per_s_decode_plus_tail": n_img / times[0],
-                            "ms_per_step_decode_plus_tail": times[0] * 1e3, "ms_per_step_decode_then_tail_as_two_calls": times[1] * 1e3,
+                            "ms_per_step_decode_plus_tail": times[0] * 1e3, "ms_per_step_through_a_working_buffer": times[1] * 1e3,
+                            "ms_per_step_decode_then_tail_as_two_calls": times[2] * 1e3,
                             "tail_kernel_ms_per_record_alone": tail_ms, "tail_kernel_algorithmic_GBps": tail_bytes / (tail_ms * 1e-3) / 1e9,
                             "tail_kernel_frac_of_hbm_peak": tail_bytes / (tail_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     cap = max(len(r) for r in records)
@@ -421,7 +424,7 @@ def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms):
         def pipeline_step():
             for j in range(len(records)):
                 ld.upload(j, need[j])
-                ld.decode_crop(j, k, crop_t[j], 224, 224, MEAN, ISTD, outs[j], tails[j])
+                ld.decode_crop(j, k, crop_t[j], 224, 224, MEAN, ISTD, None, tails[j])
 
         pipeline_step()
         for j in range(len(records)):
@@ -668,7 +671,7 @@ def main():
         line["from_pinned_host_memory"] = streamed_from_pinned(torch, pkg, records, job.outs, scan_groups if name == "ham_like" else TABLE_SCAN_GROUPS,
                                                                n_img, args.steps)
     if args.extras and name == "imagenet_like":
-        line.update(extras(torch, pkg, pcrgen, oracle, job, args, ends, {k: v[0] * 1e3 for k, v in per_k.items()}))
+        line.update(extras(torch, pkg, pcrgen, oracle, job, args, ends, {kk: v[0] * 1e3 for kk, v in per_k.items()}, headline_k))
     job.close()
     del job
     torch.cuda.synchronize()
