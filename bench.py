@@ -498,6 +498,7 @@ def main():
     ap.add_argument("--images", type=int, default=None, help="use only the first N images of the workload")
     ap.add_argument("--scan-group", type=int, default=None, help="the scan group `value` is quoted at (default: the highest)")
     ap.add_argument("--entry-interval", type=int, default=128, help="MCUs between the entry points the record writer stores (record version 2)")
+    ap.add_argument("--only", action="store_true", help="time only the scan group of --scan-group (for profiler runs)")
     ap.add_argument("--extras", action="store_true", help="also: fidelity upgrades, training tail, similarity scores, baseline files, restart intervals")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-default-queues", action="store_true", help="skip the child process that measures the step with HIP's default number of hardware queues")
@@ -525,6 +526,8 @@ def main():
     headline_k = args.scan_group or scan_groups[-1]
     if headline_k not in scan_groups:
         scan_groups = tuple(sorted(set(scan_groups) | {headline_k}))
+    if args.only:
+        scan_groups = (headline_k,)
 
     t0 = time.time()
     records, files = pcrgen.make_workload(name, limit=args.images)
@@ -678,7 +681,7 @@ def main():
     # the same files in plain records (version 1, what the input generator writes: no entry points)
     pjob = Job(torch, pkg, plain_records)
     plain = {}
-    for k in sorted(set(TABLE_SCAN_GROUPS) & set(scan_groups)):
+    for k in ([] if args.only else sorted(set(TABLE_SCAN_GROUPS) & set(scan_groups))):
         psec, psingles, _, palone, pcalls = pjob.timed(k, max(3, args.steps // 2), 2, single_steps=5)
         plain[str(k)] = {"images_per_s": n_img / psec, "ms_per_step": psec * 1e3,
                          "ms_one_record_alone": sum(ms for ms, _ in palone.values()) / pcalls}
