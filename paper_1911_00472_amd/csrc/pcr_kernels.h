@@ -52,6 +52,8 @@ struct DevRecord {
     AcTab* tabs;               // Huffman tables of the AC scans: those of the refinement scans are written by phase 1 for phase 2;
                                // with tabs_prebuilt, k_build_tables has written all of them before the entropy kernels start
     const uint32_t* tab_idx;   // [n][G] index into tabs
+    DcTab* dctabs;             // with tabs_prebuilt: the DC tables of the DC first scans, three slots per scan (one per scan component)
+    const uint32_t* dctab_idx; // [n][G] first slot of the scan in dctabs
     const uint32_t* ent_off;   // [n][G] record offset of the scan's entry points (0: none; then slot_cnt - 1 of them)
     uint32_t tabs_prebuilt;    // set per call by the host (records whose scans have restart intervals)
 };
@@ -297,9 +299,20 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     int tj1 = 0, tj2 = 0, ntab = 1;
     if (o1 != o0) { tj1 = 1; ntab = 2; }
     if (o2 == o1) tj2 = tj1; else if (o2 != o0) { tj2 = ntab; ntab++; }
-    if (threadIdx.x == 0) dctab_build(&tabs[0], R.rec + o0);
-    if (threadIdx.x == 1 && tj1 == 1) dctab_build(&tabs[1], R.rec + o1);
-    if (threadIdx.x == 2 && tj2 != 0 && tj2 != tj1) dctab_build(&tabs[tj2], R.rec + o2);
+    if (R.tabs_prebuilt) {                                  // built once per scan by k_build_tables: copy the distinct ones
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.dctabs[R.dctab_idx[(size_t)un.img * R.G + un.scan]]);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&tabs[0]);
+        constexpr uint32_t kWords = sizeof(DcTab) / 4;
+        for (uint32_t e = threadIdx.x; e < kWords; e += kEntropyLanes) {
+            dst[e] = src[e];
+            if (tj1 == 1) dst[kWords + e] = src[kWords + e];
+            if (tj2 != 0 && tj2 != tj1) dst[(uint32_t)tj2 * kWords + e] = src[2 * kWords + e];
+        }
+    } else {
+        if (threadIdx.x == 0) dctab_build(&tabs[0], R.rec + o0);
+        if (threadIdx.x == 1 && tj1 == 1) dctab_build(&tabs[1], R.rec + o1);
+        if (threadIdx.x == 2 && tj2 != 0 && tj2 != tj1) dctab_build(&tabs[tj2], R.rec + o2);
+    }
     __syncthreads();
     DcWindowReader wr;                                      // tables by scan component
     wr.init(L.words, L.byte_off, L.sub_bits, L.nbits, &tabs[0], &tabs[uni(tj1)], &tabs[uni(tj2)], L.ls.ns, threadIdx.x);
@@ -335,7 +348,12 @@ __global__ void __launch_bounds__(kEntropyLanes) k_build_tables(DevRecord R, uin
     if (R.status[i] != kOk || g >= R.img[i].nscans) return;
     const size_t ig = (size_t)i * R.G + g;
     const ScanDesc* sd = &R.scan[ig];
-    if (!sd->valid || sd->Ss == 0) return;                  // (DC scans and sequential scans build their own)
+    if (!sd->valid) return;
+    if (sd->Ss == 0) {                                      // DC first scans: the table of every scan component (sequential scans build their own)
+        if (sd->Ah == 0 && R.img[i].progressive && threadIdx.x < sd->ns)
+            dctab_build(&R.dctabs[R.dctab_idx[ig] + threadIdx.x], R.rec + sd->dc_off[threadIdx.x]);
+        return;
+    }
     if (threadIdx.x == 0) actab_build(&tab, R.rec + sd->ac_off);
     __syncthreads();
     actab_pack(&tab, sd->Ah == 0, threadIdx.x, kEntropyLanes);
@@ -890,6 +908,8 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
     __shared__ ApplyList rl[kRefine ? kMaxComp : 1];       // refinement scan lists of the components (n = 0: none)
     __shared__ uint32_t org[kPixLanes];                    // per MCU of the run: its first pixel, counted in pixels from the image's first (< 2^32)
     __shared__ uint16_t visw[kPixLanes], vish[kPixLanes];  // ... and how many of its pixel columns / rows lie inside the image
+    // kFlat: a flat block of the first component gives 64 equal pixels: their 12 output bytes (4 pixels) are made once per block
+    __shared__ uint32_t flat_rgb[kFlat ? kPixLanes : 1][3];
     short_kernel_priority();
     const uint32_t timg = uni(tiles[blockIdx.x].img), mcu0 = uni(tiles[blockIdx.x].mcu0);
     const uint32_t tid = threadIdx.x;
@@ -978,6 +998,28 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
             s[0] = s[1] = s[2] = s[3] = f;
         } else four_samples(tile + mm * bpm * 64 + G.rb[c] + (ly >> shy) * G.rs[c], x0, shx, s);
     };
+    // kFlat with the first component at full resolution (the usual case): every block of it is 64 equal pixels
+    const bool once_per_block = kFlat && shx0 == 0 && shy0 == 0;
+    if (once_per_block) {
+        const uint32_t nyb = G.nbl[0];                      // blocks of the first component per MCU
+        if (tid < nm * nyb) {
+            const uint32_t mm = (tid * recip16(nyb)) >> 16, yb = tid - mm * nyb;
+            const uint32_t ly = (yb >> (G.hs[0] - 1)) * 8, x0 = (yb & (G.hs[0] - 1)) * 8;    // the block's first pixel inside the MCU
+            uint32_t w0 = 0, w1 = 0, w2 = 0;
+            float ys[4], cb[4], cr[4];
+            fetch(0, mm, ly, x0, 0, 0, ys);
+            if (nc == 1) { w0 = put_u8(ys[0], 0, 0); w0 |= w0 << 8; w0 |= w0 << 16; w1 = w0; w2 = w0; }
+            else {
+                fetch(1, mm, ly, x0, shx1, shy1, cb); fetch(2, mm, ly, x0, shx2, shy2, cr);
+                const float u = cb[0] - 128.f, w = cr[0] - 128.f;
+                const uint32_t r = put_u8(ys[0] + 1.402f * w, 0, 0), gq = put_u8(ys[0] - 0.344136f * u - 0.714136f * w, 0, 0), bq = put_u8(ys[0] + 1.772f * u, 0, 0);
+                w0 = r | (gq << 8) | (bq << 16) | (r << 24); w1 = gq | (bq << 8) | (r << 16) | (gq << 24); w2 = bq | (r << 8) | (gq << 16) | (bq << 24);
+            }
+            if (dead) w0 = w1 = w2 = 0;
+            flat_rgb[tid][0] = w0; flat_rgb[tid][1] = w1; flat_rgb[tid][2] = w2;
+        }
+        __syncthreads();
+    }
     for (uint32_t it = tid; it < items; it += kPixLanes) {
         // lanes run along the image rows: group, then MCU, then pixel row
         const uint32_t g = it & (gpm - 1), q = it >> lg;
@@ -986,6 +1028,18 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
         if (ly >= vish[mm] || x0 >= vw) continue;
         uint8_t* wp = out + R.out_off[timg] + ((size_t)org[mm] + (size_t)ly * W + x0) * nc;
         const uint32_t left = vw - x0;                      // pixels of the group inside the image
+        if (once_per_block) {
+            const uint32_t* w = flat_rgb[mm * G.nbl[0] + (ly >> 3) * G.hs[0] + (x0 >> 3)];
+            const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
+            if (nc == 1) {
+                if (left >= 8) { struct __attribute__((packed, aligned(1))) Eight { uint32_t a, b; }; Eight e8; e8.a = w0; e8.b = w1; *reinterpret_cast<Eight*>(wp) = e8; }
+                else for (uint32_t i = 0; i < left; i++) wp[i] = (uint8_t)w0;
+            } else {
+                if (left >= 4) { struct __attribute__((packed, aligned(1))) Twelve { uint32_t a, b, c; }; Twelve tw; tw.a = w0; tw.b = w1; tw.c = w2; *reinterpret_cast<Twelve*>(wp) = tw; }
+                else for (uint32_t i = 0; i < left * 3; i++) wp[i] = (uint8_t)((i < 4 ? w0 : (i < 8 ? w1 : w2)) >> (8 * (i & 3)));
+            }
+            continue;
+        }
         if (nc == 1) {
             float a[4], bq[4];
             fetch(0, mm, ly, x0, 0, 0, a); fetch(0, mm, ly, x0 + 4, 0, 0, bq);

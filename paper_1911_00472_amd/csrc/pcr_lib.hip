@@ -375,6 +375,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     std::vector<PixelTile> tiles;
     uint64_t nm = 0; uint64_t ns = 0;
     std::vector<uint32_t> tab_idx((size_t)n * G, 0); uint32_t ntabs = 0;
+    std::vector<uint32_t> dctab_idx((size_t)n * G, 0); uint32_t ndctabs = 0;
     r->prebuild_tables = false;
     // version 2: where the entry points of every scan lie (behind the regions of the scan's group)
     std::vector<uint32_t> ent_off((size_t)n * G, 0), ent_cnt((size_t)n * G, 0);
@@ -414,7 +415,8 @@ static int finish_open(pcr_record* r, hipStream_t s) {
             const bool serial = !(d.progressive && sd.Ss == 0 && sd.Ah > 0);          // (DC refinement is read in place, without units)
             if (sd.ri == 0 && serial && ent_cnt[ig] > 0) cnt = 1 + ent_cnt[ig];         // units start at the entry points
             else ent_off[ig] = 0;
-            if (cnt > 1 && sd.Ss > 0) r->prebuild_tables = true;     // several units share a scan's table: build it once
+            if (d.progressive && sd.Ss == 0 && sd.Ah == 0) { dctab_idx[ig] = ndctabs; ndctabs += kMaxComp; }
+            if (cnt > 1 && (sd.Ss > 0 || d.progressive)) r->prebuild_tables = true;     // several units share a scan's tables: build them once
             r->slot_base[ig] = (uint32_t)ns; r->slot_cnt[ig] = cnt;
             ns += cnt + 1;
         }
@@ -431,7 +433,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     size_t need = arena_round(padded) + arena_round(r->coef_off[n] * sizeof(int16_t)) + arena_round((r->coef_off[n] / 64 + 1) * sizeof(int16_t)) + arena_round((nm + 2) * sizeof(uint64_t)) +
                   arena_round((ns + 1) * sizeof(uint32_t)) + 2 * arena_round((n + 1) * sizeof(uint64_t)) +
                   4 * arena_round(((size_t)n * G + 1) * sizeof(uint64_t)) + arena_round((tiles.size() + 1) * sizeof(PixelTile)) + arena_round((n + 1) * 8) +
-                  arena_round(((size_t)ntabs + 1) * sizeof(AcTab)) + arena_round(((size_t)n * G + 1) * sizeof(uint32_t));
+                  arena_round(((size_t)ntabs + 1) * sizeof(AcTab)) + arena_round(((size_t)ndctabs + 1) * sizeof(DcTab)) + arena_round(((size_t)n * G + 1) * sizeof(uint32_t)) + arena_round(((size_t)n * G + 1) * sizeof(uint32_t));
     need += 8 * ((ns + (size_t)n * G) * sizeof(Unit) + (size_t)n * kMaxComp * 64) + (1u << 20);
     int rc = arena_reset(&r->big, need);
     if (!rc) rc = arena_alloc(&r->big, &d.clean, padded);
@@ -451,6 +453,10 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     if (!rc) rc = arena_upload(&r->big, &r->d_dims, dims);
     uint32_t* d_tab_idx = nullptr;
     if (!rc) rc = arena_upload(&r->big, &d_tab_idx, tab_idx);
+    uint32_t* d_dctab_idx = nullptr;
+    if (!rc) rc = arena_upload(&r->big, &d_dctab_idx, dctab_idx);
+    if (!rc) rc = arena_alloc(&r->big, &d.dctabs, (size_t)ndctabs);
+    d.dctab_idx = d_dctab_idx;
     uint32_t* d_ent_off = nullptr;
     if (!rc) rc = arena_upload(&r->big, &d_ent_off, ent_off);
     d.ent_off = d_ent_off;
