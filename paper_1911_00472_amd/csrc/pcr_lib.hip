@@ -111,6 +111,9 @@ struct pcr_record {
     Arena small, big;                       // descriptor tables (sized by n and G) / everything sized by the images, and the work lists
     uint8_t* d_rec = nullptr;
     PixelTile* d_tiles = nullptr; uint32_t n_tiles = 0;
+    PixelTile* d_flat_tiles = nullptr; uint32_t n_flat_tiles = 0;   // runs of 8x8 pixel cells, for decodes of DC scans only
+    uint32_t flat_row_cells = 0;                                    // cells per row of the widest image
+    PixelTile* d_flat_rows = nullptr; uint32_t n_flat_rows = 0;     // ... and rows of cells (none if an image is too wide for k_pixel_flat_rows)
     uint32_t* d_dims = nullptr;             // [n][2] width, height (for kernels that run without a decode before them)
     bool prebuild_tables = false;           // some AC scan has restart intervals: k_build_tables runs before the entropy kernels
     // decode fused with the training tail (allocated at its first call): one tile per MCU row, the side buffer of first
@@ -372,7 +375,9 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     compute_levels(r);
     r->out_off.assign(n + 1, 0); r->coef_off.assign(n + 1, 0);
     r->mask_off.assign((size_t)n * G, 0); r->slot_base.assign((size_t)n * G, 0); r->slot_cnt.assign((size_t)n * G, 0);
-    std::vector<PixelTile> tiles;
+    std::vector<PixelTile> tiles, flat_tiles, flat_rows;
+    bool rows_fit = true;
+    r->flat_row_cells = 0;
     uint64_t nm = 0; uint64_t ns = 0;
     std::vector<uint32_t> tab_idx((size_t)n * G, 0); uint32_t ntabs = 0;
     std::vector<uint32_t> dctab_idx((size_t)n * G, 0); uint32_t ndctabs = 0;
@@ -422,9 +427,15 @@ static int finish_open(pcr_record* r, hipStream_t s) {
         }
         const uint32_t per = pixel_mcus_per_tile(d), mcus = (uint32_t)d.mcux * d.mcuy;       // runs of MCUs, one lane per block
         for (uint32_t m0 = 0; m0 < mcus; m0 += per) tiles.push_back(PixelTile{i, m0});
+        for (uint32_t c0 = 0, cells = flat_cells(d.W, d.H); c0 < cells; c0 += kFlatLanes) flat_tiles.push_back(PixelTile{i, c0});
+        rows_fit = rows_fit && flat_rows_fit(d.W);
+        r->flat_row_cells = std::max(r->flat_row_cells, ((uint32_t)d.W + 7) >> 3);
+        for (uint32_t cy = 0; cy * 8 < d.H; cy++) flat_rows.push_back(PixelTile{i, cy});
     }
     if (ns >= (1ull << 32)) return PCR_E_UNSUPPORTED;
-    r->n_masks = nm; r->n_slots = (uint32_t)ns; r->n_tiles = (uint32_t)tiles.size();
+    r->n_masks = nm; r->n_slots = (uint32_t)ns; r->n_tiles = (uint32_t)tiles.size(); r->n_flat_tiles = (uint32_t)flat_tiles.size();
+    if (!rows_fit) flat_rows.clear();
+    r->n_flat_rows = (uint32_t)flat_rows.size();
 
     DevRecord& d = r->d;
     const size_t padded = nbytes + 1024;      // slack: bit readers look ahead
@@ -432,7 +443,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     // 12 per image and component, ...): anything beyond that is allocated on its own
     size_t need = arena_round(padded) + arena_round(r->coef_off[n] * sizeof(int16_t)) + arena_round((r->coef_off[n] / 64 + 1) * sizeof(int16_t)) + arena_round((nm + 2) * sizeof(uint64_t)) +
                   arena_round((ns + 1) * sizeof(uint32_t)) + 2 * arena_round((n + 1) * sizeof(uint64_t)) +
-                  4 * arena_round(((size_t)n * G + 1) * sizeof(uint64_t)) + arena_round((tiles.size() + 1) * sizeof(PixelTile)) + arena_round((n + 1) * 8) +
+                  4 * arena_round(((size_t)n * G + 1) * sizeof(uint64_t)) + arena_round((tiles.size() + 1) * sizeof(PixelTile)) + arena_round((flat_tiles.size() + 1) * sizeof(PixelTile)) + arena_round((flat_rows.size() + 1) * sizeof(PixelTile)) + arena_round((n + 1) * 8) +
                   arena_round(((size_t)ntabs + 1) * sizeof(AcTab)) + arena_round(((size_t)ndctabs + 1) * sizeof(DcTab)) + arena_round(((size_t)n * G + 1) * sizeof(uint32_t)) + arena_round(((size_t)n * G + 1) * sizeof(uint32_t));
     need += 8 * ((ns + (size_t)n * G) * sizeof(Unit) + (size_t)n * kMaxComp * 64) + (1u << 20);
     int rc = arena_reset(&r->big, need);
@@ -448,6 +459,8 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     if (!rc) rc = arena_upload(&r->big, &d_sb, r->slot_base);
     if (!rc) rc = arena_upload(&r->big, &d_sc, r->slot_cnt);
     if (!rc) rc = arena_upload(&r->big, &r->d_tiles, tiles);
+    if (!rc) rc = arena_upload(&r->big, &r->d_flat_tiles, flat_tiles);
+    if (!rc) rc = arena_upload(&r->big, &r->d_flat_rows, flat_rows);
     std::vector<uint32_t> dims((size_t)n * 2);
     for (uint32_t i = 0; i < n; i++) { dims[2 * i] = (uint32_t)r->img[i].W; dims[2 * i + 1] = (uint32_t)r->img[i].H; }
     if (!rc) rc = arena_upload(&r->big, &r->d_dims, dims);
@@ -533,7 +546,7 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
 // buffer layout.  Everything is enqueued on s, which is synchronised before returning.  On failure the
 // handle holds no record (pcr_close is all that may follow).
 static int bind_device(pcr_record* r, const void* d_bytes, size_t nbytes, hipStream_t s) {
-    r->plans.clear(); r->resident_k = 0; r->hdr = RecordHeader{}; r->n_tiles = 0;
+    r->plans.clear(); r->resident_k = 0; r->hdr = RecordHeader{}; r->n_tiles = 0; r->n_flat_tiles = 0; r->n_flat_rows = 0;
     r->out_off.assign(1, 0); r->coef_off.assign(1, 0);        // until the bind succeeds the handle holds no record
     r->d_dims = nullptr; r->d_ssim_part = nullptr; r->ssim_tiles_max = 0;
     r->d_tail_tiles = nullptr; r->n_tail_tiles = 0; r->d_edge = nullptr; r->d_edge_off = nullptr; r->d_mcu_px_h = nullptr;
@@ -568,7 +581,7 @@ static int bind_device(pcr_record* r, const void* d_bytes, size_t nbytes, hipStr
     }
     if (!rc) rc = finish_open(r, s);
     if (!rc && hipStreamSynchronize(s) != hipSuccess) rc = PCR_E_DEVICE;
-    if (rc) { (void)hipGetLastError(); r->hdr = RecordHeader{}; r->n_tiles = 0; }
+    if (rc) { (void)hipGetLastError(); r->hdr = RecordHeader{}; r->n_tiles = 0; r->n_flat_tiles = 0; r->n_flat_rows = 0; }
     return rc;
 }
 
@@ -765,11 +778,13 @@ static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t c
     int rc = run_entropy_stages(r, k0, k, s, false, &plan);
     if (rc) return rc;
     if (plan->n_apply)
-        hipLaunchKernelGGL((k_pixel<true, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
+        hipLaunchKernelGGL(k_pixel<true>, dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
     else if (plan->has_ac)
-        hipLaunchKernelGGL((k_pixel<false, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
-    else                                                     // DC scans only: every block is flat
-        hipLaunchKernelGGL((k_pixel<false, true>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
+        hipLaunchKernelGGL(k_pixel<false>, dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
+    else if (r->n_flat_rows && !boxes)                       // DC scans only: every block is flat
+        hipLaunchKernelGGL(k_pixel_flat_rows, dim3(r->n_flat_rows), dim3(kFlatRowLanes), flat_rows_lds(r->flat_row_cells), s, r->d, r->d_flat_rows, out, r->flat_row_cells);
+    else
+        hipLaunchKernelGGL(k_pixel_flat, dim3(r->n_flat_tiles), dim3(kFlatLanes), 0, s, r->d, r->d_flat_tiles, out, boxes);
     mark(r, PCR_STAGE_PIXEL, s);
     call_end(r);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;

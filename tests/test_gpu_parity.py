@@ -327,6 +327,37 @@ def test_degenerate_shapes():
 
 
 @pytest.mark.gpu
+def test_dc_only_decodes_both_pixel_kernels(gray64):
+    """A decode that holds DC coefficients only has two pixel kernels: rows of 8x8 cells written as aligned chunks (the
+    usual case) and one lane per cell (crop boxes, or an image of more than 1024 cells per row).  Both against the
+    oracle and against each other, on odd sizes (widths that leave rows unaligned, 1 x 1, one cell row, one cell
+    column), 4:2:0, 4:4:4, 4:2:2 and gray."""
+    torch = _torch()
+    shapes = [(1, 1), (3, 2), (17, 9), (301, 203), (8, 8), (16, 300), (299, 16), (7, 64), (333, 1)]
+    recs = []
+    for si, (hs, vs) in enumerate(((2, 2), (1, 1), (2, 1))):
+        recs.append(pcrgen.write_record([pcrgen.make_jpeg(4000 + 16 * si + j, 1, w, h, 3, 6.0, hs, vs, 90) for j, (w, h) in enumerate(shapes)]))
+    recs.append(gray64[0])
+    recs.append(pcrgen.write_record([pcrgen.make_jpeg(4100, 1, 8200, 8, 3, 6.0, 2, 2, 90)]))       # 1025 cells per row
+    for rec in recs:
+        with pkg.pcr_open(rec, 0) as r:
+            lay = r.output_layout()
+            rows = r.decode_batch(1)
+            ref = oracle.decode_record(rec, 1, threads=8, want_coef=False)
+            host = rows.cpu().numpy()
+            for i, (_, p0, info) in enumerate(ref):
+                got = host[int(lay[i]):int(lay[i + 1])].reshape(info.H, info.W, info.nc).astype(int)
+                assert np.abs(got - p0).max() <= PIXEL_TOL, ("pixels", i, info.W, info.H)
+            # boxes that cover every image make the cropping call decode the same pixels through the per-cell kernel
+            boxes = torch.tensor([[0, 0, r.image_info(i)[0], r.image_info(i)[1], 0] for i in range(r.n)], dtype=torch.int32, device="cuda")
+            work = torch.full_like(rows, 7)
+            c = r.image_info(0)[2]
+            r.decode_crop_batch(1, boxes, 4, 4, [0.5] * c, [2.0] * c, pixels=work)
+            torch.cuda.synchronize()
+            assert torch.equal(work, rows)
+
+
+@pytest.mark.gpu
 def test_stage_timing_history(rgb_small):
     """Stage timing: per-call and accumulated event times, one interval per entropy kernel launch."""
     import paper_1911_00472_amd as pkg
