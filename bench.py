@@ -48,8 +48,12 @@ TABLE_SCAN_GROUPS = (1, 2, 5, 10)     # the scan groups the paper tabulates (Tab
 # and WRITE_SIZE 1.0 (profiles/), so fetched bytes are the counter x 2.  They describe the kernels as they stood when
 # the counters were taken: an entry is removed (-> null in the output) whenever its kernel changes.
 PMC = {
+    # mean of the two launches of one decode (profiles/decode_kernels_imagenet_like_k10_counters.md)
+    "ac_refine": {"salu": 731.1e6, "valu": 239.0e6, "fetch_bytes": 585.8e6, "write_bytes": 132.0e6,
+                  "source": "profiles/decode_kernels_imagenet_like_k10_counters.md (SQ_INSTS_SALU, SQ_INSTS_VALU, FETCH_SIZE x 2.0, WRITE_SIZE x 1.0)"},
 }
-RECORD0_INSTS = None           # {"scalar": ..., "vector": ...} of all kernels of that decode, same counter run
+# all kernels of that decode, same counter run
+RECORD0_INSTS = {"scalar": 2740.2e6, "vector": 1625.2e6}
 
 # The serial chain of one Huffman-coded symbol in this design, at the very least: fetch the packed word of the current
 # bit offset, test it, take its length, add it to the position, apply the position update, test for the end of the
