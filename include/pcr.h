@@ -91,7 +91,9 @@ int pcr_open_device(const void* d_bytes, size_t nbytes, void* hip_stream, pcr_re
  */
 int pcr_rebind_device(pcr_record* rec, const void* d_bytes, size_t nbytes, void* hip_stream);
 
-/* Release a handle and all device memory it owns.  NULL is allowed. */
+/* Release a handle and all device memory it owns.  NULL is allowed.  The call waits for ALL work on the handle's
+ * device (releasing device memory does that in any case), so it also holds up other handles' streams: a loader keeps
+ * its handles and re-binds them (pcr_rebind_device, pcr_loader_*) instead of closing and opening per record. */
 void pcr_close(pcr_record* rec);
 
 int pcr_num_images(const pcr_record* rec, int* n);
