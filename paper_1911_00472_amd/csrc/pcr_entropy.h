@@ -1158,21 +1158,9 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
 // Returns the sign mask (1 = positive) of the positions that become non-zero and the mask of the positions whose
 // correction bit is 1.  The stream holds exactly one correction bit per history-non-zero position of the band, in
 // zig-zag order; the bits read between two symbols are dealt out to the history positions passed on the way.
-// The position in the stream is a plain bit offset; the 32 bits at it are fetched from two words.
-PCR_HD uint32_t stream_bits(const uint32_t* words, uint32_t bit) {          // the 32 bits that start at bit offset `bit`
-    const uint32_t w = bit >> 5, sh = bit & 31;
-    const uint64_t two = ((uint64_t)words[w] << 32) | words[w + 1];
-    return (uint32_t)((two << sh) >> 32);
-}
-PCR_HD uint64_t correction_bits(const uint32_t* words, uint32_t bit, uint32_t n) {   // n <= 63 bits from `bit`; first bit read -> bit 0
-    uint64_t out = 0; uint32_t done = 0;
-    while (n > 0) {
-        const uint32_t t = n > 32 ? 32 : n;
-        out |= (uint64_t)(bitrev32(stream_bits(words, bit + done)) & (t == 32 ? ~0u : (1u << t) - 1)) << done;   // reversed: the first bit read becomes bit 0
-        done += t; n -= t;
-    }
-    return out;
-}
+// The lane keeps 64 bits of the stream in a register pair and fetches a word only when 32 of them are used up
+// (every lane of a wavefront reads another block: these are plain vector loads), and takes a symbol's correction
+// bits out of the 32 bits it looked the symbol up in whenever they fit.
 
 // bits (first bit read = bit 0) dealt out to the set bits of `where`, lowest position first
 PCR_HD uint64_t deal_bits(uint64_t bits, uint64_t where) {
@@ -1184,11 +1172,33 @@ PCR_HD uint64_t deal_bits(uint64_t bits, uint64_t where) {
     return out;
 }
 
+struct LaneBits {
+    const uint32_t* words;
+    uint64_t buf;                                             // words[wi] : words[wi + 1]
+    uint32_t wi, pos;                                         // next unread bit: bit `pos` (0..31) of buf, counted from its top
+    PCR_HD void init(const uint32_t* w, uint32_t bit) { words = w; wi = bit >> 5; pos = bit & 31; buf = ((uint64_t)words[wi] << 32) | words[wi + 1]; }
+    PCR_HD uint32_t peek() const { return (uint32_t)((buf << pos) >> 32); }          // the next 32 bits
+    PCR_HD void skip(uint32_t n) {
+        pos += n;
+        while (pos >= 32) { wi++; buf = (buf << 32) | words[wi + 1]; pos -= 32; }
+    }
+    PCR_HD uint64_t take_reversed(uint32_t n) {               // the next n <= 63 bits, first bit read -> bit 0
+        uint64_t out = 0; uint32_t done = 0;
+        while (n > 0) {
+            const uint32_t t = n > 32 ? 32 : n;
+            out |= (uint64_t)(bitrev32(peek()) & (t == 32 ? ~0u : (1u << t) - 1)) << done;
+            skip(t); done += t; n -= t;
+        }
+        return out;
+    }
+};
+
 PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, const AcTab* tab, uint64_t h, uint64_t newm, int Ss, int Se,
                          uint64_t* sign_out, uint64_t* plus_out) {
     const uint64_t band = band_mask(Ss, Se);
     h &= band;
-    uint32_t p = byte_off * 8 + (uint32_t)st;                // bit offset of the next unread bit
+    LaneBits rd;
+    rd.init(words, byte_off * 8 + (uint32_t)st);
     const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
     uint64_t sgn = 0, plus = 0;
     uint64_t todo = h;                                       // history positions whose correction bit has not been read yet
@@ -1199,36 +1209,45 @@ PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, 
         int k = Ss;                                          // first position not yet passed
         n = 0;
         while (k <= Se) {
-            const uint32_t win = stream_bits(words, p);
+            const uint32_t win = rd.peek();
             const uint32_t e = ac_code(tab, win);
             if (!e) break;                                   // phase 1 has already flagged the image
             const uint32_t len = e >> 8, r = (e >> 4) & 15, s = e & 15;
+            uint32_t used;                                   // bits of `win` this symbol takes
             int pos;
             if (s) {                                         // code, sign bit, then the corrections passed on the way
                 if (!rem) break;
                 pos = __builtin_ctzll(rem); rem &= rem - 1;
                 sgn |= (uint64_t)((win << len) >> 31) << pos;
-                p += len + 1;
+                used = len + 1;
             } else if (r == 15) {                            // sixteen zeros: lands on the sixteenth zero from k, which stays zero
-                p += len;
+                used = len;
                 uint64_t z = ~h & band & ~((1ull << k) - 1);
                 for (int q = 0; q < 15 && z; q++) z &= z - 1;
                 pos = z ? __builtin_ctzll(z) : Se;
             } else {                                         // end of band: code, run-length bits, then every correction left
-                p += len + r;
+                rd.skip(len + r);
                 n = ncorr - taken;
                 break;
             }
             const uint32_t upto = (uint32_t)__builtin_popcountll(h & ((2ull << pos) - 1));   // corrections at positions <= pos (pos itself is a zero)
             if (upto > taken) {
+                const uint32_t m = upto - taken;
                 const uint64_t span = todo & ((2ull << pos) - 1);         // the history positions up to pos not yet served
-                plus |= deal_bits(correction_bits(words, p, upto - taken), span);
-                todo &= ~span; p += upto - taken; taken = upto;
+                if (used + m <= 32) {                        // they are in the window already
+                    plus |= deal_bits(bitrev32(win << used) & ((1u << m) - 1), span);
+                    used += m;
+                } else {
+                    rd.skip(used); used = 0;
+                    plus |= deal_bits(rd.take_reversed(m), span);
+                }
+                todo &= ~span; taken = upto;
             }
+            rd.skip(used);
             k = pos + 1;
         }
     }
-    if (n) plus |= deal_bits(correction_bits(words, p, n), todo);
+    if (n) plus |= deal_bits(rd.take_reversed(n), todo);
     *sign_out = sgn; *plus_out = plus;
 }
 
