@@ -155,6 +155,18 @@ int pcr_decode_coefficients(pcr_record* rec, int k, int16_t* d_coef, void* hip_s
 int pcr_decode_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
                      void* hip_stream, int32_t* d_status);
 
+/* pcr_decode_batch with the chroma up-sampling of stock decoders (Section 5, "Decoding", hands the reassembled bytes
+ * to a stock decoder; the JPEG standard defines no up-sampling, and stock decoders interpolate where pcr_decode_batch
+ * replicates).  Every component's samples are rounded to integers first; an output sample of a component stored at
+ * half resolution is then 3/4 of the nearer and 1/4 of the farther sample of the component's own grid, down the
+ * columns first, then along the rows (beyond the component's ceil(W hs / hmax) x ceil(H vs / vmax) samples the nearest
+ * one stands in); colour conversion and the final rounding as in pcr_decode_batch.  Images without sub-sampled
+ * components differ from pcr_decode_batch only by the rounding of the samples.  The first call on a handle takes one
+ * byte per coefficient slot of working memory from the handle's arena (which may allocate).  Arguments, layout,
+ * stream order, d_status and errors as pcr_decode_batch; a following pcr_upgrade_batch starts from scan_group. */
+int pcr_decode_batch_triangle(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
+                              void* hip_stream, int32_t* d_status);
+
 /* Fidelity upgrade (Section 3 of the paper: a lower-fidelity read is a prefix of a higher-fidelity one, so
  * changing fidelity costs little): raise the planes the last pcr_decode_batch /
  * pcr_upgrade_batch call on this handle left on the device from its scan group to `scan_group` (>= it) by

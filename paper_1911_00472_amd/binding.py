@@ -33,6 +33,7 @@ SYMBOLS = {
     "pcr_coef_layout": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_decode_coefficients": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp]),
     "pcr_decode_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
+    "pcr_decode_batch_triangle": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_upgrade_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_resident_scan_group": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
     "pcr_enable_stage_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
@@ -216,6 +217,16 @@ class Record:
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_decode_batch(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
                "pcr_decode_batch")
+        return out
+
+    def decode_batch_triangle(self, k, out=None, status=None, stream=None):
+        """decode_batch with sub-sampled chroma interpolated by the triangle filter instead of replicated."""
+        import torch
+        if out is None:
+            out = torch.empty(int(self.output_layout()[-1]), dtype=torch.uint8, device="cuda:%d" % self.device)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_decode_batch_triangle(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
+               "pcr_decode_batch_triangle")
         return out
 
     def upgrade_batch(self, k, out=None, status=None, stream=None):

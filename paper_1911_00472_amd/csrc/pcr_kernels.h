@@ -894,7 +894,7 @@ PCR_D void four_samples(const float* row, uint32_t x0, uint32_t sh, float v[4]) 
     else { const float2 t = *reinterpret_cast<const float2*>(row + (x0 >> 1)); v[0] = v[1] = t.x; v[2] = v[3] = t.y; }
 }
 
-template <bool kRefine>
+template <bool kRefine, bool kPlanes>
 __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out,
                                                      const ApplyList* __restrict__ lists, const int32_t* __restrict__ list_idx,
                                                      const CropBox* __restrict__ boxes) {
@@ -965,6 +965,27 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
         else pix_finish<kRefine>(R, B, v, qz[B.c], rlc, dst, row_len);
     }
     __syncthreads();
+    if (kPlanes) {
+        // Instead of pixels: the lane's block, rounded, into the component's own plane of bytes (`out`: one byte per
+        // coefficient slot, so a component's plane lies where its coefficient plane lies, [rows of samples][bw * 8]),
+        // for k_triangle_rgb.  A damaged image's planes are left alone; that kernel writes its pixels as zeros.
+        if (mine) {
+            const uint32_t row_len = B.hs * 8, pw = pick3(B.c, G.bw[0], G.bw[1], G.bw[2]) * 8;
+            const float* src = tile + m * bpm * 64 + pick3(B.c, G.rb[0], G.rb[1], G.rb[2]) + by * 8 * row_len + bx * 8;
+            uint8_t* pd = out + R.coef_off[timg] + (size_t)pick3(B.c, G.plane0[0], G.plane0[1], G.plane0[2]) * 64 + (size_t)(B.brow * 8) * pw + B.bcol * 8;
+#pragma unroll
+            for (int y = 0; y < 8; y++) {
+                float4 lo, hi;
+                if (B.zm <= 1) { lo.x = lo.y = lo.z = lo.w = hi.x = hi.y = hi.z = hi.w = src[0]; }
+                else { lo = *reinterpret_cast<const float4*>(src + y * row_len); hi = *reinterpret_cast<const float4*>(src + y * row_len + 4); }
+                uint2 w;
+                w.x = put_u8(lo.x, 0, 0); w.x = put_u8(lo.y, 1, w.x); w.x = put_u8(lo.z, 2, w.x); w.x = put_u8(lo.w, 3, w.x);
+                w.y = put_u8(hi.x, 0, 0); w.y = put_u8(hi.y, 1, w.y); w.y = put_u8(hi.z, 2, w.y); w.y = put_u8(hi.w, 3, w.y);
+                *reinterpret_cast<uint2*>(pd + (size_t)y * pw) = w;
+            }
+        }
+        return;
+    }
     // ---- phase B: one lane per group of output bytes of one pixel row of one MCU ----
     const uint32_t shx0 = G.hs[0] == G.hmax ? 0 : 1, shy0 = G.vs[0] == G.vmax ? 0 : 1;       // sampling factors are 1 or 2
     const uint32_t shx1 = nc > 1 && G.hs[1] != G.hmax, shy1 = nc > 1 && G.vs[1] != G.vmax;
@@ -1196,6 +1217,78 @@ __global__ void __launch_bounds__(kFlatRowLanes) k_pixel_flat_rows(DevRecord R, 
     }
     if (tid < head) band[tid] = pb[tid];                    // (head < 16 <= the repeated part)
     if (tid < len - tail0) band[tail0 + tid] = pb[in_row(tail0 + tid)];
+}
+
+// --------------------------------------------------------------------------------------
+// k_triangle_rgb: pixels from planes of rounded samples (k_pixel<., true>) with the chroma up-sampling stock decoders
+// use instead of replication: every output sample of a component at half resolution is 3/4 of the nearer and 1/4 of the
+// farther sample of the component's grid, down the columns first, then along the rows; beyond the component's own
+// samples (ceil(W hs / hmax) x ceil(H vs / vmax)) the nearest one stands in.  On integer samples these weights are exact
+// in single precision.  One lane per four pixels of a row.  grid: (ceil(items of the largest image / 256), images).
+// --------------------------------------------------------------------------------------
+PCR_D float triangle_sample(const uint8_t* p, uint32_t pw, uint32_t xc, uint32_t yc, uint32_t fx, uint32_t fy, uint32_t x, uint32_t y) {
+    if (fx == 1 && fy == 1) return (float)p[(size_t)y * pw + x];
+    const uint32_t xi = fx == 2 ? x >> 1 : x;
+    uint32_t xj = fx == 2 ? ((x & 1) ? xi + 1 : (xi ? xi - 1 : 0)) : xi;
+    if (xj >= xc) xj = xc - 1;
+    const uint32_t yi = fy == 2 ? y >> 1 : y;
+    uint32_t yj = fy == 2 ? ((y & 1) ? yi + 1 : (yi ? yi - 1 : 0)) : yi;
+    if (yj >= yc) yj = yc - 1;
+    const float a0 = (float)p[(size_t)yi * pw + xi], a1 = (float)p[(size_t)yj * pw + xi];
+    const float c0 = fy == 2 ? 0.75f * a0 + 0.25f * a1 : a0;
+    if (fx != 2) return c0;
+    const float b0 = (float)p[(size_t)yi * pw + xj], b1 = (float)p[(size_t)yj * pw + xj];
+    const float c1 = fy == 2 ? 0.75f * b0 + 0.25f * b1 : b0;
+    return 0.75f * c0 + 0.25f * c1;
+}
+
+__global__ void __launch_bounds__(256) k_triangle_rgb(DevRecord R, const uint8_t* __restrict__ planes, uint8_t* __restrict__ out) {
+    const uint32_t img = blockIdx.y;
+    ImgDesc D;
+    load_desc(R.img + img, &D);
+    const uint32_t W = D.W, H = D.H, nc = D.nc;
+    const uint32_t gw = (W + 3) >> 2;                        // groups of four pixels per row
+    const uint32_t item = blockIdx.x * 256 + threadIdx.x;
+    if (item >= gw * H || (nc != 1 && nc != 3)) return;
+    const uint32_t y = item / gw, x0 = (item - y * gw) * 4;
+    const uint32_t npx = W - x0 < 4 ? W - x0 : 4;
+    const bool dead = R.status[img] != kOk;
+    float s[kMaxComp][4];
+    uint32_t plane0 = 0;
+#pragma unroll
+    for (uint32_t c = 0; c < kMaxComp; c++) {
+        if (c < nc && !dead) {
+            const uint8_t* p = planes + R.coef_off[img] + (size_t)plane0 * 64;
+            const uint32_t pw = (uint32_t)D.bw[c] * 8, fx = D.hmax / D.hs[c], fy = D.vmax / D.vs[c];
+            const uint32_t xc = (W * D.hs[c] + D.hmax - 1) / D.hmax, yc = (H * D.vs[c] + D.vmax - 1) / D.vmax;
+            for (uint32_t i = 0; i < 4; i++) s[c][i] = i < npx ? triangle_sample(p, pw, xc, yc, fx, fy, x0 + i, y) : 0.f;
+        } else for (uint32_t i = 0; i < 4; i++) s[c][i] = 0.f;
+        plane0 += c < nc ? (uint32_t)D.bw[c] * D.bh[c] : 0;
+    }
+    uint8_t* wp = out + R.out_off[img] + ((size_t)y * W + x0) * nc;
+    if (nc == 1) {
+        for (uint32_t i = 0; i < npx; i++) wp[i] = dead ? 0 : (uint8_t)put_u8(s[0][i], 0, 0);
+        return;
+    }
+    uint32_t w0 = 0, w1 = 0, w2 = 0;
+    if (!dead) {
+        float r[4], g[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const float u = s[1][i] - 128.f, w = s[2][i] - 128.f;
+            r[i] = s[0][i] + 1.402f * w; g[i] = s[0][i] - 0.344136f * u - 0.714136f * w; b[i] = s[0][i] + 1.772f * u;
+        }
+        w0 = put_u8(r[0], 0, w0); w0 = put_u8(g[0], 1, w0); w0 = put_u8(b[0], 2, w0); w0 = put_u8(r[1], 3, w0);
+        w1 = put_u8(g[1], 0, w1); w1 = put_u8(b[1], 1, w1); w1 = put_u8(r[2], 2, w1); w1 = put_u8(g[2], 3, w1);
+        w2 = put_u8(b[2], 0, w2); w2 = put_u8(r[3], 1, w2); w2 = put_u8(g[3], 2, w2); w2 = put_u8(b[3], 3, w2);
+    }
+    if (npx == 4) {
+        struct __attribute__((packed, aligned(1))) Twelve { uint32_t a, b, c; };
+        Twelve tw; tw.a = w0; tw.b = w1; tw.c = w2;
+        *reinterpret_cast<Twelve*>(wp) = tw;
+    } else {
+        for (uint32_t i = 0; i < npx * 3; i++) wp[i] = (uint8_t)((i < 4 ? w0 : (i < 8 ? w1 : w2)) >> (8 * (i & 3)));
+    }
 }
 
 // --------------------------------------------------------------------------------------

@@ -121,6 +121,7 @@ struct pcr_record {
     PixelTile* d_tail_tiles = nullptr; uint32_t n_tail_tiles = 0;
     uint8_t* d_edge = nullptr; uint64_t* d_edge_off = nullptr; uint32_t* d_mcu_px_h = nullptr;
     float2* d_ssim_part = nullptr;          // per-tile sums of the similarity kernels (allocated at their first call)
+    uint8_t* d_planes = nullptr;            // rounded samples per component, for pcr_decode_batch_triangle (allocated at its first call)
     uint32_t ssim_tiles_max = 0;
     uint8_t* d_gather = nullptr; size_t gather_cap = 0;
     std::map<int, Plan> plans;
@@ -548,7 +549,7 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
 static int bind_device(pcr_record* r, const void* d_bytes, size_t nbytes, hipStream_t s) {
     r->plans.clear(); r->resident_k = 0; r->hdr = RecordHeader{}; r->n_tiles = 0; r->n_flat_tiles = 0; r->n_flat_rows = 0;
     r->out_off.assign(1, 0); r->coef_off.assign(1, 0);        // until the bind succeeds the handle holds no record
-    r->d_dims = nullptr; r->d_ssim_part = nullptr; r->ssim_tiles_max = 0;
+    r->d_dims = nullptr; r->d_ssim_part = nullptr; r->ssim_tiles_max = 0; r->d_planes = nullptr;
     r->d_tail_tiles = nullptr; r->n_tail_tiles = 0; r->d_edge = nullptr; r->d_edge_off = nullptr; r->d_mcu_px_h = nullptr;
     // fixed part of the header, then the whole metadata block
     uint8_t fixed[24];
@@ -778,9 +779,9 @@ static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t c
     int rc = run_entropy_stages(r, k0, k, s, false, &plan);
     if (rc) return rc;
     if (plan->n_apply)
-        hipLaunchKernelGGL(k_pixel<true>, dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
+        hipLaunchKernelGGL((k_pixel<true, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
     else if (plan->has_ac)
-        hipLaunchKernelGGL(k_pixel<false>, dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
+        hipLaunchKernelGGL((k_pixel<false, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
     else if (r->n_flat_rows && !boxes)                       // DC scans only: every block is flat
         hipLaunchKernelGGL(k_pixel_flat_rows, dim3(r->n_flat_rows), dim3(kFlatRowLanes), flat_rows_lds(r->flat_row_cells), s, r->d, r->d_flat_rows, out, r->flat_row_cells);
     else
@@ -798,6 +799,37 @@ int pcr_decode_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* strea
     int rc = check_scan_group(r, k);
     if (rc) return rc;
     return decode_to_pixels(r, 0, k, out, cap, stream, d_status);
+}
+
+int pcr_decode_batch_triangle(pcr_record* r, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status) {
+    if (!r || !out) return PCR_E_ARG;
+    int rc = check_scan_group(r, k);
+    if (rc) return rc;
+    const uint32_t n = r->hdr.n;
+    if (cap < r->out_off[n]) return PCR_E_RANGE;
+    HIP_TRY(hipSetDevice(r->device));
+    if (!r->d_planes) {                                      // one byte per coefficient slot
+        rc = arena_alloc(&r->big, &r->d_planes, (size_t)r->coef_off[n] + 16);
+        if (rc) return rc;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    Plan* plan = nullptr;
+    r->resident_k = 0;
+    rc = run_entropy_stages(r, 0, k, s, false, &plan);
+    if (rc) return rc;
+    if (plan->n_apply)
+        hipLaunchKernelGGL((k_pixel<true, true>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, r->d_planes, plan->d_apply_lists, plan->d_list_idx, (const CropBox*)nullptr);
+    else
+        hipLaunchKernelGGL((k_pixel<false, true>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, r->d_planes, (const ApplyList*)nullptr, (const int32_t*)nullptr, (const CropBox*)nullptr);
+    uint32_t items = 1;
+    for (uint32_t i = 0; i < n; i++) items = std::max(items, (((uint32_t)r->img[i].W + 3) / 4) * (uint32_t)r->img[i].H);
+    hipLaunchKernelGGL(k_triangle_rgb, dim3((items + 255) / 256, n), dim3(256), 0, s, r->d, (const uint8_t*)r->d_planes, out);
+    mark(r, PCR_STAGE_PIXEL, s);
+    call_end(r);
+    if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
+    if (d_status) HIP_TRY(hipMemcpyAsync(d_status, r->d.status, n * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+    r->resident_k = k;
+    return PCR_OK;
 }
 
 int pcr_resident_scan_group(const pcr_record* r, int* k) {

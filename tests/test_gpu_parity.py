@@ -358,6 +358,44 @@ def test_dc_only_decodes_both_pixel_kernels(gray64):
 
 
 @pytest.mark.gpu
+def test_triangle_chroma_upsampling(rgb_small, gray64):
+    """pcr_decode_batch_triangle against the oracle's triangle mode (which is pinned against a stock decoder): both round
+    every component's samples to integers, interpolate sub-sampled components with weights 3/4 and 1/4 (exact in single
+    precision on integers) and convert.  Tolerance: the kernel's fp32 sample differs from the oracle's fp64 one by less
+    than 1e-2, so the two roundings of a sample differ only where it lies that close to a half, and then by 1.  (With
+    DC coefficients only a sample is a multiple of 1/8 and one in eight lies exactly on a half: the kernel computes it
+    exactly, the oracle's cosine products leave it a hair above or below.)  One such sample moves Y by 1 or an
+    interpolated chroma value by at most 1, i.e. a colour channel by at most 1.772 ahead of its own rounding, two of
+    them at one pixel by 2.772.  So every byte within 3, and all but a few in a hundred within 1.  4:2:0 (odd sizes:
+    edge samples stand in beyond the planes), 4:2:2, 4:4:4 and gray; scan groups of every kind."""
+    torch = _torch()
+    shapes = [(1, 1), (2, 3), (17, 9), (120, 77), (33, 64), (64, 31)]
+    recs = [(rgb_small[0], (1, 2, 5, 10)), (gray64[0], (1, 6))]
+    for si, (hs, vs) in enumerate(((2, 1), (1, 1), (2, 2))):
+        recs.append((pcrgen.write_record([pcrgen.make_jpeg(4300 + 16 * si + j, 1, w, h, 3, 6.0, hs, vs, 90) for j, (w, h) in enumerate(shapes)]), (1, 4, 10)))
+    for rec, ks in recs:
+        with pkg.pcr_open(rec, 0) as r:
+            lay = r.output_layout()
+            for k in ks:
+                st = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
+                got = r.decode_batch_triangle(k, status=st).cpu().numpy()
+                assert (st.cpu().numpy() == 0).all()
+                far = total = 0
+                for i in range(r.n):
+                    _, want, _ = oracle.decode(oracle.reassemble(rec, i, k), upsample="triangle", want_coef=False)
+                    g = got[int(lay[i]):int(lay[i + 1])].reshape(want.shape).astype(int)
+                    d = np.abs(g - want.astype(int))
+                    assert d.max() <= 3, (i, k, int(d.max()))
+                    far += int((d > 1).sum()); total += d.size
+                assert far <= 2e-2 * total + 2, (k, far, total)
+                assert r.resident_scan_group() == k
+            assert torch.equal(r.upgrade_batch(r.G), r.decode_batch(r.G))      # the planes under it are a decode's planes
+    # where nothing is sub-sampled and the samples are integers anyway (a DC-only gray decode is not: compare at the end)
+    with pkg.pcr_open(gray64[0], 0) as r:
+        assert torch.equal(r.decode_batch_triangle(r.G), r.decode_batch(r.G))   # gray: rounding the sample is the final rounding
+
+
+@pytest.mark.gpu
 def test_stage_timing_history(rgb_small):
     """Stage timing: per-call and accumulated event times, one interval per entropy kernel launch."""
     import paper_1911_00472_amd as pkg
