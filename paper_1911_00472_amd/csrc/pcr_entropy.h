@@ -410,7 +410,7 @@ struct LaneScan {
 // damaged stream makes of it.
 // ---------------------------------------------------------------------------------------
 struct CoefSink {
-    int16_t* plane;
+    int16_t* plane;                                           // may be null if `dense` is given: then only that copy is written
     int16_t* dense;                                           // optional second copy, one value per block: dense[element index / 64]
     uint32_t limit;                                           // elements of `plane`
     int Al;                                                   // values are stored shifted left by this
@@ -425,14 +425,14 @@ struct CoefSink {
                      : "+v"(vidx), "+v"(vval) : "s"(elem), "s"(word), "s"(slot) : "m0");
 #else
         (void)slot;
-        if (((uint32_t)word & kSymCoef) && elem < limit) { plane[elem] = (int16_t)((word >> 16) * (1 << Al)); if (dense) dense[elem >> 6] = plane[elem]; }
+        if (((uint32_t)word & kSymCoef) && elem < limit) { const int16_t val = (int16_t)((word >> 16) * (1 << Al)); if (plane) plane[elem] = val; if (dense) dense[elem >> 6] = val; }
 #endif
     }
     PCR_HD void flush() {
 #if defined(__HIP_DEVICE_COMPILE__)
         if (((uint32_t)vval & kSymCoef) && vidx < limit) {
             const int16_t val = (int16_t)((vval >> 16) * (1 << Al));
-            plane[vidx] = val;
+            if (plane) plane[vidx] = val;
             if (dense) dense[vidx >> 6] = val;
         }
         vval = 0;

@@ -286,7 +286,7 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __rest
 // SHAPE: which DC decoder (dc_shape) the units of this launch take; the host sorts the units by it.
 template <int SHAPE>
 __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
-        const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64) {
+        const uint32_t* __restrict__ clean32, const uint64_t* __restrict__ hist64, uint32_t to_planes) {
     __shared__ DcTab tabs[kMaxComp];
     dc_kernel_priority();
     const Unit un = units[blockIdx.x];
@@ -317,7 +317,8 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const U
     DcWindowReader wr;                                      // tables by scan component
     wr.init(L.words, L.byte_off, L.sub_bits, L.nbits, &tabs[0], &tabs[uni(tj1)], &tabs[uni(tj2)], L.ls.ns, threadIdx.x);
     CoefSink sink;
-    sink.init(L.base, L.base_elems, L.ls.Al, R.dc + (uni((uint64_t)R.coef_off[un.img]) >> 6));
+    // (to_planes = 0: only the compact copy, one value per block -- all a decode without AC scans and refinements reads)
+    sink.init(to_planes ? L.base : nullptr, L.base_elems, L.ls.Al, R.dc + (uni((uint64_t)R.coef_off[un.img]) >> 6));
     int rc = kEFormat;                                      // (a unit in the wrong launch: the descriptors disagree with the host's)
     if (dc_shape(L.ls.ns, L.ls.hs[0], L.ls.vs[0], L.ls.hs[1], L.ls.vs[1], L.ls.hs[2], L.ls.vs[2]) == SHAPE) rc = decode_dc_first_as<SHAPE>(&wr, L.ls, &sink);
     if (rc != kOk) R.status[un.img] = rc;
@@ -1468,14 +1469,15 @@ __global__ void __launch_bounds__(64) k_probe_scalar(uint32_t* out, uint32_t ite
     if (threadIdx.x == 0) out[blockIdx.x] = a ^ b;
 }
 
-// zero every coefficient except element 0 of each 64-element block (n16: 16-byte units, 8 per block)
-__global__ void __launch_bounds__(256) k_fill_zero_keep_dc(uint4* p, size_t n16) {
+// zero every coefficient except element 0 of each 64-element block, which is taken from the compact copy of the DC
+// coefficients (one per block, in plane order); n16: 16-byte units, 8 per block
+__global__ void __launch_bounds__(256) k_fill_zero_dc_from(uint4* p, const int16_t* __restrict__ dc, size_t n16) {
     short_kernel_priority();
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * 256;
     for (; i < n16; i += stride) {
         uint4 v = make_uint4(0, 0, 0, 0);
-        if ((i & 7) == 0) v.x = p[i].x & 0xFFFFu;          // the DC coefficient is the low half of the block's first word
+        if ((i & 7) == 0) v.x = (uint32_t)(uint16_t)dc[i >> 3];   // the DC coefficient is the low half of the block's first word
         p[i] = v;
     }
 }

@@ -127,6 +127,7 @@ struct pcr_record {
     std::map<int, Plan> plans;
     bool timing = false;
     int resident_k = 0;                        // scan group whose planes and masks the last pixel decode left behind (0: none)
+    bool dc_in_planes = false;                 // ... and whether that decode wrote the DC coefficients into the planes (always into the compact copy)
     bool borrowed = false;                  // record bytes belong to the caller (pcr_open_device)
     // stage timing: one list of events per call, the last kTimingRing calls are kept
     std::vector<CallTiming> ring;
@@ -277,7 +278,9 @@ int add_call_times(const CallTiming& c, double* ms, uint32_t* marks) {
 // refine_in_memory: also run k_apply, which leaves the refined coefficients in the planes (the coefficient
 // export needs that; the pixel kernel replays the refinement itself from the lists of k_apply_prep).
 // k0 > 0: a fidelity upgrade -- groups 1 .. k0 are in the planes and masks already, only k0+1 .. k are decoded.
-int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_in_memory, Plan** plan_out) {
+// want_planes: the caller's pixel stage reads the DC coefficients from the planes (false: from the compact copy, if the
+// decode holds nothing but first DC scans; the planes then get them when an upgrade needs them)
+int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_in_memory, Plan** plan_out, bool want_planes = true) {
     Plan* plan = nullptr;
     int rc = build_plan(r, k0, k, &plan);
     if (rc) return rc;
@@ -296,24 +299,28 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
     // fill is skipped (the coefficient export shows whole planes and always needs it).  The mask planes need no
     // fill: every entry a kernel reads was written earlier in the same call.
     // An upgrade keeps the planes; only when it brings the first AC scans must everything but the DCs be cleared.
+    const bool dc_to_planes = want_planes || refine_in_memory || plan->has_ac || plan->n_apply != 0;
     if (k0 == 0) {
         if (plan->has_ac || refine_in_memory)
             hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
-    } else if (plan->has_ac && !plan->had_ac) {
-        hipLaunchKernelGGL(k_fill_zero_keep_dc, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
+    } else if ((plan->has_ac && !plan->had_ac) || (dc_to_planes && !r->dc_in_planes)) {
+        // (the DC coefficients come from the compact copy, which every DC first scan writes)
+        hipLaunchKernelGGL(k_fill_zero_dc_from, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, (const int16_t*)r->d.dc, coef_bytes / 16);
     }
+    r->dc_in_planes = dc_to_planes;
     mark(r, PCR_STAGE_UNSTUFF, s);
     const uint32_t* c32 = reinterpret_cast<const uint32_t*>(r->d.clean);
     const uint64_t* h64 = r->d.masks;
     for (auto& l : plan->levels) {
         const dim3 grid(l.n), block(kEntropyLanes);
         if (l.kind == kDcFirst) {
+            const uint32_t dcp = dc_to_planes ? 1u : 0u;
             switch (l.shape) {
-                case 1: hipLaunchKernelGGL(k_dc_first<1>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
-                case 2: hipLaunchKernelGGL(k_dc_first<2>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
-                case 3: hipLaunchKernelGGL(k_dc_first<3>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
-                case 4: hipLaunchKernelGGL(k_dc_first<4>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
-                default: hipLaunchKernelGGL(k_dc_first<0>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); break;
+                case 1: hipLaunchKernelGGL(k_dc_first<1>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64, dcp); break;
+                case 2: hipLaunchKernelGGL(k_dc_first<2>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64, dcp); break;
+                case 3: hipLaunchKernelGGL(k_dc_first<3>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64, dcp); break;
+                case 4: hipLaunchKernelGGL(k_dc_first<4>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64, dcp); break;
+                default: hipLaunchKernelGGL(k_dc_first<0>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64, dcp); break;
             }
             mark(r, PCR_STAGE_DC_FIRST, s);
         }
@@ -547,7 +554,7 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
 // buffer layout.  Everything is enqueued on s, which is synchronised before returning.  On failure the
 // handle holds no record (pcr_close is all that may follow).
 static int bind_device(pcr_record* r, const void* d_bytes, size_t nbytes, hipStream_t s) {
-    r->plans.clear(); r->resident_k = 0; r->hdr = RecordHeader{}; r->n_tiles = 0; r->n_flat_tiles = 0; r->n_flat_rows = 0;
+    r->plans.clear(); r->resident_k = 0; r->dc_in_planes = false; r->hdr = RecordHeader{}; r->n_tiles = 0; r->n_flat_tiles = 0; r->n_flat_rows = 0;
     r->out_off.assign(1, 0); r->coef_off.assign(1, 0);        // until the bind succeeds the handle holds no record
     r->d_dims = nullptr; r->d_ssim_part = nullptr; r->ssim_tiles_max = 0; r->d_planes = nullptr;
     r->d_tail_tiles = nullptr; r->n_tail_tiles = 0; r->d_edge = nullptr; r->d_edge_off = nullptr; r->d_mcu_px_h = nullptr;
@@ -776,7 +783,7 @@ static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t c
     hipStream_t s = (hipStream_t)stream;
     Plan* plan = nullptr;
     r->resident_k = 0;
-    int rc = run_entropy_stages(r, k0, k, s, false, &plan);
+    int rc = run_entropy_stages(r, k0, k, s, false, &plan, false);   // (the pixel kernels of a decode without AC scans read the compact DC copy)
     if (rc) return rc;
     if (plan->n_apply)
         hipLaunchKernelGGL((k_pixel<true, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
