@@ -446,18 +446,35 @@ struct CoefSink {
 // carries a coefficient.  A symbol the serial part resolved by hand is written back into the reader's words.
 struct IndexSink {
     int16_t* plane;
+    int16_t* dense;                                           // sequential scans: the compact copy of the DC coefficients, dense[element index / 64]
     uint32_t limit;
     int Al;
     uint32_t vidx;                                            // device: this lane's element index, ~0 = none
-    PCR_HD void init(int16_t* p, uint32_t elems, int al) { plane = p; limit = elems; Al = al; vidx = ~0u; }
+    PCR_HD void init(int16_t* p, uint32_t elems, int al, int16_t* per_block = nullptr) { plane = p; dense = per_block; limit = elems; Al = al; vidx = ~0u; }
     // host build: store at once (there are no lanes to hold anything back)
     PCR_HD void store_now(uint32_t elem, uint32_t word) {
-        if ((word & kSymCoef) && elem < limit) plane[elem] = (int16_t)(((int32_t)word >> 16) * (1 << Al));
+        if ((word & kSymCoef) && elem < limit) {
+            plane[elem] = (int16_t)(((int32_t)word >> 16) * (1 << Al));
+            if (dense && (elem & 63) == 0) dense[elem >> 6] = plane[elem];
+        }
     }
     // words: the lanes' packed words of the window the indices belong to
     PCR_HD void flush(uint32_t words) {
 #if defined(__HIP_DEVICE_COMPILE__)
         if ((words & kSymCoef) && vidx < limit) plane[vidx] = (int16_t)(((int32_t)words >> 16) * (1 << Al));
+        vidx = ~0u;
+#else
+        (void)words;
+#endif
+    }
+    // the same for scans that also carry DC coefficients (element 0 of a block goes to the compact copy as well)
+    PCR_HD void flush_with_dc(uint32_t words) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        if ((words & kSymCoef) && vidx < limit) {
+            const int16_t val = (int16_t)(((int32_t)words >> 16) * (1 << Al));
+            plane[vidx] = val;
+            if ((vidx & 63) == 0) dense[vidx >> 6] = val;
+        }
         vidx = ~0u;
 #else
         (void)words;
@@ -809,10 +826,10 @@ PCR_HD void sequential_block(WindowReader* wr, IndexSink* sink, const DcTab* dt,
     if (wr->exhausted()) {
         *bad |= wr->overrun_bit();
         const uint32_t words = wr->refill_keep();
-        sink->flush(words);
+        sink->flush_with_dc(words);
     }
     if (at != wr->tab) {                                     // (what the lanes still hold goes out before their words change)
-        sink->flush(wr->vinfo);
+        sink->flush_with_dc(wr->vinfo);
         wr->use_table(at);
     }
     uint32_t info = wr->dc_word(dt);
@@ -829,7 +846,7 @@ PCR_HD void sequential_block(WindowReader* wr, IndexSink* sink, const DcTab* dt,
         if (wr->exhausted()) {
             *bad |= wr->overrun_bit();
             const uint32_t words = wr->refill_keep();
-            sink->flush(words);
+            sink->flush_with_dc(words);
         }
         info = opaque(ac_first_symbols(wr, sink, &kb, base_b, adv_mask, tot_field));
         if (kb >= 64) {
@@ -880,7 +897,7 @@ PCR_HD int decode_sequential(WindowReader* wr, const LaneScan& ls, const SeqTabl
         if (++mx == ls.mcu_w) { mx = 0; my++; }
         m = bad ? ls.mcu1 : m + 1;
     }
-    sink->flush(wr->vinfo);
+    sink->flush_with_dc(wr->vinfo);
     bad |= wr->overrun_bit();
     return bad ? kEFormat : kOk;
 }

@@ -417,7 +417,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_sequential(DevRecord R, const
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.sub_bits, L.nbits, L.pos0, tb.ac[0], true, threadIdx.x, true);
     IndexSink sink;
-    sink.init(L.base, L.base_elems, 0);
+    sink.init(L.base, L.base_elems, 0, R.dc + (uni((uint64_t)R.coef_off[un.img]) >> 6));
     const int rc = decode_sequential(&wr, L.ls, tb, &sink);
     if (rc != kOk) R.status[un.img] = rc;
 }
@@ -781,7 +781,7 @@ PCR_D void pix_geom(const ImgDesc* ip, PixGeom* g) {
 }
 
 // The lane's block: component c, block (brow, bcol) of the component's plane.
-struct PixBlock { uint32_t c, hs, vs, brow, bcol, b, zm; const int16_t* coef; bool covered; };
+struct PixBlock { uint32_t c, hs, vs, brow, bcol, b, zm; const int16_t* coef; const int16_t* dc; bool covered; };   // dc: the block's entry of the compact DC copy
 // j: number of the block inside its MCU (components one after the other, each vs rows of hs blocks); (my, mx): the MCU
 PCR_D void pix_block(const DevRecord& R, const PixGeom& G, uint32_t img, uint32_t j, uint32_t my, uint32_t mx, PixBlock* B, uint32_t* by_out, uint32_t* bx_out) {
     const uint32_t c = j < G.nbl[0] ? 0u : (j < G.nbl[0] + G.nbl[1] ? 1u : 2u);
@@ -792,16 +792,20 @@ PCR_D void pix_block(const DevRecord& R, const PixGeom& G, uint32_t img, uint32_
     B->b = B->brow * pick3(c, G.bw[0], G.bw[1], G.bw[2]) + B->bcol;
     B->zm = pick3(c, G.zmx[0], G.zmx[1], G.zmx[2]);
     B->coef = R.coef + R.coef_off[img] + ((size_t)pick3(c, G.plane0[0], G.plane0[1], G.plane0[2]) + B->b) * 64;
+    B->dc = R.dc + (R.coef_off[img] >> 6) + pick3(c, G.plane0[0], G.plane0[1], G.plane0[2]) + B->b;
     B->covered = B->brow < pick3(c, G.ch[0], G.ch[1], G.ch[2]) && B->bcol < pick3(c, G.cw[0], G.cw[1], G.cw[2]);
     *by_out = by; *bx_out = bx;
 }
-// the block's coefficients as they lie in memory (zig-zag order), chunks beyond zm left zero
+// the block's coefficients as they lie in memory (zig-zag order), chunks beyond zm left zero; the DC coefficient comes
+// from the compact copy (the planes hold it only for the coefficient export)
 PCR_D void pix_load(const PixBlock& B, short8 v[8]) {
+    const int16_t dc = *B.dc;
 #pragma unroll
     for (int ch = 0; ch < 8; ch++) {
         v[ch] = short8{0, 0, 0, 0, 0, 0, 0, 0};
         if ((uint32_t)ch * 8 < B.zm) v[ch] = *reinterpret_cast<const short8*>(B.coef + ch * 8);
     }
+    v[0][0] = dc;
 }
 // DC of the block after the component's DC refinement scans
 template <bool kRefine>
@@ -943,7 +947,7 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
         pix_block(R, G, timg, j, my, mx, &B, &by, &bx);
         if (B.zm <= 1) {
             v[0] = short8{0, 0, 0, 0, 0, 0, 0, 0};
-            v[0][0] = B.coef[0];
+            v[0][0] = *B.dc;
         } else pix_load(B, v);
     }
     // ---- prologue tables (the loads above are under way meanwhile) ----
@@ -1353,7 +1357,7 @@ __global__ void __launch_bounds__(kTailLanes) k_pixel_tail(DevRecord R, const Pi
     short8 v[8];
     if (mine) {
         pix_block(R, G, timg, j, my, m, &B, &by, &bx);
-        if (B.zm <= 1) { v[0] = short8{0, 0, 0, 0, 0, 0, 0, 0}; v[0][0] = B.coef[0]; }
+        if (B.zm <= 1) { v[0] = short8{0, 0, 0, 0, 0, 0, 0, 0}; v[0][0] = *B.dc; }
         else pix_load(B, v);
     }
     if (kRefine) pix_lists(lists, list_idx, timg, nc, rl, tid, kTailLanes);
@@ -1467,19 +1471,6 @@ __global__ void __launch_bounds__(64) k_probe_scalar(uint32_t* out, uint32_t ite
             : "+s"(a), "+s"(b) : : "scc");
     }
     if (threadIdx.x == 0) out[blockIdx.x] = a ^ b;
-}
-
-// zero every coefficient except element 0 of each 64-element block, which is taken from the compact copy of the DC
-// coefficients (one per block, in plane order); n16: 16-byte units, 8 per block
-__global__ void __launch_bounds__(256) k_fill_zero_dc_from(uint4* p, const int16_t* __restrict__ dc, size_t n16) {
-    short_kernel_priority();
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (; i < n16; i += stride) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if ((i & 7) == 0) v.x = (uint32_t)(uint16_t)dc[i >> 3];   // the DC coefficient is the low half of the block's first word
-        p[i] = v;
-    }
 }
 
 __global__ void __launch_bounds__(256) k_fill_zero(uint4* p, size_t n16) {

@@ -38,6 +38,7 @@ struct Plan {                               // launch geometry for one scan grou
     ApplyUnit* d_apply = nullptr; ApplyList* d_apply_lists = nullptr; int32_t* d_list_idx = nullptr; uint32_t n_apply = 0, apply_grid_x = 0;
     bool has_ac = false;                     // some scan <= k is an AC scan (else only element 0 of every block is ever touched)
     bool had_ac = false;                     // ... some scan <= k0 (the fidelity an upgrade starts from)
+    bool dc_complete = true;                 // every component of every image has its first DC scan among the scans <= k
 };
 
 // Device memory of a handle comes out of two arenas (one sized by the image and scan counts, one by the
@@ -127,7 +128,6 @@ struct pcr_record {
     std::map<int, Plan> plans;
     bool timing = false;
     int resident_k = 0;                        // scan group whose planes and masks the last pixel decode left behind (0: none)
-    bool dc_in_planes = false;                 // ... and whether that decode wrote the DC coefficients into the planes (always into the compact copy)
     bool borrowed = false;                  // record bytes belong to the caller (pcr_open_device)
     // stage timing: one list of events per call, the last kTimingRing calls are kept
     std::vector<CallTiming> ring;
@@ -172,10 +172,12 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
     for (uint32_t i = 0; i < n; i++) {
         const uint32_t upto = std::min<uint32_t>(r->img[i].nscans, (uint32_t)k);
         bool refine[kMaxComp] = {false, false, false};
+        uint32_t have_dc = 0;
         for (uint32_t g = 0; g < upto; g++) {
             const size_t ig = (size_t)i * G + g;
             const ScanDesc& sd = r->scan[ig];
             if (sd.Ah > 0) for (int j = 0; j < sd.ns; j++) refine[sd.comp[j]] = true;
+            if (sd.Ss == 0 && sd.Ah == 0) for (int j = 0; j < sd.ns; j++) have_dc |= 1u << sd.comp[j];
             const bool seq = is_sequential_scan(sd);
             if (sd.Ss > 0 || seq) { plan.has_ac = true; if (g < (uint32_t)k0) plan.had_ac = true; }
             if (g < (uint32_t)k0) continue;                    // decoded by an earlier call
@@ -195,6 +197,7 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
             for (uint32_t j = 0; j < cnt; j++)
                 lists[((size_t)(r->level[ig] - 1) * kNumKinds + kind) * kDcShapes + shape].push_back(Item{Unit{i, g, j, r->slot_base[ig]}, sd.data_len / cnt});
         }
+        if (have_dc != (1u << r->img[i].nc) - 1u) plan.dc_complete = false;
         for (int c = 0; c < r->img[i].nc; c++) if (refine[c]) {
             apply.push_back(ApplyUnit{i, (uint32_t)c});
             max_blk = std::max<uint32_t>(max_blk, (uint32_t)r->img[i].bw[c] * r->img[i].bh[c]);
@@ -278,9 +281,7 @@ int add_call_times(const CallTiming& c, double* ms, uint32_t* marks) {
 // refine_in_memory: also run k_apply, which leaves the refined coefficients in the planes (the coefficient
 // export needs that; the pixel kernel replays the refinement itself from the lists of k_apply_prep).
 // k0 > 0: a fidelity upgrade -- groups 1 .. k0 are in the planes and masks already, only k0+1 .. k are decoded.
-// want_planes: the caller's pixel stage reads the DC coefficients from the planes (false: from the compact copy, if the
-// decode holds nothing but first DC scans; the planes then get them when an upgrade needs them)
-int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_in_memory, Plan** plan_out, bool want_planes = true) {
+int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_in_memory, Plan** plan_out) {
     Plan* plan = nullptr;
     int rc = build_plan(r, k0, k, &plan);
     if (rc) return rc;
@@ -295,19 +296,17 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
     if (k > k0) hipLaunchKernelGGL(k_unstuff, dim3(n, k - k0), dim3(256), 0, s, r->d, (uint32_t)k0, (uint32_t)k);
     const size_t coef_bytes = r->coef_off[n] * sizeof(int16_t);
     // AC first scans only write the coefficients they decode: everything else must read as zero.  With DC scans
-    // only, the DC first scan writes element 0 of every block and the pixel kernel reads nothing else, so the
-    // fill is skipped (the coefficient export shows whole planes and always needs it).  The mask planes need no
-    // fill: every entry a kernel reads was written earlier in the same call.
-    // An upgrade keeps the planes; only when it brings the first AC scans must everything but the DCs be cleared.
-    const bool dc_to_planes = want_planes || refine_in_memory || plan->has_ac || plan->n_apply != 0;
-    if (k0 == 0) {
-        if (plan->has_ac || refine_in_memory)
-            hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
-    } else if ((plan->has_ac && !plan->had_ac) || (dc_to_planes && !r->dc_in_planes)) {
-        // (the DC coefficients come from the compact copy, which every DC first scan writes)
-        hipLaunchKernelGGL(k_fill_zero_dc_from, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, (const int16_t*)r->d.dc, coef_bytes / 16);
-    }
-    r->dc_in_planes = dc_to_planes;
+    // only, the pixel kernels read nothing of the planes, so the fill is skipped (the coefficient export shows whole
+    // planes and always needs it).  The mask planes need no fill: every entry a kernel reads was written earlier in
+    // the same call.  An upgrade keeps the planes; when it brings the first AC scans they are cleared first.
+    // The DC first scans write a compact copy of the DC coefficients (one per block), which is what every pixel kernel
+    // reads; the planes get them too only for the coefficient export: 2-byte stores 128 bytes apart were measured to
+    // cost the DC scan a third of its time and to slow the kernels that run beside it.
+    const bool dc_to_planes = refine_in_memory;
+    if (k0 == 0 ? (plan->has_ac || refine_in_memory) : (plan->has_ac && !plan->had_ac))
+        hipLaunchKernelGGL(k_fill_zero, dim3(2048), dim3(256), 0, s, (uint4*)r->d.coef, coef_bytes / 16);
+    if (k0 == 0 && !plan->dc_complete)                       // a component whose DC scan is not among the scans decoded reads as zero
+        hipLaunchKernelGGL(k_fill_zero, dim3(256), dim3(256), 0, s, (uint4*)r->d.dc, (r->coef_off[n] / 64 * sizeof(int16_t) + 15) / 16);
     mark(r, PCR_STAGE_UNSTUFF, s);
     const uint32_t* c32 = reinterpret_cast<const uint32_t*>(r->d.clean);
     const uint64_t* h64 = r->d.masks;
@@ -457,7 +456,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     int rc = arena_reset(&r->big, need);
     if (!rc) rc = arena_alloc(&r->big, &d.clean, padded);
     if (!rc) rc = arena_alloc(&r->big, &d.coef, r->coef_off[n]);
-    if (!rc) rc = arena_alloc(&r->big, &d.dc, r->coef_off[n] / 64 + 1);
+    if (!rc) rc = arena_alloc(&r->big, &d.dc, r->coef_off[n] / 64 + 8);              // (+8: cleared in 16-byte units)
     if (!rc) rc = arena_alloc(&r->big, &d.masks, nm + 2);
     if (!rc) rc = arena_alloc(&r->big, &d.ivl_start, ns);
     uint64_t *d_coef_off = nullptr, *d_out_off = nullptr, *d_mask_off = nullptr; uint32_t *d_sb = nullptr, *d_sc = nullptr;
@@ -554,7 +553,7 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
 // buffer layout.  Everything is enqueued on s, which is synchronised before returning.  On failure the
 // handle holds no record (pcr_close is all that may follow).
 static int bind_device(pcr_record* r, const void* d_bytes, size_t nbytes, hipStream_t s) {
-    r->plans.clear(); r->resident_k = 0; r->dc_in_planes = false; r->hdr = RecordHeader{}; r->n_tiles = 0; r->n_flat_tiles = 0; r->n_flat_rows = 0;
+    r->plans.clear(); r->resident_k = 0; r->hdr = RecordHeader{}; r->n_tiles = 0; r->n_flat_tiles = 0; r->n_flat_rows = 0;
     r->out_off.assign(1, 0); r->coef_off.assign(1, 0);        // until the bind succeeds the handle holds no record
     r->d_dims = nullptr; r->d_ssim_part = nullptr; r->ssim_tiles_max = 0; r->d_planes = nullptr;
     r->d_tail_tiles = nullptr; r->n_tail_tiles = 0; r->d_edge = nullptr; r->d_edge_off = nullptr; r->d_mcu_px_h = nullptr;
@@ -783,7 +782,7 @@ static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t c
     hipStream_t s = (hipStream_t)stream;
     Plan* plan = nullptr;
     r->resident_k = 0;
-    int rc = run_entropy_stages(r, k0, k, s, false, &plan, false);   // (the pixel kernels of a decode without AC scans read the compact DC copy)
+    int rc = run_entropy_stages(r, k0, k, s, false, &plan);
     if (rc) return rc;
     if (plan->n_apply)
         hipLaunchKernelGGL((k_pixel<true, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
