@@ -917,9 +917,13 @@ PCR_HD uint64_t band_mask(int Ss, int Se) { return ((Se >= 63) ? ~0ull : ((1ull 
 //   [kRefPlus]  positions whose correction bit is 1 (their magnitude grows by 2^Al)              } phase 2
 //   [kRefStart] bit offset of the block inside its unit | end-of-band run pending at its start << 32  } written by
 //   [kRefHist]  positions of the band already non-zero when the scan starts                      } phase 1
-// Records of consecutive blocks are contiguous; what the consumers of a finished scan need (the replay of the
-// refinement on the coefficients) is the first three words.
+// A scan keeps one array per word, each with one entry per block of the component's plane (word w of block b lies
+// at w * blocks + b): every kernel that writes a word for consecutive blocks then writes whole lines (records of five
+// words per block, of which a kernel writes two or three, were measured to cost 1.7 - 2.4 times the bytes in partial
+// sectors); what the consumers of a finished scan need (the replay of the refinement on the coefficients) is the first
+// three words.
 constexpr int kRefNz = 0, kRefSign = 1, kRefPlus = 2, kRefStart = 3, kRefHist = 4, kRefWords = 5;
+PCR_HD size_t ref_word(int w, size_t blk, size_t nblk) { return (size_t)w * nblk + blk; }
 
 // History of a refinement scan: the positions of its band that are non-zero when it starts.  What the
 // AC first scans made non-zero is read back from the coefficient plane (one coefficient per lane, a ballot
@@ -940,7 +944,8 @@ struct HistWords {                                            // one block's his
 // a trip to memory per block.  Vector loads return in order and have a counter of their own.
 PCR_HD HistWords hist_fetch(const HistPlanes& hp, uint32_t blk, uint32_t lane) {
     HistWords w;
-    const uint32_t off = (blk * kRefWords + kRefNz) * 8;      // (32-bit offsets: a scan's records stay far below 4 GiB)
+    static_assert(kRefNz == 0, "the words that become history are a scan's first array");
+    const uint32_t off = blk * 8;                             // (32-bit offsets: a plane has far fewer than 2^29 blocks)
 #if defined(__HIP_DEVICE_COMPILE__)
     w.half = 0;
     if (hp.n > 0) {
@@ -1067,7 +1072,7 @@ PCR_HD void set_bit(uint64_t* m, uint32_t n) {
 // The history of the next block is fetched while the current one is decoded.  Conditions are kept
 // as integer arithmetic and single compares: a boolean widened to an integer, or two conditions
 // and-ed together, cost the compiler a detour through the vector unit or through 64-bit lane masks.
-PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes& hp, uint64_t* recs) {
+PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes& hp, uint64_t* recs, size_t nblk) {     // nblk: blocks of the component's plane
     const uint32_t bw = ls.bw[0], mcu_w = ls.mcu_w;
     const uint64_t band = band_mask(ls.Ss, ls.Se);
     const uint32_t top64 = wr->lane == (uint32_t)ls.Se ? kZtLast : 0u;
@@ -1095,7 +1100,7 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
     auto one_block = [&](HistWords& hw, uint32_t& bcur) {
         const uint64_t h = hist_combine(hw) & band;           // already non-zero
         const uint64_t z = h ^ band;                         // still zero
-        uint64_t* rec = recs + (size_t)bcur * kRefWords;
+        uint64_t* rec = recs + bcur;
         left--;
         fblk++; if (++fcol == mcu_w) { fcol = 0; fblk += row_skip; }
         bcur = fblk < last_blk ? fblk : last_blk;
@@ -1156,7 +1161,7 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
             wr->consume(ncorr);
             eobrun--;
         }
-        rec[kRefNz] = newm; rec[kRefStart] = start; rec[kRefHist] = h;   // (phase 2 and the refinement replay work on the same history)
+        rec[ref_word(kRefNz, 0, nblk)] = newm; rec[ref_word(kRefStart, 0, nblk)] = start; rec[ref_word(kRefHist, 0, nblk)] = h;   // (phase 2 and the refinement replay work on the same history)
         bad |= wr->overrun_bit();
         left = bad ? 0 : left;                               // stop at the first damaged block
     };

@@ -451,7 +451,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     uint64_t* mk = R.masks + uni((uint64_t)R.mask_off[ig]);
     WindowReader wr;
     wr.init(L.words, L.byte_off, L.sub_bits, L.nbits, L.pos0, &tab, false, threadIdx.x, false);
-    int rc = skim_ac_refine(&wr, L.ls, hp, mk);
+    int rc = skim_ac_refine(&wr, L.ls, hp, mk, plane);
     if (rc != kOk) R.status[un.img] = rc;
 }
 
@@ -481,13 +481,13 @@ __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const Refine
     const size_t blk = (size_t)(b / cw) * bw + (b % cw);
     const size_t plane = (size_t)bw * img->bh[c];
     uint64_t* mk = R.masks + R.mask_off[ig];
-    uint64_t* rec = mk + blk * kRefWords;
-    const uint64_t h = rec[kRefHist];                        // the history phase 1 worked on
+    uint64_t* rec = mk + blk;                                // (word w of the block: rec[w * plane])
+    const uint64_t h = rec[kRefHist * plane];                // the history phase 1 worked on
     const uint32_t ivl = sd->ri ? b / sd->ri : 0;
     const uint32_t* words = reinterpret_cast<const uint32_t*>(R.clean + clean_base(sd->data_off));
     uint64_t sgn, plus;
-    refine_block(words, R.ivl_start[R.slot_base[ig] + ivl], rec[kRefStart], &tab, h, rec[kRefNz], sd->Ss, sd->Se, &sgn, &plus);
-    rec[kRefSign] = sgn; rec[kRefPlus] = plus;
+    refine_block(words, R.ivl_start[R.slot_base[ig] + ivl], rec[kRefStart * plane], &tab, h, rec[kRefNz * plane], sd->Ss, sd->Se, &sgn, &plus);
+    rec[kRefSign * plane] = sgn; rec[kRefPlus * plane] = plus;
 }
 
 // --------------------------------------------------------------------------------------
@@ -582,8 +582,8 @@ __global__ void __launch_bounds__(256) k_apply(DevRecord R, const ApplyUnit* __r
                 if (k != 0) continue;
                 if (dc_refinement_bit(R, S, row, col, hs, vs, covered)) v |= (int16_t)(1 << S.Al);
             } else if (k != 0 && covered && k >= S.Ss && k <= S.Se) {
-                const uint64_t* rec = R.masks + S.mask_off + (size_t)b * kRefWords;
-                v = refine_apply(v, k, rec[kRefNz], rec[kRefSign], rec[kRefPlus], S.Al);
+                const uint64_t* rec = R.masks + S.mask_off + b;
+                v = refine_apply(v, k, rec[kRefNz * nblk], rec[kRefSign * nblk], rec[kRefPlus * nblk], S.Al);
             }
         }
         if (v != v0) pl[idx] = v;
@@ -761,7 +761,7 @@ PCR_D uint32_t pick3(uint32_t c, uint32_t a0, uint32_t a1, uint32_t a2) { return
 // sample tile (rb) and their row length there (rs), first block of its plane in the image's coefficient buffer.
 struct PixGeom {
     uint32_t nc, W, H, hmax, vmax, mcux, mcuy, bpm;
-    uint32_t hs[kMaxComp], vs[kMaxComp], nbl[kMaxComp], rb[kMaxComp], rs[kMaxComp], plane0[kMaxComp], bw[kMaxComp], zmx[kMaxComp], cw[kMaxComp], ch[kMaxComp];
+    uint32_t hs[kMaxComp], vs[kMaxComp], nbl[kMaxComp], rb[kMaxComp], rs[kMaxComp], plane0[kMaxComp], npl[kMaxComp], bw[kMaxComp], zmx[kMaxComp], cw[kMaxComp], ch[kMaxComp];
     bool flat[kMaxComp];
 };
 PCR_D void pix_geom(const ImgDesc* ip, PixGeom* g) {
@@ -773,7 +773,8 @@ PCR_D void pix_geom(const ImgDesc* ip, PixGeom* g) {
         g->hs[c] = on ? ip->hs[c] : 0; g->vs[c] = on ? ip->vs[c] : 0;
         g->nbl[c] = g->hs[c] * g->vs[c]; g->rb[c] = bpm * 64; g->rs[c] = g->hs[c] * 8; bpm += g->nbl[c];
         g->bw[c] = on ? ip->bw[c] : 0;
-        g->plane0[c] = p0; p0 += on ? g->bw[c] * (uint32_t)ip->bh[c] : 0;
+        g->npl[c] = on ? g->bw[c] * (uint32_t)ip->bh[c] : 0;         // blocks of the component's plane
+        g->plane0[c] = p0; p0 += g->npl[c];
         g->zmx[c] = on ? ip->zmax[c] : 0; g->cw[c] = on ? ip->cw[c] : 0; g->ch[c] = on ? ip->ch[c] : 0;
         g->flat[c] = on && g->zmx[c] <= 1;
     }
@@ -781,7 +782,7 @@ PCR_D void pix_geom(const ImgDesc* ip, PixGeom* g) {
 }
 
 // The lane's block: component c, block (brow, bcol) of the component's plane.
-struct PixBlock { uint32_t c, hs, vs, brow, bcol, b, zm; const int16_t* coef; const int16_t* dc; bool covered; };   // dc: the block's entry of the compact DC copy
+struct PixBlock { uint32_t c, hs, vs, brow, bcol, b, zm, nblk; const int16_t* coef; const int16_t* dc; bool covered; };   // nblk: blocks of the component's plane;   // dc: the block's entry of the compact DC copy
 // j: number of the block inside its MCU (components one after the other, each vs rows of hs blocks); (my, mx): the MCU
 PCR_D void pix_block(const DevRecord& R, const PixGeom& G, uint32_t img, uint32_t j, uint32_t my, uint32_t mx, PixBlock* B, uint32_t* by_out, uint32_t* bx_out) {
     const uint32_t c = j < G.nbl[0] ? 0u : (j < G.nbl[0] + G.nbl[1] ? 1u : 2u);
@@ -791,6 +792,7 @@ PCR_D void pix_block(const DevRecord& R, const PixGeom& G, uint32_t img, uint32_
     B->brow = my * B->vs + by; B->bcol = mx * B->hs + bx;
     B->b = B->brow * pick3(c, G.bw[0], G.bw[1], G.bw[2]) + B->bcol;
     B->zm = pick3(c, G.zmx[0], G.zmx[1], G.zmx[2]);
+    B->nblk = pick3(c, G.npl[0], G.npl[1], G.npl[2]);
     B->coef = R.coef + R.coef_off[img] + ((size_t)pick3(c, G.plane0[0], G.plane0[1], G.plane0[2]) + B->b) * 64;
     B->dc = R.dc + (R.coef_off[img] >> 6) + pick3(c, G.plane0[0], G.plane0[1], G.plane0[2]) + B->b;
     B->covered = B->brow < pick3(c, G.ch[0], G.ch[1], G.ch[2]) && B->bcol < pick3(c, G.cw[0], G.cw[1], G.cw[2]);
@@ -833,8 +835,8 @@ PCR_D void pix_finish(const DevRecord& R, const PixBlock& B, const short8 v[8], 
         } else if (B.covered) {
             // the three words of the block's record: positions that become non-zero, their signs, positions
             // whose magnitude grows (all inside the scan's band)
-            const uint64_t* rec = R.masks + S.mask_off + (size_t)B.b * kRefWords;
-            const uint64_t nzm = rec[kRefNz], sgm = rec[kRefSign], plm = rec[kRefPlus];
+            const uint64_t* rec = R.masks + S.mask_off + B.b;
+            const uint64_t nzm = rec[kRefNz * (size_t)B.nblk], sgm = rec[kRefSign * (size_t)B.nblk], plm = rec[kRefPlus * (size_t)B.nblk];
             // A position either grows (it was non-zero: + 2^Al with its own sign) or is new (it was zero: +- 2^Al by the
             // sign bit) or stays: one step with one sign, taken from the coefficient or from the record.
             const uint64_t anym = nzm | plm, negm = nzm & ~sgm;

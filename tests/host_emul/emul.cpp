@@ -130,14 +130,14 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 } else {
                     HistPlanes hp; hp.n = sd.nhist; hp.coef = cpl[0];
                     for (int q = 0; q < kMaxHist; q++) hp.p[q] = sd.nhist ? masks[sd.hist[q < sd.nhist ? q : 0]].data() : nullptr;
-                    rc = skim_ac_refine(&wr, ls, hp, masks[g].data());
+                    rc = skim_ac_refine(&wr, ls, hp, masks[g].data(), plane);
                     if (rc) return rc;
                     // phase 2: every block of this interval on its own
                     for (uint32_t mm = ls.mcu0; mm < ls.mcu1; mm++) {
                         size_t blk = (size_t)(mm / sd.mcu_w) * img.bw[c0] + (mm % sd.mcu_w);
-                        uint64_t* rec = masks[g].data() + blk * kRefWords;
-                        refine_block(reinterpret_cast<const uint32_t*>(clean.data()), unit_base, rec[kRefStart], &at, rec[kRefHist], rec[kRefNz], sd.Ss, sd.Se,
-                                     &rec[kRefSign], &rec[kRefPlus]);
+                        uint64_t* rec = masks[g].data() + blk;
+                        refine_block(reinterpret_cast<const uint32_t*>(clean.data()), unit_base, rec[kRefStart * plane], &at, rec[kRefHist * plane], rec[kRefNz * plane], sd.Ss, sd.Se,
+                                     &rec[kRefSign * plane], &rec[kRefPlus * plane]);
                     }
                 }
             }
@@ -167,8 +167,8 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                     if (dc_refine_bit(reinterpret_cast<const uint32_t*>(cleans[g].data()), ivls[g][ivl], bit)) v |= (int16_t)(1 << sd.Al);
                 } else if (kk != 0 && covered && sd.comp[0] == c && sd.Ah != 0 && kk >= sd.Ss && kk <= sd.Se) {
                     const uint64_t* mk = masks[g].data();
-                    const uint64_t* rec = mk + blk * kRefWords;
-                    v = refine_apply(v, kk, rec[kRefNz], rec[kRefSign], rec[kRefPlus], sd.Al);
+                    const uint64_t* rec = mk + blk;
+                    v = refine_apply(v, kk, rec[kRefNz * plane], rec[kRefSign * plane], rec[kRefPlus * plane], sd.Al);
                 }
             }
             *cp = v;
