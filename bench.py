@@ -49,11 +49,11 @@ TABLE_SCAN_GROUPS = (1, 2, 5, 10)     # the scan groups the paper tabulates (Tab
 # the counters were taken: an entry is removed (-> null in the output) whenever its kernel changes.
 PMC = {
     # mean of the two launches of one decode (profiles/decode_kernels_imagenet_like_k10_counters.md)
-    "ac_refine": {"salu": 731.1e6, "valu": 239.0e6, "fetch_bytes": 585.8e6, "write_bytes": 132.0e6,
+    "ac_refine": {"salu": 743.0e6, "valu": 235.8e6, "fetch_bytes": 544.0e6, "write_bytes": 81.3e6,
                   "source": "profiles/decode_kernels_imagenet_like_k10_counters.md (SQ_INSTS_SALU, SQ_INSTS_VALU, FETCH_SIZE x 2.0, WRITE_SIZE x 1.0)"},
 }
 # all kernels of that decode, same counter run
-RECORD0_INSTS = {"scalar": 2740.2e6, "vector": 1625.2e6}
+RECORD0_INSTS = {"scalar": 2790.0e6, "vector": 1635.5e6}
 
 # The serial chain of one Huffman-coded symbol in this design, at the very least: fetch the packed word of the current
 # bit offset, test it, take its length, add it to the position, apply the position update, test for the end of the
