@@ -345,6 +345,27 @@ int pcr_record_write_indexed(const void* const* files, const size_t* sizes, cons
 int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
                               void* out, size_t capacity, uint64_t* written);
 
+/* Symbol statistics of the transcode, on the device (Section 5, "Encoding": the transcode to progressive files is the
+ * step that makes a dataset into records; an optimised Huffman table needs the number of times each symbol occurs
+ * in its scan).
+ * pcr_symbol_histograms: decodes every available scan group of the record to coefficients on the device (as
+ *   pcr_decode_coefficients does; a following pcr_upgrade_batch has nothing to start from) and counts, for every image,
+ *   the Huffman symbols of every scan of the file pcr_transcode_progressive would write from those coefficients
+ *   (restart_interval as there).  d_hist: device, n x PCR_HIST_ENTRIES counters, [image][scan of the script][table
+ *   slot][symbol] with 10 scans (a gray image uses the first 6), two table slots (slot 1: the second and third
+ *   component of the interleaved DC scan) and 256 symbols; written, not added to.  Asynchronous on hip_stream.
+ * pcr_transcode_progressive_counted: pcr_transcode_progressive with the counts of the image given (host,
+ *   PCR_HIST_ENTRIES counters, e.g. copied back from pcr_symbol_histograms) instead of counted on the host; the same
+ *   bytes.  PCR_E_FORMAT if the coefficients hold a symbol the counts do not.
+ * pcr_transcode_symbol_counts: the counts pcr_transcode_progressive makes for itself (host), for comparison. */
+#define PCR_HIST_SCANS 10
+#define PCR_HIST_ENTRIES (PCR_HIST_SCANS * 2 * 256)
+int pcr_symbol_histograms(pcr_record* rec, uint32_t restart_interval, uint32_t* d_hist, void* hip_stream);
+int pcr_transcode_progressive_counted(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
+                                      const uint32_t* counts, void* out, size_t capacity, uint64_t* written);
+int pcr_transcode_symbol_counts(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
+                                uint32_t* counts);
+
 /* Stage timing with HIP events recorded on the call's own stream (off by default; switching it on
  * starts a new history).  A stage is one kernel or a short run of kernels:
  *   INDEX_PARSE    k_index + k_parse                 UNSTUFF        k_unstuff + zero fills

@@ -55,6 +55,10 @@ SYMBOLS = {
                                                 ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint64)]),
     "pcr_transcode_progressive": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.c_size_t, ctypes.c_uint32, _vp, ctypes.c_size_t,
                                                  ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_symbol_histograms": (ctypes.c_int, [_vp, ctypes.c_uint32, _vp, _vp]),
+    "pcr_transcode_progressive_counted": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.c_size_t, ctypes.c_uint32, _vp, _vp, ctypes.c_size_t,
+                                                         ctypes.POINTER(ctypes.c_uint64)]),
+    "pcr_transcode_symbol_counts": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, ctypes.c_size_t, ctypes.c_uint32, _vp]),
     "pcr_select_scan_group": (ctypes.c_int, [_vp, ctypes.c_float, _vp, _vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_float),
                                              ctypes.POINTER(ctypes.c_int), _vp]),
     "pcr_prefix_length": (ctypes.c_int, [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
@@ -227,6 +231,16 @@ class Record:
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_decode_batch_triangle(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
                "pcr_decode_batch_triangle")
+        return out
+
+    def symbol_histograms(self, restart_interval=0, out=None, stream=None):
+        """uint32 CUDA tensor [n, 10, 2, 256]: per image, scan of the transcoder's script and table slot, how often each
+        Huffman symbol occurs in the progressive file transcode_progressive would write (counted on the device)."""
+        import torch
+        if out is None:
+            out = torch.empty((self.n, HIST_SCANS, 2, 256), dtype=torch.int32, device="cuda:%d" % self.device)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_symbol_histograms(self._h, restart_interval, out.data_ptr(), s), "pcr_symbol_histograms")
         return out
 
     def upgrade_batch(self, k, out=None, status=None, stream=None):
@@ -403,33 +417,59 @@ def record_write_indexed(files, labels=None, entry_interval=128):
     return out[:int(written.value)].tobytes()
 
 
-def transcode_progressive(src_jpeg, coef, restart_interval=0):
+HIST_SCANS = 10
+HIST_ENTRIES = HIST_SCANS * 2 * 256
+
+
+def transcode_progressive(src_jpeg, coef, restart_interval=0, counts=None):
     """Progressive file (bytes) holding the quantised coefficients `coef` (int16 numpy array in the layout of
-    coef_layout() for this one image) under the frame header and quantisation tables of src_jpeg."""
+    coef_layout() for this one image) under the frame header and quantisation tables of src_jpeg.  counts: the image's
+    symbol counts (uint32 [10, 2, 256], e.g. a row of Record.symbol_histograms()) to build the Huffman tables from."""
     src = np.frombuffer(src_jpeg, np.uint8)
     coef = np.ascontiguousarray(coef, np.int16)
     out = np.empty(src.size + src.size // 2 + 4096, np.uint8)
     written = ctypes.c_uint64(0)
-    rc = lib().pcr_transcode_progressive(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, restart_interval,
-                                         out.ctypes.data_as(_vp), out.size, ctypes.byref(written))
+    if counts is not None:
+        counts = np.ascontiguousarray(counts, np.uint32)
+        assert counts.size == HIST_ENTRIES
+
+    def call(buf):
+        if counts is None:
+            return lib().pcr_transcode_progressive(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, restart_interval,
+                                                   buf.ctypes.data_as(_vp), buf.size, ctypes.byref(written))
+        return lib().pcr_transcode_progressive_counted(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, restart_interval,
+                                                       counts.ctypes.data_as(_vp), buf.ctypes.data_as(_vp), buf.size, ctypes.byref(written))
+    rc = call(out)
     if rc == E_RANGE and written.value > out.size:
         out = np.empty(int(written.value), np.uint8)
-        rc = lib().pcr_transcode_progressive(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, restart_interval,
-                                             out.ctypes.data_as(_vp), out.size, ctypes.byref(written))
+        rc = call(out)
     _check(rc, "pcr_transcode_progressive")
     return out[:int(written.value)].tobytes()
 
 
-def transcode_files(files, device=0, threads=None, restart_interval=0):
+def transcode_symbol_counts(src_jpeg, coef, restart_interval=0):
+    """uint32 [10, 2, 256]: the symbol counts transcode_progressive makes for itself on the host."""
+    src = np.frombuffer(src_jpeg, np.uint8)
+    coef = np.ascontiguousarray(coef, np.int16)
+    counts = np.zeros(HIST_ENTRIES, np.uint32)
+    _check(lib().pcr_transcode_symbol_counts(src.ctypes.data_as(_vp), src.size, coef.ctypes.data_as(_vp), coef.size, restart_interval,
+                                             counts.ctypes.data_as(_vp)), "pcr_transcode_symbol_counts")
+    return counts.reshape(HIST_SCANS, 2, 256)
+
+
+def transcode_files(files, device=0, threads=None, restart_interval=0, device_counts=True):
     """The paper's encoding step for a list of JPEG files (baseline or progressive): their coefficients are decoded
-    on the device, re-coded as progressive files on the host.  Returns the progressive files; record_write() groups them."""
+    and the symbols of the new scans counted on the device, the progressive files written on the host.  Returns the
+    progressive files; record_write() groups them."""
     rec = record_write(files)
     with pcr_open(rec, device) as r:
         lay = r.coef_layout()
+        hist = r.symbol_histograms(restart_interval).cpu().numpy() if device_counts else None
         coef = r.decode_coefficients(r.G).cpu().numpy()
     from concurrent.futures import ThreadPoolExecutor                 # (the C call releases the interpreter lock)
     with ThreadPoolExecutor(threads or min(16, os.cpu_count() or 1)) as ex:
-        return list(ex.map(lambda i: transcode_progressive(files[i], coef[int(lay[i]):int(lay[i + 1])], restart_interval), range(len(files))))
+        return list(ex.map(lambda i: transcode_progressive(files[i], coef[int(lay[i]):int(lay[i + 1])], restart_interval,
+                                                           None if hist is None else hist[i]), range(len(files))))
 
 
 class Loader:

@@ -15,6 +15,7 @@
 
 #include "pcr_format.h"
 #include "pcr_entropy.h"
+#include "pcr_hist.h"
 
 namespace pcr {
 namespace enc {
@@ -572,28 +573,12 @@ inline void write_dht(std::vector<uint8_t>* o, int cls, int id, const HuffSpec& 
     for (int k = 0; k < H.nsym; k++) o->push_back(H.symbols[k]);
 }
 
-// The scan scripts stock encoders use by default: DC with one bit held back, the low luma band, chroma, the
-// rest of luma, then the held-back bits plane by plane.
+// The script of the files written here (pcr_hist.h: the device counts the symbols of the same scans).
 inline std::vector<ScanSpec> default_script(int nc) {
     std::vector<ScanSpec> s;
-    if (nc == 3) {
-        s.push_back(ScanSpec{3, {0, 1, 2}, 0, 0, 0, 1});
-        s.push_back(ScanSpec{1, {0, 0, 0}, 1, 5, 0, 2});
-        s.push_back(ScanSpec{1, {2, 0, 0}, 1, 63, 0, 1});
-        s.push_back(ScanSpec{1, {1, 0, 0}, 1, 63, 0, 1});
-        s.push_back(ScanSpec{1, {0, 0, 0}, 6, 63, 0, 2});
-        s.push_back(ScanSpec{1, {0, 0, 0}, 1, 63, 2, 1});
-        s.push_back(ScanSpec{3, {0, 1, 2}, 0, 0, 1, 0});
-        s.push_back(ScanSpec{1, {2, 0, 0}, 1, 63, 1, 0});
-        s.push_back(ScanSpec{1, {1, 0, 0}, 1, 63, 1, 0});
-        s.push_back(ScanSpec{1, {0, 0, 0}, 1, 63, 1, 0});
-    } else {
-        s.push_back(ScanSpec{1, {0, 0, 0}, 0, 0, 0, 1});
-        s.push_back(ScanSpec{1, {0, 0, 0}, 1, 5, 0, 2});
-        s.push_back(ScanSpec{1, {0, 0, 0}, 6, 63, 0, 2});
-        s.push_back(ScanSpec{1, {0, 0, 0}, 1, 63, 2, 1});
-        s.push_back(ScanSpec{1, {0, 0, 0}, 0, 0, 1, 0});
-        s.push_back(ScanSpec{1, {0, 0, 0}, 1, 63, 1, 0});
+    for (int i = 0; i < script_scans(nc); i++) {
+        const ScriptScan t = script_scan(nc, i);
+        s.push_back(ScanSpec{t.ns, {t.comp[0], t.comp[1], t.comp[2]}, t.Ss, t.Se, t.Ah, t.Al});
     }
     return s;
 }
@@ -602,8 +587,14 @@ inline std::vector<ScanSpec> default_script(int nc) {
 // quantised coefficients, component planes one after the other, each [bh][bw][64] in natural order over the
 // MCU-padded block grid.  Appends the progressive file to *out.
 // restart_interval: MCUs of each scan between restart markers (0: none; a scan of one component counts its blocks).
+// counts (optional): the symbol counts of the scans, [scan][table slot][symbol] (kHistPerImage entries, as k_symbol_hist
+// writes them), used for the Huffman tables instead of counting the tokens here.  counts_out (optional): receives the
+// counts of the tokens; with it and out == nullptr nothing is written.
 inline int transcode_progressive(const uint8_t* src, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
-                                 std::vector<uint8_t>* out) {
+                                 std::vector<uint8_t>* out, const uint32_t* counts = nullptr, uint32_t* counts_out = nullptr) {
+    std::vector<uint8_t> scratch;
+    if (!out) out = &scratch;
+    if (counts_out) memset(counts_out, 0, sizeof(uint32_t) * kHistPerImage);
     if (src_bytes >= (1ull << 32)) return kEUnsupported;
     if (restart_interval > 65535) return kERange;
     ParseState st;
@@ -645,13 +636,23 @@ inline int transcode_progressive(const uint8_t* src, size_t src_bytes, const int
         o.push_back(0xFF); o.push_back(0xDD);
         put_be16(&o, 4); put_be16(&o, restart_interval);
     }
+    int scan_index = -1;
     for (const ScanSpec& S : default_script(img.nc)) {
+        scan_index++;
         ScanCoder coder(F, S, restart_interval);
         coder.run();
         uint32_t freq[2][256];
         memset(freq, 0, sizeof freq);
         bool used[2] = {false, false};
-        for (const Token& t : coder.tokens) if (t.slot < kRawBits) { freq[t.slot][t.sym]++; used[t.slot] = true; }
+        if (counts) {
+            memcpy(freq, counts + (size_t)scan_index * kHistPerScan, sizeof freq);
+            for (int s2 = 0; s2 < 2; s2++) for (int y = 0; y < 256; y++) if (freq[s2][y]) used[s2] = true;
+            // (a token whose symbol the counts do not hold would get no code: refuse counts that do not fit the coefficients)
+            for (const Token& t : coder.tokens) if (t.slot < kRawBits && freq[t.slot][t.sym] == 0) return kEFormat;
+        } else {
+            for (const Token& t : coder.tokens) if (t.slot < kRawBits) { freq[t.slot][t.sym]++; used[t.slot] = true; }
+        }
+        if (counts_out) memcpy(counts_out + (size_t)scan_index * kHistPerScan, freq, sizeof freq);
         HuffSpec H[2];
         const int cls = S.Ss == 0 ? 0 : 1;
         for (int s = 0; s < 2; s++) if (used[s]) { build_table(freq[s], &H[s]); write_dht(&o, cls, s, H[s]); }

@@ -17,6 +17,7 @@
 
 #include "../../include/pcr.h"
 #include "pcr_kernels.h"
+#include "pcr_hist.h"
 #include "pcr_similarity.h"
 #include "pcr_encode.h"
 
@@ -1075,6 +1076,45 @@ int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int1
     *written = bytes.size();
     if (!out || capacity < bytes.size()) return PCR_E_RANGE;
     memcpy(out, bytes.data(), bytes.size());
+    return PCR_OK;
+}
+
+int pcr_transcode_progressive_counted(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
+                                      const uint32_t* counts, void* out, size_t capacity, uint64_t* written) {
+    if (!src_jpeg || !coef || !written || !counts) return PCR_E_ARG;
+    std::vector<uint8_t> bytes;
+    bytes.reserve(src_bytes + src_bytes / 4 + 1024);
+    const int rc = enc::transcode_progressive((const uint8_t*)src_jpeg, src_bytes, coef, coef_count, restart_interval, &bytes, counts);
+    if (rc) return rc;
+    *written = bytes.size();
+    if (!out || capacity < bytes.size()) return PCR_E_RANGE;
+    memcpy(out, bytes.data(), bytes.size());
+    return PCR_OK;
+}
+
+int pcr_transcode_symbol_counts(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
+                                uint32_t* counts) {
+    if (!src_jpeg || !coef || !counts) return PCR_E_ARG;
+    return enc::transcode_progressive((const uint8_t*)src_jpeg, src_bytes, coef, coef_count, restart_interval, nullptr, nullptr, counts);
+}
+
+int pcr_symbol_histograms(pcr_record* r, uint32_t restart_interval, uint32_t* d_hist, void* stream) {
+    if (!r || !d_hist) return PCR_E_ARG;
+    if (restart_interval > 65535) return PCR_E_RANGE;
+    const int k = (int)r->hdr.k_avail;
+    int rc = check_scan_group(r, k);
+    if (rc) return rc;
+    HIP_TRY(hipSetDevice(r->device));
+    hipStream_t s = (hipStream_t)stream;
+    Plan* plan = nullptr;
+    r->resident_k = 0;                                       // the planes are refined in place, as for the coefficient export
+    rc = run_entropy_stages(r, 0, k, s, true, &plan);
+    if (rc) return rc;
+    call_end(r);
+    static_assert(PCR_HIST_ENTRIES == kHistPerImage, "header and kernel agree on the layout of the counts");
+    hipLaunchKernelGGL(k_symbol_hist, dim3(r->hdr.n, kScriptScansMax), dim3(64), 0, s, (const ImgDesc*)r->d.img, (const int16_t*)r->d.coef, r->d.coef_off,
+                       restart_interval, d_hist);
+    if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
     return PCR_OK;
 }
 

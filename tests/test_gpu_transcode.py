@@ -45,3 +45,36 @@ def test_restart_intervals_written_by_the_transcoder_decode_the_same():
         with pkg.pcr_open(rec_p, 0) as rp:
             assert np.array_equal(rp.decode_batch(10).cpu().numpy(), want)
         _check_record(rec_p, (1, 6, 10), check_bytes=False)
+
+
+def test_symbol_histograms_on_the_device(rgb_small, gray64, extreme_record):
+    """pcr_symbol_histograms against the host coder's own counts, symbol by symbol: 4:2:0 with odd sizes, gray, 4:4:4 and
+    4:2:2, baseline sources, the hand-made extreme planes (dense blocks, zero runs inside refinement scans, end-of-band
+    runs over hundreds of blocks), a run of more than 32767 empty blocks, with and without restart intervals; and the
+    files written from the device's counts are the files written without them."""
+    import pcrgen
+    import torch
+    assert torch.cuda.is_available()
+    pix = np.full((1456, 1464, 1), 97, np.uint8)
+    pix[:8, :8, 0] = np.arange(64, dtype=np.uint8).reshape(8, 8) * 3
+    long_run = pcrgen.encode_pixels(pix, 1, 1, 90, "sequential")
+    shapes = [(33, 17), (64, 64), (100, 9)]
+    sets = [list(rgb_small[1][:10]), None, list(extreme_record[1]), _sequential_files()[:6], [long_run],
+            [pcrgen.make_jpeg(700 + i, 1, w, h, 3, 6.0, hs, vs, 90) for i, (w, h) in enumerate(shapes) for (hs, vs) in ((1, 1), (2, 1))]]
+    for si, files in enumerate(sets):
+        rec = gray64[0] if files is None else pkg.record_write(files)
+        with pkg.pcr_open(rec, 0) as r:
+            if files is None:
+                files = [r.reassemble(i, r.G) for i in range(r.n)]
+            lay = r.coef_layout()
+            coef = r.decode_coefficients(r.G).cpu().numpy()
+            for ri in ((0, 7) if si != 4 else (0,)):
+                got = r.symbol_histograms(ri).cpu().numpy().astype(np.uint32)
+                assert got.shape == (r.n, 10, 2, 256)
+                for i in range(r.n):
+                    want = pkg.transcode_symbol_counts(files[i], coef[int(lay[i]):int(lay[i + 1])], ri)
+                    assert np.array_equal(got[i], want), (si, i, ri, np.argwhere(got[i] != want)[:5])
+            assert r.resident_scan_group() == 0
+    files = _sequential_files()[:5] + list(rgb_small[1][:3])
+    for ri in (0, 9):
+        assert pkg.transcode_files(files, restart_interval=ri) == pkg.transcode_files(files, restart_interval=ri, device_counts=False)

@@ -149,6 +149,34 @@ def test_transcode_end_of_band_run_longer_than_one_symbol_can_say():
     _check_transcode(f)
 
 
+def test_symbol_counts_against_an_independent_encoder():
+    """The coder's symbol counts per scan against the generator's encoder, which is other code: a file the generator
+    wrote with the same scan script holds, scan by scan, as many Huffman-coded symbols as the transcoder counts for its
+    coefficients.  Counts handed in give the same file as counts
+    made on the spot; counts that miss a symbol are refused."""
+    for j, (seed, w, h, c, hs, vs, ri) in enumerate([(31, 77, 53, 3, 2, 2, 0), (32, 129, 65, 3, 2, 1, 0), (33, 64, 40, 3, 1, 1, 5), (34, 90, 70, 1, 1, 1, 0),
+                                                   (35, 200, 120, 3, 2, 2, 7)]):
+        f = pcrgen.make_jpeg(seed, 1 + j % 2, w, h, c, 6.0, hs, vs, 90, restart=ri)
+        theirs = pcrgen.symbol_counts(seed, 1 + j % 2, w, h, c, 6.0, hs, vs, 90, restart=ri)
+        (c0, _, info), G = _decode_file(f)
+        counts = pkg.transcode_symbol_counts(f, c0, ri)
+        assert counts.shape == (10, 2, 256)
+        ours = counts.reshape(10, -1).sum(axis=1)
+        assert np.array_equal(ours[:G], np.asarray(theirs[:G], dtype=ours.dtype)), (j, ours, theirs)
+        assert ours[G:].sum() == 0
+        # DC scans: one symbol per block of the scan; the DC refinement scan has none
+        dc_ref = 6 if c == 3 else 4
+        assert ours[dc_ref] == 0
+        plain = pkg.transcode_progressive(f, c0, ri)
+        assert pkg.transcode_progressive(f, c0, ri, counts=counts) == plain
+        bad = counts.copy()
+        s_used = int(np.flatnonzero(bad[1, 0])[0])
+        bad[1, 0, s_used] = 0                                      # a symbol the scan does use
+        with pytest.raises(pkg.PcrError) as e:
+            pkg.transcode_progressive(f, c0, ri, counts=bad)
+        assert e.value.code == pkg.E_FORMAT
+
+
 def test_transcode_argument_errors():
     f = _files()[0]
     (c0, _, _), _ = _decode_file(f)
