@@ -45,8 +45,9 @@ struct DevRecord {
     const uint32_t* slot_cnt;  // [n][G] intervals of the scan
     uint32_t* ivl_start;       // per scan: intervals+1 offsets into the clean segment
     int16_t* coef;
-    int16_t* dc;               // the DC coefficients once more, one per block in the order of the blocks of `coef` (written by the DC first
-                               // scans of progressive files): what a decode of DC scans alone reads instead of every 64th element
+    int16_t* dc;               // the DC coefficients, one per block in the order of the blocks of `coef` (written by the DC first scans and
+                               // by sequential scans): what the pixel kernels read; element 0 of a block in `coef` holds it only for the
+                               // coefficient export
     uint64_t* masks;
     int32_t* status;           // [n]
     AcTab* tabs;               // Huffman tables of the AC scans: those of the refinement scans are written by phase 1 for phase 2;
