@@ -106,15 +106,29 @@ __global__ void __launch_bounds__(64) k_parse(DevRecord R, uint32_t kmax, uint32
 // --------------------------------------------------------------------------------------
 // k_unstuff: per (image, scan) remove stuffed zeros, fill bytes and restart markers from the
 // entropy-coded segment, stop at the first other marker, note where each restart interval
-// begins.  256 lanes x 8 bytes per step, one exclusive scan per step.
+// begins.  256 lanes x 8 bytes per step.  A lane classifies its eight bytes at once (one flag bit per
+// byte in a 64-bit word: equal to FF, to 00, a restart marker's second byte, and the same of the byte
+// that follows), squeezes out the few it drops and puts the rest, byte by byte, at their place in a ring
+// in LDS; the workgroup then stores the words the step has completed, already in the big-endian order
+// the decoders read (one 4-byte store per lane instead of eight single bytes).
 // --------------------------------------------------------------------------------------
 constexpr int kUnstuffPer = 8;
+constexpr uint32_t kUnstuffRing = 4096;                    // bytes; a step adds at most 2048 to fewer than 4 left over
+
+// 0x80 in every byte of the result whose byte in x is zero (exact, no carries between bytes)
+PCR_D uint64_t zero_bytes(uint64_t x) {
+    const uint64_t m = 0x7F7F7F7F7F7F7F7Full;
+    return ~(((x & m) + m) | x | m);
+}
+// the flags (0x80 per byte) of the bytes below byte n (n >= 8: all)
+PCR_D uint64_t flags_below(uint32_t n) { return n >= 8 ? 0x8080808080808080ull : ((1ull << (8 * n)) - 1) & 0x8080808080808080ull; }
 
 // grid: (images, scan groups kfrom .. kmax-1)
 __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kfrom, uint32_t kmax) {
     short_kernel_priority();
     __shared__ uint32_t part[4];
     __shared__ uint32_t s_stop;
+    __shared__ __attribute__((aligned(16))) uint32_t ring[kUnstuffRing / 4];
     uint32_t i = blockIdx.x, g = kfrom + blockIdx.y;
     if (g >= kmax) return;
     const ImgDesc& img = R.img[i];
@@ -124,44 +138,47 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kfrom, ui
     uint8_t* dst = R.clean + clean_base(sd.data_off);     // stored as big-endian 32-bit words: byte o goes to o ^ 3
     const uint32_t L = sd.data_len;
     const uint32_t sb = R.slot_base[(size_t)i * R.G + g], sc = R.slot_cnt[(size_t)i * R.G + g];
+    uint8_t* ringb = reinterpret_cast<uint8_t*>(ring);
     uint32_t out_total = 0, rst_total = 0;
     if (threadIdx.x == 0) { s_stop = 0xFFFFFFFFu; R.ivl_start[sb] = 0; }
     __syncthreads();
     for (uint32_t base = 0; base < L; base += 256 * kUnstuffPer) {
-        uint32_t p0 = base + threadIdx.x * kUnstuffPer;
-        uint8_t b[kUnstuffPer + 2];                    // prev, 8 bytes, next
-        for (int j = 0; j < kUnstuffPer + 2; j++) {
-            uint32_t q = p0 + j;                       // index of b[j] is q - 1
-            b[j] = (q >= 1 && q - 1 < L) ? src[q - 1] : 0;
-        }
-        if (p0 == 0) b[0] = 0;
-        uint32_t keep = 0, rst = 0, stop = 0xFFFFFFFFu;
-        for (int j = 0; j < kUnstuffPer; j++) {
-            uint32_t q = p0 + j;
-            if (q >= L) break;
-            uint8_t prev = b[j], cur = b[j + 1], next = b[j + 2];
-            bool last = (q + 1 >= L);
-            if (cur == 0xFF) {
-                bool is_rst = !last && next >= 0xD0 && next <= 0xD7;
-                bool is_data = !last && next == 0x00;
-                bool is_fill = !last && next == 0xFF;
-                if (is_rst) rst |= 1u << j;
-                else if (is_data) keep |= 1u << j;
-                else if (!is_fill) { stop = q; break; }   // any other marker ends the segment
-            } else if (prev == 0xFF && (cur == 0x00 || (cur >= 0xD0 && cur <= 0xD7))) {
-                // stuffed zero or second byte of a restart marker: dropped
-            } else keep |= 1u << j;
-        }
-        if (stop != 0xFFFFFFFFu) atomicMin(&s_stop, stop);
+        const uint32_t p0 = base + threadIdx.x * kUnstuffPer;
+        const uint32_t nvalid = p0 >= L ? 0u : (L - p0 < 8 ? L - p0 : 8u);
+        uint64_t w = 0;                                  // byte j of the lane: bits 8j .. 8j+7
+        if (nvalid == 8) {
+            struct __attribute__((packed, aligned(1))) Two { uint32_t a, b; };
+            const Two t = *reinterpret_cast<const Two*>(src + p0);
+            w = (uint64_t)t.a | ((uint64_t)t.b << 32);
+        } else for (uint32_t j = 0; j < nvalid; j++) w |= (uint64_t)src[p0 + j] << (8 * j);
+        const uint32_t prevb = (p0 > 0 && p0 <= L) ? src[p0 - 1] : 0u;
+        const bool has_next = p0 + 8 < L;
+        const uint32_t nextb = has_next ? src[p0 + 8] : 0u;
+        const uint64_t top = 0x8000000000000000ull, all = 0x8080808080808080ull;
+        const uint64_t valid = flags_below(nvalid);
+        const uint64_t ff = zero_bytes(~w), z0 = zero_bytes(w), rs = zero_bytes((w & 0xF8F8F8F8F8F8F8F8ull) ^ 0xD0D0D0D0D0D0D0D0ull);
+        // the same of the byte that follows (none follows the segment's last byte) and of the byte before
+        const uint64_t nvalid_next = (valid >> 8) | (has_next ? top : 0);
+        const uint64_t nff = ((ff >> 8) | (nextb == 0xFF ? top : 0)) & nvalid_next;
+        const uint64_t nz0 = ((z0 >> 8) | (nextb == 0x00 ? top : 0)) & nvalid_next;
+        const uint64_t nrs = ((rs >> 8) | ((nextb & 0xF8) == 0xD0 ? top : 0)) & nvalid_next;
+        const uint64_t pff = (ff << 8) | (prevb == 0xFF ? 0x80ull : 0);
+        // FF: kept if a zero follows (a data byte), a restart marker if D0..D7 follows, dropped if another FF follows (fill),
+        // else the marker that ends the segment.  Others: dropped if they are the second byte of FF 00 or of a restart marker.
+        uint64_t keep = valid & ((all & ~ff & ~(pff & (z0 | rs))) | (ff & nz0));
+        uint64_t rst = valid & ff & nrs;
+        const uint64_t stopf = valid & ff & ~nrs & ~nz0 & ~nff;
+        if (stopf) atomicMin(&s_stop, p0 + ((uint32_t)__builtin_ctzll(stopf) >> 3));
         __syncthreads();
-        uint32_t stop_all = s_stop;
-        // drop what lies at or after the terminating marker
-        if (stop_all != 0xFFFFFFFFu) {
-            for (int j = 0; j < kUnstuffPer; j++) if (p0 + j >= stop_all) { keep &= ~(1u << j); rst &= ~(1u << j); }
+        const uint32_t stop_all = s_stop;
+        if (stop_all != 0xFFFFFFFFu) {                     // drop what lies at or after the terminating marker
+            const uint64_t before = flags_below(stop_all > p0 ? stop_all - p0 : 0u);
+            keep &= before; rst &= before;
         }
         // prefix sums of (bytes kept | restart markers << 16) over the 256 lanes: inside each wavefront by lane
         // shuffles, then the four wavefront totals through LDS
-        const uint32_t mine = (uint32_t)__builtin_popcount(keep) | ((uint32_t)__builtin_popcount(rst) << 16);
+        const uint32_t nkeep = (uint32_t)__builtin_popcountll(keep);
+        const uint32_t mine = nkeep | ((uint32_t)__builtin_popcountll(rst) << 16);
         const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         uint32_t incl = mine;
 #pragma unroll
@@ -174,15 +191,37 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kfrom, ui
         const uint32_t w0 = part[0], w1 = part[1], w2 = part[2], w3 = part[3];
         const uint32_t before = (wave > 0 ? w0 : 0) + (wave > 1 ? w1 : 0) + (wave > 2 ? w2 : 0);
         const uint32_t excl = before + incl - mine;
-        uint32_t o = out_total + (excl & 0xFFFF), r = rst_total + (excl >> 16);
-        for (int j = 0; j < kUnstuffPer; j++) {
-            if (keep & (1u << j)) { dst[o ^ 3u] = b[j + 1]; o++; }
-            if (rst & (1u << j)) { r++; if (r < sc) R.ivl_start[sb + r] = o; }
+        const uint32_t o = out_total + (excl & 0xFFFF);
+        if (rst) {                                         // (rare) where the next interval begins: behind the bytes kept ahead of the marker
+            uint32_t r = rst_total + (excl >> 16);
+            for (uint64_t m = rst; m; m &= m - 1) {
+                const uint32_t j = (uint32_t)__builtin_ctzll(m) >> 3;
+                r++;
+                if (r < sc) R.ivl_start[sb + r] = o + (uint32_t)__builtin_popcountll(keep & flags_below(j));
+            }
         }
+        // squeeze the dropped bytes out (few: one step of the loop per dropped byte), then the kept ones into the ring
+        uint64_t kw = w;
+        for (uint64_t drop = valid & ~keep; drop; ) {
+            const uint32_t j = 63u - (uint32_t)__builtin_clzll(drop);      // highest first, so that the positions below stay put
+            drop &= ~(1ull << j);
+            const uint32_t sh = (j >> 3) * 8;                               // first bit of the byte
+            const uint64_t low = sh ? (kw & ((1ull << sh) - 1)) : 0;
+            kw = low | (sh < 56 ? (kw >> (sh + 8)) << sh : 0);
+        }
+        for (uint32_t j = 0; j < nkeep; j++) ringb[(o + j) & (kUnstuffRing - 1)] = (uint8_t)(kw >> (8 * j));
         const uint32_t tot = w0 + w1 + w2 + w3;
-        out_total += tot & 0xFFFF; rst_total += tot >> 16;
+        const uint32_t end = out_total + (tot & 0xFFFF);
+        __syncthreads();
+        for (uint32_t wi = (out_total >> 2) + threadIdx.x; wi < (end >> 2); wi += 256)      // the words complete by now
+            *reinterpret_cast<uint32_t*>(dst + 4 * (size_t)wi) = __builtin_bswap32(ring[wi & (kUnstuffRing / 4 - 1)]);
+        out_total = end; rst_total += tot >> 16;
         __syncthreads();
         if (stop_all != 0xFFFFFFFFu) break;
+    }
+    if (threadIdx.x < (out_total & 3u)) {                  // the bytes of the last, incomplete word
+        const uint32_t q = (out_total & ~3u) + threadIdx.x;
+        dst[q ^ 3u] = ringb[q & (kUnstuffRing - 1)];
     }
     if (threadIdx.x == 0) {
         // intervals whose restart marker never showed up get an empty range; the end goes last
