@@ -1222,8 +1222,8 @@ PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, 
     LaneBits rd;
     rd.init(words, byte_off * 8 + (uint32_t)st);
     const uint32_t ncorr = (uint32_t)__builtin_popcountll(h);
-    uint64_t sgn = 0, plus = 0;
-    uint64_t todo = h;                                       // history positions whose correction bit has not been read yet
+    uint64_t sgn = 0;
+    uint64_t corr = 0;                                       // the correction bits in reading order (dealt out to the history positions at the end, once)
     uint32_t taken = 0;                                      // correction bits read so far
     uint32_t n = ncorr;                                      // inside an end-of-band run: all of them, nothing else
     if ((uint32_t)(st >> 32) == 0) {
@@ -1255,22 +1255,23 @@ PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, 
             const uint32_t upto = (uint32_t)__builtin_popcountll(h & ((2ull << pos) - 1));   // corrections at positions <= pos (pos itself is a zero)
             if (upto > taken) {
                 const uint32_t m = upto - taken;
-                const uint64_t span = todo & ((2ull << pos) - 1);         // the history positions up to pos not yet served
+                uint64_t bits;
                 if (used + m <= 32) {                        // they are in the window already
-                    plus |= deal_bits(bitrev32(win << used) & ((1u << m) - 1), span);
+                    bits = bitrev32(win << used) & ((1u << m) - 1);
                     used += m;
                 } else {
                     rd.skip(used); used = 0;
-                    plus |= deal_bits(rd.take_reversed(m), span);
+                    bits = rd.take_reversed(m);
                 }
-                todo &= ~span; taken = upto;
+                corr |= bits << taken;
+                taken = upto;
             }
             rd.skip(used);
             k = pos + 1;
         }
     }
-    if (n) plus |= deal_bits(rd.take_reversed(n), todo);
-    *sign_out = sgn; *plus_out = plus;
+    if (n) corr |= rd.take_reversed(n) << taken;             // (taken + n is at most the number of history positions, 63)
+    *sign_out = sgn; *plus_out = deal_bits(corr, h);
 }
 
 // ---------------------------------------------------------------------------------------
