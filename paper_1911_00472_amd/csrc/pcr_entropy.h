@@ -1194,6 +1194,21 @@ PCR_HD uint64_t deal_bits(uint64_t bits, uint64_t where) {
     return out;
 }
 
+// position of the n-th (n = 1, 2, ...) set bit of z, or `none` if z has fewer: a binary search on population counts
+// (a loop that clears n - 1 bits costs a wavefront its full length whenever one lane needs it)
+PCR_HD int nth_set_bit(uint64_t z, uint32_t n, int none) {
+    if ((uint32_t)__builtin_popcountll(z) < n) return none;
+    uint32_t w = (uint32_t)z, base = 0;
+    uint32_t t = (uint32_t)__builtin_popcount(w);
+    if (n > t) { n -= t; w = (uint32_t)(z >> 32); base = 32; }
+    t = (uint32_t)__builtin_popcount(w & 0xFFFFu); if (n > t) { n -= t; w >>= 16; base += 16; }
+    t = (uint32_t)__builtin_popcount(w & 0xFFu);   if (n > t) { n -= t; w >>= 8; base += 8; }
+    t = (uint32_t)__builtin_popcount(w & 0xFu);    if (n > t) { n -= t; w >>= 4; base += 4; }
+    t = (uint32_t)__builtin_popcount(w & 0x3u);    if (n > t) { n -= t; w >>= 2; base += 2; }
+    t = w & 1u;                                     if (n > t) base += 1;
+    return (int)base;
+}
+
 struct LaneBits {
     const uint32_t* words;
     uint64_t buf;                                             // words[wi] : words[wi + 1]
@@ -1244,9 +1259,7 @@ PCR_HD void refine_block(const uint32_t* words, uint32_t byte_off, uint64_t st, 
                 used = len + 1;
             } else if (r == 15) {                            // sixteen zeros: lands on the sixteenth zero from k, which stays zero
                 used = len;
-                uint64_t z = ~h & band & ~((1ull << k) - 1);
-                for (int q = 0; q < 15 && z; q++) z &= z - 1;
-                pos = z ? __builtin_ctzll(z) : Se;
+                pos = nth_set_bit(~h & band & ~((1ull << k) - 1), 16, Se);
             } else {                                         // end of band: code, run-length bits, then every correction left
                 rd.skip(len + r);
                 n = ncorr - taken;
