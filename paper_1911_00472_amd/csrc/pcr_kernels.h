@@ -550,7 +550,7 @@ constexpr uint32_t kApplyChunk = 4096;
 // a non-interleaved scan does not visit.
 PCR_D uint32_t dc_refinement_bit(const DevRecord& R, const ApplyScan& S, uint32_t row, uint32_t col, uint32_t hs, uint32_t vs, bool covered) {
     uint32_t m, within;
-    if (S.ns > 1) { m = (row / vs) * S.mcu_w + col / hs; within = S.before + (row % vs) * hs + col % hs; }
+    if (S.ns > 1) { m = (row >> (vs - 1)) * S.mcu_w + (col >> (hs - 1)); within = S.before + (row & (vs - 1)) * hs + (col & (hs - 1)); }   // (sampling factors are 1 or 2)
     else { if (!covered) return 0; m = row * S.mcu_w + col; within = 0; }
     const uint32_t ivl = S.ri ? m / S.ri : 0;
     const uint32_t bit = (m - ivl * S.ri) * S.bpm + within;
@@ -941,6 +941,20 @@ PCR_D void four_samples(const float* row, uint32_t x0, uint32_t sh, float v[4]) 
     else { const float2 t = *reinterpret_cast<const float2*>(row + (x0 >> 1)); v[0] = v[1] = t.x; v[2] = v[3] = t.y; }
 }
 
+// The first n (< 12) bytes of w0 w1 w2 to p with at most three stores (a row's last, narrower group: a loop over
+// the bytes would cost every wavefront that holds a row end its full length)
+PCR_D void store_head(uint8_t* p, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t n) {
+    struct __attribute__((packed, aligned(1))) U32 { uint32_t v; };
+    struct __attribute__((packed, aligned(1))) U16 { uint16_t v; };
+    const uint32_t words[3] = {w0, w1, w2};
+    uint32_t done = 0;
+    if (n >= 8) { reinterpret_cast<U32*>(p)->v = w0; reinterpret_cast<U32*>(p + 4)->v = w1; done = 8; }
+    else if (n >= 4) { reinterpret_cast<U32*>(p)->v = w0; done = 4; }
+    const uint32_t w = done == 8 ? words[2] : (done == 4 ? words[1] : words[0]);       // the word the rest comes from
+    if (n - done >= 2) { reinterpret_cast<U16*>(p + done)->v = (uint16_t)w; if (n - done == 3) p[done + 2] = (uint8_t)(w >> 16); }
+    else if (n - done == 1) p[done] = (uint8_t)w;
+}
+
 template <bool kRefine, bool kPlanes>
 __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out,
                                                      const ApplyList* __restrict__ lists, const int32_t* __restrict__ list_idx,
@@ -1071,7 +1085,7 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
                 Eight e8; e8.a = w0; e8.b = w1;
                 *reinterpret_cast<Eight*>(wp) = e8;
             } else {
-                for (uint32_t i = 0; i < left; i++) wp[i] = (uint8_t)((i < 4 ? w0 : w1) >> (8 * (i & 3)));
+                store_head(wp, w0, w1, 0u, left);
             }
         } else {
             float ys[4], cb[4], cr[4];
@@ -1093,7 +1107,7 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
                 Twelve tw; tw.a = w0; tw.b = w1; tw.c = w2;
                 *reinterpret_cast<Twelve*>(wp) = tw;           // one (possibly unaligned) 12-byte store
             } else {
-                for (uint32_t i = 0; i < left * 3; i++) wp[i] = (uint8_t)((i < 4 ? w0 : (i < 8 ? w1 : w2)) >> (8 * (i & 3)));
+                store_head(wp, w0, w1, w2, left * 3);
             }
         }
     }
