@@ -53,7 +53,7 @@ PMC = {
                   "source": "profiles/decode_kernels_imagenet_like_k10_counters.md (SQ_INSTS_SALU, SQ_INSTS_VALU, FETCH_SIZE x 2.0, WRITE_SIZE x 1.0)"},
 }
 # all kernels of that decode, same counter run
-RECORD0_INSTS = {"scalar": 2740.8e6, "vector": 1548.8e6}
+RECORD0_INSTS = {"scalar": 2668.5e6, "vector": 1417.3e6}
 
 # The serial chain of one Huffman-coded symbol in this design, at the very least: fetch the packed word of the current
 # bit offset, test it, take its length, add it to the position, apply the position update, test for the end of the
