@@ -684,3 +684,30 @@ def test_more_refinement_scans_than_the_replay_list_holds():
     _check_record(rec[:int(ge[k_ok - 1])], (1, 5, k_ok), check_bytes=False)
     f2, n2 = many_refinement_scans_file(extra_dc=6)
     _check_record(pcrgen.write_record([f2]), range(1, n2 + 1))
+
+
+@pytest.mark.gpu
+def test_a_decode_call_can_be_captured_into_a_graph(rgb_small):
+    """After one warm-up call per scan group (which builds the work lists) a decode call is kernel launches and one
+    device-to-device copy on the caller's stream, so it can be captured into a HIP graph: every replay gives the eager
+    result, with eager work and synchronisations between the replays."""
+    torch = _torch()
+    rec, _ = rgb_small
+    with pkg.pcr_open(rec, 0) as r:
+        for k in (1, 4, 10):
+            want = r.decode_batch(k).clone()
+            out = torch.zeros_like(want)
+            status = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                r.decode_batch(k, out=out, status=status)
+            for rep in range(3):
+                out.fill_(7); status.fill_(5)
+                other = r.decode_batch(10 if k != 10 else 2)             # eager work on the same handle in between
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(out, want), (k, rep)
+                assert (status.cpu().numpy() == 0).all()
+                del other
