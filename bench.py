@@ -364,6 +364,36 @@ def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms, k):
                 acc[(a, b)] += (time.perf_counter() - t) / reps
     res["fidelity_upgrade"] = {"%d->%d" % ab: {"ms_per_step": s * 1e3, "fresh_decode_ms_per_step": per_k_ms.get(ab[1])} for ab, s in acc.items()}
 
+    # the same step with every record's decode call captured into a HIP graph (one replay per record instead of 6 - 14
+    # kernel launches): what the launch overhead is worth at each scan group
+    graphed = {}
+    for kk in TABLE_SCAN_GROUPS:
+        job.step(kk)
+        torch.cuda.synchronize()
+        graphs = []
+        for h, o, st in zip(handles, outs, streams):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                h.decode_batch(kk, out=o, stream=st.cuda_stream)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+        def replay_all():                                           # (a replay runs on the current stream: each record on its own)
+            for g, st in zip(graphs, streams):
+                with torch.cuda.stream(st):
+                    g.replay()
+        replay_all()
+        torch.cuda.synchronize()
+        reps_g = max(5, args.steps)
+        t = time.perf_counter()
+        for _ in range(reps_g):
+            replay_all()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t) / reps_g
+        graphed[str(kk)] = {"ms_per_step": dt * 1e3, "images_per_s": n_img / dt, "eager_ms_per_step": per_k_ms.get(kk)}
+        del graphs
+    res["decode_calls_replayed_from_graphs"] = graphed
+
     # training tail: one random box per image resized to 224 x 224, flipped, normalised, fp16 NCHW
     rng = np.random.default_rng(1911_00472)
     crop_t, tails = [], []
