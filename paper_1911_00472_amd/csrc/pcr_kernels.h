@@ -27,6 +27,17 @@ namespace pcr {
 // their own wavefronts' issue priority (s_setprio; stream priorities are not touched); the DC first kernel,
 // few and latency-bound wavefronts, takes a middle value.  The AC entropy kernels stay at the default.
 PCR_D void short_kernel_priority() { __builtin_amdgcn_s_setprio(3); }
+
+// Workgroups are handed to the chip's eight dies (XCDs, each with its own L2) round-robin by their index.  Kernels whose
+// neighbouring work items write neighbouring memory (the runs of MCUs of one image row, the rows of cells of one image)
+// take item xcd_major(blockIdx.x, gridDim.x) instead of item blockIdx.x: every die then works through one contiguous
+// eighth of the list, so the cache lines two neighbours share are completed in one L2 instead of being written back
+// in parts from two.
+constexpr uint32_t kXcds = 8;
+PCR_D uint32_t xcd_major(uint32_t b, uint32_t n) {
+    const uint32_t q = n / kXcds, r = n - q * kXcds, x = b % kXcds, i = b / kXcds;
+    return x * q + (x < r ? x : r) + i;
+}
 PCR_D void dc_kernel_priority() { __builtin_amdgcn_s_setprio(2); }
 
 struct DevRecord {
@@ -968,7 +979,8 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
     __shared__ uint32_t org[kPixLanes];                    // per MCU of the run: its first pixel, counted in pixels from the image's first (< 2^32)
     __shared__ uint16_t visw[kPixLanes], vish[kPixLanes];  // ... and how many of its pixel columns / rows lie inside the image
     short_kernel_priority();
-    const uint32_t timg = uni(tiles[blockIdx.x].img), mcu0 = uni(tiles[blockIdx.x].mcu0);
+    const uint32_t item = xcd_major(blockIdx.x, gridDim.x);
+    const uint32_t timg = uni(tiles[item].img), mcu0 = uni(tiles[item].mcu0);
     const uint32_t tid = threadIdx.x;
     const ImgDesc* ip = R.img + timg;
     PixGeom G;
@@ -1167,7 +1179,8 @@ PCR_D void flat_cell_words(const DevRecord& R, const ImgDesc& D, const int16_t* 
 __global__ void __launch_bounds__(kFlatLanes) k_pixel_flat(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out,
                                                            const CropBox* __restrict__ boxes) {
     short_kernel_priority();
-    const uint32_t timg = uni(tiles[blockIdx.x].img), cell0 = uni(tiles[blockIdx.x].mcu0);
+    const uint32_t item = xcd_major(blockIdx.x, gridDim.x);
+    const uint32_t timg = uni(tiles[item].img), cell0 = uni(tiles[item].mcu0);
     ImgDesc D;
     load_desc(R.img + timg, &D);
     const uint32_t nc = D.nc, W = D.W, H = D.H;
@@ -1228,7 +1241,8 @@ __global__ void __launch_bounds__(kFlatRowLanes) k_pixel_flat_rows(DevRecord R, 
     // the pixel row: 24 bytes per cell (8 for a gray image), then its first 32 bytes again so that a chunk may run past its end
     extern __shared__ __attribute__((aligned(16))) uint32_t pat[];
     short_kernel_priority();
-    const uint32_t timg = uni(tiles[blockIdx.x].img), cy = uni(tiles[blockIdx.x].mcu0);      // (mcu0: the row of cells)
+    const uint32_t item = xcd_major(blockIdx.x, gridDim.x);
+    const uint32_t timg = uni(tiles[item].img), cy = uni(tiles[item].mcu0);      // (mcu0: the row of cells)
     ImgDesc D;
     load_desc(R.img + timg, &D);
     const uint32_t nc = D.nc, W = D.W, H = D.H, tid = threadIdx.x;
@@ -1392,7 +1406,8 @@ __global__ void __launch_bounds__(kTailLanes) k_pixel_tail(DevRecord R, const Pi
     __shared__ ApplyList rl[kRefine ? kMaxComp : 1];
     __shared__ uint32_t row_lo, row_hi;                    // output rows served here: [row_lo, row_hi)
     short_kernel_priority();
-    const uint32_t timg = uni(tiles[blockIdx.x].img), mcu0 = uni(tiles[blockIdx.x].mcu0);
+    const uint32_t item = xcd_major(blockIdx.x, gridDim.x);
+    const uint32_t timg = uni(tiles[item].img), mcu0 = uni(tiles[item].mcu0);
     const uint32_t tid = threadIdx.x;
     const ImgDesc* ip = R.img + timg;
     PixGeom G;
