@@ -1160,9 +1160,12 @@ PCR_D void flat_cell_words(const DevRecord& R, const ImgDesc& D, const int16_t* 
         s[c] = 128.f;
         if (c < D.nc) {
             const uint32_t bcol = (cx * D.hs[c]) >> (D.hmax - 1), brow = (cy * D.vs[c]) >> (D.vmax - 1);      // (sampling factors are 1 or 2)
+            // (picked with compares: an index computed at run time would put the whole descriptor into scratch memory)
             const uint32_t tq = D.tq[c] & 3;
-            const uint8_t* q = R.rec + D.qoff[tq];
-            const float q0 = (D.qprec[tq] ? (float)ld_be16(q) : (float)q[0]) * 0.125f;
+            const uint32_t qoff = tq == 0 ? D.qoff[0] : (tq == 1 ? D.qoff[1] : (tq == 2 ? D.qoff[2] : D.qoff[3]));
+            const uint32_t qprec = tq == 0 ? D.qprec[0] : (tq == 1 ? D.qprec[1] : (tq == 2 ? D.qprec[2] : D.qprec[3]));
+            const uint8_t* q = R.rec + qoff;
+            const float q0 = (qprec ? (float)ld_be16(q) : (float)q[0]) * 0.125f;
             s[c] = clamp255((float)dcp[plane0 + brow * D.bw[c] + bcol] * q0 + 128.f);
             plane0 += (uint32_t)D.bw[c] * D.bh[c];
         }

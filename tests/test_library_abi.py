@@ -105,3 +105,18 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(b, "LIB_PATH", "/nonexistent/libpcr.so")
     with pytest.raises(RuntimeError):
         b.lib()
+
+
+def test_no_kernel_spills_to_scratch_memory(tmp_path):
+    """Every kernel keeps its state in registers and LDS.  (An array indexed with a run-time value is put into scratch
+    memory by the compiler, whole: it once cost the DC-only pixel kernel 5 KB of extra memory writes per wavefront, which
+    showed in the hardware counters as half again the bytes the kernel had to write.)"""
+    import os
+    import subprocess
+    from paper_1911_00472_amd import build
+    asm = tmp_path / "pcr.s"
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    subprocess.check_call([hipcc] + flags + ["-S", "--cuda-device-only", "-o", str(asm), build.SRC], stderr=subprocess.DEVNULL)
+    sizes = [line.split()[-1] for line in asm.read_text().splitlines() if ".amdhsa_private_segment_fixed_size" in line]
+    assert len(sizes) > 30 and all(s == "0" for s in sizes), sizes
