@@ -243,8 +243,9 @@ int pcr_select_scan_group(pcr_record* rec, float min_mean_score, uint8_t* d_work
  *                      sample whose two source rows lie in that MCU row; only the first and last pixel row of every MCU
  *                      row (1/8 of the pixels for 4:2:0 images) go to a side buffer of the handle, from which a second,
  *                      small kernel interpolates the remaining output rows.  MCUs that do not touch an image's box are
- *                      not decoded.  Every image must be at most 256 / (blocks per MCU) MCUs wide (672 pixels for
- *                      4:2:0 and 4:4:4, 1024 for 4:2:2, 2048 for gray), else PCR_E_UNSUPPORTED (give a working buffer).
+ *                      not decoded.  A workgroup holds 256 / (blocks per MCU) MCUs at a time (672 pixels of width for
+ *                      4:2:0 and 4:4:4, 1024 for 4:2:2, 2048 for gray); a box wider than that is served in passes that
+ *                      overlap by one MCU, at any image width.
  *                      The first such call on a record allocates the side buffer.
  *   d_pixels != NULL   (device, layout of pcr_output_layout, pixel_capacity bytes) working memory: the pixel kernel
  *                      writes the runs of MCUs that touch an image's box there (what it held elsewhere stays), and

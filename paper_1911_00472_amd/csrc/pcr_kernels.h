@@ -1371,8 +1371,9 @@ __global__ void __launch_bounds__(256) k_triangle_rgb(DevRecord R, const uint8_t
 
 // --------------------------------------------------------------------------------------
 // k_pixel_tail: decode and training tail in one kernel, so that the full-resolution pixels never reach memory.
-// One workgroup per MCU row of one image (all its MCUs: the image must be at most kTailLanes / blocks-per-MCU MCUs
-// wide), one lane per block as in k_pixel; the samples of the MCU row lie in LDS as one row-major plane per component.
+// One workgroup per MCU row of one image, one lane per block as in k_pixel; the samples of the MCU row lie in LDS as
+// one row-major plane per component, kTailLanes / blocks-per-MCU MCUs at a time (42 for 4:2:0: one pass for images up
+// to 672 pixels wide; a wider box is done in passes that overlap by one MCU).
 // Phase B is replaced by the tail: the output samples whose two source rows both lie in this MCU row are interpolated
 // from pixels computed on the fly from the samples (colour conversion and rounding exactly as k_pixel does them, since
 // the tail is defined on the rounded pixels).  Output rows whose two source rows lie in two MCU rows cannot be served
@@ -1417,23 +1418,15 @@ __global__ void __launch_bounds__(kTailLanes) k_pixel_tail(DevRecord R, const Pi
     pix_geom(ip, &G);
     const uint32_t nc = G.nc, W = G.W, H = G.H, mcux = G.mcux, bpm = G.bpm;
     const uint32_t mcu_px_w = 8 * G.hmax, mcu_px_h = 8 * G.vmax;
-    if (bpm == 0 || mcux * bpm > (uint32_t)kTailLanes) return;          // (the host refuses such records before launching)
+    const uint32_t seg_m = min((uint32_t)kTailLanes / max(bpm, 1u), mcux);   // MCUs one pass holds in LDS
+    if (bpm == 0 || seg_m == 0 || (seg_m < 2 && mcux > 1)) return;       // (no sampling layout this library accepts gets here)
     const uint32_t my = mcu0 / mcux;
     const uint32_t ylo = my * mcu_px_h, yhi = ylo + mcu_px_h < H ? ylo + mcu_px_h : H;   // pixel rows of this MCU row
     const CropBox b = clamp_box(boxes[timg], (int)W, (int)H);
     if ((int)ylo >= b.y0 + b.h || (int)yhi <= b.y0) return;
     const uint32_t mc0 = (uint32_t)b.x0 / mcu_px_w, mc1 = (uint32_t)(b.x0 + b.w - 1) / mcu_px_w;   // MCUs the box touches
     const bool dead = uni((uint32_t)(R.status[timg] != kOk)) != 0;
-    const uint32_t m = (tid * recip16(bpm)) >> 16, j = tid - m * bpm;
-    const bool mine = !dead && m >= mc0 && m <= mc1 && m < mcux;
-    PixBlock B;
-    uint32_t by = 0, bx = 0;
-    short8 v[8];
-    if (mine) {
-        pix_block(R, G, timg, j, my, m, &B, &by, &bx);
-        if (B.zm <= 1) { v[0] = short8{0, 0, 0, 0, 0, 0, 0, 0}; v[0][0] = *B.dc; }
-        else pix_load(B, v);
-    }
+    const uint32_t ml = (tid * recip16(bpm)) >> 16, j = tid - ml * bpm;   // MCU within the pass, block within the MCU
     if (kRefine) pix_lists(lists, list_idx, timg, nc, rl, tid, kTailLanes);
     pix_quant_table(R, ip, nc, qz, tid, kTailLanes);
     if (tid == 0) { row_lo = 0xFFFFFFFFu; row_hi = 0; }
@@ -1444,49 +1437,73 @@ __global__ void __launch_bounds__(kTailLanes) k_pixel_tail(DevRecord R, const Pi
         tail_rows(b, oy, P.out_h, &ya, &yb, &fy);
         if (ya >= (int)ylo && yb < (int)yhi) { atomicMin(&row_lo, (uint32_t)oy); atomicMax(&row_hi, (uint32_t)oy + 1); }
     }
-    if (mine) {
-        const ApplyList* rlc = &rl[kRefine ? B.c : 0];
-        const uint32_t row_len = mcux * B.hs * 8;
-        float* dst = tile + mcux * pick3(B.c, G.rb[0], G.rb[1], G.rb[2]) + by * 8 * row_len + (m * B.hs + bx) * 8;
-        if (B.zm <= 1) dst[0] = clamp255((float)pix_dc<kRefine>(R, B, v[0][0], rlc) * qz[B.c][0] + 128.f);
-        else pix_finish<kRefine>(R, B, v, qz[B.c], rlc, dst, row_len);
-    }
-    __syncthreads();
     TailView V;
     V.nc = nc; V.dead = dead;
 #pragma unroll
     for (uint32_t c = 0; c < kMaxComp; c++) {
-        V.plane[c] = tile + mcux * G.rb[c]; V.len[c] = mcux * G.rs[c];
+        V.plane[c] = tile + seg_m * G.rb[c]; V.len[c] = seg_m * G.rs[c];
         V.shx[c] = c < nc && G.hs[c] != G.hmax; V.shy[c] = c < nc && G.vs[c] != G.vmax;
         V.fm[c] = G.flat[c] ? ~7u : ~0u;
     }
-    // the first and the last pixel row, for the output rows that need a neighbouring MCU row as well
-    {
-        uint8_t* e = edge + edge_off[timg] + (size_t)(2 * my) * W * nc;
-        for (uint32_t it = tid; it < 2 * (uint32_t)b.w; it += kTailLanes) {
-            const uint32_t which = it >= (uint32_t)b.w, x = (uint32_t)b.x0 + (which ? it - (uint32_t)b.w : it);
-            float px[3];
-            tail_pixel(V, x, which ? yhi - 1 - ylo : 0u, px);
-            uint8_t* wp = e + ((size_t)which * W + x) * nc;
-            for (uint32_t c = 0; c < nc; c++) wp[c] = (uint8_t)px[c];
+    // The MCUs the box touches, seg_m at a time.  A pass serves the source columns of all its MCUs but the last one,
+    // which it holds only as the right-hand neighbour (an output sample reads columns xa and xa + 1); the pass that
+    // reaches the box's last MCU serves that one too.  Most images need one pass.
+    for (uint32_t s0 = mc0;; s0 += seg_m - 1) {
+        const uint32_t s1 = min(s0 + seg_m - 1, mc1);                   // last MCU decoded in this pass
+        const bool last = s1 == mc1;
+        const uint32_t m = s0 + ml;
+        const bool mine = !dead && ml < seg_m && m <= s1;
+        PixBlock B;
+        uint32_t by = 0, bx = 0;
+        short8 v[8];
+        if (mine) {
+            pix_block(R, G, timg, j, my, m, &B, &by, &bx);
+            if (B.zm <= 1) { v[0] = short8{0, 0, 0, 0, 0, 0, 0, 0}; v[0][0] = *B.dc; }
+            else pix_load(B, v);
+            const ApplyList* rlc = &rl[kRefine ? B.c : 0];
+            const uint32_t row_len = seg_m * B.hs * 8;
+            float* dst = tile + seg_m * pick3(B.c, G.rb[0], G.rb[1], G.rb[2]) + by * 8 * row_len + (ml * B.hs + bx) * 8;
+            if (B.zm <= 1) dst[0] = clamp255((float)pix_dc<kRefine>(R, B, v[0][0], rlc) * qz[B.c][0] + 128.f);
+            else pix_finish<kRefine>(R, B, v, qz[B.c], rlc, dst, row_len);
         }
-    }
-    const uint32_t lo = row_lo, hi = row_hi;
-    if (lo >= hi) return;
-    const uint32_t ow = (uint32_t)P.out_w, items = (hi - lo) * ow;
-    const uint32_t rcpw = ow > 1 ? 0xFFFFFFFFu / ow + 1u : 0u;
-    for (uint32_t it = tid; it < items; it += kTailLanes) {
-        const uint32_t r = ow > 1 ? __umulhi(it, rcpw) : it, ox = it - r * ow, oy = lo + r;
-        int ya, yb, xa, xb; float fy, fx;
-        tail_rows(b, (int)oy, P.out_h, &ya, &yb, &fy);
-        tail_cols(b, (int)ox, P.out_w, &xa, &xb, &fx);
-        float aa[3], ab[3], ba[3], bb[3];
-        tail_pixel(V, (uint32_t)xa, (uint32_t)ya - ylo, aa); tail_pixel(V, (uint32_t)xb, (uint32_t)ya - ylo, ab);
-        tail_pixel(V, (uint32_t)xa, (uint32_t)yb - ylo, ba); tail_pixel(V, (uint32_t)xb, (uint32_t)yb - ylo, bb);
-        __half* dst = out + ((size_t)timg * nc * P.out_h + oy) * ow + ox;
+        __syncthreads();
+        const uint32_t xorg = s0 * mcu_px_w;                            // image column of the pass's first sample
+        const uint32_t xs = max((uint32_t)b.x0, xorg);                  // source columns served here: [xs, xe)
+        const uint32_t xe = last ? (uint32_t)(b.x0 + b.w) : s1 * mcu_px_w;
+        // the first and the last pixel row, for the output rows that need a neighbouring MCU row as well
+        {
+            uint8_t* e = edge + edge_off[timg] + (size_t)(2 * my) * W * nc;
+            const uint32_t span = xe - xs;
+            for (uint32_t it = tid; it < 2 * span; it += kTailLanes) {
+                const uint32_t which = it >= span, x = xs + (which ? it - span : it);
+                float px[3];
+                tail_pixel(V, x - xorg, which ? yhi - 1 - ylo : 0u, px);
+                uint8_t* wp = e + ((size_t)which * W + x) * nc;
+                for (uint32_t c = 0; c < nc; c++) wp[c] = (uint8_t)px[c];
+            }
+        }
+        const uint32_t lo = row_lo, hi = row_hi;
+        if (lo < hi) {
+            const uint32_t ow = (uint32_t)P.out_w, items = (hi - lo) * ow;
+            const uint32_t rcpw = ow > 1 ? 0xFFFFFFFFu / ow + 1u : 0u;
+            for (uint32_t it = tid; it < items; it += kTailLanes) {
+                const uint32_t r = ow > 1 ? __umulhi(it, rcpw) : it, ox = it - r * ow, oy = lo + r;
+                int ya, yb, xa, xb; float fy, fx;
+                tail_cols(b, (int)ox, P.out_w, &xa, &xb, &fx);
+                if ((uint32_t)xa < xs || (uint32_t)xa >= xe) continue;  // another pass's column
+                tail_rows(b, (int)oy, P.out_h, &ya, &yb, &fy);
+                const uint32_t ua = (uint32_t)xa - xorg, ub = (uint32_t)xb - xorg;
+                float aa[3], ab[3], ba[3], bb[3];
+                tail_pixel(V, ua, (uint32_t)ya - ylo, aa); tail_pixel(V, ub, (uint32_t)ya - ylo, ab);
+                tail_pixel(V, ua, (uint32_t)yb - ylo, ba); tail_pixel(V, ub, (uint32_t)yb - ylo, bb);
+                __half* dst = out + ((size_t)timg * nc * P.out_h + oy) * ow + ox;
 #pragma unroll
-        for (uint32_t c = 0; c < kMaxComp; c++)
-            if (c < nc) dst[(size_t)c * P.out_h * ow] = tail_value(aa[c], ab[c], ba[c], bb[c], fx, fy, P.mean[c], P.istd[c]);
+                for (uint32_t c = 0; c < kMaxComp; c++)
+                    if (c < nc) dst[(size_t)c * P.out_h * ow] = tail_value(aa[c], ab[c], ba[c], bb[c], fx, fy, P.mean[c], P.istd[c]);
+            }
+        }
+        if (last) break;
+        __syncthreads();                                                // the samples in LDS are replaced next
     }
 }
 

@@ -874,15 +874,14 @@ int pcr_crop_resize_batch(pcr_record* r, const uint8_t* d_pixels, const pcr_crop
     return PCR_OK;
 }
 
-// Tiles, side buffer and tables of the fused decode + tail (once per bound record).  PCR_E_UNSUPPORTED if an image is
-// too wide for one workgroup per MCU row.
+// Tiles, side buffer and tables of the fused decode + tail (once per bound record).
 static int prepare_fused_tail(pcr_record* r) {
     if (r->d_tail_tiles) return PCR_OK;
     const uint32_t n = r->hdr.n;
     std::vector<PixelTile> tiles; std::vector<uint64_t> eoff(n + 1, 0); std::vector<uint32_t> mh(n);
     for (uint32_t i = 0; i < n; i++) {
         const ImgDesc& d = r->img[i];
-        if ((uint32_t)d.mcux * blocks_per_mcu(d) > (uint32_t)kTailLanes) return PCR_E_UNSUPPORTED;
+        if (d.mcux > 1 && 2 * blocks_per_mcu(d) > (uint32_t)kTailLanes) return PCR_E_UNSUPPORTED;   // (a pass holds two MCUs at least)
         for (uint32_t my = 0; my < d.mcuy; my++) tiles.push_back(PixelTile{i, my * d.mcux});
         eoff[i + 1] = eoff[i] + (uint64_t)2 * d.mcuy * d.W * d.nc;
         mh[i] = 8u * d.vmax;

@@ -183,15 +183,26 @@ def test_decode_and_tail_in_one_kernel_equals_the_two_calls(rgb_small, gray64):
             want = oracle.crop_resize_normalize(pix, boxes[i][:4], bool(boxes[i][4]), 160, 160, MEAN, ISTD)
             tol = 2.0 ** -11 * np.abs(want) + 4e-6 + max(ISTD) / 255.0
             assert (np.abs(got[i].astype(np.float64) - want) <= tol).all(), i
-    # an image wider than one workgroup per MCU row can hold is refused when no working buffer is given
-    wide = pcrgen.write_record([pcrgen.make_jpeg(900, 1, 2000, 8, 3, 6.0, 2, 2, 90)])
+    # images wider than one workgroup holds at a time: passes over the MCU row that overlap by one MCU.  Boxes that end
+    # on, one before and one after a pass's last served column; flips; widths of 1, 2 and 3 passes; all samplings.
+    wide = pcrgen.write_record([pcrgen.make_jpeg(900, 1, 2000, 8, 3, 6.0, 2, 2, 90), pcrgen.make_jpeg(901, 2, 1500, 40, 3, 6.0, 1, 1, 90),
+                                pcrgen.make_jpeg(902, 0, 1371, 33, 3, 6.0, 2, 1, 85), pcrgen.make_jpeg(903, 1, 700, 50, 3, 6.0, 2, 2, 90)])
     with pkg.pcr_open(wide, 0) as r:
-        tb = torch.tensor([[0, 0, 2000, 8, 0]], dtype=torch.int32, device="cuda")
-        with pytest.raises(pkg.PcrError) as e:
-            r.decode_crop_batch(1, tb, 8, 8, MEAN, ISTD)
-        assert e.value.code == pkg.E_UNSUPPORTED
+        shapes = [r.image_info(i)[:2] for i in range(r.n)]
+        fixed = [np.array([[0, 0, 2000, 8, 0], [0, 0, 1500, 40, 1], [0, 0, 1371, 33, 0], [0, 0, 700, 50, 1]], dtype=np.int32),
+                 np.array([[3, 1, 41 * 16 - 3 + 1, 6, 1], [7, 2, 41 * 8 - 7, 30, 0], [16, 0, 41 * 16 - 16 - 1, 33, 1], [640, 3, 60, 40, 0]], dtype=np.int32),
+                 np.array([[655, 0, 3, 8, 0], [300, 5, 1200, 9, 0], [1, 1, 1369, 31, 1], [0, 0, 657, 50, 0]], dtype=np.int32)]
+        cases = fixed + [_boxes(np.random.default_rng(500 + t), shapes) for t in range(3)]
+        for t, boxes in enumerate(cases):
+            tb = torch.from_numpy(boxes).cuda()
+            for (oh, ow) in ((8, 8), (37, 1201), (224, 224)):
+                for k in (1, 5, 10):
+                    want = r.crop_resize_batch(r.decode_batch(k), tb, oh, ow, MEAN, ISTD)
+                    got = torch.full_like(want, 9.0)
+                    r.decode_crop_batch(k, tb, oh, ow, MEAN, ISTD, pixels=None, out=got)
+                    assert torch.equal(got, want), (t, oh, ow, k, int((got != want).sum()))
         work = torch.empty(int(r.output_layout()[-1]), dtype=torch.uint8, device="cuda")
-        r.decode_crop_batch(1, tb, 8, 8, MEAN, ISTD, pixels=work)                 # with one, it is served
+        r.decode_crop_batch(1, tb, 8, 8, MEAN, ISTD, pixels=work)                 # the two-kernel form of the same call
 
 
 def test_tail_argument_errors(gray64):
