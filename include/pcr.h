@@ -367,6 +367,13 @@ int pcr_transcode_progressive_counted(const void* src_jpeg, size_t src_bytes, co
 int pcr_transcode_symbol_counts(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
                                 uint32_t* counts);
 
+/* Shape of the entropy decoders (Section 4.2 of the paper: decoding is where the time goes).  A scan is cut into units
+ * (restart intervals, entry-point units); a launch either gives every unit a wavefront that decodes it on the scalar
+ * unit, or every unit a lane (64 units per wavefront).  mode 0 (default): by the number of units in the launch (lanes
+ * from 8192 on); 1: lanes wherever the kernels exist and the record's scans have several units; -1: never.  The results
+ * are the same bit for bit.  Takes effect from the next decode call.  PCR_E_ARG: null handle or another mode. */
+int pcr_set_lane_decoders(pcr_record* rec, int mode);
+
 /* Stage timing with HIP events recorded on the call's own stream (off by default; switching it on
  * starts a new history).  A stage is one kernel or a short run of kernels:
  *   INDEX_PARSE    k_index + k_parse                 UNSTUFF        k_unstuff + zero fills

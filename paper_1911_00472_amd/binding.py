@@ -37,6 +37,7 @@ SYMBOLS = {
     "pcr_upgrade_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_resident_scan_group": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
     "pcr_enable_stage_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "pcr_set_lane_decoders": (ctypes.c_int, [_vp, ctypes.c_int]),
     "pcr_last_stage_ms": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_float)]),
     "pcr_probe_scalar_issue_rate": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]),
     "pcr_stage_ms_history": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]),
@@ -329,6 +330,9 @@ class Record:
         v = ctypes.c_int(0)
         _check(lib().pcr_resident_scan_group(self._h, ctypes.byref(v)), "pcr_resident_scan_group")
         return int(v.value)
+
+    def set_lane_decoders(self, mode):
+        _check(lib().pcr_set_lane_decoders(self._h, int(mode)), "pcr_set_lane_decoders")
 
     def enable_stage_timing(self, on=True):
         _check(lib().pcr_enable_stage_timing(self._h, 1 if on else 0), "pcr_enable_stage_timing")

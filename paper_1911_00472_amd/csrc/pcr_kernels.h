@@ -14,6 +14,7 @@
 #include "pcr_common.h"
 #include "pcr_format.h"
 #include "pcr_entropy.h"
+#include "pcr_lanes.h"
 #include "pcr_pixel.h"
 
 namespace pcr {
@@ -334,6 +335,73 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __rest
     L->ok = true;
 }
 
+PCR_D uint32_t lane_le32(const uint8_t* p) { return (uint32_t)p[0] | ((uint32_t)p[1] << 8) | ((uint32_t)p[2] << 16) | ((uint32_t)p[3] << 24); }
+
+// The same checks and ranges as unit_setup (pcr_kernels.h), without the assumption that the unit is wave-uniform.
+PCR_D void lane_unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __restrict__ clean32, LaneUnit* U) {
+    U->ok = false;
+    const ImgDesc* img = &R.img[un.img];
+    if (R.status[un.img] != kOk || un.scan >= img->nscans) return;
+    const size_t ig = (size_t)un.img * R.G + un.scan;
+    const ScanDesc* sd = &R.scan[ig];
+    if (!sd->valid || sd->ns != 1 || sd->Ss == 0) return;
+    const uint32_t sb = R.slot_base[ig], sc = R.slot_cnt[ig];
+    const uint32_t ri = sd->ri, mcus = sd->mcus;
+    if (ri == 0 && sc > 1) {
+        const uint8_t* e = R.rec + R.ent_off[ig] + (size_t)kEntryBytes * un.interval;
+        const uint32_t total = R.ivl_start[sb + sc] * 8;
+        uint32_t m0 = 0, b0 = 0, m1 = mcus, b1 = total;
+        if (un.interval > 0) { m0 = lane_le32(e - 16); b0 = lane_le32(e - 12); }
+        if (un.interval + 1 < sc) { m1 = lane_le32(e); b1 = lane_le32(e + 4); }
+        if (!(m0 < m1 && m1 <= mcus && b0 <= b1 && b1 <= total)) { R.status[un.img] = kEFormat; return; }
+        U->mcu0 = m0; U->mcu1 = m1; U->bit0 = b0; U->bit1 = b1;
+    } else {
+        const uint32_t b0 = R.ivl_start[sb + un.interval], b1 = R.ivl_start[sb + un.interval + 1];
+        U->mcu0 = ri ? un.interval * ri : 0;
+        U->mcu1 = ri ? (U->mcu0 + ri < mcus ? U->mcu0 + ri : mcus) : mcus;
+        if (U->mcu0 >= mcus) return;
+        U->bit0 = b0 * 8; U->bit1 = (b1 > b0 ? b1 : b0) * 8;
+    }
+    U->mcu_w = sd->mcu_w;
+    if (U->mcu_w == 0) return;
+    U->Ss = sd->Ss; U->Se = sd->Se; U->Al = sd->Al;
+    const uint32_t c = sd->comp[0];
+    size_t po = 0;
+    for (uint32_t q = 0; q < c && q < kMaxComp; q++) po += (size_t)img->bw[q] * img->bh[q] * 64;
+    U->bw = img->bw[c];
+    U->plane = R.coef + R.coef_off[un.img] + po;
+    U->plane_elems = (uint32_t)img->bw[c] * img->bh[c] * 64;
+    U->words = clean32 + (clean_base(sd->data_off) >> 2);
+    U->tab = &R.tabs[R.tab_idx[ig]];
+    U->ok = true;
+}
+
+// One job of a lane-per-unit kernel: units [first, first + count) of the launch's list, count <= 64.
+struct LaneJob { uint32_t first, count; };
+constexpr int kLaneTabs = 12;
+constexpr uint32_t kLaneTabWords = 272;                       // an AcTab up to (not including) its pre-packed look-up, rounded up
+static_assert(offsetof(AcTab, lutp) <= kLaneTabWords * 4, "the part of a table the lane decoders read");
+
+// The AC tables of a job's lanes into LDS, one copy per distinct (image, scan) -- `key`, equal keys in neighbouring
+// lanes -- and this lane's slot (>= kLaneTabs: more tables than the job may have; the host never makes such a job).
+// Call with every lane of the wavefront.
+PCR_D uint32_t lane_table_slots(const DevRecord& R, uint32_t key, bool mine, uint32_t (*tabs)[kLaneTabWords]) {
+    const uint32_t t = threadIdx.x;
+    const uint32_t prev = (uint32_t)__shfl_up((int)key, 1);
+    const uint64_t lead = __ballot(mine && (t == 0 || key != prev));
+    const uint32_t slot = (uint32_t)__popcll(lead & ((2ull << t) - 1ull)) - 1u;
+    uint64_t todo = lead;
+    for (uint32_t sl = 0; todo != 0 && sl < (uint32_t)kLaneTabs; sl++) {
+        const uint32_t leader = (uint32_t)__builtin_ctzll(todo);
+        todo &= todo - 1;
+        const uint32_t k = (uint32_t)__builtin_amdgcn_readlane((int)key, (int)leader);
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.tabs[R.tab_idx[k]]);
+        for (uint32_t e = t; e < kLaneTabWords; e += kEntropyLanes) tabs[sl][e] = src[e];
+    }
+    __syncthreads();
+    return mine ? slot : ~0u;
+}
+
 // SHAPE: which DC decoder (dc_shape) the units of this launch take; the host sorts the units by it.
 template <int SHAPE>
 __global__ void __launch_bounds__(kEntropyLanes) k_dc_first(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
@@ -429,6 +497,30 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first(DevRecord R, const U
     IndexSink sink;
     sink.init(L.plane[0], L.plane_elems[0], L.ls.Al);
     int rc = decode_ac_first(&wr, L.ls, &sink);
+    if (rc != kOk) R.status[un.img] = rc;
+}
+
+// The same scan kind with one LANE per unit (pcr_lanes.h).  One wavefront per job: up to 64 consecutive units of the
+// launch's list that use at most kLaneTabs different Huffman tables between them (the host cuts the list that way; the
+// units of one scan lie together).  The tables (built by k_build_tables) are copied into LDS first: every lane looks
+// its codes up in its own table, and 64 scattered reads of memory per symbol would bound the kernel by the rate at
+// which the memory pipeline takes requests.
+__global__ void __launch_bounds__(kEntropyLanes) k_ac_first_lanes(DevRecord R, const Unit* __restrict__ units, const LaneJob* __restrict__ jobs,
+        const uint32_t* __restrict__ clean32) {
+    __shared__ uint32_t tabs[kLaneTabs][kLaneTabWords];
+    __shared__ LaneRing rings;
+    const LaneJob job = jobs[blockIdx.x];
+    const uint32_t t = threadIdx.x;
+    const bool mine = t < job.count;
+    Unit un = units[job.first + (mine ? t : 0u)];
+    const uint32_t key = un.img * R.G + un.scan;
+    const uint32_t slot = lane_table_slots(R, key, mine, tabs);
+    LaneUnit U;
+    U.ok = false;
+    if (mine && slot < (uint32_t)kLaneTabs) lane_unit_setup(R, un, clean32, &U);
+    if (!U.ok) return;
+    U.tab = reinterpret_cast<const AcTab*>(&tabs[slot][0]);
+    const int rc = lane_decode_ac_first(U, &rings, t);
     if (rc != kOk) R.status[un.img] = rc;
 }
 

@@ -32,6 +32,7 @@ struct LevelList {
     Unit* d_units = nullptr; uint32_t n = 0; int kind = 0;
     int shape = 0;                                                               // DC first scans: dc_shape of the units
     RefineScan* d_refine = nullptr; uint32_t n_refine = 0, refine_grid_x = 0;   // phase 2 of an AC refinement launch
+    LaneJob* d_jobs = nullptr; uint32_t n_jobs = 0;                              // the same units cut into jobs of a lane-per-unit kernel
 };
 
 struct Plan {                               // launch geometry for one scan group k
@@ -118,6 +119,7 @@ struct pcr_record {
     PixelTile* d_flat_rows = nullptr; uint32_t n_flat_rows = 0;     // ... and rows of cells (none if an image is too wide for k_pixel_flat_rows)
     uint32_t* d_dims = nullptr;             // [n][2] width, height (for kernels that run without a decode before them)
     bool prebuild_tables = false;           // some AC scan has restart intervals: k_build_tables runs before the entropy kernels
+    int lane_mode = 0;                      // pcr_set_lane_decoders: 0 by the number of units, 1 wherever possible, -1 never
     // decode fused with the training tail (allocated at its first call): one tile per MCU row, the side buffer of first
     // and last pixel rows, where each image's part of it starts, pixel rows per MCU row of every image
     PixelTile* d_tail_tiles = nullptr; uint32_t n_tail_tiles = 0;
@@ -212,6 +214,20 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
         for (size_t e = 0; e < l.size(); e++) units[e] = l[e].u;
         LevelList ll; ll.n = (uint32_t)units.size(); ll.kind = (int)((li / kDcShapes) % kNumKinds); ll.shape = (int)(li % kDcShapes);
         int rc = arena_upload(&r->big, &ll.d_units, units); if (rc) return rc;
+        if (ll.kind == kAcFirst) {
+            // jobs of the lane-per-unit kernel: up to 64 consecutive units with at most kLaneTabs different tables (the
+            // units of one scan lie together in the list)
+            std::vector<LaneJob> jobs;
+            uint32_t first = 0, tabs = 0;
+            for (uint32_t e = 0; e < ll.n; e++) {
+                const bool fresh = e == first || units[e].img != units[e - 1].img || units[e].scan != units[e - 1].scan;
+                if (e - first == (uint32_t)kEntropyLanes || (fresh && tabs == (uint32_t)kLaneTabs)) { jobs.push_back(LaneJob{first, e - first}); first = e; tabs = 0; }
+                if (fresh || e == first) tabs++;
+            }
+            if (ll.n > first) jobs.push_back(LaneJob{first, ll.n - first});
+            ll.n_jobs = (uint32_t)jobs.size();
+            rc = arena_upload(&r->big, &ll.d_jobs, jobs); if (rc) return rc;
+        }
         if (ll.kind == kAcRefine) {
             const size_t lv = li / kDcShapes / kNumKinds;
             const auto& rl = rlists[lv];
@@ -278,6 +294,16 @@ int add_call_times(const CallTiming& c, double* ms, uint32_t* marks) {
     return PCR_OK;
 }
 
+// One lane per unit or one wavefront per unit?  The lane decoders (pcr_lanes.h) are bound by the latency of one symbol
+// after another in the longest unit of a wavefront, the wavefront decoders by scalar instruction issue over all units:
+// with U units of S symbols each the first take about S x 700 cycles, the second U x S x 14 / 256, so the lanes win
+// from a few thousand units per launch on.  They read the Huffman tables from memory: the tables must be pre-built.
+constexpr uint32_t kLanesMinUnits = 8192;
+bool lanes_pay(const pcr_record* r, const LevelList& l) {
+    if (!r->prebuild_tables || r->lane_mode < 0 || l.n_jobs == 0) return false;
+    return r->lane_mode > 0 || (l.n >= kLanesMinUnits && l.n >= 32u * l.n_jobs);      // (jobs half full at least: few tables per 64 units)
+}
+
 // Steps 1-5 of the path (index .. entropy decode + refinement) for scans 1..k.
 // refine_in_memory: also run k_apply, which leaves the refined coefficients in the planes (the coefficient
 // export needs that; the pixel kernel replays the refinement itself from the lists of k_apply_prep).
@@ -325,7 +351,11 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
             mark(r, PCR_STAGE_DC_FIRST, s);
         }
         else if (l.kind == kSequential) { hipLaunchKernelGGL(k_sequential, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_SEQUENTIAL, s); }
-        else if (l.kind == kAcFirst) { hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64); mark(r, PCR_STAGE_AC_FIRST, s); }
+        else if (l.kind == kAcFirst) {
+            if (lanes_pay(r, l)) hipLaunchKernelGGL(k_ac_first_lanes, dim3(l.n_jobs), block, 0, s, r->d, l.d_units, l.d_jobs, c32);
+            else hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64);
+            mark(r, PCR_STAGE_AC_FIRST, s);
+        }
         else {
             hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64);
             mark(r, PCR_STAGE_AC_REFINE, s);
@@ -725,6 +755,12 @@ int pcr_reassemble(pcr_record* r, int i, int k, uint8_t* dst, size_t cap, size_t
     hipLaunchKernelGGL(k_gather, dim3(64), dim3(256), 0, 0, r->d, (uint32_t)i, have, add_eoi, r->d_gather);
     HIP_TRY(hipMemcpy(dst, r->d_gather, total, hipMemcpyDeviceToHost));
     *len = total;
+    return PCR_OK;
+}
+
+int pcr_set_lane_decoders(pcr_record* r, int mode) {
+    if (!r || mode < -1 || mode > 1) return PCR_E_ARG;
+    r->lane_mode = mode;
     return PCR_OK;
 }
 
