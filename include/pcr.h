@@ -369,9 +369,12 @@ int pcr_transcode_symbol_counts(const void* src_jpeg, size_t src_bytes, const in
 
 /* Shape of the entropy decoders (Section 4.2 of the paper: decoding is where the time goes).  A scan is cut into units
  * (restart intervals, entry-point units); a launch either gives every unit a wavefront that decodes it on the scalar
- * unit, or every unit a lane (64 units per wavefront).  mode 0 (default): by the number of units in the launch (lanes
- * from 8192 on); 1: lanes wherever the kernels exist and the record's scans have several units; -1: never.  The results
- * are the same bit for bit.  Takes effect from the next decode call.  PCR_E_ARG: null handle or another mode. */
+ * unit, or every unit a lane (64 units per wavefront).  Lanes need a fifth of the instructions but take longer per unit:
+ * they win when the GPU is shared between the decodes of several records, or when a launch has very many units.
+ * mode 0 (default): lanes for launches of at least 8192 units if the process has more than one record open, of at least
+ * 49152 units otherwise; 1: lanes wherever the kernels exist and the record's scans have several units; -1: never.
+ * The results are the same bit for bit.  Takes effect from the next decode call.  PCR_E_ARG: null handle or another
+ * mode. */
 int pcr_set_lane_decoders(pcr_record* rec, int mode);
 
 /* Stage timing with HIP events recorded on the call's own stream (off by default; switching it on

@@ -80,6 +80,7 @@ PCR_HD uint32_t clean_base(uint32_t data_off) { return (data_off + 3u) & ~3u; }
 __global__ void __launch_bounds__(256) k_index(DevRecord R, uint32_t kmax) {
     __shared__ uint32_t part[256];
     __shared__ uint32_t carry;
+    short_kernel_priority();
     uint32_t g = blockIdx.x;
     if (g >= kmax) return;
     uint64_t hb = ld_le64(R.rec + 16);
@@ -109,6 +110,7 @@ __global__ void __launch_bounds__(256) k_index(DevRecord R, uint32_t kmax) {
 // --------------------------------------------------------------------------------------
 // keep_status: a fidelity upgrade builds on planes decoded earlier; an image those calls found damaged stays so
 __global__ void __launch_bounds__(64) k_parse(DevRecord R, uint32_t kmax, uint32_t keep_status) {
+    short_kernel_priority();
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= R.n) return;
     parse_image(R.rec, R.off, R.len, R.n, i, R.nscans[i], kmax, &R.img[i], &R.scan[(size_t)i * R.G]);
@@ -372,31 +374,30 @@ PCR_D void lane_unit_setup(const DevRecord& R, const Unit& un, const uint32_t* _
     U->plane = R.coef + R.coef_off[un.img] + po;
     U->plane_elems = (uint32_t)img->bw[c] * img->bh[c] * 64;
     U->words = clean32 + (clean_base(sd->data_off) >> 2);
-    U->tab = &R.tabs[R.tab_idx[ig]];
+    U->tab = nullptr;                                         // (the kernel points it at the job's copy in LDS)
     U->ok = true;
 }
 
-// One job of a lane-per-unit kernel: units [first, first + count) of the launch's list, count <= 64.
-struct LaneJob { uint32_t first, count; };
-constexpr int kLaneTabs = 12;
-constexpr uint32_t kLaneTabWords = 272;                       // an AcTab up to (not including) its pre-packed look-up, rounded up
-static_assert(offsetof(AcTab, lutp) <= kLaneTabWords * 4, "the part of a table the lane decoders read");
+// One job of a lane-per-unit kernel: units [first, first + count) of the launch's list, count <= 64, and the scans they
+// belong to (image * scans per image + scan), kLaneTabs at most: one Huffman table each.
+constexpr int kLaneTabs = 8;
+struct LaneJob { uint32_t first, count, ntab; uint32_t key[kLaneTabs]; };
 
-// The AC tables of a job's lanes into LDS, one copy per distinct (image, scan) -- `key`, equal keys in neighbouring
-// lanes -- and this lane's slot (>= kLaneTabs: more tables than the job may have; the host never makes such a job).
-// Call with every lane of the wavefront.
-PCR_D uint32_t lane_table_slots(const DevRecord& R, uint32_t key, bool mine, uint32_t (*tabs)[kLaneTabWords]) {
+// The AC tables of a job into LDS (call with every lane of the wavefront) and the slot of the table of scan `key`
+// (>= kLaneTabs: not among the job's -- the host never makes such a job).
+PCR_D uint32_t lane_table_slots(const DevRecord& R, const LaneJob& job, uint32_t key, bool mine, uint32_t (*tabs)[kLaneTabWords]) {
     const uint32_t t = threadIdx.x;
-    const uint32_t prev = (uint32_t)__shfl_up((int)key, 1);
-    const uint64_t lead = __ballot(mine && (t == 0 || key != prev));
-    const uint32_t slot = (uint32_t)__popcll(lead & ((2ull << t) - 1ull)) - 1u;
-    uint64_t todo = lead;
-    for (uint32_t sl = 0; todo != 0 && sl < (uint32_t)kLaneTabs; sl++) {
-        const uint32_t leader = (uint32_t)__builtin_ctzll(todo);
-        todo &= todo - 1;
-        const uint32_t k = (uint32_t)__builtin_amdgcn_readlane((int)key, (int)leader);
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.tabs[R.tab_idx[k]]);
-        for (uint32_t e = t; e < kLaneTabWords; e += kEntropyLanes) tabs[sl][e] = src[e];
+    uint32_t slot = ~0u;
+#pragma unroll
+    for (uint32_t sl = 0; sl < (uint32_t)kLaneTabs; sl++) {
+        if (sl < job.ntab) {                                  // (the same for all lanes)
+            const uint32_t k = job.key[sl];
+            if (k < R.n * R.G) {
+                const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.tabs[R.tab_idx[k]]);
+                for (uint32_t e = t; e < kLaneTabWords; e += kEntropyLanes) tabs[sl][e] = src[e];
+                if (k == key) slot = sl;
+            }
+        }
     }
     __syncthreads();
     return mine ? slot : ~0u;
@@ -514,13 +515,35 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_first_lanes(DevRecord R, c
     const bool mine = t < job.count;
     Unit un = units[job.first + (mine ? t : 0u)];
     const uint32_t key = un.img * R.G + un.scan;
-    const uint32_t slot = lane_table_slots(R, key, mine, tabs);
+    const uint32_t slot = lane_table_slots(R, job, key, mine, tabs);
     LaneUnit U;
     U.ok = false;
     if (mine && slot < (uint32_t)kLaneTabs) lane_unit_setup(R, un, clean32, &U);
     if (!U.ok) return;
-    U.tab = reinterpret_cast<const AcTab*>(&tabs[slot][0]);
+    U.tab = reinterpret_cast<const LaneTab*>(&tabs[slot][0]);
     const int rc = lane_decode_ac_first(U, &rings, t);
+    if (rc != kOk) R.status[un.img] = rc;
+}
+
+// AC refinement scans with one lane per unit: as k_ac_first_lanes.  k_refine_history must have run for the scans of the
+// launch, k_refine_deal must follow.
+__global__ void __launch_bounds__(kEntropyLanes) k_ac_refine_lanes(DevRecord R, const Unit* __restrict__ units, const LaneJob* __restrict__ jobs,
+        const uint32_t* __restrict__ clean32) {
+    __shared__ uint32_t tabs[kLaneTabs][kLaneTabWords];
+    __shared__ LaneRing rings;
+    __shared__ LaneHistRing hring;
+    const LaneJob job = jobs[blockIdx.x];
+    const uint32_t t = threadIdx.x;
+    const bool mine = t < job.count;
+    Unit un = units[job.first + (mine ? t : 0u)];
+    const uint32_t key = un.img * R.G + un.scan;
+    const uint32_t slot = lane_table_slots(R, job, key, mine, tabs);
+    LaneUnit U;
+    U.ok = false;
+    if (mine && slot < (uint32_t)kLaneTabs) lane_unit_setup(R, un, clean32, &U);
+    if (!U.ok) return;
+    U.tab = reinterpret_cast<const LaneTab*>(&tabs[slot][0]);
+    const int rc = lane_decode_ac_refine(U, R.masks + R.mask_off[key], U.plane_elems >> 6, &rings, &hring, t);
     if (rc != kOk) R.status[un.img] = rc;
 }
 
@@ -600,6 +623,59 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
 
 // Phase 2 of AC refinement: one lane per block of the scan.  grid: (ceil(max blocks / 256), scans)
 struct RefineScan { uint32_t img; uint32_t scan; };
+
+// What the lane-per-unit refinement decoder needs before and after it, one lane per block of the scan (the grid of
+// k_refine_blocks).  k_refine_history: the kRefHist word of every block -- which positions of the band are non-zero
+// when the scan starts: what the AC first scans left in the coefficient plane, and what earlier refinement scans of the
+// band added (their kRefNz words).  k_refine_deal: the correction bits the decoder left in reading order go to the
+// history positions they belong to (kRefPlus as every consumer reads it).
+PCR_D bool refine_block_of_lane(const DevRecord& R, const RefineScan& a, size_t* ig_out, uint32_t* blk_out, uint32_t* plane_out) {
+    if (R.status[a.img] != kOk) return false;
+    const ImgDesc* img = &R.img[a.img];
+    const size_t ig = (size_t)a.img * R.G + a.scan;
+    const int c = R.scan[ig].comp[0];
+    const uint32_t cw = img->cw[c], ncov = cw * img->ch[c];
+    const uint32_t b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= ncov) return false;
+    const uint32_t bw = img->bw[c];
+    *ig_out = ig; *blk_out = (b / cw) * bw + (b % cw); *plane_out = bw * img->bh[c];
+    return true;
+}
+__global__ void __launch_bounds__(256) k_refine_history(DevRecord R, const RefineScan* __restrict__ rs) {
+    short_kernel_priority();
+    const RefineScan a = rs[blockIdx.y];
+    size_t ig; uint32_t blk, plane;
+    if (!refine_block_of_lane(R, a, &ig, &blk, &plane)) return;
+    const ImgDesc* img = &R.img[a.img];
+    const ScanDesc* sd = &R.scan[ig];
+    const int c = sd->comp[0];
+    size_t po = 0;
+    for (int q = 0; q < c; q++) po += (size_t)img->bw[q] * img->bh[q] * 64;
+    const uint4* src = reinterpret_cast<const uint4*>(R.coef + R.coef_off[a.img] + po + (size_t)blk * 64);
+    const uint32_t q0 = sd->Ss >> 3, q1 = sd->Se >> 3;       // the 16-byte chunks the band touches
+    uint64_t m = 0;
+#pragma unroll
+    for (uint32_t q = 0; q < 8; q++) {
+        if (q < q0 || q > q1) continue;
+        const uint4 v = src[q];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        uint32_t bits = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) bits |= ((w[j] & 0xFFFFu) ? 1u : 0u) << (2 * j) | ((w[j] >> 16) ? 2u : 0u) << (2 * j);
+        m |= (uint64_t)bits << (8 * q);
+    }
+    for (uint32_t q = 0; q < sd->nhist && q < (uint32_t)kMaxHist; q++)
+        m |= R.masks[R.mask_off[(size_t)a.img * R.G + sd->hist[q]] + (size_t)kRefNz * plane + blk];
+    R.masks[R.mask_off[ig] + (size_t)kRefHist * plane + blk] = m & band_mask(sd->Ss, sd->Se);
+}
+__global__ void __launch_bounds__(256) k_refine_deal(DevRecord R, const RefineScan* __restrict__ rs) {
+    short_kernel_priority();
+    const RefineScan a = rs[blockIdx.y];
+    size_t ig; uint32_t blk, plane;
+    if (!refine_block_of_lane(R, a, &ig, &blk, &plane)) return;
+    uint64_t* rec = R.masks + R.mask_off[ig] + blk;
+    rec[(size_t)kRefPlus * plane] = deal_bits(rec[(size_t)kRefPlus * plane], rec[(size_t)kRefHist * plane]);
+}
 
 __global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const RefineScan* rs) {
     __shared__ AcTab tab;

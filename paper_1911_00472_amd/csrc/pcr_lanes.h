@@ -22,6 +22,22 @@ namespace pcr {
 
 #if defined(__HIPCC__)
 
+// The part of an AcTab (pcr_entropy.h) a lane decoder reads: everything before the pre-packed look-up of the window
+// readers.  A wavefront keeps one per scan its lanes decode in LDS, and LDS is what bounds the number of resident
+// wavefronts.
+struct LaneTab {
+    uint16_t lut[256];
+    uint16_t lut2[128];
+    uint32_t limit[9];
+    uint16_t valptr[8];
+    uint32_t sh2;
+    uint8_t huffval[256];
+};
+constexpr uint32_t kLaneTabWords = sizeof(LaneTab) / 4;
+static_assert(sizeof(LaneTab) == 1080 && offsetof(AcTab, lutp) >= sizeof(LaneTab) && offsetof(AcTab, lut2) == offsetof(LaneTab, lut2) &&
+              offsetof(AcTab, limit) == offsetof(LaneTab, limit) && offsetof(AcTab, valptr) == offsetof(LaneTab, valptr) &&
+              offsetof(AcTab, sh2) == offsetof(LaneTab, sh2) && offsetof(AcTab, huffval) == offsetof(LaneTab, huffval), "a LaneTab is the head of an AcTab");
+
 // What a lane needs to know about its unit (AC scans: one component).
 struct LaneUnit {
     const uint32_t* words;        // the scan's unstuffed data as big-endian words
@@ -30,7 +46,7 @@ struct LaneUnit {
     uint32_t bw;                  // blocks per row of the (padded) plane
     uint32_t Ss, Se, Al;
     int16_t* plane; uint32_t plane_elems;
-    const AcTab* tab;
+    const LaneTab* tab;
     bool ok;
 };
 
@@ -69,10 +85,10 @@ struct LaneStream {
     PCR_D bool short_of(uint32_t words) const { return wr - wi < words; }
     PCR_D void init(const uint32_t* words, uint32_t bit0, uint32_t bit1, LaneRing* rings, uint32_t lane) {
         const uint32_t* first = words + (bit0 >> 5);
-        const uintptr_t a = reinterpret_cast<uintptr_t>(first);
-        base16 = reinterpret_cast<const uint4*>(a & ~(uintptr_t)15);
+        const uint32_t before = (uint32_t)(reinterpret_cast<uintptr_t>(first) & 15u) >> 2;   // words between the 16-byte boundary and the unit's first
+        base16 = reinterpret_cast<const uint4*>(first - before);     // (pointer arithmetic: the address stays a global one)
         ring = reinterpret_cast<uint32_t*>(&rings->chunk[0][lane]);
-        wi = (uint32_t)(a & 15) >> 2; wr = 0;
+        wi = before; wr = 0;
         refill();                                             // (wi < 4: all four chunks)
         const uint32_t off = bit0 & 31;
         const uint64_t buf = ((((uint64_t)ring_word(wi)) << 32) | ring_word(wi + 1)) << off;
@@ -94,21 +110,29 @@ struct LaneStream {
     }
 };
 
-// A code of more than 8 bits, by the canonical limits (pcr_entropy.h: limit[L - 8] is the first left-aligned 16-bit
-// value that is not a code of length <= L): its length is 9 + the number of limits at or below it; no branches, since
-// some lane of 64 meets such a code in every other symbol.  Returns (length << 8) | symbol, or 0 if it is no code.
-PCR_D uint32_t lane_long_code(const AcTab* t, uint32_t win) {
-    const uint32_t c16 = win >> 16;
-    uint32_t L = 9, below = t->limit[0];                      // below: the limit under the code's length
+// A code of more than 8 bits.  Some lane of 64 meets one in most trips, so the common case is kept short: the second
+// look-up (pcr_entropy.h: indexed by the distance from the first long code, scaled to 128 entries) resolves every long
+// code that owns a whole entry; the few that do not go through the canonical limits -- limit[L - 8] is the first
+// left-aligned 16-bit value that is not a code of length <= L, so the length is 9 + the number of limits at or below
+// the code.  Returns (length << 8) | symbol, or 0 if it is no code.
+PCR_D uint32_t lane_long_code(const LaneTab* t, uint32_t win) {
+    const uint32_t c16 = win >> 16, lim8 = t->limit[0];
+    const uint32_t i2 = (c16 - lim8) >> t->sh2;
+    const bool longer = c16 >= lim8;
+    uint32_t e = (longer && i2 < 128u) ? t->lut2[i2 & 127u] : 0u;
+    if (longer && e == 0) {
+        uint32_t L = 9, below = lim8;
 #pragma unroll
-    for (int q = 1; q <= 7; q++) {
-        const uint32_t lim = t->limit[q];
-        const bool over = c16 >= lim;
-        L += over ? 1u : 0u; below = over ? lim : below;
+        for (int q = 1; q <= 7; q++) {
+            const uint32_t lim = t->limit[q];
+            const bool over = c16 >= lim;
+            L += over ? 1u : 0u; below = over ? lim : below;
+        }
+        const uint32_t idx = t->valptr[L - 9] + ((c16 - below) >> (16 - L));
+        const uint32_t sym = t->huffval[idx & 255u];
+        e = (c16 < t->limit[8] && idx < 256u) ? (L << 8) | sym : 0u;
     }
-    const uint32_t idx = t->valptr[L - 9] + ((c16 - below) >> (16 - L));
-    const uint32_t sym = t->huffval[idx & 255u];
-    return (c16 < t->limit[8] && idx < 256u) ? (L << 8) | sym : 0u;
+    return e;
 }
 
 // AC first scan (one component, band Ss..Se, point transform Al) of one unit.  Every coefficient the unit's symbols
@@ -160,6 +184,111 @@ PCR_D int lane_decode_ac_first(const LaneUnit& U, LaneRing* rings, uint32_t lane
             col -= q * mcu_w; base += q * row_skip;
             while (col >= mcu_w) { col -= mcu_w; base += row_skip; }
         }
+    }
+    return bad ? kEFormat : kOk;
+}
+
+// ---------------------------------------------------------------------------------------
+// AC refinement scan of one unit, complete in one pass: where the new coefficients go, their signs, and the correction
+// bits.  The history of a block (which positions of the band are non-zero already) is read from the kRefHist word of
+// the block's record, which k_refine_history has written for every block of the scan beforehand; like the stream
+// words it comes through a small ring in LDS that all lanes fill at once.  Per block the lane leaves
+//   [kRefNz]    positions that become non-zero,   [kRefSign]  their signs (1 = positive),
+//   [kRefPlus]  the block's correction bits IN READING ORDER (first bit read = bit 0): k_refine_deal moves them to the
+//               history positions they belong to afterwards, one lane per block.
+// One trip of the loop is one symbol with the correction bits that follow it, or one block inside an end-of-band run
+// (correction bits only).
+// ---------------------------------------------------------------------------------------
+constexpr uint32_t kHistRing = 4;
+struct LaneHistRing { uint64_t h[kHistRing][64]; };
+
+PCR_D int lane_decode_ac_refine(const LaneUnit& U, uint64_t* recs, uint32_t nblk, LaneRing* rings, LaneHistRing* hring, uint32_t lane) {
+    LaneStream st;
+    st.init(U.words, U.bit0, U.bit1, rings, lane);
+    const uint32_t Ss = U.Ss, Se = U.Se, mcu_w = U.mcu_w, row_skip = U.bw - mcu_w;
+    const uint64_t band = band_mask((int)Ss, (int)Se);
+    const uint32_t total = U.mcu1 - U.mcu0;
+    uint32_t left = total;                                    // blocks of the unit not finished yet (the current one included)
+    const uint32_t row0 = U.mcu0 / mcu_w;
+    uint32_t col = U.mcu0 - row0 * mcu_w, blk = row0 * U.bw + col;
+    const uint64_t* hist = recs + (size_t)kRefHist * nblk;
+    // the cursor of the history fetches runs ahead of the decoder's
+    uint32_t fcol = col, fblk = blk, fetched = 0, used_up = 0;
+    auto fetch_history = [&]() {                              // every lane: as many blocks' words as its ring has room for
+        static_assert(kHistRing == 4, "the entries are spelled out (an array indexed in a loop ends up in scratch memory)");
+        uint32_t room = kHistRing - (fetched - used_up);
+        room = room < total - fetched ? room : total - fetched;
+        uint32_t b0 = fblk, b1, b2, b3;
+        auto step = [&](uint32_t b) { uint32_t n = b + 1; fcol++; if (fcol == mcu_w) { fcol = 0; n += row_skip; } return n; };
+        const uint32_t c0 = fcol;
+        b1 = step(b0); b2 = step(b1); b3 = step(b2); const uint32_t b4 = step(b3);
+        // (blocks past the unit's last are not read: the index is held at the last one wanted)
+        const uint32_t l1 = room > 1 ? b1 : b0, l2 = room > 2 ? b2 : l1, l3 = room > 3 ? b3 : l2;
+        const uint64_t v0 = hist[room > 0 ? b0 : blk];
+        const uint64_t v1 = hist[room > 0 ? l1 : blk], v2 = hist[room > 0 ? l2 : blk], v3 = hist[room > 0 ? l3 : blk];
+        if (room > 0) hring->h[(fetched + 0) & 3u][lane] = v0;
+        if (room > 1) hring->h[(fetched + 1) & 3u][lane] = v1;
+        if (room > 2) hring->h[(fetched + 2) & 3u][lane] = v2;
+        if (room > 3) hring->h[(fetched + 3) & 3u][lane] = v3;
+        // the cursor moves on by `room` blocks
+        fblk = room == 0 ? b0 : (room == 1 ? b1 : (room == 2 ? b2 : (room == 3 ? b3 : b4)));
+        uint32_t fc = c0 + room;
+        while (fc >= mcu_w) fc -= mcu_w;
+        fcol = fc;
+        fetched += room;
+    };
+    fetch_history();
+    uint64_t h = hring->h[0][lane] & band, z = band & ~h;
+    used_up = 1;
+    uint64_t newm = 0, sgn = 0, corr = 0;
+    uint32_t ncorr = 0, k = Ss, eobrun = 0, bad = 0;
+    while (left != 0) {
+        if (__any(st.short_of(4) || (fetched == used_up && fetched < total))) { st.refill(); fetch_history(); }
+        uint32_t pos = Se;                                    // inside an end-of-band run: every correction of the block, nothing else
+        bool endb = true;
+        if (eobrun == 0) {
+            st.top_up();
+            const uint32_t win = st.window();
+            uint32_t e = U.tab->lut[win >> 24];
+            if (e == 0) e = lane_long_code(U.tab, win);
+            bad |= e == 0 ? 1u : 0u;
+            e = e ? e : (1u << 8);
+            const uint32_t len = e >> 8, r = (e >> 4) & 15u, s = e & 15u;
+            bad |= s > 1 ? 1u : 0u;                           // sizes above 1 do not exist in a refinement scan
+            const bool coef = s != 0, eob = s == 0 && r != 15u;
+            const uint32_t extra = ((win << len) >> 1) >> (31u - (eob ? r : 0u));   // the length bits of an end-of-band run
+            const uint32_t sign = (win << len) >> 31;
+            // a coefficient takes the (r + 1)-th zero from k on, sixteen zeros land on the sixteenth (and leave it zero)
+            const int p = nth_set_bit(z & (~0ull << k), coef ? r + 1u : 16u, 64);
+            bad |= (coef && p == 64) ? 1u : 0u;               // a new coefficient with no zero left to take
+            pos = (eob || p == 64) ? Se : (uint32_t)p;
+            const uint64_t bit = coef ? 1ull << pos : 0ull;
+            newm |= bit; sgn |= sign ? bit : 0ull;
+            eobrun = eob ? (1u << r) + extra : 0u;
+            st.consume(len + (coef ? 1u : (eob ? r : 0u)));
+            endb = eob;
+        }
+        // the correction bits of the history positions from k to pos
+        uint32_t m = (uint32_t)__builtin_popcountll(h & (~0ull << k) & ((2ull << pos) - 1ull));
+        while (m) {
+            st.top_up();
+            const uint32_t t = m < 31u ? m : 31u;
+            corr |= (uint64_t)(bitrev32(st.window()) & ((1u << t) - 1u)) << ncorr;
+            ncorr += t; m -= t;
+            st.consume(t);
+        }
+        k = pos + 1;
+        bad |= st.remain < 0 ? 1u : 0u;
+        if (endb || k > Se) {                                 // the block is complete
+            uint64_t* rec = recs + blk;
+            rec[(size_t)kRefNz * nblk] = newm; rec[(size_t)kRefSign * nblk] = sgn; rec[(size_t)kRefPlus * nblk] = corr;
+            eobrun -= eobrun ? 1u : 0u;                       // (a run counts the block it starts in)
+            left--;
+            blk++; if (++col == mcu_w) { col = 0; blk += row_skip; }
+            if (left != 0) { h = hring->h[used_up & 3u][lane] & band; used_up++; z = band & ~h; }
+            newm = 0; sgn = 0; corr = 0; ncorr = 0; k = Ss;
+        }
+        if (bad) left = 0;                                    // stop at the first damaged block
     }
     return bad ? kEFormat : kOk;
 }

@@ -7,6 +7,7 @@
 #include <unistd.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cstring>
 #include <map>
@@ -99,7 +100,14 @@ struct CallTiming {
     size_t used = 0;                           // events recorded by the call that last used this slot
 };
 
+// Records this process has open: the default choice between the two shapes of entropy decoder looks at it (lanes_pay).
+static std::atomic<int> g_open_records{0};
+
 struct pcr_record {
+    pcr_record() { g_open_records.fetch_add(1, std::memory_order_relaxed); }
+    ~pcr_record() { g_open_records.fetch_sub(1, std::memory_order_relaxed); }
+    pcr_record(const pcr_record&) = delete;
+    pcr_record& operator=(const pcr_record&) = delete;
     int device = 0;
     size_t nbytes = 0;
     RecordHeader hdr{};
@@ -120,6 +128,8 @@ struct pcr_record {
     uint32_t* d_dims = nullptr;             // [n][2] width, height (for kernels that run without a decode before them)
     bool prebuild_tables = false;           // some AC scan has restart intervals: k_build_tables runs before the entropy kernels
     int lane_mode = 0;                      // pcr_set_lane_decoders: 0 by the number of units, 1 wherever possible, -1 never
+    std::vector<uint32_t> ent_off_h;        // record offset of every scan's entry points (0: none), as uploaded
+    std::vector<uint32_t> unit_bits;        // records opened from host bytes: entropy-coded bits of every unit, by slot (else empty)
     // decode fused with the training tail (allocated at its first call): one tile per MCU row, the side buffer of first
     // and last pixel rows, where each image's part of it starts, pixel rows per MCU row of every image
     PixelTile* d_tail_tiles = nullptr; uint32_t n_tail_tiles = 0;
@@ -167,7 +177,7 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
     if (it != r->plans.end()) { *out = &it->second; return PCR_OK; }
     const uint32_t n = r->hdr.n, G = r->hdr.G;
     Plan plan;
-    struct Item { Unit u; uint32_t bytes; };
+    struct Item { Unit u; uint32_t bytes; uint32_t bits; };      // bytes: the scan's mean per unit; bits: the unit's own, if known
     // one list per (dependency level, kind of scan, DC decoder shape: 0 for the AC kinds)
     std::vector<std::vector<Item>> lists((size_t)r->max_level * kNumKinds * kDcShapes);
     std::vector<std::vector<RefineScan>> rlists(r->max_level); std::vector<uint32_t> rmax(r->max_level, 0);
@@ -198,7 +208,8 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
             }
             const uint32_t cnt = r->slot_cnt[ig];
             for (uint32_t j = 0; j < cnt; j++)
-                lists[((size_t)(r->level[ig] - 1) * kNumKinds + kind) * kDcShapes + shape].push_back(Item{Unit{i, g, j, r->slot_base[ig]}, sd.data_len / cnt});
+                lists[((size_t)(r->level[ig] - 1) * kNumKinds + kind) * kDcShapes + shape].push_back(
+                    Item{Unit{i, g, j, r->slot_base[ig]}, sd.data_len / cnt, r->unit_bits.empty() ? sd.data_len / cnt * 8 : r->unit_bits[r->slot_base[ig] + j]});
         }
         if (have_dc != (1u << r->img[i].nc) - 1u) plan.dc_complete = false;
         for (int c = 0; c < r->img[i].nc; c++) if (refine[c]) {
@@ -210,21 +221,37 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
         auto& l = lists[li];
         if (l.empty()) continue;
         std::stable_sort(l.begin(), l.end(), [](const Item& a, const Item& b) { return a.bytes > b.bytes; });   // longest first
+        const int kind_of_list = (int)((li / kDcShapes) % kNumKinds);
+        std::vector<LaneJob> jobs;
+        if (kind_of_list == kAcFirst || kind_of_list == kAcRefine) {
+            // Jobs of the lane-per-unit kernels.  A wavefront takes as long as its longest lane, and it holds kLaneTabs
+            // Huffman tables: the list (scan after scan, the scans ordered by their mean unit) is cut into windows of
+            // kLaneTabs scans, the units of a window are ordered by their own length, and every 64 of them are a job.
+            size_t w0 = 0;
+            while (w0 < l.size()) {
+                LaneJob proto{}; size_t w1 = w0;
+                while (w1 < l.size()) {
+                    const uint32_t key = l[w1].u.img * G + l[w1].u.scan;
+                    if (proto.ntab == 0 || proto.key[proto.ntab - 1] != key) {
+                        if (proto.ntab == (uint32_t)kLaneTabs) break;
+                        proto.key[proto.ntab++] = key;
+                    }
+                    w1++;
+                }
+                std::stable_sort(l.begin() + w0, l.begin() + w1, [](const Item& a, const Item& b) { return a.bits > b.bits; });
+                for (size_t e = w0; e < w1; e += kEntropyLanes) {
+                    LaneJob j = proto;
+                    j.first = (uint32_t)e; j.count = (uint32_t)std::min<size_t>(kEntropyLanes, w1 - e);
+                    jobs.push_back(j);
+                }
+                w0 = w1;
+            }
+        }
         std::vector<Unit> units(l.size());
         for (size_t e = 0; e < l.size(); e++) units[e] = l[e].u;
-        LevelList ll; ll.n = (uint32_t)units.size(); ll.kind = (int)((li / kDcShapes) % kNumKinds); ll.shape = (int)(li % kDcShapes);
+        LevelList ll; ll.n = (uint32_t)units.size(); ll.kind = kind_of_list; ll.shape = (int)(li % kDcShapes);
         int rc = arena_upload(&r->big, &ll.d_units, units); if (rc) return rc;
-        if (ll.kind == kAcFirst) {
-            // jobs of the lane-per-unit kernel: up to 64 consecutive units with at most kLaneTabs different tables (the
-            // units of one scan lie together in the list)
-            std::vector<LaneJob> jobs;
-            uint32_t first = 0, tabs = 0;
-            for (uint32_t e = 0; e < ll.n; e++) {
-                const bool fresh = e == first || units[e].img != units[e - 1].img || units[e].scan != units[e - 1].scan;
-                if (e - first == (uint32_t)kEntropyLanes || (fresh && tabs == (uint32_t)kLaneTabs)) { jobs.push_back(LaneJob{first, e - first}); first = e; tabs = 0; }
-                if (fresh || e == first) tabs++;
-            }
-            if (ll.n > first) jobs.push_back(LaneJob{first, ll.n - first});
+        if (!jobs.empty()) {
             ll.n_jobs = (uint32_t)jobs.size();
             rc = arena_upload(&r->big, &ll.d_jobs, jobs); if (rc) return rc;
         }
@@ -294,14 +321,21 @@ int add_call_times(const CallTiming& c, double* ms, uint32_t* marks) {
     return PCR_OK;
 }
 
-// One lane per unit or one wavefront per unit?  The lane decoders (pcr_lanes.h) are bound by the latency of one symbol
-// after another in the longest unit of a wavefront, the wavefront decoders by scalar instruction issue over all units:
-// with U units of S symbols each the first take about S x 700 cycles, the second U x S x 14 / 256, so the lanes win
-// from a few thousand units per launch on.  They read the Huffman tables from memory: the tables must be pre-built.
-constexpr uint32_t kLanesMinUnits = 8192;
+// One lane per unit or one wavefront per unit?  The wavefront decoders are bound by scalar instruction issue over all
+// units of a launch (about 14 instructions per symbol, 256 issued per cycle), the lane decoders (pcr_lanes.h) by the
+// latency of one symbol after another in the longest unit of a wavefront (about a microsecond per symbol), with a
+// fifth of the instructions in total.  A launch that has the GPU to itself is therefore faster with lanes only from
+// about 50 000 units on (measured on 1024-image records: the AC first scans yes, the refinement levels no); a launch
+// that shares the GPU with the decodes of other records (other streams) already from a few thousand, because what it
+// leaves idle the others use: four records in flight decode 1.7 times faster with lanes.  The library cannot see what
+// else runs on the device; it takes the number of records the process has open as the sign of it.
+// The lane kernels read the Huffman tables from memory: the tables must be pre-built.
+constexpr uint32_t kLanesMinUnitsShared = 8192, kLanesMinUnitsAlone = 49152;
 bool lanes_pay(const pcr_record* r, const LevelList& l) {
     if (!r->prebuild_tables || r->lane_mode < 0 || l.n_jobs == 0) return false;
-    return r->lane_mode > 0 || (l.n >= kLanesMinUnits && l.n >= 32u * l.n_jobs);      // (jobs half full at least: few tables per 64 units)
+    if (r->lane_mode > 0) return true;
+    const uint32_t least = g_open_records.load(std::memory_order_relaxed) > 1 ? kLanesMinUnitsShared : kLanesMinUnitsAlone;
+    return l.n >= least && l.n >= 32u * l.n_jobs;            // (jobs half full at least: few tables per 64 units)
 }
 
 // Steps 1-5 of the path (index .. entropy decode + refinement) for scans 1..k.
@@ -355,6 +389,14 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
             if (lanes_pay(r, l)) hipLaunchKernelGGL(k_ac_first_lanes, dim3(l.n_jobs), block, 0, s, r->d, l.d_units, l.d_jobs, c32);
             else hipLaunchKernelGGL(k_ac_first, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64);
             mark(r, PCR_STAGE_AC_FIRST, s);
+        }
+        else if (lanes_pay(r, l)) {
+            const dim3 per_block(l.refine_grid_x, l.n_refine);
+            hipLaunchKernelGGL(k_refine_history, per_block, dim3(256), 0, s, r->d, l.d_refine);
+            hipLaunchKernelGGL(k_ac_refine_lanes, dim3(l.n_jobs), block, 0, s, r->d, l.d_units, l.d_jobs, c32);
+            mark(r, PCR_STAGE_AC_REFINE, s);
+            hipLaunchKernelGGL(k_refine_deal, per_block, dim3(256), 0, s, r->d, l.d_refine);
+            mark(r, PCR_STAGE_REFINE_BLOCKS, s);
         }
         else {
             hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64);
@@ -508,6 +550,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     if (!rc) rc = arena_upload(&r->big, &d_dctab_idx, dctab_idx);
     if (!rc) rc = arena_alloc(&r->big, &d.dctabs, (size_t)ndctabs);
     d.dctab_idx = d_dctab_idx;
+    r->ent_off_h = ent_off; r->unit_bits.clear();
     uint32_t* d_ent_off = nullptr;
     if (!rc) rc = arena_upload(&r->big, &d_ent_off, ent_off);
     d.ent_off = d_ent_off;
@@ -539,6 +582,33 @@ static int alloc_descriptor_buffers(pcr_record* r, hipStream_t s) {
     d.len = (const uint32_t*)(d.rec + hdr_len_pos(n, G, 0, 0));
     d.nscans = (const uint32_t*)(d.rec + hdr_nscans_pos(n, G, 0));
     return rc;
+}
+
+// Entropy-coded bits of every unit, for records whose bytes the host has: the entry points say where the units of a scan
+// start (the lane-per-unit kernels put units of like length into one wavefront).  Scans cut by restart markers, whose
+// intervals only the unstuff kernel finds, get their mean.
+static void measure_units(pcr_record* r, const uint8_t* bytes, size_t nbytes) {
+    const uint32_t n = r->hdr.n, G = r->hdr.G;
+    size_t slots = 0;
+    for (size_t ig = 0; ig < (size_t)n * G; ig++) slots = std::max<size_t>(slots, (size_t)r->slot_base[ig] + r->slot_cnt[ig] + 1);
+    r->unit_bits.assign(slots, 0);
+    for (uint32_t i = 0; i < n; i++) {
+        for (uint32_t g = 0; g < r->img[i].nscans && g < r->hdr.k_avail; g++) {
+            const size_t ig = (size_t)i * G + g;
+            const uint32_t cnt = r->slot_cnt[ig], sb = r->slot_base[ig], eo = r->ent_off_h[ig];
+            const uint64_t all = (uint64_t)r->scan[ig].data_len * 8;
+            if (eo && cnt > 1 && (size_t)eo + (size_t)kEntryBytes * (cnt - 1) <= nbytes) {
+                uint64_t prev = 0;
+                for (uint32_t j = 0; j < cnt; j++) {
+                    const uint64_t end = j + 1 < cnt ? ld_le32(bytes + eo + (size_t)kEntryBytes * j + 4) : std::max<uint64_t>(all, prev);
+                    r->unit_bits[sb + j] = (uint32_t)std::min<uint64_t>(end > prev ? end - prev : 0, 0xFFFFFFFFu);
+                    prev = std::max(prev, end);
+                }
+            } else {
+                for (uint32_t j = 0; j < cnt; j++) r->unit_bits[sb + j] = (uint32_t)(all / std::max<uint32_t>(cnt, 1));
+            }
+        }
+    }
 }
 
 int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out) {
@@ -573,6 +643,7 @@ int pcr_open(const void* bytes_, size_t nbytes, int device_id, pcr_record** out)
     if (!rc && hipMemset(r->d_rec + nbytes, 0, 64) != hipSuccess) rc = PCR_E_DEVICE;
     if (!rc) { r->d.rec = r->d_rec; rc = alloc_descriptor_buffers(r, nullptr); }
     if (!rc) rc = finish_open(r, nullptr);
+    if (!rc) measure_units(r, bytes, nbytes);
     if (!rc && hipStreamSynchronize(nullptr) != hipSuccess) rc = PCR_E_DEVICE;
     if (rc) { (void)hipGetLastError(); pcr_close(r); return rc; }
     *out = r;

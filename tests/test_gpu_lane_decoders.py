@@ -91,11 +91,17 @@ def test_damaged_data_gives_the_same_status_and_touches_no_other_image():
 
 
 def test_headline_record_takes_the_lane_decoders_by_itself():
-    """1024 images with an entry about every 128 MCUs: tens of thousands of units per launch, so the default mode takes
-    the lane decoders; the output must be what the wavefront decoders give."""
+    """1024 images with an entry about every 128 MCUs: tens of thousands of units per launch.  With a second record open
+    the default mode takes the lane decoders for every AC launch, with this record alone for the AC first scans only;
+    either way the output must be what the wavefront decoders give."""
     torch = _torch()
     _, files = pcrgen.make_workload("imagenet_like", limit=1024)
     rec = pkg.record_write_indexed(files, (np.arange(1024) * 7919) % 1000, 128)
+    for companions in (1, 0):
+        _headline_record(torch, rec, [pkg.pcr_open(pcrgen.write_record(files[:2]), 0) for _ in range(companions)])
+
+
+def _headline_record(torch, rec, others):
     with pkg.pcr_open(rec, 0) as r:
         for k in (2, 5, 10):
             r.set_lane_decoders(0)
@@ -108,3 +114,5 @@ def test_headline_record_takes_the_lane_decoders_by_itself():
         c = r.decode_coefficients(10).clone()
         r.set_lane_decoders(-1)
         assert torch.equal(c, r.decode_coefficients(10))
+    for o in others:
+        o.close()
