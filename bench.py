@@ -43,22 +43,30 @@ WORKLOAD_SCAN_GROUPS = {"imagenet_like": tuple(range(1, 11)), "rgb256": tuple(ra
                         "hires1024": (1, 5, 10), "ham_like": tuple(range(1, 11))}
 TABLE_SCAN_GROUPS = (1, 2, 5, 10)     # the scan groups the paper tabulates (Tables 1 and 2)
 
+VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane operations/s
+                                                    # (the chip's 157.3 TFLOP/s of packed fp32 FMA is this figure x 2 x 2)
+
 # rocprofv3 counters of the kernels of ONE decode of record 0 of the default workload at scan group 10, read off the
 # summaries under profiles/ (which give the commands).  FETCH_SIZE reads 0.5 KiB per KiB a plain copy kernel fetches
 # and WRITE_SIZE 1.0 (profiles/), so fetched bytes are the counter x 2.  They describe the kernels as they stood when
 # the counters were taken: an entry is removed (-> null in the output) whenever its kernel changes.
 PMC = {
-    # mean of the two launches of one decode (profiles/decode_kernels_imagenet_like_k10_counters.md)
-    "ac_refine": {"salu": 743.0e6, "valu": 235.8e6, "fetch_bytes": 544.0e6, "write_bytes": 81.3e6,
-                  "source": "profiles/decode_kernels_imagenet_like_k10_counters.md (SQ_INSTS_SALU, SQ_INSTS_VALU, FETCH_SIZE x 2.0, WRITE_SIZE x 1.0)"},
 }
 # all kernels of that decode, same counter run
-RECORD0_INSTS = {"scalar": 2668.5e6, "vector": 1417.3e6}
+RECORD0_INSTS = None
 
-# The serial chain of one Huffman-coded symbol in this design, at the very least: fetch the packed word of the current
-# bit offset, test it, take its length, add it to the position, apply the position update, test for the end of the
-# block and of the window (8 scalar operations); everything else a symbol needs is data-parallel work of the lanes.
+# The work of one Huffman-coded symbol, at the very least.
+# One wavefront per unit (pcr_entropy.h): the serial chain -- fetch the packed word of the current bit offset, test it,
+# take its length, add it to the position, apply the position update, test for the end of the block and of the window
+# (8 scalar operations); everything else a symbol needs is data-parallel work of the lanes.
 CHAIN_OPS_PER_SYMBOL = 8
+# One lane per unit (pcr_lanes.h), in operations of that lane.  AC first scan: window, table index, look-up, split the
+# entry into length / run / size (3), the appended bits (2), their sign extension (3), position, element address (2),
+# point transform, store, buffer advance (3), end-of-band test (2): 21.  AC refinement: window, index, look-up, split
+# (3), zeros from the position on (2), the n-th of them by halving a 64-bit mask (6 x 3), the new coefficient's bit and
+# sign (4), the history positions passed: mask and count (4), their correction bits: extract and merge (5), buffer
+# advance (3), position, end-of-block test: 46.
+LANE_OPS_PER_SYMBOL = {"ac_first": 21, "ac_refine": 46}
 
 
 def read_scan_script(jpeg):
@@ -138,6 +146,8 @@ def stage_of(scan):
 class Job:
     """One workload resident on the device: handles, output buffers, one stream per record."""
 
+    lane_decoders = 0                                       # --lane-decoders: pcr_set_lane_decoders of every handle (0: the library's choice)
+
     def __init__(self, torch, pkg, records, on_device=False):
         self.torch, self.pkg, self.records = torch, pkg, records
         t0 = time.perf_counter()
@@ -150,6 +160,8 @@ class Job:
             self.handles = [pkg.pcr_open(r, 0) for r in records]
         torch.cuda.synchronize()
         self.open_ms = (time.perf_counter() - t0) * 1e3 / len(records)
+        for h in self.handles:
+            h.set_lane_decoders(Job.lane_decoders)
         self.outs = [torch.empty(int(h.output_layout()[-1]), dtype=torch.uint8, device="cuda") for h in self.handles]
         self.streams = [torch.cuda.Stream() for _ in self.handles]          # default priority
         self.n_img = sum(h.n for h in self.handles)
@@ -211,23 +223,48 @@ def per_launch(d):
     return {n: (ms / launches if launches else 0.0) for n, (ms, launches) in d.items()}
 
 
-def dominant_kernel_roofline(workload, k, script, symbols0, ends0, alone, calls, over, probe, default_config):
-    """Roofline object for the kernel with the largest share of a record's decode at scan group k."""
+def dominant_kernel_roofline(workload, k, script, symbols0, ends0, alone, calls, over, probe, default_config, lanes):
+    """Roofline object for the kernel with the largest share of a record's decode at scan group k.  lanes: the AC scans were
+    decoded with one lane per unit (else one wavefront per unit)."""
     stage_ms = {n: ms / calls for n, (ms, launches) in alone.items()}
     name = max(stage_ms, key=lambda n: stage_ms[n])
     launches_per_call = max(1, alone[name][1] // calls)
     ms = alone[name][0] / max(1, alone[name][1])
     over_ms = per_launch(over)[name]
     entropy = name in ("dc_first", "ac_first", "ac_refine", "sequential")
+    by_lane = lanes and name in LANE_OPS_PER_SYMBOL
     scans = [g for g, sc in enumerate(script[:k]) if stage_of(sc) == name]
     sizes = np.diff(np.concatenate([np.zeros((ends0.shape[0], 1), dtype=np.int64), ends0], axis=1), axis=1)
     alg_bytes = float(sum(sizes[:, g].sum() for g in scans)) / launches_per_call if entropy else None
     sym = (float(sum(symbols0[:, g].sum() for g in scans)) / launches_per_call) if (entropy and symbols0 is not None) else None
-    pmc = PMC.get(name) if default_config else None
-    out = {"kernel": "k_%s (record 0 decoded alone, mean of its %d launches per decode)" % (name, launches_per_call),
+    pmc = PMC.get(name + ("_lanes" if by_lane else "")) if default_config else None
+    out = {"kernel": "k_%s%s (record 0 decoded alone, mean of its %d launches per decode)" % (name, "_lanes" if by_lane else "", launches_per_call),
            "share_of_a_lone_record_decode": stage_ms[name] / sum(stage_ms.values()),
            "ms_per_launch": ms, "ms_per_launch_overlapped": over_ms, "peak_measured_G_scalar_insts_per_s": probe}
-    if entropy:
+    hbm_view = ({"algorithmic_bytes_per_launch": alg_bytes, "achieved_GBps": alg_bytes / (ms * 1e-3) / 1e9,
+                 "frac_of_8TBps": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "note": "the entropy-coded bytes of the launch's scans, read once"} if entropy else None)
+    if by_lane:
+        ops = LANE_OPS_PER_SYMBOL[name]
+        achieved = ops * sym / (ms * 1e-3) / 1e12 if sym else None
+        out.update({
+            "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TLANEOPS, "unit": "T lane operations/s",
+            "frac": achieved / VALU_PEAK_TLANEOPS if achieved else None,
+            "frac_is": "algorithmic vector-lane operations (symbols x %d operations of the lane that decodes them) / launch duration / vector "
+                       "ALU peak (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz).  A lane-per-unit launch on its own is bound by the latency of one "
+                       "symbol after another in its longest unit, not by issue: what it leaves idle the decodes of the other records use "
+                       "(ms_per_launch_overlapped; path_issue gives the whole step); `issued` gives the same launch by executed instructions" % ops,
+            "traffic": (pmc["fetch_bytes"] + pmc["write_bytes"]) if pmc else None,
+            "algorithmic": {"symbols_per_launch": sym, "lane_operations_per_symbol": ops,
+                            "symbols_per_s": sym / (ms * 1e-3) if sym else None,
+                            "source": "pcrgen.workload_symbol_counts (the encoder's own count of the Huffman-coded symbols of the scans of this launch)"},
+            "issued": ({"vector_insts_per_launch": pmc["valu"], "scalar_insts_per_launch": pmc["salu"],
+                        "vector_insts_per_symbol_per_lane": pmc["valu"] * 64 / sym if sym else None,
+                        "T_lane_operations_per_s": pmc["valu"] * 64 / (ms * 1e-3) / 1e12,
+                        "frac_of_peak": pmc["valu"] * 64 / (ms * 1e-3) / 1e12 / VALU_PEAK_TLANEOPS, "source": pmc["source"]} if pmc else None),
+            "hbm_view": hbm_view,
+        })
+    elif entropy:
         achieved = CHAIN_OPS_PER_SYMBOL * sym / (ms * 1e-3) / 1e9 if sym else None
         out.update({
             "bound": "alu", "achieved": achieved, "peak": SALU_PEAK_GINSTS, "unit": "G scalar operations/s",
@@ -243,9 +280,7 @@ def dominant_kernel_roofline(workload, k, script, symbols0, ends0, alone, calls,
                         "scalar_insts_per_symbol": pmc["salu"] / sym if sym else None,
                         "G_scalar_insts_per_s": pmc["salu"] / (ms * 1e-3) / 1e9,
                         "frac_of_peak": pmc["salu"] / (ms * 1e-3) / 1e9 / SALU_PEAK_GINSTS, "source": pmc["source"]} if pmc else None),
-            "hbm_view": {"algorithmic_bytes_per_launch": alg_bytes, "achieved_GBps": alg_bytes / (ms * 1e-3) / 1e9,
-                         "frac_of_8TBps": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "note": "the entropy-coded bytes of the launch's scans, read once"},
+            "hbm_view": hbm_view,
         })
     else:                                                   # a data-parallel kernel: bytes against HBM (achieved is filled in by the caller)
         out.update({"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
@@ -278,7 +313,7 @@ def measure_default_queues(records, k, steps, warmup):
         env = dict(os.environ)
         env.pop("GPU_MAX_HW_QUEUES", None)
         try:
-            out = subprocess.run([sys.executable, os.path.abspath(__file__), "--keep-queues", "--child-records", path, "--scan-group", str(k),
+            out = subprocess.run([sys.executable, os.path.abspath(__file__), "--keep-queues", "--child-records", path, "--scan-group", str(k), "--lane-decoders", str(Job.lane_decoders),
                                   "--steps", str(steps), "--warmup", str(warmup)], env=env, capture_output=True, text=True, timeout=300)
             return json.loads(out.stdout.strip().splitlines()[-1])
         except Exception as e:                              # the figure is a side note: never fail the benchmark over it
@@ -534,6 +569,9 @@ def main():
     ap.add_argument("--entry-interval", type=int, default=128, help="MCUs between the entry points the record writer stores (record version 2)")
     ap.add_argument("--only", action="store_true", help="time only the scan group of --scan-group (for profiler runs)")
     ap.add_argument("--extras", action="store_true", help="also: fidelity upgrades, training tail, similarity scores, baseline files, restart intervals")
+    ap.add_argument("--lane-decoders", type=int, default=0, choices=(-1, 0, 1),
+                    help="shape of the AC entropy decoders: 0 the library's choice (by units per launch and records open), 1 one lane per unit "
+                         "wherever possible, -1 one wavefront per unit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-default-queues", action="store_true", help="skip the child process that measures the step with HIP's default number of hardware queues")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -545,6 +583,7 @@ def main():
         print("bench.py measures one GPU: the decode path shards by record with no exchange between GPUs, "
               "and this build runs on a single MI355X; --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    Job.lane_decoders = args.lane_decoders
     if args.child_records:
         return child_main(args)
 
@@ -652,7 +691,11 @@ def main():
 
     default_config = name == "imagenet_like" and args.images is None and headline_k == 10
     nrec0 = job.handles[0].n
-    roofline, dom = dominant_kernel_roofline(name, headline_k, script, symbols0, ends[:nrec0], alone, calls, over, probe, default_config)
+    job.handles[0].decode_batch(headline_k, out=job.outs[0], stream=job.streams[0].cuda_stream)
+    torch.cuda.synchronize()
+    lane_launches, wave_launches = job.handles[0].last_decoder_shapes()
+    roofline, dom = dominant_kernel_roofline(name, headline_k, script, symbols0, ends[:nrec0], alone, calls, over, probe, default_config,
+                                             lane_launches > 0 and wave_launches == 0)
     if roofline["bound"] == "hbm":                            # data-parallel kernel: its algorithmic bytes for record 0
         ab0 = algorithmic_bytes(ends[:nrec0], shapes[:nrec0], script, sampling, headline_k)
         kb = {"pixel": ab0["touched"] + ab0["out"], "unstuff": 2 * ab0["compressed"]}.get(dom)
@@ -696,9 +739,13 @@ def main():
                           "by_scan_group": {k: v["hbm_roofline_frac"] for k, v in report.items()}},
         "path_issue": ({"scalar_insts_per_step": RECORD0_INSTS["scalar"] * len(records), "vector_insts_per_step": RECORD0_INSTS["vector"] * len(records),
                         "G_scalar_insts_per_s": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9,
-                        "frac_of_peak": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9 / SALU_PEAK_GINSTS,
-                        "frac_of_measured_peak": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9 / probe}
-                       if (default_config and RECORD0_INSTS) else None),
+                        "G_vector_insts_per_s": RECORD0_INSTS["vector"] * len(records) / sec / 1e9,
+                        "scalar_frac_of_peak": RECORD0_INSTS["scalar"] * len(records) / sec / 1e9 / SALU_PEAK_GINSTS,
+                        "vector_frac_of_peak": RECORD0_INSTS["vector"] * len(records) * 64 / sec / 1e12 / VALU_PEAK_TLANEOPS,
+                        "note": "instructions executed per step (rocprofv3, record 0 x records) over the step time; each unit issues "
+                                "614 G wavefront instructions/s at most", "source": RECORD0_INSTS["source"]}
+                       if (default_config and RECORD0_INSTS and lane_launches > 0 and wave_launches == 0) else None),
+        "ac_decoder_shape": {"lane_per_unit_launches": lane_launches, "wavefront_per_unit_launches": wave_launches},
         "roofline": roofline,
         "pixel_kernel": pixel_kernel,
         "cpu_baseline": cpu,

@@ -38,6 +38,7 @@ SYMBOLS = {
     "pcr_resident_scan_group": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
     "pcr_enable_stage_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
     "pcr_set_lane_decoders": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "pcr_last_decoder_shapes": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
     "pcr_last_stage_ms": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_float)]),
     "pcr_probe_scalar_issue_rate": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]),
     "pcr_stage_ms_history": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]),
@@ -333,6 +334,12 @@ class Record:
 
     def set_lane_decoders(self, mode):
         _check(lib().pcr_set_lane_decoders(self._h, int(mode)), "pcr_set_lane_decoders")
+
+    def last_decoder_shapes(self):
+        """(launches with one lane per unit, launches with one wavefront per unit) of the last decode call's AC scans."""
+        a, b = ctypes.c_int(0), ctypes.c_int(0)
+        _check(lib().pcr_last_decoder_shapes(self._h, ctypes.byref(a), ctypes.byref(b)), "pcr_last_decoder_shapes")
+        return a.value, b.value
 
     def enable_stage_timing(self, on=True):
         _check(lib().pcr_enable_stage_timing(self._h, 1 if on else 0), "pcr_enable_stage_timing")

@@ -651,18 +651,25 @@ __global__ void __launch_bounds__(256) k_refine_history(DevRecord R, const Refin
     const int c = sd->comp[0];
     size_t po = 0;
     for (int q = 0; q < c; q++) po += (size_t)img->bw[q] * img->bh[q] * 64;
-    const uint4* src = reinterpret_cast<const uint4*>(R.coef + R.coef_off[a.img] + po + (size_t)blk * 64);
-    const uint32_t q0 = sd->Ss >> 3, q1 = sd->Se >> 3;       // the 16-byte chunks the band touches
     uint64_t m = 0;
+    // An earlier refinement scan of the very same band has this word already: what it started from and what it added
+    // are what this scan starts from (16 bytes per block instead of the block's 128 bytes of coefficients).
+    const ScanDesc* first = sd->nhist ? &R.scan[(size_t)a.img * R.G + sd->hist[0]] : sd;
+    if (sd->nhist && first->Ss == sd->Ss && first->Se == sd->Se) {
+        m = R.masks[R.mask_off[(size_t)a.img * R.G + sd->hist[0]] + (size_t)kRefHist * plane + blk];
+    } else {
+        const uint4* src = reinterpret_cast<const uint4*>(R.coef + R.coef_off[a.img] + po + (size_t)blk * 64);
+        const uint32_t q0 = sd->Ss >> 3, q1 = sd->Se >> 3;   // the 16-byte chunks the band touches
 #pragma unroll
-    for (uint32_t q = 0; q < 8; q++) {
-        if (q < q0 || q > q1) continue;
-        const uint4 v = src[q];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-        uint32_t bits = 0;
+        for (uint32_t q = 0; q < 8; q++) {
+            if (q < q0 || q > q1) continue;
+            const uint4 v = src[q];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            uint32_t bits = 0;
 #pragma unroll
-        for (uint32_t j = 0; j < 4; j++) bits |= ((w[j] & 0xFFFFu) ? 1u : 0u) << (2 * j) | ((w[j] >> 16) ? 2u : 0u) << (2 * j);
-        m |= (uint64_t)bits << (8 * q);
+            for (uint32_t j = 0; j < 4; j++) bits |= ((w[j] & 0xFFFFu) ? 1u : 0u) << (2 * j) | ((w[j] >> 16) ? 2u : 0u) << (2 * j);
+            m |= (uint64_t)bits << (8 * q);
+        }
     }
     for (uint32_t q = 0; q < sd->nhist && q < (uint32_t)kMaxHist; q++)
         m |= R.masks[R.mask_off[(size_t)a.img * R.G + sd->hist[q]] + (size_t)kRefNz * plane + blk];

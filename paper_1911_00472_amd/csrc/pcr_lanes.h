@@ -108,6 +108,10 @@ struct LaneStream {
         hi = __builtin_amdgcn_alignbit(hi, lo, 32u - n);
         lo <<= n; have -= (int)n; remain -= (int)n;
     }
+    PCR_D void consume_any(uint32_t n) {                      // n in 0..31
+        hi = n ? __builtin_amdgcn_alignbit(hi, lo, 32u - n) : hi;
+        lo <<= n; have -= (int)n; remain -= (int)n;
+    }
 };
 
 // A code of more than 8 bits.  Some lane of 64 meets one in most trips, so the common case is kept short: the second
@@ -244,11 +248,12 @@ PCR_D int lane_decode_ac_refine(const LaneUnit& U, uint64_t* recs, uint32_t nblk
     uint32_t ncorr = 0, k = Ss, eobrun = 0, bad = 0;
     while (left != 0) {
         if (__any(st.short_of(4) || (fetched == used_up && fetched < total))) { st.refill(); fetch_history(); }
+        st.top_up();
+        const uint32_t win = st.window();
         uint32_t pos = Se;                                    // inside an end-of-band run: every correction of the block, nothing else
+        uint32_t used = 0;                                    // bits of the window the symbol takes
         bool endb = true;
         if (eobrun == 0) {
-            st.top_up();
-            const uint32_t win = st.window();
             uint32_t e = U.tab->lut[win >> 24];
             if (e == 0) e = lane_long_code(U.tab, win);
             bad |= e == 0 ? 1u : 0u;
@@ -265,17 +270,24 @@ PCR_D int lane_decode_ac_refine(const LaneUnit& U, uint64_t* recs, uint32_t nblk
             const uint64_t bit = coef ? 1ull << pos : 0ull;
             newm |= bit; sgn |= sign ? bit : 0ull;
             eobrun = eob ? (1u << r) + extra : 0u;
-            st.consume(len + (coef ? 1u : (eob ? r : 0u)));
+            used = len + (coef ? 1u : (eob ? r : 0u));
             endb = eob;
         }
-        // the correction bits of the history positions from k to pos
+        // the correction bits of the history positions from k to pos follow: mostly a few, inside the window still
         uint32_t m = (uint32_t)__builtin_popcountll(h & (~0ull << k) & ((2ull << pos) - 1ull));
-        while (m) {
-            st.top_up();
-            const uint32_t t = m < 31u ? m : 31u;
-            corr |= (uint64_t)(bitrev32(st.window()) & ((1u << t) - 1u)) << ncorr;
-            ncorr += t; m -= t;
-            st.consume(t);
+        if (used + m <= 31u) {
+            corr |= (uint64_t)(bitrev32(win << used) & ((1u << m) - 1u)) << ncorr;
+            ncorr += m;
+            st.consume_any(used + m);
+        } else {
+            st.consume_any(used);
+            while (m) {
+                st.top_up();
+                const uint32_t t = m < 31u ? m : 31u;
+                corr |= (uint64_t)(bitrev32(st.window()) & ((1u << t) - 1u)) << ncorr;
+                ncorr += t; m -= t;
+                st.consume(t);
+            }
         }
         k = pos + 1;
         bad |= st.remain < 0 ? 1u : 0u;

@@ -128,6 +128,7 @@ struct pcr_record {
     uint32_t* d_dims = nullptr;             // [n][2] width, height (for kernels that run without a decode before them)
     bool prebuild_tables = false;           // some AC scan has restart intervals: k_build_tables runs before the entropy kernels
     int lane_mode = 0;                      // pcr_set_lane_decoders: 0 by the number of units, 1 wherever possible, -1 never
+    int last_lane_launches = 0, last_wave_launches = 0;   // AC entropy launches of the last decode call, by decoder shape
     std::vector<uint32_t> ent_off_h;        // record offset of every scan's entry points (0: none), as uploaded
     std::vector<uint32_t> unit_bits;        // records opened from host bytes: entropy-coded bits of every unit, by slot (else empty)
     // decode fused with the training tail (allocated at its first call): one tile per MCU row, the side buffer of first
@@ -371,8 +372,10 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
     mark(r, PCR_STAGE_UNSTUFF, s);
     const uint32_t* c32 = reinterpret_cast<const uint32_t*>(r->d.clean);
     const uint64_t* h64 = r->d.masks;
+    r->last_lane_launches = r->last_wave_launches = 0;
     for (auto& l : plan->levels) {
         const dim3 grid(l.n), block(kEntropyLanes);
+        if (l.kind == kAcFirst || l.kind == kAcRefine) { if (lanes_pay(r, l)) r->last_lane_launches++; else r->last_wave_launches++; }
         if (l.kind == kDcFirst) {
             const uint32_t dcp = dc_to_planes ? 1u : 0u;
             switch (l.shape) {
@@ -393,6 +396,7 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
         else if (lanes_pay(r, l)) {
             const dim3 per_block(l.refine_grid_x, l.n_refine);
             hipLaunchKernelGGL(k_refine_history, per_block, dim3(256), 0, s, r->d, l.d_refine);
+            mark(r, PCR_STAGE_REFINE_BLOCKS, s);
             hipLaunchKernelGGL(k_ac_refine_lanes, dim3(l.n_jobs), block, 0, s, r->d, l.d_units, l.d_jobs, c32);
             mark(r, PCR_STAGE_AC_REFINE, s);
             hipLaunchKernelGGL(k_refine_deal, per_block, dim3(256), 0, s, r->d, l.d_refine);
@@ -832,6 +836,12 @@ int pcr_reassemble(pcr_record* r, int i, int k, uint8_t* dst, size_t cap, size_t
 int pcr_set_lane_decoders(pcr_record* r, int mode) {
     if (!r || mode < -1 || mode > 1) return PCR_E_ARG;
     r->lane_mode = mode;
+    return PCR_OK;
+}
+
+int pcr_last_decoder_shapes(pcr_record* r, int* lane_launches, int* wavefront_launches) {
+    if (!r || !lane_launches || !wavefront_launches) return PCR_E_ARG;
+    *lane_launches = r->last_lane_launches; *wavefront_launches = r->last_wave_launches;
     return PCR_OK;
 }
 

@@ -26,6 +26,8 @@ def _both_shapes(rec, ks, coef_ks=()):
                 r.set_lane_decoders(mode)
                 st = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
                 pix = r.decode_batch(k, status=st).clone()
+                lanes, waves = r.last_decoder_shapes()
+                assert (lanes == 0) if mode < 0 else (waves == 0 or lanes == 0), (mode, lanes, waves)   # (mode 1 without several units per scan: no lanes)
                 coef = r.decode_coefficients(k).clone() if k in coef_ks else None
                 res.append((pix, st.clone(), coef))
             (p0, s0, c0), (p1, s1, c1) = res
@@ -108,8 +110,13 @@ def _headline_record(torch, rec, others):
             st = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
             a = r.decode_batch(k, status=st).clone()
             assert (st.cpu().numpy() == 0).all()
+            levels = {2: 1, 5: 1, 10: 3}[k]                  # AC launches: the first scans, then one per refinement level
+            # (alone: only the launch of all four AC first scans, 53 thousand units, is large enough for lanes)
+            alone = {2: (0, 1), 5: (1, 0), 10: (1, 2)}[k]
+            assert r.last_decoder_shapes() == ((levels, 0) if others else alone), (k, r.last_decoder_shapes())
             r.set_lane_decoders(-1)
             assert torch.equal(a, r.decode_batch(k)), k
+            assert r.last_decoder_shapes() == (0, levels)
         r.set_lane_decoders(0)
         c = r.decode_coefficients(10).clone()
         r.set_lane_decoders(-1)
