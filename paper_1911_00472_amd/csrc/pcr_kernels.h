@@ -2,9 +2,12 @@
 //   k_index      scan-group index (prefix sums of region lengths)
 //   k_parse      JPEG marker parsing, one lane per image
 //   k_unstuff    byte un-stuffing + restart-interval location, one workgroup per (image, scan)
-//   k_dc_first, k_ac_first, k_ac_refine   progressive Huffman decode, one wavefront per restart
-//                interval of a scan (per scan where there are no restart markers)
+//   k_dc_first, k_ac_first, k_ac_refine   progressive Huffman decode, one wavefront per unit: a restart
+//                interval of a scan, or the stretch between two entry points of the record (the whole scan
+//                where there is neither)
 //   k_refine_blocks   second phase of AC refinement, one lane per block
+//   k_ac_first_lanes, k_ac_refine_lanes   the AC scans again with one LANE per unit (pcr_lanes.h), for launches
+//                with very many units; k_refine_history, k_refine_deal: per-block work before and after
 //   k_apply      data-parallel refinement (DC bits, AC corrections and new coefficients)
 //   k_pixel      de-quantise + IDCT + chroma replication + YCbCr->RGB + store
 //   k_gather     materialise an image's scan prefix (parity hook)
@@ -265,6 +268,8 @@ __global__ void __launch_bounds__(256) k_unstuff(DevRecord R, uint32_t kfrom, ui
 // wavefront makes every loop iteration pay for the union of all lanes' branches; one stream
 // per wavefront costs only the branch actually taken and lets thousands of streams interleave
 // on the SIMDs.  The host orders units by decreasing byte length (longest first).
+// (With tens of thousands of units per launch the balance tips: see pcr_lanes.h and the kernels
+// k_ac_first_lanes / k_ac_refine_lanes below, which the host takes for such launches.)
 // --------------------------------------------------------------------------------------
 constexpr int kEntropyLanes = 64;
 // clean32 and hist64 are R.clean and R.masks again, as separate restrict-qualified kernel arguments: the

@@ -20,7 +20,27 @@
 
 namespace pcr {
 
-#if defined(__HIPCC__)
+// The decoders below are compiled for the host as well (one "lane", plain arrays for the rings): the CPU tests run them
+// against the oracle and, on damaged input, under the sanitizers.
+#if !defined(__HIPCC__)
+struct uint4 { uint32_t x, y, z, w; };
+#endif
+// true if `v` holds in any lane of the wavefront that is still in the loop
+PCR_HD bool any_lane(bool v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __any(v) != 0;
+#else
+    return v;
+#endif
+}
+// bits [n, n + 32) of hi:lo counted from hi's top bit, n in 1..31 (one instruction on the device)
+PCR_HD uint32_t funnel(uint32_t hi, uint32_t lo, uint32_t n) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_alignbit(hi, lo, 32u - n);
+#else
+    return (uint32_t)((((uint64_t)hi << 32) | lo) >> (32u - n));
+#endif
+}
 
 // The part of an AcTab (pcr_entropy.h) a lane decoder reads: everything before the pre-packed look-up of the window
 // readers.  A wavefront keeps one per scan its lanes decode in LDS, and LDS is what bounds the number of resident
@@ -68,9 +88,9 @@ struct LaneStream {
     uint32_t wi, wr;              // next word to enter the buffer; the ring holds the words before wr (a multiple of 4)
     uint32_t hi, lo; int have;
     int remain;                   // bits of the unit not consumed yet (negative: the decoder ran past the end)
-    PCR_D uint32_t ring_word(uint32_t w) const { return ring[((w >> 2) & (kRingChunks - 1)) * 256u + (w & 3u)]; }
+    PCR_HD uint32_t ring_word(uint32_t w) const { return ring[((w >> 2) & (kRingChunks - 1)) * 256u + (w & 3u)]; }
     // Call with every lane that is still decoding; `mine`: this lane takes part.
-    PCR_D void refill() {
+    PCR_HD void refill() {
         const uint32_t room = (kRingWords - (wr - wi)) >> 2;  // whole chunks that fit
         const uint4* src = base16 + (wr >> 2);
         static_assert(kRingChunks == 4, "the chunks are spelled out (an array indexed in a loop ends up in scratch memory)");
@@ -82,8 +102,8 @@ struct LaneStream {
         if (room > 3) *reinterpret_cast<uint4*>(ring + ((c0 + 3) & 3u) * 256u) = v3;
         wr += room * 4;
     }
-    PCR_D bool short_of(uint32_t words) const { return wr - wi < words; }
-    PCR_D void init(const uint32_t* words, uint32_t bit0, uint32_t bit1, LaneRing* rings, uint32_t lane) {
+    PCR_HD bool short_of(uint32_t words) const { return wr - wi < words; }
+    PCR_HD void init(const uint32_t* words, uint32_t bit0, uint32_t bit1, LaneRing* rings, uint32_t lane) {
         const uint32_t* first = words + (bit0 >> 5);
         const uint32_t before = (uint32_t)(reinterpret_cast<uintptr_t>(first) & 15u) >> 2;   // words between the 16-byte boundary and the unit's first
         base16 = reinterpret_cast<const uint4*>(first - before);     // (pointer arithmetic: the address stays a global one)
@@ -96,20 +116,20 @@ struct LaneStream {
         have = 64 - (int)off; wi += 2;
         remain = (int)(bit1 - bit0);
     }
-    PCR_D void top_up() {
+    PCR_HD void top_up() {
         if (have <= 32) {                                     // (then lo is empty)
             const uint64_t t = (uint64_t)ring_word(wi) << (32 - have);
             hi |= (uint32_t)(t >> 32); lo = (uint32_t)t;
             have += 32; wi++;
         }
     }
-    PCR_D uint32_t window() const { return hi; }
-    PCR_D void consume(uint32_t n) {                          // n in 1..31
-        hi = __builtin_amdgcn_alignbit(hi, lo, 32u - n);
+    PCR_HD uint32_t window() const { return hi; }
+    PCR_HD void consume(uint32_t n) {                          // n in 1..31
+        hi = funnel(hi, lo, n);
         lo <<= n; have -= (int)n; remain -= (int)n;
     }
-    PCR_D void consume_any(uint32_t n) {                      // n in 0..31
-        hi = n ? __builtin_amdgcn_alignbit(hi, lo, 32u - n) : hi;
+    PCR_HD void consume_any(uint32_t n) {                      // n in 0..31
+        hi = n ? funnel(hi, lo, n) : hi;
         lo <<= n; have -= (int)n; remain -= (int)n;
     }
 };
@@ -119,7 +139,7 @@ struct LaneStream {
 // code that owns a whole entry; the few that do not go through the canonical limits -- limit[L - 8] is the first
 // left-aligned 16-bit value that is not a code of length <= L, so the length is 9 + the number of limits at or below
 // the code.  Returns (length << 8) | symbol, or 0 if it is no code.
-PCR_D uint32_t lane_long_code(const LaneTab* t, uint32_t win) {
+PCR_HD uint32_t lane_long_code(const LaneTab* t, uint32_t win) {
     const uint32_t c16 = win >> 16, lim8 = t->limit[0];
     const uint32_t i2 = (c16 - lim8) >> t->sh2;
     const bool longer = c16 >= lim8;
@@ -142,7 +162,7 @@ PCR_D uint32_t lane_long_code(const LaneTab* t, uint32_t win) {
 // AC first scan (one component, band Ss..Se, point transform Al) of one unit.  Every coefficient the unit's symbols
 // carry is stored (2 bytes); everything else in the plane was zero-filled before.  One symbol per trip, the three kinds
 // of symbol (coefficient after a run, sixteen zeros, end of band) told apart by selects.
-PCR_D int lane_decode_ac_first(const LaneUnit& U, LaneRing* rings, uint32_t lane) {
+PCR_HD int lane_decode_ac_first(const LaneUnit& U, LaneRing* rings, uint32_t lane) {
     LaneStream st;
     st.init(U.words, U.bit0, U.bit1, rings, lane);
     const uint32_t Ss = U.Ss, Se = U.Se, mcu_w = U.mcu_w;
@@ -154,7 +174,7 @@ PCR_D int lane_decode_ac_first(const LaneUnit& U, LaneRing* rings, uint32_t lane
     const float rcp_w = 1.0f / (float)mcu_w;
     uint32_t k = Ss, bad = 0;
     while (left != 0) {
-        if (__any(st.short_of(2))) st.refill();              // (a trip takes one word at most)
+        if (any_lane(st.short_of(2))) st.refill();              // (a trip takes one word at most)
         st.top_up();
         const uint32_t win = st.window();
         uint32_t e = U.tab->lut[win >> 24];
@@ -206,7 +226,7 @@ PCR_D int lane_decode_ac_first(const LaneUnit& U, LaneRing* rings, uint32_t lane
 constexpr uint32_t kHistRing = 4;
 struct LaneHistRing { uint64_t h[kHistRing][64]; };
 
-PCR_D int lane_decode_ac_refine(const LaneUnit& U, uint64_t* recs, uint32_t nblk, LaneRing* rings, LaneHistRing* hring, uint32_t lane) {
+PCR_HD int lane_decode_ac_refine(const LaneUnit& U, uint64_t* recs, uint32_t nblk, LaneRing* rings, LaneHistRing* hring, uint32_t lane) {
     LaneStream st;
     st.init(U.words, U.bit0, U.bit1, rings, lane);
     const uint32_t Ss = U.Ss, Se = U.Se, mcu_w = U.mcu_w, row_skip = U.bw - mcu_w;
@@ -247,7 +267,7 @@ PCR_D int lane_decode_ac_refine(const LaneUnit& U, uint64_t* recs, uint32_t nblk
     uint64_t newm = 0, sgn = 0, corr = 0;
     uint32_t ncorr = 0, k = Ss, eobrun = 0, bad = 0;
     while (left != 0) {
-        if (__any(st.short_of(4) || (fetched == used_up && fetched < total))) { st.refill(); fetch_history(); }
+        if (any_lane(st.short_of(4) || (fetched == used_up && fetched < total))) { st.refill(); fetch_history(); }
         st.top_up();
         const uint32_t win = st.window();
         uint32_t pos = Se;                                    // inside an end-of-band run: every correction of the block, nothing else
@@ -304,7 +324,5 @@ PCR_D int lane_decode_ac_refine(const LaneUnit& U, uint64_t* recs, uint32_t nblk
     }
     return bad ? kEFormat : kOk;
 }
-
-#endif  // __HIPCC__
 
 }  // namespace pcr

@@ -7,9 +7,15 @@
 #include <vector>
 #include "../../paper_1911_00472_amd/csrc/pcr_format.h"
 #include "../../paper_1911_00472_amd/csrc/pcr_entropy.h"
+#include "../../paper_1911_00472_amd/csrc/pcr_lanes.h"
 #include "../../paper_1911_00472_amd/csrc/pcr_pixel.h"
 
 using namespace pcr;
+
+// 0: the AC scans go through the one-wavefront-per-unit decoders (pcr_entropy.h); 1: through the one-lane-per-unit
+// decoders (pcr_lanes.h), with what k_refine_history and k_refine_deal do around them done here by plain loops
+static int g_lane_decoders = 0;
+extern "C" void emul_set_lane_decoders(int on) { g_lane_decoders = on; }
 
 // serial stand-in for the unstuff kernel: same rules (drop stuffed zeros, fill bytes and
 // restart markers, stop at any other marker, note interval starts)
@@ -74,12 +80,21 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
             }
         }
         const uint32_t total_bits = (uint32_t)clean.size() * 8;
-        clean.resize((clean.size() + 3) / 4 * 4 + 64, 0xFF);      // look-ahead slack
+        clean.resize((clean.size() + 3) / 4 * 4 + 256, 0xFF);     // look-ahead slack (the lane decoders fetch up to 28 words ahead)
         for (size_t e = 0; e + 3 < clean.size(); e += 4) { std::swap(clean[e], clean[e + 3]); std::swap(clean[e + 1], clean[e + 2]); }   // big-endian words
         int c0 = sd.comp[0];
         size_t plane = (size_t)img.bw[c0] * img.bh[c0];
         if (sd.Ss > 0 && sd.Ah) masks[g].assign(plane * kRefWords, 0);
         if (sd.Ss == 0 && sd.Ah > 0) continue;                     // DC refinement: applied below, in place
+        const bool by_lane = g_lane_decoders && sd.Ss > 0 && !is_sequential_scan(sd);
+        if (by_lane && sd.Ah) {                                    // (k_refine_history) what is non-zero in the band when the scan starts
+            const uint64_t band = band_mask(sd.Ss, sd.Se);
+            for (size_t blk = 0; blk < plane; blk++) {
+                uint64_t hm = nz_mask_of_block(coef.data() + poff[c0] + blk * 64, sd.Ss, sd.Se);
+                for (int q = 0; q < sd.nhist; q++) hm |= masks[sd.hist[q]][kRefNz * plane + blk];
+                masks[g][kRefHist * plane + blk] = hm & band;
+            }
+        }
         for (uint32_t j = 0; j < nint; j++) {
             LaneScan ls;
             ls.mcu_w = sd.mcu_w; ls.mcu0 = sd.ri ? j * sd.ri : 0;
@@ -121,6 +136,18 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 DcWindowReader dw; dw.init(reinterpret_cast<const uint32_t*>(clean.data()), byte_off, sub_bits, nbits, &dt[0], &dt[1], &dt[2], sd.ns, 0);
                 CoefSink dsink; dsink.init(coef.data(), (uint32_t)coef.size(), ls.Al);
                 rc = decode_dc_first(&dw, ls, &dsink);
+            } else if (by_lane) {
+                AcTab at; actab_build(&at, rec + sd.ac_off);
+                static LaneRing ring; static LaneHistRing hring;
+                LaneUnit U;
+                U.words = reinterpret_cast<const uint32_t*>(clean.data());
+                U.bit0 = byte_off * 8 + sub_bits; U.bit1 = byte_off * 8 + nbits;
+                U.mcu0 = ls.mcu0; U.mcu1 = ls.mcu1; U.mcu_w = sd.mcu_w; U.bw = img.bw[c0];
+                U.Ss = sd.Ss; U.Se = sd.Se; U.Al = sd.Al;
+                U.plane = cpl[0]; U.plane_elems = (uint32_t)plane * 64;
+                U.tab = reinterpret_cast<const LaneTab*>(&at); U.ok = true;
+                if (U.mcu0 >= U.mcu1 || U.mcu_w == 0) return kEFormat;
+                rc = sd.Ah == 0 ? lane_decode_ac_first(U, &ring, 0) : lane_decode_ac_refine(U, masks[g].data(), (uint32_t)plane, &ring, &hring, 0);
             } else {
                 AcTab at; actab_build(&at, rec + sd.ac_off); actab_pack(&at, sd.Ah == 0, 0, 1);
                 WindowReader wr; wr.init(reinterpret_cast<const uint32_t*>(clean.data()), byte_off, sub_bits, nbits, pos0, &at, sd.Ah == 0, 0, sd.Ah == 0);
@@ -143,6 +170,9 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
             }
             if (rc) return rc;
         }
+        if (by_lane && sd.Ah)                                      // (k_refine_deal) correction bits from reading order to their positions
+            for (size_t blk = 0; blk < plane; blk++)
+                masks[g][kRefPlus * plane + blk] = deal_bits(masks[g][kRefPlus * plane + blk], masks[g][kRefHist * plane + blk]);
     }
     // refinement, one coefficient at a time (mirrors refine_coefficient of the kernels)
     for (int c = 0; c < img.nc; c++) {

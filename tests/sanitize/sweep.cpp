@@ -1,7 +1,7 @@
 // Corruption sweep under AddressSanitizer / UndefinedBehaviorSanitizer, CPU only.  Reads a record file and the JPEG
 // files it was made of, damages copies of them in seeded ways (bit flips, byte runs, truncations, header fields), and
 // pushes every damaged copy through the host-side code that parses untrusted bytes: the CPU oracle, the library's
-// lane code as compiled for the CPU (marker parser, Huffman tables, scan decoders: emul_decode_record), and the
+// lane code as compiled for the CPU (marker parser, Huffman tables, scan decoders of both shapes: emul_decode_record), and the
 // library's record writer with its entry-point walk and scan splitter.  Nothing is checked but "no sanitizer
 // report": results of damaged input are allowed to be errors or garbage.  Test infrastructure only.
 #include <cstdint>
@@ -14,6 +14,7 @@
 
 extern "C" {
 int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int64_t want_img, int16_t* coef_out, uint8_t* pix_out, int* W, int* H, int* C);
+void emul_set_lane_decoders(int on);
 int orc_record_header(const uint8_t* rec, size_t nbytes, uint32_t* n, uint32_t* G, uint64_t* header_bytes, int* k_avail);
 typedef struct { int W, H, nc, hs[3], vs[3], bw[3], bh[3], nscans, progressive; } orc_info_t;
 int orc_record_image_info(const uint8_t* rec, size_t nbytes, uint32_t i, orc_info_t* info);
@@ -66,7 +67,10 @@ static void through_the_decoders(const std::vector<uint8_t>& rec) {
             if (!known) continue;
             (void)orc_decode_record_image(rec.data(), rec.size(), i, k, 0, 0, coef.data(), pix.data());
             int W = 0, H = 0, C = 0;
-            (void)emul_decode_record(rec.data(), rec.size(), k, (int64_t)i, coef.data(), pix.data(), &W, &H, &C);
+            for (int lanes = 0; lanes < 2; lanes++) {                    // both shapes of AC decoder (pcr_entropy.h, pcr_lanes.h)
+                emul_set_lane_decoders(lanes);
+                (void)emul_decode_record(rec.data(), rec.size(), k, (int64_t)i, coef.data(), pix.data(), &W, &H, &C);
+            }
         }
     }
 }

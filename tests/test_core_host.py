@@ -24,8 +24,12 @@ def emul():
     L = ctypes.CDLL(LIB)
     L.emul_decode_record.argtypes = [u8p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int64, ctypes.POINTER(ctypes.c_int16), u8p] + \
         [ctypes.POINTER(ctypes.c_int)] * 3
+    L.emul_set_lane_decoders.argtypes = [ctypes.c_int]
+    L.emul_set_lane_decoders.restype = None
 
-    def run(rec, i, k, info):
+    def run(rec, i, k, info, lanes=False):
+        """lanes: the AC scans through the one-lane-per-unit decoders (pcr_lanes.h) instead of the one-wavefront-per-unit ones."""
+        L.emul_set_lane_decoders(1 if lanes else 0)
         a = np.frombuffer(rec, np.uint8)
         coef = np.zeros(info.coef_count, np.int16)
         pix = np.zeros((info.H, info.W, info.nc), np.uint8)
@@ -38,14 +42,14 @@ def emul():
     return run
 
 
-def _compare(emul, rec, images, ks):
+def _compare(emul, rec, images, ks, lanes=False):
     for i in images:
         info = oracle.record_image_info(rec, i)
         for k in ks:
             c0, p0, _ = oracle.decode_record_image(rec, i, k)
-            c1, p1 = emul(rec, i, k, info)
-            assert np.array_equal(c0, c1), (i, k)
-            assert np.abs(p0.astype(int) - p1).max() <= 1, (i, k)
+            c1, p1 = emul(rec, i, k, info, lanes)
+            assert np.array_equal(c0, c1), (i, k, lanes)
+            assert np.abs(p0.astype(int) - p1).max() <= 1, (i, k, lanes)
 
 
 def test_lane_code_matches_oracle_small_colour(emul, rgb_small):
@@ -83,6 +87,31 @@ def test_lane_code_matches_oracle_extreme_coefficients(emul, extreme_record):
     rec, files = extreme_record
     G = oracle.record_header(rec)["G"]
     _compare(emul, rec, range(len(files)), range(1, G + 1))
+
+
+def test_lane_per_unit_decoders_match_oracle(emul, rgb_small, extreme_record):
+    """The second shape of AC decoder (one lane per unit, pcr_lanes.h; on the CPU one lane, plain arrays for its rings in
+    LDS): restart intervals, entry points at three intervals, the deep successive-approximation script, the extreme
+    planes, noisy images with long codes."""
+    from test_oracle_entropy import DEEP
+    import paper_1911_00472_amd as pkg
+    rec, files = rgb_small
+    _compare(emul, rec, range(len(files)), range(1, 11), lanes=True)
+    for interval in (5, 32, 128):
+        _compare(emul, pkg.record_write_indexed(files, None, interval), range(0, len(files), 2), (2, 5, 6, 9, 10), lanes=True)
+    deep = []
+    for i, (w, h) in enumerate([(50, 35), (90, 41), (33, 70)]):
+        img = pcrgen.synth(300 + i, 2, w, h, 3, 10.0)
+        deep.append(pcrgen.encode_pixels(img, 1, 1, 95, None, restart=i % 2))
+        deep.append(pcrgen.encode_pixels(img, 2, 1, 80, DEEP, restart=0))
+    for r in (pcrgen.write_record(deep), pkg.record_write_indexed(deep, None, 7)):
+        _compare(emul, r, range(len(deep)), range(1, len(DEEP) + 1), lanes=True)
+    rec, files = extreme_record
+    G = oracle.record_header(rec)["G"]
+    for r in (rec, pkg.record_write_indexed(files, None, 16)):
+        _compare(emul, r, range(len(files)), range(1, G + 1), lanes=True)
+    records, hfiles = pcrgen.make_workload("imagenet_like", limit=4)
+    _compare(emul, pkg.record_write_indexed(hfiles, None, 128), range(4), (2, 5, 6, 10), lanes=True)
 
 
 def test_lane_code_matches_oracle_sequential_files(emul):
