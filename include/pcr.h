@@ -332,15 +332,17 @@ int pcr_record_write(const void* const* files, const size_t* sizes, const int32_
 /* pcr_record_write with entry points (record version 2).  The paper's metadata says where every scan group starts;
  * its Section 4.2 names the decode as the bottleneck, and each scan of a stock file is one serial stream.  This
  * writer walks every scan once and stores, about every entry_interval MCUs of the scan (blocks, for a scan of one
- * component), a place where a decoder may start: a block boundary outside any end-of-band run, its bit offset in
- * the scan's data without the stuffed bytes, and the DC predictions there (16 bytes per entry, kept at the end of
- * the scan's own scan group, so a read at fidelity k brings only the entries of scans 1..k; about 1.5 % of the
- * record at an interval of 128).  The image bytes are those pcr_record_write writes, byte for byte, and every call
- * of this library gives the same results for both records; the decoder gives every entry a wavefront of its own
- * (as it does for restart intervals), which shortens the decode of a record without touching the files.  Scans with
- * restart markers and files the walk cannot follow get no entries.  entry_interval: 1 .. 2^20 (PCR_E_RANGE); other
- * arguments and errors as pcr_record_write; the size cannot be known before the walk: on PCR_E_RANGE *written says
- * how much is needed (sum of the file sizes + 2 % + the header always suffices for intervals of 64 and more). */
+ * component; every entry_interval / 2 in AC refinement scans, whose symbols take a decoder longest), a place where a
+ * decoder may start: a block boundary outside any end-of-band run, its bit offset in the scan's data without the
+ * stuffed bytes, and the DC predictions there (16 bytes per entry, kept at the end of the scan's own scan group, so a
+ * read at fidelity k brings only the entries of scans 1..k; about 2.2 % of a record of 100 kB photographs at an
+ * interval of 128).  The image bytes are those pcr_record_write writes, byte for byte, and every call of this library
+ * gives the same results for both records; the decoder makes every stretch between two entries a unit of its own -- a
+ * wavefront's or a lane's work, see pcr_set_lane_decoders -- as it does for restart intervals, which shortens the
+ * decode of a record without touching the files.  Scans with restart markers and files the walk cannot follow get no
+ * entries.  entry_interval: 1 .. 2^20 (PCR_E_RANGE); other arguments and errors as pcr_record_write; the size cannot
+ * be known before the walk: on PCR_E_RANGE *written says how much is needed (for photographs at usual qualities the
+ * sum of the file sizes + 5 % + the header suffices for intervals of 128 and more). */
 int pcr_record_write_indexed(const void* const* files, const size_t* sizes, const int32_t* labels, uint32_t n, uint32_t entry_interval,
                              void* out, size_t capacity, uint64_t* written);
 int pcr_transcode_progressive(const void* src_jpeg, size_t src_bytes, const int16_t* coef, size_t coef_count, uint32_t restart_interval,
@@ -372,7 +374,7 @@ int pcr_transcode_symbol_counts(const void* src_jpeg, size_t src_bytes, const in
  * unit, or every unit a lane (64 units per wavefront).  Lanes need a fifth of the instructions but take longer per unit:
  * they win when the GPU is shared between the decodes of several records, or when a launch has very many units.
  * mode 0 (default): lanes for launches of at least 8192 units if the process has more than one record open, of at least
- * 49152 units otherwise; 1: lanes wherever the kernels exist and the record's scans have several units; -1: never.
+ * 32768 units otherwise; 1: lanes wherever the kernels exist and the record's scans have several units; -1: never.
  * The results are the same bit for bit.  Takes effect from the next decode call.  PCR_E_ARG: null handle or another
  * mode. */
 int pcr_set_lane_decoders(pcr_record* rec, int mode);

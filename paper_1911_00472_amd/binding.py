@@ -410,12 +410,13 @@ def record_write(files, labels=None):
 
 def record_write_indexed(files, labels=None, entry_interval=128):
     """A version-2 record (bytes) from JPEG files: as record_write, plus entry points about every entry_interval MCUs
-    of every scan, which the decoder uses as it uses restart intervals (pcr_record_write_indexed)."""
+    of every scan (every entry_interval / 2 in AC refinement scans), which the decoder uses as it uses restart intervals
+    (pcr_record_write_indexed)."""
     bufs, ptrs, sizes = _file_table(files)
     lab = None if labels is None else np.ascontiguousarray(labels, np.int32)
     assert lab is None or lab.size == len(bufs)
     total = sum(b.size for b in bufs)
-    cap = total + total // 50 + 64 * 1024 + 64 * len(bufs) * 4
+    cap = total + total // 20 + 64 * 1024 + 64 * len(bufs) * 4
     written = ctypes.c_uint64(0)
     for _ in range(2):
         out = np.empty(cap, np.uint8)

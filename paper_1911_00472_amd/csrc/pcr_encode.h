@@ -191,13 +191,17 @@ inline int find_entry_points(const uint8_t* file, const uint64_t* ends, uint32_t
             int pred[kMaxComp] = {0, 0, 0};
             uint32_t eobrun = 0;
             const uint32_t m0 = sd.ri ? iv * sd.ri : 0, m1 = sd.ri ? std::min(m0 + sd.ri, sd.mcus) : sd.mcus;
-            uint32_t next_entry = interval;
+            // AC refinement scans get an entry every interval / 2: a symbol of theirs takes a decoder more than twice as
+            // long as one of a first scan (zero runs are counted against the block's history, correction bits follow), and
+            // a launch of the lane-per-unit decoders takes as long as its longest unit.
+            const uint32_t step = (!seq && sd.Ss > 0 && sd.Ah > 0 && interval >= 2) ? interval / 2 : interval;
+            uint32_t next_entry = step;
             for (uint32_t m = m0; m < m1 && !b.bad; m++) {
                 if (sd.ri == 0 && m >= next_entry && eobrun == 0 && E.size() < 65535) {
                     EntryPoint e; e.mcu = m; e.bit = (uint32_t)b.pos; e.zero = 0;
                     for (int j = 0; j < kMaxComp; j++) e.pred[j] = (int16_t)pred[j];
                     E.push_back(e);
-                    next_entry = (m / interval + 1) * interval;
+                    next_entry = (m / step + 1) * step;
                 }
                 if (seq || sd.Ss == 0) {                             // blocks of every scan component of the MCU
                     for (int j = 0; j < sd.ns && !b.bad; j++) {

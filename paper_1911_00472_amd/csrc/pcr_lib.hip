@@ -326,12 +326,13 @@ int add_call_times(const CallTiming& c, double* ms, uint32_t* marks) {
 // units of a launch (about 14 instructions per symbol, 256 issued per cycle), the lane decoders (pcr_lanes.h) by the
 // latency of one symbol after another in the longest unit of a wavefront (about a microsecond per symbol), with a
 // fifth of the instructions in total.  A launch that has the GPU to itself is therefore faster with lanes only from
-// about 50 000 units on (measured on 1024-image records: the AC first scans yes, the refinement levels no); a launch
-// that shares the GPU with the decodes of other records (other streams) already from a few thousand, because what it
-// leaves idle the others use: four records in flight decode 1.7 times faster with lanes.  The library cannot see what
+// some tens of thousands of units on (measured on 1024-image records with an entry every 128 MCUs, every 64 in refinement
+// scans: 53, 58 and 40 thousand units per launch, a record alone 5.4 ms against 6.6); a launch that shares the GPU with
+// the decodes of other records (other streams) already from a few thousand, because what it leaves idle the others use:
+// four records in flight decode twice as fast with lanes.  The library cannot see what
 // else runs on the device; it takes the number of records the process has open as the sign of it.
 // The lane kernels read the Huffman tables from memory: the tables must be pre-built.
-constexpr uint32_t kLanesMinUnitsShared = 8192, kLanesMinUnitsAlone = 49152;
+constexpr uint32_t kLanesMinUnitsShared = 8192, kLanesMinUnitsAlone = 32768;
 bool lanes_pay(const pcr_record* r, const LevelList& l) {
     if (!r->prebuild_tables || r->lane_mode < 0 || l.n_jobs == 0) return false;
     if (r->lane_mode > 0) return true;

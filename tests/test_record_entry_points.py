@@ -107,6 +107,19 @@ def test_entries_are_ordered_in_range_and_their_dc_predictions_are_the_previous_
             assert [x[1] for x in e] == sorted(x[1] for x in e)
 
 
+def test_refinement_scans_get_entries_twice_as_often():
+    """AC refinement scans are cut every interval / 2 (their symbols take a decoder longest): for the 10-scan script,
+    scan 10 (luma, last bit) has about twice the entries of scan 5 (luma 6..63, first pass) over the same blocks."""
+    _, files = pcrgen.make_workload("imagenet_like", limit=3)
+    ent, iv = _entries(pkg.record_write_indexed(files, None, 128))
+    assert iv == 128
+    for i in range(3):
+        first, refine = len(ent[(4, i)]), len(ent[(9, i)])
+        assert first >= 10 and 1.8 * first <= refine <= 2.2 * first + 2, (i, first, refine)
+        assert abs(len(ent[(5, i)]) - refine) <= 2                    # scan 6: the same blocks, refinement as well
+        assert abs(len(ent[(1, i)]) - first) <= 2                     # scan 2: the same blocks, a first scan
+
+
 def test_lane_code_started_at_the_entries_matches_the_oracle(emul):  # noqa: F811
     files = _files()
     for interval in (128, 7):
