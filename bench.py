@@ -390,7 +390,7 @@ def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms, k):
     chain = list(TABLE_SCAN_GROUPS)
     reps = max(2, args.steps // 2)
     acc = {(a, b): 0.0 for a, b in zip(chain[:-1], chain[1:])}
-    for it in range(reps + 1):                                   # the first round warms the plans up
+    for it in range(reps + 1):                                   # the first pass warms the plans up
         job.step(chain[0])
         torch.cuda.synchronize()
         for a, b in zip(chain[:-1], chain[1:]):

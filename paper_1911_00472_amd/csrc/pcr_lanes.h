@@ -33,6 +33,15 @@ PCR_HD bool any_lane(bool v) {
     return v;
 #endif
 }
+// Waits here for every load issued so far (device).  The wait the compiler would otherwise place at a loaded value's
+// first use -- or at the first re-use of its register -- can land inside the symbol loop, and a wait for a load is a wait
+// for every store issued before it as well: the loop would stand still for the round trip of its own stores in every
+// trip.  (s_waitcnt vmcnt(0); the other counters are left at their maxima.)
+PCR_HD void loads_arrived() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+#endif
+}
 // bits [n, n + 32) of hi:lo counted from hi's top bit, n in 1..31 (one instruction on the device)
 PCR_HD uint32_t funnel(uint32_t hi, uint32_t lo, uint32_t n) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -95,6 +104,7 @@ struct LaneStream {
         const uint4* src = base16 + (wr >> 2);
         static_assert(kRingChunks == 4, "the chunks are spelled out (an array indexed in a loop ends up in scratch memory)");
         const uint4 v0 = src[0], v1 = src[1], v2 = src[2], v3 = src[3];   // (all four: the data stays readable well past a unit's end)
+        loads_arrived();
         const uint32_t c0 = wr >> 2;
         if (room > 0) *reinterpret_cast<uint4*>(ring + ((c0 + 0) & 3u) * 256u) = v0;
         if (room > 1) *reinterpret_cast<uint4*>(ring + ((c0 + 1) & 3u) * 256u) = v1;
@@ -250,6 +260,7 @@ PCR_HD int lane_decode_ac_refine(const LaneUnit& U, uint64_t* recs, uint32_t nbl
         const uint32_t l1 = room > 1 ? b1 : b0, l2 = room > 2 ? b2 : l1, l3 = room > 3 ? b3 : l2;
         const uint64_t v0 = hist[room > 0 ? b0 : blk];
         const uint64_t v1 = hist[room > 0 ? l1 : blk], v2 = hist[room > 0 ? l2 : blk], v3 = hist[room > 0 ? l3 : blk];
+        loads_arrived();
         if (room > 0) hring->h[(fetched + 0) & 3u][lane] = v0;
         if (room > 1) hring->h[(fetched + 1) & 3u][lane] = v1;
         if (room > 2) hring->h[(fetched + 2) & 3u][lane] = v2;
