@@ -1,12 +1,12 @@
 // Entropy decoders with ONE LANE PER UNIT: the 64 lanes of a wavefront decode 64 different units (restart intervals or
-// entry-point units) of the same kind of scan, each lane with its own bit buffer, Huffman table (read from the tables
-// k_build_tables left in memory) and position in its image's coefficient plane.
+// entry-point units) of the same kind of scan, each lane with its own bit buffer, Huffman table (the wavefront's copy, in
+// LDS, of a table k_build_tables left in memory) and position in its image's coefficient plane.
 //
 // When they pay.  A wavefront that decodes one unit on the scalar ALU (pcr_entropy.h) spends about 14 scalar
 // instructions per symbol, and the chip issues 256 of those per cycle: a throughput bound that a record with tens of
 // thousands of units reaches.  A lane-per-unit wavefront is bound by latency instead: one symbol of every lane per trip
-// round a dependent chain (buffer -> table entry -> lengths -> buffer) of some hundred cycles, but 64 symbols per trip,
-// and the trips of the wavefronts resident on a SIMD overlap.  With U units the scan takes about
+// round a dependent chain (buffer -> table entry -> lengths -> buffer) of one to two thousand cycles, but 64 symbols per
+// trip, with a fifth of the instructions all told, and the trips of the wavefronts resident on a SIMD overlap.  With U units the scan takes about
 // (symbols of the longest unit) x (chain latency), whatever U is, as long as the U / 64 wavefronts are resident at
 // once; the host takes this path for launches with enough units (see lanes_pay in pcr_lib.hip) and the
 // one-wavefront-per-unit kernels otherwise (few long units: plain records, small records).
@@ -98,7 +98,7 @@ struct LaneStream {
     uint32_t hi, lo; int have;
     int remain;                   // bits of the unit not consumed yet (negative: the decoder ran past the end)
     PCR_HD uint32_t ring_word(uint32_t w) const { return ring[((w >> 2) & (kRingChunks - 1)) * 256u + (w & 3u)]; }
-    // Call with every lane that is still decoding; `mine`: this lane takes part.
+    // Call with every lane that is still decoding.
     PCR_HD void refill() {
         const uint32_t room = (kRingWords - (wr - wi)) >> 2;  // whole chunks that fit
         const uint4* src = base16 + (wr >> 2);
