@@ -1184,14 +1184,24 @@ PCR_HD int skim_ac_refine(WindowReader* wr, const LaneScan& ls, const HistPlanes
 // (every lane of a wavefront reads another block: these are plain vector loads), and takes a symbol's correction
 // bits out of the 32 bits it looked the symbol up in whenever they fit.
 
-// bits (first bit read = bit 0) dealt out to the set bits of `where`, lowest position first
-PCR_HD uint64_t deal_bits(uint64_t bits, uint64_t where) {
-    uint64_t out = 0;
+// bits (first bit read = bit 0) dealt out to the set bits of `where`, lowest position first.  The two 32-bit halves of
+// `where` are dealt to separately (the low half takes the first popcount(low half) bits): 64-bit shifts and carries
+// would double the work of every step.
+PCR_HD uint32_t deal_bits32(uint32_t bits, uint32_t where) {
+    uint32_t out = 0;
     while (where) {
-        out |= (bits & 1) << __builtin_ctzll(where);
-        where &= where - 1; bits >>= 1;
+        const uint32_t low = where & (0u - where);            // the lowest position left
+        out |= (bits & 1u) ? low : 0u;
+        where ^= low; bits >>= 1;
     }
     return out;
+}
+PCR_HD uint64_t deal_bits(uint64_t bits, uint64_t where) {
+    const uint32_t wlo = (uint32_t)where, whi = (uint32_t)(where >> 32);
+    const uint32_t nlo = (uint32_t)__builtin_popcount(wlo);
+    const uint32_t lo = deal_bits32((uint32_t)bits, wlo);
+    const uint32_t hi = deal_bits32((uint32_t)(nlo < 32 ? bits >> nlo : bits >> 32), whi);   // (at most 63 bits are ever dealt)
+    return ((uint64_t)hi << 32) | lo;
 }
 
 // position of the n-th (n = 1, 2, ...) set bit of z, or `none` if z has fewer: a binary search on population counts
