@@ -646,36 +646,52 @@ PCR_D bool refine_block_of_lane(const DevRecord& R, const RefineScan& a, size_t*
     *ig_out = ig; *blk_out = (b / cw) * bw + (b % cw); *plane_out = bw * img->bh[c];
     return true;
 }
+// k_refine_history works through the padded plane (blocks the image does not cover included: they hold zeros), 64
+// consecutive blocks -- 8 KB of coefficients -- per wavefront: lane i of step j loads 16-byte chunk 64 j + i of them, so
+// that every load instruction reads one contiguous kilobyte, turns its eight coefficients into eight mask bits, and leaves
+// the byte in LDS where the lane that owns the block picks up all eight.  grid: (ceil(max plane blocks / 256), scans).
 __global__ void __launch_bounds__(256) k_refine_history(DevRecord R, const RefineScan* __restrict__ rs) {
+    __shared__ __attribute__((aligned(8))) uint8_t bytes[4][64 * 8];
     short_kernel_priority();
     const RefineScan a = rs[blockIdx.y];
-    size_t ig; uint32_t blk, plane;
-    if (!refine_block_of_lane(R, a, &ig, &blk, &plane)) return;
+    if (R.status[a.img] != kOk) return;
     const ImgDesc* img = &R.img[a.img];
+    const size_t ig = (size_t)a.img * R.G + a.scan;
     const ScanDesc* sd = &R.scan[ig];
     const int c = sd->comp[0];
-    size_t po = 0;
-    for (int q = 0; q < c; q++) po += (size_t)img->bw[q] * img->bh[q] * 64;
+    const uint32_t plane = (uint32_t)img->bw[c] * img->bh[c];
+    if (blockIdx.x * 256 >= plane) return;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t blk0 = blockIdx.x * 256 + wave * 64, blk = blk0 + lane;
     uint64_t m = 0;
     // An earlier refinement scan of the very same band has this word already: what it started from and what it added
     // are what this scan starts from (16 bytes per block instead of the block's 128 bytes of coefficients).
     const ScanDesc* first = sd->nhist ? &R.scan[(size_t)a.img * R.G + sd->hist[0]] : sd;
-    if (sd->nhist && first->Ss == sd->Ss && first->Se == sd->Se) {
-        m = R.masks[R.mask_off[(size_t)a.img * R.G + sd->hist[0]] + (size_t)kRefHist * plane + blk];
+    const bool from_records = sd->nhist && first->Ss == sd->Ss && first->Se == sd->Se;
+    if (from_records) {
+        if (blk < plane) m = R.masks[R.mask_off[(size_t)a.img * R.G + sd->hist[0]] + (size_t)kRefHist * plane + blk];
     } else {
-        const uint4* src = reinterpret_cast<const uint4*>(R.coef + R.coef_off[a.img] + po + (size_t)blk * 64);
-        const uint32_t q0 = sd->Ss >> 3, q1 = sd->Se >> 3;   // the 16-byte chunks the band touches
+        size_t po = 0;
+        for (int q = 0; q < c; q++) po += (size_t)img->bw[q] * img->bh[q] * 64;
+        const uint4* src = reinterpret_cast<const uint4*>(R.coef + R.coef_off[a.img] + po) + (size_t)blk0 * 8;
+        const uint32_t chunk = lane & 7u;                     // (the same in every step: 64 is a multiple of 8)
+        const bool wanted = chunk >= (uint32_t)(sd->Ss >> 3) && chunk <= (uint32_t)(sd->Se >> 3);
 #pragma unroll
-        for (uint32_t q = 0; q < 8; q++) {
-            if (q < q0 || q > q1) continue;
-            const uint4 v = src[q];
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        for (uint32_t j = 0; j < 8; j++) {
+            const uint32_t e = j * 64 + lane;                 // chunk e & 7 of block blk0 + (e >> 3)
             uint32_t bits = 0;
+            if (wanted && blk0 + (e >> 3) < plane) {
+                const uint4 v = src[e];
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (uint32_t j = 0; j < 4; j++) bits |= ((w[j] & 0xFFFFu) ? 1u : 0u) << (2 * j) | ((w[j] >> 16) ? 2u : 0u) << (2 * j);
-            m |= (uint64_t)bits << (8 * q);
+                for (uint32_t q = 0; q < 4; q++) bits |= ((w[q] & 0xFFFFu) ? 1u : 0u) << (2 * q) | ((w[q] >> 16) ? 2u : 0u) << (2 * q);
+            }
+            bytes[wave][e] = (uint8_t)bits;
         }
     }
+    __syncthreads();
+    if (blk >= plane) return;
+    if (!from_records) m = *reinterpret_cast<const uint64_t*>(&bytes[wave][lane * 8]);
     for (uint32_t q = 0; q < sd->nhist && q < (uint32_t)kMaxHist; q++)
         m |= R.masks[R.mask_off[(size_t)a.img * R.G + sd->hist[q]] + (size_t)kRefNz * plane + blk];
     R.masks[R.mask_off[ig] + (size_t)kRefHist * plane + blk] = m & band_mask(sd->Ss, sd->Se);

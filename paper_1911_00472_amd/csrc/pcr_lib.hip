@@ -33,6 +33,7 @@ struct LevelList {
     Unit* d_units = nullptr; uint32_t n = 0; int kind = 0;
     int shape = 0;                                                               // DC first scans: dc_shape of the units
     RefineScan* d_refine = nullptr; uint32_t n_refine = 0, refine_grid_x = 0;   // phase 2 of an AC refinement launch
+    uint32_t plane_grid_x = 0;                                                   // ... counted in blocks of the padded planes (k_refine_history)
     LaneJob* d_jobs = nullptr; uint32_t n_jobs = 0;                              // the same units cut into jobs of a lane-per-unit kernel
 };
 
@@ -181,7 +182,7 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
     struct Item { Unit u; uint32_t bytes; uint32_t bits; };      // bytes: the scan's mean per unit; bits: the unit's own, if known
     // one list per (dependency level, kind of scan, DC decoder shape: 0 for the AC kinds)
     std::vector<std::vector<Item>> lists((size_t)r->max_level * kNumKinds * kDcShapes);
-    std::vector<std::vector<RefineScan>> rlists(r->max_level); std::vector<uint32_t> rmax(r->max_level, 0);
+    std::vector<std::vector<RefineScan>> rlists(r->max_level); std::vector<uint32_t> rmax(r->max_level, 0), rmax_plane(r->max_level, 0);
     std::vector<ApplyUnit> apply; uint32_t max_blk = 0;
     for (uint32_t i = 0; i < n; i++) {
         const uint32_t upto = std::min<uint32_t>(r->img[i].nscans, (uint32_t)k);
@@ -200,6 +201,7 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
             if (kind == kAcRefine) {
                 rlists[r->level[ig] - 1].push_back(RefineScan{i, g});
                 rmax[r->level[ig] - 1] = std::max<uint32_t>(rmax[r->level[ig] - 1], (uint32_t)r->img[i].cw[sd.comp[0]] * r->img[i].ch[sd.comp[0]]);
+                rmax_plane[r->level[ig] - 1] = std::max<uint32_t>(rmax_plane[r->level[ig] - 1], (uint32_t)r->img[i].bw[sd.comp[0]] * r->img[i].bh[sd.comp[0]]);
             }
             int shape = 0;
             if (kind == kDcFirst) {
@@ -259,7 +261,7 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
         if (ll.kind == kAcRefine) {
             const size_t lv = li / kDcShapes / kNumKinds;
             const auto& rl = rlists[lv];
-            ll.n_refine = (uint32_t)rl.size(); ll.refine_grid_x = (rmax[lv] + 255) / 256;
+            ll.n_refine = (uint32_t)rl.size(); ll.refine_grid_x = (rmax[lv] + 255) / 256; ll.plane_grid_x = (rmax_plane[lv] + 255) / 256;
             rc = arena_upload(&r->big, &ll.d_refine, rl); if (rc) return rc;
         }
         plan.levels.push_back(ll);
@@ -396,7 +398,7 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
         }
         else if (lanes_pay(r, l)) {
             const dim3 per_block(l.refine_grid_x, l.n_refine);
-            hipLaunchKernelGGL(k_refine_history, per_block, dim3(256), 0, s, r->d, l.d_refine);
+            hipLaunchKernelGGL(k_refine_history, dim3(l.plane_grid_x, l.n_refine), dim3(256), 0, s, r->d, l.d_refine);
             mark(r, PCR_STAGE_REFINE_BLOCKS, s);
             hipLaunchKernelGGL(k_ac_refine_lanes, dim3(l.n_jobs), block, 0, s, r->d, l.d_units, l.d_jobs, c32);
             mark(r, PCR_STAGE_AC_REFINE, s);
