@@ -939,14 +939,18 @@ __global__ void __launch_bounds__(256) k_crop_resize(const uint32_t* __restrict_
 //            whole 8x8 inverse DCT in registers: zig-zag order becomes register naming, the row and the column
 //            pass need no exchange between lanes, no LDS and no barrier.  The constant factors of the transform
 //            (1/2 per pass, cos(pi/4) on terms 0 and 4) are folded into the de-quantisation table.  The clamped
-//            samples go to LDS, MCU by MCU: per MCU the blocks of each component as one small row-major plane.
-//            A component that only has its DC writes one sample per block (the block is flat).
-//   phase B  chroma replication + colour + one rounding + store: one lane per group of 12 output bytes (4 RGB
+//            samples stay in the lane's registers.
+//   phase B  twice, for the upper and for the lower half of the pixel rows of the MCUs: the lanes put the part of
+//            their block that lies in the half into LDS, MCU by MCU (per MCU the rows of each component as one small
+//            row-major plane; a component that only has its DC writes one sample per block: the block is flat);
+//            then chroma replication + colour + one rounding + store: one lane per group of 12 output bytes (4 RGB
 //            pixels; 8 gray ones) of one pixel row of one MCU, lanes ordered along the image rows, the samples
 //            read from LDS as 16- and 8-byte vectors, the group written with one (possibly unaligned) store.
-// The kernel is bound by memory latency times occupancy, not by arithmetic, so the chain of dependent trips to
-// memory is kept short: the image's descriptor is read with scalar loads (no copy through LDS, no barrier), and
-// the coefficient loads are issued before the tables of the prologue are built.  (A decode without any AC scan goes
+// The kernel is bound by memory latency times occupancy, not by arithmetic.  Occupancy is bounded by LDS, which is
+// why the samples go through it in halves (128 bytes per lane at a time: four wavefronts per SIMD instead of two,
+// measured a third faster); and the chain of dependent trips to memory is kept short: the image's descriptor is read
+// with scalar loads (no copy through LDS, no barrier), and the coefficient loads are issued before the tables of the
+// prologue are built.  (A decode without any AC scan goes
 // through k_pixel_flat instead.)
 // The refinement is applied here, on the way in: the coefficient planes hold what the first scans wrote, and the
 // lane replays the component's refinement scans from the records the refinement kernels left (exactly what k_apply
@@ -956,7 +960,7 @@ __global__ void __launch_bounds__(256) k_crop_resize(const uint32_t* __restrict_
 // boxes (optional): one box per image; runs of MCUs that do not touch their image's box are skipped altogether
 // (their pixels are left as they are): for callers that go on to read only the boxes (pcr_decode_crop_batch).
 // --------------------------------------------------------------------------------------
-constexpr int kPixLanes = 128;             // blocks per workgroup (the samples of a run take kPixLanes * 256 bytes of LDS)
+constexpr int kPixLanes = 128;             // blocks per workgroup (the samples of half a run take kPixLanes * 128 bytes of LDS)
 
 struct PixelTile { uint32_t img; uint32_t mcu0; };          // first MCU of the run
 typedef short short8 __attribute__((ext_vector_type(8)));
@@ -1064,10 +1068,10 @@ PCR_D int pix_dc(const DevRecord& R, const PixBlock& B, int dcv, const ApplyList
         if (rlc->sc[e].Ss == 0 && dc_refinement_bit(R, rlc->sc[e], B.brow, B.bcol, B.hs, B.vs, B.covered)) dcv |= 1 << rlc->sc[e].Al;
     return dcv;
 }
-// Refinement replay, de-quantisation and the 8x8 inverse transform of the lane's block; the clamped samples go to
-// dst[y * row_len + x].  qc: the component's folded quantiser steps (zig-zag order); rlc: its refinement scan list.
+// Refinement replay, de-quantisation and the 8x8 inverse transform of the lane's block; the clamped samples are left in
+// F[8 y + x].  qc: the component's folded quantiser steps (zig-zag order); rlc: its refinement scan list.
 template <bool kRefine>
-PCR_D void pix_finish(const DevRecord& R, const PixBlock& B, const short8 v[8], const float* qc, const ApplyList* rlc, float* dst, uint32_t row_len) {
+PCR_D void pix_samples(const DevRecord& R, const PixBlock& B, const short8 v[8], const float* qc, const ApplyList* rlc, float F[64]) {
     int ci[64];
 #pragma unroll
     for (int ch = 0; ch < 8; ch++) {
@@ -1098,9 +1102,8 @@ PCR_D void pix_finish(const DevRecord& R, const PixBlock& B, const short8 v[8], 
             }
         }
     }
-    float F[64];                                             // natural order: F[8 v + u]
 #pragma unroll
-    for (int k4 = 0; k4 < 16; k4++) {
+    for (int k4 = 0; k4 < 16; k4++) {                        // natural order: F[8 v + u]
         const float4 qq = *reinterpret_cast<const float4*>(qc + 4 * k4);
         F[zigzag_lookup(4 * k4)] = (float)ci[4 * k4] * qq.x; F[zigzag_lookup(4 * k4 + 1)] = (float)ci[4 * k4 + 1] * qq.y;
         F[zigzag_lookup(4 * k4 + 2)] = (float)ci[4 * k4 + 2] * qq.z; F[zigzag_lookup(4 * k4 + 3)] = (float)ci[4 * k4 + 3] * qq.w;
@@ -1112,12 +1115,35 @@ PCR_D void pix_finish(const DevRecord& R, const PixBlock& B, const short8 v[8], 
     for (int x = 0; x < 8; x++)
         idct8_scaled(F[x], F[8 + x], F[16 + x], F[24 + x], F[32 + x], F[40 + x], F[48 + x], F[56 + x]);
 #pragma unroll
-    for (int y = 0; y < 8; y++) {
-        float4 lo, hi;
-        lo.x = clamp255(F[8 * y] + 128.f); lo.y = clamp255(F[8 * y + 1] + 128.f); lo.z = clamp255(F[8 * y + 2] + 128.f); lo.w = clamp255(F[8 * y + 3] + 128.f);
-        hi.x = clamp255(F[8 * y + 4] + 128.f); hi.y = clamp255(F[8 * y + 5] + 128.f); hi.z = clamp255(F[8 * y + 6] + 128.f); hi.w = clamp255(F[8 * y + 7] + 128.f);
-        *reinterpret_cast<float4*>(dst + y * row_len) = lo;
-        *reinterpret_cast<float4*>(dst + y * row_len + 4) = hi;
+    for (int e = 0; e < 64; e++) F[e] = clamp255(F[e] + 128.f);
+}
+// rows y0 .. y0 + kRows - 1 of the block's samples to dst[(y - y0) * row_len + x]
+template <int y0, int kRows>
+PCR_D void pix_put_rows(const float F[64], float* dst, uint32_t row_len) {
+#pragma unroll
+    for (int y = 0; y < kRows; y++) {
+        *reinterpret_cast<float4*>(dst + y * row_len) = float4{F[8 * (y0 + y)], F[8 * (y0 + y) + 1], F[8 * (y0 + y) + 2], F[8 * (y0 + y) + 3]};
+        *reinterpret_cast<float4*>(dst + y * row_len + 4) = float4{F[8 * (y0 + y) + 4], F[8 * (y0 + y) + 5], F[8 * (y0 + y) + 6], F[8 * (y0 + y) + 7]};
+    }
+}
+// the same, with the whole block stored to dst[y * row_len + x]
+template <bool kRefine>
+PCR_D void pix_finish(const DevRecord& R, const PixBlock& B, const short8 v[8], const float* qc, const ApplyList* rlc, float* dst, uint32_t row_len) {
+    float F[64];
+    pix_samples<kRefine>(R, B, v, qc, rlc, F);
+    pix_put_rows<0, 8>(F, dst, row_len);
+}
+// Half kHalf (0: upper, 1: lower) of the pixel rows of an MCU: the part of the lane's block that lies in it, to the
+// component's rows of the half (sampling factors are 1 or 2: a block of a component with two block rows per MCU lies
+// in one half whole, any other block has four sample rows in each).  dst: the block's first sample row in the half.
+// A flat block (flat: only its DC) is one sample.
+template <int kHalf>
+PCR_D void pix_put_half(const float F[64], bool flat, uint32_t vs, uint32_t by, float* dst, uint32_t row_len) {
+    if (vs == 2) {
+        if (by != (uint32_t)kHalf) return;
+        if (flat) dst[0] = F[0]; else pix_put_rows<0, 8>(F, dst, row_len);
+    } else {
+        if (flat) dst[0] = F[0]; else pix_put_rows<4 * kHalf, 4>(F, dst, row_len);
     }
 }
 // the component's folded quantiser steps into LDS; every lane of the workgroup calls it
@@ -1166,8 +1192,8 @@ template <bool kRefine, bool kPlanes>
 __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out,
                                                      const ApplyList* __restrict__ lists, const int32_t* __restrict__ list_idx,
                                                      const CropBox* __restrict__ boxes) {
-    // samples of the run: 64 per block
-    __shared__ __attribute__((aligned(16))) float tile[kPixLanes * 64];
+    // samples of half the pixel rows of the run: 32 per block
+    __shared__ __attribute__((aligned(16))) float tile[kPixLanes * 32];
     // quantiser steps in zig-zag order times the folded transform factors; the rows of the three components start
     // four banks apart, so that lanes of different components read them without bank conflicts
     __shared__ __attribute__((aligned(16))) float qz[kMaxComp][68];
@@ -1225,97 +1251,110 @@ __global__ void __launch_bounds__(kPixLanes) k_pixel(DevRecord R, const PixelTil
         vish[tid] = (uint16_t)(y >= H ? 0 : (H - y < mcu_px_h ? H - y : mcu_px_h));
     }
     __syncthreads();
-    // ---- phase A, second half ----
+    // ---- phase A, second half: the block's samples, in registers ----
+    float S[64];
+    const bool flatb = mine && B.zm <= 1;                   // flat: one sample stands for the block
     if (mine) {
         const ApplyList* rlc = &rl[kRefine ? B.c : 0];
-        const uint32_t row_len = B.hs * 8;
-        float* dst = tile + m * bpm * 64 + pick3(B.c, G.rb[0], G.rb[1], G.rb[2]) + by * 8 * row_len + bx * 8;
-        if (B.zm <= 1) dst[0] = clamp255((float)pix_dc<kRefine>(R, B, v[0][0], rlc) * qz[B.c][0] + 128.f);   // flat: one sample stands for the block
-        else pix_finish<kRefine>(R, B, v, qz[B.c], rlc, dst, row_len);
+        if (flatb) S[0] = clamp255((float)pix_dc<kRefine>(R, B, v[0][0], rlc) * qz[B.c][0] + 128.f);
+        else pix_samples<kRefine>(R, B, v, qz[B.c], rlc, S);
     }
-    __syncthreads();
     if (kPlanes) {
         // Instead of pixels: the lane's block, rounded, into the component's own plane of bytes (`out`: one byte per
         // coefficient slot, so a component's plane lies where its coefficient plane lies, [rows of samples][bw * 8]),
         // for k_triangle_rgb.  A damaged image's planes are left alone; that kernel writes its pixels as zeros.
         if (mine) {
-            const uint32_t row_len = B.hs * 8, pw = pick3(B.c, G.bw[0], G.bw[1], G.bw[2]) * 8;
-            const float* src = tile + m * bpm * 64 + pick3(B.c, G.rb[0], G.rb[1], G.rb[2]) + by * 8 * row_len + bx * 8;
+            const uint32_t pw = pick3(B.c, G.bw[0], G.bw[1], G.bw[2]) * 8;
             uint8_t* pd = out + R.coef_off[timg] + (size_t)pick3(B.c, G.plane0[0], G.plane0[1], G.plane0[2]) * 64 + (size_t)(B.brow * 8) * pw + B.bcol * 8;
 #pragma unroll
             for (int y = 0; y < 8; y++) {
-                float4 lo, hi;
-                if (B.zm <= 1) { lo.x = lo.y = lo.z = lo.w = hi.x = hi.y = hi.z = hi.w = src[0]; }
-                else { lo = *reinterpret_cast<const float4*>(src + y * row_len); hi = *reinterpret_cast<const float4*>(src + y * row_len + 4); }
                 uint2 w;
-                w.x = put_u8(lo.x, 0, 0); w.x = put_u8(lo.y, 1, w.x); w.x = put_u8(lo.z, 2, w.x); w.x = put_u8(lo.w, 3, w.x);
-                w.y = put_u8(hi.x, 0, 0); w.y = put_u8(hi.y, 1, w.y); w.y = put_u8(hi.z, 2, w.y); w.y = put_u8(hi.w, 3, w.y);
+                if (flatb) {
+                    w.x = put_u8(S[0], 0, 0); w.x = put_u8(S[0], 1, w.x); w.x = put_u8(S[0], 2, w.x); w.x = put_u8(S[0], 3, w.x);
+                    w.y = w.x;
+                } else {
+                    w.x = put_u8(S[8 * y], 0, 0); w.x = put_u8(S[8 * y + 1], 1, w.x); w.x = put_u8(S[8 * y + 2], 2, w.x); w.x = put_u8(S[8 * y + 3], 3, w.x);
+                    w.y = put_u8(S[8 * y + 4], 0, 0); w.y = put_u8(S[8 * y + 5], 1, w.y); w.y = put_u8(S[8 * y + 6], 2, w.y); w.y = put_u8(S[8 * y + 7], 3, w.y);
+                }
                 *reinterpret_cast<uint2*>(pd + (size_t)y * pw) = w;
             }
         }
         return;
     }
-    // ---- phase B: one lane per group of output bytes of one pixel row of one MCU ----
+    // ---- phase B: one lane per group of output bytes of one pixel row of one MCU, the upper half of the pixel rows of
+    // the MCUs first, then the lower: the samples of half a run are what the workgroup holds in LDS at a time ----
     const uint32_t shx0 = G.hs[0] == G.hmax ? 0 : 1, shy0 = G.vs[0] == G.vmax ? 0 : 1;       // sampling factors are 1 or 2
     const uint32_t shx1 = nc > 1 && G.hs[1] != G.hmax, shy1 = nc > 1 && G.vs[1] != G.vmax;
     const uint32_t shx2 = nc > 2 && G.hs[2] != G.hmax, shy2 = nc > 2 && G.vs[2] != G.vmax;
     const uint32_t ppg = nc == 1 ? 8u : 4u;                 // pixels per group: 8 gray bytes, or 12 bytes of RGB
     const uint32_t gpm = mcu_px_w / ppg;                    // groups per pixel row of an MCU: 1, 2 or 4
     const uint32_t lg = gpm == 4 ? 2u : (gpm == 2 ? 1u : 0u);
-    const uint32_t items = nm * mcu_px_h * gpm;
+    const uint32_t half_h = mcu_px_h >> 1;                  // pixel rows of an MCU per half: 4 or 8
+    const uint32_t items = nm * half_h * gpm;
     const uint32_t rcpn = nm > 1 ? 0xFFFFFFFFu / nm + 1u : 0u;       // q / nm as the high word of q * rcpn: exact while q * nm < 2^32
-    // component c's four samples for pixels x0.. of row ly of MCU mm: a flat component has one per block
+    const uint32_t mstride = bpm * 32;                      // samples of an MCU in one half
+    // component c's four samples for pixels x0.. of row ly (counted inside the half) of MCU mm: a flat component has one per block
     auto fetch = [&](uint32_t c, uint32_t mm, uint32_t ly, uint32_t x0, uint32_t shx, uint32_t shy, float s[4]) {
         if (G.flat[c]) {
-            const uint32_t brow_in = (ly >> shy) >> 3, bcol_in = (x0 >> shx) >> 3;
-            const float f = tile[mm * bpm * 64 + G.rb[c] + brow_in * 8 * G.rs[c] + bcol_in * 8];
+            const float f = tile[mm * mstride + (G.rb[c] >> 1) + ((x0 >> shx) >> 3) * 8];      // (a half holds one block row of the component, or half of one)
             s[0] = s[1] = s[2] = s[3] = f;
-        } else four_samples(tile + mm * bpm * 64 + G.rb[c] + (ly >> shy) * G.rs[c], x0, shx, s);
+        } else four_samples(tile + mm * mstride + (G.rb[c] >> 1) + (ly >> shy) * G.rs[c], x0, shx, s);
     };
-    for (uint32_t it = tid; it < items; it += kPixLanes) {
-        // lanes run along the image rows: group, then MCU, then pixel row
-        const uint32_t g = it & (gpm - 1), q = it >> lg;
-        const uint32_t ly = nm > 1 ? __umulhi(q, rcpn) : q, mm = q - ly * nm;
-        const uint32_t x0 = g * ppg, vw = visw[mm];
-        if (ly >= vish[mm] || x0 >= vw) continue;
-        uint8_t* wp = out + R.out_off[timg] + ((size_t)org[mm] + (size_t)ly * W + x0) * nc;
-        const uint32_t left = vw - x0;                      // pixels of the group inside the image
-        if (nc == 1) {
-            float a[4], bq[4];
-            fetch(0, mm, ly, x0, 0, 0, a); fetch(0, mm, ly, x0 + 4, 0, 0, bq);
-            uint32_t w0 = 0, w1 = 0;
-            if (!dead) {
-                w0 = put_u8(a[0], 0, w0); w0 = put_u8(a[1], 1, w0); w0 = put_u8(a[2], 2, w0); w0 = put_u8(a[3], 3, w0);
-                w1 = put_u8(bq[0], 0, w1); w1 = put_u8(bq[1], 1, w1); w1 = put_u8(bq[2], 2, w1); w1 = put_u8(bq[3], 3, w1);
-            }
-            if (left >= 8) {
-                struct __attribute__((packed, aligned(1))) Eight { uint32_t a, b; };
-                Eight e8; e8.a = w0; e8.b = w1;
-                *reinterpret_cast<Eight*>(wp) = e8;
-            } else {
-                store_head(wp, w0, w1, 0u, left);
-            }
-        } else {
-            float ys[4], cb[4], cr[4];
-            uint32_t w0 = 0, w1 = 0, w2 = 0;
-            if (!dead) {
-                fetch(0, mm, ly, x0, shx0, shy0, ys); fetch(1, mm, ly, x0, shx1, shy1, cb); fetch(2, mm, ly, x0, shx2, shy2, cr);
-                float r[4], gg[4], bb[4];
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    const float u = cb[i] - 128.f, w = cr[i] - 128.f;
-                    r[i] = ys[i] + 1.402f * w; gg[i] = ys[i] - 0.344136f * u - 0.714136f * w; bb[i] = ys[i] + 1.772f * u;
+    for (int half = 0; half < 2; half++) {
+        if (half) __syncthreads();                          // (the upper half has been read)
+        if (mine) {
+            float* const dst = tile + m * mstride + (pick3(B.c, G.rb[0], G.rb[1], G.rb[2]) >> 1) + bx * 8;
+            if (half == 0) pix_put_half<0>(S, flatb, B.vs, by, dst, B.hs * 8);
+            else pix_put_half<1>(S, flatb, B.vs, by, dst, B.hs * 8);
+        }
+        __syncthreads();
+        for (uint32_t it = tid; it < items; it += kPixLanes) {
+            // lanes run along the image rows: group, then MCU, then pixel row
+            const uint32_t g = it & (gpm - 1), q = it >> lg;
+            const uint32_t lyh = nm > 1 ? __umulhi(q, rcpn) : q, mm = q - lyh * nm;
+            const uint32_t ly = lyh + half * half_h;        // the pixel row inside the MCU
+            const uint32_t x0 = g * ppg, vw = visw[mm];
+            if (ly >= vish[mm] || x0 >= vw) continue;
+            uint8_t* wp = out + R.out_off[timg] + ((size_t)org[mm] + (size_t)ly * W + x0) * nc;
+            const uint32_t left = vw - x0;                  // pixels of the group inside the image
+            if (nc == 1) {
+                float a[4], bq[4];
+                fetch(0, mm, lyh, x0, 0, 0, a); fetch(0, mm, lyh, x0 + 4, 0, 0, bq);
+                uint32_t w0 = 0, w1 = 0;
+                if (!dead) {
+                    w0 = put_u8(a[0], 0, w0); w0 = put_u8(a[1], 1, w0); w0 = put_u8(a[2], 2, w0); w0 = put_u8(a[3], 3, w0);
+                    w1 = put_u8(bq[0], 0, w1); w1 = put_u8(bq[1], 1, w1); w1 = put_u8(bq[2], 2, w1); w1 = put_u8(bq[3], 3, w1);
                 }
-                w0 = put_u8(r[0], 0, w0); w0 = put_u8(gg[0], 1, w0); w0 = put_u8(bb[0], 2, w0); w0 = put_u8(r[1], 3, w0);
-                w1 = put_u8(gg[1], 0, w1); w1 = put_u8(bb[1], 1, w1); w1 = put_u8(r[2], 2, w1); w1 = put_u8(gg[2], 3, w1);
-                w2 = put_u8(bb[2], 0, w2); w2 = put_u8(r[3], 1, w2); w2 = put_u8(gg[3], 2, w2); w2 = put_u8(bb[3], 3, w2);
-            }
-            if (left >= 4) {
-                struct __attribute__((packed, aligned(1))) Twelve { uint32_t a, b, c; };
-                Twelve tw; tw.a = w0; tw.b = w1; tw.c = w2;
-                *reinterpret_cast<Twelve*>(wp) = tw;           // one (possibly unaligned) 12-byte store
+                if (left >= 8) {
+                    struct __attribute__((packed, aligned(1))) Eight { uint32_t a, b; };
+                    Eight e8; e8.a = w0; e8.b = w1;
+                    *reinterpret_cast<Eight*>(wp) = e8;
+                } else {
+                    store_head(wp, w0, w1, 0u, left);
+                }
             } else {
-                store_head(wp, w0, w1, w2, left * 3);
+                float ys[4], cb[4], cr[4];
+                uint32_t w0 = 0, w1 = 0, w2 = 0;
+                if (!dead) {
+                    fetch(0, mm, lyh, x0, shx0, shy0, ys); fetch(1, mm, lyh, x0, shx1, shy1, cb); fetch(2, mm, lyh, x0, shx2, shy2, cr);
+                    float r[4], gg[4], bb[4];
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        const float u = cb[i] - 128.f, w = cr[i] - 128.f;
+                        r[i] = ys[i] + 1.402f * w; gg[i] = ys[i] - 0.344136f * u - 0.714136f * w; bb[i] = ys[i] + 1.772f * u;
+                    }
+                    w0 = put_u8(r[0], 0, w0); w0 = put_u8(gg[0], 1, w0); w0 = put_u8(bb[0], 2, w0); w0 = put_u8(r[1], 3, w0);
+                    w1 = put_u8(gg[1], 0, w1); w1 = put_u8(bb[1], 1, w1); w1 = put_u8(r[2], 2, w1); w1 = put_u8(gg[2], 3, w1);
+                    w2 = put_u8(bb[2], 0, w2); w2 = put_u8(r[3], 1, w2); w2 = put_u8(gg[3], 2, w2); w2 = put_u8(bb[3], 3, w2);
+                }
+                if (left >= 4) {
+                    struct __attribute__((packed, aligned(1))) Twelve { uint32_t a, b, c; };
+                    Twelve tw; tw.a = w0; tw.b = w1; tw.c = w2;
+                    *reinterpret_cast<Twelve*>(wp) = tw;           // one (possibly unaligned) 12-byte store
+                } else {
+                    store_head(wp, w0, w1, w2, left * 3);
+                }
             }
         }
     }
