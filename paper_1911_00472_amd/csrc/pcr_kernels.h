@@ -628,19 +628,23 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
 
 // Phase 2 of AC refinement: one lane per block of the scan.  grid: (ceil(max blocks / 256), scans)
 struct RefineScan { uint32_t img; uint32_t scan; };
+// The per-block helpers of the lane decoders take their work from a list instead: chunk `chunk` (256 blocks) of scan
+// `entry` of the launch's RefineScan list -- the planes of a record differ in size by an order of magnitude (luma and
+// chroma, small and large images), and a grid sized for the largest would be mostly workgroups that find nothing to do.
+struct RefineTile { uint32_t entry; uint32_t chunk; };
 
 // What the lane-per-unit refinement decoder needs before and after it, one lane per block of the scan (the grid of
 // k_refine_blocks).  k_refine_history: the kRefHist word of every block -- which positions of the band are non-zero
 // when the scan starts: what the AC first scans left in the coefficient plane, and what earlier refinement scans of the
 // band added (their kRefNz words).  k_refine_deal: the correction bits the decoder left in reading order go to the
 // history positions they belong to (kRefPlus as every consumer reads it).
-PCR_D bool refine_block_of_lane(const DevRecord& R, const RefineScan& a, size_t* ig_out, uint32_t* blk_out, uint32_t* plane_out) {
+PCR_D bool refine_block_of_lane(const DevRecord& R, const RefineScan& a, uint32_t chunk, size_t* ig_out, uint32_t* blk_out, uint32_t* plane_out) {
     if (R.status[a.img] != kOk) return false;
     const ImgDesc* img = &R.img[a.img];
     const size_t ig = (size_t)a.img * R.G + a.scan;
     const int c = R.scan[ig].comp[0];
     const uint32_t cw = img->cw[c], ncov = cw * img->ch[c];
-    const uint32_t b = blockIdx.x * 256 + threadIdx.x;
+    const uint32_t b = chunk * 256 + threadIdx.x;
     if (b >= ncov) return false;
     const uint32_t bw = img->bw[c];
     *ig_out = ig; *blk_out = (b / cw) * bw + (b % cw); *plane_out = bw * img->bh[c];
@@ -649,20 +653,21 @@ PCR_D bool refine_block_of_lane(const DevRecord& R, const RefineScan& a, size_t*
 // k_refine_history works through the padded plane (blocks the image does not cover included: they hold zeros), 64
 // consecutive blocks -- 8 KB of coefficients -- per wavefront: lane i of step j loads 16-byte chunk 64 j + i of them, so
 // that every load instruction reads one contiguous kilobyte, turns its eight coefficients into eight mask bits, and leaves
-// the byte in LDS where the lane that owns the block picks up all eight.  grid: (ceil(max plane blocks / 256), scans).
-__global__ void __launch_bounds__(256) k_refine_history(DevRecord R, const RefineScan* __restrict__ rs) {
+// the byte in LDS where the lane that owns the block picks up all eight.  grid: one workgroup per tile (chunks of the padded planes).
+__global__ void __launch_bounds__(256) k_refine_history(DevRecord R, const RefineScan* __restrict__ rs, const RefineTile* __restrict__ tiles) {
     __shared__ __attribute__((aligned(8))) uint8_t bytes[4][64 * 8];
     short_kernel_priority();
-    const RefineScan a = rs[blockIdx.y];
+    const RefineTile tile = tiles[blockIdx.x];
+    const RefineScan a = rs[tile.entry];
     if (R.status[a.img] != kOk) return;
     const ImgDesc* img = &R.img[a.img];
     const size_t ig = (size_t)a.img * R.G + a.scan;
     const ScanDesc* sd = &R.scan[ig];
     const int c = sd->comp[0];
     const uint32_t plane = (uint32_t)img->bw[c] * img->bh[c];
-    if (blockIdx.x * 256 >= plane) return;
+    if (tile.chunk * 256 >= plane) return;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const uint32_t blk0 = blockIdx.x * 256 + wave * 64, blk = blk0 + lane;
+    const uint32_t blk0 = tile.chunk * 256 + wave * 64, blk = blk0 + lane;
     uint64_t m = 0;
     // An earlier refinement scan of the very same band has this word already: what it started from and what it added
     // are what this scan starts from (16 bytes per block instead of the block's 128 bytes of coefficients).
@@ -696,11 +701,13 @@ __global__ void __launch_bounds__(256) k_refine_history(DevRecord R, const Refin
         m |= R.masks[R.mask_off[(size_t)a.img * R.G + sd->hist[q]] + (size_t)kRefNz * plane + blk];
     R.masks[R.mask_off[ig] + (size_t)kRefHist * plane + blk] = m & band_mask(sd->Ss, sd->Se);
 }
-__global__ void __launch_bounds__(256) k_refine_deal(DevRecord R, const RefineScan* __restrict__ rs) {
+// grid: one workgroup per tile (chunks of the blocks the image covers)
+__global__ void __launch_bounds__(256) k_refine_deal(DevRecord R, const RefineScan* __restrict__ rs, const RefineTile* __restrict__ tiles) {
     short_kernel_priority();
-    const RefineScan a = rs[blockIdx.y];
+    const RefineTile tile = tiles[blockIdx.x];
+    const RefineScan a = rs[tile.entry];
     size_t ig; uint32_t blk, plane;
-    if (!refine_block_of_lane(R, a, &ig, &blk, &plane)) return;
+    if (!refine_block_of_lane(R, a, tile.chunk, &ig, &blk, &plane)) return;
     uint64_t* rec = R.masks + R.mask_off[ig] + blk;
     rec[(size_t)kRefPlus * plane] = deal_bits(rec[(size_t)kRefPlus * plane], rec[(size_t)kRefHist * plane]);
 }

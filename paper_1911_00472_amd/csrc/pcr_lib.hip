@@ -33,7 +33,8 @@ struct LevelList {
     Unit* d_units = nullptr; uint32_t n = 0; int kind = 0;
     int shape = 0;                                                               // DC first scans: dc_shape of the units
     RefineScan* d_refine = nullptr; uint32_t n_refine = 0, refine_grid_x = 0;   // phase 2 of an AC refinement launch
-    uint32_t plane_grid_x = 0;                                                   // ... counted in blocks of the padded planes (k_refine_history)
+    RefineTile* d_plane_tiles = nullptr; uint32_t n_plane_tiles = 0;              // k_refine_history: chunks of the padded planes of those scans
+    RefineTile* d_cov_tiles = nullptr; uint32_t n_cov_tiles = 0;                  // k_refine_deal: chunks of the blocks the images cover
     LaneJob* d_jobs = nullptr; uint32_t n_jobs = 0;                              // the same units cut into jobs of a lane-per-unit kernel
 };
 
@@ -182,7 +183,7 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
     struct Item { Unit u; uint32_t bytes; uint32_t bits; };      // bytes: the scan's mean per unit; bits: the unit's own, if known
     // one list per (dependency level, kind of scan, DC decoder shape: 0 for the AC kinds)
     std::vector<std::vector<Item>> lists((size_t)r->max_level * kNumKinds * kDcShapes);
-    std::vector<std::vector<RefineScan>> rlists(r->max_level); std::vector<uint32_t> rmax(r->max_level, 0), rmax_plane(r->max_level, 0);
+    std::vector<std::vector<RefineScan>> rlists(r->max_level); std::vector<uint32_t> rmax(r->max_level, 0);
     std::vector<ApplyUnit> apply; uint32_t max_blk = 0;
     for (uint32_t i = 0; i < n; i++) {
         const uint32_t upto = std::min<uint32_t>(r->img[i].nscans, (uint32_t)k);
@@ -201,7 +202,6 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
             if (kind == kAcRefine) {
                 rlists[r->level[ig] - 1].push_back(RefineScan{i, g});
                 rmax[r->level[ig] - 1] = std::max<uint32_t>(rmax[r->level[ig] - 1], (uint32_t)r->img[i].cw[sd.comp[0]] * r->img[i].ch[sd.comp[0]]);
-                rmax_plane[r->level[ig] - 1] = std::max<uint32_t>(rmax_plane[r->level[ig] - 1], (uint32_t)r->img[i].bw[sd.comp[0]] * r->img[i].bh[sd.comp[0]]);
             }
             int shape = 0;
             if (kind == kDcFirst) {
@@ -261,8 +261,19 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
         if (ll.kind == kAcRefine) {
             const size_t lv = li / kDcShapes / kNumKinds;
             const auto& rl = rlists[lv];
-            ll.n_refine = (uint32_t)rl.size(); ll.refine_grid_x = (rmax[lv] + 255) / 256; ll.plane_grid_x = (rmax_plane[lv] + 255) / 256;
+            ll.n_refine = (uint32_t)rl.size(); ll.refine_grid_x = (rmax[lv] + 255) / 256;
             rc = arena_upload(&r->big, &ll.d_refine, rl); if (rc) return rc;
+            std::vector<RefineTile> plane_tiles, cov_tiles;
+            for (uint32_t e = 0; e < ll.n_refine; e++) {
+                const ImgDesc& im = r->img[rl[e].img];
+                const int c = r->scan[(size_t)rl[e].img * G + rl[e].scan].comp[0];
+                const uint32_t plane = (uint32_t)im.bw[c] * im.bh[c], cov = (uint32_t)im.cw[c] * im.ch[c];
+                for (uint32_t ch = 0; ch * 256 < plane; ch++) plane_tiles.push_back(RefineTile{e, ch});
+                for (uint32_t ch = 0; ch * 256 < cov; ch++) cov_tiles.push_back(RefineTile{e, ch});
+            }
+            ll.n_plane_tiles = (uint32_t)plane_tiles.size(); ll.n_cov_tiles = (uint32_t)cov_tiles.size();
+            if (ll.n_plane_tiles) { rc = arena_upload(&r->big, &ll.d_plane_tiles, plane_tiles); if (rc) return rc; }
+            if (ll.n_cov_tiles) { rc = arena_upload(&r->big, &ll.d_cov_tiles, cov_tiles); if (rc) return rc; }
         }
         plan.levels.push_back(ll);
     }
@@ -397,12 +408,11 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
             mark(r, PCR_STAGE_AC_FIRST, s);
         }
         else if (lanes_pay(r, l)) {
-            const dim3 per_block(l.refine_grid_x, l.n_refine);
-            hipLaunchKernelGGL(k_refine_history, dim3(l.plane_grid_x, l.n_refine), dim3(256), 0, s, r->d, l.d_refine);
+            if (l.n_plane_tiles) hipLaunchKernelGGL(k_refine_history, dim3(l.n_plane_tiles), dim3(256), 0, s, r->d, l.d_refine, l.d_plane_tiles);
             mark(r, PCR_STAGE_REFINE_BLOCKS, s);
             hipLaunchKernelGGL(k_ac_refine_lanes, dim3(l.n_jobs), block, 0, s, r->d, l.d_units, l.d_jobs, c32);
             mark(r, PCR_STAGE_AC_REFINE, s);
-            hipLaunchKernelGGL(k_refine_deal, per_block, dim3(256), 0, s, r->d, l.d_refine);
+            if (l.n_cov_tiles) hipLaunchKernelGGL(k_refine_deal, dim3(l.n_cov_tiles), dim3(256), 0, s, r->d, l.d_refine, l.d_cov_tiles);
             mark(r, PCR_STAGE_REFINE_BLOCKS, s);
         }
         else {
@@ -533,6 +543,7 @@ static int finish_open(pcr_record* r, hipStream_t s) {
                   4 * arena_round(((size_t)n * G + 1) * sizeof(uint64_t)) + arena_round((tiles.size() + 1) * sizeof(PixelTile)) + arena_round((flat_tiles.size() + 1) * sizeof(PixelTile)) + arena_round((flat_rows.size() + 1) * sizeof(PixelTile)) + arena_round((n + 1) * 8) +
                   arena_round(((size_t)ntabs + 1) * sizeof(AcTab)) + arena_round(((size_t)ndctabs + 1) * sizeof(DcTab)) + arena_round(((size_t)n * G + 1) * sizeof(uint32_t)) + arena_round(((size_t)n * G + 1) * sizeof(uint32_t));
     need += 8 * ((ns + (size_t)n * G) * sizeof(Unit) + (size_t)n * kMaxComp * 64) + (1u << 20);
+    need += 8 * (r->coef_off[n] / 64 / 256 + (size_t)n * G) * 2 * sizeof(RefineTile);     // (the tile lists of the refinement helpers: one entry per 256 blocks)
     int rc = arena_reset(&r->big, need);
     if (!rc) rc = arena_alloc(&r->big, &d.clean, padded);
     if (!rc) rc = arena_alloc(&r->big, &d.coef, r->coef_off[n]);
