@@ -626,7 +626,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine(DevRecord R, const 
     if (rc != kOk) R.status[un.img] = rc;
 }
 
-// Phase 2 of AC refinement: one lane per block of the scan.  grid: (ceil(max blocks / 256), scans)
+// Phase 2 of AC refinement: one lane per block of the scan.
 struct RefineScan { uint32_t img; uint32_t scan; };
 // The per-block helpers of the lane decoders take their work from a list instead: chunk `chunk` (256 blocks) of scan
 // `entry` of the launch's RefineScan list -- the planes of a record differ in size by an order of magnitude (luma and
@@ -712,24 +712,25 @@ __global__ void __launch_bounds__(256) k_refine_deal(DevRecord R, const RefineSc
     rec[(size_t)kRefPlus * plane] = deal_bits(rec[(size_t)kRefPlus * plane], rec[(size_t)kRefHist * plane]);
 }
 
-__global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const RefineScan* rs) {
+__global__ void __launch_bounds__(256) k_refine_blocks(DevRecord R, const RefineScan* __restrict__ rs, const RefineTile* __restrict__ tiles) {
     __shared__ AcTab tab;
     short_kernel_priority();
-    const RefineScan a = rs[blockIdx.y];
+    const RefineTile tile = tiles[blockIdx.x];
+    const RefineScan a = rs[tile.entry];
     if (R.status[a.img] != kOk) return;
     const ImgDesc* img = &R.img[a.img];
     const size_t ig = (size_t)a.img * R.G + a.scan;
     const ScanDesc* sd = &R.scan[ig];
     const int c = sd->comp[0];
     const uint32_t cw = img->cw[c], ncov = cw * img->ch[c];
-    if (blockIdx.x * 256 >= ncov) return;
+    if (tile.chunk * 256 >= ncov) return;
     {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&R.tabs[R.tab_idx[ig]]);
         uint32_t* dst = reinterpret_cast<uint32_t*>(&tab);
         for (uint32_t e = threadIdx.x; e < sizeof(AcTab) / 4; e += 256) dst[e] = src[e];
     }
     __syncthreads();
-    const uint32_t b = blockIdx.x * 256 + threadIdx.x;
+    const uint32_t b = tile.chunk * 256 + threadIdx.x;
     if (b >= ncov) return;
     const uint32_t bw = img->bw[c];
     const size_t blk = (size_t)(b / cw) * bw + (b % cw);

@@ -32,9 +32,9 @@ enum Kind { kDcFirst = 0, kAcFirst = 1, kAcRefine = 2, kSequential = 3, kNumKind
 struct LevelList {
     Unit* d_units = nullptr; uint32_t n = 0; int kind = 0;
     int shape = 0;                                                               // DC first scans: dc_shape of the units
-    RefineScan* d_refine = nullptr; uint32_t n_refine = 0, refine_grid_x = 0;   // phase 2 of an AC refinement launch
+    RefineScan* d_refine = nullptr; uint32_t n_refine = 0;                      // the scans of an AC refinement launch, for its per-block kernels
     RefineTile* d_plane_tiles = nullptr; uint32_t n_plane_tiles = 0;              // k_refine_history: chunks of the padded planes of those scans
-    RefineTile* d_cov_tiles = nullptr; uint32_t n_cov_tiles = 0;                  // k_refine_deal: chunks of the blocks the images cover
+    RefineTile* d_cov_tiles = nullptr; uint32_t n_cov_tiles = 0;                  // k_refine_deal, k_refine_blocks: chunks of the blocks the images cover
     LaneJob* d_jobs = nullptr; uint32_t n_jobs = 0;                              // the same units cut into jobs of a lane-per-unit kernel
 };
 
@@ -183,7 +183,7 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
     struct Item { Unit u; uint32_t bytes; uint32_t bits; };      // bytes: the scan's mean per unit; bits: the unit's own, if known
     // one list per (dependency level, kind of scan, DC decoder shape: 0 for the AC kinds)
     std::vector<std::vector<Item>> lists((size_t)r->max_level * kNumKinds * kDcShapes);
-    std::vector<std::vector<RefineScan>> rlists(r->max_level); std::vector<uint32_t> rmax(r->max_level, 0);
+    std::vector<std::vector<RefineScan>> rlists(r->max_level);
     std::vector<ApplyUnit> apply; uint32_t max_blk = 0;
     for (uint32_t i = 0; i < n; i++) {
         const uint32_t upto = std::min<uint32_t>(r->img[i].nscans, (uint32_t)k);
@@ -201,7 +201,6 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
             const int kind = seq ? kSequential : (sd.Ss == 0 ? kDcFirst : (sd.Ah == 0 ? kAcFirst : kAcRefine));
             if (kind == kAcRefine) {
                 rlists[r->level[ig] - 1].push_back(RefineScan{i, g});
-                rmax[r->level[ig] - 1] = std::max<uint32_t>(rmax[r->level[ig] - 1], (uint32_t)r->img[i].cw[sd.comp[0]] * r->img[i].ch[sd.comp[0]]);
             }
             int shape = 0;
             if (kind == kDcFirst) {
@@ -261,7 +260,7 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
         if (ll.kind == kAcRefine) {
             const size_t lv = li / kDcShapes / kNumKinds;
             const auto& rl = rlists[lv];
-            ll.n_refine = (uint32_t)rl.size(); ll.refine_grid_x = (rmax[lv] + 255) / 256;
+            ll.n_refine = (uint32_t)rl.size();
             rc = arena_upload(&r->big, &ll.d_refine, rl); if (rc) return rc;
             std::vector<RefineTile> plane_tiles, cov_tiles;
             for (uint32_t e = 0; e < ll.n_refine; e++) {
@@ -418,7 +417,7 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
         else {
             hipLaunchKernelGGL(k_ac_refine, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64);
             mark(r, PCR_STAGE_AC_REFINE, s);
-            hipLaunchKernelGGL(k_refine_blocks, dim3(l.refine_grid_x, l.n_refine), dim3(256), 0, s, r->d, l.d_refine);
+            if (l.n_cov_tiles) hipLaunchKernelGGL(k_refine_blocks, dim3(l.n_cov_tiles), dim3(256), 0, s, r->d, l.d_refine, l.d_cov_tiles);
             mark(r, PCR_STAGE_REFINE_BLOCKS, s);
         }
     }
