@@ -1099,14 +1099,16 @@ PCR_D void pix_samples(const DevRecord& R, const PixBlock& B, const short8 v[8],
             // A position either grows (it was non-zero: + 2^Al with its own sign) or is new (it was zero: +- 2^Al by the
             // sign bit) or stays: one step with one sign, taken from the coefficient or from the record.
             const uint64_t anym = nzm | plm, negm = nzm & ~sgm;
-            const int p1 = 1 << S.Al;
+            const int p1 = 1 << S.Al, above = -2 * p1;       // (above: the bits over bit Al)
 #pragma unroll
             for (int k = 1; k < 64; k++) {
                 const uint32_t anw = k < 32 ? (uint32_t)anym : (uint32_t)(anym >> 32), ngw = k < 32 ? (uint32_t)negm : (uint32_t)(negm >> 32);
                 const int bit = k & 31;
-                const int any = ((int)(anw << (31 - bit))) >> 31;           // all ones where the coefficient changes
-                const int neg = (ci[k] >> 31) | (((int)(ngw << (31 - bit))) >> 31);   // all ones where the step is negative
-                ci[k] += ((p1 ^ neg) - neg) & any;
+                const int neg = (ci[k] | (int)(ngw << (31 - bit))) >> 31;   // all ones where the step is negative
+                const int step = (neg & above) | p1;                        // -2^Al or 2^Al
+                // ... taken where the coefficient changes: bit x step + coefficient in one instruction (written out: the
+                // compiler turns a product with a single bit into a mask, an `and` and an addition)
+                asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(ci[k]) : "v"((anw >> bit) & 1u), "v"(step), "v"(ci[k]));
             }
         }
     }

@@ -81,7 +81,7 @@ struct LaneUnit {
 
 // A lane's view of its stream.  The next unread bit is the top bit of `hi`; hi:lo hold `have` valid bits (always more
 // than 32 after top_up(), so that hi is a full look-ahead window; a symbol takes 31 at most).  A symbol's bits leave
-// through a funnel shift (one instruction; 64-bit shifts run at a quarter of the rate).
+// through a funnel shift (one instruction where a 64-bit shift of the pair and the copies around it are three or four).
 //
 // Words come from a ring of kRingWords words per lane in LDS, not from memory: the counter a wavefront waits on for a
 // load is shared by all its lanes and returns in order, so a loop in which some lane or other fetches a word in every

@@ -28,7 +28,15 @@ PCR_HD void idct8(const float in[8], float out[8]) {
     out[3] = e3 + o3; out[4] = e3 - o3;
 }
 
-PCR_HD float clamp255(float v) { return v < 0.f ? 0.f : (v > 255.f ? 255.f : v); }
+// v (finite) clamped to [0, 255].  On the device the median of (v, 0, 255) is one instruction; written with compares it
+// is four, and the pixel kernels clamp every sample.
+PCR_HD float clamp255(float v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_fmed3f(v, 0.f, 255.f);
+#else
+    return v < 0.f ? 0.f : (v > 255.f ? 255.f : v);
+#endif
+}
 
 PCR_HD uint8_t round_u8(float v) {
     v = __builtin_floorf(v + 0.5f);
