@@ -1118,6 +1118,9 @@ PCR_D void pix_samples(const DevRecord& R, const PixBlock& B, const short8 v[8],
         F[zigzag_lookup(4 * k4)] = (float)ci[4 * k4] * qq.x; F[zigzag_lookup(4 * k4 + 1)] = (float)ci[4 * k4 + 1] * qq.y;
         F[zigzag_lookup(4 * k4 + 2)] = (float)ci[4 * k4 + 2] * qq.z; F[zigzag_lookup(4 * k4 + 3)] = (float)ci[4 * k4 + 3] * qq.w;
     }
+    // the level shift: the DC term reaches every sample with weight one (its folded factor is exactly 1/8 and the
+    // transforms only add it), so 128 is added to it once instead of to the 64 samples
+    F[0] += 128.f;
 #pragma unroll
     for (int r = 0; r < 8; r++)
         idct8_scaled(F[8 * r], F[8 * r + 1], F[8 * r + 2], F[8 * r + 3], F[8 * r + 4], F[8 * r + 5], F[8 * r + 6], F[8 * r + 7]);
@@ -1125,7 +1128,7 @@ PCR_D void pix_samples(const DevRecord& R, const PixBlock& B, const short8 v[8],
     for (int x = 0; x < 8; x++)
         idct8_scaled(F[x], F[8 + x], F[16 + x], F[24 + x], F[32 + x], F[40 + x], F[48 + x], F[56 + x]);
 #pragma unroll
-    for (int e = 0; e < 64; e++) F[e] = clamp255(F[e] + 128.f);
+    for (int e = 0; e < 64; e++) F[e] = clamp255(F[e]);
 }
 // rows y0 .. y0 + kRows - 1 of the block's samples to dst[(y - y0) * row_len + x]
 template <int y0, int kRows>
