@@ -334,9 +334,11 @@ int pcr_record_write(const void* const* files, const size_t* sizes, const int32_
  * writer walks every scan once and stores, about every entry_interval MCUs of the scan (blocks, for a scan of one
  * component; every entry_interval / 2 in AC refinement scans, whose symbols take a decoder longest), a place where a
  * decoder may start: a block boundary outside any end-of-band run, its bit offset in the scan's data without the
- * stuffed bytes, and the DC predictions there (16 bytes per entry, kept at the end of the scan's own scan group, so a
- * read at fidelity k brings only the entries of scans 1..k; about 2.2 % of a record of 100 kB photographs at an
- * interval of 128).  The image bytes are those pcr_record_write writes, byte for byte, and every call of this library
+ * stuffed bytes, and -- where the scan has them -- the DC predictions there (16 bytes per entry with predictions, 8 bytes
+ * per entry of an AC scan, which has none and is where nearly all entries are; kept at the end of the scan's own scan
+ * group, so a read at fidelity k brings only the entries of scans 1..k; about 1.2 % of a record of 100 kB photographs
+ * at an interval of 128, 2.4 % at 64).  The header's entry count of an (image, scan) is 15 bits; its top bit marks the
+ * 8-byte form.  The image bytes are those pcr_record_write writes, byte for byte, and every call of this library
  * gives the same results for both records; the decoder makes every stretch between two entries a unit of its own -- a
  * wavefront's or a lane's work, see pcr_set_lane_decoders -- as it does for restart intervals, which shortens the
  * decode of a record without touching the files.  Scans with restart markers and files the walk cannot follow get no

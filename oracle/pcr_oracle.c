@@ -78,8 +78,9 @@ int orc_record_index(const uint8_t* rec, size_t nbytes, uint64_t* off, uint32_t*
     const uint8_t* pz = pn + 4 * (size_t)n;
     for (uint32_t i = 0; i < n; i++) { if (label) label[i] = (int32_t)rd32(pl + 4 * i); if (nscans) nscans[i] = rd32(pn + 4 * i); }
     /* Version 2 records end every group with decoder hints (places inside the scans where a decoder may start),
-     * 16 bytes each, as many per image as the count table behind the length table says.  A plain decoder has
-     * no use for them: they are skipped, and only their size enters the check that the group is tiled. */
+     * as many per image as the count table behind the length table says: the low 15 bits of an entry of that
+     * table are the count, the top bit says that the hints of this scan are 8 bytes each instead of 16.  A plain
+     * decoder has no use for them: they are skipped, and only their size enters the check that the group is tiled. */
     const uint8_t* pe = rd32(rec + 4) == 2 ? pz + 4 * (size_t)G * n + 8 : NULL;
     uint64_t start = hb;
     for (uint32_t g = 0; g < G; g++) {
@@ -88,7 +89,11 @@ int orc_record_index(const uint8_t* rec, size_t nbytes, uint64_t* off, uint32_t*
             uint32_t L = rd32(pz + 4 * ((size_t)g * n + i));
             off[(size_t)g * n + i] = pos; len[(size_t)g * n + i] = L; pos += L;
         }
-        if (pe) for (uint32_t i = 0; i < n; i++) { const uint8_t* c = pe + 2 * ((size_t)g * n + i); pos += 16ull * (c[0] | ((uint32_t)c[1] << 8)); }
+        if (pe) for (uint32_t i = 0; i < n; i++) {
+            const uint8_t* c = pe + 2 * ((size_t)g * n + i);
+            const uint32_t field = c[0] | ((uint32_t)c[1] << 8);
+            pos += (uint64_t)(field & 0x7FFFu) * ((field & 0x8000u) ? 8u : 16u);
+        }
         if (pos != rd64(p + 8 * g)) return ORC_E_FORMAT;      /* regions (and hints) must tile the group */
         start = pos;
     }

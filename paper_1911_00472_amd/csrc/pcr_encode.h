@@ -197,8 +197,8 @@ inline int find_entry_points(const uint8_t* file, const uint64_t* ends, uint32_t
             const uint32_t step = (!seq && sd.Ss > 0 && sd.Ah > 0 && interval >= 2) ? interval / 2 : interval;
             uint32_t next_entry = step;
             for (uint32_t m = m0; m < m1 && !b.bad; m++) {
-                if (sd.ri == 0 && m >= next_entry && eobrun == 0 && E.size() < 65535) {
-                    EntryPoint e; e.mcu = m; e.bit = (uint32_t)b.pos; e.zero = 0;
+                if (sd.ri == 0 && m >= next_entry && eobrun == 0 && E.size() < kMaxEntriesPerScan) {
+                    EntryPoint e; e.mcu = m; e.bit = (uint32_t)b.pos; e.zero = (!seq && sd.Ss > 0) ? 1 : 0;   // (in memory: 1 = written in the short form)
                     for (int j = 0; j < kMaxComp; j++) e.pred[j] = (int16_t)pred[j];
                     E.push_back(e);
                     next_entry = (m / step + 1) * step;
@@ -299,13 +299,13 @@ inline int plan_record_indexed(const void* const* files, const size_t* sizes, ui
     for (uint32_t t = 1; t < nthreads; t++) pool.emplace_back(work);
     work();
     for (auto& t : pool) t.join();
-    uint64_t entries = 0;
-    for (const auto& e : Q->ent) entries += e.size();
+    uint64_t entry_bytes_total = 0;
+    for (const auto& e : Q->ent) entry_bytes_total += e.size() * (uint64_t)((!e.empty() && e[0].zero) ? kEntryBytesShort : kEntryBytes);
     const uint64_t raw = hdr_ecount_pos(n, Q->P.G, Q->P.G, 0);
     Q->P.header_bytes = (raw + 63) / 64 * 64;
     uint64_t payload = 0;
     for (uint32_t i = 0; i < n; i++) payload += sizes[i];
-    Q->P.total = Q->P.header_bytes + payload + entries * kEntryBytes;
+    Q->P.total = Q->P.header_bytes + payload + entry_bytes_total;
     if (Q->P.total >= (1ull << 32)) return kEUnsupported;
     return kOk;
 }
@@ -333,9 +333,12 @@ inline void write_record_indexed(const IndexedPlan& Q, const void* const* files,
         for (uint32_t i = 0; i < n; i++) {                          // the group's entries behind its regions
             const std::vector<EntryPoint>& E = Q.ent[(size_t)i * kMaxScansPerFile + g];
             uint8_t* c = out + hdr_ecount_pos(n, G, g, i);
-            c[0] = (uint8_t)E.size(); c[1] = (uint8_t)(E.size() >> 8);
+            const bool brief = !E.empty() && E[0].zero;            // an AC scan: no DC predictions to carry
+            const uint32_t field = (uint32_t)E.size() | (brief ? kEntryShortFlag : 0u);
+            c[0] = (uint8_t)field; c[1] = (uint8_t)(field >> 8);
             for (const EntryPoint& e : E) {
                 st_le32(out + pos, e.mcu); st_le32(out + pos + 4, e.bit);
+                if (brief) { pos += kEntryBytesShort; continue; }
                 for (int j = 0; j < 3; j++) { out[pos + 8 + 2 * j] = (uint8_t)(uint16_t)e.pred[j]; out[pos + 9 + 2 * j] = (uint8_t)((uint16_t)e.pred[j] >> 8); }
                 out[pos + 14] = out[pos + 15] = 0;
                 pos += kEntryBytes;

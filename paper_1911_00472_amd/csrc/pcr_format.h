@@ -33,7 +33,10 @@ struct RecordHeader {
     uint32_t version;                      // 1, or 2: with entry points
     uint32_t entry_interval;               // version 2: MCUs between entry points the writer aimed at (informative)
 };
-constexpr uint32_t kEntryBytes = 16;
+// Version 2: an entry point is 16 bytes (MCU, bit offset, three DC predictions, two reserved bytes), or 8 (MCU and bit
+// offset only) where the scan has no DC predictions to resume -- the AC scans, nearly all entries of a record.  The
+// header's 16-bit entry count of an (image, scan) carries the form in its top bit.
+constexpr uint32_t kEntryBytes = 16, kEntryBytesShort = 8, kEntryShortFlag = 0x8000u, kMaxEntriesPerScan = 0x7FFFu;
 
 PCR_HD uint64_t hdr_group_end_pos(uint32_t g) { return 24 + 8ull * g; }
 PCR_HD uint64_t hdr_label_pos(uint32_t G, uint32_t i) { return 24 + 8ull * G + 4ull * i; }
@@ -42,6 +45,10 @@ PCR_HD uint64_t hdr_len_pos(uint32_t n, uint32_t G, uint32_t g, uint32_t i) { re
 PCR_HD uint64_t hdr_entry_interval_pos(uint32_t n, uint32_t G) { return hdr_len_pos(n, G, G, 0); }                  // version 2
 PCR_HD uint64_t hdr_ecount_pos(uint32_t n, uint32_t G, uint32_t g, uint32_t i) { return hdr_len_pos(n, G, G, 0) + 8 + 2ull * ((uint64_t)g * n + i); }
 PCR_HD uint32_t ld_le16(const uint8_t* p) { return (uint32_t)p[0] | ((uint32_t)p[1] << 8); }
+// the entry-count field of the header taken apart
+PCR_HD uint32_t entry_count(uint32_t field) { return field & kMaxEntriesPerScan; }
+PCR_HD uint32_t entry_stride(uint32_t field) { return (field & kEntryShortFlag) ? kEntryBytesShort : kEntryBytes; }
+PCR_HD uint64_t entry_bytes(uint32_t field) { return (uint64_t)entry_count(field) * entry_stride(field); }
 
 // Validate the fixed part of the header.  `bytes` must hold at least min(nbytes, header).
 PCR_HD int parse_record_header(const uint8_t* bytes, uint64_t nbytes, RecordHeader* h) {

@@ -304,12 +304,14 @@ PCR_D void unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __rest
     if (ri == 0 && sc > 1) {
         // Units of a scan without restart markers start at the record's entry points: unit j runs from entry j-1
         // (the scan's start for j = 0) to entry j (the scan's end for the last unit).
-        const uint8_t* e = R.rec + uni(R.ent_off[ig]) + (size_t)kEntryBytes * un.interval;        // entry j; entry j-1 lies 16 bytes before it
+        const uint32_t stride = uni(entry_stride(ld_le16(R.rec + hdr_ecount_pos(R.n, R.G, un.scan, un.img))));   // 16 bytes, or 8 without DC predictions
+        const uint8_t* e = R.rec + uni(R.ent_off[ig]) + (size_t)stride * un.interval;             // entry j; entry j-1 lies one stride before it
         const uint32_t total = uni(R.ivl_start[sb + sc]) * 8;                                    // bits of the scan's unstuffed data
         uint32_t m0 = 0, bit0 = 0, m1 = mcus, bit1 = total;
         if (un.interval > 0) {
-            m0 = uni(ld_le32(e - 16)); bit0 = uni(ld_le32(e - 12));
-            ls.pred[0] = uni((int)(int16_t)ld_le16(e - 8)); ls.pred[1] = uni((int)(int16_t)ld_le16(e - 6)); ls.pred[2] = uni((int)(int16_t)ld_le16(e - 4));
+            const uint8_t* p = e - stride;
+            m0 = uni(ld_le32(p)); bit0 = uni(ld_le32(p + 4));
+            if (stride == kEntryBytes) { ls.pred[0] = uni((int)(int16_t)ld_le16(p + 8)); ls.pred[1] = uni((int)(int16_t)ld_le16(p + 10)); ls.pred[2] = uni((int)(int16_t)ld_le16(p + 12)); }
         }
         if (un.interval + 1 < sc) { m1 = uni(ld_le32(e)); bit1 = uni(ld_le32(e + 4)); }
         if (!(m0 < m1 && m1 <= mcus && bit0 <= bit1 && bit1 <= total)) { R.status[un.img] = kEFormat; return; }   // entries out of order or out of range
@@ -355,10 +357,11 @@ PCR_D void lane_unit_setup(const DevRecord& R, const Unit& un, const uint32_t* _
     const uint32_t sb = R.slot_base[ig], sc = R.slot_cnt[ig];
     const uint32_t ri = sd->ri, mcus = sd->mcus;
     if (ri == 0 && sc > 1) {
-        const uint8_t* e = R.rec + R.ent_off[ig] + (size_t)kEntryBytes * un.interval;
+        const uint32_t stride = entry_stride(ld_le16(R.rec + hdr_ecount_pos(R.n, R.G, un.scan, un.img)));
+        const uint8_t* e = R.rec + R.ent_off[ig] + (size_t)stride * un.interval;
         const uint32_t total = R.ivl_start[sb + sc] * 8;
         uint32_t m0 = 0, b0 = 0, m1 = mcus, b1 = total;
-        if (un.interval > 0) { m0 = lane_le32(e - 16); b0 = lane_le32(e - 12); }
+        if (un.interval > 0) { m0 = lane_le32(e - stride); b0 = lane_le32(e - stride + 4); }
         if (un.interval + 1 < sc) { m1 = lane_le32(e); b1 = lane_le32(e + 4); }
         if (!(m0 < m1 && m1 <= mcus && b0 <= b1 && b1 <= total)) { R.status[un.img] = kEFormat; return; }
         U->mcu0 = m0; U->mcu1 = m1; U->bit0 = b0; U->bit1 = b1;

@@ -448,7 +448,7 @@ static int validate_index(const uint8_t* hdr, const RecordHeader& h, std::vector
             (*off)[(size_t)g * n + i] = (uint32_t)pos; (*len)[(size_t)g * n + i] = L; pos += L;
         }
         if (h.version == 2)                                       // the group's entry points lie behind its regions
-            for (uint32_t i = 0; i < n; i++) pos += (uint64_t)kEntryBytes * ld_le16(hdr + hdr_ecount_pos(n, G, g, i));
+            for (uint32_t i = 0; i < n; i++) pos += entry_bytes(ld_le16(hdr + hdr_ecount_pos(n, G, g, i)));
         if (pos != ld_le64(hdr + hdr_group_end_pos(g))) return PCR_E_FORMAT;
         start = pos;
     }
@@ -483,13 +483,13 @@ static int finish_open(pcr_record* r, hipStream_t s) {
     if (r->hdr.version == 2) {
         const uint8_t* hdr = r->header.data();
         for (uint32_t g = 0; g < r->hdr.k_avail; g++) {
-            uint64_t cnt = 0;
-            for (uint32_t i = 0; i < n; i++) cnt += ld_le16(hdr + hdr_ecount_pos(n, G, g, i));
-            uint64_t at = ld_le64(hdr + hdr_group_end_pos(g)) - cnt * kEntryBytes;      // (validate_index: this is where the regions end)
+            uint64_t all = 0;
+            for (uint32_t i = 0; i < n; i++) all += entry_bytes(ld_le16(hdr + hdr_ecount_pos(n, G, g, i)));
+            uint64_t at = ld_le64(hdr + hdr_group_end_pos(g)) - all;                   // (validate_index: this is where the regions end)
             for (uint32_t i = 0; i < n; i++) {
-                const uint32_t c = ld_le16(hdr + hdr_ecount_pos(n, G, g, i));
-                ent_off[(size_t)i * G + g] = (uint32_t)at; ent_cnt[(size_t)i * G + g] = c;
-                at += (uint64_t)c * kEntryBytes;
+                const uint32_t field = ld_le16(hdr + hdr_ecount_pos(n, G, g, i));
+                ent_off[(size_t)i * G + g] = (uint32_t)at; ent_cnt[(size_t)i * G + g] = entry_count(field);
+                at += entry_bytes(field);
             }
         }
     }
@@ -614,10 +614,11 @@ static void measure_units(pcr_record* r, const uint8_t* bytes, size_t nbytes) {
             const size_t ig = (size_t)i * G + g;
             const uint32_t cnt = r->slot_cnt[ig], sb = r->slot_base[ig], eo = r->ent_off_h[ig];
             const uint64_t all = (uint64_t)r->scan[ig].data_len * 8;
-            if (eo && cnt > 1 && (size_t)eo + (size_t)kEntryBytes * (cnt - 1) <= nbytes) {
+            const uint32_t stride = entry_stride(ld_le16(r->header.data() + hdr_ecount_pos(n, G, g, i)));
+            if (eo && cnt > 1 && (size_t)eo + (size_t)stride * (cnt - 1) <= nbytes) {
                 uint64_t prev = 0;
                 for (uint32_t j = 0; j < cnt; j++) {
-                    const uint64_t end = j + 1 < cnt ? ld_le32(bytes + eo + (size_t)kEntryBytes * j + 4) : std::max<uint64_t>(all, prev);
+                    const uint64_t end = j + 1 < cnt ? ld_le32(bytes + eo + (size_t)stride * j + 4) : std::max<uint64_t>(all, prev);
                     r->unit_bits[sb + j] = (uint32_t)std::min<uint64_t>(end > prev ? end - prev : 0, 0xFFFFFFFFu);
                     prev = std::max(prev, end);
                 }

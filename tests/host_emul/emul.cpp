@@ -45,7 +45,7 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
     for (uint32_t g = 0; g < h.k_avail; g++) {
         uint64_t pos = start;
         for (uint32_t i = 0; i < n; i++) { uint32_t L = ld_le32(rec + hdr_len_pos(n, G, g, i)); off[(size_t)g * n + i] = (uint32_t)pos; len[(size_t)g * n + i] = L; pos += L; }
-        if (h.version == 2) for (uint32_t i = 0; i < n; i++) pos += (uint64_t)kEntryBytes * ld_le16(rec + hdr_ecount_pos(n, G, g, i));
+        if (h.version == 2) for (uint32_t i = 0; i < n; i++) pos += entry_bytes(ld_le16(rec + hdr_ecount_pos(n, G, g, i)));
         start = pos;
     }
     uint32_t i = (uint32_t)want_img;
@@ -69,14 +69,14 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
         if (starts.size() != nint) return kEFormat;
         starts.push_back((uint32_t)clean.size());
         // version 2: the units of a scan without restart markers start at its entry points
-        const uint8_t* ent = nullptr;
+        const uint8_t* ent = nullptr; uint32_t stride = kEntryBytes;
         if (h.version == 2 && sd.ri == 0 && !(img.progressive && sd.Ss == 0 && sd.Ah > 0)) {
-            const uint32_t ec = ld_le16(rec + hdr_ecount_pos(n, G, g, i));
-            if (ec) {
-                uint64_t cnt = 0, before = 0;
-                for (uint32_t q = 0; q < n; q++) { const uint32_t c = ld_le16(rec + hdr_ecount_pos(n, G, g, q)); cnt += c; if (q < i) before += c; }
-                ent = rec + ld_le64(rec + hdr_group_end_pos(g)) - cnt * kEntryBytes + before * kEntryBytes;
-                nint = 1 + ec;
+            const uint32_t field = ld_le16(rec + hdr_ecount_pos(n, G, g, i));
+            if (entry_count(field)) {
+                uint64_t all = 0, before = 0;
+                for (uint32_t q = 0; q < n; q++) { const uint64_t c = entry_bytes(ld_le16(rec + hdr_ecount_pos(n, G, g, q))); all += c; if (q < i) before += c; }
+                ent = rec + ld_le64(rec + hdr_group_end_pos(g)) - all + before;
+                nint = 1 + entry_count(field); stride = entry_stride(field);
             }
         }
         const uint32_t total_bits = (uint32_t)clean.size() * 8;
@@ -102,10 +102,13 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
             ls.pred[0] = ls.pred[1] = ls.pred[2] = 0;
             uint32_t byte_off, sub_bits = 0, nbits, pos0 = 0;
             if (ent) {
-                const uint8_t* e = ent + (size_t)kEntryBytes * j;
+                const uint8_t* e = ent + (size_t)stride * j;
                 uint32_t bit0 = 0, bit1 = total_bits;
                 ls.mcu0 = 0; ls.mcu1 = sd.mcus;
-                if (j > 0) { ls.mcu0 = ld_le32(e - 16); bit0 = ld_le32(e - 12); for (int q = 0; q < 3; q++) ls.pred[q] = (int16_t)ld_le16(e - 8 + 2 * q); }
+                if (j > 0) {
+                    ls.mcu0 = ld_le32(e - stride); bit0 = ld_le32(e - stride + 4);
+                    if (stride == kEntryBytes) for (int q = 0; q < 3; q++) ls.pred[q] = (int16_t)ld_le16(e - 8 + 2 * q);
+                }
                 if (j + 1 < nint) { ls.mcu1 = ld_le32(e); bit1 = ld_le32(e + 4); }
                 if (!(ls.mcu0 < ls.mcu1 && ls.mcu1 <= sd.mcus && bit0 <= bit1 && bit1 <= total_bits)) return kEFormat;
                 byte_off = bit0 >> 3; sub_bits = bit0 & 7; nbits = bit1 - (bit0 & ~7u); pos0 = bit0 & ~7u;

@@ -9,7 +9,7 @@ import oracle
 import pcrgen
 import paper_1911_00472_amd as pkg
 from test_gpu_parity import _check_record, _compare_pixels, _decode_on_streams, _torch
-from test_record_entry_points import _entries, _files
+from test_record_entry_points import _entries, _entry_at, _files
 
 pytestmark = pytest.mark.gpu
 
@@ -84,16 +84,13 @@ def test_damaged_entries_flag_the_image_and_nothing_else():
     torch = _torch()
     files = _files()[:4]
     rec = pkg.record_write_indexed(files, None, 32)
-    n, G = 4, 10
-    base = 24 + 8 * G + 8 * n + 4 * G * n
-    ec = np.frombuffer(rec[base + 8:base + 8 + 2 * G * n], np.uint16).reshape(G, n)
-    ge = np.frombuffer(rec[24:24 + 8 * G], np.uint64)
+    n = 4
     with pkg.pcr_open(rec, 0) as r:
         good = r.decode_batch(10).cpu().numpy()
         lay = r.output_layout()
     victim = 3
     for g, field, value, must_flag in ((1, 0, 10 ** 9, True), (4, 4, 2 ** 31, True), (0, 0, 0, True), (5, 4, None, False), (0, 8, None, False)):
-        at = int(ge[g]) - 16 * int(ec[g].sum()) + 16 * int(ec[g][:victim].sum()) + 16          # the victim's second entry of scan g + 1
+        at, _ = _entry_at(rec, g, victim, 1)                                                    # the victim's second entry of scan g + 1
         bad = bytearray(rec)
         if value is None:
             old = int.from_bytes(bad[at + field:at + field + 4], "little")

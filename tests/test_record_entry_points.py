@@ -21,25 +21,42 @@ def _files():
     return files
 
 
+def _entry_at(rec, g, i, j):
+    """Byte offset of entry j of scan g + 1 of image i in the record, and the size of the entries of that scan."""
+    n, G = int.from_bytes(rec[8:12], "little"), int.from_bytes(rec[12:16], "little")
+    base = 24 + 8 * G + 8 * n + 4 * G * n
+    field = np.frombuffer(bytes(rec[base + 8:base + 8 + 2 * G * n]), np.uint16).reshape(G, n).astype(np.int64)
+    size = (field & 0x7FFF) * np.where(field & 0x8000, 8, 16)
+    stride = 8 if field[g, i] & 0x8000 else 16
+    assert j < (field[g, i] & 0x7FFF)
+    ge = np.frombuffer(bytes(rec[24:24 + 8 * G]), np.uint64)
+    return int(ge[g]) - int(size[g].sum()) + int(size[g][:i].sum()) + stride * j, stride
+
+
 def _entries(rec):
-    """{(g, i): [(mcu, bit, (p0, p1, p2))]} and the interval, parsed here from the layout in include/pcr.h."""
+    """{(g, i): [(mcu, bit, (p0, p1, p2))]} and the interval, parsed here from the layout in include/pcr.h (entries of
+    16 bytes, or of 8 without the predictions where the count's top bit says so)."""
     n, G = int.from_bytes(rec[8:12], "little"), int.from_bytes(rec[12:16], "little")
     assert int.from_bytes(rec[4:8], "little") == 2
     base = 24 + 8 * G + 8 * n + 4 * G * n
     interval = int.from_bytes(rec[base:base + 4], "little")
-    ec = np.frombuffer(rec[base + 8:base + 8 + 2 * G * n], np.uint16).reshape(G, n)
+    field = np.frombuffer(rec[base + 8:base + 8 + 2 * G * n], np.uint16).reshape(G, n).astype(np.int64)
+    ec, stride = field & 0x7FFF, np.where(field & 0x8000, 8, 16)
     ge = np.frombuffer(rec[24:24 + 8 * G], np.uint64)
     out = {}
     for g in range(G):
-        at = int(ge[g]) - 16 * int(ec[g].sum())
+        at = int(ge[g]) - int((ec[g] * stride[g]).sum())
         for i in range(n):
             lst = []
             for _ in range(int(ec[g, i])):
-                e = rec[at:at + 16]
-                lst.append((int.from_bytes(e[0:4], "little"), int.from_bytes(e[4:8], "little"),
-                            tuple(int.from_bytes(e[8 + 2 * j:10 + 2 * j], "little", signed=True) for j in range(3))))
-                assert e[14:16] == b"\0\0"
-                at += 16
+                e = rec[at:at + int(stride[g, i])]
+                if stride[g, i] == 16:
+                    lst.append((int.from_bytes(e[0:4], "little"), int.from_bytes(e[4:8], "little"),
+                                tuple(int.from_bytes(e[8 + 2 * j:10 + 2 * j], "little", signed=True) for j in range(3))))
+                    assert e[14:16] == b"\0\0"
+                else:
+                    lst.append((int.from_bytes(e[0:4], "little"), int.from_bytes(e[4:8], "little"), (0, 0, 0)))
+                at += int(stride[g, i])
             out[(g, i)] = lst
         assert at == int(ge[g])
     return out, interval
@@ -59,7 +76,10 @@ def test_indexed_record_holds_the_same_images_and_the_oracle_sees_no_difference(
         ent, iv = _entries(r2)
         assert iv == interval
         nent = sum(len(v) for v in ent.values())
-        assert len(r2) == len(r1) + (h2["header_bytes"] - h1["header_bytes"]) + 16 * nent
+        # entries with DC predictions (DC scans; every scan of a baseline file) take 16 bytes, those of AC scans 8
+        ebytes = sum(len(v) * _entry_at(r2, g, i, 0)[1] for (g, i), v in ent.items() if v)
+        assert len(r2) == len(r1) + (h2["header_bytes"] - h1["header_bytes"]) + ebytes
+        assert all(_entry_at(r2, g, i, 0)[1] == (16 if g == 0 else 8) for (g, i), v in ent.items() if v)       # (progressive files here: scan 1 is the DC scan)
         if interval == 1000000:
             assert nent == 0
         for i in range(len(files)):
@@ -147,12 +167,7 @@ def test_damaged_entries_are_refused_or_harmless_never_out_of_range(emul):  # no
     files = _files()[:2]
     rec = bytearray(pkg.record_write_indexed(files, None, 32))
     ent, _ = _entries(bytes(rec))
-    G = 10
-    ge = np.frombuffer(bytes(rec[24:24 + 8 * G]), np.uint64)
-    n = 2
-    base = 24 + 8 * G + 8 * n + 4 * G * n
-    ec = np.frombuffer(bytes(rec[base + 8:base + 8 + 2 * G * n]), np.uint16).reshape(G, n)
-    at = int(ge[1]) - 16 * int(ec[1].sum())                                 # first entry of scan 2 of image 0
+    at, _ = _entry_at(rec, 1, 0, 0)                                         # first entry of scan 2 of image 0
     info = oracle.record_image_info(bytes(rec), 0)
     for field, value in ((0, 10 ** 9), (4, 2 ** 31)):
         bad = bytearray(rec)
