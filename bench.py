@@ -52,11 +52,11 @@ VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # vector ALU: 256 CUs x 4 SIM
 # the counters were taken: an entry is removed (-> null in the output) whenever its kernel changes.
 PMC = {
     # mean of the two launches of one decode (profiles/decode_kernels_imagenet_like_k10_counters.md)
-    "ac_refine_lanes": {"salu": 39.6e6, "valu": 175.5e6, "fetch_bytes": 321.0e6, "write_bytes": 410.9e6,
+    "ac_refine_lanes": {"salu": 36.4e6, "valu": 160.6e6, "fetch_bytes": 499.6e6, "write_bytes": 324.5e6,
                         "source": "profiles/decode_kernels_imagenet_like_k10_counters.md (SQ_INSTS_SALU, SQ_INSTS_VALU, FETCH_SIZE x 2.0, WRITE_SIZE x 1.0)"},
 }
 # all kernels of that decode, same counter run
-RECORD0_INSTS = {"scalar": 302.6e6, "vector": 840.3e6, "source": "profiles/decode_kernels_imagenet_like_k10_counters.md (whole decode)"}
+RECORD0_INSTS = {"scalar": 294.8e6, "vector": 796.5e6, "source": "profiles/decode_kernels_imagenet_like_k10_counters.md (whole decode)"}
 
 # The work of one Huffman-coded symbol, at the very least.
 # One wavefront per unit (pcr_entropy.h): the serial chain -- fetch the packed word of the current bit offset, test it,
@@ -569,7 +569,7 @@ def main():
     ap.add_argument("--workload", default="imagenet_like", choices=sorted(WORKLOAD_SCAN_GROUPS))
     ap.add_argument("--images", type=int, default=None, help="use only the first N images of the workload")
     ap.add_argument("--scan-group", type=int, default=None, help="the scan group `value` is quoted at (default: the highest)")
-    ap.add_argument("--entry-interval", type=int, default=128, help="MCUs between the entry points the record writer stores (record version 2)")
+    ap.add_argument("--entry-interval", type=int, default=64, help="MCUs between the entry points the record writer stores (record version 2)")
     ap.add_argument("--only", action="store_true", help="time only the scan group of --scan-group (for profiler runs)")
     ap.add_argument("--extras", action="store_true", help="also: fidelity upgrades, training tail, similarity scores, baseline files, restart intervals")
     ap.add_argument("--lane-decoders", type=int, default=0, choices=(-1, 0, 1),
@@ -692,7 +692,7 @@ def main():
     copy_gbps = 5 * 2 * ca.numel() / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
     del ca, cb
 
-    default_config = name == "imagenet_like" and args.images is None and headline_k == 10
+    default_config = name == "imagenet_like" and args.images is None and headline_k == 10 and args.entry_interval == ap.get_default("entry_interval")
     nrec0 = job.handles[0].n
     job.handles[0].decode_batch(headline_k, out=job.outs[0], stream=job.streams[0].cuda_stream)
     torch.cuda.synchronize()

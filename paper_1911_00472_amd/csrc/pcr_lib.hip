@@ -183,6 +183,10 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
     struct Item { Unit u; uint32_t bytes; uint32_t bits; };      // bytes: the scan's mean per unit; bits: the unit's own, if known
     // one list per (dependency level, kind of scan, DC decoder shape: 0 for the AC kinds)
     std::vector<std::vector<Item>> lists((size_t)r->max_level * kNumKinds * kDcShapes);
+    // ... and, per list, the runs of units that belong to one scan (first item, count, the scan's mean bytes per unit):
+    // ordering a list scan by scan moves whole runs, a few thousand of them, not hundreds of thousands of units
+    struct Run { uint32_t first, count, bytes; };
+    std::vector<std::vector<Run>> runs(lists.size());
     std::vector<std::vector<RefineScan>> rlists(r->max_level);
     std::vector<ApplyUnit> apply; uint32_t max_blk = 0;
     for (uint32_t i = 0; i < n; i++) {
@@ -209,9 +213,10 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
                 shape = dc_shape(sd.ns, hs[0], vs[0], hs[1], vs[1], hs[2], vs[2]);
             }
             const uint32_t cnt = r->slot_cnt[ig];
+            const size_t li = ((size_t)(r->level[ig] - 1) * kNumKinds + kind) * kDcShapes + shape;
+            if (cnt) runs[li].push_back(Run{(uint32_t)lists[li].size(), cnt, sd.data_len / cnt});
             for (uint32_t j = 0; j < cnt; j++)
-                lists[((size_t)(r->level[ig] - 1) * kNumKinds + kind) * kDcShapes + shape].push_back(
-                    Item{Unit{i, g, j, r->slot_base[ig]}, sd.data_len / cnt, r->unit_bits.empty() ? sd.data_len / cnt * 8 : r->unit_bits[r->slot_base[ig] + j]});
+                lists[li].push_back(Item{Unit{i, g, j, r->slot_base[ig]}, sd.data_len / cnt, r->unit_bits.empty() ? sd.data_len / cnt * 8 : r->unit_bits[r->slot_base[ig] + j]});
         }
         if (have_dc != (1u << r->img[i].nc) - 1u) plan.dc_complete = false;
         for (int c = 0; c < r->img[i].nc; c++) if (refine[c]) {
@@ -220,9 +225,15 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
         }
     }
     for (size_t li = 0; li < lists.size(); li++) {
-        auto& l = lists[li];
-        if (l.empty()) continue;
-        std::stable_sort(l.begin(), l.end(), [](const Item& a, const Item& b) { return a.bytes > b.bytes; });   // longest first
+        if (lists[li].empty()) continue;
+        std::vector<Item> l;                                          // the list with the scans of the longest units first
+        {
+            auto& rn = runs[li];
+            std::stable_sort(rn.begin(), rn.end(), [](const Run& a, const Run& b) { return a.bytes > b.bytes; });
+            l.reserve(lists[li].size());
+            for (const Run& q : rn) l.insert(l.end(), lists[li].begin() + q.first, lists[li].begin() + q.first + q.count);
+            std::vector<Item>().swap(lists[li]);
+        }
         const int kind_of_list = (int)((li / kDcShapes) % kNumKinds);
         std::vector<LaneJob> jobs;
         if (kind_of_list == kAcFirst || kind_of_list == kAcRefine) {
@@ -240,7 +251,9 @@ int build_plan(pcr_record* r, int k0, int k, Plan** out) {
                     }
                     w1++;
                 }
-                std::stable_sort(l.begin() + w0, l.begin() + w1, [](const Item& a, const Item& b) { return a.bits > b.bits; });
+                // (without the units' own lengths -- a record opened from device memory -- every unit carries its scan's mean,
+                // and the scans are in that order already)
+                if (!r->unit_bits.empty()) std::stable_sort(l.begin() + w0, l.begin() + w1, [](const Item& a, const Item& b) { return a.bits > b.bits; });
                 for (size_t e = w0; e < w1; e += kEntropyLanes) {
                     LaneJob j = proto;
                     j.first = (uint32_t)e; j.count = (uint32_t)std::min<size_t>(kEntropyLanes, w1 - e);
