@@ -112,3 +112,24 @@ def test_damaged_entries_flag_the_image_and_nothing_else():
             assert not out[sl].any()
         else:
             assert not np.array_equal(out[sl], good[sl])
+
+
+def test_entry_counts_that_do_not_fit_the_group_are_refused_at_open():
+    """The header says how many entries every (image, scan) has and of which form (16 bytes, or 8 where the count's top
+    bit is set); regions and entries must tile the group exactly, so a flipped form bit or a wrong count is a format
+    error when the record is opened, before anything is decoded."""
+    files = _files()[:3]
+    rec = pkg.record_write_indexed(files, None, 16)
+    n, G = 3, 10
+    base = 24 + 8 * G + 8 * n + 4 * G * n + 8
+    for g, i, change in ((1, 0, 0x8000), (0, 1, 0x8000), (4, 1, 1), (9, 0, -1)):
+        pos = base + 2 * (g * n + i)
+        field = int.from_bytes(rec[pos:pos + 2], "little")
+        assert field & 0x7FFF
+        bad = bytearray(rec)
+        bad[pos:pos + 2] = ((field ^ change) if change == 0x8000 else (field + change)).to_bytes(2, "little")
+        with pytest.raises(pkg.PcrError) as e:
+            pkg.pcr_open(bytes(bad), 0)
+        assert e.value.code == pkg.E_FORMAT
+    with pkg.pcr_open(rec, 0) as r:
+        assert r.n == 3

@@ -175,5 +175,4 @@ def test_damaged_entries_are_refused_or_harmless_never_out_of_range(emul):  # no
         oracle.decode_record_image(bytes(bad), 0, 10)
         with pytest.raises(AssertionError, match="-2"):
             emul(bytes(bad), 0, 10, info)
-    # file sizes that do not fit the entry counts are refused when the record is opened (host check)
-    L = pkg.lib()
+    # (entry counts that do not fit the group are refused when the record is opened: tests/test_gpu_entry_points.py)
