@@ -332,7 +332,7 @@ int pcr_record_write(const void* const* files, const size_t* sizes, const int32_
 /* pcr_record_write with entry points (record version 2).  The paper's metadata says where every scan group starts;
  * its Section 4.2 names the decode as the bottleneck, and each scan of a stock file is one serial stream.  This
  * writer walks every scan once and stores, about every entry_interval MCUs of the scan (blocks, for a scan of one
- * component; every entry_interval / 2 in AC refinement scans, whose symbols take a decoder longest), a place where a
+ * component; every entry_interval / 2 in AC refinement scans and in DC first scans, whose units take a decoder longest), a place where a
  * decoder may start: a block boundary outside any end-of-band run, its bit offset in the scan's data without the
  * stuffed bytes, and -- where the scan has them -- the DC predictions there (16 bytes per entry with predictions, 8 bytes
  * per entry of an AC scan, which has none and is where nearly all entries are; kept at the end of the scan's own scan
@@ -375,8 +375,9 @@ int pcr_transcode_symbol_counts(const void* src_jpeg, size_t src_bytes, const in
  * (restart intervals, entry-point units); a launch either gives every unit a wavefront that decodes it on the scalar
  * unit, or every unit a lane (64 units per wavefront).  Lanes need a fifth of the instructions but take longer per unit:
  * they win when the GPU is shared between the decodes of several records, or when a launch has very many units.
- * mode 0 (default): lanes for launches of at least 8192 units if the process has more than one record open, of at least
- * 32768 units otherwise; 1: lanes wherever the kernels exist and the record's scans have several units; -1: never.
+ * mode 0 (default): lanes for AC launches of at least 8192 units if the process has more than one record open, of at
+ * least 32768 units otherwise, and for launches of DC first scans of at least 4096 units if it has more than one record
+ * open; 1: lanes wherever the kernels exist and the record's scans have several units; -1: never.
  * The results are the same bit for bit.  Takes effect from the next decode call.  PCR_E_ARG: null handle or another
  * mode. */
 int pcr_set_lane_decoders(pcr_record* rec, int mode);

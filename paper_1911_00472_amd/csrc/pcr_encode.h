@@ -192,9 +192,11 @@ inline int find_entry_points(const uint8_t* file, const uint64_t* ends, uint32_t
             uint32_t eobrun = 0;
             const uint32_t m0 = sd.ri ? iv * sd.ri : 0, m1 = sd.ri ? std::min(m0 + sd.ri, sd.mcus) : sd.mcus;
             // AC refinement scans get an entry every interval / 2: a symbol of theirs takes a decoder more than twice as
-            // long as one of a first scan (zero runs are counted against the block's history, correction bits follow), and
-            // a launch of the lane-per-unit decoders takes as long as its longest unit.
-            const uint32_t step = (!seq && sd.Ss > 0 && sd.Ah > 0 && interval >= 2) ? interval / 2 : interval;
+            // long as one of an AC first scan (zero runs are counted against the block's history, correction bits follow),
+            // and a launch of the lane-per-unit decoders takes as long as its longest unit.  So do DC first scans: an MCU
+            // of theirs is several symbols (six with 4:2:0 sampling), each found by comparing with the table's codes.
+            const bool halved = !seq && interval >= 2 && ((sd.Ss > 0 && sd.Ah > 0) || sd.Ss == 0);
+            const uint32_t step = halved ? interval / 2 : interval;
             uint32_t next_entry = step;
             for (uint32_t m = m0; m < m1 && !b.bad; m++) {
                 if (sd.ri == 0 && m >= next_entry && eobrun == 0 && E.size() < kMaxEntriesPerScan) {

@@ -6,8 +6,8 @@
 //                interval of a scan, or the stretch between two entry points of the record (the whole scan
 //                where there is neither)
 //   k_refine_blocks   second phase of AC refinement, one lane per block
-//   k_ac_first_lanes, k_ac_refine_lanes   the AC scans again with one LANE per unit (pcr_lanes.h), for launches
-//                with very many units; k_refine_history, k_refine_deal: per-block work before and after
+//   k_dc_first_lanes, k_ac_first_lanes, k_ac_refine_lanes   the same scans with one LANE per unit (pcr_lanes.h), for
+//                launches with very many units; k_refine_history, k_refine_deal: per-block work before and after
 //   k_apply      data-parallel refinement (DC bits, AC corrections and new coefficients)
 //   k_pixel      de-quantise + IDCT + chroma replication + YCbCr->RGB + store
 //   k_gather     materialise an image's scan prefix (parity hook)
@@ -552,6 +552,76 @@ __global__ void __launch_bounds__(kEntropyLanes) k_ac_refine_lanes(DevRecord R, 
     if (!U.ok) return;
     U.tab = reinterpret_cast<const LaneTab*>(&tabs[slot][0]);
     const int rc = lane_decode_ac_refine(U, R.masks + R.mask_off[key], U.plane_elems >> 6, &rings, &hring, t);
+    if (rc != kOk) R.status[un.img] = rc;
+}
+
+// DC first scans with one lane per unit (pcr_lanes.h: lane_decode_dc_first): 64 consecutive units of the launch's list
+// per wavefront, whatever images they belong to -- every lane builds its own small tables.  The checks and ranges are
+// those of unit_setup.
+PCR_D __attribute__((always_inline)) void lane_dc_unit_setup(const DevRecord& R, const Unit& un, const uint32_t* __restrict__ clean32, uint32_t to_planes, LaneDcUnit* U) {
+    U->ok = false;
+    const ImgDesc* img = &R.img[un.img];
+    if (R.status[un.img] != kOk || un.scan >= img->nscans) return;
+    const size_t ig = (size_t)un.img * R.G + un.scan;
+    const ScanDesc* sd = &R.scan[ig];
+    if (!sd->valid || sd->Ss != 0 || sd->Ah != 0 || !img->progressive || sd->ns < 1 || sd->ns > kMaxComp) return;
+    const uint32_t sb = R.slot_base[ig], sc = R.slot_cnt[ig];
+    const uint32_t ri = sd->ri, mcus = sd->mcus;
+    U->pred0 = U->pred1 = U->pred2 = 0;
+    if (ri == 0 && sc > 1) {
+        const uint32_t stride = entry_stride(ld_le16(R.rec + hdr_ecount_pos(R.n, R.G, un.scan, un.img)));
+        const uint8_t* e = R.rec + R.ent_off[ig] + (size_t)stride * un.interval;
+        const uint32_t total = R.ivl_start[sb + sc] * 8;
+        uint32_t m0 = 0, b0 = 0, m1 = mcus, b1 = total;
+        if (un.interval > 0) {
+            const uint8_t* p = e - stride;
+            m0 = lane_le32(p); b0 = lane_le32(p + 4);
+            if (stride == kEntryBytes) { U->pred0 = (int)(int16_t)ld_le16(p + 8); U->pred1 = (int)(int16_t)ld_le16(p + 10); U->pred2 = (int)(int16_t)ld_le16(p + 12); }
+        }
+        if (un.interval + 1 < sc) { m1 = lane_le32(e); b1 = lane_le32(e + 4); }
+        if (!(m0 < m1 && m1 <= mcus && b0 <= b1 && b1 <= total)) { R.status[un.img] = kEFormat; return; }
+        U->mcu0 = m0; U->mcu1 = m1; U->bit0 = b0; U->bit1 = b1;
+    } else {
+        const uint32_t b0 = R.ivl_start[sb + un.interval], b1 = R.ivl_start[sb + un.interval + 1];
+        U->mcu0 = ri ? un.interval * ri : 0;
+        U->mcu1 = ri ? (U->mcu0 + ri < mcus ? U->mcu0 + ri : mcus) : mcus;
+        if (U->mcu0 >= mcus) return;
+        U->bit0 = b0 * 8; U->bit1 = (b1 > b0 ? b1 : b0) * 8;
+    }
+    U->mcu_w = sd->mcu_w;
+    if (U->mcu_w == 0) return;
+    U->ns = sd->ns; U->Al = sd->Al;
+    const uint32_t nb0 = (uint32_t)img->bw[0] * img->bh[0], nb1 = img->nc > 1 ? (uint32_t)img->bw[1] * img->bh[1] : 0u, nb2 = img->nc > 2 ? (uint32_t)img->bw[2] * img->bh[2] : 0u;
+    const bool one = sd->ns == 1;                               // a scan of one component goes block by block
+    // scan component j is component c of the image (sampling factors are 1 or 2: the parser refuses anything else)
+    auto component = [&](int j, uint32_t* hs, uint32_t* vs, uint32_t* bw, uint32_t* pblk, const uint8_t** def) {
+        const int c = j < sd->ns ? (int)sd->comp[j] : 0;
+        *hs = one ? 1u : (uint32_t)img->hs[c]; *vs = one ? 1u : (uint32_t)img->vs[c]; *bw = img->bw[c];
+        *pblk = c == 0 ? 0u : (c == 1 ? nb0 : nb0 + nb1);
+        *def = R.rec + sd->dc_off[j < sd->ns ? j : 0];
+    };
+    component(0, &U->hs0, &U->vs0, &U->bw0, &U->pblk0, &U->def0);
+    component(1, &U->hs1, &U->vs1, &U->bw1, &U->pblk1, &U->def1);
+    component(2, &U->hs2, &U->vs2, &U->bw2, &U->pblk2, &U->def2);
+    U->nblocks = nb0 + nb1 + nb2;
+    U->dense = R.dc + (R.coef_off[un.img] >> 6);
+    U->planes = to_planes ? R.coef + R.coef_off[un.img] : nullptr;
+    U->words = clean32 + (clean_base(sd->data_off) >> 2);
+    U->ok = true;
+}
+
+__global__ void __launch_bounds__(kEntropyLanes) k_dc_first_lanes(DevRecord R, const Unit* __restrict__ units, uint32_t nunits,
+        const uint32_t* __restrict__ clean32, uint32_t to_planes) {
+    __shared__ LaneRing rings;
+    __shared__ LaneDcTabs tabs;
+    dc_kernel_priority();
+    const uint32_t t = threadIdx.x, u = blockIdx.x * kEntropyLanes + t;
+    LaneDcUnit U;
+    U.ok = false;
+    Unit un = units[u < nunits ? u : 0u];
+    if (u < nunits) lane_dc_unit_setup(R, un, clean32, to_planes, &U);
+    if (!U.ok) return;
+    const int rc = lane_decode_dc_first(U, &rings, &tabs, t);
     if (rc != kOk) R.status[un.img] = rc;
 }
 

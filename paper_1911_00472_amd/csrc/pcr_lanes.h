@@ -223,6 +223,138 @@ PCR_HD int lane_decode_ac_first(const LaneUnit& U, LaneRing* rings, uint32_t lan
 }
 
 // ---------------------------------------------------------------------------------------
+// DC first scan of one unit (interleaved: up to three components, their blocks MCU by MCU; or one component, block by
+// block over the blocks that cover its samples).  A unit's lanes belong to different images, each with its own two or
+// three small tables, so the tables do not go through the job mechanism of the AC kernels: every lane makes its own,
+// in LDS, in a form that needs no look-up memory worth the name -- the first sixteen codes of the table (more are no
+// DC categories; the wavefront decoders drop them the same way) in code order, each as its left-aligned 16-bit value.
+// Canonical codes in that form are increasing, so the code at the head of a 16-bit window w is the last one that is
+// <= w: the lane counts them.  One symbol -- one block -- per trip.
+// ---------------------------------------------------------------------------------------
+constexpr uint32_t kLaneDcCodes = 16;
+struct LaneDcTab {                                            // 80 bytes: a multiple of 16 (the limits are read as two 16-byte vectors)
+    uint16_t lim[kLaneDcCodes];                               // left-aligned code of entry i; 0xFFFF where there is none (no code is all ones)
+    uint16_t ls[kLaneDcCodes];                                // (length << 8) | category; 0: no code
+    uint32_t end;                                             // first left-aligned value that is no code of the (truncated) table
+    uint32_t pad[3];
+};
+static_assert(sizeof(LaneDcTab) == 80, "LaneDcTab layout");
+struct LaneDcTabs { LaneDcTab t[kMaxComp][64]; };            // [scan component][lane]
+
+struct LaneDcUnit {
+    const uint32_t* words; uint32_t bit0, bit1;               // as LaneUnit
+    uint32_t mcu0, mcu1, mcu_w;
+    uint32_t ns;                                              // components of the scan
+    // per scan component 0, 1, 2 (single members, no arrays: a member picked by a run-time component number must be a
+    // select between registers, and from an array the compiler makes it a load from a selected address in scratch memory):
+    uint32_t hs0, hs1, hs2, vs0, vs1, vs2;                    // blocks per MCU (1 x 1 if ns == 1)
+    uint32_t bw0, bw1, bw2;                                   // blocks per row of the component's plane
+    uint32_t pblk0, pblk1, pblk2;                             // first block of its plane in the image's coefficient buffer
+    int pred0, pred1, pred2;                                  // DC predictions at the unit's first MCU
+    uint32_t Al;
+    int16_t* dense;                                           // the image's compact copy of the DC coefficients: one value per block of the buffer
+    int16_t* planes;                                          // the image's coefficient buffer (element 0 of every block), or null
+    uint32_t nblocks;                                         // blocks of that buffer
+    const uint8_t *def0, *def1, *def2;                        // each scan component's table definition: 16 counts, then the symbols in code order
+    bool ok;
+};
+
+// The table of a definition (call per lane; t is the lane's own).
+PCR_HD __attribute__((always_inline)) void lane_dctab_build(LaneDcTab* t, const uint8_t* bits_vals) {
+    for (uint32_t i = 0; i < kLaneDcCodes; i++) { t->lim[i] = 0xFFFFu; t->ls[i] = 0; }
+    uint32_t code = 0, k = 0, end = 0;
+    bool open = true;                                         // the first kLaneDcCodes codes are still being listed
+    for (uint32_t L = 1; L <= 16; L++) {
+        const uint32_t cnt = bits_vals[L - 1];
+        for (uint32_t j = 0; j < cnt; j++) {
+            const uint32_t left = code << (16 - L);
+            if (k < kLaneDcCodes && left < 0xFFFFu) {
+                t->lim[k] = (uint16_t)left; t->ls[k] = (uint16_t)((L << 8) | (bits_vals[16 + k] & 15u));
+                end = left + (1u << (16 - L));
+            } else open = false;
+            code++; k++;
+        }
+        code <<= 1;
+    }
+    (void)open;
+    t->end = end > 0x10000u ? 0x10000u : end;
+}
+
+// v, as a value in a vector register whose origin the compiler does not look behind (see lane_decode_dc_first)
+PCR_HD uint32_t lane_value(uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("" : "+v"(v));
+#endif
+    return v;
+}
+
+PCR_HD __attribute__((always_inline)) int lane_decode_dc_first(const LaneDcUnit& U, LaneRing* rings, LaneDcTabs* tabs, uint32_t lane) {
+    // The per-component members as plain values: picked by a run-time component number straight from U, the compiler
+    // picks the member's address instead and loads from it, which puts the whole of U into scratch memory.
+    const uint32_t hs0 = lane_value(U.hs0), hs1 = lane_value(U.hs1), hs2 = lane_value(U.hs2);
+    const uint32_t vs0 = lane_value(U.vs0), vs1 = lane_value(U.vs1), vs2 = lane_value(U.vs2);
+    const uint32_t bw0 = lane_value(U.bw0), bw1 = lane_value(U.bw1), bw2 = lane_value(U.bw2);
+    const uint32_t pb0 = lane_value(U.pblk0), pb1 = lane_value(U.pblk1), pb2 = lane_value(U.pblk2);
+    LaneStream st;
+    st.init(U.words, U.bit0, U.bit1, rings, lane);
+    static_assert(kMaxComp == 3, "the components are spelled out (an array indexed in a loop ends up in scratch memory)");
+    lane_dctab_build(&tabs->t[0][lane], U.def0);
+    if (U.ns > 1) lane_dctab_build(&tabs->t[1][lane], U.def1);
+    if (U.ns > 2) lane_dctab_build(&tabs->t[2][lane], U.def2);
+    const uint32_t n0 = hs0 * vs0, n01 = n0 + (U.ns > 1 ? hs1 * vs1 : 0u);
+    const uint32_t bpm = n01 + (U.ns > 2 ? hs2 * vs2 : 0u);
+    uint32_t left = U.mcu1 - U.mcu0;                          // MCUs not finished yet
+    uint32_t my = U.mcu0 / U.mcu_w, mx = U.mcu0 - my * U.mcu_w, j = 0;
+    int pred0 = U.pred0, pred1 = U.pred1, pred2 = U.pred2;
+    uint32_t bad = 0;
+    while (left != 0) {
+        if (any_lane(st.short_of(2))) st.refill();
+        st.top_up();
+        const uint32_t win = st.window(), w16 = win >> 16;
+        // the block: component c of the scan, block (by, bx) of its part of the MCU (sampling factors are 1 or 2)
+        const uint32_t c = (j >= n0 ? 1u : 0u) + (j >= n01 ? 1u : 0u);
+        const uint32_t jj = j - (c == 0 ? 0u : (c == 1 ? n0 : n01));
+        const uint32_t hs = c == 0 ? hs0 : (c == 1 ? hs1 : hs2), vs = c == 0 ? vs0 : (c == 1 ? vs1 : vs2);
+        const uint32_t bw = c == 0 ? bw0 : (c == 1 ? bw1 : bw2), p0 = c == 0 ? pb0 : (c == 1 ? pb1 : pb2);
+        const uint32_t bx = jj & (hs - 1u), by = jj >> (hs - 1u);
+        const uint32_t blk = p0 + (my * vs + by) * bw + mx * hs + bx;
+        // the code: the last of the table's that is not above the window
+        const LaneDcTab* T = &tabs->t[c][lane];
+        const uint4 la = *reinterpret_cast<const uint4*>(&T->lim[0]), lb = *reinterpret_cast<const uint4*>(&T->lim[8]);
+        uint32_t cnt = 0;
+        const uint32_t lw[8] = {la.x, la.y, la.z, la.w, lb.x, lb.y, lb.z, lb.w};
+#pragma unroll
+        for (int q = 0; q < 8; q++) cnt += ((lw[q] & 0xFFFFu) <= w16 ? 1u : 0u) + ((lw[q] >> 16) <= w16 ? 1u : 0u);
+        const uint32_t e = cnt ? T->ls[cnt - 1] : 0u;
+        const bool code_ok = e != 0 && w16 < T->end;
+        const uint32_t len = code_ok ? e >> 8 : 1u, s = code_ok ? e & 15u : 0u;
+        const uint32_t extra = ((win << len) >> 1) >> (31u - s);
+        const int diff = extend(extra, (int)s);
+        st.consume(len + s);
+        bad |= code_ok ? 0u : 1u;
+        bad |= st.remain < 0 ? 1u : 0u;                       // never walk beyond the unit's data
+        int pred = c == 0 ? pred0 : (c == 1 ? pred1 : pred2);
+        pred += diff;
+        pred0 = c == 0 ? pred : pred0; pred1 = c == 1 ? pred : pred1; pred2 = c == 2 ? pred : pred2;
+        if (!bad && blk < U.nblocks) {
+            const int16_t v = (int16_t)(pred * (1 << U.Al));
+            U.dense[blk] = v;
+            if (U.planes) U.planes[(size_t)blk * 64] = v;
+        }
+        // on to the next block, MCU, row of MCUs
+        j++;
+        const bool mcu_done = j == bpm;
+        j = mcu_done ? 0u : j;
+        mx += mcu_done ? 1u : 0u;
+        const bool row_done = mx == U.mcu_w;
+        mx = row_done ? 0u : mx; my += row_done ? 1u : 0u;
+        left -= mcu_done ? 1u : 0u;
+        if (bad) left = 0;                                    // stop at the first damaged block
+    }
+    return bad ? kEFormat : kOk;
+}
+
+// ---------------------------------------------------------------------------------------
 // AC refinement scan of one unit, complete in one pass: where the new coefficients go, their signs, and the correction
 // bits.  The history of a block (which positions of the band are non-zero already) is read from the kRefHist word of
 // the block's record, which k_refine_history has written for every block of the scan beforehand; like the stream

@@ -365,6 +365,16 @@ bool lanes_pay(const pcr_record* r, const LevelList& l) {
     return l.n >= least && l.n >= 32u * l.n_jobs;            // (jobs half full at least: few tables per 64 units)
 }
 
+// The same question for a launch of DC first scans.  A lane decodes a DC symbol with a fifth of the instructions a
+// wavefront spends on it, but a launch of lanes takes as long as one unit, however few there are: it pays when the
+// wavefront decoders of several records would queue for the scalar units.
+constexpr uint32_t kDcLanesMinUnits = 4096;
+bool dc_lanes_pay(const pcr_record* r, const LevelList& l) {
+    if (r->lane_mode < 0) return false;
+    if (r->lane_mode > 0) return l.n >= (uint32_t)kEntropyLanes;
+    return g_open_records.load(std::memory_order_relaxed) > 1 && l.n >= kDcLanesMinUnits;
+}
+
 // Steps 1-5 of the path (index .. entropy decode + refinement) for scans 1..k.
 // refine_in_memory: also run k_apply, which leaves the refined coefficients in the planes (the coefficient
 // export needs that; the pixel kernel replays the refinement itself from the lists of k_apply_prep).
@@ -402,7 +412,11 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
     for (auto& l : plan->levels) {
         const dim3 grid(l.n), block(kEntropyLanes);
         if (l.kind == kAcFirst || l.kind == kAcRefine) { if (lanes_pay(r, l)) r->last_lane_launches++; else r->last_wave_launches++; }
-        if (l.kind == kDcFirst) {
+        if (l.kind == kDcFirst && dc_lanes_pay(r, l)) {
+            hipLaunchKernelGGL(k_dc_first_lanes, dim3((l.n + kEntropyLanes - 1) / kEntropyLanes), block, 0, s, r->d, l.d_units, l.n, c32, dc_to_planes ? 1u : 0u);
+            mark(r, PCR_STAGE_DC_FIRST, s);
+        }
+        else if (l.kind == kDcFirst) {
             const uint32_t dcp = dc_to_planes ? 1u : 0u;
             switch (l.shape) {
                 case 1: hipLaunchKernelGGL(k_dc_first<1>, grid, block, 0, s, r->d, l.d_units, l.n, c32, h64, dcp); break;

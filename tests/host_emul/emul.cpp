@@ -133,6 +133,28 @@ extern "C" int emul_decode_record(const uint8_t* rec, size_t nbytes, int k, int6
                 sw.init(reinterpret_cast<const uint32_t*>(clean.data()), byte_off, sub_bits, nbits, pos0, tb.ac[0], true, 0, true);
                 IndexSink ssink; ssink.init(coef.data(), (uint32_t)coef.size(), 0);
                 rc = decode_sequential(&sw, ls, tb, &ssink);
+            } else if (sd.Ss == 0 && by_lane && img.progressive && sd.Ah == 0) {
+                // the DC first scan with the lane decoder: the unit set up as k_dc_first_lanes sets it up
+                static LaneRing ring; static LaneDcTabs dtabs;
+                std::vector<int16_t> dense(coef.size() / 64 + 1, 0);
+                LaneDcUnit U;
+                U.words = reinterpret_cast<const uint32_t*>(clean.data());
+                U.bit0 = byte_off * 8 + sub_bits; U.bit1 = byte_off * 8 + nbits;
+                U.mcu0 = ls.mcu0; U.mcu1 = ls.mcu1; U.mcu_w = sd.mcu_w; U.ns = (uint32_t)sd.ns; U.Al = (uint32_t)sd.Al;
+                const bool one = sd.ns == 1;
+                uint32_t hsv[3], vsv[3], bwv[3], pbv[3]; const uint8_t* defv[3];
+                for (int q = 0; q < kMaxComp; q++) {
+                    const int c = q < sd.ns ? sd.comp[q] : 0;
+                    hsv[q] = one ? 1u : img.hs[c]; vsv[q] = one ? 1u : img.vs[c]; bwv[q] = img.bw[c]; pbv[q] = (uint32_t)(poff[c] / 64);
+                    defv[q] = rec + sd.dc_off[q < sd.ns ? q : 0];
+                }
+                U.hs0 = hsv[0]; U.hs1 = hsv[1]; U.hs2 = hsv[2]; U.vs0 = vsv[0]; U.vs1 = vsv[1]; U.vs2 = vsv[2];
+                U.bw0 = bwv[0]; U.bw1 = bwv[1]; U.bw2 = bwv[2]; U.pblk0 = pbv[0]; U.pblk1 = pbv[1]; U.pblk2 = pbv[2];
+                U.def0 = defv[0]; U.def1 = defv[1]; U.def2 = defv[2];
+                U.pred0 = ls.pred[0]; U.pred1 = ls.pred[1]; U.pred2 = ls.pred[2];
+                U.dense = dense.data(); U.planes = coef.data(); U.nblocks = (uint32_t)(coef.size() / 64);
+                U.ok = true;
+                rc = lane_decode_dc_first(U, &ring, &dtabs, 0);
             } else if (sd.Ss == 0) {
                 std::vector<DcTab> dt(3);
                 for (int q = 0; q < sd.ns; q++) dctab_build(&dt[q], rec + sd.dc_off[q]);
