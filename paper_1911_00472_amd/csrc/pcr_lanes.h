@@ -24,6 +24,7 @@ namespace pcr {
 // against the oracle and, on damaged input, under the sanitizers.
 #if !defined(__HIPCC__)
 struct uint4 { uint32_t x, y, z, w; };
+struct uint2 { uint32_t x, y; };
 #endif
 // true if `v` holds in any lane of the wavefront that is still in the loop
 PCR_HD bool any_lane(bool v) {
@@ -232,11 +233,12 @@ PCR_HD int lane_decode_ac_first(const LaneUnit& U, LaneRing* rings, uint32_t lan
 // <= w: the lane counts them.  One symbol -- one block -- per trip.
 // ---------------------------------------------------------------------------------------
 constexpr uint32_t kLaneDcCodes = 16;
-struct LaneDcTab {                                            // 80 bytes: a multiple of 16 (the limits are read as two 16-byte vectors)
+struct LaneDcTab {                                            // 80 bytes: read as 16-byte vectors, and five of them apart keeps 8 lanes on 32 banks
     uint16_t lim[kLaneDcCodes];                               // left-aligned code of entry i; 0xFFFF where there is none (no code is all ones)
-    uint16_t ls[kLaneDcCodes];                                // (length << 8) | category; 0: no code
+    uint32_t len[2], cat[2];                                  // 4 bits per entry: code length - 1, category (entry i: bits 4 (i & 7) of word i >> 3)
+    uint32_t n;                                               // entries
     uint32_t end;                                             // first left-aligned value that is no code of the (truncated) table
-    uint32_t pad[3];
+    uint32_t pad[6];
 };
 static_assert(sizeof(LaneDcTab) == 80, "LaneDcTab layout");
 struct LaneDcTabs { LaneDcTab t[kMaxComp][64]; };            // [scan component][lane]
@@ -261,22 +263,24 @@ struct LaneDcUnit {
 
 // The table of a definition (call per lane; t is the lane's own).
 PCR_HD __attribute__((always_inline)) void lane_dctab_build(LaneDcTab* t, const uint8_t* bits_vals) {
-    for (uint32_t i = 0; i < kLaneDcCodes; i++) { t->lim[i] = 0xFFFFu; t->ls[i] = 0; }
-    uint32_t code = 0, k = 0, end = 0;
-    bool open = true;                                         // the first kLaneDcCodes codes are still being listed
+    for (uint32_t i = 0; i < kLaneDcCodes; i++) t->lim[i] = 0xFFFFu;
+    uint32_t code = 0, k = 0, n = 0, end = 0, len0 = 0, len1 = 0, cat0 = 0, cat1 = 0;
     for (uint32_t L = 1; L <= 16; L++) {
         const uint32_t cnt = bits_vals[L - 1];
         for (uint32_t j = 0; j < cnt; j++) {
             const uint32_t left = code << (16 - L);
             if (k < kLaneDcCodes && left < 0xFFFFu) {
-                t->lim[k] = (uint16_t)left; t->ls[k] = (uint16_t)((L << 8) | (bits_vals[16 + k] & 15u));
+                t->lim[k] = (uint16_t)left;
+                const uint32_t sh = 4u * (k & 7u), c = bits_vals[16 + k] & 15u;
+                if (k < 8) { len0 |= (L - 1u) << sh; cat0 |= c << sh; } else { len1 |= (L - 1u) << sh; cat1 |= c << sh; }
                 end = left + (1u << (16 - L));
-            } else open = false;
+                n = k + 1;
+            }
             code++; k++;
         }
         code <<= 1;
     }
-    (void)open;
+    t->len[0] = len0; t->len[1] = len1; t->cat[0] = cat0; t->cat[1] = cat1; t->n = n;
     t->end = end > 0x10000u ? 0x10000u : end;
 }
 
@@ -320,14 +324,22 @@ PCR_HD __attribute__((always_inline)) int lane_decode_dc_first(const LaneDcUnit&
         const uint32_t blk = p0 + (my * vs + by) * bw + mx * hs + bx;
         // the code: the last of the table's that is not above the window
         const LaneDcTab* T = &tabs->t[c][lane];
+        // (three 16-byte reads that do not wait for the window: limits, limits, lengths and categories; then no further
+        // trip to LDS stands between the window and the symbol)
         const uint4 la = *reinterpret_cast<const uint4*>(&T->lim[0]), lb = *reinterpret_cast<const uint4*>(&T->lim[8]);
-        uint32_t cnt = 0;
+        const uint4 lc = *reinterpret_cast<const uint4*>(&T->len[0]);
+        const uint2 ne = *reinterpret_cast<const uint2*>(&T->n);
         const uint32_t lw[8] = {la.x, la.y, la.z, la.w, lb.x, lb.y, lb.z, lb.w};
+        uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;              // (four sums: no chain of sixteen additions)
 #pragma unroll
-        for (int q = 0; q < 8; q++) cnt += ((lw[q] & 0xFFFFu) <= w16 ? 1u : 0u) + ((lw[q] >> 16) <= w16 ? 1u : 0u);
-        const uint32_t e = cnt ? T->ls[cnt - 1] : 0u;
-        const bool code_ok = e != 0 && w16 < T->end;
-        const uint32_t len = code_ok ? e >> 8 : 1u, s = code_ok ? e & 15u : 0u;
+        for (int q = 0; q < 8; q += 2) {
+            c0 += (lw[q] & 0xFFFFu) <= w16 ? 1u : 0u; c1 += (lw[q] >> 16) <= w16 ? 1u : 0u;
+            c2 += (lw[q + 1] & 0xFFFFu) <= w16 ? 1u : 0u; c3 += (lw[q + 1] >> 16) <= w16 ? 1u : 0u;
+        }
+        const uint32_t cnt = (c0 + c1) + (c2 + c3);           // codes at or below the window: the last of them is the one
+        const uint32_t idx = (cnt - 1u) & 15u, sh = 4u * (idx & 7u);
+        const bool code_ok = cnt != 0 && cnt <= ne.x && w16 < ne.y;
+        const uint32_t len = code_ok ? (((idx < 8 ? lc.x : lc.y) >> sh) & 15u) + 1u : 1u, s = code_ok ? ((idx < 8 ? lc.z : lc.w) >> sh) & 15u : 0u;
         const uint32_t extra = ((win << len) >> 1) >> (31u - s);
         const int diff = extend(extra, (int)s);
         st.consume(len + s);
