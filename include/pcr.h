@@ -388,8 +388,8 @@ int pcr_last_decoder_shapes(pcr_record* rec, int* lane_launches, int* wavefront_
 /* Stage timing with HIP events recorded on the call's own stream (off by default; switching it on
  * starts a new history).  A stage is one kernel or a short run of kernels:
  *   INDEX_PARSE    k_index + k_parse                 UNSTUFF        k_unstuff + zero fills
- *   DC_FIRST, AC_FIRST, AC_REFINE, REFINE_BLOCKS, SEQUENTIAL     one interval per launch of that kernel (AC_FIRST, AC_REFINE:
- *                  of either decoder shape; REFINE_BLOCKS: k_refine_blocks after a wavefront-per-unit launch, k_refine_history
+ *   DC_FIRST, AC_FIRST, AC_REFINE, REFINE_BLOCKS, SEQUENTIAL     one interval per launch of that kernel (DC_FIRST, AC_FIRST,
+ *                  AC_REFINE: of either decoder shape; REFINE_BLOCKS: k_refine_blocks after a wavefront-per-unit launch, k_refine_history
  *                  before and k_refine_deal after a lane-per-unit launch)
  *   REFINE_APPLY   k_apply_prep + k_apply            PIXEL          k_pixel
  * pcr_last_stage_ms: milliseconds per stage of the last pcr_decode_batch / pcr_decode_coefficients
