@@ -123,3 +123,41 @@ def _headline_record(torch, rec, others):
         assert torch.equal(c, r.decode_coefficients(10))
     for o in others:
         o.close()
+
+
+def test_dc_first_scans_with_a_lane_per_unit_many_small_images_and_damage():
+    """A launch of DC first scans takes the lane decoder from 64 units on when lanes are forced: 96 small images with an
+    entry at every MCU of the DC scan give a thousand.  Colour with three sampling layouts and gray (a DC scan of one
+    component, decoded block by block); then one image's DC data is damaged: same status words, same pixels elsewhere."""
+    torch = _torch()
+    files = []
+    for i in range(96):
+        hs, vs = ((2, 2), (1, 1), (2, 1), (1, 2))[i % 4]
+        if i % 8 == 7:
+            files.append(pcrgen.make_jpeg(3000 + i, 0, 40 + i % 9, 31 + i % 5, 1, 8.0, 1, 1, 90))
+        else:
+            files.append(pcrgen.make_jpeg(3000 + i, 1 + i % 2, 49 + i % 11, 37 + i % 7, 3, 6.0, hs, vs, 88))
+    rec = pkg.record_write_indexed(files, None, 2)
+    out, clay = _both_shapes(rec, [1, 2, 10], coef_ks=(1, 10))
+    coef = out[10][2].cpu().numpy()
+    ref = oracle.decode_record(rec, 10, images=list(range(len(files))), threads=16)
+    for i, (c0, _, _) in enumerate(ref):
+        assert np.array_equal(coef[int(clay[i]):int(clay[i + 1])], c0), i
+    off, ln, _, _, _ = oracle.record_index(rec)
+    with pkg.pcr_open(rec, 0) as r:
+        good = r.decode_batch(10).cpu().numpy()
+        lay = r.output_layout()
+    rng = np.random.default_rng(7)
+    for victim in (5, 7, 40):
+        a = bytearray(rec)
+        L = int(ln[0, victim])
+        p = int(off[0, victim]) + L - 12                      # the tail of the file's first region: DC scan data
+        for j in range(8):
+            a[p + j] = int(rng.integers(0, 255))
+        res, _ = _both_shapes(bytes(a), [10])
+        pix, st, _ = res[10]
+        pix, st = pix.cpu().numpy(), st.cpu().numpy()
+        for i in range(len(files)):
+            if i != victim:
+                sl = slice(int(lay[i]), int(lay[i + 1]))
+                assert st[i] == 0 and np.array_equal(pix[sl], good[sl]), (victim, i)
