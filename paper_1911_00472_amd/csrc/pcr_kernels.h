@@ -614,7 +614,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_dc_first_lanes(DevRecord R, c
         const uint32_t* __restrict__ clean32, uint32_t to_planes) {
     __shared__ LaneRing rings;
     __shared__ LaneDcTabs tabs;
-    dc_kernel_priority();
+    short_kernel_priority();
     const uint32_t t = threadIdx.x, u = blockIdx.x * kEntropyLanes + t;
     LaneDcUnit U;
     U.ok = false;
