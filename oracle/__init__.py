@@ -53,6 +53,7 @@ def lib():
         L.orc_reassemble.argtypes = [u8p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_int, u8p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
         L.orc_image_info.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(Info)]
         L.orc_decode.argtypes = [u8p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int16), u8p]
+        L.orc_decode_smooth.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int16), u8p]
         L.orc_decode_record_image.argtypes = [u8p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.POINTER(ctypes.c_int16), u8p]
         L.orc_record_image_info.argtypes = [u8p, ctypes.c_size_t, ctypes.c_uint32, ctypes.POINTER(Info)]
@@ -123,6 +124,19 @@ def decode(jpg, upsample="replicate", idct="separable", want_coef=True, want_pix
     _check(lib().orc_decode(p, a.size, 1 if upsample == "triangle" else 0, 1 if idct == "direct" else 0,
                             coef.ctypes.data_as(ctypes.POINTER(ctypes.c_int16)) if want_coef else None,
                             pix.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)) if want_pix else None))
+    return coef, pix, info
+
+
+def decode_smooth(jpg, want_coef=True, want_pix=True):
+    """decode() with the five lowest AC coefficients of every component that has received only its DC first
+    scan predicted from the neighbouring DC coefficients (T.81 K.8); coef holds the predictions."""
+    a, p = _u8(jpg)
+    info = image_info(jpg)
+    coef = np.empty(info.coef_count, np.int16) if want_coef else None
+    pix = np.empty((info.H, info.W, info.nc), np.uint8) if want_pix else None
+    _check(lib().orc_decode_smooth(p, a.size,
+                                   coef.ctypes.data_as(ctypes.POINTER(ctypes.c_int16)) if want_coef else None,
+                                   pix.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)) if want_pix else None))
     return coef, pix, info
 
 

@@ -152,6 +152,7 @@ typedef struct {
     int ri;
     int16_t* coef[3];
     int zz[64];
+    int nscan_c[3], dc_first_c[3];   /* per component: scans received that carry it; DC first scans among them */
 } dec_t;
 
 static void gen_zigzag(int zz[64]) {
@@ -430,6 +431,7 @@ static int walk(const uint8_t* d, size_t n, dec_t* D, orc_info_t* info, int16_t*
                 break;
             }
             nscans++;
+            for (int j = 0; j < S.ns; j++) { D->nscan_c[S.c[j]]++; if (D->progressive && S.Ss == 0 && S.Se == 0 && S.Ah == 0) D->dc_first_c[S.c[j]]++; }
             if (coef) {
                 for (int j = 0; j < S.ns; j++) {
                     int needs_dc = !D->progressive || (S.Ss == 0 && S.Ah == 0), needs_ac = !D->progressive || S.Ss > 0;
@@ -509,13 +511,57 @@ static double tri(const double* p, int n, int stride, int i2) {
 }
 
 /*
+ * Smoothing of a component of which only the DC first scan has been received (T.81 K.8: the five lowest AC
+ * coefficients of a block are predicted from the DC coefficients of the block and its eight neighbours, the
+ * coefficients of the quadratic surface whose means over the nine blocks are the nine DC values).  In the integer
+ * form used here the weights are 36/256, 9/256 and 5/256 of the de-quantised DC differences, and the prediction is
+ * rounded to a multiple of the coefficient's own quantiser step, halves away from zero:
+ *     zig-zag 1 (horizontal frequency 1):  36 (left - right)
+ *     zig-zag 2 (vertical frequency 1):    36 (above - below)
+ *     zig-zag 3 (vertical frequency 2):     9 (above + below - 2 centre)
+ *     zig-zag 4 (one of each):              5 ((above-left - above-right) - (below-left - below-right))
+ *     zig-zag 5 (horizontal frequency 2):   9 (left + right - 2 centre)
+ * A neighbour beyond the component's block grid is the nearest block inside it.  Predictions are limited to
+ * +-1023, the range of an AC coefficient of 8-bit samples.  Components that have received anything besides
+ * their DC first scan, and sequential files, are left as they are.
+ */
+static int16_t predict(int64_t w, int64_t q0, int64_t delta, int64_t qz) {
+    int64_t num = w * q0 * delta, den = 256 * qz, v = num >= 0 ? (num + den / 2) / den : -((-num + den / 2) / den);
+    if (v > 1023) v = 1023;
+    if (v < -1023) v = -1023;
+    return (int16_t)v;
+}
+static void smooth_dc_only_components(dec_t* D) {
+    for (int c = 0; c < D->nc; c++) {
+        if (!D->progressive || D->nscan_c[c] != 1 || D->dc_first_c[c] != 1) continue;
+        const uint16_t* q = D->q[D->tq[c]];
+        int bw = D->bw[c], bh = D->bh[c];
+        for (int by = 0; by < bh; by++) for (int bx = 0; bx < bw; bx++) {
+            int64_t d[3][3];
+            for (int dy = -1; dy <= 1; dy++) for (int dx = -1; dx <= 1; dx++) {
+                int y = by + dy, x = bx + dx;
+                y = y < 0 ? 0 : (y >= bh ? bh - 1 : y); x = x < 0 ? 0 : (x >= bw ? bw - 1 : x);
+                d[dy + 1][dx + 1] = D->coef[c][((size_t)y * bw + x) * 64];
+            }
+            int16_t* blk = D->coef[c] + ((size_t)by * bw + bx) * 64;
+            /* (blk is in natural order: index 8 v + u; q in zig-zag order) */
+            blk[1]  = predict(36, q[0], d[1][0] - d[1][2], q[1]);
+            blk[8]  = predict(36, q[0], d[0][1] - d[2][1], q[2]);
+            blk[16] = predict(9,  q[0], d[0][1] + d[2][1] - 2 * d[1][1], q[3]);
+            blk[9]  = predict(5,  q[0], (d[0][0] - d[0][2]) - (d[2][0] - d[2][2]), q[4]);
+            blk[2]  = predict(9,  q[0], d[1][0] + d[1][2] - 2 * d[1][1], q[5]);
+        }
+    }
+}
+
+/*
  * Decode one JPEG byte string (all scans present in it).
  *   coef  optional: receives the coefficient planes
  *   pix   optional: receives H*W*nc bytes, row-major, channel-interleaved
  *   upsample  0 replicate (the contract), 1 triangle + per-plane rounding (comparison only)
  *   idct_direct  1 = evaluate the O(N^4) definition, 0 = separable
  */
-int orc_decode(const uint8_t* jpg, size_t n, int upsample, int idct_direct, int16_t* coef, uint8_t* pix) {
+static int decode_impl(const uint8_t* jpg, size_t n, int upsample, int idct_direct, int smooth, int16_t* coef, uint8_t* pix) {
     orc_info_t info;
     dec_t* D = (dec_t*)malloc(sizeof(dec_t));
     int rc = walk(jpg, n, D, &info, NULL);
@@ -524,9 +570,10 @@ int orc_decode(const uint8_t* jpg, size_t n, int upsample, int idct_direct, int1
     for (int c = 0; c < info.nc; c++) total += (size_t)info.bw[c] * info.bh[c] * 64;
     int16_t* cbuf = coef ? coef : (int16_t*)malloc(total * sizeof(int16_t));
     rc = walk(jpg, n, D, &info, cbuf);
-    if (!rc && pix) {
+    if (!rc && (pix || smooth)) {
         for (int c = 0; c < D->nc; c++) if (!D->qdef[D->tq[c]]) rc = ORC_E_FORMAT;
     }
+    if (!rc && smooth) smooth_dc_only_components(D);
     if (!rc && pix) {
         double* plane[3] = {0, 0, 0};
         for (int c = 0; c < D->nc; c++) plane[c] = (double*)malloc(sizeof(double) * (size_t)D->bw[c] * D->bh[c] * 64);
@@ -566,6 +613,14 @@ int orc_decode(const uint8_t* jpg, size_t n, int upsample, int idct_direct, int1
     if (!coef) free(cbuf);
     free(D);
     return rc;
+}
+int orc_decode(const uint8_t* jpg, size_t n, int upsample, int idct_direct, int16_t* coef, uint8_t* pix) {
+    return decode_impl(jpg, n, upsample, idct_direct, 0, coef, pix);
+}
+/* The same with the smoothing above (replicated chroma, separable transform); coef, if given, receives the
+ * coefficients with the predictions in place. */
+int orc_decode_smooth(const uint8_t* jpg, size_t n, int16_t* coef, uint8_t* pix) {
+    return decode_impl(jpg, n, 0, 0, 1, coef, pix);
 }
 
 /* Convenience for whole records: decode image i at fidelity k straight from the record. */
