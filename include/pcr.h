@@ -167,6 +167,23 @@ int pcr_decode_batch(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size
 int pcr_decode_batch_triangle(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
                               void* hip_stream, int32_t* d_status);
 
+/* pcr_decode_batch with the smoothing stock decoders apply to the first scans of a progressive file (Section 5,
+ * "Decoding", hands the reassembled bytes to a stock decoder; the pictures of the early scans in the paper's figure of
+ * the ten scans were made that way).  Every component of which only the DC first scan lies inside scan_group gets the
+ * five lowest AC coefficients of each block predicted from the DC coefficients of the block and its eight neighbours
+ * (JPEG standard, T.81 K.8: the coefficients of the quadratic surface whose means over the nine blocks are the nine DC
+ * values).  Integer form, per coefficient with quantiser step Qz, DC step Q0 and DC coefficients as received:
+ *   zig-zag 1: 36 Q0 (left - right)        zig-zag 2: 36 Q0 (above - below)      zig-zag 3: 9 Q0 (above + below - 2 centre)
+ *   zig-zag 4: 5 Q0 ((above-left - above-right) - (below-left - below-right))    zig-zag 5: 9 Q0 (left + right - 2 centre)
+ * divided by 256 Qz and rounded to the nearest integer, halves away from zero, limited to +-1023; a neighbour beyond
+ * the component's (MCU-padded) block grid is the nearest block inside it.  Components that have received an AC scan or
+ * a DC refinement scan, and sequential files, decode exactly as in pcr_decode_batch, so at the last scan group the two
+ * calls agree bit for bit.  The predictions live in the coefficient planes only for the duration of the call: a
+ * following pcr_upgrade_batch starts from scan_group as after pcr_decode_batch.  Arguments, layout, stream order,
+ * d_status and errors as pcr_decode_batch. */
+int pcr_decode_batch_smooth(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
+                            void* hip_stream, int32_t* d_status);
+
 /* Fidelity upgrade (Section 3 of the paper: a lower-fidelity read is a prefix of a higher-fidelity one, so
  * changing fidelity costs little): raise the planes the last pcr_decode_batch /
  * pcr_upgrade_batch call on this handle left on the device from its scan group to `scan_group` (>= it) by

@@ -34,6 +34,7 @@ SYMBOLS = {
     "pcr_decode_coefficients": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp]),
     "pcr_decode_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_decode_batch_triangle": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
+    "pcr_decode_batch_smooth": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_upgrade_batch": (ctypes.c_int, [_vp, ctypes.c_int, _vp, ctypes.c_size_t, _vp, _vp]),
     "pcr_resident_scan_group": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int)]),
     "pcr_enable_stage_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
@@ -233,6 +234,17 @@ class Record:
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         _check(lib().pcr_decode_batch_triangle(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
                "pcr_decode_batch_triangle")
+        return out
+
+    def decode_batch_smooth(self, k, out=None, status=None, stream=None):
+        """decode_batch with the five lowest AC coefficients of components that hold only their DC first scan predicted
+        from the neighbouring DC coefficients."""
+        import torch
+        if out is None:
+            out = torch.empty(int(self.output_layout()[-1]), dtype=torch.uint8, device="cuda:%d" % self.device)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().pcr_decode_batch_smooth(self._h, k, out.data_ptr(), out.numel(), s, status.data_ptr() if status is not None else None),
+               "pcr_decode_batch_smooth")
         return out
 
     def symbol_histograms(self, restart_interval=0, out=None, stream=None):

@@ -1691,6 +1691,83 @@ __global__ void __launch_bounds__(256) k_triangle_rgb(DevRecord R, const uint8_t
 }
 
 // --------------------------------------------------------------------------------------
+// k_smooth: the five lowest AC coefficients of every block of a component of which only the DC first scan has been
+// received, predicted from the DC coefficients of the block and its eight neighbours (T.81 K.8: the coefficients of
+// the quadratic surface whose means over the nine blocks are the nine DC values; what stock decoders show for the
+// first scans of a progressive file).  Integer form: weights 36/256, 9/256 and 5/256 of the de-quantised DC
+// differences, rounded to a multiple of the coefficient's own quantiser step, halves away from zero, limited to
+// +-1023; a neighbour beyond the component's block grid is the nearest block inside it.
+// kClear = false: writes the first 16-byte chunk of each such block of the coefficient planes (zig-zag positions
+// 0..7: 1..5 predicted, the others zero; the pixel kernel takes position 0 from the compact DC copy) and raises the
+// component's zmax to 6, so that k_pixel reads that chunk and nothing more.  kClear = true, after k_pixel: the chunks
+// are zero again and zmax is 1, the state an upgrade to a higher scan group builds on.
+// grid: (kSmoothGroups, images); 256 lanes, a block per lane and trip.
+// --------------------------------------------------------------------------------------
+constexpr uint32_t kSmoothGroups = 8;
+PCR_D int smooth_predict(int64_t w, int64_t q0, int64_t delta, int64_t qz) {
+    const int64_t num = w * q0 * delta, den = 256 * qz;
+    int64_t v = num >= 0 ? (num + den / 2) / den : -((-num + den / 2) / den);
+    v = v > 1023 ? 1023 : (v < -1023 ? -1023 : v);
+    return (int)v;
+}
+template <bool kClear>
+__global__ void __launch_bounds__(256) k_smooth(DevRecord R) {
+    __shared__ uint32_t does[kMaxComp];                      // per component: 1 if it holds its DC first scan and nothing else
+    __shared__ uint32_t qs[kMaxComp][6];                     // its quantiser steps of zig-zag positions 0..5
+    const uint32_t img = blockIdx.y, tid = threadIdx.x;
+    ImgDesc* ip = R.img + img;
+    const uint32_t nc = ip->nc;
+    if (ip->status != kOk || !ip->progressive || nc > kMaxComp) return;
+    if (tid < kMaxComp) {
+        uint32_t carried = 0, dc_first = 0, tq = 0;
+        if (tid < nc) {
+            tq = ip->tq[tid];
+            const ScanDesc* sc = R.scan + (size_t)img * R.G;
+            const uint32_t ng = ip->nscans < R.G ? ip->nscans : R.G;
+            for (uint32_t g = 0; g < ng; g++)
+                for (uint32_t j = 0; j < sc[g].ns && j < kMaxComp; j++)
+                    if (sc[g].comp[j] == tid) { carried++; dc_first += (sc[g].Ss == 0 && sc[g].Se == 0 && sc[g].Ah == 0) ? 1u : 0u; }
+        }
+        const bool on = carried == 1 && dc_first == 1 && ip->qoff[tq] != 0;
+        does[tid] = on ? 1u : 0u;
+        if (on) {
+            const uint8_t* q = R.rec + ip->qoff[tq];
+            const bool wide = ip->qprec[tq] != 0;
+            for (uint32_t k = 0; k < 6; k++) { const uint32_t v = wide ? ld_be16(q + 2 * k) : q[k]; qs[tid][k] = v ? v : 1u; }
+        }
+    }
+    __syncthreads();
+    uint32_t plane0 = 0;
+    for (uint32_t c = 0; c < nc; c++) {
+        const uint32_t bw = ip->bw[c], bh = ip->bh[c], nb = bw * bh;
+        if ((uint64_t)(plane0 + nb) * 64 > R.coef_off[img + 1] - R.coef_off[img]) return;   // (cannot happen for an image the parser accepted)
+        if (does[c]) {
+            if (blockIdx.x == 0 && tid == 0) ip->zmax[c] = kClear ? 1 : 6;
+            const int16_t* dc = R.dc + (R.coef_off[img] >> 6) + plane0;
+            int16_t* planes = R.coef + R.coef_off[img] + (size_t)plane0 * 64;
+            const int64_t q0 = qs[c][0], q1 = qs[c][1], q2 = qs[c][2], q3 = qs[c][3], q4 = qs[c][4], q5 = qs[c][5];
+            for (uint32_t b = blockIdx.x * 256 + tid; b < nb; b += kSmoothGroups * 256) {
+                short8 o = short8{0, 0, 0, 0, 0, 0, 0, 0};
+                if (!kClear) {
+                    const uint32_t by = b / bw, bx = b - by * bw;
+                    const uint32_t xl = bx ? bx - 1 : 0, xr = bx + 1 < bw ? bx + 1 : bx, ya = by ? by - 1 : 0, yb = by + 1 < bh ? by + 1 : by;
+                    const int64_t al = dc[ya * bw + xl], a = dc[ya * bw + bx], ar = dc[ya * bw + xr];
+                    const int64_t l = dc[by * bw + xl], m = dc[b], r = dc[by * bw + xr];
+                    const int64_t bl = dc[yb * bw + xl], be = dc[yb * bw + bx], br = dc[yb * bw + xr];
+                    o[1] = (short)smooth_predict(36, q0, l - r, q1);
+                    o[2] = (short)smooth_predict(36, q0, a - be, q2);
+                    o[3] = (short)smooth_predict(9, q0, a + be - 2 * m, q3);
+                    o[4] = (short)smooth_predict(5, q0, (al - ar) - (bl - br), q4);
+                    o[5] = (short)smooth_predict(9, q0, l + r - 2 * m, q5);
+                }
+                *reinterpret_cast<short8*>(planes + (size_t)b * 64) = o;
+            }
+        }
+        plane0 += nb;
+    }
+}
+
+// --------------------------------------------------------------------------------------
 // k_pixel_tail: decode and training tail in one kernel, so that the full-resolution pixels never reach memory.
 // One workgroup per MCU row of one image, one lane per block as in k_pixel; the samples of the MCU row lie in LDS as
 // one row-major plane per component, kTailLanes / blocks-per-MCU MCUs at a time (42 for 4:2:0: one pass for images up

@@ -935,7 +935,8 @@ int pcr_decode_coefficients(pcr_record* r, int k, int16_t* d_coef, void* stream)
 }
 
 // k0 = 0: from scratch; k0 > 0: on top of the planes and masks a previous call left for scan group k0
-static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status, const CropBox* boxes = nullptr) {
+static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status, const CropBox* boxes = nullptr,
+                            bool smooth = false) {
     if (cap < r->out_off[r->hdr.n]) return PCR_E_RANGE;
     HIP_TRY(hipSetDevice(r->device));
     hipStream_t s = (hipStream_t)stream;
@@ -943,14 +944,17 @@ static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t c
     r->resident_k = 0;
     int rc = run_entropy_stages(r, k0, k, s, false, &plan);
     if (rc) return rc;
+    // smoothing: predicted coefficients go into the planes for the pixel kernel and are taken out again after it
+    if (smooth) hipLaunchKernelGGL(k_smooth<false>, dim3(kSmoothGroups, r->hdr.n), dim3(256), 0, s, r->d);
     if (plan->n_apply)
         hipLaunchKernelGGL((k_pixel<true, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
-    else if (plan->has_ac)
+    else if (plan->has_ac || smooth)
         hipLaunchKernelGGL((k_pixel<false, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);
     else if (r->n_flat_rows && !boxes)                       // DC scans only: every block is flat
         hipLaunchKernelGGL(k_pixel_flat_rows, dim3(r->n_flat_rows), dim3(kFlatRowLanes), flat_rows_lds(r->flat_row_cells), s, r->d, r->d_flat_rows, out, r->flat_row_cells);
     else
         hipLaunchKernelGGL(k_pixel_flat, dim3(r->n_flat_tiles), dim3(kFlatLanes), 0, s, r->d, r->d_flat_tiles, out, boxes);
+    if (smooth) hipLaunchKernelGGL(k_smooth<true>, dim3(kSmoothGroups, r->hdr.n), dim3(256), 0, s, r->d);
     mark(r, PCR_STAGE_PIXEL, s);
     call_end(r);
     if (hipGetLastError() != hipSuccess) return PCR_E_DEVICE;
@@ -964,6 +968,13 @@ int pcr_decode_batch(pcr_record* r, int k, uint8_t* out, size_t cap, void* strea
     int rc = check_scan_group(r, k);
     if (rc) return rc;
     return decode_to_pixels(r, 0, k, out, cap, stream, d_status);
+}
+
+int pcr_decode_batch_smooth(pcr_record* r, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status) {
+    if (!r || !out) return PCR_E_ARG;
+    int rc = check_scan_group(r, k);
+    if (rc) return rc;
+    return decode_to_pixels(r, 0, k, out, cap, stream, d_status, nullptr, true);
 }
 
 int pcr_decode_batch_triangle(pcr_record* r, int k, uint8_t* out, size_t cap, void* stream, int32_t* d_status) {

@@ -1,0 +1,118 @@
+"""GPU parity of pcr_decode_batch_smooth against the oracle's smoothing (pinned in test_oracle_smoothing.py): the
+predictions are integers on both sides, the pixels then differ as everywhere else by at most 1 LSB (fp32 against fp64,
+one final rounding).  Also: what the call must leave alone, and what it must leave behind."""
+import numpy as np
+import pytest
+
+import oracle
+import pcrgen
+import paper_1911_00472_amd as pkg
+from jpeg_files import VARIANTS
+
+pytestmark = pytest.mark.gpu
+
+PIXEL_TOL = 1
+
+
+def _torch():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def _check_smooth(rec, ks, images=None):
+    torch = _torch()
+    with pkg.pcr_open(rec, 0) as r:
+        lay = r.output_layout()
+        idx = list(range(r.n)) if images is None else list(images)
+        changed = 0
+        for k in ks:
+            st = torch.full((r.n,), 77, dtype=torch.int32, device="cuda")
+            got_t = r.decode_batch_smooth(k, status=st)
+            assert (st.cpu().numpy() == 0).all()
+            assert r.resident_scan_group() == k
+            got = got_t.cpu().numpy()
+            for i in idx:
+                _, want, _ = oracle.decode_smooth(oracle.reassemble(rec, i, k), want_coef=False)
+                g = got[int(lay[i]):int(lay[i + 1])].reshape(want.shape).astype(int)
+                assert np.abs(g - want.astype(int)).max() <= PIXEL_TOL, ("pixels", i, k)
+            plain = r.decode_batch(k)
+            changed += int(not torch.equal(plain, got_t))
+            if k == r.G:
+                assert torch.equal(plain, got_t)
+        return changed
+
+
+def test_odd_sizes_420_gray_444_422(rgb_small, gray64):
+    assert _check_smooth(rgb_small[0], (1, 2, 3, 4, 10)) >= 3      # chroma holds only its DC scan up to scan group 3
+    assert _check_smooth(gray64[0], (1, 2, 6)) == 1
+    shapes = [(1, 1), (2, 3), (17, 9), (120, 77), (33, 64), (64, 31), (8, 200), (200, 8)]
+    for si, (hs, vs) in enumerate(((2, 1), (1, 1))):
+        rec = pcrgen.write_record([pcrgen.make_jpeg(5300 + 16 * si + j, 1, w, h, 3, 6.0, hs, vs, 90, restart=j % 2) for j, (w, h) in enumerate(shapes)])
+        assert _check_smooth(rec, (1, 2, 3, 10)) >= 2
+
+
+def test_many_tiles_and_the_headline_workload():
+    records, _ = pcrgen.make_workload("rgb256", limit=48)
+    assert _check_smooth(records[0], (1, 2, 3)) == 3
+    records, _ = pcrgen.make_workload("imagenet_like", limit=128)
+    sample = sorted(np.random.default_rng(6).choice(128, size=10, replace=False).tolist())
+    assert _check_smooth(records[0], (1, 3), images=sample) == 2
+    records, _ = pcrgen.make_workload("hires1024", limit=1)
+    assert _check_smooth(records[0], (1,)) == 1
+
+
+def test_wide_steps_16_bit_tables_sequential_files_and_dc_refinement_first():
+    # coarse DC step, fine AC steps, the largest DC differences: predictions at their limit; 16-bit tables
+    rng = np.random.default_rng(77)
+    q = np.ones((2, 64), np.uint16)
+    q[0, 0] = 255
+    c = np.zeros((6, 7, 64), np.int16)
+    c[:, :, 0] = rng.integers(-4, 5, size=(6, 7))
+    c[2, 3, 0], c[2, 4, 0] = 4, -4
+    gray2 = [(1, 0, 0, 0, 0, 0, 0, 0), (1, 0, 0, 0, 1, 63, 0, 0)]
+    wide = pcrgen.encode_coefs(c.reshape(-1), 56, 48, 1, 1, 1, q, gray2)
+    cf = oracle.decode_smooth(oracle.reassemble(pcrgen.write_record([wide]), 0, 1), want_pix=False)[0]
+    assert np.abs(cf.reshape(-1, 64)[:, 1:6]).max() >= 280       # (36 * 255 * 8 / 256)
+    # a component whose DC refinement scan comes before its AC scans: smoothed at scan group 1 only
+    c2 = np.zeros((3, 3, 64), np.int16)
+    c2[:, :, 0] = [[10, 20, 30], [40, 50, 60], [70, 80, 91]]
+    c2[1, 1, 5] = 3
+    script = [(1, 0, 0, 0, 0, 0, 0, 1), (1, 0, 0, 0, 0, 0, 1, 0), (1, 0, 0, 0, 1, 63, 0, 0)]
+    early = pcrgen.encode_coefs(c2.reshape(-1), 24, 24, 1, 1, 1, np.full((2, 64), 3, np.uint16), script)
+    seq = pcrgen.encode_pixels(pcrgen.synth(31, 1, 40, 56, 3, 6.0), 2, 2, 90, "sequential", restart=1)
+    prog = pcrgen.make_jpeg(32, 1, 90, 70, 3, 6.0, 2, 2, 85)
+    assert _check_smooth(pcrgen.write_record([wide, VARIANTS["dqt16"](wide)]), (1, 2)) == 1
+    assert _check_smooth(pcrgen.write_record([early]), (1, 2, 3)) == 1
+    assert _check_smooth(pcrgen.write_record([VARIANTS["dqt16"](prog), prog]), (1, 2, 10)) == 2
+    torch = _torch()
+    with pkg.pcr_open(pcrgen.write_record([seq]), 0) as r:        # a sequential file: whole blocks, nothing predicted
+        assert torch.equal(r.decode_batch_smooth(1), r.decode_batch(1))
+
+
+def test_planes_are_left_as_a_plain_decode_leaves_them(rgb_small, extreme_record):
+    torch = _torch()
+    for rec in (rgb_small[0], extreme_record[0]):
+        with pkg.pcr_open(rec, 0) as r, pkg.pcr_open(rec, 0) as fresh:
+            for k0, k1 in ((1, 2), (2, 3), (1, r.G), (3, 3)):
+                r.decode_batch_smooth(k0)
+                assert r.resident_scan_group() == k0
+                assert torch.equal(r.upgrade_batch(k1), fresh.decode_batch(k1)), (k0, k1)
+            r.decode_batch_smooth(2)
+            assert torch.equal(r.decode_coefficients(2), fresh.decode_coefficients(2))
+            a = r.decode_batch_smooth(1).clone()
+            r.decode_batch(r.G)
+            assert torch.equal(r.decode_batch_smooth(1), a)       # repeatable, whatever the planes held before
+
+
+def test_argument_errors():
+    rec = pcrgen.write_record([pcrgen.make_jpeg(1, 1, 24, 24, 3, 6.0, 2, 2, 90)])
+    torch = _torch()
+    with pkg.pcr_open(rec, 0) as r:
+        small = torch.empty(8, dtype=torch.uint8, device="cuda")
+        with pytest.raises(pkg.PcrError):
+            r.decode_batch_smooth(1, out=small)
+        with pytest.raises(pkg.PcrError):
+            r.decode_batch_smooth(0)
+        with pytest.raises(pkg.PcrError):
+            r.decode_batch_smooth(r.G + 1)
