@@ -116,3 +116,37 @@ def test_argument_errors():
             r.decode_batch_smooth(0)
         with pytest.raises(pkg.PcrError):
             r.decode_batch_smooth(r.G + 1)
+
+
+def test_damaged_dc_data_flags_the_image_only(rgb_small):
+    """Damage inside one image's DC scan: the image is flagged (its pixels zero) or decodes to something; the smoothing
+    of every other image is untouched, and the planes stay fit for an upgrade."""
+    rec, files = rgb_small
+    torch = _torch()
+    off, ln, _, _, _ = oracle.record_index(rec)
+    a = bytearray(rec)
+    victim = 6
+    p = int(off[0, victim]) + int(ln[0, victim]) - 40
+    for j in range(30):
+        a[p + j] = 0x55 if a[p + j] != 0x55 else 0xAA
+    bad = bytes(a)
+    with pkg.pcr_open(rec, 0) as r:
+        good = {k: r.decode_batch_smooth(k).cpu().numpy() for k in (1, 2)}
+        good_up = r.decode_batch(4).cpu().numpy()
+        lay = r.output_layout()
+    with pkg.pcr_open(bad, 0) as r:
+        for k in (1, 2):
+            status = torch.zeros(r.n, dtype=torch.int32, device="cuda")
+            out = r.decode_batch_smooth(k, status=status).cpu().numpy()
+            st = status.cpu().numpy()
+            for i in range(len(files)):
+                sl = slice(int(lay[i]), int(lay[i + 1]))
+                if i != victim:
+                    assert st[i] == 0 and np.array_equal(out[sl], good[k][sl]), (i, k)
+                elif st[i] != 0:
+                    assert not out[sl].any()
+        up = r.upgrade_batch(4).cpu().numpy()
+        for i in range(len(files)):
+            if i != victim:
+                sl = slice(int(lay[i]), int(lay[i + 1]))
+                assert np.array_equal(up[sl], good_up[sl]), i
