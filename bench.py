@@ -528,6 +528,20 @@ def extras(torch, pkg, pcrgen, oracle, job, args, ends, per_k_ms, k):
     torch.cuda.synchronize()
     res["fidelity_estimate"] = {"measure": "multi-scale structural similarity on luma against scan group %d, mean over record 0" % G0,
                                 "mean_score_by_scan_group": mean_score, "ms_per_record": e0.elapsed_time(e1) / 5}
+    # ... and with the smoothing of DC-only components, which matters at the first scan group (luma is DC-only there)
+    with torch.cuda.stream(streams[0]):
+        handles[0].decode_batch_smooth(1, out=outs[0], stream=streams[0].cuda_stream)
+        handles[0].msssim_batch(outs[0], full0, out=scores0, stream=streams[0].cuda_stream)
+        smooth_score = float(scores0.mean().item())
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    reps_s = max(5, args.steps)
+    for _ in range(reps_s):
+        for h, o, st in zip(handles, outs, streams):
+            h.decode_batch_smooth(1, out=o, stream=st.cuda_stream)
+    torch.cuda.synchronize()
+    res["fidelity_estimate"]["scan_group_1_smoothed"] = {"mean_score": smooth_score, "ms_per_step": (time.perf_counter() - t) / reps_s * 1e3,
+                                                         "plain_ms_per_step": per_k_ms.get(1)}
     del full0
 
     # the same images as baseline (non-progressive) files, and with restart intervals in every scan
