@@ -526,6 +526,7 @@ static double tri(const double* p, int n, int stride, int i2) {
  * their DC first scan, and sequential files, are left as they are.
  */
 static int16_t predict(int64_t w, int64_t q0, int64_t delta, int64_t qz) {
+    if (qz == 0) return 0;   /* (a step the standard does not allow: the coefficient would de-quantise to zero anyway) */
     int64_t num = w * q0 * delta, den = 256 * qz, v = num >= 0 ? (num + den / 2) / den : -((-num + den / 2) / den);
     if (v > 1023) v = 1023;
     if (v < -1023) v = -1023;

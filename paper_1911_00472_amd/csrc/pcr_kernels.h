@@ -1733,7 +1733,9 @@ __global__ void __launch_bounds__(256) k_smooth(DevRecord R) {
         if (on) {
             const uint8_t* q = R.rec + ip->qoff[tq];
             const bool wide = ip->qprec[tq] != 0;
-            for (uint32_t k = 0; k < 6; k++) { const uint32_t v = wide ? ld_be16(q + 2 * k) : q[k]; qs[tid][k] = v ? v : 1u; }
+            // (a step of zero, which the standard does not allow, predicts nothing: DC step zero makes every difference zero,
+            // and a coefficient with step zero de-quantises to zero whatever it is; the divisor only must not be zero)
+            for (uint32_t k = 0; k < 6; k++) { const uint32_t v = wide ? ld_be16(q + 2 * k) : q[k]; qs[tid][k] = (v || k == 0) ? v : 1u; }
         }
     }
     __syncthreads();
@@ -1764,6 +1766,160 @@ __global__ void __launch_bounds__(256) k_smooth(DevRecord R) {
             }
         }
         plane0 += nb;
+    }
+}
+
+// --------------------------------------------------------------------------------------
+// k_pixel_smooth_flat: the pixels of a decode that holds DC first scans only, with k_smooth's predictions, without the
+// detour through the coefficient planes and the full transform: one lane per 8x8 cell of pixels, as in k_pixel_flat.
+// A block with zig-zag coefficients 0..5 only is
+//     f(y, x) = F00 / 8 + a (F01 c1(x) + F02 c2(x)) + a (F10 c1(y) + F20 c2(y)) + F11 c1(x) c1(y) / 4,
+//     a = 1 / (4 sqrt 2),  c1(t) = cos((2t + 1) pi / 16),  c2(t) = cos((2t + 1) pi / 8),
+// a sum of a function of x, a function of y and one product: per component the lane keeps the two functions of x for
+// its eight pixel columns and the two of y for its eight pixel rows (a cell of a component at half resolution covers
+// four of the block's sample columns or rows, each twice), and a sample costs two operations.  Clamping, colour
+// conversion and rounding as everywhere.  The predictions are the same integers k_smooth writes (32-bit arithmetic when
+// the quantiser table has 8-bit entries: 36 x 255 x four DC coefficients fits).  Launched by the host only when every scan decoded
+// is a DC first scan; a component without its DC scan reads as zero and is not predicted.
+// grid: the flat tile list (runs of kFlatLanes cells of one image).
+// --------------------------------------------------------------------------------------
+PCR_D int smooth_predict32(uint32_t w, uint32_t q0, int delta, uint32_t qz) {
+    const uint32_t mag = (uint32_t)(delta < 0 ? -delta : delta);
+    const uint32_t num = w * q0 * mag, den = 256u * qz;
+    uint32_t v = (num + den / 2) / den;
+    v = v > 1023u ? 1023u : v;
+    return delta < 0 ? -(int)v : (int)v;
+}
+__global__ void __launch_bounds__(kFlatLanes) k_pixel_smooth_flat(DevRecord R, const PixelTile* __restrict__ tiles, uint8_t* __restrict__ out) {
+    __shared__ uint32_t does[kMaxComp];
+    short_kernel_priority();
+    const uint32_t item = xcd_major(blockIdx.x, gridDim.x);
+    const uint32_t timg = uni(tiles[item].img), cell0 = uni(tiles[item].mcu0);
+    ImgDesc D;
+    load_desc(R.img + timg, &D);
+    const uint32_t nc = D.nc, W = D.W, H = D.H;
+    if (!flat_image(D)) return;
+    if (threadIdx.x < kMaxComp) {
+        uint32_t carried = 0, dc_first = 0;
+        if (threadIdx.x < nc && D.progressive) {
+            const ScanDesc* sc = R.scan + (size_t)timg * R.G;
+            const uint32_t ng = D.nscans < R.G ? D.nscans : R.G;
+            for (uint32_t g = 0; g < ng; g++)
+                for (uint32_t j = 0; j < sc[g].ns && j < kMaxComp; j++)
+                    if (sc[g].comp[j] == threadIdx.x) { carried++; dc_first += (sc[g].Ss == 0 && sc[g].Se == 0 && sc[g].Ah == 0) ? 1u : 0u; }
+        }
+        does[threadIdx.x] = (carried == 1 && dc_first == 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    const uint32_t cells_w = (W + 7) >> 3, total = cells_w * ((H + 7) >> 3);
+    const uint32_t cell = cell0 + threadIdx.x;
+    if (cell >= total) return;
+    const uint32_t cy = cells_w == 1 ? cell : ((uint64_t)total * cells_w < (1ull << 32) ? __umulhi(cell, 0xFFFFFFFFu / cells_w + 1u) : cell / cells_w);
+    const uint32_t cx = cell - cy * cells_w;
+    const uint32_t x = cx * 8, y = cy * 8;
+    const bool dead = uni((uint32_t)(R.status[timg] != kOk)) != 0;
+    constexpr float kC1[8] = {0.98078528f, 0.83146961f, 0.55557023f, 0.19509032f, -0.19509032f, -0.55557023f, -0.83146961f, -0.98078528f};
+    constexpr float kC2[8] = {0.92387953f, 0.38268343f, -0.38268343f, -0.92387953f, -0.92387953f, -0.38268343f, 0.38268343f, 0.92387953f};
+    constexpr float kA = 0.17677670f;
+    // per component and pixel column: the function of x and the factor of the product; per pixel row: the same of y
+    float fx[kMaxComp][8], px[kMaxComp][8], fy[kMaxComp][8], py[kMaxComp][8];
+    const int16_t* dcp = R.dc + (R.coef_off[timg] >> 6);
+    uint32_t plane0 = 0;
+#pragma unroll
+    for (uint32_t c = 0; c < kMaxComp; c++) {
+#pragma unroll
+        for (int t = 0; t < 8; t++) { fx[c][t] = 128.f; px[c][t] = 0.f; fy[c][t] = 0.f; py[c][t] = 0.f; }
+        if (c < nc) {
+            const uint32_t shx = D.hs[c] == D.hmax ? 0u : 1u, shy = D.vs[c] == D.vmax ? 0u : 1u;      // (sampling factors are 1 or 2)
+            const uint32_t bcol = (cx * D.hs[c]) >> (D.hmax - 1), brow = (cy * D.vs[c]) >> (D.vmax - 1);
+            const uint32_t bw = D.bw[c], bh = D.bh[c];
+            const uint32_t tq = D.tq[c] & 3;
+            const uint32_t qoff = tq == 0 ? D.qoff[0] : (tq == 1 ? D.qoff[1] : (tq == 2 ? D.qoff[2] : D.qoff[3]));
+            const uint32_t wide = tq == 0 ? D.qprec[0] : (tq == 1 ? D.qprec[1] : (tq == 2 ? D.qprec[2] : D.qprec[3]));
+            const uint8_t* q = R.rec + qoff;
+            uint32_t qs[6], qd[6];                           // the steps, and the divisors (a step of zero predicts nothing)
+#pragma unroll
+            for (uint32_t k = 0; k < 6; k++) { qs[k] = wide ? ld_be16(q + 2 * k) : q[k]; qd[k] = qs[k] ? qs[k] : 1u; }
+            const int16_t* d = dcp + plane0;
+            const int m = d[brow * bw + bcol];
+            int p1 = 0, p2 = 0, p3 = 0, p4 = 0, p5 = 0;
+            if (does[c] && qoff != 0 && bcol < bw && brow < bh) {
+                const uint32_t xl = bcol ? bcol - 1 : 0, xr = bcol + 1 < bw ? bcol + 1 : bcol, ya = brow ? brow - 1 : 0, yb = brow + 1 < bh ? brow + 1 : brow;
+                const int al = d[ya * bw + xl], a = d[ya * bw + bcol], ar = d[ya * bw + xr];
+                const int l = d[brow * bw + xl], r = d[brow * bw + xr];
+                const int bl = d[yb * bw + xl], be = d[yb * bw + bcol], br = d[yb * bw + xr];
+                if (wide) {
+                    p1 = smooth_predict(36, qs[0], l - r, qd[1]); p2 = smooth_predict(36, qs[0], a - be, qd[2]);
+                    p3 = smooth_predict(9, qs[0], a + be - 2 * m, qd[3]); p4 = smooth_predict(5, qs[0], (al - ar) - (bl - br), qd[4]);
+                    p5 = smooth_predict(9, qs[0], l + r - 2 * m, qd[5]);
+                } else {
+                    p1 = smooth_predict32(36, qs[0], l - r, qd[1]); p2 = smooth_predict32(36, qs[0], a - be, qd[2]);
+                    p3 = smooth_predict32(9, qs[0], a + be - 2 * m, qd[3]); p4 = smooth_predict32(5, qs[0], (al - ar) - (bl - br), qd[4]);
+                    p5 = smooth_predict32(9, qs[0], l + r - 2 * m, qd[5]);
+                }
+            }
+            const float F00 = (float)m * (float)qs[0], F01 = (float)p1 * (float)qs[1], F10 = (float)p2 * (float)qs[2];
+            const float F20 = (float)p3 * (float)qs[3], F11 = (float)p4 * (float)qs[4], F02 = (float)p5 * (float)qs[5];
+            // the eight sample columns and rows of the block ...
+            float gx[8], hx[8], gy[8];
+#pragma unroll
+            for (int t = 0; t < 8; t++) {
+                gx[t] = F00 * 0.125f + 128.f + kA * (F01 * kC1[t] + F02 * kC2[t]);
+                hx[t] = 0.25f * F11 * kC1[t];
+                gy[t] = kA * (F10 * kC1[t] + F20 * kC2[t]);
+            }
+            // ... and those the cell's pixel columns and rows take them from
+            const bool right = shx && (cx & 1u), low = shy && (cy & 1u);
+#pragma unroll
+            for (int t = 0; t < 8; t++) {
+                fx[c][t] = shx ? (right ? gx[4 + (t >> 1)] : gx[t >> 1]) : gx[t];
+                px[c][t] = shx ? (right ? hx[4 + (t >> 1)] : hx[t >> 1]) : hx[t];
+                fy[c][t] = shy ? (low ? gy[4 + (t >> 1)] : gy[t >> 1]) : gy[t];
+                py[c][t] = shy ? (low ? kC1[4 + (t >> 1)] : kC1[t >> 1]) : kC1[t];
+            }
+            plane0 += bw * bh;
+        }
+    }
+    const uint32_t npx = W - x < 8 ? W - x : 8, nrows = H - y < 8 ? H - y : 8;
+    const size_t pitch = (size_t)W * nc;
+    uint8_t* wp = out + R.out_off[timg] + (size_t)y * pitch + (size_t)x * nc;
+    struct __attribute__((packed, aligned(1))) Words2 { uint32_t a, b; };
+    struct __attribute__((packed, aligned(1))) Words4 { uint32_t a, b, c, d; };
+#pragma unroll
+    for (int r = 0; r < 8; r++) {
+        if ((uint32_t)r < nrows) {
+            uint32_t w[6] = {0, 0, 0, 0, 0, 0};
+            if (!dead) {
+#pragma unroll
+                for (int t = 0; t < 8; t++) {
+                    const float s0 = clamp255(fx[0][t] + fy[0][r] + px[0][t] * py[0][r]);
+                    if (nc == 1) w[t >> 2] = put_u8(s0, t & 3, w[t >> 2]);
+                    else {
+                        const float u = clamp255(fx[1][t] + fy[1][r] + px[1][t] * py[1][r]) - 128.f;
+                        const float v = clamp255(fx[2][t] + fy[2][r] + px[2][t] * py[2][r]) - 128.f;
+                        w[(3 * t) >> 2] = put_u8(s0 + 1.402f * v, (3 * t) & 3, w[(3 * t) >> 2]);
+                        w[(3 * t + 1) >> 2] = put_u8(s0 - 0.344136f * u - 0.714136f * v, (3 * t + 1) & 3, w[(3 * t + 1) >> 2]);
+                        w[(3 * t + 2) >> 2] = put_u8(s0 + 1.772f * u, (3 * t + 2) & 3, w[(3 * t + 2) >> 2]);
+                    }
+                }
+            }
+            uint8_t* rp = wp + (size_t)r * pitch;
+            if (npx == 8) {
+                if (nc == 1) { Words2 e; e.a = w[0]; e.b = w[1]; *reinterpret_cast<Words2*>(rp) = e; }
+                else {
+                    Words4 e; e.a = w[0]; e.b = w[1]; e.c = w[2]; e.d = w[3];
+                    Words2 f; f.a = w[4]; f.b = w[5];
+                    *reinterpret_cast<Words4*>(rp) = e; *reinterpret_cast<Words2*>(rp + 16) = f;
+                }
+            } else {                                        // the image's last, narrower column of cells
+                const uint32_t nb = npx * nc;
+                for (uint32_t i = 0; i < nb; i++) {
+                    const uint32_t wi = i >> 2;
+                    const uint32_t word = wi == 0 ? w[0] : (wi == 1 ? w[1] : (wi == 2 ? w[2] : (wi == 3 ? w[3] : (wi == 4 ? w[4] : w[5]))));
+                    rp[i] = (uint8_t)(word >> (8 * (i & 3)));
+                }
+            }
+        }
     }
 }
 

@@ -944,9 +944,14 @@ static int decode_to_pixels(pcr_record* r, int k0, int k, uint8_t* out, size_t c
     r->resident_k = 0;
     int rc = run_entropy_stages(r, k0, k, s, false, &plan);
     if (rc) return rc;
-    // smoothing: predicted coefficients go into the planes for the pixel kernel and are taken out again after it
+    // smoothing: with DC first scans only, a kernel of its own; otherwise the predicted coefficients go into the planes
+    // for the pixel kernel and are taken out again after it
+    const bool smooth_flat = smooth && !plan->has_ac && !plan->n_apply && !boxes;
+    if (smooth_flat) smooth = false;
     if (smooth) hipLaunchKernelGGL(k_smooth<false>, dim3(kSmoothGroups, r->hdr.n), dim3(256), 0, s, r->d);
-    if (plan->n_apply)
+    if (smooth_flat)
+        hipLaunchKernelGGL(k_pixel_smooth_flat, dim3(r->n_flat_tiles), dim3(kFlatLanes), 0, s, r->d, r->d_flat_tiles, out);
+    else if (plan->n_apply)
         hipLaunchKernelGGL((k_pixel<true, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, plan->d_apply_lists, plan->d_list_idx, boxes);
     else if (plan->has_ac || smooth)
         hipLaunchKernelGGL((k_pixel<false, false>), dim3(r->n_tiles), dim3(kPixLanes), 0, s, r->d, r->d_tiles, out, (const ApplyList*)nullptr, (const int32_t*)nullptr, boxes);

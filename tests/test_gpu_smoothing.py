@@ -83,6 +83,10 @@ def test_wide_steps_16_bit_tables_sequential_files_and_dc_refinement_first():
     seq = pcrgen.encode_pixels(pcrgen.synth(31, 1, 40, 56, 3, 6.0), 2, 2, 90, "sequential", restart=1)
     prog = pcrgen.make_jpeg(32, 1, 90, 70, 3, 6.0, 2, 2, 85)
     assert _check_smooth(pcrgen.write_record([wide, VARIANTS["dqt16"](wide)]), (1, 2)) == 1
+    qz = q.copy()
+    qz[0, 0], qz[0, 1], qz[0, 4] = 16, 0, 0                       # steps of zero: nothing predicted there, nothing divided by them
+    zero = pcrgen.encode_coefs(c.reshape(-1), 56, 48, 1, 1, 1, qz, gray2)
+    assert _check_smooth(pcrgen.write_record([zero, VARIANTS["dqt16"](zero)]), (1, 2)) == 1
     assert _check_smooth(pcrgen.write_record([early]), (1, 2, 3)) == 1
     assert _check_smooth(pcrgen.write_record([VARIANTS["dqt16"](prog), prog]), (1, 2, 10)) == 2
     torch = _torch()

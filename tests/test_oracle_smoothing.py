@@ -78,6 +78,10 @@ def test_predictions_are_limited_to_the_range_of_an_ac_coefficient():
     c[0, :, 0] = [1000, 0, -1000]
     cf = oracle.decode_smooth(_first_scans(pcrgen.encode_coefs(c.reshape(-1), 24, 8, 1, 1, 1, q, GRAY2)), want_pix=False)[0].reshape(3, 64)
     assert cf[1, 1] == 1023 and 36 * 255 * 2000 // 256 > 1023
+    # a quantiser step of zero (not allowed by the standard, T.81 B.2.4.1) predicts nothing instead of dividing by it
+    q[0, 0], q[0, 1] = 16, 0
+    cf = oracle.decode_smooth(_first_scans(pcrgen.encode_coefs(c.reshape(-1), 24, 8, 1, 1, 1, q, GRAY2)), want_pix=False)[0].reshape(3, 64)
+    assert cf[1, 1] == 0 and cf[1, 2] == 0 and cf[0, 2] != 0
 
 
 def _surface(H=96, W=96):
