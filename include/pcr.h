@@ -178,8 +178,9 @@ int pcr_decode_batch_triangle(pcr_record* rec, int scan_group, uint8_t* out_u8_n
  * divided by 256 Qz and rounded to the nearest integer, halves away from zero, limited to +-1023; a neighbour beyond
  * the component's (MCU-padded) block grid is the nearest block inside it.  Components that have received an AC scan or
  * a DC refinement scan, and sequential files, decode exactly as in pcr_decode_batch, so at the last scan group the two
- * calls agree bit for bit.  The predictions live in the coefficient planes only for the duration of the call: a
- * following pcr_upgrade_batch starts from scan_group as after pcr_decode_batch.  Arguments, layout, stream order,
+ * calls agree bit for bit.  The coefficient planes are left as pcr_decode_batch leaves them (the predictions are in
+ * them at most for the duration of the call): a following pcr_upgrade_batch starts from scan_group as after
+ * pcr_decode_batch.  Arguments, layout, stream order,
  * d_status and errors as pcr_decode_batch. */
 int pcr_decode_batch_smooth(pcr_record* rec, int scan_group, uint8_t* out_u8_nhwc, size_t out_capacity,
                             void* hip_stream, int32_t* d_status);
