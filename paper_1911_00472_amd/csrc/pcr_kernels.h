@@ -469,8 +469,9 @@ PCR_D void load_ac_table(const DevRecord& R, size_t ig, bool first, AcTab* tab) 
 }
 
 // One wavefront per (image, scan): the scan's AC table, built once for all its restart intervals.
-// grid: (n, scans), scans k0 .. k0 + gridDim.y - 1.
-__global__ void __launch_bounds__(kEntropyLanes) k_build_tables(DevRecord R, uint32_t k0) {
+// grid: (n, scans), scans k0 .. k0 + gridDim.y - 1.  dc_too = 0: the DC first scans of this call are all decoded by
+// k_dc_first_lanes, which builds its own tables.
+__global__ void __launch_bounds__(kEntropyLanes) k_build_tables(DevRecord R, uint32_t k0, uint32_t dc_too) {
     __shared__ AcTab tab;
     short_kernel_priority();
     const uint32_t i = blockIdx.x, g = k0 + blockIdx.y;
@@ -479,7 +480,7 @@ __global__ void __launch_bounds__(kEntropyLanes) k_build_tables(DevRecord R, uin
     const ScanDesc* sd = &R.scan[ig];
     if (!sd->valid) return;
     if (sd->Ss == 0) {                                      // DC first scans: the table of every scan component (sequential scans build their own)
-        if (sd->Ah == 0 && R.img[i].progressive && threadIdx.x < sd->ns)
+        if (dc_too && sd->Ah == 0 && R.img[i].progressive && threadIdx.x < sd->ns)
             dctab_build(&R.dctabs[R.dctab_idx[ig] + threadIdx.x], R.rec + sd->dc_off[threadIdx.x]);
         return;
     }

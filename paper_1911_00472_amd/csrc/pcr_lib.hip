@@ -389,7 +389,19 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
     hipLaunchKernelGGL(k_index, dim3(k), dim3(256), 0, s, r->d, (uint32_t)k);
     hipLaunchKernelGGL(k_parse, dim3((n + 63) / 64), dim3(64), 0, s, r->d, (uint32_t)k, (uint32_t)(k0 > 0));
     r->d.tabs_prebuilt = r->prebuild_tables ? 1u : 0u;
-    if (r->prebuild_tables && k > k0) hipLaunchKernelGGL(k_build_tables, dim3(n, k - k0), dim3(kEntropyLanes), 0, s, r->d, (uint32_t)k0);
+    // (the wavefront decoders of DC first scans read pre-built tables, the lane decoder makes its own: when every launch
+    // of DC first scans of this call goes to the lanes their tables are not built, and with DC first scans only, none are)
+    // (decided once per call: the answer depends on how many records the process has open, which another thread may change)
+    bool dc_tables = false;
+    std::vector<char> dc_by_lanes(plan->levels.size(), 0);
+    for (size_t li = 0; li < plan->levels.size(); li++) {
+        const LevelList& l = plan->levels[li];
+        if (l.kind != kDcFirst || !l.n) continue;
+        dc_by_lanes[li] = dc_lanes_pay(r, l) ? 1 : 0;
+        if (!dc_by_lanes[li]) dc_tables = true;
+    }
+    if (r->prebuild_tables && k > k0 && (dc_tables || plan->has_ac))
+        hipLaunchKernelGGL(k_build_tables, dim3(n, k - k0), dim3(kEntropyLanes), 0, s, r->d, (uint32_t)k0, dc_tables ? 1u : 0u);
     mark(r, PCR_STAGE_INDEX_PARSE, s);
     if (k > k0) hipLaunchKernelGGL(k_unstuff, dim3(n, k - k0), dim3(256), 0, s, r->d, (uint32_t)k0, (uint32_t)k);
     const size_t coef_bytes = r->coef_off[n] * sizeof(int16_t);
@@ -409,10 +421,11 @@ int run_entropy_stages(pcr_record* r, int k0, int k, hipStream_t s, bool refine_
     const uint32_t* c32 = reinterpret_cast<const uint32_t*>(r->d.clean);
     const uint64_t* h64 = r->d.masks;
     r->last_lane_launches = r->last_wave_launches = 0;
-    for (auto& l : plan->levels) {
+    for (size_t li = 0; li < plan->levels.size(); li++) {
+        auto& l = plan->levels[li];
         const dim3 grid(l.n), block(kEntropyLanes);
         if (l.kind == kAcFirst || l.kind == kAcRefine) { if (lanes_pay(r, l)) r->last_lane_launches++; else r->last_wave_launches++; }
-        if (l.kind == kDcFirst && dc_lanes_pay(r, l)) {
+        if (l.kind == kDcFirst && dc_by_lanes[li]) {
             hipLaunchKernelGGL(k_dc_first_lanes, dim3((l.n + kEntropyLanes - 1) / kEntropyLanes), block, 0, s, r->d, l.d_units, l.n, c32, dc_to_planes ? 1u : 0u);
             mark(r, PCR_STAGE_DC_FIRST, s);
         }
