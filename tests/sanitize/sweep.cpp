@@ -20,6 +20,7 @@ typedef struct { int W, H, nc, hs[3], vs[3], bw[3], bh[3], nscans, progressive; 
 int orc_record_image_info(const uint8_t* rec, size_t nbytes, uint32_t i, orc_info_t* info);
 int orc_decode_record_image(const uint8_t* rec, size_t nbytes, uint32_t i, int k, int upsample, int idct, int16_t* coef, uint8_t* pix);
 int orc_reassemble(const uint8_t* rec, size_t nbytes, uint32_t i, int k, uint8_t* dst, size_t cap, size_t* out_len);
+int orc_decode_smooth(const uint8_t* jpg, size_t n, int16_t* coef, uint8_t* pix);
 }
 
 static uint64_t rng_state = 1;
@@ -66,6 +67,7 @@ static void through_the_decoders(const std::vector<uint8_t>& rec) {
             (void)orc_reassemble(rec.data(), rec.size(), i, k, tmp.data(), tmp.size(), &len);
             if (!known) continue;
             (void)orc_decode_record_image(rec.data(), rec.size(), i, k, 0, 0, coef.data(), pix.data());
+            if (k <= 3) (void)orc_decode_smooth(tmp.data(), len, coef.data(), pix.data());      // (the first groups are where components hold only DC)
             int W = 0, H = 0, C = 0;
             for (int lanes = 0; lanes < 2; lanes++) {                    // both shapes of AC decoder (pcr_entropy.h, pcr_lanes.h)
                 emul_set_lane_decoders(lanes);
