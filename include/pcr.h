@@ -168,8 +168,8 @@ int pcr_decode_batch_triangle(pcr_record* rec, int scan_group, uint8_t* out_u8_n
                               void* hip_stream, int32_t* d_status);
 
 /* pcr_decode_batch with the smoothing stock decoders apply to the first scans of a progressive file (Section 5,
- * "Decoding", hands the reassembled bytes to a stock decoder; the pictures of the early scans in the paper's figure of
- * the ten scans were made that way).  Every component of which only the DC first scan lies inside scan_group gets the
+ * "Decoding", hands the reassembled bytes to a stock decoder, and stock decoders smooth what has only its DC
+ * coefficients).  Every component of which only the DC first scan lies inside scan_group gets the
  * five lowest AC coefficients of each block predicted from the DC coefficients of the block and its eight neighbours
  * (JPEG standard, T.81 K.8: the coefficients of the quadratic surface whose means over the nine blocks are the nine DC
  * values).  Integer form, per coefficient with quantiser step Qz, DC step Q0 and DC coefficients as received:

@@ -1,6 +1,6 @@
 """The oracle's smoothing of components that have received only their DC first scan (T.81 K.8: the five lowest AC
-coefficients predicted from the DC coefficients of the block and its eight neighbours; what stock decoders show for the
-first scan groups of a progressive file, which is how the paper's Figure 3 pictures of scan 1 and 2 were made).
+coefficients predicted from the DC coefficients of the block and its eight neighbours; what stock decoders, to which
+the paper's Section 5 hands the reassembled bytes, show for the first scan groups of a progressive file).
 Pinned against things other than the oracle: the exact coefficients of the surfaces the predictor is built on (scipy's
 DCT) and the constants T.81 prints; a block worked by hand; a picture that is a quadratic surface, which the prediction
 must nearly restore; a stock decoder (Pillow), which smooths too; and the cases that must stay untouched."""
