@@ -1886,38 +1886,59 @@ __global__ void __launch_bounds__(kFlatLanes) k_pixel_smooth_flat(DevRecord R, c
     uint8_t* wp = out + R.out_off[timg] + (size_t)y * pitch + (size_t)x * nc;
     struct __attribute__((packed, aligned(1))) Words2 { uint32_t a, b; };
     struct __attribute__((packed, aligned(1))) Words4 { uint32_t a, b, c, d; };
+    // both chroma components at half resolution both ways (4:2:0): a chroma sample serves a 2 x 2 group of pixels and is
+    // evaluated once for it (the same expression on the same values as below, so the pixels do not depend on the path)
+    const bool quarter = nc == 3 && D.hs[0] == D.hmax && D.vs[0] == D.vmax && D.hs[1] != D.hmax && D.vs[1] != D.vmax && D.hs[2] != D.hmax && D.vs[2] != D.vmax;
 #pragma unroll
-    for (int r = 0; r < 8; r++) {
-        if ((uint32_t)r < nrows) {
+    for (int rp = 0; rp < 4; rp++) {
+        float u[8], v[8];
+#pragma unroll
+        for (int t = 0; t < 8; t++) { u[t] = 0.f; v[t] = 0.f; }
+        if (quarter && !dead && (uint32_t)(2 * rp) < nrows) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                u[2 * j] = u[2 * j + 1] = clamp255(fx[1][2 * j] + fy[1][2 * rp] + px[1][2 * j] * py[1][2 * rp]) - 128.f;
+                v[2 * j] = v[2 * j + 1] = clamp255(fx[2][2 * j] + fy[2][2 * rp] + px[2][2 * j] * py[2][2 * rp]) - 128.f;
+            }
+        }
+#pragma unroll
+        for (int dr = 0; dr < 2; dr++) {
+            const int r = 2 * rp + dr;
+            if ((uint32_t)r >= nrows) continue;
             uint32_t w[6] = {0, 0, 0, 0, 0, 0};
             if (!dead) {
+                if (nc == 3 && !quarter) {
+#pragma unroll
+                    for (int t = 0; t < 8; t++) {
+                        u[t] = clamp255(fx[1][t] + fy[1][r] + px[1][t] * py[1][r]) - 128.f;
+                        v[t] = clamp255(fx[2][t] + fy[2][r] + px[2][t] * py[2][r]) - 128.f;
+                    }
+                }
 #pragma unroll
                 for (int t = 0; t < 8; t++) {
                     const float s0 = clamp255(fx[0][t] + fy[0][r] + px[0][t] * py[0][r]);
                     if (nc == 1) w[t >> 2] = put_u8(s0, t & 3, w[t >> 2]);
                     else {
-                        const float u = clamp255(fx[1][t] + fy[1][r] + px[1][t] * py[1][r]) - 128.f;
-                        const float v = clamp255(fx[2][t] + fy[2][r] + px[2][t] * py[2][r]) - 128.f;
-                        w[(3 * t) >> 2] = put_u8(s0 + 1.402f * v, (3 * t) & 3, w[(3 * t) >> 2]);
-                        w[(3 * t + 1) >> 2] = put_u8(s0 - 0.344136f * u - 0.714136f * v, (3 * t + 1) & 3, w[(3 * t + 1) >> 2]);
-                        w[(3 * t + 2) >> 2] = put_u8(s0 + 1.772f * u, (3 * t + 2) & 3, w[(3 * t + 2) >> 2]);
+                        w[(3 * t) >> 2] = put_u8(s0 + 1.402f * v[t], (3 * t) & 3, w[(3 * t) >> 2]);
+                        w[(3 * t + 1) >> 2] = put_u8(s0 - 0.344136f * u[t] - 0.714136f * v[t], (3 * t + 1) & 3, w[(3 * t + 1) >> 2]);
+                        w[(3 * t + 2) >> 2] = put_u8(s0 + 1.772f * u[t], (3 * t + 2) & 3, w[(3 * t + 2) >> 2]);
                     }
                 }
             }
-            uint8_t* rp = wp + (size_t)r * pitch;
+            uint8_t* rp8 = wp + (size_t)r * pitch;
             if (npx == 8) {
-                if (nc == 1) { Words2 e; e.a = w[0]; e.b = w[1]; *reinterpret_cast<Words2*>(rp) = e; }
+                if (nc == 1) { Words2 e; e.a = w[0]; e.b = w[1]; *reinterpret_cast<Words2*>(rp8) = e; }
                 else {
                     Words4 e; e.a = w[0]; e.b = w[1]; e.c = w[2]; e.d = w[3];
                     Words2 f; f.a = w[4]; f.b = w[5];
-                    *reinterpret_cast<Words4*>(rp) = e; *reinterpret_cast<Words2*>(rp + 16) = f;
+                    *reinterpret_cast<Words4*>(rp8) = e; *reinterpret_cast<Words2*>(rp8 + 16) = f;
                 }
             } else {                                        // the image's last, narrower column of cells
                 const uint32_t nb = npx * nc;
                 for (uint32_t i = 0; i < nb; i++) {
                     const uint32_t wi = i >> 2;
                     const uint32_t word = wi == 0 ? w[0] : (wi == 1 ? w[1] : (wi == 2 ? w[2] : (wi == 3 ? w[3] : (wi == 4 ? w[4] : w[5]))));
-                    rp[i] = (uint8_t)(word >> (8 * (i & 3)));
+                    rp8[i] = (uint8_t)(word >> (8 * (i & 3)));
                 }
             }
         }
