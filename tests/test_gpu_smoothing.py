@@ -83,6 +83,17 @@ def test_wide_steps_16_bit_tables_sequential_files_and_dc_refinement_first():
     seq = pcrgen.encode_pixels(pcrgen.synth(31, 1, 40, 56, 3, 6.0), 2, 2, 90, "sequential", restart=1)
     prog = pcrgen.make_jpeg(32, 1, 90, 70, 3, 6.0, 2, 2, 85)
     assert _check_smooth(pcrgen.write_record([wide, VARIANTS["dqt16"](wide)]), (1, 2)) == 1
+    # the largest DC differences a file of 8-bit samples can hold, coarse and fine steps: the 32-bit arithmetic of the
+    # kernel that serves DC-only decodes against the oracle's 64-bit one
+    cb = np.zeros((6, 7, 64), np.int16)
+    cb[:, :, 0] = np.where((np.add.outer(np.arange(6), np.arange(7)) % 2) == 0, 1016, -1024)
+    cb[3, :, 0] = rng.integers(-1024, 1017, size=7)
+    for steps in ((255, 1, 1, 1, 1, 1), (255, 255, 254, 253, 252, 251), (1, 255, 3, 7, 2, 9)):
+        qe = np.ones((2, 64), np.uint16)
+        qe[0, :6] = steps
+        ext = pcrgen.encode_coefs(cb.reshape(-1), 56, 48, 1, 1, 1, qe, gray2)
+        changed = _check_smooth(pcrgen.write_record([ext, VARIANTS["dqt16"](ext)]), (1,))
+        assert changed == (1 if steps[0] == 1 else changed)       # (with the coarse DC step every sample is clamped: nothing to see)
     qz = q.copy()
     qz[0, 0], qz[0, 1], qz[0, 4] = 16, 0, 0                       # steps of zero: nothing predicted there, nothing divided by them
     zero = pcrgen.encode_coefs(c.reshape(-1), 56, 48, 1, 1, 1, qz, gray2)
